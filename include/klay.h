@@ -1,0 +1,182 @@
+/*
+ * klay.h -- C ABI of the MI355X (gfx950) layered arithmetic-circuit evaluator.
+ *
+ * The library evaluates a negation-normal-form circuit DAG (paper Section 2, Eq. 1: leaves
+ * are literals, inner nodes AND / OR gates) on a batch of leaf-weight vectors, layer by
+ * layer (Section 3.1, Eq. 2; Section 4, Alg. 1; Appendix C, Alg. 2-4), and differentiates
+ * the root values with respect to the leaf weights.
+ *
+ * Conventions
+ *   - Plain C, no exceptions.  Every call returns a klay_status; klay_last_error() gives a
+ *     thread-local message for the last failing call on the calling thread.
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory on
+ *     the circuit's device.  The library never takes ownership of caller buffers.
+ *   - klay_forward / klay_backward only enqueue work on the caller's stream; they do not
+ *     synchronise the host with the device.  A handle must not be used from two streams at
+ *     once (its activation workspace is shared between calls).
+ */
+#ifndef KLAY_H
+#define KLAY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct klay_circuit klay_circuit;   /* opaque; owns index arrays and (unless set) a workspace */
+
+typedef enum {
+    KLAY_OK = 0,
+    KLAY_EINVAL = 1,   /* malformed argument or circuit (index out of range, empty gate, ...) */
+    KLAY_ECYCLE = 2,   /* the node graph is not acyclic */
+    KLAY_ENOMEM = 3,   /* host or device allocation failed, or caller workspace too small */
+    KLAY_EHIP = 4,     /* a HIP runtime call failed */
+    KLAY_ESTATE = 5    /* call order violated (backward before forward, host-only handle, ...) */
+} klay_status;
+
+/* Semiring of the evaluation (Section 4): REAL = (+, x) on probabilities, LOG = (logsumexp, +)
+ * on log-probabilities (Alg. 4 with epsilon = 0). */
+typedef enum { KLAY_REAL = 0, KLAY_LOG = 1 } klay_semiring;
+
+/* node_type codes of the input DAG */
+enum { KLAY_LIT = 0, KLAY_AND = 1, KLAY_OR = 2, KLAY_TRUE = 3, KLAY_FALSE = 4 };
+
+/* Build-time options; zero-initialise and override.  0 means "library default". */
+typedef struct klay_options {
+    int32_t no_reorder;      /* 1: keep nodes of a layer in input-id order (no locality sort)     */
+    int32_t heavy_fan;       /* rows with more sources than this are split (default 128)          */
+    int32_t min_segment;     /* smallest split segment, in edges (default 32)                     */
+    int32_t reserved[5];
+} klay_options;
+
+typedef struct klay_info_t {
+    int32_t num_vars;
+    int32_t num_roots;
+    int32_t num_layers;       /* L: gate layers 1..L above the leaf layer 0                        */
+    int32_t device;           /* -1 for a host-only handle                                        */
+    int64_t num_nodes;        /* nodes of the layered circuit, all layers, unary chain nodes incl. */
+    int64_t num_edges;        /* edges of the layered circuit = sum over layers of |S_l|           */
+    int64_t dag_nodes;        /* input nodes reachable from the roots                              */
+    int64_t dag_edges;        /* their child edges                                                 */
+    int64_t num_pad_nodes;    /* unary chain nodes inserted by layerization                        */
+    int64_t max_layer_nodes;
+    int64_t max_fan_in;
+    int64_t max_fan_out;
+    int64_t num_split_rows;   /* rows (forward) and columns (backward) evaluated by split passes   */
+    int64_t index_bytes;      /* device bytes held by index arrays                                 */
+} klay_info_t;
+
+/* Per-kernel-class timing of the most recent forward / backward call, filled only while
+ * profiling is enabled.  Durations come from HIP events recorded on the caller's stream. */
+enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
+       KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_COUNT };
+typedef struct klay_profile_t {
+    float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
+    int32_t launches[KLAY_K_COUNT];
+    double  alg_bytes[KLAY_K_COUNT];   /* algorithmic bytes moved by those launches (no-reuse model) */
+} klay_profile_t;
+
+/*
+ * klay_build -- layerize and tensorize a circuit (Section 3.1 Eq. 2, Section 3.2, Alg. 2, Alg. 3)
+ * and upload the per-layer index arrays.
+ *
+ *   num_vars      V; literals name variables 0..V-1
+ *   num_nodes     number of nodes of the input DAG
+ *   node_type     host [num_nodes], KLAY_LIT .. KLAY_FALSE
+ *   node_lit      host [num_nodes]; for KLAY_LIT +(v+1) (positive) or -(v+1) (negated), else ignored
+ *   child_ptr     host [num_nodes+1]; children of node i are child_idx[child_ptr[i] .. child_ptr[i+1])
+ *   child_idx     host [child_ptr[num_nodes]] node ids, in any order
+ *   num_roots, roots   host [num_roots] node ids; out[:, r] of klay_forward is roots[r]'s value
+ *   device        HIP device ordinal, or -1 for a host-only handle (layerization only: the
+ *                 inspection calls work, forward/backward return KLAY_ESTATE)
+ *   out           receives the handle
+ *
+ * All arrays are borrowed for the duration of the call only.  Nodes not reachable from a root
+ * are dropped.  Gates of the wrong parity for their height (an OR directly over leaves, an AND
+ * under an AND) are lifted one layer so that odd layers hold AND and even layers OR (Section 3.1).
+ * Layer-skipping edges get one chain of unary nodes per (child, layer); all roots are extended to
+ * the height of the tallest (Section 3.2).
+ * Errors: KLAY_EINVAL (bad sizes, index or literal out of range, a gate without children, a child
+ * listed twice under one gate, a leaf with children, no roots), KLAY_ECYCLE, KLAY_ENOMEM, KLAY_EHIP.
+ */
+klay_status klay_build(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
+                       const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,
+                       int32_t num_roots, const int32_t* roots, int32_t device, klay_circuit** out);
+
+/* Same with explicit options (opts may be NULL). */
+klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
+                          const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,
+                          int32_t num_roots, const int32_t* roots, int32_t device,
+                          const klay_options* opts, klay_circuit** out);
+
+/*
+ * klay_forward -- evaluate all layers (Alg. 1 for KLAY_REAL, Alg. 4 for KLAY_LOG).
+ *   leaf_weights  device [B, V] row-major fp32: p_v (REAL) or log p_v (LOG).  The negated literal
+ *                 of v gets 1 - p_v resp. log(1 - exp(x_v)).
+ *   B             batch size >= 1
+ *   out           device [B, R] row-major fp32; out[b, r] = value of roots[r] on sample b
+ *   stream        hipStream_t (as void*), may be NULL for the default stream
+ * Keeps every layer's values in the workspace for klay_backward.  Grows the library-owned
+ * workspace (hipMalloc, which synchronises) when B exceeds what earlier calls needed, unless a
+ * caller workspace was set.  Errors: KLAY_EINVAL, KLAY_ENOMEM, KLAY_EHIP, KLAY_ESTATE.
+ */
+klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
+                         klay_semiring semiring, void* stream);
+
+/*
+ * klay_backward -- reverse-mode derivative of the most recent klay_forward on this handle
+ * (the paper obtains it from autograd, Section 6; here it is a reverse sweep over the layers).
+ *   dout          device [B, R] fp32, adjoint of `out`
+ *   dleaf         device [B, V] fp32, receives sum_r dout[b,r] * d out[b,r] / d leaf_weights[b,v];
+ *                 every entry is written (0 for variables the circuit does not use)
+ * Uses B, the semiring and the activations of that forward call; the caller must not have run
+ * another forward in between.  A literal whose adjoint is exactly 0 contributes 0 even where the
+ * derivative of its weight is infinite (log-domain negated literal at p = 1).
+ * Errors: KLAY_ESTATE if no forward was run, KLAY_EINVAL, KLAY_EHIP.
+ */
+klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void* stream);
+
+/* Structure of the layered circuit. */
+klay_status klay_info(const klay_circuit* c, klay_info_t* info);
+
+/* nodes[l], edges[l] for l = 0..L (host arrays of num_layers+1 entries; edges[0] = 0). */
+klay_status klay_layer_sizes(const klay_circuit* c, int64_t* nodes, int64_t* edges);
+
+/*
+ * Host copy of layer l's index vectors (Section 4 / Alg. 3), 1 <= l <= L, in CSR form:
+ * row_ptr [n_l + 1], child [e_l].  child is the paper's S_l (position in layer l-1); the paper's
+ * R_l is row_ptr expanded (edge j belongs to parent r iff row_ptr[r] <= j < row_ptr[r+1]).
+ */
+klay_status klay_layer_csr(const klay_circuit* c, int32_t layer, int64_t* row_ptr, int32_t* child);
+
+/*
+ * Host copy of what each node of layer l (0 <= l <= L) stands for: origin[i] is the input node id
+ * whose value row i holds (for a unary chain node: the id of the node the chain starts from),
+ * is_pad[i] is 1 for chain nodes.
+ */
+klay_status klay_layer_nodes(const klay_circuit* c, int32_t layer, int32_t* origin, uint8_t* is_pad);
+
+/* Bytes of device workspace a forward (and, if need_backward, backward) call with batch B needs. */
+size_t klay_workspace_bytes(const klay_circuit* c, int32_t B, int need_backward);
+
+/* Use caller device memory (256-byte aligned) as workspace instead of library-owned memory;
+ * dev_ptr = NULL returns to library-owned memory.  The caller keeps ownership. */
+klay_status klay_set_workspace(klay_circuit* c, void* dev_ptr, size_t bytes);
+
+/* Enable (1) / disable (0) per-kernel-class event timing; klay_get_profile synchronises on the
+ * recorded events and returns the figures of the most recent forward and backward calls. */
+klay_status klay_set_profiling(klay_circuit* c, int32_t enable);
+klay_status klay_get_profile(klay_circuit* c, klay_profile_t* profile);
+
+/* Frees index arrays and library-owned workspace.  NULL is allowed. */
+void klay_destroy(klay_circuit* c);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* klay_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KLAY_H */

@@ -1,0 +1,633 @@
+// C ABI of the layered circuit evaluator (see include/klay.h): handle management, workspace,
+// and the launch sequences of the forward sweep (paper Section 4, Alg. 1 / Appendix C, Alg. 4)
+// and of the reverse sweep that yields the derivative with respect to the leaf weights.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/klay.h"
+#include "klay_kernels.hip.h"
+#include "layerize.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+klay_status fail(klay_status s, const std::string& msg) {
+    g_err = msg;
+    return s;
+}
+
+#define KLAY_HIP(call)                                                                         \
+    do {                                                                                       \
+        hipError_t e__ = (call);                                                               \
+        if (e__ != hipSuccess)                                                                 \
+            return fail(KLAY_EHIP, std::string(#call) + ": " + hipGetErrorString(e__));        \
+    } while (0)
+
+constexpr size_t kAlignInts = 64;   // 256-byte alignment of every uploaded array
+
+struct DevPass {
+    const int32_t *ptr = nullptr, *idx = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_row = nullptr;
+    int32_t n_main = 0, n_seg = 0, n_heavy = 0;
+    int64_t edges = 0;
+};
+
+struct DevLayer {
+    int64_t n = 0, e = 0;
+    int64_t row0 = 0;        // first row of this layer in the activation buffer
+    DevPass fwd, bwd;
+};
+
+struct Geometry {            // how a batch of B columns is mapped onto lanes
+    int vec = 1, w = 64, ld = 0, tiles = 1;
+};
+
+Geometry geometry(int B) {
+    Geometry g;
+    if (B > 128) { g.vec = 4; g.w = 64; }
+    else if (B > 64) { g.vec = 2; g.w = 64; }
+    else if (B > 32) { g.vec = 1; g.w = 64; }
+    else {
+        g.vec = 1;
+        g.w = 1;
+        while (g.w < B) g.w *= 2;
+    }
+    g.ld = (B + g.vec - 1) / g.vec * g.vec;
+    const int tile = g.w * g.vec;
+    g.tiles = (B + tile - 1) / tile;
+    return g;
+}
+
+size_t align_floats(size_t n) { return (n + 63) / 64 * 64; }
+
+struct Workspace {
+    size_t act = 0, wT = 0, scratch = 0, g0 = 0, g1 = 0, total = 0;   // offsets in floats
+};
+
+struct EventRec {
+    int cls;
+    hipEvent_t start, stop;
+    double bytes;
+};
+
+}  // namespace
+
+struct klay_circuit {
+    klay::CircuitPlan plan;
+    int device = -1;
+    std::vector<DevLayer> dl;
+    int32_t* d_index = nullptr;          // one allocation holding every index array
+    size_t index_bytes = 0;
+    const int32_t *d_pos_row = nullptr, *d_neg_row = nullptr, *d_root_pos = nullptr, *d_top_ptr = nullptr,
+                  *d_top_root = nullptr, *d_iota = nullptr;
+    int32_t true_row = -1, false_row = -1;
+    void* ws_own = nullptr;
+    size_t ws_own_bytes = 0;
+    void* ws_user = nullptr;
+    size_t ws_user_bytes = 0;
+    // state of the most recent forward
+    bool have_fwd = false;
+    int32_t last_B = 0;
+    int last_semiring = 0;
+    bool last_ws_has_bwd = false;
+    // profiling
+    bool profiling = false;
+    std::vector<EventRec> ev_fwd, ev_bwd;
+    std::vector<hipEvent_t> ev_pool;
+};
+
+namespace {
+
+Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
+    const Geometry g = geometry(B);
+    const klay::CircuitPlan& p = c->plan;
+    Workspace w;
+    size_t off = 0;
+    w.act = off; off += align_floats((size_t)p.num_nodes * g.ld);
+    w.wT = off; off += align_floats((size_t)std::max(1, p.num_vars) * g.ld);
+    const int64_t seg = std::max(p.max_fwd_seg, need_bwd ? p.max_bwd_seg : 0);
+    w.scratch = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
+    if (need_bwd) {
+        w.g0 = off; off += align_floats((size_t)p.max_layer_nodes * g.ld);
+        w.g1 = off; off += align_floats((size_t)p.max_layer_nodes * g.ld);
+    }
+    w.total = off;
+    return w;
+}
+
+template <int OP, int VEC, int W>
+void launch_one(const klay::PassArgs& a, dim3 grid, hipStream_t s) {
+    hipLaunchKernelGGL((klay::pass_kernel<OP, VEC, W>), grid, dim3(256), 0, s, a);
+}
+
+template <int OP>
+void launch_op(const klay::PassArgs& a, const Geometry& g, dim3 grid, hipStream_t s) {
+    if (g.w == 64) {
+        if (g.vec == 4) launch_one<OP, 4, 64>(a, grid, s);
+        else if (g.vec == 2) launch_one<OP, 2, 64>(a, grid, s);
+        else launch_one<OP, 1, 64>(a, grid, s);
+        return;
+    }
+    switch (g.w) {
+    case 32: launch_one<OP, 1, 32>(a, grid, s); break;
+    case 16: launch_one<OP, 1, 16>(a, grid, s); break;
+    case 8: launch_one<OP, 1, 8>(a, grid, s); break;
+    case 4: launch_one<OP, 1, 4>(a, grid, s); break;
+    case 2: launch_one<OP, 1, 2>(a, grid, s); break;
+    default: launch_one<OP, 1, 1>(a, grid, s); break;
+    }
+}
+
+// Launch one gather-reduce pass over `n_total` rows.
+void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
+    if (a.n_total <= 0) return;
+    const int rpw = 64 / g.w;
+    const int64_t groups = ((int64_t)a.n_total + rpw - 1) / rpw;     // row groups = wave work items
+    // enough waves to fill 256 CUs several times over before a wave takes more than one group
+    int iters = (int)std::min<int64_t>(8, std::max<int64_t>(1, groups / 32768));
+    a.iters = iters;
+    int64_t blocks = (groups + (int64_t)4 * iters - 1) / ((int64_t)4 * iters);
+    blocks = (blocks + 7) / 8 * 8;
+    dim3 grid((unsigned)blocks, (unsigned)g.tiles);
+    switch (op) {
+    case klay::OP_SUM: launch_op<klay::OP_SUM>(a, g, grid, s); break;
+    case klay::OP_PROD: launch_op<klay::OP_PROD>(a, g, grid, s); break;
+    case klay::OP_LSE: launch_op<klay::OP_LSE>(a, g, grid, s); break;
+    default: launch_op<klay::OP_SOFTMAX_BWD>(a, g, grid, s); break;
+    }
+}
+
+struct Profiler {
+    klay_circuit* c;
+    std::vector<EventRec>* recs;
+    hipStream_t s;
+    size_t next = 0;
+    bool on;
+    Profiler(klay_circuit* c_, std::vector<EventRec>* r, hipStream_t s_) : c(c_), recs(r), s(s_), on(c_->profiling) {
+        if (on) recs->clear();
+    }
+    hipEvent_t get() {
+        // events of the previous forward stay referenced by ev_fwd while backward records its own
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        c->ev_pool.push_back(e);
+        return e;
+    }
+    void begin(int cls, double bytes) {
+        if (!on) return;
+        EventRec r{cls, get(), get(), bytes};
+        if (r.start) (void)hipEventRecord(r.start, s);
+        recs->push_back(r);
+    }
+    void end() {
+        if (!on || recs->empty()) return;
+        if (recs->back().stop) (void)hipEventRecord(recs->back().stop, s);
+    }
+};
+
+void release_events(klay_circuit* c) {
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    c->ev_pool.clear();
+    c->ev_fwd.clear();
+    c->ev_bwd.clear();
+}
+
+klay_status get_workspace(klay_circuit* c, int B, bool need_bwd, float** base, Workspace* lay) {
+    *lay = workspace_layout(c, B, need_bwd);
+    const size_t bytes = lay->total * sizeof(float);
+    if (c->ws_user) {
+        if (bytes > c->ws_user_bytes)
+            return fail(KLAY_ENOMEM, "caller workspace too small: need " + std::to_string(bytes) + " bytes");
+        *base = static_cast<float*>(c->ws_user);
+        return KLAY_OK;
+    }
+    if (bytes > c->ws_own_bytes) {
+        if (c->ws_own) { KLAY_HIP(hipFree(c->ws_own)); c->ws_own = nullptr; c->ws_own_bytes = 0; }
+        if (hipMalloc(&c->ws_own, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(KLAY_ENOMEM, "hipMalloc of " + std::to_string(bytes) + " workspace bytes failed");
+        }
+        c->ws_own_bytes = bytes;
+    }
+    *base = static_cast<float*>(c->ws_own);
+    return KLAY_OK;
+}
+
+// Packs host arrays into one buffer with 256-byte aligned starts; returns offsets in ints.
+struct Packer {
+    std::vector<int32_t> buf;
+    size_t add(const std::vector<int32_t>& v) { return add(v.data(), v.size()); }
+    size_t add(const int32_t* p, size_t n) {
+        size_t off = (buf.size() + kAlignInts - 1) / kAlignInts * kAlignInts;
+        buf.resize(off + std::max<size_t>(n, 1), 0);
+        if (n) std::memcpy(buf.data() + off, p, n * sizeof(int32_t));
+        return off;
+    }
+};
+
+struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_row; };
+
+PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
+    PassOffsets o;
+    o.ptr = pk.add(p.ptr);
+    o.idx = pk.add(p.idx);
+    o.seg_owner = pk.add(p.seg_owner);
+    o.comb_ptr = pk.add(p.comb_ptr);
+    o.comb_row = pk.add(p.comb_row);
+    return o;
+}
+
+void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const int32_t* base) {
+    d.ptr = base + o.ptr;
+    d.idx = base + o.idx;
+    d.seg_owner = base + o.seg_owner;
+    d.comb_ptr = base + o.comb_ptr;
+    d.comb_row = base + o.comb_row;
+    d.n_main = p.n_main;
+    d.n_seg = p.n_seg;
+    d.n_heavy = p.n_heavy;
+    d.edges = p.edges;
+}
+
+klay_status upload(klay_circuit* c) {
+    const klay::CircuitPlan& p = c->plan;
+    Packer pk;
+    const int L = p.num_layers;
+    std::vector<PassOffsets> fo((size_t)L + 1), bo((size_t)L + 1);
+    for (int l = 1; l <= L; ++l) {
+        fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
+        bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
+    }
+    const size_t o_pos = pk.add(p.pos_row), o_neg = pk.add(p.neg_row), o_root = pk.add(p.root_pos);
+    const size_t o_tptr = pk.add(p.top_ptr), o_troot = pk.add(p.top_root);
+    std::vector<int32_t> iota((size_t)std::max(p.max_fwd_seg, p.max_bwd_seg) + 8);
+    for (size_t i = 0; i < iota.size(); ++i) iota[i] = (int32_t)i;
+    const size_t o_iota = pk.add(iota);
+
+    KLAY_HIP(hipSetDevice(c->device));
+    c->index_bytes = pk.buf.size() * sizeof(int32_t);
+    if (hipMalloc(reinterpret_cast<void**>(&c->d_index), c->index_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(KLAY_ENOMEM, "hipMalloc of " + std::to_string(c->index_bytes) + " index bytes failed");
+    }
+    KLAY_HIP(hipMemcpy(c->d_index, pk.buf.data(), c->index_bytes, hipMemcpyHostToDevice));
+    const int32_t* base = c->d_index;
+    c->dl.resize((size_t)L + 1);
+    int64_t row0 = 0;
+    for (int l = 0; l <= L; ++l) {
+        DevLayer& d = c->dl[(size_t)l];
+        d.n = p.layers[(size_t)l].n;
+        d.e = p.layers[(size_t)l].e;
+        d.row0 = row0;
+        row0 += d.n;
+        if (l >= 1) {
+            bind_pass(d.fwd, p.layers[(size_t)l].fwd, fo[(size_t)l], base);
+            bind_pass(d.bwd, p.layers[(size_t)l].bwd, bo[(size_t)l], base);
+        }
+    }
+    c->d_pos_row = base + o_pos;
+    c->d_neg_row = base + o_neg;
+    c->d_root_pos = base + o_root;
+    c->d_top_ptr = base + o_tptr;
+    c->d_top_root = base + o_troot;
+    c->d_iota = base + o_iota;
+    return KLAY_OK;
+}
+
+// One layer-level gather-reduce: main rows + segments of split rows, then the combine pass.
+void run_pass_set(int op, int combine_op, const DevPass& dp, const klay_circuit* c, const float* src,
+                  const float* src2, const float* own, float* dst, float* scratch, const Geometry& g,
+                  int B, hipStream_t s) {
+    klay::PassArgs a{};
+    a.ptr = dp.ptr;
+    a.idx = dp.idx;
+    a.src = src;
+    a.src2 = src2;
+    a.own = own;
+    a.seg_owner = dp.seg_owner;
+    a.out_row = nullptr;
+    a.dst = dst;
+    a.dst_seg = scratch;
+    a.n_main = dp.n_main;
+    a.n_total = dp.n_main + dp.n_seg;
+    a.B = B;
+    a.ld = g.ld;
+    a.skip_empty = 1;
+    launch_pass(op, a, g, s);
+    if (dp.n_heavy > 0) {
+        klay::PassArgs cmb{};
+        cmb.ptr = dp.comb_ptr;
+        cmb.idx = c->d_iota;
+        cmb.src = scratch;
+        cmb.out_row = dp.comb_row;
+        cmb.dst = dst;
+        cmb.dst_seg = nullptr;
+        cmb.n_main = dp.n_heavy;
+        cmb.n_total = dp.n_heavy;
+        cmb.B = B;
+        cmb.ld = g.ld;
+        cmb.skip_empty = 0;
+        launch_pass(combine_op, cmb, g, s);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* klay_last_error(void) { return g_err.c_str(); }
+
+klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
+                          const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,
+                          int32_t num_roots, const int32_t* roots, int32_t device,
+                          const klay_options* opts, klay_circuit** out) {
+    if (!out) return fail(KLAY_EINVAL, "klay_build: out is null");
+    *out = nullptr;
+    klay::Options o;
+    if (opts) {
+        o.no_reorder = opts->no_reorder != 0;
+        if (opts->heavy_fan > 0) o.heavy_fan = opts->heavy_fan;
+        if (opts->min_segment > 0) o.min_segment = opts->min_segment;
+    }
+    std::unique_ptr<klay_circuit> c;
+    try {
+        c.reset(new klay_circuit());
+        std::string err;
+        int st = klay::layerize(num_vars, num_nodes, node_type, node_lit, child_ptr, child_idx, num_roots,
+                                roots, o, c->plan, err);
+        if (st != 0) return fail(static_cast<klay_status>(st), err);
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_build: out of host memory");
+    }
+    for (int64_t i = 0; i < c->plan.layers[0].n; ++i) {
+        if (c->plan.leaf_code[(size_t)i] == INT32_MAX) c->true_row = (int32_t)i;
+        if (c->plan.leaf_code[(size_t)i] == INT32_MIN) c->false_row = (int32_t)i;
+    }
+    c->device = device;
+    if (device >= 0) {
+        int ndev = 0;
+        if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
+            (void)hipGetLastError();
+            return fail(KLAY_EHIP, "klay_build: HIP device " + std::to_string(device) + " not available");
+        }
+        klay_status st;
+        try {
+            st = upload(c.get());
+        } catch (const std::bad_alloc&) {
+            st = fail(KLAY_ENOMEM, "klay_build: out of host memory");
+        }
+        if (st != KLAY_OK) {
+            if (c->d_index) (void)hipFree(c->d_index);
+            return st;
+        }
+    }
+    *out = c.release();
+    return KLAY_OK;
+}
+
+klay_status klay_build(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
+                       const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,
+                       int32_t num_roots, const int32_t* roots, int32_t device, klay_circuit** out) {
+    return klay_build_ex(num_vars, num_nodes, node_type, node_lit, child_ptr, child_idx, num_roots, roots,
+                         device, nullptr, out);
+}
+
+void klay_destroy(klay_circuit* c) {
+    if (!c) return;
+    if (c->device >= 0) {
+        (void)hipSetDevice(c->device);
+        release_events(c);
+        if (c->d_index) (void)hipFree(c->d_index);
+        if (c->ws_own) (void)hipFree(c->ws_own);
+    }
+    delete c;
+}
+
+klay_status klay_info(const klay_circuit* c, klay_info_t* info) {
+    if (!c || !info) return fail(KLAY_EINVAL, "klay_info: null argument");
+    const klay::CircuitPlan& p = c->plan;
+    std::memset(info, 0, sizeof(*info));
+    info->num_vars = p.num_vars;
+    info->num_roots = p.num_roots;
+    info->num_layers = p.num_layers;
+    info->device = c->device;
+    info->num_nodes = p.num_nodes;
+    info->num_edges = p.num_edges;
+    info->dag_nodes = p.dag_nodes;
+    info->dag_edges = p.dag_edges;
+    info->num_pad_nodes = p.num_pad_nodes;
+    info->max_layer_nodes = p.max_layer_nodes;
+    info->max_fan_in = p.max_fan_in;
+    info->max_fan_out = p.max_fan_out;
+    info->num_split_rows = p.num_split_rows;
+    info->index_bytes = (int64_t)c->index_bytes;
+    return KLAY_OK;
+}
+
+klay_status klay_layer_sizes(const klay_circuit* c, int64_t* nodes, int64_t* edges) {
+    if (!c || !nodes || !edges) return fail(KLAY_EINVAL, "klay_layer_sizes: null argument");
+    for (int l = 0; l <= c->plan.num_layers; ++l) {
+        nodes[l] = c->plan.layers[(size_t)l].n;
+        edges[l] = c->plan.layers[(size_t)l].e;
+    }
+    return KLAY_OK;
+}
+
+klay_status klay_layer_csr(const klay_circuit* c, int32_t layer, int64_t* row_ptr, int32_t* child) {
+    if (!c || !row_ptr || !child) return fail(KLAY_EINVAL, "klay_layer_csr: null argument");
+    if (layer < 1 || layer > c->plan.num_layers) return fail(KLAY_EINVAL, "klay_layer_csr: layer out of range");
+    const klay::LayerPlan& l = c->plan.layers[(size_t)layer];
+    for (int64_t i = 0; i <= l.n; ++i) row_ptr[i] = l.row_ptr[(size_t)i];
+    std::copy(l.child.begin(), l.child.end(), child);
+    return KLAY_OK;
+}
+
+klay_status klay_layer_nodes(const klay_circuit* c, int32_t layer, int32_t* origin, uint8_t* is_pad) {
+    if (!c || !origin || !is_pad) return fail(KLAY_EINVAL, "klay_layer_nodes: null argument");
+    if (layer < 0 || layer > c->plan.num_layers) return fail(KLAY_EINVAL, "klay_layer_nodes: layer out of range");
+    const klay::LayerPlan& l = c->plan.layers[(size_t)layer];
+    std::copy(l.origin.begin(), l.origin.end(), origin);
+    std::copy(l.is_pad.begin(), l.is_pad.end(), is_pad);
+    return KLAY_OK;
+}
+
+size_t klay_workspace_bytes(const klay_circuit* c, int32_t B, int need_backward) {
+    if (!c || B < 1) return 0;
+    return workspace_layout(c, B, need_backward != 0).total * sizeof(float);
+}
+
+klay_status klay_set_workspace(klay_circuit* c, void* dev_ptr, size_t bytes) {
+    if (!c) return fail(KLAY_EINVAL, "klay_set_workspace: null handle");
+    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255u))
+        return fail(KLAY_EINVAL, "klay_set_workspace: pointer must be 256-byte aligned");
+    c->ws_user = dev_ptr;
+    c->ws_user_bytes = dev_ptr ? bytes : 0;
+    c->have_fwd = false;
+    return KLAY_OK;
+}
+
+klay_status klay_set_profiling(klay_circuit* c, int32_t enable) {
+    if (!c) return fail(KLAY_EINVAL, "klay_set_profiling: null handle");
+    if (c->device < 0) return fail(KLAY_ESTATE, "klay_set_profiling: host-only handle");
+    KLAY_HIP(hipSetDevice(c->device));
+    c->profiling = enable != 0;
+    if (!c->profiling) release_events(c);
+    return KLAY_OK;
+}
+
+klay_status klay_get_profile(klay_circuit* c, klay_profile_t* prof) {
+    if (!c || !prof) return fail(KLAY_EINVAL, "klay_get_profile: null argument");
+    std::memset(prof, 0, sizeof(*prof));
+    for (const std::vector<EventRec>* recs : {&c->ev_fwd, &c->ev_bwd})
+        for (const EventRec& r : *recs) {
+            if (!r.start || !r.stop) continue;
+            KLAY_HIP(hipEventSynchronize(r.stop));
+            float ms = 0.f;
+            KLAY_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+            prof->ms[r.cls] += ms;
+            prof->launches[r.cls] += 1;
+            prof->alg_bytes[r.cls] += r.bytes;
+        }
+    return KLAY_OK;
+}
+
+klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
+                         klay_semiring semiring, void* stream) {
+    if (!c || !leaf_weights || !out) return fail(KLAY_EINVAL, "klay_forward: null argument");
+    if (c->device < 0) return fail(KLAY_ESTATE, "klay_forward: host-only handle (built with device = -1)");
+    if (B < 1) return fail(KLAY_EINVAL, "klay_forward: B must be >= 1");
+    if (semiring != KLAY_REAL && semiring != KLAY_LOG) return fail(KLAY_EINVAL, "klay_forward: unknown semiring");
+    KLAY_HIP(hipSetDevice(c->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const klay::CircuitPlan& p = c->plan;
+    const Geometry g = geometry(B);
+    const bool log_domain = semiring == KLAY_LOG;
+    if (c->profiling && !c->ev_pool.empty()) release_events(c);
+
+    float* ws = nullptr;
+    Workspace lay;
+    c->have_fwd = false;
+    // the backward regions are part of the layout whenever the workspace can hold them
+    bool with_bwd = true;
+    if (c->ws_user && workspace_layout(c, B, true).total * sizeof(float) > c->ws_user_bytes) with_bwd = false;
+    klay_status st = get_workspace(c, B, with_bwd, &ws, &lay);
+    if (st != KLAY_OK) return st;
+
+    float* act = ws + lay.act;
+    float* wT = ws + lay.wT;
+    float* scratch = ws + lay.scratch;
+    const int L = p.num_layers;
+    const int V = p.num_vars;
+    Profiler prof(c, &c->ev_fwd, s);
+
+    // leaf layer
+    prof.begin(KLAY_K_LEAF, 4.0 * B * V + 4.0 * B * (double)(V + p.layers[0].n));
+    if (V > 0) {
+        dim3 grid((unsigned)((V + 31) / 32), (unsigned)((g.ld + 63) / 64));
+        hipLaunchKernelGGL(klay::leaf_fwd_kernel, grid, dim3(256), 0, s, leaf_weights, (int)B, V, g.ld,
+                           c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);
+    }
+    if (c->true_row >= 0)
+        hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((g.ld + 255) / 256)), dim3(256), 0, s,
+                           act + (size_t)c->true_row * g.ld, g.ld, log_domain ? 0.0f : 1.0f);
+    if (c->false_row >= 0)
+        hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((g.ld + 255) / 256)), dim3(256), 0, s,
+                           act + (size_t)c->false_row * g.ld, g.ld, log_domain ? -INFINITY : 0.0f);
+    prof.end();
+
+    // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4)
+    for (int l = 1; l <= L; ++l) {
+        const DevLayer& d = c->dl[(size_t)l];
+        const bool is_and = (l & 1) != 0;
+        const int op = log_domain ? (is_and ? klay::OP_SUM : klay::OP_LSE) : (is_and ? klay::OP_PROD : klay::OP_SUM);
+        const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM : (op == klay::OP_PROD ? KLAY_K_FWD_PROD : KLAY_K_FWD_LSE);
+        prof.begin(cls, 4.0 * B * ((double)d.e + (double)d.n) + 4.0 * ((double)d.e + (double)d.n));
+        run_pass_set(op, op, d.fwd, c, act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld, nullptr, nullptr,
+                     act + (size_t)d.row0 * g.ld, scratch, g, B, s);
+        prof.end();
+    }
+
+    // roots
+    prof.begin(KLAY_K_ROOT, 8.0 * B * p.num_roots);
+    {
+        dim3 grid((unsigned)p.num_roots);
+        hipLaunchKernelGGL(klay::root_out_kernel, grid, dim3(256), 0, s,
+                           act + (size_t)c->dl[(size_t)L].row0 * g.ld, c->d_root_pos, (int)B, p.num_roots, g.ld, out);
+    }
+    prof.end();
+    KLAY_HIP(hipGetLastError());
+    c->have_fwd = true;
+    c->last_B = B;
+    c->last_semiring = semiring;
+    c->last_ws_has_bwd = with_bwd;
+    return KLAY_OK;
+}
+
+klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void* stream) {
+    if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward: null argument");
+    if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward: host-only handle");
+    if (!c->have_fwd) return fail(KLAY_ESTATE, "klay_backward: no forward pass to differentiate");
+    if (c->last_semiring != KLAY_LOG)
+        return fail(KLAY_EINVAL, "klay_backward: only the log semiring is differentiated by this build");
+    if (!c->last_ws_has_bwd) return fail(KLAY_ENOMEM, "klay_backward: caller workspace has no room for adjoints");
+    KLAY_HIP(hipSetDevice(c->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const klay::CircuitPlan& p = c->plan;
+    const int B = c->last_B;
+    const Geometry g = geometry(B);
+    float* ws = nullptr;
+    Workspace lay;
+    klay_status st = get_workspace(c, B, true, &ws, &lay);
+    if (st != KLAY_OK) return st;
+    float* act = ws + lay.act;
+    float* wT = ws + lay.wT;
+    float* scratch = ws + lay.scratch;
+    float* gcur = ws + lay.g0;
+    float* gnext = ws + lay.g1;
+    const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
+    Profiler prof(c, &c->ev_bwd, s);
+
+    prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
+    {
+        dim3 grid((unsigned)c->dl[(size_t)L].n);
+        hipLaunchKernelGGL(klay::seed_kernel, grid, dim3(256), 0, s, dout, c->d_top_ptr, c->d_top_root, B, R,
+                           g.ld, gcur);
+    }
+    prof.end();
+
+    for (int l = L; l >= 1; --l) {
+        const DevLayer& d = c->dl[(size_t)l];
+        const DevLayer& below = c->dl[(size_t)l - 1];
+        const bool is_and = (l & 1) != 0;
+        if (is_and) {
+            prof.begin(KLAY_K_BWD_SUM, 4.0 * B * ((double)d.e + (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
+            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, c, gcur, nullptr, nullptr, gnext, scratch, g, B, s);
+        } else {
+            prof.begin(KLAY_K_BWD_SOFTMAX,
+                       4.0 * B * (2.0 * (double)d.e + 2.0 * (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
+            run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, c, gcur, act + (size_t)d.row0 * g.ld,
+                         act + (size_t)below.row0 * g.ld, gnext, scratch, g, B, s);
+        }
+        prof.end();
+        std::swap(gcur, gnext);
+    }
+
+    prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
+    if (V > 0) {
+        dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
+        hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B,
+                           V, g.ld, 1, dleaf);
+    }
+    prof.end();
+    KLAY_HIP(hipGetLastError());
+    return KLAY_OK;
+}
+
+}  // extern "C"

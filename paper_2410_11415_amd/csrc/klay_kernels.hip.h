@@ -1,0 +1,270 @@
+// Device kernels of the layered circuit evaluator for gfx950 (wave64).
+//
+// Data layout: every layer's node values live in one activation buffer, row = node,
+// `ld` consecutive floats per row = the batch (batch-inner), so the gather of one edge
+// (paper Section 4: E_l = N_{l-1}[S_l]) is one contiguous read of B floats.  A layer is
+// evaluated by a fused gather + segment-reduce (Alg. 1 / Alg. 4 without materialising E_l,
+// M or T): a lane group of W lanes owns one parent row and VEC consecutive batch columns per
+// lane, loops over the row's CSR range and keeps the reduction in registers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace klay {
+
+enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3 };
+
+struct PassArgs {
+    const int32_t* ptr;        // [n_total + 1] CSR offsets into idx
+    const int32_t* idx;        // source row per edge (readable up to 8 entries past the end)
+    const float* src;          // [*, ld] source rows (values of the layer below, adjoints, or partials)
+    const float* src2;         // OP_SOFTMAX_BWD: values N_l of the parents, same row index as src
+    const float* own;          // OP_SOFTMAX_BWD: values N_{l-1} of the output rows
+    const int32_t* seg_owner;  // output row owning segment i (rows >= n_main), may be null
+    const int32_t* out_row;    // optional output row map for rows < n_main (combine pass)
+    float* dst;                // output rows for rows < n_main
+    float* dst_seg;            // scratch rows for rows >= n_main
+    int32_t n_main;
+    int32_t n_total;
+    int32_t B;
+    int32_t ld;
+    int32_t iters;             // row groups per wave
+    int32_t skip_empty;        // 1: a row < n_main with an empty range is left untouched
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// exp and log on the transcendental unit (v_exp_f32 / v_log_f32 are base 2).  Arguments of
+// fexp are <= 0 here, so the rounding of x*log2(e) costs at most |x| e^x 2^-24 absolute.
+__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+__device__ __forceinline__ float flog(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
+
+template <int VEC> struct Pack;
+template <> struct Pack<1> { using T = float; };
+template <> struct Pack<2> { using T = float2; };
+template <> struct Pack<4> { using T = float4; };
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(float (&x)[VEC], const float* p) {
+    using T = typename Pack<VEC>::T;
+    T t = *reinterpret_cast<const T*>(p);
+    const float* f = reinterpret_cast<const float*>(&t);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) x[v] = f[v];
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float* p, const float (&x)[VEC]) {
+    using T = typename Pack<VEC>::T;
+    T t;
+    float* f = reinterpret_cast<float*>(&t);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) f[v] = x[v];
+    *reinterpret_cast<T*>(p) = t;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous eighth of the
+// rows so that neighbouring rows (which read neighbouring children) share one L2.  The grid's
+// x extent is a multiple of 8.
+__device__ __forceinline__ int xcd_block(int bid, int nblocks) { return (bid & 7) * (nblocks >> 3) + (bid >> 3); }
+
+template <int OP, int VEC, int W>
+__global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
+    constexpr int RPW = 64 / W;                       // rows per wave
+    constexpr int CH = (OP == OP_SOFTMAX_BWD) ? 4 : 8;    // sources in flight per lane
+    const int lane = threadIdx.x & 63;
+    int wave = threadIdx.x >> 6;
+    if (W == 64) wave = __builtin_amdgcn_readfirstlane(wave);
+    const int sub = (W == 64) ? 0 : lane / W;
+    const int col = ((int)blockIdx.y * W + (lane % W)) * VEC;
+    if (col >= a.B) return;
+    const int blk = xcd_block((int)blockIdx.x, (int)gridDim.x);
+    const int64_t first_group = ((int64_t)blk * 4 + wave) * a.iters;
+
+    for (int it = 0; it < a.iters; ++it) {
+        const int64_t row64 = (first_group + it) * RPW + sub;
+        if (row64 >= a.n_total) break;
+        const int row = (int)row64;
+        const int beg = a.ptr[row], end = a.ptr[row + 1];
+        if (a.skip_empty && beg == end && row < a.n_main) continue;
+
+        float nc[VEC];                                // OP_SOFTMAX_BWD: own value
+        if (OP == OP_SOFTMAX_BWD) {
+            const int owner = row < a.n_main ? row : a.seg_owner[row - a.n_main];
+            load_vec<VEC>(nc, a.own + (size_t)owner * a.ld + col);
+        }
+        float acc[VEC], mx[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            acc[v] = (OP == OP_PROD) ? 1.0f : 0.0f;
+            mx[v] = -INFINITY;
+        }
+
+        for (int j = beg; j < end; j += CH) {
+            const int n = end - j;
+            int id[CH];
+#pragma unroll
+            for (int i = 0; i < CH; ++i) id[i] = a.idx[j + i];          // padded array: always in bounds
+            float x[CH][VEC], y[CH][VEC];
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                if (i < n) {
+                    load_vec<VEC>(x[i], a.src + (size_t)id[i] * a.ld + col);
+                    if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], a.src2 + (size_t)id[i] * a.ld + col);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        x[i][v] = (OP == OP_PROD) ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
+                        y[i][v] = 0.0f;
+                    }
+                }
+            }
+            if (OP == OP_SUM) {
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] += x[i][v];
+            } else if (OP == OP_PROD) {
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] *= x[i][v];
+            } else if (OP == OP_LSE) {
+                // running (max, sum of exp(x - max)); one rescale per chunk
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float cm = x[0][v];
+#pragma unroll
+                    for (int i = 1; i < CH; ++i) cm = fmaxf(cm, x[i][v]);
+                    const float mn = fmaxf(mx[v], cm);
+                    const float sh = (mn == -INFINITY) ? 0.0f : mn;       // all -inf so far: avoid inf - inf
+                    float s = acc[v] * fexp(mx[v] - sh);
+#pragma unroll
+                    for (int i = 0; i < CH; ++i)
+                        if (i < n) s += fexp(x[i][v] - sh);
+                    acc[v] = s;
+                    mx[v] = mn;
+                }
+            } else {
+                // adjoint of logsumexp: g_parent * exp(own - parent), nothing from a -inf parent
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    if (i < n) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            const float wgt = (y[i][v] == -INFINITY) ? 0.0f : fexp(nc[v] - y[i][v]);
+                            acc[v] = fmaf(x[i][v], wgt, acc[v]);
+                        }
+                    }
+            }
+        }
+        if (OP == OP_LSE) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = (mx[v] == -INFINITY) ? -INFINITY : mx[v] + flog(acc[v]);
+        }
+        float* out;
+        if (row < a.n_main) out = a.dst + (size_t)(a.out_row ? a.out_row[row] : row) * a.ld + col;
+        else out = a.dst_seg + (size_t)(row - a.n_main) * a.ld + col;
+        store_vec<VEC>(out, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Leaf layer: leaf_weights[B,V] (batch-outer) -> wT[V,ld] (kept for the backward pass) and the
+// literal rows of layer 0; the negated literal gets 1-p (REAL) or log(1-exp(x)) (LOG).
+// Tile = 32 variables x 64 batch columns through LDS.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float log1mexp_f(float x) {
+    return x > -0.69314718f ? logf(-expm1f(x)) : log1pf(-expf(x));
+}
+
+__global__ __launch_bounds__(256) void leaf_fwd_kernel(const float* __restrict__ w, int B, int V, int ld,
+                                                       const int32_t* __restrict__ pos_row,
+                                                       const int32_t* __restrict__ neg_row,
+                                                       float* __restrict__ wT, float* __restrict__ act0,
+                                                       int log_domain) {
+    __shared__ float tile[32][65];
+    const int v0 = blockIdx.x * 32, b0 = blockIdx.y * 64;
+    {
+        const int vx = threadIdx.x & 31, by = threadIdx.x >> 5;
+        for (int k = 0; k < 8; ++k) {
+            const int b = b0 + by + 8 * k, v = v0 + vx;
+            tile[vx][by + 8 * k] = (b < B && v < V) ? w[(size_t)b * V + v] : 0.0f;
+        }
+    }
+    __syncthreads();
+    const int bx = threadIdx.x & 63, vy = threadIdx.x >> 6;
+    const int b = b0 + bx;
+    if (b >= ld) return;
+    for (int k = 0; k < 8; ++k) {
+        const int v = v0 + vy + 4 * k;
+        if (v >= V) break;
+        const float x = tile[vy + 4 * k][bx];
+        wT[(size_t)v * ld + b] = x;
+        const int pr = pos_row[v], nr = neg_row[v];
+        if (pr >= 0) act0[(size_t)pr * ld + b] = x;
+        if (nr >= 0) act0[(size_t)nr * ld + b] = (b >= B) ? 0.0f : (log_domain ? log1mexp_f(x) : 1.0f - x);
+    }
+}
+
+__global__ void fill_row_kernel(float* row, int ld, float value) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < ld) row[b] = value;
+}
+
+// out[b, r] = top[root_pos[r], b]
+__global__ void root_out_kernel(const float* __restrict__ top, const int32_t* __restrict__ root_pos,
+                                int B, int R, int ld, float* __restrict__ out) {
+    const int r = blockIdx.x;
+    const float* row = top + (size_t)root_pos[r] * ld;
+    for (int b = threadIdx.x; b < B; b += blockDim.x) out[(size_t)b * R + r] = row[b];
+}
+
+// G_top[i, b] = sum of dout[b, r] over the root columns r that read top-layer node i
+__global__ void seed_kernel(const float* __restrict__ dout, const int32_t* __restrict__ top_ptr,
+                            const int32_t* __restrict__ top_root, int B, int R, int ld,
+                            float* __restrict__ g) {
+    const int i = blockIdx.x;
+    for (int b = threadIdx.x; b < ld; b += blockDim.x) {
+        float acc = 0.0f;
+        if (b < B)
+            for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)b * R + top_root[t]];
+        g[(size_t)i * ld + b] = acc;
+    }
+}
+
+// dleaf[b, v] = G0[+v, b] + G0[-v, b] * d(negated weight)/d(weight); tile transposed through LDS.
+__global__ __launch_bounds__(256) void leaf_bwd_kernel(const float* __restrict__ g0, const float* __restrict__ wT,
+                                                       const int32_t* __restrict__ pos_row,
+                                                       const int32_t* __restrict__ neg_row, int B, int V,
+                                                       int ld, int log_domain, float* __restrict__ dleaf) {
+    __shared__ float tile[32][65];
+    const int v0 = blockIdx.x * 32, b0 = blockIdx.y * 64;
+    {
+        const int bx = threadIdx.x & 63, vy = threadIdx.x >> 6;
+        const int b = b0 + bx;
+        for (int k = 0; k < 8; ++k) {
+            const int v = v0 + vy + 4 * k;
+            float d = 0.0f;
+            if (v < V && b < B) {
+                const int pr = pos_row[v], nr = neg_row[v];
+                if (pr >= 0) d = g0[(size_t)pr * ld + b];
+                if (nr >= 0) {
+                    const float gn = g0[(size_t)nr * ld + b];
+                    if (gn != 0.0f) d += log_domain ? -gn / expm1f(-wT[(size_t)v * ld + b]) : -gn;
+                }
+            }
+            tile[vy + 4 * k][bx] = d;
+        }
+    }
+    __syncthreads();
+    const int vx = threadIdx.x & 31, by = threadIdx.x >> 5;
+    for (int k = 0; k < 8; ++k) {
+        const int b = b0 + by + 8 * k, v = v0 + vx;
+        if (b < B && v < V) dleaf[(size_t)b * V + v] = tile[vx][by + 8 * k];
+    }
+}
+
+}  // namespace klay

@@ -1,0 +1,407 @@
+// Host-side layerization and tensorization (paper Section 3.1 Eq. 2, Section 3.2, Alg. 2, Alg. 3).
+#include "layerize.h"
+
+#include <algorithm>
+#include <climits>
+#include <cmath>
+#include <numeric>
+
+namespace klay {
+
+namespace {
+enum : uint8_t { T_LIT = 0, T_AND = 1, T_OR = 2, T_TRUE = 3, T_FALSE = 4 };
+constexpr int ST_OK = 0, ST_INVAL = 1, ST_CYCLE = 2;
+
+// Segment length for a split row of k sources: about sqrt(k), so that the segment pass and
+// the combine pass both see rows of that length.
+int32_t segment_len(int64_t k, const Options& opt) {
+    int64_t s = (int64_t)std::ceil(std::sqrt((double)k));
+    return (int32_t)std::max<int64_t>(s, std::max(1, opt.min_segment));
+}
+}  // namespace
+
+void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out) {
+    const int64_t e = ptr[n];
+    out = PassPlan();
+    out.n_main = (int32_t)n;
+    out.edges = e;
+    const int32_t heavy = std::max(1, opt.heavy_fan);
+    int64_t n_seg = 0, n_heavy = 0, heavy_edges = 0;
+    for (int64_t r = 0; r < n; ++r) {
+        int64_t k = ptr[r + 1] - ptr[r];
+        if (k > heavy) {
+            int32_t s = segment_len(k, opt);
+            n_seg += (k + s - 1) / s;
+            ++n_heavy;
+            heavy_edges += k;
+        }
+    }
+    out.n_seg = (int32_t)n_seg;
+    out.n_heavy = (int32_t)n_heavy;
+    out.ptr.resize((size_t)(n + n_seg + 1));
+    out.idx.assign((size_t)(e + 8), 0);
+    out.seg_owner.resize((size_t)n_seg);
+    out.comb_ptr.resize((size_t)(n_heavy + 1));
+    out.comb_row.resize((size_t)n_heavy);
+    // light rows keep their order and their edges come first; split rows get an empty range
+    int32_t w = 0;
+    for (int64_t r = 0; r < n; ++r) {
+        out.ptr[(size_t)r] = w;
+        int64_t k = ptr[r + 1] - ptr[r];
+        if (k <= heavy) {
+            std::copy(idx + ptr[r], idx + ptr[r + 1], out.idx.begin() + w);
+            w += (int32_t)k;
+        }
+    }
+    out.ptr[(size_t)n] = w;
+    int64_t seg = 0, h = 0;
+    out.comb_ptr[0] = 0;
+    for (int64_t r = 0; r < n && n_heavy; ++r) {
+        int64_t k = ptr[r + 1] - ptr[r];
+        if (k <= heavy) continue;
+        int32_t s = segment_len(k, opt);
+        for (int64_t a = 0; a < k; a += s) {
+            int64_t len = std::min<int64_t>(s, k - a);
+            std::copy(idx + ptr[r] + a, idx + ptr[r] + a + len, out.idx.begin() + w);
+            w += (int32_t)len;
+            out.seg_owner[(size_t)seg] = (int32_t)r;
+            ++seg;
+            out.ptr[(size_t)(n + seg)] = w;
+        }
+        out.comb_row[(size_t)h] = (int32_t)r;
+        out.comb_ptr[(size_t)(++h)] = (int32_t)seg;
+    }
+    (void)heavy_edges;
+}
+
+int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node_lit,
+             const int64_t* child_ptr, const int32_t* child_idx_in, int32_t R, const int32_t* roots_in,
+             const Options& opt, CircuitPlan& plan, std::string& err) {
+    plan = CircuitPlan();
+    const int32_t* child_idx = child_idx_in;
+    const int32_t* roots = roots_in;
+    // ---------------------------------------------------------------- validation
+    if (V < 0 || N <= 0 || R <= 0 || !node_type || !node_lit || !child_ptr || !roots) {
+        err = "klay_build: null array or non-positive size";
+        return ST_INVAL;
+    }
+    if (N >= INT32_MAX) { err = "klay_build: more than 2^31-1 nodes"; return ST_INVAL; }
+    if (child_ptr[0] != 0) { err = "klay_build: child_ptr[0] must be 0"; return ST_INVAL; }
+    for (int64_t i = 0; i < N; ++i)
+        if (child_ptr[i + 1] < child_ptr[i]) { err = "klay_build: child_ptr is not monotone"; return ST_INVAL; }
+    const int64_t E = child_ptr[N];
+    if (E > 0 && !child_idx) { err = "klay_build: child_idx is null"; return ST_INVAL; }
+    for (int64_t i = 0; i < N; ++i) {
+        const int64_t k = child_ptr[i + 1] - child_ptr[i];
+        switch (node_type[i]) {
+        case T_LIT: {
+            int64_t l = node_lit[i];
+            if (l == 0 || std::llabs(l) > V) {
+                err = "klay_build: literal of node " + std::to_string(i) + " out of range";
+                return ST_INVAL;
+            }
+        }   // fallthrough
+        case T_TRUE:
+        case T_FALSE:
+            if (k != 0) { err = "klay_build: leaf node " + std::to_string(i) + " has children"; return ST_INVAL; }
+            break;
+        case T_AND:
+        case T_OR:
+            if (k == 0) { err = "klay_build: gate " + std::to_string(i) + " has no children"; return ST_INVAL; }
+            break;
+        default:
+            err = "klay_build: unknown node type at node " + std::to_string(i);
+            return ST_INVAL;
+        }
+    }
+    for (int64_t j = 0; j < E; ++j)
+        if (child_idx[j] < 0 || child_idx[j] >= N) { err = "klay_build: child index out of range"; return ST_INVAL; }
+    for (int32_t r = 0; r < R; ++r)
+        if (roots[r] < 0 || roots[r] >= N) { err = "klay_build: root index out of range"; return ST_INVAL; }
+
+    // Leaves that carry the same literal (or the same constant) are one node: every reference is
+    // redirected to the first of them (the leaf case of the node identification of Section 3.2).
+    std::vector<int32_t> cidx((size_t)E), croots((size_t)R);
+    {
+        std::vector<int32_t> first_lit((size_t)2 * V + 2, -1), canon((size_t)N);
+        for (int64_t i = 0; i < N; ++i) {
+            canon[(size_t)i] = (int32_t)i;
+            int64_t slot = -1;
+            if (node_type[i] == T_LIT) slot = 2 * (std::llabs((int64_t)node_lit[i]) - 1) + (node_lit[i] < 0 ? 1 : 0);
+            else if (node_type[i] == T_TRUE) slot = 2 * (int64_t)V;
+            else if (node_type[i] == T_FALSE) slot = 2 * (int64_t)V + 1;
+            if (slot >= 0) {
+                if (first_lit[(size_t)slot] < 0) first_lit[(size_t)slot] = (int32_t)i;
+                canon[(size_t)i] = first_lit[(size_t)slot];
+            }
+        }
+        for (int64_t j = 0; j < E; ++j) cidx[(size_t)j] = canon[(size_t)child_idx[j]];
+        for (int32_t r = 0; r < R; ++r) croots[(size_t)r] = canon[(size_t)roots[r]];
+        child_idx = cidx.data();
+        roots = croots.data();
+        std::vector<int32_t> stamp((size_t)N, -1);
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t j = child_ptr[i]; j < child_ptr[i + 1]; ++j) {
+                int32_t c = child_idx[j];
+                if (stamp[(size_t)c] == (int32_t)i) { err = "klay_build: gate " + std::to_string(i) + " lists a child twice"; return ST_INVAL; }
+                stamp[(size_t)c] = (int32_t)i;
+            }
+    }
+
+    // ---------------------------------------------------------------- parents of every node
+    std::vector<int64_t> par_ptr((size_t)N + 1, 0);
+    for (int64_t j = 0; j < E; ++j) ++par_ptr[(size_t)child_idx[j] + 1];
+    for (int64_t i = 0; i < N; ++i) par_ptr[(size_t)i + 1] += par_ptr[(size_t)i];
+    std::vector<int32_t> par_idx((size_t)E);
+    {
+        std::vector<int64_t> fill(par_ptr.begin(), par_ptr.end() - 1);
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t j = child_ptr[i]; j < child_ptr[i + 1]; ++j) par_idx[(size_t)fill[(size_t)child_idx[j]]++] = (int32_t)i;
+    }
+
+    // ---------------------------------------------------------------- heights, children first (Eq. 2)
+    // h = 0 for leaves, 1 + max over children otherwise; a gate whose parity disagrees with its
+    // type (AND must sit on an odd layer, OR on an even one) is lifted by one layer.
+    std::vector<int32_t> h((size_t)N, 0);
+    {
+        std::vector<int64_t> pending((size_t)N);
+        std::vector<int32_t> ready;
+        ready.reserve((size_t)N);
+        for (int64_t i = 0; i < N; ++i) {
+            pending[(size_t)i] = child_ptr[i + 1] - child_ptr[i];
+            if (pending[(size_t)i] == 0) ready.push_back((int32_t)i);
+        }
+        int64_t done = 0;
+        while (!ready.empty()) {
+            int32_t n = ready.back();
+            ready.pop_back();
+            ++done;
+            if (node_type[n] == T_AND || node_type[n] == T_OR) {
+                int32_t m = 0;
+                for (int64_t j = child_ptr[n]; j < child_ptr[n + 1]; ++j) m = std::max(m, h[(size_t)child_idx[j]]);
+                int32_t hn = m + 1;
+                const bool odd = (hn & 1) != 0;
+                if ((node_type[n] == T_AND) != odd) ++hn;
+                h[(size_t)n] = hn;
+            }
+            for (int64_t j = par_ptr[(size_t)n]; j < par_ptr[(size_t)n + 1]; ++j)
+                if (--pending[(size_t)par_idx[(size_t)j]] == 0) ready.push_back(par_idx[(size_t)j]);
+        }
+        if (done != N) { err = "klay_build: the node graph has a cycle"; return ST_CYCLE; }
+    }
+
+    // ---------------------------------------------------------------- reachability from the roots
+    std::vector<uint8_t> reach((size_t)N, 0);
+    {
+        std::vector<int32_t> stack;
+        for (int32_t r = 0; r < R; ++r)
+            if (!reach[(size_t)roots[r]]) { reach[(size_t)roots[r]] = 1; stack.push_back(roots[r]); }
+        while (!stack.empty()) {
+            int32_t n = stack.back();
+            stack.pop_back();
+            for (int64_t j = child_ptr[n]; j < child_ptr[n + 1]; ++j) {
+                int32_t c = child_idx[j];
+                if (!reach[(size_t)c]) { reach[(size_t)c] = 1; stack.push_back(c); }
+            }
+        }
+    }
+    int32_t L = 0;
+    for (int32_t r = 0; r < R; ++r) L = std::max(L, h[(size_t)roots[r]]);
+
+    // ---------------------------------------------------------------- unary chains (Section 3.1; one per (child, layer))
+    // need[c] = highest layer at which a stand-in for c is read: parent height - 1, or L for roots.
+    std::vector<int32_t> need(h);
+    for (int64_t p = 0; p < N; ++p) {
+        if (!reach[(size_t)p]) continue;
+        plan.dag_nodes++;
+        plan.dag_edges += child_ptr[p + 1] - child_ptr[p];
+        for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) {
+            int32_t c = child_idx[j];
+            need[(size_t)c] = std::max(need[(size_t)c], h[(size_t)p] - 1);
+        }
+    }
+    for (int32_t r = 0; r < R; ++r) need[(size_t)roots[r]] = L;
+
+    std::vector<int64_t> count((size_t)L + 1, 0);
+    std::vector<int64_t> pad_base((size_t)N + 1, 0);
+    for (int64_t c = 0; c < N; ++c) {
+        pad_base[(size_t)c + 1] = pad_base[(size_t)c];
+        if (!reach[(size_t)c]) continue;
+        ++count[(size_t)h[(size_t)c]];
+        const int32_t pads = need[(size_t)c] - h[(size_t)c];
+        pad_base[(size_t)c + 1] += pads;
+        for (int32_t l = h[(size_t)c] + 1; l <= need[(size_t)c]; ++l) ++count[(size_t)l];
+    }
+    plan.num_pad_nodes = pad_base[(size_t)N];
+    for (int32_t l = 0; l <= L; ++l)
+        if (count[(size_t)l] >= INT32_MAX) { err = "klay_build: a layer has more than 2^31-1 nodes"; return ST_INVAL; }
+
+    // slot of every node within its layer before ordering: real nodes by id, then chain nodes by id
+    std::vector<int32_t> pos_real((size_t)N, -1);
+    std::vector<int32_t> pos_pad((size_t)plan.num_pad_nodes, -1);
+    plan.layers.resize((size_t)L + 1);
+    {
+        std::vector<int64_t> fill((size_t)L + 1, 0);
+        for (int32_t l = 0; l <= L; ++l) {
+            plan.layers[(size_t)l].n = count[(size_t)l];
+            plan.layers[(size_t)l].origin.resize((size_t)count[(size_t)l]);
+            plan.layers[(size_t)l].is_pad.assign((size_t)count[(size_t)l], 0);
+        }
+        for (int64_t c = 0; c < N; ++c)
+            if (reach[(size_t)c]) {
+                int32_t l = h[(size_t)c];
+                pos_real[(size_t)c] = (int32_t)fill[(size_t)l];
+                plan.layers[(size_t)l].origin[(size_t)fill[(size_t)l]++] = (int32_t)c;
+            }
+        for (int64_t c = 0; c < N; ++c)
+            if (reach[(size_t)c])
+                for (int32_t l = h[(size_t)c] + 1; l <= need[(size_t)c]; ++l) {
+                    pos_pad[(size_t)(pad_base[(size_t)c] + l - h[(size_t)c] - 1)] = (int32_t)fill[(size_t)l];
+                    plan.layers[(size_t)l].origin[(size_t)fill[(size_t)l]] = (int32_t)c;
+                    plan.layers[(size_t)l].is_pad[(size_t)fill[(size_t)l]++] = 1;
+                }
+    }
+    // position of the stand-in of node c at `level` (h[c] <= level <= need[c])
+    auto at = [&](int32_t c, int32_t level) -> int32_t {
+        return level == h[(size_t)c] ? pos_real[(size_t)c]
+                                     : pos_pad[(size_t)(pad_base[(size_t)c] + level - h[(size_t)c] - 1)];
+    };
+    auto set_at = [&](int32_t c, int32_t level, int32_t p) {
+        if (level == h[(size_t)c]) pos_real[(size_t)c] = p;
+        else pos_pad[(size_t)(pad_base[(size_t)c] + level - h[(size_t)c] - 1)] = p;
+    };
+
+    // ---------------------------------------------------------------- node order within layers (Section 4: arbitrary)
+    // Layer 0: by variable, positive literal first, then constants.  Higher layers: by the mean
+    // position of a node's children in the layer below, so rows evaluated together read
+    // neighbouring rows (one bottom-up barycentre sweep); ties keep slot order.
+    auto apply_order = [&](int32_t l, const std::vector<int32_t>& order /* new position -> old slot */) {
+        LayerPlan& lay = plan.layers[(size_t)l];
+        std::vector<int32_t> origin(lay.origin.size());
+        std::vector<uint8_t> is_pad(lay.is_pad.size());
+        for (size_t p = 0; p < order.size(); ++p) {
+            origin[p] = lay.origin[(size_t)order[p]];
+            is_pad[p] = lay.is_pad[(size_t)order[p]];
+            set_at(origin[p], l, (int32_t)p);
+        }
+        lay.origin.swap(origin);
+        lay.is_pad.swap(is_pad);
+    };
+    {
+        LayerPlan& l0 = plan.layers[0];
+        std::vector<int32_t> order((size_t)l0.n);
+        std::iota(order.begin(), order.end(), 0);
+        auto key = [&](int32_t slot) -> int64_t {
+            int32_t c = l0.origin[(size_t)slot];
+            if (node_type[c] == T_LIT) {
+                int64_t lit = node_lit[c];
+                return 2 * (std::llabs(lit) - 1) + (lit < 0 ? 1 : 0);
+            }
+            return 2 * (int64_t)V + (node_type[c] == T_TRUE ? 0 : 1);
+        };
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key(a) < key(b); });
+        apply_order(0, order);
+    }
+    if (!opt.no_reorder) {
+        for (int32_t l = 1; l <= L; ++l) {
+            LayerPlan& lay = plan.layers[(size_t)l];
+            std::vector<double> key((size_t)lay.n);
+            for (int64_t s = 0; s < lay.n; ++s) {
+                int32_t c = lay.origin[(size_t)s];
+                if (lay.is_pad[(size_t)s]) key[(size_t)s] = at(c, l - 1);
+                else {
+                    double acc = 0;
+                    for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) acc += at(child_idx[j], l - 1);
+                    key[(size_t)s] = acc / (double)(child_ptr[c + 1] - child_ptr[c]);
+                }
+            }
+            std::vector<int32_t> order((size_t)lay.n);
+            std::iota(order.begin(), order.end(), 0);
+            std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[(size_t)a] < key[(size_t)b]; });
+            apply_order(l, order);
+        }
+    }
+
+    // ---------------------------------------------------------------- index vectors per layer (Alg. 3), CSR by parent
+    Options popt = opt;
+    for (int32_t l = 1; l <= L; ++l) {
+        LayerPlan& lay = plan.layers[(size_t)l];
+        int64_t e = 0;
+        for (int64_t p = 0; p < lay.n; ++p)
+            e += lay.is_pad[(size_t)p] ? 1 : child_ptr[lay.origin[(size_t)p] + 1] - child_ptr[lay.origin[(size_t)p]];
+        if (e >= INT32_MAX - 16) { err = "klay_build: a layer has more than 2^31 edges"; return ST_INVAL; }
+        lay.e = e;
+        lay.row_ptr.resize((size_t)lay.n + 1);
+        lay.child.resize((size_t)e);
+        int32_t w = 0;
+        for (int64_t p = 0; p < lay.n; ++p) {
+            lay.row_ptr[(size_t)p] = w;
+            int32_t c = lay.origin[(size_t)p];
+            if (lay.is_pad[(size_t)p]) lay.child[(size_t)w++] = at(c, l - 1);
+            else {
+                const int32_t w0 = w;
+                for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) lay.child[(size_t)w++] = at(child_idx[j], l - 1);
+                std::sort(lay.child.begin() + w0, lay.child.begin() + w);
+            }
+            plan.max_fan_in = std::max<int64_t>(plan.max_fan_in, w - lay.row_ptr[(size_t)p]);
+        }
+        lay.row_ptr[(size_t)lay.n] = w;
+        make_pass_plan(lay.n, lay.row_ptr.data(), lay.child.data(), popt, lay.fwd);
+
+        // by child (for the reverse sweep): rows = nodes of layer l-1, sources = parents in layer l
+        const int64_t nc = plan.layers[(size_t)l - 1].n;
+        std::vector<int32_t> cptr((size_t)nc + 1, 0), cpar((size_t)e);
+        for (int64_t j = 0; j < e; ++j) ++cptr[(size_t)lay.child[(size_t)j] + 1];
+        for (int64_t i = 0; i < nc; ++i) {
+            plan.max_fan_out = std::max<int64_t>(plan.max_fan_out, cptr[(size_t)i + 1]);
+            cptr[(size_t)i + 1] += cptr[(size_t)i];
+        }
+        {
+            std::vector<int32_t> fill(cptr.begin(), cptr.end() - 1);
+            for (int64_t p = 0; p < lay.n; ++p)
+                for (int32_t j = lay.row_ptr[(size_t)p]; j < lay.row_ptr[(size_t)p + 1]; ++j)
+                    cpar[(size_t)fill[(size_t)lay.child[(size_t)j]]++] = (int32_t)p;
+        }
+        make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd);
+        plan.num_split_rows += lay.fwd.n_heavy + lay.bwd.n_heavy;
+        plan.max_fwd_seg = std::max<int64_t>(plan.max_fwd_seg, lay.fwd.n_seg);
+        plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, lay.bwd.n_seg);
+        plan.num_edges += e;
+    }
+    for (int32_t l = 0; l <= L; ++l) {
+        plan.num_nodes += plan.layers[(size_t)l].n;
+        plan.max_layer_nodes = std::max(plan.max_layer_nodes, plan.layers[(size_t)l].n);
+    }
+
+    // ---------------------------------------------------------------- leaf layer and roots
+    plan.num_vars = V;
+    plan.num_roots = R;
+    plan.num_layers = L;
+    plan.pos_row.assign((size_t)V, -1);
+    plan.neg_row.assign((size_t)V, -1);
+    plan.leaf_code.resize((size_t)plan.layers[0].n);
+    for (int64_t p = 0; p < plan.layers[0].n; ++p) {
+        int32_t c = plan.layers[0].origin[(size_t)p];
+        if (node_type[c] == T_LIT) {
+            int32_t lit = node_lit[c];
+            plan.leaf_code[(size_t)p] = lit;
+            (lit > 0 ? plan.pos_row : plan.neg_row)[(size_t)(std::abs(lit) - 1)] = (int32_t)p;
+        } else {
+            plan.leaf_code[(size_t)p] = node_type[c] == T_TRUE ? INT32_MAX : INT32_MIN;
+        }
+    }
+    plan.root_pos.resize((size_t)R);
+    for (int32_t r = 0; r < R; ++r) plan.root_pos[(size_t)r] = at(roots[r], L);
+    {
+        const int64_t nt = plan.layers[(size_t)L].n;
+        plan.top_ptr.assign((size_t)nt + 1, 0);
+        plan.top_root.resize((size_t)R);
+        for (int32_t r = 0; r < R; ++r) ++plan.top_ptr[(size_t)plan.root_pos[(size_t)r] + 1];
+        for (int64_t i = 0; i < nt; ++i) plan.top_ptr[(size_t)i + 1] += plan.top_ptr[(size_t)i];
+        std::vector<int32_t> fill(plan.top_ptr.begin(), plan.top_ptr.end() - 1);
+        for (int32_t r = 0; r < R; ++r) plan.top_root[(size_t)fill[(size_t)plan.root_pos[(size_t)r]]++] = r;
+    }
+    return ST_OK;
+}
+
+}  // namespace klay

@@ -1,0 +1,65 @@
+// Host-side layerization and tensorization of a circuit DAG (paper Section 3.1 Eq. 2,
+// Section 3.2, Appendix C Alg. 2 and Alg. 3).  Pure C++, no device code: the result is a set
+// of plain index arrays that the evaluator uploads once.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+namespace klay {
+
+struct Options {
+    bool no_reorder = false;
+    int32_t heavy_fan = 128;    // rows with more sources than this are evaluated in split passes
+    int32_t min_segment = 32;   // smallest segment of a split row, in edges
+};
+
+// One gather-reduce pass set over a CSR whose rows are the outputs.
+//   rows [0, n_main)                 write output row i; an empty range marks a split row
+//   rows [n_main, n_main + n_seg)    are segments of split rows, writing scratch row (i - n_main)
+//   combine: output row comb_row[h] reduces scratch rows [comb_ptr[h], comb_ptr[h+1])
+struct PassPlan {
+    int32_t n_main = 0;
+    int32_t n_seg = 0;
+    int32_t n_heavy = 0;
+    int64_t edges = 0;
+    std::vector<int32_t> ptr;        // [n_main + n_seg + 1]
+    std::vector<int32_t> idx;        // [edges + 8], zero padded so 8-wide index reads stay in bounds
+    std::vector<int32_t> seg_owner;  // [n_seg] output row each segment belongs to
+    std::vector<int32_t> comb_ptr;   // [n_heavy + 1]
+    std::vector<int32_t> comb_row;   // [n_heavy]
+};
+
+struct LayerPlan {
+    int64_t n = 0;                   // nodes in this layer
+    int64_t e = 0;                   // edges from this layer down to layer - 1
+    std::vector<int32_t> row_ptr;    // [n + 1] plain CSR by parent (Alg. 3: R_l implicit)
+    std::vector<int32_t> child;      // [e]    S_l: position of the child in layer - 1
+    std::vector<int32_t> origin;     // [n] input node id the row stands for
+    std::vector<uint8_t> is_pad;     // [n] 1 for unary chain nodes
+    PassPlan fwd;                    // outputs = nodes of this layer, sources = layer - 1
+    PassPlan bwd;                    // outputs = nodes of layer - 1, sources = this layer
+};
+
+struct CircuitPlan {
+    int32_t num_vars = 0, num_roots = 0, num_layers = 0;
+    std::vector<LayerPlan> layers;       // 0 .. num_layers
+    std::vector<int32_t> leaf_code;      // layer 0: +(v+1), -(v+1), INT32_MAX (TRUE), INT32_MIN (FALSE)
+    std::vector<int32_t> pos_row, neg_row;   // [V] layer-0 row of each literal or -1
+    std::vector<int32_t> root_pos;       // [R] position of each root in the top layer
+    std::vector<int32_t> top_ptr, top_root;  // top-layer node -> root columns that read it
+    int64_t num_nodes = 0, num_edges = 0, dag_nodes = 0, dag_edges = 0, num_pad_nodes = 0;
+    int64_t max_layer_nodes = 0, max_fan_in = 0, max_fan_out = 0, num_split_rows = 0;
+    int64_t max_fwd_seg = 0, max_bwd_seg = 0;   // scratch rows needed by split passes
+};
+
+// Status codes mirror klay_status (0 ok, 1 invalid, 2 cycle, 3 no memory).
+int layerize(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type, const int32_t* node_lit,
+             const int64_t* child_ptr, const int32_t* child_idx, int32_t num_roots,
+             const int32_t* roots, const Options& opt, CircuitPlan& plan, std::string& err);
+
+// Split a CSR (n rows, ptr[n+1], idx) into main rows, segments and combine rows.
+void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out);
+
+}  // namespace klay

@@ -1,0 +1,34 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/klay.h declares."""
+import ctypes
+import os
+import re
+
+from paper_2410_11415_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "klay.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(klay_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = binding.load()
+    names = declared_functions()
+    assert "klay_build" in names and "klay_forward" in names and "klay_backward" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_struct_sizes_match_the_header():
+    assert ctypes.sizeof(binding.klay_options) == 32
+    assert ctypes.sizeof(binding.klay_info_t) == 16 + 10 * 8
+    assert ctypes.sizeof(binding.klay_profile_t) == 9 * 4 + 9 * 4 + 9 * 8
+    assert len(binding.KERNEL_CLASSES) == 9
+
+
+def test_last_error_is_a_string():
+    assert isinstance(binding.klay_last_error(), str)

@@ -1,0 +1,243 @@
+"""Host-side layerization / tensorization (klay_build with device = -1) against the paper's worked
+examples (Section 3.1 Figure 2, Section 3.2 Figure 3, Section 4 Figure 4) and structural invariants.
+No GPU needed."""
+import numpy as np
+import pytest
+
+from klay_synth import AND, LIT, OR, CircuitBuilder, layered_random, make_config, tiny_ddnnf
+from paper_2410_11415_amd import Circuit, KlayError
+from paper_2410_11415_amd.binding import KLAY_ECYCLE, KLAY_EINVAL, KLAY_ESTATE
+
+
+def host(c, **kw):
+    return Circuit(*c.arrays(), device=-1, **kw)
+
+
+def ints(meta_value):
+    return [int(x) for x in meta_value]
+
+
+def canonical_edges(row_ptr, child, child_names, parent_names):
+    """multiset of (parent label, child label) pairs of one layer"""
+    out = []
+    for r in range(len(row_ptr) - 1):
+        for j in range(row_ptr[r], row_ptr[r + 1]):
+            out.append((parent_names[r], child_names[child[j]]))
+    return sorted(out)
+
+
+def test_fig2_layer_and_edge_counts(golden):
+    c = golden("fig1b_ddnnf.txt")
+    k = host(c)
+    nodes, edges = k.layer_sizes()
+    assert nodes.tolist() == ints(c.meta["layer_nodes"])
+    assert edges[1:].tolist() == ints(c.meta["layer_edges"])
+    info = k.info()
+    assert info["num_nodes"] == 25 and info["num_pad_nodes"] == 10
+    assert info["dag_nodes"] == 15 and info["dag_edges"] == 16
+
+
+def test_fig4_first_layer_index_vectors(golden):
+    """S_1 / R_1 of Figure 4, up to the (arbitrary) order of the nodes of layer 1."""
+    c = golden("fig1b_ddnnf.txt")
+    k = host(c)
+    origin0, pad0 = k.layer_nodes(0)
+    # layer 0 is ordered a, -a, b, -b, c, -c, d, -d as in Section 4
+    assert c.node_lit[origin0].tolist() == [1, -1, 2, -2, 3, -3, 4, -4] and not pad0.any()
+    row_ptr, child = k.layer_csr(1)
+    S1, R1 = ints(c.meta["S1"]), ints(c.meta["R1"])
+    paper_rows = sorted(tuple(sorted(s for s, r in zip(S1, R1) if r == p)) for p in set(R1))
+    ours = sorted(tuple(sorted(child[row_ptr[r]:row_ptr[r + 1]].tolist())) for r in range(len(row_ptr) - 1))
+    assert ours == paper_rows
+
+
+def test_fig3_merged_two_root_circuit(golden):
+    c = golden("fig3_multiroot.txt")
+    k = host(c)
+    nodes, edges = k.layer_sizes()
+    assert nodes.tolist() == ints(c.meta["layer_nodes"])
+    assert edges[1:].tolist() == ints(c.meta["layer_edges"])
+    single = golden("fig3a_single.txt")
+    assert host(single).layer_sizes()[0].tolist() == ints(single.meta["layer_nodes"])
+
+
+def check_structure(c, k):
+    """Invariants of Section 3.1: every child sits in the layer directly below; odd layers hold AND
+    gates and even layers OR gates (chain nodes aside); one chain node per (node, layer); the layered
+    circuit restricted to real nodes is the input DAG."""
+    nodes, edges = k.layer_sizes()
+    L = len(nodes) - 1
+    below_origin, below_pad = k.layer_nodes(0)
+    assert not below_pad.any()
+    seen_real = set(below_origin.tolist())
+    dag_edges = set()
+    for l in range(1, L + 1):
+        origin, pad = k.layer_nodes(l)
+        row_ptr, child = k.layer_csr(l)
+        assert row_ptr[0] == 0 and row_ptr[-1] == edges[l] and np.all(np.diff(row_ptr) >= 1)
+        assert child.min() >= 0 and child.max() < nodes[l - 1]
+        # every node of the layer below is read by someone (otherwise it would be dead weight)
+        assert np.unique(child).size == nodes[l - 1]
+        real = origin[~pad]
+        want = AND if l % 2 == 1 else OR
+        assert np.all(c.node_type[real] == want)
+        assert len(set(zip(origin.tolist(), pad.tolist()))) == len(origin)
+        for r in range(len(origin)):
+            kids = below_origin[child[row_ptr[r]:row_ptr[r + 1]]]
+            if pad[r]:
+                assert len(kids) == 1 and kids[0] == origin[r]
+            else:
+                assert sorted(kids.tolist()) == sorted(_canon_children(c, origin[r]))
+                dag_edges.update((int(origin[r]), int(x)) for x in kids)
+        seen_real.update(real.tolist())
+        below_origin = origin
+    return seen_real, dag_edges
+
+
+def _canon_children(c, n):
+    """children with duplicate leaves mapped to the first node carrying the same literal"""
+    first = {}
+    for i in range(c.num_nodes):
+        if c.node_type[i] == LIT:
+            first.setdefault(int(c.node_lit[i]), i)
+    return [first[int(c.node_lit[x])] if c.node_type[x] == LIT else int(x) for x in c.children(n)]
+
+
+@pytest.mark.parametrize("no_reorder", [False, True])
+def test_structure_invariants_small_random(no_reorder):
+    c = layered_random(3, num_vars=24, depth=8, num_gates=400, fanin=("geom", 2.0), groups=2, num_roots=4)
+    k = host(c, no_reorder=no_reorder)
+    seen, dag_edges = check_structure(c, k)
+    info = k.info()
+    assert len(seen) == info["dag_nodes"]
+    assert len(dag_edges) == info["dag_edges"]
+    assert info["num_layers"] == 8
+    nodes, edges = k.layer_sizes()
+    assert nodes.sum() == info["num_nodes"] and edges.sum() == info["num_edges"]
+    assert info["num_nodes"] == info["dag_nodes"] + info["num_pad_nodes"]
+
+
+def test_structure_invariants_tiny_ddnnf():
+    c, _, _ = tiny_ddnnf(0)
+    check_structure(c, host(c))
+
+
+def test_parity_rule_lifts_gates_of_the_wrong_parity():
+    b = CircuitBuilder(3)
+    x, y, z = b.lit(0), b.lit(1), b.lit(2)
+    o = b.or_(x, y)              # OR directly over leaves: height 1 is odd -> lifted to layer 2
+    a = b.and_(o, z)             # layer 3
+    a2 = b.and_(a, x)            # AND under AND: 4 is even -> layer 5
+    c = b.finish([a2])
+    k = host(c)
+    nodes, _ = k.layer_sizes()
+    assert len(nodes) - 1 == 5
+    for l, want in [(2, o), (3, a), (5, a2)]:
+        origin, pad = k.layer_nodes(l)
+        assert origin[~pad].tolist() == [want]
+    check_structure(c, k)
+
+
+def test_roots_are_extended_to_a_common_height_and_may_repeat():
+    b = CircuitBuilder(2)
+    x, nx, y = b.lit(0), b.lit(0, False), b.lit(1)
+    a = b.and_(x, y)
+    o = b.or_(a, b.and_(nx, y))
+    c = b.finish([o, a, x, o])           # heights 2, 1, 0 and a repeated root
+    k = host(c)
+    nodes, _ = k.layer_sizes()
+    assert len(nodes) - 1 == 2
+    top, pad = k.layer_nodes(2)
+    assert sorted(zip(top.tolist(), pad.tolist())) == sorted([(o, False), (a, True), (x, True)])
+
+
+def test_leaf_roots_only_give_zero_layers():
+    b = CircuitBuilder(2)
+    c = b.finish([b.lit(1, False), b.lit(0)])
+    k = host(c)
+    assert k.info()["num_layers"] == 0 and k.layer_sizes()[0].tolist() == [2]
+
+
+def test_unreachable_nodes_are_dropped_and_duplicate_literals_merge():
+    b = CircuitBuilder(2)
+    x = b.lit(0)
+    b.types.append(LIT); b.lits.append(1); b.kids.append([])      # a second node carrying literal x0
+    x_dup = len(b.types) - 1
+    y = b.lit(1)
+    dead = b.or_(x, y)
+    root = b.and_(x_dup, y)
+    c = b.finish([root])
+    k = host(c)
+    info = k.info()
+    assert info["dag_nodes"] == 3 and info["num_nodes"] == 3 and dead not in k.layer_nodes(1)[0].tolist()
+    assert k.layer_sizes()[0].tolist() == [2, 1]
+
+
+def test_split_plans_cover_every_edge_once():
+    """rows above the fan threshold are evaluated as segments + combine; the plain CSR is unchanged"""
+    c = layered_random(1, num_vars=64, depth=6, num_gates=600, fanin=("zipf", 1.2, 200), groups=1, num_roots=3)
+    a, b_ = host(c), host(c, heavy_fan=4, min_segment=2)
+    assert b_.info()["num_split_rows"] > 0
+    for l in range(1, a.num_layers + 1):
+        ra, ca = a.layer_csr(l)
+        rb, cb = b_.layer_csr(l)
+        np.testing.assert_array_equal(ra, rb)
+        np.testing.assert_array_equal(ca, cb)
+
+
+@pytest.mark.parametrize("mutate,status", [
+    ("cycle", KLAY_ECYCLE), ("empty_gate", KLAY_EINVAL), ("dup_child", KLAY_EINVAL), ("bad_child", KLAY_EINVAL),
+    ("bad_lit", KLAY_EINVAL), ("bad_root", KLAY_EINVAL), ("leaf_with_child", KLAY_EINVAL), ("bad_type", KLAY_EINVAL),
+    ("dup_literal_child", KLAY_EINVAL),
+])
+def test_invalid_circuits_are_rejected(mutate, status):
+    node_type = np.array([LIT, LIT, AND, OR], dtype=np.uint8)
+    node_lit = np.array([1, -2, 0, 0], dtype=np.int32)
+    child_ptr = np.array([0, 0, 0, 2, 4], dtype=np.int64)
+    child_idx = np.array([0, 1, 2, 1], dtype=np.int32)
+    roots = np.array([3], dtype=np.int32)
+    V = 2
+    if mutate == "cycle":
+        child_idx = np.array([0, 3, 2, 1], dtype=np.int32)
+    elif mutate == "empty_gate":
+        child_ptr = np.array([0, 0, 0, 0, 2], dtype=np.int64); child_idx = child_idx[2:]
+    elif mutate == "dup_child":
+        child_idx = np.array([0, 0, 2, 1], dtype=np.int32)
+    elif mutate == "bad_child":
+        child_idx = np.array([0, 7, 2, 1], dtype=np.int32)
+    elif mutate == "bad_lit":
+        node_lit = np.array([1, -3, 0, 0], dtype=np.int32)
+    elif mutate == "bad_root":
+        roots = np.array([4], dtype=np.int32)
+    elif mutate == "leaf_with_child":
+        child_ptr = np.array([0, 1, 1, 3, 5], dtype=np.int64); child_idx = np.array([1, 0, 1, 2, 1], dtype=np.int32)
+    elif mutate == "bad_type":
+        node_type = np.array([LIT, 9, AND, OR], dtype=np.uint8)
+    elif mutate == "dup_literal_child":
+        node_lit = np.array([1, 1, 0, 0], dtype=np.int32)      # both leaves are x0: AND(x0, x0)
+    with pytest.raises(KlayError) as e:
+        Circuit(V, node_type, node_lit, child_ptr, child_idx, roots, device=-1)
+    assert e.value.status == status and len(str(e.value)) > 20
+
+
+def test_host_only_handle_refuses_evaluation():
+    import ctypes
+    from paper_2410_11415_amd import binding
+    c, _, _ = tiny_ddnnf(0)
+    k = host(c)
+    buf = (ctypes.c_float * 64)()
+    with pytest.raises(KlayError) as e:
+        binding.klay_forward(k._h, ctypes.addressof(buf), 1, ctypes.addressof(buf), binding.KLAY_LOG, 0)
+    assert e.value.status == KLAY_ESTATE
+    assert k.workspace_bytes(256) > 0
+
+
+def test_full_size_headline_circuit_layerizes():
+    c, _, _ = make_config("layered_3m_fwd_bwd", seed=0)
+    k = host(c)
+    info = k.info()
+    assert info["num_layers"] == 60
+    assert 2.9e6 < info["dag_nodes"] <= 3.0e6 and 0.95e7 < info["dag_edges"] < 1.05e7
+    assert info["num_nodes"] == info["dag_nodes"] + info["num_pad_nodes"]
+    nodes, edges = k.layer_sizes()
+    assert nodes[-1] == 64 and edges.sum() == info["num_edges"]
