@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: forward + backward of the layered circuit evaluator
+on the headline workload (3e6-node, 1e7-edge random layered circuit, depth 60, V=8192, B=256,
+fp32 log semiring), reported as edge-evaluations per second with the roofline of the dominant
+kernel and the CPU oracle timed beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Prints ONE JSON line.  A "step" is one klay_forward + klay_backward over one batch that is already
+resident in device memory; klay_build (host layerization + upload) is outside the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+class HipEvents:
+    """hipEvent timing on an explicit stream, straight from the HIP runtime."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = ctypes.c_void_p()
+        assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.hip.hipEventRecord(e, ctypes.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b):
+        assert self.hip.hipEventSynchronize(b) == 0
+        ms = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return float(ms.value)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="layered_3m_fwd_bwd")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the batch shards with no exchange; "
+              "see DESIGN.md); rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2410_11415_amd as pkg
+    from klay_synth import as_inputs, make_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    pkg.load()                                    # no fallback: fails if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    t0 = time.perf_counter()
+    circ, p, spec = make_config(args.workload, seed=args.seed, batch=args.batch)
+    t_gen = time.perf_counter() - t0
+    B = p.shape[0]
+    backward = bool(spec["backward"])
+    semiring = pkg.KLAY_LOG if "log" in spec["semirings"] else pkg.KLAY_REAL
+    w32 = as_inputs(p, semiring == pkg.KLAY_LOG)
+
+    t0 = time.perf_counter()
+    k = pkg.Circuit(*circ.arrays(), device=0)
+    t_build = time.perf_counter() - t0
+    info = k.info()
+    E, N = info["num_edges"], info["num_nodes"]
+
+    stream = torch.cuda.current_stream()
+    w = torch.from_numpy(w32).cuda()
+    out = torch.empty((B, k.num_roots), dtype=torch.float32, device="cuda")
+    dout = torch.ones((B, k.num_roots), dtype=torch.float32, device="cuda")
+    dleaf = torch.empty((B, k.num_vars), dtype=torch.float32, device="cuda")
+
+    def step():
+        k.forward(w, semiring, out=out, stream=stream)
+        if backward:
+            k.backward(dout, dleaf=dleaf, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev.record(e0, stream.cuda_stream)
+    for _ in range(args.steps):
+        step()
+    ev.record(e1, stream.cuda_stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_events = ev.elapsed_ms(e0, e1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = B * E * args.steps / wall
+
+    # per-kernel-class durations: the same steps again with HIP events around every launch group
+    k.set_profiling(True)
+    classes = {}
+    prof_steps = max(1, min(args.steps, 5))
+    t0 = time.perf_counter()
+    for _ in range(prof_steps):
+        step()
+        torch.cuda.synchronize()
+        for name, rec in k.get_profile().items():
+            c = classes.setdefault(name, {"ms": 0.0, "launches": 0, "alg_bytes": 0.0})
+            for f in c:
+                c[f] += rec[f]
+    k.set_profiling(False)
+    dom = max(classes, key=lambda n: classes[n]["ms"])
+    d = classes[dom]
+    achieved = d["alg_bytes"] / (d["ms"] * 1e-3) / 1e9 if d["ms"] > 0 else 0.0
+    kernel_ms_total = sum(c["ms"] for c in classes.values()) / prof_steps
+    alg_bytes_step = sum(c["alg_bytes"] for c in classes.values()) / prof_steps
+    roofline = {
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "kernel": dom, "kernel_avg_launch_us": round(d["ms"] * 1e3 / max(1, d["launches"]), 2),
+        "kernel_launches_per_step": d["launches"] // prof_steps,
+        "kernel_alg_bytes_per_launch": round(d["alg_bytes"] / max(1, d["launches"])),
+        "whole_step": {"alg_bytes": round(alg_bytes_step), "kernel_ms": round(kernel_ms_total, 3),
+                       "achieved_GBs": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
+                       "frac": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "per_class_ms": {n: round(c["ms"] / prof_steps, 3) for n, c in classes.items() if c["launches"]},
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        threads = min(oracle.max_threads(), 16)
+        cols = args.cpu_columns or (2 * threads if backward else 4 * threads)
+        cols = min(cols, B)
+        sample = np.ascontiguousarray(w32[:cols]).astype(np.float64)
+        t0 = time.perf_counter()
+        ref = oracle.forward(*circ.arrays(), sample, oracle.LOG if semiring == pkg.KLAY_LOG else oracle.REAL,
+                             nthreads=threads)
+        if backward:
+            rgrad = oracle.backward(*circ.arrays(), sample, oracle.LOG, np.ones_like(ref), nthreads=threads)
+        t_cpu = time.perf_counter() - t0
+        got = out[:cols].cpu().numpy()
+        err = float(np.abs(got - ref).max())
+        cpu_baseline = {
+            "value": cols * E / t_cpu, "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d batch columns of the same workload, %s, fp64 post-order over the unlayered DAG "
+                      "(%d nodes, %d edges); counted in layered edges like the GPU figure; %.1f s" % (
+                          cols, B, "forward+backward" if backward else "forward", info["dag_nodes"],
+                          info["dag_edges"], t_cpu),
+            "max_abs_err_vs_gpu": err,
+        }
+        if backward:
+            gerr = np.abs(dleaf[:cols].cpu().numpy() - rgrad) / np.maximum(1.0, np.abs(rgrad))
+            cpu_baseline["max_grad_err_vs_gpu"] = float(gerr.max())
+        cpu_baseline["max_abs_log_ref"] = float(np.abs(ref[np.isfinite(ref)]).max())
+
+    result = {
+        "metric": "edge-evals/sec (batch x edges/s) fwd+bwd at B=256; % of HBM roofline"
+                  if backward else "edge-evals/sec (batch x edges/s) forward",
+        "value": value, "unit": "edge-evals/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "ms_per_step_hip_events": ms_events / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": B, "semiring": "log" if semiring == pkg.KLAY_LOG else "real",
+                   "pass": "forward+backward" if backward else "forward", "seed": args.seed,
+                   "layers": info["num_layers"], "layered_nodes": N, "layered_edges": E,
+                   "dag_nodes": info["dag_nodes"], "dag_edges": info["dag_edges"],
+                   "pad_nodes": info["num_pad_nodes"], "num_vars": info["num_vars"], "num_roots": info["num_roots"],
+                   "max_fan_in": info["max_fan_in"], "max_fan_out": info["max_fan_out"],
+                   "build_seconds": round(t_build, 2), "generate_seconds": round(t_gen, 2)},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -165,12 +165,15 @@ int klay_oracle_forward(int32_t num_vars, int64_t num_nodes, const uint8_t* node
  *   literal +v       : dleaf += adj
  *   literal -v       : dleaf += adj * d(neg weight)/dw = -adj (REAL), -adj / expm1(-x) (LOG);
  *                      a zero adjoint contributes 0 even where that derivative is infinite.
+ * With abs_mode != 0 the same sweep runs on |dout| and adds |adj * d(neg weight)/dw| at negated
+ * literals, so that dleaf becomes the sum over all root-to-leaf paths of |contribution|: the
+ * scale against which a floating-point gradient's cancellation error has to be judged.
  */
 int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
                          const int32_t* node_lit, const int64_t* child_ptr,
                          const int32_t* child_idx, int32_t num_roots, const int32_t* roots,
                          int32_t B, const double* w, int semiring, const double* dout,
-                         double* dleaf, int nthreads) {
+                         double* dleaf, int nthreads, int abs_mode) {
     int32_t* order = (int32_t*)malloc(sizeof(int32_t) * ((size_t)num_nodes + 1));
     if (!order) return -2;
     int64_t n_order = klay_oracle_postorder(num_nodes, child_ptr, child_idx, num_roots, roots, order);
@@ -197,7 +200,10 @@ int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* nod
             eval_column(semiring, node_type, node_lit, child_ptr, child_idx, order, n_order, wb, val);
             for (int64_t i = 0; i < n_order; ++i) adj[order[i]] = 0.0;
             for (int32_t v = 0; v < num_vars; ++v) gb[v] = 0.0;
-            for (int32_t r = 0; r < num_roots; ++r) adj[roots[r]] += dout[(size_t)b * num_roots + r];
+            for (int32_t r = 0; r < num_roots; ++r) {
+                double d = dout[(size_t)b * num_roots + r];
+                adj[roots[r]] += abs_mode ? fabs(d) : d;
+            }
             for (int64_t i = n_order - 1; i >= 0; --i) {
                 int32_t n = order[i];
                 double g = adj[n];
@@ -207,7 +213,10 @@ int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* nod
                     int32_t l = node_lit[n];
                     int32_t v = (l > 0 ? l : -l) - 1;
                     if (l > 0) gb[v] += g;
-                    else if (g != 0.0) gb[v] += semiring == S_REAL ? -g : -g / expm1(-wb[v]);
+                    else if (g != 0.0) {
+                        double t = semiring == S_REAL ? -g : -g / expm1(-wb[v]);
+                        gb[v] += abs_mode ? fabs(t) : t;
+                    }
                     break;
                 }
                 case T_AND:

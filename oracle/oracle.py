@@ -51,7 +51,7 @@ def _load():
             lib.klay_oracle_forward.restype = ctypes.c_int
             lib.klay_oracle_forward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, ctypes.c_int, p, p, ctypes.c_int]
             lib.klay_oracle_backward.restype = ctypes.c_int
-            lib.klay_oracle_backward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, ctypes.c_int, p, p, ctypes.c_int]
+            lib.klay_oracle_backward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, ctypes.c_int, p, p, ctypes.c_int, ctypes.c_int]
             lib.klay_oracle_max_threads.restype = ctypes.c_int
             _lib = lib
             del dbl
@@ -116,8 +116,11 @@ def forward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights,
 
 
 def backward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights, semiring,
-             dout, nthreads: int = 1):
-    """``dleaf[B,V] = sum_r dout[b,r] * d out[b,r] / d weights[b,v]`` (fp64, reverse mode)."""
+             dout, nthreads: int = 1, path_mass: bool = False):
+    """``dleaf[B,V] = sum_r dout[b,r] * d out[b,r] / d weights[b,v]`` (fp64, reverse mode).
+
+    With ``path_mass`` the sweep runs on absolute values and returns the sum over all root-to-leaf
+    paths of |contribution| (>= |dleaf|): the scale of the cancellation in the gradient."""
     lib = _load()
     node_type, node_lit, child_ptr, child_idx, roots = _circuit_arrays(
         num_vars, node_type, node_lit, child_ptr, child_idx, roots)
@@ -129,7 +132,7 @@ def backward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights
     dleaf = np.empty((B, num_vars), dtype=np.float64)
     rc = lib.klay_oracle_backward(num_vars, n, _ptr(node_type), _ptr(node_lit), _ptr(child_ptr),
                                   _ptr(child_idx), R, _ptr(roots), B, _ptr(w), int(semiring),
-                                  _ptr(g), _ptr(dleaf), int(nthreads))
+                                  _ptr(g), _ptr(dleaf), int(nthreads), int(bool(path_mass)))
     if rc == -1:
         raise ValueError("circuit has a cycle")
     if rc != 0:

@@ -34,7 +34,8 @@ klay_status fail(klay_status s, const std::string& msg) {
 constexpr size_t kAlignInts = 64;   // 256-byte alignment of every uploaded array
 
 struct DevPass {
-    const int32_t *ptr = nullptr, *idx = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_row = nullptr;
+    const int32_t *ptr = nullptr, *idx = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_idx = nullptr,
+                  *comb_row = nullptr;
     int32_t n_main = 0, n_seg = 0, n_heavy = 0;
     int64_t edges = 0;
 };
@@ -86,7 +87,7 @@ struct klay_circuit {
     int32_t* d_index = nullptr;          // one allocation holding every index array
     size_t index_bytes = 0;
     const int32_t *d_pos_row = nullptr, *d_neg_row = nullptr, *d_root_pos = nullptr, *d_top_ptr = nullptr,
-                  *d_top_root = nullptr, *d_iota = nullptr;
+                  *d_top_root = nullptr;
     int32_t true_row = -1, false_row = -1;
     void* ws_own = nullptr;
     size_t ws_own_bytes = 0;
@@ -232,7 +233,7 @@ struct Packer {
     }
 };
 
-struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_row; };
+struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_idx, comb_row; };
 
 PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
     PassOffsets o;
@@ -240,6 +241,7 @@ PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
     o.idx = pk.add(p.idx);
     o.seg_owner = pk.add(p.seg_owner);
     o.comb_ptr = pk.add(p.comb_ptr);
+    o.comb_idx = pk.add(p.comb_idx);
     o.comb_row = pk.add(p.comb_row);
     return o;
 }
@@ -249,6 +251,7 @@ void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const 
     d.idx = base + o.idx;
     d.seg_owner = base + o.seg_owner;
     d.comb_ptr = base + o.comb_ptr;
+    d.comb_idx = base + o.comb_idx;
     d.comb_row = base + o.comb_row;
     d.n_main = p.n_main;
     d.n_seg = p.n_seg;
@@ -267,9 +270,6 @@ klay_status upload(klay_circuit* c) {
     }
     const size_t o_pos = pk.add(p.pos_row), o_neg = pk.add(p.neg_row), o_root = pk.add(p.root_pos);
     const size_t o_tptr = pk.add(p.top_ptr), o_troot = pk.add(p.top_root);
-    std::vector<int32_t> iota((size_t)std::max(p.max_fwd_seg, p.max_bwd_seg) + 8);
-    for (size_t i = 0; i < iota.size(); ++i) iota[i] = (int32_t)i;
-    const size_t o_iota = pk.add(iota);
 
     KLAY_HIP(hipSetDevice(c->device));
     c->index_bytes = pk.buf.size() * sizeof(int32_t);
@@ -297,12 +297,11 @@ klay_status upload(klay_circuit* c) {
     c->d_root_pos = base + o_root;
     c->d_top_ptr = base + o_tptr;
     c->d_top_root = base + o_troot;
-    c->d_iota = base + o_iota;
     return KLAY_OK;
 }
 
 // One layer-level gather-reduce: main rows + segments of split rows, then the combine pass.
-void run_pass_set(int op, int combine_op, const DevPass& dp, const klay_circuit* c, const float* src,
+void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
                   const float* src2, const float* own, float* dst, float* scratch, const Geometry& g,
                   int B, hipStream_t s) {
     klay::PassArgs a{};
@@ -324,7 +323,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const klay_circuit*
     if (dp.n_heavy > 0) {
         klay::PassArgs cmb{};
         cmb.ptr = dp.comb_ptr;
-        cmb.idx = c->d_iota;
+        cmb.idx = dp.comb_idx;
         cmb.src = scratch;
         cmb.out_row = dp.comb_row;
         cmb.dst = dst;
@@ -549,7 +548,7 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
         const int op = log_domain ? (is_and ? klay::OP_SUM : klay::OP_LSE) : (is_and ? klay::OP_PROD : klay::OP_SUM);
         const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM : (op == klay::OP_PROD ? KLAY_K_FWD_PROD : KLAY_K_FWD_LSE);
         prof.begin(cls, 4.0 * B * ((double)d.e + (double)d.n) + 4.0 * ((double)d.e + (double)d.n));
-        run_pass_set(op, op, d.fwd, c, act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld, nullptr, nullptr,
+        run_pass_set(op, op, d.fwd, act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld, nullptr, nullptr,
                      act + (size_t)d.row0 * g.ld, scratch, g, B, s);
         prof.end();
     }
@@ -608,11 +607,11 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
         const bool is_and = (l & 1) != 0;
         if (is_and) {
             prof.begin(KLAY_K_BWD_SUM, 4.0 * B * ((double)d.e + (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
-            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, c, gcur, nullptr, nullptr, gnext, scratch, g, B, s);
+            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s);
         } else {
             prof.begin(KLAY_K_BWD_SOFTMAX,
                        4.0 * B * (2.0 * (double)d.e + 2.0 * (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
-            run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, c, gcur, act + (size_t)d.row0 * g.ld,
+            run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld,
                          act + (size_t)below.row0 * g.ld, gnext, scratch, g, B, s);
         }
         prof.end();

@@ -54,22 +54,43 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
         }
     }
     out.ptr[(size_t)n] = w;
-    int64_t seg = 0, h = 0;
-    out.comb_ptr[0] = 0;
-    for (int64_t r = 0; r < n && n_heavy; ++r) {
+    if (n_heavy == 0) return;
+    // Segments of all split rows, ordered by the first source they read: segments that read the
+    // same stretch of source rows then run next to each other (and on the same XCD), so the
+    // stretch is fetched once and served from L2 to the rest.
+    struct Seg { int32_t owner, first_src; int64_t begin; int32_t len; };
+    std::vector<Seg> segs;
+    segs.reserve((size_t)n_seg);
+    for (int64_t r = 0; r < n; ++r) {
         int64_t k = ptr[r + 1] - ptr[r];
         if (k <= heavy) continue;
         int32_t s = segment_len(k, opt);
-        for (int64_t a = 0; a < k; a += s) {
-            int64_t len = std::min<int64_t>(s, k - a);
-            std::copy(idx + ptr[r] + a, idx + ptr[r] + a + len, out.idx.begin() + w);
-            w += (int32_t)len;
-            out.seg_owner[(size_t)seg] = (int32_t)r;
-            ++seg;
-            out.ptr[(size_t)(n + seg)] = w;
+        for (int64_t a = 0; a < k; a += s)
+            segs.push_back(Seg{(int32_t)r, idx[ptr[r] + a], ptr[r] + a, (int32_t)std::min<int64_t>(s, k - a)});
+    }
+    std::stable_sort(segs.begin(), segs.end(), [](const Seg& a, const Seg& b) { return a.first_src < b.first_src; });
+    // combine lists: scratch rows of each split row, in segment order
+    std::vector<int32_t> per_owner_count((size_t)n, 0);
+    for (const Seg& sg : segs) ++per_owner_count[(size_t)sg.owner];
+    int64_t h = 0;
+    std::vector<int32_t> owner_slot((size_t)n, -1);
+    out.comb_ptr[0] = 0;
+    for (int64_t r = 0; r < n; ++r)
+        if (per_owner_count[(size_t)r] > 0) {
+            owner_slot[(size_t)r] = (int32_t)h;
+            out.comb_row[(size_t)h] = (int32_t)r;
+            out.comb_ptr[(size_t)h + 1] = out.comb_ptr[(size_t)h] + per_owner_count[(size_t)r];
+            ++h;
         }
-        out.comb_row[(size_t)h] = (int32_t)r;
-        out.comb_ptr[(size_t)(++h)] = (int32_t)seg;
+    out.comb_idx.assign((size_t)n_seg + 8, 0);
+    std::vector<int32_t> fill(out.comb_ptr.begin(), out.comb_ptr.end() - 1);
+    for (size_t sidx = 0; sidx < segs.size(); ++sidx) {
+        const Seg& sg = segs[sidx];
+        std::copy(idx + sg.begin, idx + sg.begin + sg.len, out.idx.begin() + w);
+        w += sg.len;
+        out.seg_owner[sidx] = sg.owner;
+        out.ptr[(size_t)n + sidx + 1] = w;
+        out.comb_idx[(size_t)fill[(size_t)owner_slot[(size_t)sg.owner]]++] = (int32_t)sidx;
     }
     (void)heavy_edges;
 }

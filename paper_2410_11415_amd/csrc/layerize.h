@@ -18,7 +18,7 @@ struct Options {
 // One gather-reduce pass set over a CSR whose rows are the outputs.
 //   rows [0, n_main)                 write output row i; an empty range marks a split row
 //   rows [n_main, n_main + n_seg)    are segments of split rows, writing scratch row (i - n_main)
-//   combine: output row comb_row[h] reduces scratch rows [comb_ptr[h], comb_ptr[h+1])
+//   combine: output row comb_row[h] reduces scratch rows comb_idx[comb_ptr[h] .. comb_ptr[h+1])
 struct PassPlan {
     int32_t n_main = 0;
     int32_t n_seg = 0;
@@ -28,6 +28,7 @@ struct PassPlan {
     std::vector<int32_t> idx;        // [edges + 8], zero padded so 8-wide index reads stay in bounds
     std::vector<int32_t> seg_owner;  // [n_seg] output row each segment belongs to
     std::vector<int32_t> comb_ptr;   // [n_heavy + 1]
+    std::vector<int32_t> comb_idx;   // [n_seg + 8] scratch rows per split row, zero padded
     std::vector<int32_t> comb_row;   // [n_heavy]
 };
 

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Tolerances: |delta log| <= 1e-4 (fp32 log semiring), relative 1e-5
+(fp32 real semiring), gradients |delta| <= 1e-4 max(1, |ref|)."""
+import numpy as np
+import pytest
+
+from klay_synth import (CircuitBuilder, as_inputs, layered_random, leaf_probs, make_config,
+                        parse_text_circuit, tautology)
+from tests.gpu_util import (assert_grad_close, assert_log_close, assert_real_close, gpu_eval, oracle_eval)
+
+pytestmark = pytest.mark.gpu
+
+REAL, LOG = 0, 1
+
+
+@pytest.fixture(scope="module")
+def klay():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2410_11415_amd as pkg
+    pkg.load()                         # fails loudly if the HIP library is missing
+    return pkg
+
+
+def build(klay, c, **kw):
+    return klay.Circuit(*c.arrays(), device=0, **kw)
+
+
+def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", **kw):
+    k = build(klay, c, **kw)
+    rng = np.random.default_rng(123)
+    stats = {}
+    levels = k.num_layers // 2
+    for s in semirings:
+        w32 = as_inputs(p, s == LOG)
+        dout = rng.normal(size=(p.shape[0], c.roots.shape[0])).astype(np.float32) if (backward and s == LOG) else None
+        got, gd = gpu_eval(k, w32, s, dout)
+        ref, rd = oracle_eval(c, w32, s, dout, or_levels=levels)
+        if s == LOG:
+            stats["log"] = assert_log_close(got, ref, what + " log")
+            if dout is not None:
+                stats["grad"] = assert_grad_close(gd, rd, what + " grad")
+        else:
+            stats["real"] = assert_real_close(got, ref, what + " real")
+    k.close()
+    return stats
+
+
+# ------------------------------------------------------------------ the paper's worked circuits
+@pytest.mark.parametrize("name,nv", [("fig1b_ddnnf.txt", 4), ("fig3_multiroot.txt", 5), ("fig3a_single.txt", 4),
+                                      ("appD_mnist_add.txt", 2)])
+def test_worked_examples(klay, golden, name, nv):
+    c = golden(name)
+    for B in (1, 3, 70):
+        check_both(klay, c, leaf_probs(B, B, nv, ("uniform", 0.01, 0.99)), what=name)
+
+
+# ------------------------------------------------------------------ config 1
+@pytest.mark.parametrize("seed", [0, 1])
+def test_tiny_ddnnf_batch4(klay, seed):
+    c, p, spec = make_config("tiny_ddnnf", seed=seed)
+    assert p.shape[0] == 4
+    check_both(klay, c, p, what="tiny_ddnnf")
+    # and against brute-force model counting over the CNF (4096 assignments)
+    cv, cp = spec["cnf"]
+    bits = ((np.arange(4096)[:, None] >> np.arange(12)[None, :]) & 1).astype(bool)
+    sat = np.ones(4096, dtype=bool)
+    for vs, pos in zip(cv, cp):
+        sat &= (bits[:, vs] == pos[None, :]).any(axis=1)
+    w32 = as_inputs(p, True)
+    p32 = np.exp(w32.astype(np.float64))
+    q32 = -np.expm1(w32.astype(np.float64))
+    ref = np.log(np.prod(np.where(bits[None, sat, :], p32[:, None, :], q32[:, None, :]), axis=2).sum(1))
+    k = build(klay, c)
+    got, _ = gpu_eval(k, w32, LOG)
+    assert_log_close(got[:, 0], ref, "tiny_ddnnf vs brute force")
+
+
+# ------------------------------------------------------------------ config 2 (full size, element by element)
+def test_layered_100k_full_size_log_forward(klay):
+    c, p, spec = make_config("layered_100k", seed=0)
+    assert p.shape[0] == 128
+    stats = check_both(klay, c, p, backward=False, semirings=(LOG,), what="layered_100k")
+    print("layered_100k max|dlog| %.2e" % stats["log"])
+
+
+# ------------------------------------------------------------------ configs 3-5 at reduced size, element by element
+@pytest.mark.parametrize("name,scale,batches", [
+    ("layered_1m", 0.05, (1, 256)),
+    ("powerlaw_10m", 0.08, (64,)),
+    ("layered_3m_fwd_bwd", 0.02, (256,)),
+])
+def test_configs_reduced_size(klay, name, scale, batches):
+    for B in batches:
+        c, p, spec = make_config(name, seed=1, scale=scale, batch=B)
+        sem = tuple(REAL if s == "real" else LOG for s in spec["semirings"])
+        stats = check_both(klay, c, p, backward=True, semirings=sem, what="%s B=%d" % (name, B))
+        print(name, B, stats)
+
+
+# ------------------------------------------------------------------ full sizes, sampled batch columns
+@pytest.mark.parametrize("name,semiring,backward", [
+    ("layered_1m", REAL, False), ("layered_1m", LOG, False), ("powerlaw_10m", LOG, False),
+    ("layered_3m_fwd_bwd", LOG, True),
+])
+def test_configs_full_size_sampled_columns(klay, name, semiring, backward):
+    """The launch configuration the benchmark times; the oracle evaluates 4 of the B columns."""
+    c, p, spec = make_config(name, seed=0)
+    B = p.shape[0]
+    w32 = as_inputs(p, semiring == LOG)
+    dout = np.ones((B, c.roots.shape[0]), dtype=np.float32) if backward else None
+    k = build(klay, c)
+    got, gd = gpu_eval(k, w32, semiring, dout)
+    cols = np.array([0, B // 3, B // 2 + 1, B - 1])
+    ref, rd = oracle_eval(c, w32[cols], semiring, None if dout is None else dout[cols], nthreads=4,
+                          or_levels=k.num_layers // 2)
+    if semiring == LOG:
+        e = assert_log_close(got[cols], ref, name)
+        print("%s: max|dlog| %.2e, max|log ref| %.1f" % (name, e, np.abs(ref[np.isfinite(ref)]).max()))
+    else:
+        print("%s: max rel %.2e" % (name, assert_real_close(got[cols], ref, name)))
+    if backward:
+        print("%s: grad err %.2e, max|grad ref| %.2e" % (name, assert_grad_close(gd[cols], rd, name), np.abs(rd).max()))
+    if name == "layered_1m" and semiring == LOG:      # B = 1 latency case on the same circuit
+        got1, _ = gpu_eval(k, w32[:1], LOG)
+        assert_log_close(got1, ref[:1], name + " B=1")
+    k.close()
+
+
+# ------------------------------------------------------------------ batch shapes (lane mappings, ragged tails)
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 9, 17, 31, 32, 33, 63, 64, 65, 100, 101, 128, 129, 255, 257, 300, 513])
+def test_batch_sizes(klay, B):
+    c = layered_random(4, num_vars=48, depth=8, num_gates=1500, fanin=("geom", 2.0), groups=2, num_roots=7)
+    check_both(klay, c, leaf_probs(B, B, 48), what="B=%d" % B)
+
+
+# ------------------------------------------------------------------ split rows (high fan-in / fan-out)
+@pytest.mark.parametrize("heavy,seg", [(2, 1), (3, 2), (8, 4), (64, 16)])
+@pytest.mark.parametrize("B", [3, 64, 256])
+def test_split_rows(klay, heavy, seg, B):
+    c = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
+    k = build(klay, c, heavy_fan=heavy, min_segment=seg)
+    assert k.info()["num_split_rows"] > 0
+    k.close()
+    check_both(klay, c, leaf_probs(5, B, 64, ("beta", 0.5, 0.5)), what="split", heavy_fan=heavy, min_segment=seg)
+
+
+def test_very_high_fan_in_and_gate_with_magnitude_aware_bound(klay):
+    """one AND and one OR over 10^4 literals: exercises the split path at the fan-in cap; |log| of the
+    AND reaches ~10^4, where fp32 cannot hold 1e-4 absolute, so the bound scales with sum |x_j| / 64"""
+    V = 10_000
+    b = CircuitBuilder(V)
+    leaves = [b.lit(v, v % 3 != 0) for v in range(V)]
+    c = b.finish([b.and_(*leaves), b.or_(*leaves)])
+    p = leaf_probs(0, 64, V, ("uniform", 0.2, 1.0))
+    w32 = as_inputs(p, True)
+    k = build(klay, c)
+    assert k.info()["max_fan_in"] == V and k.info()["num_split_rows"] >= 2
+    got, _ = gpu_eval(k, w32, LOG)
+    ref, _ = oracle_eval(c, w32, LOG)
+    assert_log_close(got[:, 1], ref[:, 1], "OR over 1e4")
+    bound = 1e-4 * np.maximum(1.0, np.abs(ref[:, 0]) / 64)
+    assert np.all(np.abs(got[:, 0] - ref[:, 0]) <= bound)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_zero_one_probabilities_and_constants(klay):
+    b = CircuitBuilder(3)
+    x, nx, y, ny, z = b.lit(0), b.lit(0, False), b.lit(1), b.lit(1, False), b.lit(2)
+    root = b.or_(b.and_(x, y), b.and_(nx, ny, z))
+    dead = b.or_(b.and_(x, ny), b.and_(nx, y))
+    t, f = b.true(), b.false()
+    c = b.finish([root, dead, t, f, b.and_(t, z), b.or_(f, b.and_(z, x)), z, nx])
+    p = np.array([[1.0, 1.0, 0.3], [0.0, 0.0, 0.0], [0.0, 1.0, 0.5], [0.4, 0.6, 0.2]])
+    k = build(klay, c)
+    with np.errstate(divide="ignore"):
+        w32 = as_inputs(p, True)
+    got, _ = gpu_eval(k, w32, LOG)
+    ref, _ = oracle_eval(c, w32, LOG)
+    assert_log_close(got, ref, "zero/one log")
+    gotr, _ = gpu_eval(k, as_inputs(p, False), REAL)
+    refr, _ = oracle_eval(c, as_inputs(p, False), REAL)
+    assert_real_close(gotr, refr, "zero/one real")
+    # gradients on the rows without infinite derivatives
+    dout = np.zeros((4, 8), dtype=np.float32); dout[:, 0] = 1.0; dout[:, 4] = -2.0
+    _, gd = gpu_eval(k, w32, LOG, dout)
+    _, rd = oracle_eval(c, w32, LOG, dout)
+    assert_grad_close(gd[3:], rd[3:], "grad")
+    assert not np.isnan(gd).any()
+    k.close()
+
+
+def test_leaf_roots_and_repeated_roots(klay):
+    b = CircuitBuilder(2)
+    x, ny = b.lit(0), b.lit(1, False)
+    c = b.finish([ny, x, ny])
+    check_both(klay, c, leaf_probs(0, 5, 2, ("uniform", 0.1, 0.9)), what="leaf roots")
+    b = CircuitBuilder(3)
+    a = b.and_(b.lit(0), b.lit(1))
+    o = b.or_(a, b.and_(b.lit(0, False), b.lit(2)))
+    c = b.finish([o, a, b.lit(2), o, a])
+    check_both(klay, c, leaf_probs(1, 6, 3, ("uniform", 0.1, 0.9)), what="mixed-height roots")
+
+
+def test_tautology_is_one(klay):
+    c = tautology(0, 40, width=5)
+    p = leaf_probs(0, 16, 40, ("beta", 0.5, 0.5))
+    k = build(klay, c)
+    got, _ = gpu_eval(k, as_inputs(p, True), LOG)
+    assert np.abs(got).max() <= 1e-4
+    k.close()
+
+
+def test_node_order_does_not_change_results(klay):
+    c = layered_random(9, num_vars=32, depth=10, num_gates=3000, fanin=("geom", 2.0), groups=2, num_roots=9)
+    p = leaf_probs(9, 40, 32)
+    w32 = as_inputs(p, True)
+    outs = []
+    for kw in ({}, {"no_reorder": True}):
+        k = build(klay, c, **kw)
+        outs.append(gpu_eval(k, w32, LOG, np.ones((40, 9), np.float32)))
+        k.close()
+    ref, rd = oracle_eval(c, w32, LOG, np.ones((40, 9), np.float32))
+    for got, gd in outs:
+        assert_log_close(got, ref)
+        assert_grad_close(gd, rd)
+
+
+def test_runs_are_bitwise_reproducible_and_workspace_can_be_callers(klay):
+    import torch
+    c, p, _ = make_config("layered_100k", seed=3, scale=0.2, batch=96)
+    w32 = as_inputs(p, True)
+    d = np.ones((96, c.roots.shape[0]), np.float32)
+    k = build(klay, c)
+    a = gpu_eval(k, w32, LOG, d)
+    b = gpu_eval(k, w32, LOG, d)
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[1], b[1])
+    ws = torch.empty(k.workspace_bytes(96, True) // 4, dtype=torch.float32, device="cuda")
+    k.set_workspace(ws)
+    e = gpu_eval(k, w32, LOG, d)
+    np.testing.assert_array_equal(a[0], e[0])
+    np.testing.assert_array_equal(a[1], e[1])
+    small = torch.empty(1024, dtype=torch.float32, device="cuda")
+    k.set_workspace(small)
+    with pytest.raises(klay.KlayError) as err:
+        gpu_eval(k, w32, LOG)
+    assert err.value.status == 3
+    k.set_workspace(None)
+    k.close()
+
+
+def test_call_order_errors(klay):
+    import torch
+    c, p, _ = make_config("tiny_ddnnf", seed=0)
+    k = build(klay, c)
+    d = torch.ones((4, 1), device="cuda")
+    g = torch.empty((4, 12), device="cuda")
+    with pytest.raises(klay.KlayError) as e:
+        klay.klay_backward(k._h, d.data_ptr(), g.data_ptr(), 0)
+    assert e.value.status == 5
+    k.forward(torch.from_numpy(as_inputs(p, False)).cuda(), REAL)
+    with pytest.raises(klay.KlayError) as e:
+        klay.klay_backward(k._h, d.data_ptr(), g.data_ptr(), 0)
+    assert e.value.status == 1                       # real-semiring backward is not built yet
+    k.close()
+
+
+def test_profile_reports_kernel_classes(klay):
+    c, p, _ = make_config("layered_100k", seed=0, scale=0.2, batch=64)
+    k = build(klay, c)
+    k.set_profiling(True)
+    gpu_eval(k, as_inputs(p, True), LOG, np.ones((64, c.roots.shape[0]), np.float32))
+    prof = k.get_profile()
+    assert prof["fwd_lse"]["launches"] >= 10 and prof["fwd_lse"]["ms"] > 0
+    assert prof["bwd_softmax"]["launches"] >= 10 and prof["bwd_softmax"]["alg_bytes"] > 0
+    k.set_profiling(False)
+    k.close()

@@ -290,3 +290,27 @@ def test_threads_do_not_change_results():
     np.testing.assert_array_equal(fwd(c, w, LOG, nthreads=1), fwd(c, w, LOG, nthreads=4))
     d = np.ones((9, c.roots.shape[0]))
     np.testing.assert_array_equal(bwd(c, w, LOG, d, nthreads=1), bwd(c, w, LOG, d, nthreads=4))
+
+
+def test_path_mass_bounds_the_gradient_and_equals_it_without_cancellation():
+    c, p, _ = make_config("layered_100k", seed=4, scale=0.03, batch=3)
+    R = c.roots.shape[0]
+    w = np.log(p)
+    dout = np.random.default_rng(4).normal(size=(3, R))
+    g = bwd(c, w, LOG, dout)
+    mass = oracle.backward(*c.arrays(), w, LOG, dout, path_mass=True)
+    assert np.all(mass >= np.abs(g) * (1 - 1e-12))
+    # a circuit without negated literals and a positive seed has no cancellation at all
+    b = CircuitBuilder(4)
+    x = [b.lit(v) for v in range(4)]
+    root = b.or_(b.and_(x[0], x[1]), b.and_(x[1], x[2], x[3]), b.and_(x[0], x[3]))
+    cc = b.finish([root])
+    w = np.log(leaf_probs(0, 5, 4, ("uniform", 0.1, 0.9)))
+    ones = np.ones((5, 1))
+    np.testing.assert_allclose(oracle.backward(*cc.arrays(), w, LOG, ones, path_mass=True), bwd(cc, w, LOG, ones), rtol=1e-14)
+    # and with a negated literal the mass is the sum of the two branches' magnitudes
+    b = CircuitBuilder(1)
+    cc = b.finish([b.or_(b.lit(0), b.lit(0, False))])      # p + (1-p) = 1: gradient 0, mass 2p
+    pp = np.array([[0.3]])
+    np.testing.assert_allclose(bwd(cc, pp, REAL, np.ones((1, 1))), 0.0, atol=1e-15)
+    np.testing.assert_allclose(oracle.backward(*cc.arrays(), pp, REAL, np.ones((1, 1)), path_mass=True), 2.0, rtol=1e-14)
