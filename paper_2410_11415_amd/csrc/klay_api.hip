@@ -34,9 +34,9 @@ klay_status fail(klay_status s, const std::string& msg) {
 constexpr size_t kAlignInts = 64;   // 256-byte alignment of every uploaded array
 
 struct DevPass {
-    const int32_t *ptr = nullptr, *idx = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_idx = nullptr,
-                  *comb_row = nullptr;
-    int32_t n_main = 0, n_seg = 0, n_heavy = 0;
+    const int32_t *ptr = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_row = nullptr, *tasks = nullptr;
+    const uint32_t *idx = nullptr, *comb_idx = nullptr;
+    int32_t n_main = 0, n_seg = 0, n_heavy = 0, n_tasks = 0;
     int64_t edges = 0;
 };
 
@@ -148,9 +148,10 @@ void launch_op(const klay::PassArgs& a, const Geometry& g, dim3 grid, hipStream_
 
 // Launch one gather-reduce pass over `n_total` rows.
 void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
-    if (a.n_total <= 0) return;
+    const int64_t rows = (int64_t)a.n_total - a.row_begin;
+    if (rows <= 0) return;
     const int rpw = 64 / g.w;
-    const int64_t groups = ((int64_t)a.n_total + rpw - 1) / rpw;     // row groups = wave work items
+    const int64_t groups = (rows + rpw - 1) / rpw;                    // row groups = wave work items
     // enough waves to fill 256 CUs several times over before a wave takes more than one group
     int iters = (int)std::min<int64_t>(8, std::max<int64_t>(1, groups / 32768));
     a.iters = iters;
@@ -162,6 +163,33 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
     case klay::OP_PROD: launch_op<klay::OP_PROD>(a, g, grid, s); break;
     case klay::OP_LSE: launch_op<klay::OP_LSE>(a, g, grid, s); break;
     default: launch_op<klay::OP_SOFTMAX_BWD>(a, g, grid, s); break;
+    }
+}
+
+template <int OP>
+void launch_stream_op(const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
+                      float* dst, int B, hipStream_t s) {
+    int64_t blocks = ((int64_t)dp.n_tasks + 3) / 4;
+    blocks = (blocks + 7) / 8 * 8;
+    dim3 grid((unsigned)blocks, (unsigned)g.tiles);
+    const int2* tasks = reinterpret_cast<const int2*>(dp.tasks);
+    if (g.vec == 4)
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld);
+    else if (g.vec == 2)
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld);
+    else
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld);
+}
+
+// Streaming kernel over the main rows of a pass (batch tiles of one wave: B > 32).
+void launch_stream(int op, const DevPass& dp, const Geometry& g, const float* src, const float* src2,
+                   const float* own, float* dst, int B, hipStream_t s) {
+    if (dp.n_tasks <= 0) return;
+    switch (op) {
+    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, g, src, src2, own, dst, B, s); break;
+    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, g, src, src2, own, dst, B, s); break;
+    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, g, src, src2, own, dst, B, s); break;
+    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, B, s); break;
     }
 }
 
@@ -225,6 +253,7 @@ klay_status get_workspace(klay_circuit* c, int B, bool need_bwd, float** base, W
 struct Packer {
     std::vector<int32_t> buf;
     size_t add(const std::vector<int32_t>& v) { return add(v.data(), v.size()); }
+    size_t add(const std::vector<uint32_t>& v) { return add(reinterpret_cast<const int32_t*>(v.data()), v.size()); }
     size_t add(const int32_t* p, size_t n) {
         size_t off = (buf.size() + kAlignInts - 1) / kAlignInts * kAlignInts;
         buf.resize(off + std::max<size_t>(n, 1), 0);
@@ -233,7 +262,7 @@ struct Packer {
     }
 };
 
-struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_idx, comb_row; };
+struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_idx, comb_row, tasks; };
 
 PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
     PassOffsets o;
@@ -243,16 +272,19 @@ PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
     o.comb_ptr = pk.add(p.comb_ptr);
     o.comb_idx = pk.add(p.comb_idx);
     o.comb_row = pk.add(p.comb_row);
+    o.tasks = pk.add(p.tasks);
     return o;
 }
 
 void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const int32_t* base) {
     d.ptr = base + o.ptr;
-    d.idx = base + o.idx;
+    d.idx = reinterpret_cast<const uint32_t*>(base + o.idx);
     d.seg_owner = base + o.seg_owner;
     d.comb_ptr = base + o.comb_ptr;
-    d.comb_idx = base + o.comb_idx;
+    d.comb_idx = reinterpret_cast<const uint32_t*>(base + o.comb_idx);
     d.comb_row = base + o.comb_row;
+    d.tasks = base + o.tasks;
+    d.n_tasks = p.n_tasks;
     d.n_main = p.n_main;
     d.n_seg = p.n_seg;
     d.n_heavy = p.n_heavy;
@@ -300,7 +332,7 @@ klay_status upload(klay_circuit* c) {
     return KLAY_OK;
 }
 
-// One layer-level gather-reduce: main rows + segments of split rows, then the combine pass.
+// One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
                   const float* src2, const float* own, float* dst, float* scratch, const Geometry& g,
                   int B, hipStream_t s) {
@@ -318,7 +350,12 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
     a.n_total = dp.n_main + dp.n_seg;
     a.B = B;
     a.ld = g.ld;
-    a.skip_empty = 1;
+    if (g.w == 64) {
+        launch_stream(op, dp, g, src, src2, own, dst, B, s);
+        a.row_begin = dp.n_main;                 // segments only
+    } else {
+        a.row_begin = 0;
+    }
     launch_pass(op, a, g, s);
     if (dp.n_heavy > 0) {
         klay::PassArgs cmb{};
@@ -328,11 +365,11 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
         cmb.out_row = dp.comb_row;
         cmb.dst = dst;
         cmb.dst_seg = nullptr;
+        cmb.row_begin = 0;
         cmb.n_main = dp.n_heavy;
         cmb.n_total = dp.n_heavy;
         cmb.B = B;
         cmb.ld = g.ld;
-        cmb.skip_empty = 0;
         launch_pass(combine_op, cmb, g, s);
     }
 }

@@ -15,9 +15,13 @@ namespace klay {
 
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3 };
 
+// Index entries: bits 0..30 = source row, bit 31 = last edge of its output row.  kSkip (all ones)
+// stands for a whole output row that this pass leaves untouched (a split row).
+constexpr uint32_t kLast = 0x80000000u, kSkip = 0xFFFFFFFFu, kIdMask = 0x7FFFFFFFu;
+
 struct PassArgs {
     const int32_t* ptr;        // [n_total + 1] CSR offsets into idx
-    const int32_t* idx;        // source row per edge (readable up to 8 entries past the end)
+    const uint32_t* idx;       // index entries (readable up to 16 entries past the end)
     const float* src;          // [*, ld] source rows (values of the layer below, adjoints, or partials)
     const float* src2;         // OP_SOFTMAX_BWD: values N_l of the parents, same row index as src
     const float* own;          // OP_SOFTMAX_BWD: values N_{l-1} of the output rows
@@ -25,12 +29,12 @@ struct PassArgs {
     const int32_t* out_row;    // optional output row map for rows < n_main (combine pass)
     float* dst;                // output rows for rows < n_main
     float* dst_seg;            // scratch rows for rows >= n_main
+    int32_t row_begin;         // first row this launch evaluates
     int32_t n_main;
     int32_t n_total;
     int32_t B;
     int32_t ld;
     int32_t iters;             // row groups per wave
-    int32_t skip_empty;        // 1: a row < n_main with an empty range is left untouched
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -70,6 +74,146 @@ __device__ __forceinline__ void store_vec(float* p, const float (&x)[VEC]) {
 // x extent is a multiple of 8.
 __device__ __forceinline__ int xcd_block(int bid, int nblocks) { return (bid & 7) * (nblocks >> 3) + (bid >> 3); }
 
+// One step of the streaming reductions.  acc/mx carry the state of the current output row:
+//   OP_SUM / OP_PROD  acc = running sum / product
+//   OP_LSE            (mx, acc) = (running max, sum of exp(x - mx)); one exp per element:
+//                     a new maximum rescales the sum by exp(mx - x), otherwise exp(x - mx) is added
+//   OP_SOFTMAX_BWD    acc += g * exp(own - parent value); a parent at -inf passes nothing down
+template <int OP>
+__device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc) {
+    if (OP == OP_SUM) acc += x;
+    else if (OP == OP_PROD) acc *= x;
+    else if (OP == OP_LSE) {
+        const float d = x - mx;                                   // +inf on the first finite element
+        const float e = (x == -INFINITY) ? 0.0f : fexp(-fabsf(d));
+        acc = (d > 0.0f) ? fmaf(acc, e, 1.0f) : acc + e;          // d is NaN only for -inf - -inf: e = 0
+        mx = fmaxf(mx, x);
+    } else {
+        const float wgt = (y == -INFINITY) ? 0.0f : fexp(nc - y);
+        acc = fmaf(x, wgt, acc);
+    }
+}
+
+template <int OP>
+__device__ __forceinline__ float finish(float acc, float mx) {
+    if (OP == OP_LSE) return (mx == -INFINITY) ? -INFINITY : mx + flog(acc);
+    return acc;
+}
+
+template <int OP>
+__device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : 0.0f; }
+
+// ---------------------------------------------------------------------------------------------
+// Streaming segmented gather-reduce for B > 32 (one wave spans the batch tile, VEC columns per
+// lane).  A task is a run of consecutive output rows with a bounded number of edges, fixed at
+// build time; the wave walks the task's edges in chunks of CH, keeps CH row gathers in flight,
+// prefetches the next chunk's index entries while they fly, and closes an output row whenever
+// an entry carries the end-of-row bit.  Everything that steers control flow is wave-uniform.
+// Index entries past a task's end are valid entries of later rows (or zero padding).
+// ---------------------------------------------------------------------------------------------
+template <int OP, int VEC>
+__global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ tasks, int n_tasks,
+                                                     const uint32_t* __restrict__ idx,
+                                                     const float* __restrict__ src,
+                                                     const float* __restrict__ src2,
+                                                     const float* __restrict__ own, float* __restrict__ dst,
+                                                     int B, int ld) {
+    constexpr int CH = (OP == OP_SOFTMAX_BWD) ? 4 : 8;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = ((int)blockIdx.y * 64 + lane) * VEC;
+    if (col >= B) return;
+    const int t = xcd_block((int)blockIdx.x, (int)gridDim.x) * 4 + wave;
+    if (t >= n_tasks) return;
+    const int2 t0 = tasks[t], t1 = tasks[t + 1];
+    int row = t0.x;
+    int j = t0.y;
+    const int e1 = t1.y;
+    const int last_row = t1.x - 1;
+    const float* srcc = src + col;
+    const float* src2c = src2 + col;
+    const float* ownc = own + col;
+    float* dstc = dst + col;
+
+    float acc[VEC], mx[VEC], nc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { acc[v] = identity<OP>(); mx[v] = -INFINITY; nc[v] = 0.0f; }
+    bool fresh = true;                       // the next edge opens a new output row
+    uint32_t ids[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) ids[i] = idx[j + i];
+
+    while (j < e1) {
+        const int n = e1 - j;
+        int rws[CH];
+        bool first[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            rws[i] = row;
+            first[i] = fresh;
+            if (i < n) {
+                fresh = (ids[i] & kLast) != 0;
+                row += fresh ? 1 : 0;
+            }
+        }
+        // All CH gathers are issued unconditionally (entries past the task's end or kSkip are
+        // redirected to valid rows and their data ignored): loads under wave-uniform branches
+        // would make the compiler drain the memory pipeline before each of them.
+        float x[CH][VEC], y[CH][VEC], z[CH][VEC];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const uint32_t srow = (ids[i] == kSkip) ? 0u : (ids[i] & kIdMask);
+            const size_t off = (size_t)srow * (size_t)ld;
+            load_vec<VEC>(x[i], srcc + off);
+            if (OP == OP_SOFTMAX_BWD) {
+                load_vec<VEC>(y[i], src2c + off);
+                const int orow = rws[i] < last_row ? rws[i] : last_row;
+                load_vec<VEC>(z[i], ownc + (size_t)orow * (size_t)ld);
+            }
+        }
+        uint32_t nxt[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) nxt[i] = idx[j + CH + i];       // padded: always readable
+        // s_waitcnt vmcnt(0) (scalar prefetch left in flight): the gathers are complete on every
+        // path from here on, so no later register reuse has to wait on them again.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            // branch-free accumulation: a dead entry contributes the identity
+            const bool live = (i < n) && (ids[i] != kSkip);
+            if (OP == OP_SOFTMAX_BWD) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) nc[v] = (live && first[i]) ? z[i][v] : nc[v];
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const float dead = OP == OP_PROD ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
+                const float xv = live ? x[i][v] : dead;
+                const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
+                accumulate<OP>(acc[v], mx[v], xv, yv, nc[v]);
+            }
+            if (live && (ids[i] & kLast)) {
+                float o[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    o[v] = finish<OP>(acc[v], mx[v]);
+                    acc[v] = identity<OP>();
+                    mx[v] = -INFINITY;
+                }
+                store_vec<VEC>(dstc + (size_t)rws[i] * (size_t)ld, o);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) ids[i] = nxt[i];
+        j += CH;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic gather-reduce: a lane group of W lanes owns one output row (W < 64: several rows per
+// wave, for small batches).  Also evaluates the segments of split rows (rows >= n_main, written
+// to scratch rows) and the combine pass (out_row map).
+// ---------------------------------------------------------------------------------------------
 template <int OP, int VEC, int W>
 __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
     constexpr int RPW = 64 / W;                       // rows per wave
@@ -84,90 +228,50 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
     const int64_t first_group = ((int64_t)blk * 4 + wave) * a.iters;
 
     for (int it = 0; it < a.iters; ++it) {
-        const int64_t row64 = (first_group + it) * RPW + sub;
+        const int64_t row64 = (first_group + it) * RPW + sub + a.row_begin;
         if (row64 >= a.n_total) break;
         const int row = (int)row64;
         const int beg = a.ptr[row], end = a.ptr[row + 1];
-        if (a.skip_empty && beg == end && row < a.n_main) continue;
+        if (a.idx[beg] == kSkip) continue;            // split row: evaluated by segments + combine
 
         float nc[VEC];                                // OP_SOFTMAX_BWD: own value
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) nc[v] = 0.0f;
         if (OP == OP_SOFTMAX_BWD) {
             const int owner = row < a.n_main ? row : a.seg_owner[row - a.n_main];
             load_vec<VEC>(nc, a.own + (size_t)owner * a.ld + col);
         }
         float acc[VEC], mx[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            acc[v] = (OP == OP_PROD) ? 1.0f : 0.0f;
-            mx[v] = -INFINITY;
-        }
+        for (int v = 0; v < VEC; ++v) { acc[v] = identity<OP>(); mx[v] = -INFINITY; }
 
         for (int j = beg; j < end; j += CH) {
             const int n = end - j;
-            int id[CH];
+            uint32_t id[CH];
 #pragma unroll
-            for (int i = 0; i < CH; ++i) id[i] = a.idx[j + i];          // padded array: always in bounds
+            for (int i = 0; i < CH; ++i) id[i] = a.idx[j + i] & kIdMask;      // padded array: always in bounds
             float x[CH][VEC], y[CH][VEC];
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 if (i < n) {
                     load_vec<VEC>(x[i], a.src + (size_t)id[i] * a.ld + col);
                     if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], a.src2 + (size_t)id[i] * a.ld + col);
-                } else {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        x[i][v] = (OP == OP_PROD) ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
-                        y[i][v] = 0.0f;
-                    }
                 }
             }
-            if (OP == OP_SUM) {
 #pragma unroll
-                for (int i = 0; i < CH; ++i)
+            for (int i = 0; i < CH; ++i)
+                if (i < n) {
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[v] += x[i][v];
-            } else if (OP == OP_PROD) {
-#pragma unroll
-                for (int i = 0; i < CH; ++i)
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[v] *= x[i][v];
-            } else if (OP == OP_LSE) {
-                // running (max, sum of exp(x - max)); one rescale per chunk
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    float cm = x[0][v];
-#pragma unroll
-                    for (int i = 1; i < CH; ++i) cm = fmaxf(cm, x[i][v]);
-                    const float mn = fmaxf(mx[v], cm);
-                    const float sh = (mn == -INFINITY) ? 0.0f : mn;       // all -inf so far: avoid inf - inf
-                    float s = acc[v] * fexp(mx[v] - sh);
-#pragma unroll
-                    for (int i = 0; i < CH; ++i)
-                        if (i < n) s += fexp(x[i][v] - sh);
-                    acc[v] = s;
-                    mx[v] = mn;
+                    for (int v = 0; v < VEC; ++v) accumulate<OP>(acc[v], mx[v], x[i][v], OP == OP_SOFTMAX_BWD ? y[i][v] : 0.0f, nc[v]);
                 }
-            } else {
-                // adjoint of logsumexp: g_parent * exp(own - parent), nothing from a -inf parent
-#pragma unroll
-                for (int i = 0; i < CH; ++i)
-                    if (i < n) {
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) {
-                            const float wgt = (y[i][v] == -INFINITY) ? 0.0f : fexp(nc[v] - y[i][v]);
-                            acc[v] = fmaf(x[i][v], wgt, acc[v]);
-                        }
-                    }
-            }
         }
-        if (OP == OP_LSE) {
+        float o[VEC];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[v] = (mx[v] == -INFINITY) ? -INFINITY : mx[v] + flog(acc[v]);
-        }
+        for (int v = 0; v < VEC; ++v) o[v] = finish<OP>(acc[v], mx[v]);
         float* out;
         if (row < a.n_main) out = a.dst + (size_t)(a.out_row ? a.out_row[row] : row) * a.ld + col;
         else out = a.dst_seg + (size_t)(row - a.n_main) * a.ld + col;
-        store_vec<VEC>(out, acc);
+        store_vec<VEC>(out, o);
     }
 }
 

@@ -39,21 +39,40 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
     out.n_seg = (int32_t)n_seg;
     out.n_heavy = (int32_t)n_heavy;
     out.ptr.resize((size_t)(n + n_seg + 1));
-    out.idx.assign((size_t)(e + 8), 0);
+    out.idx.assign((size_t)(e - heavy_edges + n_heavy + heavy_edges + kIdxPad), 0u);
     out.seg_owner.resize((size_t)n_seg);
     out.comb_ptr.resize((size_t)(n_heavy + 1));
     out.comb_row.resize((size_t)n_heavy);
-    // light rows keep their order and their edges come first; split rows get an empty range
+    // main rows keep their order and their entries come first; a split row is one kSkipRow entry
     int32_t w = 0;
     for (int64_t r = 0; r < n; ++r) {
         out.ptr[(size_t)r] = w;
         int64_t k = ptr[r + 1] - ptr[r];
         if (k <= heavy) {
-            std::copy(idx + ptr[r], idx + ptr[r + 1], out.idx.begin() + w);
-            w += (int32_t)k;
+            for (int64_t j = ptr[r]; j < ptr[r + 1]; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j];
+            if (k > 0) out.idx[(size_t)w - 1] |= kLastEdge;
+        } else {
+            out.idx[(size_t)w++] = kSkipRow;
         }
     }
     out.ptr[(size_t)n] = w;
+    // tasks over the main rows: close a task once it holds `target` entries (or 64 rows)
+    {
+        const int64_t main_entries = w;
+        const int64_t target = std::min<int64_t>(64, std::max<int64_t>(16, main_entries / 16384));
+        out.tasks.clear();
+        int64_t r = 0;
+        while (r < n) {
+            out.tasks.push_back((int32_t)r);
+            out.tasks.push_back(out.ptr[(size_t)r]);
+            int64_t r1 = r;
+            while (r1 < n && r1 - r < 64 && out.ptr[(size_t)r1] - out.ptr[(size_t)r] < target) ++r1;
+            r = r1;
+        }
+        out.n_tasks = (int32_t)(out.tasks.size() / 2);
+        out.tasks.push_back((int32_t)n);
+        out.tasks.push_back(w);
+    }
     if (n_heavy == 0) return;
     // Segments of all split rows, ordered by the first source they read: segments that read the
     // same stretch of source rows then run next to each other (and on the same XCD), so the
@@ -82,17 +101,16 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
             out.comb_ptr[(size_t)h + 1] = out.comb_ptr[(size_t)h] + per_owner_count[(size_t)r];
             ++h;
         }
-    out.comb_idx.assign((size_t)n_seg + 8, 0);
+    out.comb_idx.assign((size_t)n_seg + kIdxPad, 0u);
     std::vector<int32_t> fill(out.comb_ptr.begin(), out.comb_ptr.end() - 1);
     for (size_t sidx = 0; sidx < segs.size(); ++sidx) {
         const Seg& sg = segs[sidx];
-        std::copy(idx + sg.begin, idx + sg.begin + sg.len, out.idx.begin() + w);
-        w += sg.len;
+        for (int64_t j = sg.begin; j < sg.begin + sg.len; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j];
+        out.idx[(size_t)w - 1] |= kLastEdge;
         out.seg_owner[sidx] = sg.owner;
         out.ptr[(size_t)n + sidx + 1] = w;
-        out.comb_idx[(size_t)fill[(size_t)owner_slot[(size_t)sg.owner]]++] = (int32_t)sidx;
+        out.comb_idx[(size_t)fill[(size_t)owner_slot[(size_t)sg.owner]]++] = (uint32_t)sidx;
     }
-    (void)heavy_edges;
 }
 
 int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node_lit,
@@ -350,7 +368,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         int64_t e = 0;
         for (int64_t p = 0; p < lay.n; ++p)
             e += lay.is_pad[(size_t)p] ? 1 : child_ptr[lay.origin[(size_t)p] + 1] - child_ptr[lay.origin[(size_t)p]];
-        if (e >= INT32_MAX - 16) { err = "klay_build: a layer has more than 2^31 edges"; return ST_INVAL; }
+        if (e + lay.n >= INT32_MAX - 64) { err = "klay_build: a layer has more than 2^31 edges"; return ST_INVAL; }
         lay.e = e;
         lay.row_ptr.resize((size_t)lay.n + 1);
         lay.child.resize((size_t)e);

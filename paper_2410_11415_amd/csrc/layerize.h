@@ -16,19 +16,26 @@ struct Options {
 };
 
 // One gather-reduce pass set over a CSR whose rows are the outputs.
-//   rows [0, n_main)                 write output row i; an empty range marks a split row
+//   rows [0, n_main)                 write output row i; a split row holds the single entry kSkip
 //   rows [n_main, n_main + n_seg)    are segments of split rows, writing scratch row (i - n_main)
 //   combine: output row comb_row[h] reduces scratch rows comb_idx[comb_ptr[h] .. comb_ptr[h+1])
+// Index entries carry the source row in bits 0..30 and "last edge of its row" in bit 31.
+// tasks: runs of consecutive main rows with a bounded edge count, as (first row, first edge)
+// pairs with a closing (n_main, main edge count) pair: the unit of work of one wave.
+constexpr uint32_t kLastEdge = 0x80000000u, kSkipRow = 0xFFFFFFFFu;
+constexpr int kIdxPad = 16;
 struct PassPlan {
     int32_t n_main = 0;
     int32_t n_seg = 0;
     int32_t n_heavy = 0;
     int64_t edges = 0;
     std::vector<int32_t> ptr;        // [n_main + n_seg + 1]
-    std::vector<int32_t> idx;        // [edges + 8], zero padded so 8-wide index reads stay in bounds
+    std::vector<uint32_t> idx;       // entries of all rows, zero padded by kIdxPad for chunked reads
+    std::vector<int32_t> tasks;      // [2 * (n_tasks + 1)]
+    int32_t n_tasks = 0;
     std::vector<int32_t> seg_owner;  // [n_seg] output row each segment belongs to
     std::vector<int32_t> comb_ptr;   // [n_heavy + 1]
-    std::vector<int32_t> comb_idx;   // [n_seg + 8] scratch rows per split row, zero padded
+    std::vector<uint32_t> comb_idx;  // [n_seg + kIdxPad] scratch rows per split row, zero padded
     std::vector<int32_t> comb_row;   // [n_heavy]
 };
 
