@@ -24,6 +24,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
+# HBM bytes per launch of a kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (scaled by the copy probe: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), see
+# profiles/stream_kernels_layered_3m_fwd_bwd_hbm_traffic.md.  Keyed by (workload, batch, class).
+MEASURED_TRAFFIC_PER_LAUNCH = {
+    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 482.1e6,
+    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 219.4e6,
+}
+
 
 class HipEvents:
     """hipEvent timing on an explicit stream, straight from the HIP runtime."""
@@ -61,6 +69,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="first run 5 plain device-to-device copies of this many MiB (calibrates the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters and gives the achievable copy rate)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the batch shards with no exchange; "
@@ -77,6 +88,22 @@ def main():
         sys.exit(2)
     pkg.load()                                    # no fallback: fails if the HIP library is missing
     torch.cuda.set_device(0)
+
+    copy_probe = None
+    if args.copy_probe_mib > 0:
+        n = args.copy_probe_mib * (1 << 20) // 4
+        a = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        copy_probe = {"mib": args.copy_probe_mib, "read_plus_write_GBs": round(2 * n * 4 / dt / 1e9, 1)}
+        del a, b
+        torch.cuda.empty_cache()
 
     t0 = time.perf_counter()
     circ, p, spec = make_config(args.workload, seed=args.seed, batch=args.batch)
@@ -141,7 +168,8 @@ def main():
     alg_bytes_step = sum(c["alg_bytes"] for c in classes.values()) / prof_steps
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((args.workload, B, dom)),
         "kernel": dom, "kernel_avg_launch_us": round(d["ms"] * 1e3 / max(1, d["launches"]), 2),
         "kernel_launches_per_step": d["launches"] // prof_steps,
         "kernel_alg_bytes_per_launch": round(d["alg_bytes"] / max(1, d["launches"])),
@@ -196,6 +224,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }
+    if copy_probe:
+        result["copy_probe"] = copy_probe
     print(json.dumps(result))
 
 
