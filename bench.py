@@ -68,6 +68,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tail", action="store_true", help="one launch per layer also for the narrow top layers")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="first run 5 plain device-to-device copies of this many MiB (calibrates the "
@@ -114,7 +115,7 @@ def main():
     w32 = as_inputs(p, semiring == pkg.KLAY_LOG)
 
     t0 = time.perf_counter()
-    k = pkg.Circuit(*circ.arrays(), device=0)
+    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail)
     t_build = time.perf_counter() - t0
     info = k.info()
     E, N = info["num_edges"], info["num_nodes"]

@@ -48,7 +48,8 @@ typedef struct klay_options {
     int32_t no_reorder;      /* 1: keep nodes of a layer in input-id order (no locality sort)     */
     int32_t heavy_fan;       /* rows with more sources than this are split (default 128)          */
     int32_t min_segment;     /* smallest split segment, in edges (default 32)                     */
-    int32_t reserved[5];
+    int32_t no_tail;         /* 1: one launch per layer also for the narrow top layers            */
+    int32_t reserved[4];
 } klay_options;
 
 typedef struct klay_info_t {
@@ -66,12 +67,15 @@ typedef struct klay_info_t {
     int64_t max_fan_out;
     int64_t num_split_rows;   /* rows (forward) and columns (backward) evaluated by split passes   */
     int64_t index_bytes;      /* device bytes held by index arrays                                 */
+    int64_t tail_first_layer; /* first layer that may run in the persistent top-of-circuit kernel
+                                 (0: none); the layers actually taken depend on the batch size       */
 } klay_info_t;
 
 /* Per-kernel-class timing of the most recent forward / backward call, filled only while
  * profiling is enabled.  Durations come from HIP events recorded on the caller's stream. */
 enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
-       KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_COUNT };
+       KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
+       KLAY_K_TAIL_BWD, KLAY_K_COUNT };
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];

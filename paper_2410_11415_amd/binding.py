@@ -18,7 +18,8 @@ from . import build as _build
 KLAY_OK, KLAY_EINVAL, KLAY_ECYCLE, KLAY_ENOMEM, KLAY_EHIP, KLAY_ESTATE = range(6)
 KLAY_REAL, KLAY_LOG = 0, 1
 KLAY_LIT, KLAY_AND, KLAY_OR, KLAY_TRUE, KLAY_FALSE = range(5)
-KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf")
+KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf",
+                  "tail_fwd", "tail_bwd")
 
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
@@ -33,7 +34,7 @@ class KlayError(RuntimeError):
 
 class klay_options(ctypes.Structure):
     _fields_ = [("no_reorder", ctypes.c_int32), ("heavy_fan", ctypes.c_int32), ("min_segment", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 5)]
+                ("no_tail", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
 
 
 class klay_info_t(ctypes.Structure):
@@ -41,11 +42,12 @@ class klay_info_t(ctypes.Structure):
                 ("device", ctypes.c_int32), ("num_nodes", ctypes.c_int64), ("num_edges", ctypes.c_int64),
                 ("dag_nodes", ctypes.c_int64), ("dag_edges", ctypes.c_int64), ("num_pad_nodes", ctypes.c_int64),
                 ("max_layer_nodes", ctypes.c_int64), ("max_fan_in", ctypes.c_int64), ("max_fan_out", ctypes.c_int64),
-                ("num_split_rows", ctypes.c_int64), ("index_bytes", ctypes.c_int64)]
+                ("num_split_rows", ctypes.c_int64), ("index_bytes", ctypes.c_int64),
+                ("tail_first_layer", ctypes.c_int64)]
 
 
 class klay_profile_t(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_float * 9), ("launches", ctypes.c_int32 * 9), ("alg_bytes", ctypes.c_double * 9)]
+    _fields_ = [("ms", ctypes.c_float * 11), ("launches", ctypes.c_int32 * 11), ("alg_bytes", ctypes.c_double * 11)]
 
 
 _lib = None
@@ -142,7 +144,7 @@ class Circuit:
     """A built circuit.  ``device=-1`` gives a host-only handle (layerization inspection only)."""
 
     def __init__(self, num_vars, node_type, node_lit, child_ptr, child_idx, roots, device=0,
-                 no_reorder=False, heavy_fan=0, min_segment=0):
+                 no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False):
         node_type = np.ascontiguousarray(node_type, dtype=np.uint8)
         node_lit = np.ascontiguousarray(node_lit, dtype=np.int32)
         child_ptr = np.ascontiguousarray(child_ptr, dtype=np.int64)
@@ -152,7 +154,7 @@ class Circuit:
             raise ValueError("node_type, node_lit and child_ptr sizes disagree")
         if child_ptr.shape[0] and child_idx.shape[0] != child_ptr[-1]:
             raise ValueError("child_idx must have child_ptr[-1] entries")
-        opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment))
+        opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail))
         self._h = None
         self._h = klay_build(int(num_vars), node_type.shape[0], _np_ptr(node_type), _np_ptr(node_lit),
                              _np_ptr(child_ptr), _np_ptr(child_idx) if child_idx.size else None,

@@ -89,6 +89,9 @@ struct klay_circuit {
     const int32_t *d_pos_row = nullptr, *d_neg_row = nullptr, *d_root_pos = nullptr, *d_top_ptr = nullptr,
                   *d_top_root = nullptr;
     int32_t true_row = -1, false_row = -1;
+    const klay::TailLayer* d_tail = nullptr;   // descriptors of layers plan.tail_first .. L
+    bool tail_lds_ok = false;                  // the large-LDS attribute was accepted for the tail kernels
+    int32_t last_tail_first = 0;               // first layer the last forward ran in the tail kernel (0: none)
     void* ws_own = nullptr;
     size_t ws_own_bytes = 0;
     void* ws_user = nullptr;
@@ -171,14 +174,16 @@ void launch_stream_op(const DevPass& dp, const Geometry& g, const float* src, co
                       float* dst, int B, hipStream_t s) {
     int64_t blocks = ((int64_t)dp.n_tasks + 3) / 4;
     blocks = (blocks + 7) / 8 * 8;
+    // outputs larger than the L2s together (8 x 4 MB) are written with streaming stores
+    const int nt = (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
     const int2* tasks = reinterpret_cast<const int2*>(dp.tasks);
     if (g.vec == 4)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
     else if (g.vec == 2)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
     else
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
 }
 
 // Streaming kernel over the main rows of a pass (batch tiles of one wave: B > 32).
@@ -300,6 +305,32 @@ klay_status upload(klay_circuit* c) {
         fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
         bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
     }
+    // tail candidates: plain index vectors by parent and by child, then the descriptor array
+    size_t o_tail = 0;
+    if (p.tail_first > 0) {
+        std::vector<klay::TailLayer> descs;
+        int64_t row0 = 0;
+        for (int l = 0; l < p.tail_first; ++l) row0 += p.layers[(size_t)l].n;
+        for (int l = p.tail_first; l <= L; ++l) {
+            const klay::LayerPlan& lay = p.layers[(size_t)l];
+            klay::TailLayer t{};
+            t.n = (int32_t)lay.n;
+            t.e = (int32_t)lay.e;
+            t.n_below = (int32_t)p.layers[(size_t)l - 1].n;
+            std::vector<int32_t> f(lay.row_ptr);
+            f.insert(f.end(), lay.child.begin(), lay.child.end());
+            t.fwd_off = (int32_t)pk.add(f);
+            std::vector<int32_t> b(lay.col_ptr);
+            b.insert(b.end(), lay.parent.begin(), lay.parent.end());
+            t.bwd_off = (int32_t)pk.add(b);
+            t.row0 = row0;
+            t.row0_below = row0 - t.n_below;
+            row0 += lay.n;
+            descs.push_back(t);
+        }
+        static_assert(sizeof(klay::TailLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
+        o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::TailLayer) / sizeof(int32_t));
+    }
     const size_t o_pos = pk.add(p.pos_row), o_neg = pk.add(p.neg_row), o_root = pk.add(p.root_pos);
     const size_t o_tptr = pk.add(p.top_ptr), o_troot = pk.add(p.top_root);
 
@@ -329,6 +360,7 @@ klay_status upload(klay_circuit* c) {
     c->d_root_pos = base + o_root;
     c->d_top_ptr = base + o_tptr;
     c->d_top_root = base + o_troot;
+    if (p.tail_first > 0) c->d_tail = reinterpret_cast<const klay::TailLayer*>(base + o_tail);
     return KLAY_OK;
 }
 
@@ -374,6 +406,133 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
     }
 }
 
+
+// ---- persistent kernels for the narrow top layers --------------------------------------------
+constexpr int kTailLdsWords = 32768;       // 128 KB of the 160 KB LDS of a CU
+
+struct TailChoice {
+    int first = 0;       // first layer run by the tail kernels (0: tail not used)
+    int ct = 1;          // batch columns per workgroup
+    int nmax = 0;        // LDS rows per buffer
+};
+
+int tail_ct(int B) {
+    if (B >= 8) return 8;
+    int ct = 1;
+    while (ct < B) ct *= 2;
+    return ct;
+}
+
+// Largest suffix of the tail candidates whose buffers fit the LDS budget for `buffers` value
+// arrays of CT columns; at least two layers, otherwise the tail is not worth a kernel of its own.
+TailChoice choose_tail(const klay_circuit* c, int B, int buffers) {
+    TailChoice t;
+    const klay::CircuitPlan& p = c->plan;
+    if (p.tail_first <= 0 || !c->tail_lds_ok) return t;
+    t.ct = tail_ct(B);
+    const int L = p.num_layers;
+    int64_t nmax = 0, imax = 0;
+    int first = 0;
+    for (int l = L; l >= p.tail_first; --l) {
+        const klay::LayerPlan& lay = p.layers[(size_t)l];
+        const int64_t n2 = std::max(nmax, lay.n);
+        const int64_t below = p.layers[(size_t)l - 1].n;
+        const int64_t i2 = std::max(imax, std::max(lay.n, below) + 1 + lay.e);
+        if ((int64_t)buffers * n2 * t.ct + i2 > kTailLdsWords) break;
+        // the reverse sweep also holds the adjoints of layer l-1 when l is not the first tail layer;
+        // that layer is then a tail layer itself and is checked in the next iteration
+        nmax = n2;
+        imax = i2;
+        first = l;
+    }
+    if (first == 0 || L - first + 1 < 2) return t;
+    t.first = first;
+    t.nmax = (int)nmax;
+    return t;
+}
+
+size_t tail_lds_bytes(const klay_circuit* c, const TailChoice& t, int buffers) {
+    const klay::CircuitPlan& p = c->plan;
+    int64_t imax = 0;
+    for (int l = t.first; l <= p.num_layers; ++l)
+        imax = std::max(imax, std::max(p.layers[(size_t)l].n, p.layers[(size_t)l - 1].n) + 1 + p.layers[(size_t)l].e);
+    return (size_t)((int64_t)buffers * t.nmax * t.ct + imax) * sizeof(float);
+}
+
+template <int CT>
+hipError_t tail_attr() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&klay::tail_fwd_kernel<CT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kTailLdsWords * 4);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&klay::tail_bwd_kernel<CT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kTailLdsWords * 4);
+}
+
+bool enable_tail_lds() {
+    hipError_t e = tail_attr<8>();
+    if (e == hipSuccess) e = tail_attr<4>();
+    if (e == hipSuccess) e = tail_attr<2>();
+    if (e == hipSuccess) e = tail_attr<1>();
+    if (e != hipSuccess) { (void)hipGetLastError(); return false; }
+    return true;
+}
+
+void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int B, int ld, bool log_domain,
+                     hipStream_t s) {
+    const klay::CircuitPlan& p = c->plan;
+    const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
+    const int n_layers = p.num_layers - t.first + 1;
+    const int first_is_and = t.first & 1;
+    const size_t lds = tail_lds_bytes(c, t, 2);
+    dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
+#define KLAY_TAIL_FWD(CT)                                                                              \
+    hipLaunchKernelGGL((klay::tail_fwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
+                       n_layers, first_is_and, c->d_index, act, B, ld, log_domain ? 1 : 0, t.nmax)
+    switch (t.ct) {
+    case 8: KLAY_TAIL_FWD(8); break;
+    case 4: KLAY_TAIL_FWD(4); break;
+    case 2: KLAY_TAIL_FWD(2); break;
+    default: KLAY_TAIL_FWD(1); break;
+    }
+#undef KLAY_TAIL_FWD
+}
+
+void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* act, const float* dout,
+                     float* g_out, int B, int ld, hipStream_t s) {
+    const klay::CircuitPlan& p = c->plan;
+    const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
+    const int n_layers = p.num_layers - t.first + 1;
+    const int first_is_and = t.first & 1;
+    const size_t lds = tail_lds_bytes(c, t, 3);
+    dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
+#define KLAY_TAIL_BWD(CT)                                                                              \
+    hipLaunchKernelGGL((klay::tail_bwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
+                       n_layers, first_is_and, c->d_index, act, dout, c->d_top_ptr, c->d_top_root,     \
+                       p.num_roots, g_out, B, ld, t.nmax)
+    switch (t.ct) {
+    case 8: KLAY_TAIL_BWD(8); break;
+    case 4: KLAY_TAIL_BWD(4); break;
+    case 2: KLAY_TAIL_BWD(2); break;
+    default: KLAY_TAIL_BWD(1); break;
+    }
+#undef KLAY_TAIL_BWD
+}
+
+double tail_alg_bytes(const klay_circuit* c, int first, int B, bool backward) {
+    double bytes = 0;
+    for (int l = first; l <= c->plan.num_layers; ++l) {
+        const klay::LayerPlan& lay = c->plan.layers[(size_t)l];
+        const double below = (double)c->plan.layers[(size_t)l - 1].n;
+        if (!backward) bytes += 4.0 * B * ((double)lay.e + (double)lay.n) + 4.0 * ((double)lay.e + (double)lay.n);
+        else if (l > first) {
+            const bool is_and = (l & 1) != 0;
+            bytes += 4.0 * B * ((is_and ? 1.0 : 2.0) * (double)lay.e + (is_and ? 1.0 : 2.0) * below) +
+                     4.0 * ((double)lay.e + below);
+        }
+    }
+    return bytes;
+}
+
 }  // namespace
 
 extern "C" {
@@ -391,6 +550,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
         o.no_reorder = opts->no_reorder != 0;
         if (opts->heavy_fan > 0) o.heavy_fan = opts->heavy_fan;
         if (opts->min_segment > 0) o.min_segment = opts->min_segment;
+        o.no_tail = opts->no_tail != 0;
     }
     std::unique_ptr<klay_circuit> c;
     try {
@@ -423,6 +583,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
             if (c->d_index) (void)hipFree(c->d_index);
             return st;
         }
+        c->tail_lds_ok = c->plan.tail_first > 0 && enable_tail_lds();
     }
     *out = c.release();
     return KLAY_OK;
@@ -464,6 +625,7 @@ klay_status klay_info(const klay_circuit* c, klay_info_t* info) {
     info->max_fan_out = p.max_fan_out;
     info->num_split_rows = p.num_split_rows;
     info->index_bytes = (int64_t)c->index_bytes;
+    info->tail_first_layer = p.tail_first;
     return KLAY_OK;
 }
 
@@ -578,8 +740,10 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
                            act + (size_t)c->false_row * g.ld, g.ld, log_domain ? -INFINITY : 0.0f);
     prof.end();
 
-    // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4)
-    for (int l = 1; l <= L; ++l) {
+    // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4); the narrow top runs in one persistent kernel
+    const TailChoice tail = choose_tail(c, B, with_bwd ? 3 : 2);
+    const int last_regular = tail.first > 0 ? tail.first - 1 : L;
+    for (int l = 1; l <= last_regular; ++l) {
         const DevLayer& d = c->dl[(size_t)l];
         const bool is_and = (l & 1) != 0;
         const int op = log_domain ? (is_and ? klay::OP_SUM : klay::OP_LSE) : (is_and ? klay::OP_PROD : klay::OP_SUM);
@@ -587,6 +751,12 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
         prof.begin(cls, 4.0 * B * ((double)d.e + (double)d.n) + 4.0 * ((double)d.e + (double)d.n));
         run_pass_set(op, op, d.fwd, act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld, nullptr, nullptr,
                      act + (size_t)d.row0 * g.ld, scratch, g, B, s);
+        prof.end();
+    }
+
+    if (tail.first > 0) {
+        prof.begin(KLAY_K_TAIL_FWD, tail_alg_bytes(c, tail.first, B, false));
+        launch_tail_fwd(c, tail, act, B, g.ld, log_domain, s);
         prof.end();
     }
 
@@ -603,6 +773,7 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
     c->last_B = B;
     c->last_semiring = semiring;
     c->last_ws_has_bwd = with_bwd;
+    c->last_tail_first = tail.first;
     return KLAY_OK;
 }
 
@@ -630,15 +801,25 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
     Profiler prof(c, &c->ev_bwd, s);
 
-    prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
-    {
+    // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
+    // which seeds the adjoints itself and leaves those of its first layer in gcur
+    int top = L;
+    if (c->last_tail_first > 0) {
+        TailChoice tail = choose_tail(c, B, 3);
+        if (tail.first != c->last_tail_first) return fail(KLAY_ESTATE, "klay_backward: tail layout changed since forward");
+        prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R);
+        launch_tail_bwd(c, tail, act, dout, gcur, B, g.ld, s);
+        prof.end();
+        top = tail.first;
+    } else {
+        prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
         dim3 grid((unsigned)c->dl[(size_t)L].n);
         hipLaunchKernelGGL(klay::seed_kernel, grid, dim3(256), 0, s, dout, c->d_top_ptr, c->d_top_root, B, R,
                            g.ld, gcur);
+        prof.end();
     }
-    prof.end();
 
-    for (int l = L; l >= 1; --l) {
+    for (int l = top; l >= 1; --l) {
         const DevLayer& d = c->dl[(size_t)l];
         const DevLayer& below = c->dl[(size_t)l - 1];
         const bool is_and = (l & 1) != 0;

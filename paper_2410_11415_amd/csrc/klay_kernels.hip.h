@@ -59,6 +59,22 @@ __device__ __forceinline__ void load_vec(float (&x)[VEC], const float* p) {
     for (int v = 0; v < VEC; ++v) x[v] = f[v];
 }
 
+// Streaming store: the rows of a wide layer are written once and next read by another kernel,
+// long after they have left the 4 MB L2, so they are marked non-temporal to leave the L2 to the
+// gathers.  Narrow layers keep ordinary stores: their rows are still in L2 when the next layer reads.
+template <int VEC>
+__device__ __forceinline__ void store_vec_stream(float* p, const float (&x)[VEC]) {
+    typedef float vf __attribute__((ext_vector_type(VEC)));
+    vf t;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) t[v] = x[v];
+    __builtin_nontemporal_store(t, reinterpret_cast<vf*>(p));
+}
+template <>
+__device__ __forceinline__ void store_vec_stream<1>(float* p, const float (&x)[1]) {
+    __builtin_nontemporal_store(x[0], p);
+}
+
 template <int VEC>
 __device__ __forceinline__ void store_vec(float* p, const float (&x)[VEC]) {
     using T = typename Pack<VEC>::T;
@@ -117,7 +133,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                                                      const float* __restrict__ src,
                                                      const float* __restrict__ src2,
                                                      const float* __restrict__ own, float* __restrict__ dst,
-                                                     int B, int ld) {
+                                                     int B, int ld, int stream_stores) {
     constexpr int CH = (OP == OP_SOFTMAX_BWD) ? 4 : 8;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -200,7 +216,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                     acc[v] = identity<OP>();
                     mx[v] = -INFINITY;
                 }
-                store_vec<VEC>(dstc + (size_t)rws[i] * (size_t)ld, o);
+                if (stream_stores) store_vec_stream<VEC>(dstc + (size_t)rws[i] * (size_t)ld, o);
+                else store_vec<VEC>(dstc + (size_t)rws[i] * (size_t)ld, o);
             }
         }
 #pragma unroll
@@ -273,6 +290,143 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
         else out = a.dst_seg + (size_t)(row - a.n_main) * a.ld + col;
         store_vec<VEC>(out, o);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Persistent kernels for the narrow top of the circuit (layers that taper to the roots): instead
+// of one launch per layer, a workgroup owns CT batch columns, keeps the values (forward) or the
+// adjoints (backward) of the current and the previous layer in LDS and walks the layers with a
+// barrier in between; batch columns are independent, so no grid-wide barrier is needed.  Each
+// layer's index vectors are staged into LDS first.  Values are also written to the activation
+// buffer, because the backward pass reads them.
+//   LDS (floats): forward 2 * nmax * CT values, backward 3 * nmax * CT, then nmax + 1 + emax ints.
+// ---------------------------------------------------------------------------------------------
+struct TailLayer {
+    int32_t n, e;          // nodes and edges of this layer
+    int32_t n_below;       // nodes of the layer below
+    int32_t fwd_off;       // [row_ptr (n+1) | child (e)] by parent, offset in ints into the index buffer
+    int32_t bwd_off;       // [col_ptr (n_below+1) | parent (e)] by child
+    int32_t pad_;
+    int64_t row0;          // first activation row of this layer
+    int64_t row0_below;
+};
+
+constexpr int kTailThreads = 1024;
+
+template <int OP, int CT>
+__device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib, const float* prev, float* cur,
+                                              const float* below, bool from_global, float* act_out, int ld,
+                                              bool active) {
+    constexpr int RS = kTailThreads / CT;
+    const int c = threadIdx.x % CT;
+    for (int r = threadIdx.x / CT; r < L.n; r += RS) {
+        const int beg = ib[r], end = ib[r + 1];
+        float acc = identity<OP>(), mx = -INFINITY;
+        for (int j = beg; j < end; ++j) {
+            const int ch = ib[L.n + 1 + j];
+            float x;
+            if (from_global) x = active ? below[(size_t)ch * ld] : identity<OP>();
+            else x = prev[ch * CT + c];
+            accumulate<OP>(acc, mx, x, 0.0f, 0.0f);
+        }
+        const float o = finish<OP>(acc, mx);
+        cur[r * CT + c] = o;
+        if (active) act_out[(size_t)r * ld] = o;
+    }
+}
+
+template <int CT>
+__global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer* __restrict__ layers, int n_layers,
+                                                                int first_is_and, const int32_t* __restrict__ ibase,
+                                                                float* act, int B, int ld, int log_domain,
+                                                                int nmax) {
+    extern __shared__ float smem[];
+    float* prev = smem;
+    float* cur = smem + (size_t)nmax * CT;
+    int* ib = reinterpret_cast<int*>(smem + (size_t)2 * nmax * CT);
+    const int col = (int)blockIdx.x * CT + (int)(threadIdx.x % CT);
+    const bool active = col < B;
+    for (int t = 0; t < n_layers; ++t) {
+        const TailLayer L = layers[t];
+        const int32_t* g = ibase + L.fwd_off;
+        for (int i = threadIdx.x; i < L.n + 1 + L.e; i += kTailThreads) ib[i] = g[i];
+        __syncthreads();
+        const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
+        const float* below = act + (size_t)L.row0_below * ld + col;
+        float* out = act + (size_t)L.row0 * ld + col;
+        const bool fg = t == 0;
+        if (log_domain) {
+            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+            else tail_fwd_rows<OP_LSE, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+        } else {
+            if (is_and) tail_fwd_rows<OP_PROD, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+            else tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+        }
+        __syncthreads();
+        float* tmp = prev; prev = cur; cur = tmp;
+    }
+}
+
+// Reverse sweep over the same layers (log semiring): seeds the top layer's adjoints from dout,
+// walks down to the first tail layer and leaves that layer's adjoints in g_out[n_first, ld].
+template <int CT>
+__global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer* __restrict__ layers, int n_layers,
+                                                                int first_is_and, const int32_t* __restrict__ ibase,
+                                                                const float* __restrict__ act,
+                                                                const float* __restrict__ dout,
+                                                                const int32_t* __restrict__ top_ptr,
+                                                                const int32_t* __restrict__ top_root, int R,
+                                                                float* __restrict__ g_out, int B, int ld, int nmax) {
+    extern __shared__ float smem[];
+    constexpr int RS = kTailThreads / CT;
+    float* cur = smem;
+    float* nxt = smem + (size_t)nmax * CT;
+    float* nl = smem + (size_t)2 * nmax * CT;
+    int* ib = reinterpret_cast<int*>(smem + (size_t)3 * nmax * CT);
+    const int c = threadIdx.x % CT;
+    const int col0 = (int)blockIdx.x * CT;
+    const int col = col0 + c;
+    const bool active = col < B;
+    {   // adjoint seed of the top layer
+        const TailLayer L = layers[n_layers - 1];
+        for (int i = threadIdx.x / CT; i < L.n; i += RS) {
+            float acc = 0.0f;
+            if (active)
+                for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)col * R + top_root[t]];
+            cur[i * CT + c] = acc;
+        }
+    }
+    for (int t = n_layers - 1; t >= 1; --t) {          // step t: adjoints of layer t -> layer t-1
+        const TailLayer L = layers[t];
+        const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
+        const int32_t* g = ibase + L.bwd_off;
+        for (int i = threadIdx.x; i < L.n_below + 1 + L.e; i += kTailThreads) ib[i] = g[i];
+        if (!is_and)
+            for (int i = threadIdx.x; i < L.n * CT; i += kTailThreads) {
+                const int cc = col0 + i % CT;
+                nl[i] = cc < B ? act[((size_t)L.row0 + i / CT) * ld + cc] : 0.0f;
+            }
+        __syncthreads();
+        for (int r = threadIdx.x / CT; r < L.n_below; r += RS) {
+            const int beg = ib[r], end = ib[r + 1];
+            float acc = 0.0f, mx = 0.0f;
+            if (is_and) {
+                for (int j = beg; j < end; ++j) acc += cur[ib[L.n_below + 1 + j] * CT + c];
+            } else {
+                const float own = active ? act[((size_t)L.row0_below + r) * ld + col] : 0.0f;
+                for (int j = beg; j < end; ++j) {
+                    const int p = ib[L.n_below + 1 + j];
+                    accumulate<OP_SOFTMAX_BWD>(acc, mx, cur[p * CT + c], nl[p * CT + c], own);
+                }
+            }
+            nxt[r * CT + c] = acc;
+        }
+        __syncthreads();
+        float* tmp = cur; cur = nxt; nxt = tmp;
+    }
+    const int n_first = layers[0].n;
+    if (active)
+        for (int r = threadIdx.x / CT; r < n_first; r += RS) g_out[(size_t)r * ld + col] = cur[r * CT + c];
 }
 
 // ---------------------------------------------------------------------------------------------

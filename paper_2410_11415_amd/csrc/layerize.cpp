@@ -402,6 +402,10 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                     cpar[(size_t)fill[(size_t)lay.child[(size_t)j]]++] = (int32_t)p;
         }
         make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd);
+        if (lay.n <= kTailRowsCap && nc <= kTailRowsCap && e <= kTailEdgesCap) {
+            lay.col_ptr.swap(cptr);
+            lay.parent.swap(cpar);
+        }
         plan.num_split_rows += lay.fwd.n_heavy + lay.bwd.n_heavy;
         plan.max_fwd_seg = std::max<int64_t>(plan.max_fwd_seg, lay.fwd.n_seg);
         plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, lay.bwd.n_seg);
@@ -410,6 +414,14 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     for (int32_t l = 0; l <= L; ++l) {
         plan.num_nodes += plan.layers[(size_t)l].n;
         plan.max_layer_nodes = std::max(plan.max_layer_nodes, plan.layers[(size_t)l].n);
+    }
+
+    // the narrow top: the longest suffix of layers that all kept their plain index vectors
+    plan.tail_first = 0;
+    if (!opt.no_tail) {
+        int32_t t = L + 1;
+        while (t - 1 >= 1 && !plan.layers[(size_t)t - 1].col_ptr.empty()) --t;
+        if (t <= L) plan.tail_first = t;
     }
 
     // ---------------------------------------------------------------- leaf layer and roots

@@ -13,7 +13,13 @@ struct Options {
     bool no_reorder = false;
     int32_t heavy_fan = 128;    // rows with more sources than this are evaluated in split passes
     int32_t min_segment = 32;   // smallest segment of a split row, in edges
+    bool no_tail = false;       // never use the persistent kernels for the narrow top layers
 };
+
+// Layers at the top of the circuit with at most this many nodes (and 4x as many edges) keep
+// plain by-parent and by-child index vectors for the persistent LDS kernels.
+constexpr int64_t kTailRowsCap = 4096;
+constexpr int64_t kTailEdgesCap = 4 * kTailRowsCap;
 
 // One gather-reduce pass set over a CSR whose rows are the outputs.
 //   rows [0, n_main)                 write output row i; a split row holds the single entry kSkip
@@ -46,6 +52,8 @@ struct LayerPlan {
     std::vector<int32_t> child;      // [e]    S_l: position of the child in layer - 1
     std::vector<int32_t> origin;     // [n] input node id the row stands for
     std::vector<uint8_t> is_pad;     // [n] 1 for unary chain nodes
+    std::vector<int32_t> col_ptr;    // [n_below + 1] by child (kept for tail candidates only)
+    std::vector<int32_t> parent;     // [e]
     PassPlan fwd;                    // outputs = nodes of this layer, sources = layer - 1
     PassPlan bwd;                    // outputs = nodes of layer - 1, sources = this layer
 };
@@ -60,6 +68,7 @@ struct CircuitPlan {
     int64_t num_nodes = 0, num_edges = 0, dag_nodes = 0, dag_edges = 0, num_pad_nodes = 0;
     int64_t max_layer_nodes = 0, max_fan_in = 0, max_fan_out = 0, num_split_rows = 0;
     int64_t max_fwd_seg = 0, max_bwd_seg = 0;   // scratch rows needed by split passes
+    int32_t tail_first = 0;              // layers tail_first..num_layers are tail candidates (0: none)
 };
 
 // Status codes mirror klay_status (0 ok, 1 invalid, 2 cycle, 3 no memory).

@@ -25,9 +25,9 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.klay_options) == 32
-    assert ctypes.sizeof(binding.klay_info_t) == 16 + 10 * 8
-    assert ctypes.sizeof(binding.klay_profile_t) == 9 * 4 + 9 * 4 + 9 * 8
-    assert len(binding.KERNEL_CLASSES) == 9
+    assert ctypes.sizeof(binding.klay_info_t) == 16 + 11 * 8
+    assert ctypes.sizeof(binding.klay_profile_t) == 11 * 4 + 11 * 4 + 11 * 8
+    assert len(binding.KERNEL_CLASSES) == 11
 
 
 def test_last_error_is_a_string():

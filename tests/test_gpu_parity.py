@@ -268,7 +268,7 @@ def test_call_order_errors(klay):
 
 def test_profile_reports_kernel_classes(klay):
     c, p, _ = make_config("layered_100k", seed=0, scale=0.2, batch=64)
-    k = build(klay, c)
+    k = build(klay, c, no_tail=True)
     k.set_profiling(True)
     gpu_eval(k, as_inputs(p, True), LOG, np.ones((64, c.roots.shape[0]), np.float32))
     prof = k.get_profile()
@@ -276,3 +276,28 @@ def test_profile_reports_kernel_classes(klay):
     assert prof["bwd_softmax"]["launches"] >= 10 and prof["bwd_softmax"]["alg_bytes"] > 0
     k.set_profiling(False)
     k.close()
+
+
+@pytest.mark.parametrize("B", [1, 3, 8, 37, 256])
+def test_persistent_top_kernel_matches_per_layer_launches(klay, B):
+    """the narrow top layers run in one LDS-resident kernel; with no_tail every layer is its own launch"""
+    c, p, _ = make_config("layered_100k", seed=5, scale=0.3, batch=B)
+    w32 = as_inputs(p, True)
+    d = np.random.default_rng(5).normal(size=(B, c.roots.shape[0])).astype(np.float32)
+    k_tail, k_flat = build(klay, c), build(klay, c, no_tail=True)
+    assert k_tail.info()["tail_first_layer"] > 0 and k_flat.info()["tail_first_layer"] == 0
+    k_tail.set_profiling(True)
+    a = gpu_eval(k_tail, w32, LOG, d)
+    prof = k_tail.get_profile()
+    assert prof["tail_fwd"]["launches"] == 1 and prof["tail_bwd"]["launches"] == 1
+    k_tail.set_profiling(False)
+    b = gpu_eval(k_flat, w32, LOG, d)
+    ref, rd = oracle_eval(c, w32, LOG, d, or_levels=k_tail.num_layers // 2)
+    for got, gd in (a, b):
+        assert_log_close(got, ref, "tail")
+        assert_grad_close(gd, rd, "tail grad")
+    np.testing.assert_allclose(a[0], b[0], rtol=0, atol=2e-5)
+    ar, _ = gpu_eval(k_tail, as_inputs(p, False), REAL)
+    refr, _ = oracle_eval(c, as_inputs(p, False), REAL)
+    assert_real_close(ar, refr, "tail real")
+    k_tail.close(); k_flat.close()
