@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tail", action="store_true", help="one launch per layer also for the narrow top layers")
+    ap.add_argument("--alias-chains", action="store_true",
+                    help="padding-free evaluation: no unary chain nodes, edges read the child's own row")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="first run 5 plain device-to-device copies of this many MiB (calibrates the "
@@ -115,7 +117,7 @@ def main():
     w32 = as_inputs(p, semiring == pkg.KLAY_LOG)
 
     t0 = time.perf_counter()
-    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail)
+    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, alias_chains=args.alias_chains)
     t_build = time.perf_counter() - t0
     info = k.info()
     E, N = info["num_edges"], info["num_nodes"]
@@ -217,6 +219,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "semiring": "log" if semiring == pkg.KLAY_LOG else "real",
                    "pass": "forward+backward" if backward else "forward", "seed": args.seed,
+                   "layerization": "alias_chains (no unary chain nodes)" if args.alias_chains else
+                                   "unary chain nodes per (node, layer)",
                    "layers": info["num_layers"], "layered_nodes": N, "layered_edges": E,
                    "dag_nodes": info["dag_nodes"], "dag_edges": info["dag_edges"],
                    "pad_nodes": info["num_pad_nodes"], "num_vars": info["num_vars"], "num_roots": info["num_roots"],

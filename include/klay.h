@@ -49,7 +49,10 @@ typedef struct klay_options {
     int32_t heavy_fan;       /* rows with more sources than this are split (default 128)          */
     int32_t min_segment;     /* smallest split segment, in edges (default 32)                     */
     int32_t no_tail;         /* 1: one launch per layer also for the narrow top layers            */
-    int32_t reserved[4];
+    int32_t alias_chains;    /* 1: insert no unary chain nodes; an edge that skips layers reads the
+                                child's own row (same values, fewer rows and edges; klay_layer_csr
+                                then returns rows of the whole activation buffer, layer 0 first)    */
+    int32_t reserved[3];
 } klay_options;
 
 typedef struct klay_info_t {

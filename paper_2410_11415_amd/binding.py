@@ -34,7 +34,7 @@ class KlayError(RuntimeError):
 
 class klay_options(ctypes.Structure):
     _fields_ = [("no_reorder", ctypes.c_int32), ("heavy_fan", ctypes.c_int32), ("min_segment", ctypes.c_int32),
-                ("no_tail", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+                ("no_tail", ctypes.c_int32), ("alias_chains", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class klay_info_t(ctypes.Structure):
@@ -144,7 +144,8 @@ class Circuit:
     """A built circuit.  ``device=-1`` gives a host-only handle (layerization inspection only)."""
 
     def __init__(self, num_vars, node_type, node_lit, child_ptr, child_idx, roots, device=0,
-                 no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False):
+                 no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False,
+                 alias_chains=False):
         node_type = np.ascontiguousarray(node_type, dtype=np.uint8)
         node_lit = np.ascontiguousarray(node_lit, dtype=np.int32)
         child_ptr = np.ascontiguousarray(child_ptr, dtype=np.int64)
@@ -154,7 +155,7 @@ class Circuit:
             raise ValueError("node_type, node_lit and child_ptr sizes disagree")
         if child_ptr.shape[0] and child_idx.shape[0] != child_ptr[-1]:
             raise ValueError("child_idx must have child_ptr[-1] entries")
-        opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail))
+        opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail), int(alias_chains))
         self._h = None
         self._h = klay_build(int(num_vars), node_type.shape[0], _np_ptr(node_type), _np_ptr(node_lit),
                              _np_ptr(child_ptr), _np_ptr(child_idx) if child_idx.size else None,

@@ -37,6 +37,7 @@ struct DevPass {
     const int32_t *ptr = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_row = nullptr, *tasks = nullptr;
     const uint32_t *idx = nullptr, *comb_idx = nullptr;
     int32_t n_main = 0, n_seg = 0, n_heavy = 0, n_tasks = 0;
+    bool has_weighted = false;
     int64_t edges = 0;
 };
 
@@ -84,6 +85,7 @@ struct klay_circuit {
     klay::CircuitPlan plan;
     int device = -1;
     std::vector<DevLayer> dl;
+    DevPass top_bwd;                     // alias mode: adjoints of the top layer (from the dout rows)
     int32_t* d_index = nullptr;          // one allocation holding every index array
     size_t index_bytes = 0;
     const int32_t *d_pos_row = nullptr, *d_neg_row = nullptr, *d_root_pos = nullptr, *d_top_ptr = nullptr,
@@ -118,7 +120,11 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     w.wT = off; off += align_floats((size_t)std::max(1, p.num_vars) * g.ld);
     const int64_t seg = std::max(p.max_fwd_seg, need_bwd ? p.max_bwd_seg : 0);
     w.scratch = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
-    if (need_bwd) {
+    if (need_bwd && p.alias) {
+        // adjoints of every row plus one row per root column for the transposed dout
+        w.g0 = off; off += align_floats((size_t)(p.num_nodes + p.num_roots) * g.ld);
+        w.g1 = w.g0;
+    } else if (need_bwd) {
         w.g0 = off; off += align_floats((size_t)p.max_layer_nodes * g.ld);
         w.g1 = off; off += align_floats((size_t)p.max_layer_nodes * g.ld);
     }
@@ -290,6 +296,7 @@ void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const 
     d.comb_row = base + o.comb_row;
     d.tasks = base + o.tasks;
     d.n_tasks = p.n_tasks;
+    d.has_weighted = p.has_weighted;
     d.n_main = p.n_main;
     d.n_seg = p.n_seg;
     d.n_heavy = p.n_heavy;
@@ -305,6 +312,8 @@ klay_status upload(klay_circuit* c) {
         fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
         bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
     }
+    PassOffsets to{};
+    if (p.alias) to = pack_pass(pk, p.top_bwd);
     // tail candidates: plain index vectors by parent and by child, then the descriptor array
     size_t o_tail = 0;
     if (p.tail_first > 0) {
@@ -355,6 +364,7 @@ klay_status upload(klay_circuit* c) {
             bind_pass(d.bwd, p.layers[(size_t)l].bwd, bo[(size_t)l], base);
         }
     }
+    if (p.alias) bind_pass(c->top_bwd, p.top_bwd, to, base);
     c->d_pos_row = base + o_pos;
     c->d_neg_row = base + o_neg;
     c->d_root_pos = base + o_root;
@@ -551,6 +561,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
         if (opts->heavy_fan > 0) o.heavy_fan = opts->heavy_fan;
         if (opts->min_segment > 0) o.min_segment = opts->min_segment;
         o.no_tail = opts->no_tail != 0;
+        o.alias_chains = opts->alias_chains != 0;
     }
     std::unique_ptr<klay_circuit> c;
     try {
@@ -749,8 +760,9 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
         const int op = log_domain ? (is_and ? klay::OP_SUM : klay::OP_LSE) : (is_and ? klay::OP_PROD : klay::OP_SUM);
         const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM : (op == klay::OP_PROD ? KLAY_K_FWD_PROD : KLAY_K_FWD_LSE);
         prof.begin(cls, 4.0 * B * ((double)d.e + (double)d.n) + 4.0 * ((double)d.e + (double)d.n));
-        run_pass_set(op, op, d.fwd, act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld, nullptr, nullptr,
-                     act + (size_t)d.row0 * g.ld, scratch, g, B, s);
+        // alias mode: child entries are rows of the whole buffer, otherwise of the layer below
+        const float* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
+        run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, scratch, g, B, s);
         prof.end();
     }
 
@@ -765,7 +777,8 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
     {
         dim3 grid((unsigned)p.num_roots);
         hipLaunchKernelGGL(klay::root_out_kernel, grid, dim3(256), 0, s,
-                           act + (size_t)c->dl[(size_t)L].row0 * g.ld, c->d_root_pos, (int)B, p.num_roots, g.ld, out);
+                           p.alias ? act : act + (size_t)c->dl[(size_t)L].row0 * g.ld, c->d_root_pos, (int)B,
+                           p.num_roots, g.ld, out);
     }
     prof.end();
     KLAY_HIP(hipGetLastError());
@@ -801,6 +814,40 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
     Profiler prof(c, &c->ev_bwd, s);
 
+    if (p.alias) {
+        // One adjoint row per activation row; rows N .. N+R-1 hold dout transposed.  Layer by layer
+        // from the top, every row gathers from its parents, wherever they live (all final by then).
+        float* G = gcur;
+        prof.begin(KLAY_K_SEED, 8.0 * B * R);
+        hipLaunchKernelGGL(klay::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, g.ld,
+                           G + (size_t)p.num_nodes * g.ld);
+        prof.end();
+        for (int l = L; l >= 0; --l) {
+            const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
+            const DevLayer& d = c->dl[(size_t)l];
+            const double rows = (double)d.n, e = (double)dp.edges;
+            if (dp.has_weighted) {
+                prof.begin(KLAY_K_BWD_SOFTMAX, 4.0 * B * (2.0 * e + 2.0 * rows) + 4.0 * (e + rows));
+                run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, act + (size_t)d.row0 * g.ld,
+                             G + (size_t)d.row0 * g.ld, scratch, g, B, s);
+            } else {
+                prof.begin(KLAY_K_BWD_SUM, 4.0 * B * (e + rows) + 4.0 * (e + rows));
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, G + (size_t)d.row0 * g.ld, scratch,
+                             g, B, s);
+            }
+            prof.end();
+        }
+        prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
+        if (V > 0) {
+            dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
+            hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B, V,
+                               g.ld, 1, dleaf);
+        }
+        prof.end();
+        KLAY_HIP(hipGetLastError());
+        return KLAY_OK;
+    }
+
     // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
     // which seeds the adjoints itself and leaves those of its first layer in gcur
     int top = L;
@@ -822,7 +869,7 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     for (int l = top; l >= 1; --l) {
         const DevLayer& d = c->dl[(size_t)l];
         const DevLayer& below = c->dl[(size_t)l - 1];
-        const bool is_and = (l & 1) != 0;
+        const bool is_and = (l & 1) != 0 || !d.bwd.has_weighted;   // no weighted edge: plain sums
         if (is_and) {
             prof.begin(KLAY_K_BWD_SUM, 4.0 * B * ((double)d.e + (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
             run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s);

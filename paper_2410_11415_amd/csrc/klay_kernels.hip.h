@@ -15,9 +15,11 @@ namespace klay {
 
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3 };
 
-// Index entries: bits 0..30 = source row, bit 31 = last edge of its output row.  kSkip (all ones)
-// stands for a whole output row that this pass leaves untouched (a split row).
-constexpr uint32_t kLast = 0x80000000u, kSkip = 0xFFFFFFFFu, kIdMask = 0x7FFFFFFFu;
+// Index entries: bits 0..29 = source row, bit 31 = last edge of its output row, bit 30 = weighted
+// edge (reverse sweep only: the parent is an OR node with more than one child, so the adjoint
+// passes through the softmax weight exp(child - parent); an unweighted edge passes it unchanged).
+// kSkip (all ones) stands for a whole output row that this pass leaves untouched (a split row).
+constexpr uint32_t kLast = 0x80000000u, kWeighted = 0x40000000u, kSkip = 0xFFFFFFFFu, kIdMask = 0x3FFFFFFFu;
 
 struct PassArgs {
     const int32_t* ptr;        // [n_total + 1] CSR offsets into idx
@@ -94,9 +96,10 @@ __device__ __forceinline__ int xcd_block(int bid, int nblocks) { return (bid & 7
 //   OP_SUM / OP_PROD  acc = running sum / product
 //   OP_LSE            (mx, acc) = (running max, sum of exp(x - mx)); one exp per element:
 //                     a new maximum rescales the sum by exp(mx - x), otherwise exp(x - mx) is added
-//   OP_SOFTMAX_BWD    acc += g * exp(own - parent value); a parent at -inf passes nothing down
+//   OP_SOFTMAX_BWD    acc += g * exp(own - parent value) on weighted edges (a parent at -inf
+//                     passes nothing down), acc += g on unweighted ones
 template <int OP>
-__device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc) {
+__device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc, bool weighted = true) {
     if (OP == OP_SUM) acc += x;
     else if (OP == OP_PROD) acc *= x;
     else if (OP == OP_LSE) {
@@ -105,7 +108,7 @@ __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float
         acc = (d > 0.0f) ? fmaf(acc, e, 1.0f) : acc + e;          // d is NaN only for -inf - -inf: e = 0
         mx = fmaxf(mx, x);
     } else {
-        const float wgt = (y == -INFINITY) ? 0.0f : fexp(nc - y);
+        const float wgt = !weighted ? 1.0f : ((y == -INFINITY) ? 0.0f : fexp(nc - y));
         acc = fmaf(x, wgt, acc);
     }
 }
@@ -182,7 +185,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
             const size_t off = (size_t)srow * (size_t)ld;
             load_vec<VEC>(x[i], srcc + off);
             if (OP == OP_SOFTMAX_BWD) {
-                load_vec<VEC>(y[i], src2c + off);
+                // an unweighted edge needs no parent value: re-read the row just requested (an L1 hit)
+                load_vec<VEC>(y[i], ((ids[i] & kWeighted) && ids[i] != kSkip ? src2c : srcc) + off);
                 const int orow = rws[i] < last_row ? rws[i] : last_row;
                 load_vec<VEC>(z[i], ownc + (size_t)orow * (size_t)ld);
             }
@@ -206,7 +210,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                 const float dead = OP == OP_PROD ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
                 const float xv = live ? x[i][v] : dead;
                 const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
-                accumulate<OP>(acc[v], mx[v], xv, yv, nc[v]);
+                accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], (ids[i] & kWeighted) != 0);
             }
             if (live && (ids[i] & kLast)) {
                 float o[VEC];
@@ -265,21 +269,27 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
         for (int j = beg; j < end; j += CH) {
             const int n = end - j;
             uint32_t id[CH];
+            bool wt[CH];
 #pragma unroll
-            for (int i = 0; i < CH; ++i) id[i] = a.idx[j + i] & kIdMask;      // padded array: always in bounds
+            for (int i = 0; i < CH; ++i) {                                    // padded array: always in bounds
+                const uint32_t raw = a.idx[j + i];
+                id[i] = raw & kIdMask;
+                wt[i] = (raw & kWeighted) != 0;
+            }
             float x[CH][VEC], y[CH][VEC];
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 if (i < n) {
                     load_vec<VEC>(x[i], a.src + (size_t)id[i] * a.ld + col);
-                    if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], a.src2 + (size_t)id[i] * a.ld + col);
+                    if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], (wt[i] ? a.src2 : a.src) + (size_t)id[i] * a.ld + col);
                 }
             }
 #pragma unroll
             for (int i = 0; i < CH; ++i)
                 if (i < n) {
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) accumulate<OP>(acc[v], mx[v], x[i][v], OP == OP_SOFTMAX_BWD ? y[i][v] : 0.0f, nc[v]);
+                    for (int v = 0; v < VEC; ++v)
+                        accumulate<OP>(acc[v], mx[v], x[i][v], OP == OP_SOFTMAX_BWD ? y[i][v] : 0.0f, nc[v], wt[i]);
                 }
         }
         float o[VEC];
@@ -491,6 +501,12 @@ __global__ void seed_kernel(const float* __restrict__ dout, const int32_t* __res
             for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)b * R + top_root[t]];
         g[(size_t)i * ld + b] = acc;
     }
+}
+
+// rows[r, b] = dout[b, r]: the adjoint seed as one row per root column
+__global__ void seed_rows_kernel(const float* __restrict__ dout, int B, int R, int ld, float* __restrict__ rows) {
+    const int r = blockIdx.x;
+    for (int b = threadIdx.x; b < ld; b += blockDim.x) rows[(size_t)r * ld + b] = b < B ? dout[(size_t)b * R + r] : 0.0f;
 }
 
 // dleaf[b, v] = G0[+v, b] + G0[-v, b] * d(negated weight)/d(weight); tile transposed through LDS.

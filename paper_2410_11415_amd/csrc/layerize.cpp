@@ -20,9 +20,12 @@ int32_t segment_len(int64_t k, const Options& opt) {
 }
 }  // namespace
 
-void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out) {
+void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out,
+                    const uint32_t* flags) {
     const int64_t e = ptr[n];
     out = PassPlan();
+    if (flags)
+        for (int64_t j = 0; j < e && !out.has_weighted; ++j) out.has_weighted = (flags[j] & kWeightedEdge) != 0;
     out.n_main = (int32_t)n;
     out.edges = e;
     const int32_t heavy = std::max(1, opt.heavy_fan);
@@ -49,7 +52,7 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
         out.ptr[(size_t)r] = w;
         int64_t k = ptr[r + 1] - ptr[r];
         if (k <= heavy) {
-            for (int64_t j = ptr[r]; j < ptr[r + 1]; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j];
+            for (int64_t j = ptr[r]; j < ptr[r + 1]; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j] | (flags ? flags[j] : 0u);
             if (k > 0) out.idx[(size_t)w - 1] |= kLastEdge;
         } else {
             out.idx[(size_t)w++] = kSkipRow;
@@ -105,7 +108,7 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
     std::vector<int32_t> fill(out.comb_ptr.begin(), out.comb_ptr.end() - 1);
     for (size_t sidx = 0; sidx < segs.size(); ++sidx) {
         const Seg& sg = segs[sidx];
-        for (int64_t j = sg.begin; j < sg.begin + sg.len; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j];
+        for (int64_t j = sg.begin; j < sg.begin + sg.len; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j] | (flags ? flags[j] : 0u);
         out.idx[(size_t)w - 1] |= kLastEdge;
         out.seg_owner[sidx] = sg.owner;
         out.ptr[(size_t)n + sidx + 1] = w;
@@ -249,17 +252,22 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
 
     // ---------------------------------------------------------------- unary chains (Section 3.1; one per (child, layer))
     // need[c] = highest layer at which a stand-in for c is read: parent height - 1, or L for roots.
+    // With alias_chains no stand-ins are made: an edge reads the child's own row wherever it lives.
+    const bool alias = opt.alias_chains;
+    plan.alias = alias;
     std::vector<int32_t> need(h);
     for (int64_t p = 0; p < N; ++p) {
         if (!reach[(size_t)p]) continue;
         plan.dag_nodes++;
         plan.dag_edges += child_ptr[p + 1] - child_ptr[p];
+        if (alias) continue;
         for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) {
             int32_t c = child_idx[j];
             need[(size_t)c] = std::max(need[(size_t)c], h[(size_t)p] - 1);
         }
     }
-    for (int32_t r = 0; r < R; ++r) need[(size_t)roots[r]] = L;
+    if (!alias)
+        for (int32_t r = 0; r < R; ++r) need[(size_t)roots[r]] = L;
 
     std::vector<int64_t> count((size_t)L + 1, 0);
     std::vector<int64_t> pad_base((size_t)N + 1, 0);
@@ -300,10 +308,22 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                     plan.layers[(size_t)l].is_pad[(size_t)fill[(size_t)l]++] = 1;
                 }
     }
-    // position of the stand-in of node c at `level` (h[c] <= level <= need[c])
+    plan.row0.assign((size_t)L + 2, 0);
+    for (int32_t l = 0; l <= L; ++l) plan.row0[(size_t)l + 1] = plan.row0[(size_t)l] + count[(size_t)l];
+    if (plan.row0[(size_t)L + 1] + R >= (int64_t)1 << 30) { err = "klay_build: more than 2^30 rows"; return ST_INVAL; }
+    // position of the stand-in of node c at `level` (h[c] <= level <= need[c]); in alias mode the
+    // row of c itself in the whole activation buffer
     auto at = [&](int32_t c, int32_t level) -> int32_t {
+        if (alias) return (int32_t)(plan.row0[(size_t)h[(size_t)c]] + pos_real[(size_t)c]);
         return level == h[(size_t)c] ? pos_real[(size_t)c]
                                      : pos_pad[(size_t)(pad_base[(size_t)c] + level - h[(size_t)c] - 1)];
+    };
+    // ordering key of a child: its position in the layer below, or (alias mode) its relative
+    // position within its own layer scaled to the width of the layer below
+    auto child_key = [&](int32_t c, int32_t level) -> double {
+        if (!alias) return (double)at(c, level);
+        const int32_t hc = h[(size_t)c];
+        return (double)pos_real[(size_t)c] / (double)std::max<int64_t>(1, count[(size_t)hc]) * (double)count[(size_t)level];
     };
     auto set_at = [&](int32_t c, int32_t level, int32_t p) {
         if (level == h[(size_t)c]) pos_real[(size_t)c] = p;
@@ -347,10 +367,10 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             std::vector<double> key((size_t)lay.n);
             for (int64_t s = 0; s < lay.n; ++s) {
                 int32_t c = lay.origin[(size_t)s];
-                if (lay.is_pad[(size_t)s]) key[(size_t)s] = at(c, l - 1);
+                if (lay.is_pad[(size_t)s]) key[(size_t)s] = child_key(c, l - 1);
                 else {
                     double acc = 0;
-                    for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) acc += at(child_idx[j], l - 1);
+                    for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) acc += child_key(child_idx[j], l - 1);
                     key[(size_t)s] = acc / (double)(child_ptr[c + 1] - child_ptr[c]);
                 }
             }
@@ -387,9 +407,16 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         lay.row_ptr[(size_t)lay.n] = w;
         make_pass_plan(lay.n, lay.row_ptr.data(), lay.child.data(), popt, lay.fwd);
 
-        // by child (for the reverse sweep): rows = nodes of layer l-1, sources = parents in layer l
+        plan.num_edges += e;
+        plan.num_split_rows += lay.fwd.n_heavy;
+        plan.max_fwd_seg = std::max<int64_t>(plan.max_fwd_seg, lay.fwd.n_seg);
+        if (alias) continue;
+
+        // by child (for the reverse sweep): rows = nodes of layer l-1, sources = parents in layer l;
+        // an edge is weighted when its parent is an OR node with more than one child
         const int64_t nc = plan.layers[(size_t)l - 1].n;
         std::vector<int32_t> cptr((size_t)nc + 1, 0), cpar((size_t)e);
+        std::vector<uint32_t> cflag((size_t)e, 0u);
         for (int64_t j = 0; j < e; ++j) ++cptr[(size_t)lay.child[(size_t)j] + 1];
         for (int64_t i = 0; i < nc; ++i) {
             plan.max_fan_out = std::max<int64_t>(plan.max_fan_out, cptr[(size_t)i + 1]);
@@ -398,18 +425,61 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         {
             std::vector<int32_t> fill(cptr.begin(), cptr.end() - 1);
             for (int64_t p = 0; p < lay.n; ++p)
-                for (int32_t j = lay.row_ptr[(size_t)p]; j < lay.row_ptr[(size_t)p + 1]; ++j)
-                    cpar[(size_t)fill[(size_t)lay.child[(size_t)j]]++] = (int32_t)p;
+                for (int32_t j = lay.row_ptr[(size_t)p]; j < lay.row_ptr[(size_t)p + 1]; ++j) {
+                    const int32_t slot = fill[(size_t)lay.child[(size_t)j]]++;
+                    cpar[(size_t)slot] = (int32_t)p;
+                    if ((l & 1) == 0 && lay.row_ptr[(size_t)p + 1] - lay.row_ptr[(size_t)p] > 1) cflag[(size_t)slot] = kWeightedEdge;
+                }
         }
-        make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd);
+        make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd, cflag.data());
         if (lay.n <= kTailRowsCap && nc <= kTailRowsCap && e <= kTailEdgesCap) {
             lay.col_ptr.swap(cptr);
             lay.parent.swap(cpar);
         }
-        plan.num_split_rows += lay.fwd.n_heavy + lay.bwd.n_heavy;
-        plan.max_fwd_seg = std::max<int64_t>(plan.max_fwd_seg, lay.fwd.n_seg);
+        plan.num_split_rows += lay.bwd.n_heavy;
         plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, lay.bwd.n_seg);
-        plan.num_edges += e;
+    }
+    if (alias) {
+        // Reverse-sweep sources of every row of the activation buffer: its parents (rows of any
+        // higher layer) and, for a root, the adjoint rows that hold the transposed dout.
+        const int64_t NR = plan.row0[(size_t)L + 1];
+        std::vector<int32_t> gptr((size_t)NR + 1, 0);
+        for (int32_t l = 1; l <= L; ++l)
+            for (int32_t ch : plan.layers[(size_t)l].child) ++gptr[(size_t)ch + 1];
+        std::vector<int32_t> root_row((size_t)R);
+        for (int32_t r = 0; r < R; ++r) { root_row[(size_t)r] = at(roots[r], L); ++gptr[(size_t)root_row[(size_t)r] + 1]; }
+        for (int64_t i = 0; i < NR; ++i) {
+            plan.max_fan_out = std::max<int64_t>(plan.max_fan_out, gptr[(size_t)i + 1]);
+            if ((int64_t)gptr[(size_t)i] + gptr[(size_t)i + 1] >= INT32_MAX - 64) { err = "klay_build: more than 2^31 edges"; return ST_INVAL; }
+            gptr[(size_t)i + 1] += gptr[(size_t)i];
+        }
+        std::vector<int32_t> gsrc((size_t)gptr[(size_t)NR]);
+        std::vector<uint32_t> gflag((size_t)gptr[(size_t)NR], 0u);
+        {
+            std::vector<int32_t> fill(gptr.begin(), gptr.end() - 1);
+            for (int32_t l = 1; l <= L; ++l) {
+                const LayerPlan& lay = plan.layers[(size_t)l];
+                for (int64_t p = 0; p < lay.n; ++p) {
+                    const bool weighted = (l & 1) == 0 && lay.row_ptr[(size_t)p + 1] - lay.row_ptr[(size_t)p] > 1;
+                    for (int32_t j = lay.row_ptr[(size_t)p]; j < lay.row_ptr[(size_t)p + 1]; ++j) {
+                        const int32_t slot = fill[(size_t)lay.child[(size_t)j]]++;
+                        gsrc[(size_t)slot] = (int32_t)(plan.row0[(size_t)l] + p);
+                        if (weighted) gflag[(size_t)slot] = kWeightedEdge;
+                    }
+                }
+            }
+            for (int32_t r = 0; r < R; ++r) gsrc[(size_t)fill[(size_t)root_row[(size_t)r]]++] = (int32_t)(NR + r);
+        }
+        for (int32_t l = 0; l <= L; ++l) {
+            // rows of layer l: a CSR slice rebased to start at 0
+            const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;
+            std::vector<int32_t> lptr((size_t)n + 1);
+            for (int64_t i = 0; i <= n; ++i) lptr[(size_t)i] = gptr[(size_t)(a + i)] - gptr[(size_t)a];
+            PassPlan& dst = l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd;
+            make_pass_plan(n, lptr.data(), gsrc.data() + gptr[(size_t)a], popt, dst, gflag.data() + gptr[(size_t)a]);
+            plan.num_split_rows += dst.n_heavy;
+            plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, dst.n_seg);
+        }
     }
     for (int32_t l = 0; l <= L; ++l) {
         plan.num_nodes += plan.layers[(size_t)l].n;
@@ -418,7 +488,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
 
     // the narrow top: the longest suffix of layers that all kept their plain index vectors
     plan.tail_first = 0;
-    if (!opt.no_tail) {
+    if (!opt.no_tail && !alias) {
         int32_t t = L + 1;
         while (t - 1 >= 1 && !plan.layers[(size_t)t - 1].col_ptr.empty()) --t;
         if (t <= L) plan.tail_first = t;
@@ -443,7 +513,10 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     }
     plan.root_pos.resize((size_t)R);
     for (int32_t r = 0; r < R; ++r) plan.root_pos[(size_t)r] = at(roots[r], L);
-    {
+    if (alias) {
+        plan.top_ptr.assign(2, 0);
+        plan.top_root.assign(1, 0);
+    } else {
         const int64_t nt = plan.layers[(size_t)L].n;
         plan.top_ptr.assign((size_t)nt + 1, 0);
         plan.top_root.resize((size_t)R);

@@ -14,6 +14,7 @@ struct Options {
     int32_t heavy_fan = 128;    // rows with more sources than this are evaluated in split passes
     int32_t min_segment = 32;   // smallest segment of a split row, in edges
     bool no_tail = false;       // never use the persistent kernels for the narrow top layers
+    bool alias_chains = false;  // no unary chain nodes: edges index the rows of any lower layer
 };
 
 // Layers at the top of the circuit with at most this many nodes (and 4x as many edges) keep
@@ -25,10 +26,11 @@ constexpr int64_t kTailEdgesCap = 4 * kTailRowsCap;
 //   rows [0, n_main)                 write output row i; a split row holds the single entry kSkip
 //   rows [n_main, n_main + n_seg)    are segments of split rows, writing scratch row (i - n_main)
 //   combine: output row comb_row[h] reduces scratch rows comb_idx[comb_ptr[h] .. comb_ptr[h+1])
-// Index entries carry the source row in bits 0..30 and "last edge of its row" in bit 31.
+// Index entries carry the source row in bits 0..29, "last edge of its row" in bit 31 and, in the
+// reverse sweep, "weighted edge" in bit 30 (the parent is an OR node with more than one child).
 // tasks: runs of consecutive main rows with a bounded edge count, as (first row, first edge)
 // pairs with a closing (n_main, main edge count) pair: the unit of work of one wave.
-constexpr uint32_t kLastEdge = 0x80000000u, kSkipRow = 0xFFFFFFFFu;
+constexpr uint32_t kLastEdge = 0x80000000u, kWeightedEdge = 0x40000000u, kSkipRow = 0xFFFFFFFFu;
 constexpr int kIdxPad = 16;
 struct PassPlan {
     int32_t n_main = 0;
@@ -39,6 +41,7 @@ struct PassPlan {
     std::vector<uint32_t> idx;       // entries of all rows, zero padded by kIdxPad for chunked reads
     std::vector<int32_t> tasks;      // [2 * (n_tasks + 1)]
     int32_t n_tasks = 0;
+    bool has_weighted = false;       // some entry carries kWeightedEdge
     std::vector<int32_t> seg_owner;  // [n_seg] output row each segment belongs to
     std::vector<int32_t> comb_ptr;   // [n_heavy + 1]
     std::vector<uint32_t> comb_idx;  // [n_seg + kIdxPad] scratch rows per split row, zero padded
@@ -69,6 +72,13 @@ struct CircuitPlan {
     int64_t max_layer_nodes = 0, max_fan_in = 0, max_fan_out = 0, num_split_rows = 0;
     int64_t max_fwd_seg = 0, max_bwd_seg = 0;   // scratch rows needed by split passes
     int32_t tail_first = 0;              // layers tail_first..num_layers are tail candidates (0: none)
+    // alias mode (Options::alias_chains): child entries, root_pos and the reverse-sweep sources are
+    // rows of the whole activation buffer (row0[l] = first row of layer l); layers[l].bwd gathers
+    // the adjoints of layer l-1 from parents in any higher layer, top_bwd those of the top layer;
+    // adjoint rows num_nodes .. num_nodes + R - 1 hold the transposed dout (one per root column)
+    bool alias = false;
+    std::vector<int64_t> row0;
+    PassPlan top_bwd;
 };
 
 // Status codes mirror klay_status (0 ok, 1 invalid, 2 cycle, 3 no memory).
@@ -77,6 +87,8 @@ int layerize(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type, cons
              const int32_t* roots, const Options& opt, CircuitPlan& plan, std::string& err);
 
 // Split a CSR (n rows, ptr[n+1], idx) into main rows, segments and combine rows.
-void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out);
+// `flags` (optional, one per edge) is OR-ed into the entries.
+void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out,
+                    const uint32_t* flags = nullptr);
 
 }  // namespace klay

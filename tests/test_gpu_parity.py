@@ -301,3 +301,42 @@ def test_persistent_top_kernel_matches_per_layer_launches(klay, B):
     refr, _ = oracle_eval(c, as_inputs(p, False), REAL)
     assert_real_close(ar, refr, "tail real")
     k_tail.close(); k_flat.close()
+
+
+# ------------------------------------------------------------------ padding-free evaluation (alias_chains)
+@pytest.mark.parametrize("name,scale,B", [("tiny_ddnnf", 1.0, 4), ("layered_100k", 0.3, 128), ("layered_1m", 0.05, 1),
+                                          ("powerlaw_10m", 0.08, 64), ("layered_3m_fwd_bwd", 0.02, 256)])
+def test_alias_chains_mode_matches_the_oracle(klay, name, scale, B):
+    c, p, spec = make_config(name, seed=2, scale=scale, batch=B)
+    sem = tuple(REAL if s == "real" else LOG for s in spec["semirings"])      # real underflows fp32 on powerlaw
+    stats = check_both(klay, c, p, semirings=sem, what=name + " alias", alias_chains=True)
+    print(name, stats)
+
+
+def test_alias_chains_mode_on_odd_shapes(klay, golden):
+    for f, nv in (("fig1b_ddnnf.txt", 4), ("fig3_multiroot.txt", 5), ("appD_mnist_add.txt", 2)):
+        check_both(klay, golden(f), leaf_probs(1, 5, nv, ("uniform", 0.05, 0.95)), what=f + " alias", alias_chains=True)
+    b = CircuitBuilder(3)
+    x, y, z = b.lit(0), b.lit(1), b.lit(2)
+    o = b.or_(x, y)                       # OR directly over leaves: lifted to layer 2, layer 1 stays empty
+    a = b.and_(o, z)
+    c = b.finish([a, o, x, a, b.lit(2, False)])
+    check_both(klay, c, leaf_probs(2, 9, 3, ("uniform", 0.05, 0.95)), what="lifted alias", alias_chains=True)
+    c = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
+    check_both(klay, c, leaf_probs(5, 70, 64, ("beta", 0.5, 0.5)), what="split alias", alias_chains=True,
+               heavy_fan=4, min_segment=2)
+
+
+def test_alias_chains_full_size_sampled_columns(klay):
+    c, p, spec = make_config("layered_3m_fwd_bwd", seed=0)
+    B = p.shape[0]
+    w32 = as_inputs(p, True)
+    dout = np.ones((B, c.roots.shape[0]), dtype=np.float32)
+    k = build(klay, c, alias_chains=True)
+    info = k.info()
+    assert info["num_edges"] == info["dag_edges"] and info["num_pad_nodes"] == 0
+    got, gd = gpu_eval(k, w32, LOG, dout)
+    cols = np.array([0, B // 3, B // 2 + 1, B - 1])
+    ref, rd = oracle_eval(c, w32[cols], LOG, dout[cols], nthreads=4, or_levels=k.num_layers // 2)
+    print("alias full size: max|dlog| %.2e grad %.2e" % (assert_log_close(got[cols], ref), assert_grad_close(gd[cols], rd)))
+    k.close()

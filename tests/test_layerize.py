@@ -241,3 +241,25 @@ def test_full_size_headline_circuit_layerizes():
     assert info["num_nodes"] == info["dag_nodes"] + info["num_pad_nodes"]
     nodes, edges = k.layer_sizes()
     assert nodes[-1] == 64 and edges.sum() == info["num_edges"]
+
+
+def test_alias_mode_has_no_chain_nodes_and_indexes_the_whole_buffer(golden):
+    c = golden("fig1b_ddnnf.txt")
+    k = host(c, alias_chains=True)
+    info = k.info()
+    assert info["num_pad_nodes"] == 0 and info["num_nodes"] == info["dag_nodes"] == 15
+    assert info["num_edges"] == info["dag_edges"] == 16
+    nodes, edges = k.layer_sizes()
+    assert nodes.tolist() == [8, 2, 2, 2, 1] and edges.tolist() == [0, 4, 4, 5, 3]
+    row0 = np.concatenate([[0], np.cumsum(nodes)])
+    origin = np.concatenate([k.layer_nodes(l)[0] for l in range(5)])      # input node per buffer row
+    for l in range(1, 5):
+        row_ptr, child = k.layer_csr(l)
+        assert child.max() < row0[l]                                       # children live in lower layers
+        own, _ = k.layer_nodes(l)
+        for r in range(len(own)):
+            assert sorted(origin[child[row_ptr[r]:row_ptr[r + 1]]].tolist()) == sorted(c.children(own[r]).tolist())
+    big = layered_random(3, num_vars=24, depth=8, num_gates=400, fanin=("geom", 2.0), groups=2, num_roots=4)
+    kb = host(big, alias_chains=True)
+    ib = kb.info()
+    assert ib["num_pad_nodes"] == 0 and ib["num_edges"] == ib["dag_edges"] and ib["tail_first_layer"] == 0
