@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tail", action="store_true", help="one launch per layer also for the narrow top layers")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph (torch.cuda.graph) and time its replays")
     ap.add_argument("--alias-chains", action="store_true",
                     help="padding-free evaluation: no unary chain nodes, edges read the child's own row")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
@@ -137,6 +139,27 @@ def main():
         step()
     torch.cuda.synchronize()
 
+    eager_step = step
+    if args.graph:
+        # the library only enqueues kernels on the given stream (no allocation once the workspace
+        # exists, no host synchronisation), so a whole step can be captured and replayed
+        side = torch.cuda.Stream()
+        stream = side
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            eager_step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                eager_step()
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+
+        def step():
+            graph.replay()
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+
     ev = HipEvents()
     e0, e1 = ev.create(), ev.create()
     torch.cuda.synchronize()
@@ -152,6 +175,7 @@ def main():
     value = B * E * args.steps / wall
 
     # per-kernel-class durations: the same steps again with HIP events around every launch group
+    step = eager_step
     k.set_profiling(True)
     classes = {}
     prof_steps = max(1, min(args.steps, 5))
@@ -219,6 +243,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "semiring": "log" if semiring == pkg.KLAY_LOG else "real",
                    "pass": "forward+backward" if backward else "forward", "seed": args.seed,
+                   "launch": "hip graph replay" if args.graph else "eager",
                    "layerization": "alias_chains (no unary chain nodes)" if args.alias_chains else
                                    "unary chain nodes per (node, layer)",
                    "layers": info["num_layers"], "layered_nodes": N, "layered_edges": E,

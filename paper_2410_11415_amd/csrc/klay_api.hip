@@ -426,10 +426,11 @@ struct TailChoice {
     int nmax = 0;        // LDS rows per buffer
 };
 
+// Batch columns per workgroup: one column per workgroup until the batch needs more workgroups
+// than the chip has compute units; few columns mean few rows per thread and a short layer time.
 int tail_ct(int B) {
-    if (B >= 8) return 8;
     int ct = 1;
-    while (ct < B) ct *= 2;
+    while (ct < 8 && (B + ct - 1) / ct > 256) ct *= 2;
     return ct;
 }
 

@@ -273,24 +273,28 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
 #pragma unroll
             for (int i = 0; i < CH; ++i) {                                    // padded array: always in bounds
                 const uint32_t raw = a.idx[j + i];
-                id[i] = raw & kIdMask;
+                id[i] = raw == kSkip ? 0u : (raw & kIdMask);
                 wt[i] = (raw & kWeighted) != 0;
             }
+            // all gathers are issued unconditionally: entries past the row's end are valid entries of
+            // later rows (or zero padding); their data is ignored below
             float x[CH][VEC], y[CH][VEC];
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
-                if (i < n) {
-                    load_vec<VEC>(x[i], a.src + (size_t)id[i] * a.ld + col);
-                    if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], (wt[i] ? a.src2 : a.src) + (size_t)id[i] * a.ld + col);
-                }
+                load_vec<VEC>(x[i], a.src + (size_t)id[i] * a.ld + col);
+                if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], (wt[i] ? a.src2 : a.src) + (size_t)id[i] * a.ld + col);
             }
 #pragma unroll
-            for (int i = 0; i < CH; ++i)
-                if (i < n) {
+            for (int i = 0; i < CH; ++i) {
+                const bool live = i < n;
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v)
-                        accumulate<OP>(acc[v], mx[v], x[i][v], OP == OP_SOFTMAX_BWD ? y[i][v] : 0.0f, nc[v], wt[i]);
+                for (int v = 0; v < VEC; ++v) {
+                    const float dead = OP == OP_PROD ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
+                    const float xv = live ? x[i][v] : dead;
+                    const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
+                    accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], wt[i]);
                 }
+            }
         }
         float o[VEC];
 #pragma unroll
@@ -322,6 +326,7 @@ struct TailLayer {
 };
 
 constexpr int kTailThreads = 1024;
+constexpr int kTailStash = 20;          // index entries per thread: covers rows + 1 + edges <= 20480
 
 template <int OP, int CT>
 __device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib, const float* prev, float* cur,
@@ -332,8 +337,21 @@ __device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib,
     for (int r = threadIdx.x / CT; r < L.n; r += RS) {
         const int beg = ib[r], end = ib[r + 1];
         float acc = identity<OP>(), mx = -INFINITY;
-        for (int j = beg; j < end; ++j) {
-            const int ch = ib[L.n + 1 + j];
+        const int* kids = ib + L.n + 1;
+        int j = beg;
+        for (; j + 4 <= end; j += 4) {                 // four independent reads in flight
+            float x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ch = kids[j + u];
+                if (from_global) x[u] = active ? below[(size_t)ch * ld] : identity<OP>();
+                else x[u] = prev[ch * CT + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) accumulate<OP>(acc, mx, x[u], 0.0f, 0.0f);
+        }
+        for (; j < end; ++j) {
+            const int ch = kids[j];
             float x;
             if (from_global) x = active ? below[(size_t)ch * ld] : identity<OP>();
             else x = prev[ch * CT + c];
@@ -356,11 +374,34 @@ __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer*
     int* ib = reinterpret_cast<int*>(smem + (size_t)2 * nmax * CT);
     const int col = (int)blockIdx.x * CT + (int)(threadIdx.x % CT);
     const bool active = col < B;
+    // index vectors of the next layer travel to registers while the current layer is evaluated
+    int stash[kTailStash];
+    {
+        const TailLayer L0 = layers[0];
+        const int32_t* g = ibase + L0.fwd_off;
+#pragma unroll
+        for (int u = 0; u < kTailStash; ++u) {
+            const int i = threadIdx.x + u * kTailThreads;
+            stash[u] = i < L0.n + 1 + L0.e ? g[i] : 0;
+        }
+    }
     for (int t = 0; t < n_layers; ++t) {
         const TailLayer L = layers[t];
-        const int32_t* g = ibase + L.fwd_off;
-        for (int i = threadIdx.x; i < L.n + 1 + L.e; i += kTailThreads) ib[i] = g[i];
+#pragma unroll
+        for (int u = 0; u < kTailStash; ++u) {
+            const int i = threadIdx.x + u * kTailThreads;
+            if (i < L.n + 1 + L.e) ib[i] = stash[u];
+        }
         __syncthreads();
+        if (t + 1 < n_layers) {
+            const TailLayer Ln = layers[t + 1];
+            const int32_t* g = ibase + Ln.fwd_off;
+#pragma unroll
+            for (int u = 0; u < kTailStash; ++u) {
+                const int i = threadIdx.x + u * kTailThreads;
+                stash[u] = i < Ln.n + 1 + Ln.e ? g[i] : 0;
+            }
+        }
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
         const float* below = act + (size_t)L.row0_below * ld + col;
         float* out = act + (size_t)L.row0 * ld + col;
@@ -406,11 +447,33 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
             cur[i * CT + c] = acc;
         }
     }
+    int stash[kTailStash];
+    if (n_layers > 1) {
+        const TailLayer Lt = layers[n_layers - 1];
+        const int32_t* g = ibase + Lt.bwd_off;
+#pragma unroll
+        for (int u = 0; u < kTailStash; ++u) {
+            const int i = threadIdx.x + u * kTailThreads;
+            stash[u] = i < Lt.n_below + 1 + Lt.e ? g[i] : 0;
+        }
+    }
     for (int t = n_layers - 1; t >= 1; --t) {          // step t: adjoints of layer t -> layer t-1
         const TailLayer L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
-        const int32_t* g = ibase + L.bwd_off;
-        for (int i = threadIdx.x; i < L.n_below + 1 + L.e; i += kTailThreads) ib[i] = g[i];
+#pragma unroll
+        for (int u = 0; u < kTailStash; ++u) {
+            const int i = threadIdx.x + u * kTailThreads;
+            if (i < L.n_below + 1 + L.e) ib[i] = stash[u];
+        }
+        if (t > 1) {
+            const TailLayer Ln = layers[t - 1];
+            const int32_t* g = ibase + Ln.bwd_off;
+#pragma unroll
+            for (int u = 0; u < kTailStash; ++u) {
+                const int i = threadIdx.x + u * kTailThreads;
+                stash[u] = i < Ln.n_below + 1 + Ln.e ? g[i] : 0;
+            }
+        }
         if (!is_and)
             for (int i = threadIdx.x; i < L.n * CT; i += kTailThreads) {
                 const int cc = col0 + i % CT;

@@ -432,7 +432,10 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 }
         }
         make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd, cflag.data());
-        if (lay.n <= kTailRowsCap && nc <= kTailRowsCap && e <= kTailEdgesCap) {
+        int64_t layer_fan = 0;
+        for (int64_t i = 0; i < lay.n; ++i) layer_fan = std::max<int64_t>(layer_fan, lay.row_ptr[(size_t)i + 1] - lay.row_ptr[(size_t)i]);
+        for (int64_t i = 0; i < nc; ++i) layer_fan = std::max<int64_t>(layer_fan, cptr[(size_t)i + 1] - cptr[(size_t)i]);
+        if (lay.n <= kTailRowsCap && nc <= kTailRowsCap && e <= kTailEdgesCap && layer_fan <= kTailFanCap) {
             lay.col_ptr.swap(cptr);
             lay.parent.swap(cpar);
         }

@@ -20,7 +20,8 @@ struct Options {
 // Layers at the top of the circuit with at most this many nodes (and 4x as many edges) keep
 // plain by-parent and by-child index vectors for the persistent LDS kernels.
 constexpr int64_t kTailRowsCap = 4096;
-constexpr int64_t kTailEdgesCap = 4 * kTailRowsCap;
+constexpr int64_t kTailEdgesCap = 16000;              // rows + 1 + edges must stay <= 20480 (kernel stash)
+constexpr int64_t kTailFanCap = 64;                   // no row with more sources than this (one thread walks a row)
 
 // One gather-reduce pass set over a CSR whose rows are the outputs.
 //   rows [0, n_main)                 write output row i; a split row holds the single entry kSkip

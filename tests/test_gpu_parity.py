@@ -340,3 +340,38 @@ def test_alias_chains_full_size_sampled_columns(klay):
     ref, rd = oracle_eval(c, w32[cols], LOG, dout[cols], nthreads=4, or_levels=k.num_layers // 2)
     print("alias full size: max|dlog| %.2e grad %.2e" % (assert_log_close(got[cols], ref), assert_grad_close(gd[cols], rd)))
     k.close()
+
+
+def test_forward_backward_can_be_captured_in_a_hip_graph(klay):
+    """klay_forward / klay_backward only enqueue kernels; a captured step must replay to the eager
+    result several times, with eager work and synchronisation in between"""
+    import torch
+    c, p, _ = make_config("layered_100k", seed=6, scale=0.5, batch=96)
+    k = build(klay, c)
+    R, V = c.roots.shape[0], c.num_vars
+    w = torch.from_numpy(as_inputs(p, True)).cuda()
+    out = torch.empty((96, R), device="cuda")
+    dout = torch.ones((96, R), device="cuda")
+    dleaf = torch.empty((96, V), device="cuda")
+    k.forward(w, LOG, out=out)
+    k.backward(dout, dleaf=dleaf)
+    torch.cuda.synchronize()
+    ref_out, ref_grad = out.clone(), dleaf.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            k.forward(w, LOG, out=out, stream=side)
+            k.backward(dout, dleaf=dleaf, stream=side)
+    torch.cuda.synchronize()
+    for i in range(4):
+        out.fill_(float("nan")); dleaf.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_out) and torch.equal(dleaf, ref_grad), "replay %d differs" % i
+        # eager work between replays, on other inputs, must not disturb the next replay
+        w2 = (w * 1.5).contiguous()
+        k.forward(w2, LOG)
+        torch.cuda.synchronize()
+    k.close()
