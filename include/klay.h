@@ -52,7 +52,8 @@ typedef struct klay_options {
     int32_t alias_chains;    /* 1: insert no unary chain nodes; an edge that skips layers reads the
                                 child's own row (same values, fewer rows and edges; klay_layer_csr
                                 then returns rows of the whole activation buffer, layer 0 first)    */
-    int32_t reserved[3];
+    int32_t no_merge;        /* 1: do not identify structurally identical gates (Section 3.2)         */
+    int32_t reserved[2];
 } klay_options;
 
 typedef struct klay_info_t {
@@ -72,6 +73,7 @@ typedef struct klay_info_t {
     int64_t index_bytes;      /* device bytes held by index arrays                                 */
     int64_t tail_first_layer; /* first layer that may run in the persistent top-of-circuit kernel
                                  (0: none); the layers actually taken depend on the batch size       */
+    int64_t num_merged_nodes; /* input gates identified with a structurally identical gate          */
 } klay_info_t;
 
 /* Per-kernel-class timing of the most recent forward / backward call, filled only while
@@ -101,7 +103,9 @@ typedef struct klay_profile_t {
  *   out           receives the handle
  *
  * All arrays are borrowed for the duration of the call only.  Nodes not reachable from a root
- * are dropped.  Gates of the wrong parity for their height (an OR directly over leaves, an AND
+ * are dropped.  Leaves carrying the same literal and gates with the same type and the same
+ * children are identified bottom-up (Section 3.2, Eq. 3, Theorem 1; child lists are compared on
+ * a hash hit, so a collision never merges different gates); values are unchanged by it.  Gates of the wrong parity for their height (an OR directly over leaves, an AND
  * under an AND) are lifted one layer so that odd layers hold AND and even layers OR (Section 3.1).
  * Layer-skipping edges get one chain of unary nodes per (child, layer); all roots are extended to
  * the height of the tallest (Section 3.2).

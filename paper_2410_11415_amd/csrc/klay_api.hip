@@ -563,6 +563,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
         if (opts->min_segment > 0) o.min_segment = opts->min_segment;
         o.no_tail = opts->no_tail != 0;
         o.alias_chains = opts->alias_chains != 0;
+        o.no_merge = opts->no_merge != 0;
     }
     std::unique_ptr<klay_circuit> c;
     try {
@@ -638,6 +639,7 @@ klay_status klay_info(const klay_circuit* c, klay_info_t* info) {
     info->num_split_rows = p.num_split_rows;
     info->index_bytes = (int64_t)c->index_bytes;
     info->tail_first_layer = p.tail_first;
+    info->num_merged_nodes = p.num_merged;
     return KLAY_OK;
 }
 

@@ -5,6 +5,7 @@
 #include <climits>
 #include <cmath>
 #include <numeric>
+#include <unordered_map>
 
 namespace klay {
 
@@ -205,6 +206,8 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     // h = 0 for leaves, 1 + max over children otherwise; a gate whose parity disagrees with its
     // type (AND must sit on an odd layer, OR on an even one) is lifted by one layer.
     std::vector<int32_t> h((size_t)N, 0);
+    std::vector<int32_t> topo;                  // every node, children before parents
+    topo.reserve((size_t)N);
     {
         std::vector<int64_t> pending((size_t)N);
         std::vector<int32_t> ready;
@@ -218,6 +221,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             int32_t n = ready.back();
             ready.pop_back();
             ++done;
+            topo.push_back(n);
             if (node_type[n] == T_AND || node_type[n] == T_OR) {
                 int32_t m = 0;
                 for (int64_t j = child_ptr[n]; j < child_ptr[n + 1]; ++j) m = std::max(m, h[(size_t)child_idx[j]]);
@@ -230,6 +234,52 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 if (--pending[(size_t)par_idx[(size_t)j]] == 0) ready.push_back(par_idx[(size_t)j]);
         }
         if (done != N) { err = "klay_build: the node graph has a cycle"; return ST_CYCLE; }
+    }
+
+    // ---------------------------------------------------------------- identical sub-circuits (Section 3.2, Eq. 3, Theorem 1)
+    // Bottom-up, a gate is identified by its type and the multiset of its (already identified)
+    // children.  The hash is a permutation-invariant sum of mixed child ids; on a hash hit the child
+    // lists are compared, so a collision can never merge different gates.  Identical gates have
+    // identical heights, so the layers computed above stay valid.
+    if (!opt.no_merge) {
+        auto mix = [](uint64_t x) {
+            x += 0x9E3779B97F4A7C15ull;
+            x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+            x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+            return x ^ (x >> 31);
+        };
+        std::vector<int32_t> rep((size_t)N);
+        std::iota(rep.begin(), rep.end(), 0);
+        std::unordered_map<uint64_t, int32_t> head;
+        head.reserve((size_t)N);
+        std::vector<int32_t> next_same((size_t)N, -1);
+        for (int32_t n : topo) {
+            if (node_type[n] != T_AND && node_type[n] != T_OR) continue;
+            const int64_t a = child_ptr[n], b = child_ptr[n + 1];
+            for (int64_t j = a; j < b; ++j) cidx[(size_t)j] = rep[(size_t)cidx[(size_t)j]];
+            std::sort(cidx.begin() + a, cidx.begin() + b);
+            uint64_t hsh = mix((uint64_t)node_type[n] * 0x51ED27ull + (uint64_t)(b - a));
+            for (int64_t j = a; j < b; ++j) hsh += mix((uint64_t)cidx[(size_t)j]);
+            auto it = head.find(hsh);
+            int32_t found = -1;
+            if (it != head.end()) {
+                for (int32_t m = it->second; m >= 0; m = next_same[(size_t)m]) {
+                    const int64_t ma = child_ptr[m], mb = child_ptr[m + 1];
+                    if (node_type[m] == node_type[n] && mb - ma == b - a &&
+                        std::equal(cidx.begin() + a, cidx.begin() + b, cidx.begin() + ma)) { found = m; break; }
+                }
+            }
+            if (found >= 0) {
+                rep[(size_t)n] = found;
+                ++plan.num_merged;
+            } else if (it != head.end()) {
+                next_same[(size_t)n] = it->second;
+                it->second = n;
+            } else {
+                head.emplace(hsh, n);
+            }
+        }
+        for (int32_t r = 0; r < R; ++r) croots[(size_t)r] = rep[(size_t)croots[(size_t)r]];
     }
 
     // ---------------------------------------------------------------- reachability from the roots

@@ -15,6 +15,7 @@ struct Options {
     int32_t min_segment = 32;   // smallest segment of a split row, in edges
     bool no_tail = false;       // never use the persistent kernels for the narrow top layers
     bool alias_chains = false;  // no unary chain nodes: edges index the rows of any lower layer
+    bool no_merge = false;      // keep structurally identical gates apart
 };
 
 // Layers at the top of the circuit with at most this many nodes (and 4x as many edges) keep
@@ -71,6 +72,7 @@ struct CircuitPlan {
     std::vector<int32_t> top_ptr, top_root;  // top-layer node -> root columns that read it
     int64_t num_nodes = 0, num_edges = 0, dag_nodes = 0, dag_edges = 0, num_pad_nodes = 0;
     int64_t max_layer_nodes = 0, max_fan_in = 0, max_fan_out = 0, num_split_rows = 0;
+    int64_t num_merged = 0;              // input gates identified with an identical gate
     int64_t max_fwd_seg = 0, max_bwd_seg = 0;   // scratch rows needed by split passes
     int32_t tail_first = 0;              // layers tail_first..num_layers are tail candidates (0: none)
     // alias mode (Options::alias_chains): child entries, root_pos and the reverse-sweep sources are

@@ -106,7 +106,7 @@ def _canon_children(c, n):
 @pytest.mark.parametrize("no_reorder", [False, True])
 def test_structure_invariants_small_random(no_reorder):
     c = layered_random(3, num_vars=24, depth=8, num_gates=400, fanin=("geom", 2.0), groups=2, num_roots=4)
-    k = host(c, no_reorder=no_reorder)
+    k = host(c, no_reorder=no_reorder, no_merge=True)
     seen, dag_edges = check_structure(c, k)
     info = k.info()
     assert len(seen) == info["dag_nodes"]
@@ -119,7 +119,7 @@ def test_structure_invariants_small_random(no_reorder):
 
 def test_structure_invariants_tiny_ddnnf():
     c, _, _ = tiny_ddnnf(0)
-    check_structure(c, host(c))
+    check_structure(c, host(c, no_merge=True))
 
 
 def test_parity_rule_lifts_gates_of_the_wrong_parity():
@@ -234,10 +234,13 @@ def test_host_only_handle_refuses_evaluation():
 
 def test_full_size_headline_circuit_layerizes():
     c, _, _ = make_config("layered_3m_fwd_bwd", seed=0)
+    assert 2.9e6 < c.num_nodes <= 3.0e6 and 0.95e7 < c.num_edges < 1.05e7      # the input DAG as specified
     k = host(c)
     info = k.info()
     assert info["num_layers"] == 60
-    assert 2.9e6 < info["dag_nodes"] <= 3.0e6 and 0.95e7 < info["dag_edges"] < 1.05e7
+    # identical gates of the random input are identified (Section 3.2): fewer nodes, same values
+    assert info["num_merged_nodes"] > 0 and info["dag_nodes"] + info["num_merged_nodes"] <= c.num_nodes
+    assert 0.9e7 < info["num_edges"] < 1.1e7
     assert info["num_nodes"] == info["dag_nodes"] + info["num_pad_nodes"]
     nodes, edges = k.layer_sizes()
     assert nodes[-1] == 64 and edges.sum() == info["num_edges"]
@@ -263,3 +266,48 @@ def test_alias_mode_has_no_chain_nodes_and_indexes_the_whole_buffer(golden):
     kb = host(big, alias_chains=True)
     ib = kb.info()
     assert ib["num_pad_nodes"] == 0 and ib["num_edges"] == ib["dag_edges"] and ib["tail_first_layer"] == 0
+
+
+def test_identical_subcircuits_are_merged_fig3(golden):
+    """Section 3.2: the two circuits of Figure 3 given as separate copies (no shared nodes) merge into
+    the two-rooted circuit of Figure 3(b); without merging the copies stay apart."""
+    b = CircuitBuilder(5)
+    A, B_, C, D, E = range(5)
+
+    def fresh_lit(v, pos=True):           # a new node per use: nothing is shared in the input
+        b.types.append(LIT); b.lits.append((v + 1) if pos else -(v + 1)); b.kids.append([])
+        return len(b.types) - 1
+    # circuit 1: Figure 1(b)
+    n30 = b.and_(fresh_lit(C), fresh_lit(D))
+    n20 = b.or_(n30, fresh_lit(C, False))
+    n21 = b.or_(n30, fresh_lit(D, False))
+    n10 = b.and_(fresh_lit(B_, False), fresh_lit(A, False))
+    n11 = b.and_(fresh_lit(A, False), fresh_lit(B_), n20)
+    n12 = b.and_(n21, fresh_lit(A))
+    root0 = b.or_(n10, n11, n12)
+    # circuit 2: Figure 3(a), its own copy of the (c AND d), (.. OR -d), (.. AND a) chain, children reordered
+    m14 = b.and_(fresh_lit(D), fresh_lit(C))
+    m24 = b.or_(fresh_lit(D, False), m14)
+    m32 = b.and_(fresh_lit(A), m24)
+    m17 = b.and_(fresh_lit(A, False), fresh_lit(E))
+    root1 = b.or_(m17, m32)
+    c = b.finish([root0, root1])
+    ref = golden("fig3_multiroot.txt")
+    k = host(c)
+    nodes, edges = k.layer_sizes()
+    assert nodes.tolist() == ints(ref.meta["layer_nodes"]) and edges[1:].tolist() == ints(ref.meta["layer_edges"])
+    assert k.info()["num_merged_nodes"] == 3
+    k2 = host(c, no_merge=True)
+    assert k2.layer_sizes()[0].sum() > nodes.sum() and k2.info()["num_merged_nodes"] == 0
+
+
+def test_merging_keeps_multiplicity():
+    """OR(A, A') with A' a structural copy of A is A + A: the merged gate keeps both edges"""
+    b = CircuitBuilder(2)
+    a1 = b.and_(b.lit(0), b.lit(1))
+    a2 = b.and_(b.lit(1), b.lit(0))
+    c = b.finish([b.or_(a1, a2)])
+    k = host(c)
+    assert k.info()["num_merged_nodes"] == 1
+    row_ptr, child = k.layer_csr(2)
+    assert child.tolist() == [0, 0] and k.layer_sizes()[0].tolist() == [2, 1, 1]
