@@ -143,7 +143,9 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
  *   dleaf         device [B, V] fp32, receives sum_r dout[b,r] * d out[b,r] / d leaf_weights[b,v];
  *                 every entry is written (0 for variables the circuit does not use)
  * Uses B, the semiring and the activations of that forward call; the caller must not have run
- * another forward in between.  A literal whose adjoint is exactly 0 contributes 0 even where the
+ * another forward in between.  The first real-semiring call on a handle uploads extra index
+ * arrays and allocates a per-edge buffer (hipMalloc, which synchronises); later calls only
+ * enqueue.  The real semiring is not differentiated on handles built with alias_chains.  A literal whose adjoint is exactly 0 contributes 0 even where the
  * derivative of its weight is infinite (log-domain negated literal at p = 1).
  * Errors: KLAY_ESTATE if no forward was run, KLAY_EINVAL, KLAY_EHIP.
  */

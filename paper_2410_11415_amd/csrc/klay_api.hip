@@ -94,6 +94,14 @@ struct klay_circuit {
     const klay::TailLayer* d_tail = nullptr;   // descriptors of layers plan.tail_first .. L
     bool tail_lds_ok = false;                  // the large-LDS attribute was accepted for the tail kernels
     int32_t last_tail_first = 0;               // first layer the last forward ran in the tail kernel (0: none)
+    // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
+    // vectors and a by-child pass whose entries are edge positions, plus the per-edge buffer M
+    struct RealLayer { const int32_t* ptr = nullptr; const int32_t* child = nullptr; DevPass by_child; };
+    std::vector<RealLayer> real_layers;
+    int32_t* d_real_index = nullptr;
+    int64_t real_max_edges = 0, real_max_seg = 0;
+    float* real_buf = nullptr;                 // M [max e_l, ld] followed by scratch rows for split rows
+    size_t real_buf_bytes = 0;
     void* ws_own = nullptr;
     size_t ws_own_bytes = 0;
     void* ws_user = nullptr;
@@ -544,6 +552,83 @@ double tail_alg_bytes(const klay_circuit* c, int first, int B, bool backward) {
     return bytes;
 }
 
+
+// ---- real-semiring reverse sweep -----------------------------------------------------------------
+klay_status ensure_real_bwd(klay_circuit* c, int ld) {
+    const klay::CircuitPlan& p = c->plan;
+    const int L = p.num_layers;
+    if (c->real_layers.empty()) {
+        Packer pk;
+        struct Off { size_t ptr = 0, child = 0; PassOffsets pass{}; klay::PassPlan plan; };
+        std::vector<Off> offs((size_t)L + 1);
+        klay::Options opt;
+        for (int l = 1; l <= L; l += 2) {                       // AND layers
+            const klay::LayerPlan& lay = p.layers[(size_t)l];
+            Off& o = offs[(size_t)l];
+            o.ptr = pk.add(lay.row_ptr);
+            o.child = pk.add(lay.child);
+            // by child: rows = nodes of layer l-1, entries = positions of their edges in `child`
+            const int64_t nc = p.layers[(size_t)l - 1].n;
+            std::vector<int32_t> cptr((size_t)nc + 1, 0), cedge((size_t)lay.e);
+            for (int64_t j = 0; j < lay.e; ++j) ++cptr[(size_t)lay.child[(size_t)j] + 1];
+            for (int64_t i = 0; i < nc; ++i) cptr[(size_t)i + 1] += cptr[(size_t)i];
+            std::vector<int32_t> fill(cptr.begin(), cptr.end() - 1);
+            for (int64_t j = 0; j < lay.e; ++j) cedge[(size_t)fill[(size_t)lay.child[(size_t)j]]++] = (int32_t)j;
+            klay::make_pass_plan(nc, cptr.data(), cedge.data(), opt, o.plan);
+            o.pass = pack_pass(pk, o.plan);
+            c->real_max_edges = std::max<int64_t>(c->real_max_edges, lay.e);
+            c->real_max_seg = std::max<int64_t>(c->real_max_seg, o.plan.n_seg);
+        }
+        const size_t bytes = pk.buf.size() * sizeof(int32_t);
+        if (hipMalloc(reinterpret_cast<void**>(&c->d_real_index), bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(KLAY_ENOMEM, "klay_backward: hipMalloc of the real-semiring index arrays failed");
+        }
+        KLAY_HIP(hipMemcpy(c->d_real_index, pk.buf.data(), bytes, hipMemcpyHostToDevice));
+        c->real_layers.resize((size_t)L + 1);
+        for (int l = 1; l <= L; l += 2) {
+            klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
+            r.ptr = c->d_real_index + offs[(size_t)l].ptr;
+            r.child = c->d_real_index + offs[(size_t)l].child;
+            bind_pass(r.by_child, offs[(size_t)l].plan, offs[(size_t)l].pass, c->d_real_index);
+        }
+    }
+    const size_t need = (size_t)(c->real_max_edges + std::max<int64_t>(c->real_max_seg, 1) + 1) * ld * sizeof(float);
+    if (need > c->real_buf_bytes) {
+        if (c->real_buf) { KLAY_HIP(hipFree(c->real_buf)); c->real_buf = nullptr; c->real_buf_bytes = 0; }
+        if (hipMalloc(reinterpret_cast<void**>(&c->real_buf), need) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(KLAY_ENOMEM, "klay_backward: hipMalloc of the per-edge buffer failed");
+        }
+        c->real_buf_bytes = need;
+    }
+    return KLAY_OK;
+}
+
+void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* below, const float* gl, float* M,
+                       const Geometry& g, int B, hipStream_t s) {
+    const int rpw = 64 / g.w;
+    const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
+    dim3 grid((unsigned)blocks, (unsigned)g.tiles);
+#define KLAY_PE(VEC, W) \
+    hipLaunchKernelGGL((klay::prod_edge_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, M, n, B, g.ld)
+    if (g.w == 64) {
+        if (g.vec == 4) KLAY_PE(4, 64);
+        else if (g.vec == 2) KLAY_PE(2, 64);
+        else KLAY_PE(1, 64);
+    } else {
+        switch (g.w) {
+        case 32: KLAY_PE(1, 32); break;
+        case 16: KLAY_PE(1, 16); break;
+        case 8: KLAY_PE(1, 8); break;
+        case 4: KLAY_PE(1, 4); break;
+        case 2: KLAY_PE(1, 2); break;
+        default: KLAY_PE(1, 1); break;
+        }
+    }
+#undef KLAY_PE
+}
+
 }  // namespace
 
 extern "C" {
@@ -616,6 +701,8 @@ void klay_destroy(klay_circuit* c) {
         release_events(c);
         if (c->d_index) (void)hipFree(c->d_index);
         if (c->ws_own) (void)hipFree(c->ws_own);
+        if (c->d_real_index) (void)hipFree(c->d_real_index);
+        if (c->real_buf) (void)hipFree(c->real_buf);
     }
     delete c;
 }
@@ -797,8 +884,9 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward: host-only handle");
     if (!c->have_fwd) return fail(KLAY_ESTATE, "klay_backward: no forward pass to differentiate");
-    if (c->last_semiring != KLAY_LOG)
-        return fail(KLAY_EINVAL, "klay_backward: only the log semiring is differentiated by this build");
+    const bool real = c->last_semiring == KLAY_REAL;
+    if (real && c->plan.alias)
+        return fail(KLAY_EINVAL, "klay_backward: the real semiring is not differentiated in alias_chains mode");
     if (!c->last_ws_has_bwd) return fail(KLAY_ENOMEM, "klay_backward: caller workspace has no room for adjoints");
     KLAY_HIP(hipSetDevice(c->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -816,6 +904,43 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     float* gnext = ws + lay.g1;
     const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
     Profiler prof(c, &c->ev_bwd, s);
+
+    if (real) {
+        // Real semiring: sum layers pass adjoints through; product layers go through the per-edge
+        // buffer M (adjoint times the product of the other children), summed by child.
+        klay_status rs = ensure_real_bwd(c, g.ld);
+        if (rs != KLAY_OK) return rs;
+        float* M = c->real_buf;
+        float* rscratch = c->real_buf + (size_t)(c->real_max_edges + 1) * g.ld;
+        prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
+        hipLaunchKernelGGL(klay::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
+                           c->d_top_root, B, R, g.ld, gcur);
+        prof.end();
+        for (int l = L; l >= 1; --l) {
+            const DevLayer& d = c->dl[(size_t)l];
+            const DevLayer& below = c->dl[(size_t)l - 1];
+            if ((l & 1) == 0) {
+                prof.begin(KLAY_K_BWD_SUM, 4.0 * B * ((double)d.e + (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s);
+            } else {
+                prof.begin(KLAY_K_BWD_SOFTMAX, 4.0 * B * (4.0 * (double)d.e + (double)d.n + (double)below.n));
+                launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, M, g, B, s);
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, M, nullptr, nullptr, gnext,
+                             rscratch, g, B, s);
+            }
+            prof.end();
+            std::swap(gcur, gnext);
+        }
+        prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
+        if (V > 0) {
+            dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
+            hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B, V,
+                               g.ld, 0, dleaf);
+        }
+        prof.end();
+        KLAY_HIP(hipGetLastError());
+        return KLAY_OK;
+    }
 
     if (p.alias) {
         // One adjoint row per activation row; rows N .. N+R-1 hold dout transposed.  Layer by layer

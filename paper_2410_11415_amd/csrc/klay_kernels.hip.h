@@ -503,6 +503,53 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
 }
 
 // ---------------------------------------------------------------------------------------------
+// Reverse sweep of a product (AND) layer in the real semiring.  The adjoint of child j of parent r
+// is G[r] times the product of r's other children.  Per parent the kernel forms, per batch column,
+// the product q of the non-zero children and the number z of zero children, and writes per edge
+//   M[j] = G[r] * (x_j != 0 ? (z == 0 ? q / x_j : 0) : (z == 1 ? q : 0)),
+// which is exact also when children are zero (p = 0 or p = 1 leaves).  A by-child sum over M then
+// gives the adjoints of the layer below.  A lane group of W lanes owns one parent row.
+// ---------------------------------------------------------------------------------------------
+template <int VEC, int W>
+__global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restrict__ ptr,
+                                                        const int32_t* __restrict__ child,
+                                                        const float* __restrict__ below,
+                                                        const float* __restrict__ g, float* __restrict__ M, int n,
+                                                        int B, int ld) {
+    constexpr int RPW = 64 / W;
+    const int lane = threadIdx.x & 63;
+    const int col = ((int)blockIdx.y * W + (lane % W)) * VEC;
+    if (col >= B) return;
+    const int64_t row64 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / W;
+    if (row64 >= n) return;
+    const int row = (int)row64;
+    const int beg = ptr[row], end = ptr[row + 1];
+    float q[VEC], z[VEC], gr[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { q[v] = 1.0f; z[v] = 0.0f; }
+    for (int j = beg; j < end; ++j) {
+        float x[VEC];
+        load_vec<VEC>(x, below + (size_t)child[j] * ld + col);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            if (x[v] == 0.0f) z[v] += 1.0f;
+            else q[v] *= x[v];
+        }
+    }
+    load_vec<VEC>(gr, g + (size_t)row * ld + col);
+    for (int j = beg; j < end; ++j) {
+        float x[VEC], m[VEC];
+        load_vec<VEC>(x, below + (size_t)child[j] * ld + col);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const float others = x[v] != 0.0f ? (z[v] == 0.0f ? q[v] / x[v] : 0.0f) : (z[v] == 1.0f ? q[v] : 0.0f);
+            m[v] = gr[v] * others;
+        }
+        store_vec<VEC>(M + (size_t)j * ld + col, m);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Leaf layer: leaf_weights[B,V] (batch-outer) -> wT[V,ld] (kept for the backward pass) and the
 // literal rows of layer 0; the negated literal gets 1-p (REAL) or log(1-exp(x)) (LOG).
 // Tile = 32 variables x 64 batch columns through LDS.

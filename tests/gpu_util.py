@@ -5,11 +5,12 @@ import numpy as np
 LOG_ATOL = 1e-4      # |delta log| for the fp32 log semiring
 REAL_RTOL = 1e-5     # relative error for the fp32 real semiring
 REAL_FLOOR = 1.2e-38 # below fp32's normal range only absolute agreement is asked
-# Gradients: |delta| <= GRAD_TOL * max(1, |ref|) + rel * mass, where mass is the sum over all
+# Gradients (log semiring): |delta| <= GRAD_TOL * max(1, |ref|) + rel * mass, where mass is the sum over all
 # root-to-leaf paths of |contribution| (the oracle's path-mass sweep) and
 #   rel = 64 u + 4 u * or_levels * max|node value|,   u = 2^-24:
 # 64 unit roundoffs for the fp32 summations, and per OR level a softmax weight exp(N_c - N_r)
 # whose argument carries the storage rounding u |N| of both values plus that of the difference.
+# Real semiring: rel = (64 + 16 * or_levels) u, and the absolute part is REAL_RTOL * |ref| + fp32 floor.
 GRAD_TOL = 1e-4
 U32 = 2.0 ** -24
 
@@ -45,7 +46,12 @@ def oracle_eval(c, w32, semiring, dout=None, nthreads=8, or_levels=None):
             dleaf = oracle.backward(*c.arrays(), w64, semiring, d64, nthreads=nthreads)
             mass = oracle.backward(*c.arrays(), w64, semiring, d64, nthreads=nthreads, path_mass=True)
             levels = 64 if or_levels is None else or_levels
-            dleaf = GradRef(dleaf, mass, 64 * U32 + 4 * U32 * levels * maxabs)
+            if semiring == 1:
+                rel = 64 * U32 + 4 * U32 * levels * maxabs
+            else:
+                # real semiring: every level multiplies by a quotient of fp32 products (a few roundoffs each)
+                rel = (64 + 16 * levels) * U32
+            dleaf = GradRef(dleaf, mass, rel)
     return out, dleaf
 
 
@@ -89,7 +95,7 @@ def assert_real_close(got, ref, what=""):
     return float(worst)
 
 
-def assert_grad_close(got, ref, what=""):
+def assert_grad_close(got, ref, what="", real=False):
     got = np.asarray(got, dtype=np.float64)
     assert not np.isnan(got).any(), what + ": NaN in GPU gradient"
     mass = getattr(ref, "mass", None)
@@ -99,6 +105,8 @@ def assert_grad_close(got, ref, what=""):
     inf = np.isinf(ref)
     np.testing.assert_array_equal(got[inf], ref[inf])
     bound = GRAD_TOL * np.maximum(1.0, np.abs(ref[~inf])) + rel * mass[~inf]
+    if real:
+        bound = REAL_RTOL * np.abs(ref[~inf]) + REAL_FLOOR + rel * mass[~inf]
     err = np.abs(got[~inf] - ref[~inf]) / bound
     assert err.size == 0 or err.max() <= 1.0, "%s: gradient error is %.3g x the bound (max |ref| %.3g, max mass %.3g)" % (
         what, err.max(), np.abs(ref[~inf]).max(), mass[~inf].max())

@@ -33,7 +33,8 @@ def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", **kw):
     levels = k.num_layers // 2
     for s in semirings:
         w32 = as_inputs(p, s == LOG)
-        dout = rng.normal(size=(p.shape[0], c.roots.shape[0])).astype(np.float32) if (backward and s == LOG) else None
+        can_bwd = backward and (s == LOG or not kw.get("alias_chains"))
+        dout = rng.normal(size=(p.shape[0], c.roots.shape[0])).astype(np.float32) if can_bwd else None
         got, gd = gpu_eval(k, w32, s, dout)
         ref, rd = oracle_eval(c, w32, s, dout, or_levels=levels)
         if s == LOG:
@@ -42,6 +43,8 @@ def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", **kw):
                 stats["grad"] = assert_grad_close(gd, rd, what + " grad")
         else:
             stats["real"] = assert_real_close(got, ref, what + " real")
+            if dout is not None:
+                stats["real_grad"] = assert_grad_close(gd, rd, what + " real grad", real=True)
     k.close()
     return stats
 
@@ -259,11 +262,13 @@ def test_call_order_errors(klay):
     with pytest.raises(klay.KlayError) as e:
         klay.klay_backward(k._h, d.data_ptr(), g.data_ptr(), 0)
     assert e.value.status == 5
-    k.forward(torch.from_numpy(as_inputs(p, False)).cuda(), REAL)
-    with pytest.raises(klay.KlayError) as e:
-        klay.klay_backward(k._h, d.data_ptr(), g.data_ptr(), 0)
-    assert e.value.status == 1                       # real-semiring backward is not built yet
     k.close()
+    ka = build(klay, c, alias_chains=True)
+    ka.forward(torch.from_numpy(as_inputs(p, False)).cuda(), REAL)
+    with pytest.raises(klay.KlayError) as e:
+        klay.klay_backward(ka._h, d.data_ptr(), g.data_ptr(), 0)
+    assert e.value.status == 1                       # real semiring + alias_chains: not differentiated
+    ka.close()
 
 
 def test_profile_reports_kernel_classes(klay):
@@ -374,4 +379,21 @@ def test_forward_backward_can_be_captured_in_a_hip_graph(klay):
         w2 = (w * 1.5).contiguous()
         k.forward(w2, LOG)
         torch.cuda.synchronize()
+    k.close()
+
+
+def test_real_semiring_gradient_with_zero_children(klay):
+    """product layers with children that are exactly zero: the adjoint of the zero child is the
+    product of the others, of everyone else zero (two zeros: all zero)"""
+    b = CircuitBuilder(4)
+    x = [b.lit(v) for v in range(4)]
+    root = b.or_(b.and_(x[0], x[1], x[2]), b.and_(b.lit(0, False), x[3]), b.and_(x[1], x[3]))
+    c = b.finish([root, b.and_(x[0], x[1], x[2], x[3])])
+    p = np.array([[0.0, 0.5, 0.25, 0.8], [0.0, 0.0, 0.3, 0.6], [1.0, 0.2, 0.0, 0.0], [0.3, 0.6, 0.9, 0.1]])
+    k = build(klay, c)
+    dout = np.array([[1.0, 2.0]] * 4, dtype=np.float32)
+    got, gd = gpu_eval(k, as_inputs(p, False), REAL, dout)
+    ref, rd = oracle_eval(c, as_inputs(p, False), REAL, dout, or_levels=1)
+    assert_real_close(got, ref)
+    np.testing.assert_allclose(gd, np.asarray(rd), rtol=1e-5, atol=1e-7)
     k.close()
