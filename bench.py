@@ -28,8 +28,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # script (scaled by the copy probe: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), see
 # profiles/stream_kernels_layered_3m_fwd_bwd_hbm_traffic.md.  Keyed by (workload, batch, class).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 482.1e6,
-    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 219.4e6,
+    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 526.8e6,    # 435.5 MB fetched + 91.3 MB written
+    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 254.1e6,
+    ("layered_3m_fwd_bwd", 256, "fwd_sum"): 175.3e6,
 }
 
 
@@ -188,6 +189,12 @@ def main():
             for f in c:
                 c[f] += rec[f]
     k.set_profiling(False)
+    # every class below except "split" is one kernel (one template instance) launched once per layer
+    kernel_of = {"fwd_sum": "stream_kernel<OP_SUM>", "fwd_prod": "stream_kernel<OP_PROD>", "fwd_lse": "stream_kernel<OP_LSE>",
+                 "bwd_sum": "stream_kernel<OP_SUM>", "bwd_softmax": "stream_kernel<OP_SOFTMAX_BWD>",
+                 "split": "pass_kernel (segments and combine rows of split rows)", "tail_fwd": "tail_fwd_kernel",
+                 "tail_bwd": "tail_bwd_kernel", "leaf": "leaf_fwd_kernel", "bwd_leaf": "leaf_bwd_kernel",
+                 "root": "root_out_kernel", "seed": "seed_kernel", "prod_edges": "prod_edge_kernel"}
     dom = max(classes, key=lambda n: classes[n]["ms"])
     d = classes[dom]
     achieved = d["alg_bytes"] / (d["ms"] * 1e-3) / 1e9 if d["ms"] > 0 else 0.0
@@ -197,7 +204,7 @@ def main():
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((args.workload, B, dom)),
-        "kernel": dom, "kernel_avg_launch_us": round(d["ms"] * 1e3 / max(1, d["launches"]), 2),
+        "kernel": kernel_of.get(dom, dom) + " [" + dom + "]", "kernel_avg_launch_us": round(d["ms"] * 1e3 / max(1, d["launches"]), 2),
         "kernel_launches_per_step": d["launches"] // prof_steps,
         "kernel_alg_bytes_per_launch": round(d["alg_bytes"] / max(1, d["launches"])),
         "whole_step": {"alg_bytes": round(alg_bytes_step), "kernel_ms": round(kernel_ms_total, 3),

@@ -77,10 +77,13 @@ typedef struct klay_info_t {
 } klay_info_t;
 
 /* Per-kernel-class timing of the most recent forward / backward call, filled only while
- * profiling is enabled.  Durations come from HIP events recorded on the caller's stream. */
+ * profiling is enabled.  Durations come from HIP events recorded on the caller's stream around
+ * every single launch.  FWD_x / BWD_x are the main-row launches of a layer (one kernel each:
+ * the streaming kernel for B > 32), SPLIT the segment and combine launches of split rows,
+ * PROD_EDGES the per-edge products of the real-semiring reverse sweep. */
 enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
-       KLAY_K_TAIL_BWD, KLAY_K_COUNT };
+       KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_COUNT };
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];

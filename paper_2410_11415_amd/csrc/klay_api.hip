@@ -39,6 +39,7 @@ struct DevPass {
     int32_t n_main = 0, n_seg = 0, n_heavy = 0, n_tasks = 0;
     bool has_weighted = false;
     int64_t edges = 0;
+    int64_t main_entries = 0, seg_entries = 0;   // index entries of light main rows / of segments
 };
 
 struct DevLayer {
@@ -305,6 +306,8 @@ void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const 
     d.tasks = base + o.tasks;
     d.n_tasks = p.n_tasks;
     d.has_weighted = p.has_weighted;
+    d.main_entries = (int64_t)p.ptr[(size_t)p.n_main] - p.n_heavy;
+    d.seg_entries = (int64_t)p.ptr[(size_t)p.n_main + (size_t)p.n_seg] - p.ptr[(size_t)p.n_main];
     d.n_main = p.n_main;
     d.n_seg = p.n_seg;
     d.n_heavy = p.n_heavy;
@@ -382,10 +385,20 @@ klay_status upload(klay_circuit* c) {
     return KLAY_OK;
 }
 
-// One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.
-void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
-                  const float* src2, const float* own, float* dst, float* scratch, const Geometry& g,
-                  int B, hipStream_t s) {
+// Algorithmic bytes (no-reuse model) of a gather-reduce over `rows` output rows with `entries` index
+// entries: every entry gathers one row (two in the softmax adjoint), every output row is written once
+// (and, in the softmax adjoint, reads its own value row), plus the index entries themselves.
+double pass_bytes(int op, double entries, double rows, int B) {
+    const double per_entry = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
+    const double per_row = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
+    return 4.0 * B * (per_entry * entries + per_row * rows) + 4.0 * (entries + rows);
+}
+
+// One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.  The main
+// launch is timed under `cls`, the launches that serve split rows under KLAY_K_SPLIT.
+void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
+                  const float* own, float* dst, float* scratch, const Geometry& g, int B, hipStream_t s,
+                  Profiler& prof, int cls) {
     klay::PassArgs a{};
     a.ptr = dp.ptr;
     a.idx = dp.idx;
@@ -400,13 +413,23 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
     a.n_total = dp.n_main + dp.n_seg;
     a.B = B;
     a.ld = g.ld;
+    const double light_rows = (double)dp.n_main - dp.n_heavy;
     if (g.w == 64) {
+        prof.begin(cls, pass_bytes(op, (double)dp.main_entries, light_rows, B));
         launch_stream(op, dp, g, src, src2, own, dst, B, s);
-        a.row_begin = dp.n_main;                 // segments only
+        prof.end();
+        if (dp.n_seg > 0) {
+            a.row_begin = dp.n_main;             // segments only
+            prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B));
+            launch_pass(op, a, g, s);
+            prof.end();
+        }
     } else {
-        a.row_begin = 0;
+        a.row_begin = 0;                         // small batches: main rows and segments in one launch
+        prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B));
+        launch_pass(op, a, g, s);
+        prof.end();
     }
-    launch_pass(op, a, g, s);
     if (dp.n_heavy > 0) {
         klay::PassArgs cmb{};
         cmb.ptr = dp.comb_ptr;
@@ -420,10 +443,11 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src,
         cmb.n_total = dp.n_heavy;
         cmb.B = B;
         cmb.ld = g.ld;
+        prof.begin(KLAY_K_SPLIT, pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B));
         launch_pass(combine_op, cmb, g, s);
+        prof.end();
     }
 }
-
 
 // ---- persistent kernels for the narrow top layers --------------------------------------------
 constexpr int kTailLdsWords = 32768;       // 128 KB of the 160 KB LDS of a CU
@@ -849,11 +873,9 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
         const bool is_and = (l & 1) != 0;
         const int op = log_domain ? (is_and ? klay::OP_SUM : klay::OP_LSE) : (is_and ? klay::OP_PROD : klay::OP_SUM);
         const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM : (op == klay::OP_PROD ? KLAY_K_FWD_PROD : KLAY_K_FWD_LSE);
-        prof.begin(cls, 4.0 * B * ((double)d.e + (double)d.n) + 4.0 * ((double)d.e + (double)d.n));
         // alias mode: child entries are rows of the whole buffer, otherwise of the layer below
         const float* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
-        run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, scratch, g, B, s);
-        prof.end();
+        run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, scratch, g, B, s, prof, cls);
     }
 
     if (tail.first > 0) {
@@ -920,15 +942,15 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
             const DevLayer& d = c->dl[(size_t)l];
             const DevLayer& below = c->dl[(size_t)l - 1];
             if ((l & 1) == 0) {
-                prof.begin(KLAY_K_BWD_SUM, 4.0 * B * ((double)d.e + (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s);
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s, prof,
+                             KLAY_K_BWD_SUM);
             } else {
-                prof.begin(KLAY_K_BWD_SOFTMAX, 4.0 * B * (4.0 * (double)d.e + (double)d.n + (double)below.n));
+                prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n));
                 launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, M, g, B, s);
+                prof.end();
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, M, nullptr, nullptr, gnext,
-                             rscratch, g, B, s);
+                             rscratch, g, B, s, prof, KLAY_K_BWD_SUM);
             }
-            prof.end();
             std::swap(gcur, gnext);
         }
         prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
@@ -953,17 +975,12 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
         for (int l = L; l >= 0; --l) {
             const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
             const DevLayer& d = c->dl[(size_t)l];
-            const double rows = (double)d.n, e = (double)dp.edges;
-            if (dp.has_weighted) {
-                prof.begin(KLAY_K_BWD_SOFTMAX, 4.0 * B * (2.0 * e + 2.0 * rows) + 4.0 * (e + rows));
+            if (dp.has_weighted)
                 run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, act + (size_t)d.row0 * g.ld,
-                             G + (size_t)d.row0 * g.ld, scratch, g, B, s);
-            } else {
-                prof.begin(KLAY_K_BWD_SUM, 4.0 * B * (e + rows) + 4.0 * (e + rows));
+                             G + (size_t)d.row0 * g.ld, scratch, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
+            else
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, G + (size_t)d.row0 * g.ld, scratch,
-                             g, B, s);
-            }
-            prof.end();
+                             g, B, s, prof, KLAY_K_BWD_SUM);
         }
         prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
         if (V > 0) {
@@ -998,16 +1015,12 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
         const DevLayer& d = c->dl[(size_t)l];
         const DevLayer& below = c->dl[(size_t)l - 1];
         const bool is_and = (l & 1) != 0 || !d.bwd.has_weighted;   // no weighted edge: plain sums
-        if (is_and) {
-            prof.begin(KLAY_K_BWD_SUM, 4.0 * B * ((double)d.e + (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
-            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s);
-        } else {
-            prof.begin(KLAY_K_BWD_SOFTMAX,
-                       4.0 * B * (2.0 * (double)d.e + 2.0 * (double)below.n) + 4.0 * ((double)d.e + (double)below.n));
+        if (is_and)
+            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s, prof,
+                         KLAY_K_BWD_SUM);
+        else
             run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld,
-                         act + (size_t)below.row0 * g.ld, gnext, scratch, g, B, s);
-        }
-        prof.end();
+                         act + (size_t)below.row0 * g.ld, gnext, scratch, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
         std::swap(gcur, gnext);
     }
 
