@@ -34,9 +34,10 @@ klay_status fail(klay_status s, const std::string& msg) {
 constexpr size_t kAlignInts = 64;   // 256-byte alignment of every uploaded array
 
 struct DevPass {
-    const int32_t *ptr = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_row = nullptr, *tasks = nullptr;
+    const int32_t *ptr = nullptr, *seg_owner = nullptr, *comb_ptr = nullptr, *comb_row = nullptr, *tasks = nullptr,
+                  *seg_tasks = nullptr;
     const uint32_t *idx = nullptr, *comb_idx = nullptr;
-    int32_t n_main = 0, n_seg = 0, n_heavy = 0, n_tasks = 0;
+    int32_t n_main = 0, n_seg = 0, n_heavy = 0, n_tasks = 0, n_seg_tasks = 0;
     bool has_weighted = false;
     int64_t edges = 0;
     int64_t main_entries = 0, seg_entries = 0;   // index entries of light main rows / of segments
@@ -62,7 +63,7 @@ Geometry geometry(int B) {
         g.w = 1;
         while (g.w < B) g.w *= 2;
     }
-    g.ld = (B + g.vec - 1) / g.vec * g.vec;
+    g.ld = B > 32 ? (B + 3) / 4 * 4 : B;        // rows of wave-wide batches are float4-aligned
     const int tile = g.w * g.vec;
     g.tiles = (B + tile - 1) / tile;
     return g;
@@ -154,6 +155,17 @@ void launch_op(const klay::PassArgs& a, const Geometry& g, dim3 grid, hipStream_
         else launch_one<OP, 1, 64>(a, grid, s);
         return;
     }
+    if (g.vec == 4) {
+        switch (g.w) {
+        case 32: launch_one<OP, 4, 32>(a, grid, s); break;
+        case 16: launch_one<OP, 4, 16>(a, grid, s); break;
+        case 8: launch_one<OP, 4, 8>(a, grid, s); break;
+        case 4: launch_one<OP, 4, 4>(a, grid, s); break;
+        case 2: launch_one<OP, 4, 2>(a, grid, s); break;
+        default: launch_one<OP, 4, 1>(a, grid, s); break;
+        }
+        return;
+    }
     switch (g.w) {
     case 32: launch_one<OP, 1, 32>(a, grid, s); break;
     case 16: launch_one<OP, 1, 16>(a, grid, s); break;
@@ -185,31 +197,32 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
 }
 
 template <int OP>
-void launch_stream_op(const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
-                      float* dst, int B, hipStream_t s) {
-    int64_t blocks = ((int64_t)dp.n_tasks + 3) / 4;
+void launch_stream_op(const DevPass& dp, bool segments, const Geometry& g, const float* src, const float* src2,
+                      const float* own, float* dst, int B, hipStream_t s) {
+    const int n_tasks = segments ? dp.n_seg_tasks : dp.n_tasks;
+    int64_t blocks = ((int64_t)n_tasks + 3) / 4;
     blocks = (blocks + 7) / 8 * 8;
     // outputs larger than the L2s together (8 x 4 MB) are written with streaming stores
-    const int nt = (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
+    const int nt = !segments && (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
-    const int2* tasks = reinterpret_cast<const int2*>(dp.tasks);
+    const int2* tasks = reinterpret_cast<const int2*>(segments ? dp.seg_tasks : dp.tasks);
     if (g.vec == 4)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
     else if (g.vec == 2)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
     else
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
 }
 
 // Streaming kernel over the main rows of a pass (batch tiles of one wave: B > 32).
-void launch_stream(int op, const DevPass& dp, const Geometry& g, const float* src, const float* src2,
-                   const float* own, float* dst, int B, hipStream_t s) {
-    if (dp.n_tasks <= 0) return;
+void launch_stream(int op, const DevPass& dp, bool segments, const Geometry& g, const float* src,
+                   const float* src2, const float* own, float* dst, int B, hipStream_t s) {
+    if ((segments ? dp.n_seg_tasks : dp.n_tasks) <= 0) return;
     switch (op) {
-    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, g, src, src2, own, dst, B, s); break;
-    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, g, src, src2, own, dst, B, s); break;
-    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, g, src, src2, own, dst, B, s); break;
-    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, B, s); break;
+    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, segments, g, src, src2, own, dst, B, s); break;
+    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, segments, g, src, src2, own, dst, B, s); break;
+    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, segments, g, src, src2, own, dst, B, s); break;
+    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, segments, g, src, src2, own, dst, B, s); break;
     }
 }
 
@@ -282,7 +295,7 @@ struct Packer {
     }
 };
 
-struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_idx, comb_row, tasks; };
+struct PassOffsets { size_t ptr, idx, seg_owner, comb_ptr, comb_idx, comb_row, tasks, seg_tasks; };
 
 PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
     PassOffsets o;
@@ -293,6 +306,7 @@ PassOffsets pack_pass(Packer& pk, const klay::PassPlan& p) {
     o.comb_idx = pk.add(p.comb_idx);
     o.comb_row = pk.add(p.comb_row);
     o.tasks = pk.add(p.tasks);
+    o.seg_tasks = pk.add(p.seg_tasks);
     return o;
 }
 
@@ -305,6 +319,8 @@ void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const 
     d.comb_row = base + o.comb_row;
     d.tasks = base + o.tasks;
     d.n_tasks = p.n_tasks;
+    d.seg_tasks = base + o.seg_tasks;
+    d.n_seg_tasks = p.n_seg_tasks;
     d.has_weighted = p.has_weighted;
     d.main_entries = (int64_t)p.ptr[(size_t)p.n_main] - p.n_heavy;
     d.seg_entries = (int64_t)p.ptr[(size_t)p.n_main + (size_t)p.n_seg] - p.ptr[(size_t)p.n_main];
@@ -416,12 +432,19 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     const double light_rows = (double)dp.n_main - dp.n_heavy;
     if (g.w == 64) {
         prof.begin(cls, pass_bytes(op, (double)dp.main_entries, light_rows, B));
-        launch_stream(op, dp, g, src, src2, own, dst, B, s);
+        launch_stream(op, dp, false, g, src, src2, own, dst, B, s);
         prof.end();
         if (dp.n_seg > 0) {
-            a.row_begin = dp.n_main;             // segments only
             prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B));
-            launch_pass(op, a, g, s);
+            if (op != klay::OP_SOFTMAX_BWD && g.vec == 4) {
+                // segment row n_main + i writes scratch row i: same streaming kernel, shifted output base
+                // (the shifted pointer is only ever indexed with rows >= n_main).  Narrower batch tiles
+                // (one or two columns per lane) measured faster through the generic kernel.
+                launch_stream(op, dp, true, g, src, src2, own, scratch - (ptrdiff_t)dp.n_main * g.ld, B, s);
+            } else {
+                a.row_begin = dp.n_main;         // the softmax adjoint needs each segment's owner row
+                launch_pass(op, a, g, s);
+            }
             prof.end();
         }
     } else {
@@ -640,6 +663,15 @@ void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* bel
         if (g.vec == 4) KLAY_PE(4, 64);
         else if (g.vec == 2) KLAY_PE(2, 64);
         else KLAY_PE(1, 64);
+    } else if (g.vec == 4) {
+        switch (g.w) {
+        case 32: KLAY_PE(4, 32); break;
+        case 16: KLAY_PE(4, 16); break;
+        case 8: KLAY_PE(4, 8); break;
+        case 4: KLAY_PE(4, 4); break;
+        case 2: KLAY_PE(4, 2); break;
+        default: KLAY_PE(4, 1); break;
+        }
     } else {
         switch (g.w) {
         case 32: KLAY_PE(1, 32); break;

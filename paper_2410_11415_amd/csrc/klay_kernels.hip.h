@@ -284,6 +284,8 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
                 load_vec<VEC>(x[i], a.src + (size_t)id[i] * a.ld + col);
                 if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], (wt[i] ? a.src2 : a.src) + (size_t)id[i] * a.ld + col);
             }
+            // branch-free accumulation (a conditional use would let the compiler sink each load into
+            // its branch and serialise the gathers): a dead entry contributes the identity
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 const bool live = i < n;

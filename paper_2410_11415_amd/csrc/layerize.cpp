@@ -71,23 +71,25 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
         }
     }
     out.ptr[(size_t)n] = w;
-    // tasks over the main rows: close a task once it holds `target` entries (or 64 rows)
-    {
-        const int64_t main_entries = w;
-        const int64_t target = std::min<int64_t>(kTaskMax, std::max<int64_t>(kTaskMin, main_entries / kTaskDiv));
-        out.tasks.clear();
-        int64_t r = 0;
-        while (r < n) {
-            out.tasks.push_back((int32_t)r);
-            out.tasks.push_back(out.ptr[(size_t)r]);
+    // tasks: close a task once it holds `target` entries (or 64 rows)
+    auto cut_tasks = [&](int64_t r_begin, int64_t r_end, std::vector<int32_t>& tasks) -> int32_t {
+        const int64_t entries = out.ptr[(size_t)r_end] - out.ptr[(size_t)r_begin];
+        const int64_t target = std::min<int64_t>(kTaskMax, std::max<int64_t>(kTaskMin, entries / kTaskDiv));
+        tasks.clear();
+        int64_t r = r_begin;
+        while (r < r_end) {
+            tasks.push_back((int32_t)r);
+            tasks.push_back(out.ptr[(size_t)r]);
             int64_t r1 = r;
-            while (r1 < n && r1 - r < 64 && out.ptr[(size_t)r1] - out.ptr[(size_t)r] < target) ++r1;
+            while (r1 < r_end && r1 - r < 64 && out.ptr[(size_t)r1] - out.ptr[(size_t)r] < target) ++r1;
             r = r1;
         }
-        out.n_tasks = (int32_t)(out.tasks.size() / 2);
-        out.tasks.push_back((int32_t)n);
-        out.tasks.push_back(w);
-    }
+        const int32_t count = (int32_t)(tasks.size() / 2);
+        tasks.push_back((int32_t)r_end);
+        tasks.push_back(out.ptr[(size_t)r_end]);
+        return count;
+    };
+    out.n_tasks = cut_tasks(0, n, out.tasks);
     if (n_heavy == 0) return;
     // Segments of all split rows, ordered by the first source they read: segments that read the
     // same stretch of source rows then run next to each other (and on the same XCD), so the
@@ -126,6 +128,7 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
         out.ptr[(size_t)n + sidx + 1] = w;
         out.comb_idx[(size_t)fill[(size_t)owner_slot[(size_t)sg.owner]]++] = (uint32_t)sidx;
     }
+    out.n_seg_tasks = cut_tasks(n, n + n_seg, out.seg_tasks);
 }
 
 int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node_lit,

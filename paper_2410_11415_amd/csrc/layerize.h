@@ -43,6 +43,8 @@ struct PassPlan {
     std::vector<uint32_t> idx;       // entries of all rows, zero padded by kIdxPad for chunked reads
     std::vector<int32_t> tasks;      // [2 * (n_tasks + 1)]
     int32_t n_tasks = 0;
+    std::vector<int32_t> seg_tasks;  // same for the segment rows n_main .. n_main + n_seg - 1
+    int32_t n_seg_tasks = 0;
     bool has_weighted = false;       // some entry carries kWeightedEdge
     std::vector<int32_t> seg_owner;  // [n_seg] output row each segment belongs to
     std::vector<int32_t> comb_ptr;   // [n_heavy + 1]
