@@ -167,6 +167,12 @@ class Circuit:
         i = self.info()
         self.num_vars, self.num_roots, self.num_layers = i["num_vars"], i["num_roots"], i["num_layers"]
 
+    @classmethod
+    def from_nnf(cls, path: str, **kw):
+        """Build from a d-DNNF compiler's ``.nnf`` text file (see :mod:`.nnf`)."""
+        from .nnf import load_nnf
+        return cls(*load_nnf(path), **kw)
+
     # -- inspection
     def info(self) -> dict:
         s = klay_info_t()
