@@ -80,8 +80,8 @@ def main():
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters and gives the achievable copy rate)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (the batch shards with no exchange; "
-              "see DESIGN.md); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (batch columns are independent, so more GPUs "
+              "would each take a slice of the batch with no exchange); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
