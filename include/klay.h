@@ -46,8 +46,8 @@ enum { KLAY_LIT = 0, KLAY_AND = 1, KLAY_OR = 2, KLAY_TRUE = 3, KLAY_FALSE = 4 };
 /* Build-time options; zero-initialise and override.  0 means "library default". */
 typedef struct klay_options {
     int32_t no_reorder;      /* 1: keep nodes of a layer in input-id order (no locality sort)     */
-    int32_t heavy_fan;       /* rows with more sources than this are split (default 128)          */
-    int32_t min_segment;     /* smallest split segment, in edges (default 32)                     */
+    int32_t heavy_fan;       /* rows with more sources than this are split (default 48)           */
+    int32_t min_segment;     /* smallest split segment, in edges (default 24)                     */
     int32_t no_tail;         /* 1: one launch per layer also for the narrow top layers            */
     int32_t alias_chains;    /* 1: insert no unary chain nodes; an edge that skips layers reads the
                                 child's own row (same values, fewer rows and edges; klay_layer_csr

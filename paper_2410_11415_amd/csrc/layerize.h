@@ -11,8 +11,8 @@ namespace klay {
 
 struct Options {
     bool no_reorder = false;
-    int32_t heavy_fan = 128;    // rows with more sources than this are evaluated in split passes
-    int32_t min_segment = 32;   // smallest segment of a split row, in edges
+    int32_t heavy_fan = 48;     // rows with more sources than this are evaluated in split passes
+    int32_t min_segment = 24;   // smallest segment of a split row, in edges
     bool no_tail = false;       // never use the persistent kernels for the narrow top layers
     bool alias_chains = false;  // no unary chain nodes: edges index the rows of any lower layer
     bool no_merge = false;      // keep structurally identical gates apart
