@@ -397,3 +397,75 @@ def test_real_semiring_gradient_with_zero_children(klay):
     assert_real_close(got, ref)
     np.testing.assert_allclose(gd, np.asarray(rd), rtol=1e-5, atol=1e-7)
     k.close()
+
+
+# ------------------------------------------------------------------ shapes at the edges of the launch logic
+def test_deep_narrow_circuit_runs_mostly_in_the_persistent_kernel(klay):
+    """300 layers of at most a few dozen nodes: almost every layer is a tail layer"""
+    c = layered_random(11, num_vars=300, depth=300, num_gates=6000, fanin=("geom", 1.0), groups=1, num_roots=3)
+    k = build(klay, c)
+    assert k.num_layers == 300 and 0 < k.info()["tail_first_layer"] <= 2
+    k.close()
+    check_both(klay, c, leaf_probs(11, 33, 300, ("uniform", 0.2, 1.0)), semirings=(LOG,), what="deep")
+
+
+def test_one_very_wide_layer(klay):
+    """a single AND layer of 300k gates over two literals each, one OR root over all of them"""
+    V = 2000
+    rng = np.random.default_rng(0)
+    n = 300_000
+    a, b_ = rng.integers(0, V, size=n), rng.integers(0, V, size=n)
+    b_ = np.where(a == b_, (b_ + 1) % V, b_)
+    sa, sb = rng.integers(0, 2, size=n), rng.integers(0, 2, size=n)
+    node_type = np.concatenate([np.zeros(2 * V, np.uint8), np.full(n, 1, np.uint8), np.array([2], np.uint8)])
+    node_lit = np.zeros(2 * V + n + 1, np.int32)
+    node_lit[0:2 * V:2] = np.arange(1, V + 1)
+    node_lit[1:2 * V:2] = -np.arange(1, V + 1)
+    child_ptr = np.concatenate([np.zeros(2 * V + 1, np.int64), 2 * np.arange(1, n + 1), [2 * n + n]]).astype(np.int64)
+    child_idx = np.concatenate([np.stack([2 * a + sa, 2 * b_ + sb], 1).ravel(), 2 * V + np.arange(n)]).astype(np.int32)
+    from klay_synth import Circuit as Dag
+    c = Dag(V, node_type, node_lit, child_ptr, child_idx, np.array([2 * V + n], np.int32))
+    p = leaf_probs(1, 48, V, ("uniform", 0.0, 1.0))
+    w32 = as_inputs(p, True)
+    k = build(klay, c)
+    assert k.info()["max_layer_nodes"] > 100_000
+    d = np.ones((48, 1), np.float32)
+    got, gd = gpu_eval(k, w32, LOG, d)
+    ref, rd = oracle_eval(c, w32, LOG, d, or_levels=1)
+    assert_log_close(got, ref, "wide")
+    assert_grad_close(gd, rd, "wide grad")
+    k.close()
+
+
+def test_constant_only_circuit_and_unused_variables(klay):
+    b = CircuitBuilder(3)
+    t, f = b.true(), b.false()
+    c = b.finish([b.or_(t, f), b.and_(t, b.or_(f, t)), f])
+    p = leaf_probs(0, 7, 3)
+    k = build(klay, c)
+    got, gd = gpu_eval(k, as_inputs(p, True), LOG, np.ones((7, 3), np.float32))
+    ref, rd = oracle_eval(c, as_inputs(p, True), LOG, np.ones((7, 3), np.float32), or_levels=2)
+    assert_log_close(got, ref, "constants")
+    np.testing.assert_array_equal(gd, 0.0)           # no variable is used: every entry written as 0
+    k.close()
+
+
+def test_changing_batch_size_and_two_handles_on_one_stream(klay):
+    c1 = layered_random(21, num_vars=40, depth=8, num_gates=2000, fanin=("geom", 2.0), groups=2, num_roots=6)
+    c2 = layered_random(22, num_vars=40, depth=6, num_gates=900, fanin=("geom", 1.5), groups=1, num_roots=2)
+    k1, k2 = build(klay, c1), build(klay, c2)
+    for B in (300, 7, 64, 1, 129):
+        p = leaf_probs(B, B, 40)
+        w32 = as_inputs(p, True)
+        d1 = np.ones((B, 6), np.float32); d2 = np.ones((B, 2), np.float32)
+        # interleave the two handles: each keeps its own activations
+        import torch
+        w = torch.from_numpy(w32).cuda()
+        o1 = k1.forward(w, LOG); o2 = k2.forward(w, LOG)
+        g1 = k1.backward(torch.from_numpy(d1).cuda()); g2 = k2.backward(torch.from_numpy(d2).cuda())
+        torch.cuda.synchronize()
+        r1, rg1 = oracle_eval(c1, w32, LOG, d1, or_levels=4)
+        r2, rg2 = oracle_eval(c2, w32, LOG, d2, or_levels=3)
+        assert_log_close(o1.cpu().numpy(), r1); assert_log_close(o2.cpu().numpy(), r2)
+        assert_grad_close(g1.cpu().numpy(), rg1); assert_grad_close(g2.cpu().numpy(), rg2)
+    k1.close(); k2.close()
