@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--semiring", choices=("log", "real"), default=None, help="default: log where the workload lists it")
+    ap.add_argument("--backward", choices=("on", "off"), default=None, help="default: as the workload specifies")
     ap.add_argument("--no-tail", action="store_true", help="one launch per layer also for the narrow top layers")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph (torch.cuda.graph) and time its replays")
@@ -114,8 +116,11 @@ def main():
     circ, p, spec = make_config(args.workload, seed=args.seed, batch=args.batch)
     t_gen = time.perf_counter() - t0
     B = p.shape[0]
-    backward = bool(spec["backward"])
-    semiring = pkg.KLAY_LOG if "log" in spec["semirings"] else pkg.KLAY_REAL
+    backward = bool(spec["backward"]) if args.backward is None else args.backward == "on"
+    if args.semiring is not None:
+        semiring = pkg.KLAY_LOG if args.semiring == "log" else pkg.KLAY_REAL
+    else:
+        semiring = pkg.KLAY_LOG if "log" in spec["semirings"] else pkg.KLAY_REAL
     w32 = as_inputs(p, semiring == pkg.KLAY_LOG)
 
     t0 = time.perf_counter()
@@ -223,7 +228,8 @@ def main():
         ref = oracle.forward(*circ.arrays(), sample, oracle.LOG if semiring == pkg.KLAY_LOG else oracle.REAL,
                              nthreads=threads)
         if backward:
-            rgrad = oracle.backward(*circ.arrays(), sample, oracle.LOG, np.ones_like(ref), nthreads=threads)
+            rgrad = oracle.backward(*circ.arrays(), sample, oracle.LOG if semiring == pkg.KLAY_LOG else oracle.REAL,
+                                    np.ones_like(ref), nthreads=threads)
         t_cpu = time.perf_counter() - t0
         got = out[:cols].cpu().numpy()
         err = float(np.abs(got - ref).max())

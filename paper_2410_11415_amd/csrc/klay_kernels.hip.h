@@ -529,25 +529,51 @@ __global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restric
     float q[VEC], z[VEC], gr[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { q[v] = 1.0f; z[v] = 0.0f; }
-    for (int j = beg; j < end; ++j) {
-        float x[VEC];
-        load_vec<VEC>(x, below + (size_t)child[j] * ld + col);
+    load_vec<VEC>(gr, g + (size_t)row * ld + col);
+    constexpr int CH = 8;
+    float x[CH][VEC];
+    // first pass: 8 gathers in flight (entries past the row's end re-read its last child), product of
+    // the non-zero children and count of the zero ones
+    for (int j = beg; j < end; j += CH) {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            if (x[v] == 0.0f) z[v] += 1.0f;
-            else q[v] *= x[v];
+        for (int i = 0; i < CH; ++i) {
+            const int jj = j + i < end ? j + i : end - 1;
+            load_vec<VEC>(x[i], below + (size_t)child[jj] * ld + col);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool live = j + i < end;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const bool zero = x[i][v] == 0.0f;
+                z[v] += (live && zero) ? 1.0f : 0.0f;
+                q[v] *= (live && !zero) ? x[i][v] : 1.0f;
+            }
         }
     }
-    load_vec<VEC>(gr, g + (size_t)row * ld + col);
-    for (int j = beg; j < end; ++j) {
-        float x[VEC], m[VEC];
-        load_vec<VEC>(x, below + (size_t)child[j] * ld + col);
+    // second pass: per-edge products; a row of at most 8 children still has them in registers
+    const bool short_row = end - beg <= CH;
+    for (int j = beg; j < end; j += CH) {
+        if (!short_row) {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            const float others = x[v] != 0.0f ? (z[v] == 0.0f ? q[v] / x[v] : 0.0f) : (z[v] == 1.0f ? q[v] : 0.0f);
-            m[v] = gr[v] * others;
+            for (int i = 0; i < CH; ++i) {
+                const int jj = j + i < end ? j + i : end - 1;
+                load_vec<VEC>(x[i], below + (size_t)child[jj] * ld + col);
+            }
         }
-        store_vec<VEC>(M + (size_t)j * ld + col, m);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            if (j + i < end) {
+                float m[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const float xv = x[i][v];
+                    const float others = xv != 0.0f ? (z[v] == 0.0f ? q[v] / xv : 0.0f) : (z[v] == 1.0f ? q[v] : 0.0f);
+                    m[v] = gr[v] * others;
+                }
+                store_vec<VEC>(M + (size_t)(j + i) * ld + col, m);
+            }
+        }
     }
 }
 
