@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # script (scaled by the copy probe: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), see
 # profiles/stream_kernels_layered_3m_fwd_bwd_hbm_traffic.md.  Keyed by (workload, batch, class).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 508.9e6,    # 417.7 MB fetched + 91.2 MB written
-    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 254.0e6,        # 178.5 MB fetched + 75.4 MB written
+    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 489.7e6,    # 398.5 MB fetched + 91.2 MB written
+    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 237.3e6,        # 161.9 MB fetched + 75.4 MB written
 }
 
 
