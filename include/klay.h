@@ -186,6 +186,34 @@ klay_status klay_set_workspace(klay_circuit* c, void* dev_ptr, size_t bytes);
 klay_status klay_set_profiling(klay_circuit* c, int32_t enable);
 klay_status klay_get_profile(klay_circuit* c, klay_profile_t* profile);
 
+/*
+ * Incremental construction of a multi-rooted circuit (Section 3.2: circuits that share variables
+ * are merged into one layered circuit, one after the other, and share every node they have in
+ * common).  A builder collects circuits; klay_builder_finish layerizes all of them together, so
+ * identical sub-circuits of different circuits become one set of rows and all roots reach the
+ * height of the tallest circuit.
+ *
+ *   klay_builder_create   num_vars = V of the leaf-weight array all circuits are evaluated on.
+ *   klay_builder_add      same arrays as klay_build (node ids are local to this circuit; borrowed
+ *                         for the call).  first_root (may be NULL) receives the column of `out`
+ *                         that this circuit's roots[0] will occupy; its roots take consecutive
+ *                         columns, circuits in the order they were added.  Range errors are
+ *                         reported here (KLAY_EINVAL) and leave the builder unchanged; structural
+ *                         errors (cycle, empty gate, repeated child) are reported by finish.
+ *   klay_builder_finish   layerize what has been added so far (as klay_build_ex).  The builder
+ *                         stays valid: more circuits may be added and finish called again, each
+ *                         call returning an independent handle.  KLAY_ESTATE if nothing was added.
+ *   klay_builder_destroy  NULL is allowed.
+ */
+typedef struct klay_builder klay_builder;
+klay_status klay_builder_create(int32_t num_vars, klay_builder** out);
+klay_status klay_builder_add(klay_builder* b, int64_t num_nodes, const uint8_t* node_type,
+                             const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,
+                             int32_t num_roots, const int32_t* roots, int32_t* first_root);
+klay_status klay_builder_finish(const klay_builder* b, int32_t device, const klay_options* opts,
+                                klay_circuit** out);
+void klay_builder_destroy(klay_builder* b);
+
 /* Frees index arrays and library-owned workspace.  NULL is allowed. */
 void klay_destroy(klay_circuit* c);
 

@@ -23,7 +23,8 @@ KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd
 
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
-           "klay_set_profiling", "klay_get_profile", "klay_destroy", "klay_last_error")
+           "klay_set_profiling", "klay_get_profile", "klay_destroy", "klay_last_error", "klay_builder_create",
+           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy")
 
 
 class KlayError(RuntimeError):
@@ -92,6 +93,14 @@ def load():
     lib.klay_set_profiling.argtypes = [vp, i32]
     lib.klay_get_profile.restype = ctypes.c_int
     lib.klay_get_profile.argtypes = [vp, ctypes.POINTER(klay_profile_t)]
+    lib.klay_builder_create.restype = ctypes.c_int
+    lib.klay_builder_create.argtypes = [i32, ctypes.POINTER(vp)]
+    lib.klay_builder_add.restype = ctypes.c_int
+    lib.klay_builder_add.argtypes = [vp, i64, vp, vp, vp, vp, i32, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.klay_builder_finish.restype = ctypes.c_int
+    lib.klay_builder_finish.argtypes = [vp, i32, ctypes.POINTER(klay_options), ctypes.POINTER(vp)]
+    lib.klay_builder_destroy.restype = None
+    lib.klay_builder_destroy.argtypes = [vp]
     lib.klay_destroy.restype = None
     lib.klay_destroy.argtypes = [vp]
     lib.klay_last_error.restype = ctypes.c_char_p
@@ -140,6 +149,31 @@ def klay_destroy(handle):
     load().klay_destroy(handle)
 
 
+def klay_builder_create(num_vars):
+    b = ctypes.c_void_p()
+    _check(load().klay_builder_create(num_vars, ctypes.byref(b)))
+    return b
+
+
+def klay_builder_add(builder, num_nodes, node_type_ptr, node_lit_ptr, child_ptr_ptr, child_idx_ptr, num_roots,
+                     roots_ptr) -> int:
+    first = ctypes.c_int32(-1)
+    _check(load().klay_builder_add(builder, num_nodes, node_type_ptr, node_lit_ptr, child_ptr_ptr, child_idx_ptr,
+                                   num_roots, roots_ptr, ctypes.byref(first)))
+    return first.value
+
+
+def klay_builder_finish(builder, device, options: klay_options | None = None):
+    h = ctypes.c_void_p()
+    _check(load().klay_builder_finish(builder, device, ctypes.byref(options) if options is not None else None,
+                                      ctypes.byref(h)))
+    return h
+
+
+def klay_builder_destroy(builder):
+    load().klay_builder_destroy(builder)
+
+
 # ---- convenience wrapper --------------------------------------------------------------------
 class Circuit:
     """A built circuit.  ``device=-1`` gives a host-only handle (layerization inspection only)."""
@@ -162,10 +196,20 @@ class Circuit:
         self._h = klay_build(int(num_vars), node_type.shape[0], _np_ptr(node_type), _np_ptr(node_lit),
                              _np_ptr(child_ptr), _np_ptr(child_idx) if child_idx.size else None,
                              roots.shape[0], _np_ptr(roots), int(device), opts)
-        self.device = int(device)
+        self._adopt(int(device))
+
+    def _adopt(self, device):
+        self.device = device
         self._workspace = None
         i = self.info()
         self.num_vars, self.num_roots, self.num_layers = i["num_vars"], i["num_roots"], i["num_layers"]
+
+    @classmethod
+    def _from_handle(cls, handle, device):
+        c = cls.__new__(cls)
+        c._h = handle
+        c._adopt(int(device))
+        return c
 
     @classmethod
     def from_nnf(cls, path: str, **kw):
@@ -264,6 +308,46 @@ class Circuit:
         if self._h is not None:
             klay_destroy(self._h)
             self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Builder:
+    """Collects circuits over the same variables and builds them as one multi-rooted circuit."""
+
+    def __init__(self, num_vars):
+        self._b = None
+        self._b = klay_builder_create(int(num_vars))
+
+    def add(self, node_type, node_lit, child_ptr, child_idx, roots) -> int:
+        """Adds one circuit; returns the column of ``out`` its first root will occupy."""
+        node_type = np.ascontiguousarray(node_type, dtype=np.uint8)
+        node_lit = np.ascontiguousarray(node_lit, dtype=np.int32)
+        child_ptr = np.ascontiguousarray(child_ptr, dtype=np.int64)
+        child_idx = np.ascontiguousarray(child_idx, dtype=np.int32)
+        roots = np.ascontiguousarray(roots, dtype=np.int32)
+        if node_lit.shape[0] != node_type.shape[0] or child_ptr.shape[0] != node_type.shape[0] + 1:
+            raise ValueError("node_type, node_lit and child_ptr sizes disagree")
+        if child_idx.shape[0] != child_ptr[-1]:
+            raise ValueError("child_idx must have child_ptr[-1] entries")
+        return klay_builder_add(self._b, node_type.shape[0], _np_ptr(node_type), _np_ptr(node_lit),
+                                _np_ptr(child_ptr), _np_ptr(child_idx) if child_idx.size else None,
+                                roots.shape[0], _np_ptr(roots))
+
+    def finish(self, device=0, no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False,
+               alias_chains=False, no_merge=False) -> Circuit:
+        opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail), int(alias_chains),
+                            int(no_merge))
+        return Circuit._from_handle(klay_builder_finish(self._b, int(device), opts), device)
+
+    def close(self):
+        if self._b is not None:
+            klay_builder_destroy(self._b)
+            self._b = None
 
     def __del__(self):
         try:

@@ -687,6 +687,16 @@ void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* bel
 
 }  // namespace
 
+// Circuits collected for a joint layerization: node arrays concatenated, ids shifted.
+struct klay_builder {
+    int32_t num_vars = 0;
+    std::vector<uint8_t> type;
+    std::vector<int32_t> lit;
+    std::vector<int64_t> ptr{0};
+    std::vector<int32_t> idx;
+    std::vector<int32_t> roots;
+};
+
 extern "C" {
 
 const char* klay_last_error(void) { return g_err.c_str(); }
@@ -749,6 +759,68 @@ klay_status klay_build(int32_t num_vars, int64_t num_nodes, const uint8_t* node_
     return klay_build_ex(num_vars, num_nodes, node_type, node_lit, child_ptr, child_idx, num_roots, roots,
                          device, nullptr, out);
 }
+
+klay_status klay_builder_create(int32_t num_vars, klay_builder** out) {
+    if (!out) return fail(KLAY_EINVAL, "klay_builder_create: out is null");
+    *out = nullptr;
+    if (num_vars < 0) return fail(KLAY_EINVAL, "klay_builder_create: negative num_vars");
+    try {
+        *out = new klay_builder();
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_builder_create: out of host memory");
+    }
+    (*out)->num_vars = num_vars;
+    return KLAY_OK;
+}
+
+klay_status klay_builder_add(klay_builder* b, int64_t num_nodes, const uint8_t* node_type,
+                             const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,
+                             int32_t num_roots, const int32_t* roots, int32_t* first_root) {
+    if (!b) return fail(KLAY_EINVAL, "klay_builder_add: null builder");
+    if (num_nodes <= 0 || num_roots <= 0 || !node_type || !node_lit || !child_ptr || !roots)
+        return fail(KLAY_EINVAL, "klay_builder_add: empty circuit or null array");
+    const int64_t base = (int64_t)b->type.size();
+    if (base + num_nodes > (int64_t)INT32_MAX || (int64_t)b->roots.size() + num_roots > (int64_t)INT32_MAX)
+        return fail(KLAY_EINVAL, "klay_builder_add: more than 2^31-1 nodes or roots in total");
+    if (child_ptr[0] != 0) return fail(KLAY_EINVAL, "klay_builder_add: child_ptr[0] must be 0");
+    for (int64_t i = 0; i < num_nodes; ++i)
+        if (child_ptr[i + 1] < child_ptr[i]) return fail(KLAY_EINVAL, "klay_builder_add: child_ptr not monotone");
+    const int64_t ne = child_ptr[num_nodes];
+    if (ne > 0 && !child_idx) return fail(KLAY_EINVAL, "klay_builder_add: child_idx is null");
+    for (int64_t j = 0; j < ne; ++j)
+        if (child_idx[j] < 0 || child_idx[j] >= num_nodes)
+            return fail(KLAY_EINVAL, "klay_builder_add: child index out of range");
+    for (int32_t r = 0; r < num_roots; ++r)
+        if (roots[r] < 0 || roots[r] >= num_nodes) return fail(KLAY_EINVAL, "klay_builder_add: root out of range");
+    try {
+        const size_t e0 = b->idx.size();
+        b->type.reserve(b->type.size() + (size_t)num_nodes);
+        b->lit.reserve(b->lit.size() + (size_t)num_nodes);
+        b->ptr.reserve(b->ptr.size() + (size_t)num_nodes);
+        b->idx.reserve(e0 + (size_t)ne);
+        b->roots.reserve(b->roots.size() + (size_t)num_roots);
+        // nothing below can throw: capacity is reserved
+        b->type.insert(b->type.end(), node_type, node_type + num_nodes);
+        b->lit.insert(b->lit.end(), node_lit, node_lit + num_nodes);
+        for (int64_t i = 0; i < num_nodes; ++i) b->ptr.push_back((int64_t)e0 + child_ptr[i + 1]);
+        for (int64_t j = 0; j < ne; ++j) b->idx.push_back((int32_t)(base + child_idx[j]));
+        if (first_root) *first_root = (int32_t)b->roots.size();
+        for (int32_t r = 0; r < num_roots; ++r) b->roots.push_back((int32_t)(base + roots[r]));
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_builder_add: out of host memory");
+    }
+    return KLAY_OK;
+}
+
+klay_status klay_builder_finish(const klay_builder* b, int32_t device, const klay_options* opts,
+                                klay_circuit** out) {
+    if (!b) return fail(KLAY_EINVAL, "klay_builder_finish: null builder");
+    if (b->type.empty()) return fail(KLAY_ESTATE, "klay_builder_finish: no circuit was added");
+    return klay_build_ex(b->num_vars, (int64_t)b->type.size(), b->type.data(), b->lit.data(), b->ptr.data(),
+                         b->idx.data(), (int32_t)b->roots.size(), b->roots.data(), device, opts, out);
+}
+
+void klay_builder_destroy(klay_builder* b) { delete b; }
 
 void klay_destroy(klay_circuit* c) {
     if (!c) return;

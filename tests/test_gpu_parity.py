@@ -469,3 +469,36 @@ def test_changing_batch_size_and_two_handles_on_one_stream(klay):
         assert_log_close(o1.cpu().numpy(), r1); assert_log_close(o2.cpu().numpy(), r2)
         assert_grad_close(g1.cpu().numpy(), rg1); assert_grad_close(g2.cpu().numpy(), rg2)
     k1.close(); k2.close()
+
+
+# ------------------------------------------------------------------ circuits added one at a time (Section 3.2)
+def test_builder_circuits_share_nodes_and_keep_their_values(klay):
+    """three circuits over the same variables, one of them added twice, built as one multi-rooted
+    circuit: every root block equals the oracle on its own circuit, the gradient is the sum of the
+    circuits' gradients, and the repeated circuit adds no rows"""
+    from tests.gpu_util import GradRef
+    V, B = 96, 70
+    parts = [layered_random(seed=s, num_vars=V, depth=d, num_gates=g, fanin=("geom", 2.0), groups=1, num_roots=r)
+             for s, d, g, r in ((11, 8, 3000, 3), (12, 14, 5000, 1), (13, 5, 800, 2))]
+    bld = klay.Builder(V)
+    first = [bld.add(*c.arrays()[1:]) for c in parts]
+    assert first == [0, 3, 4]
+    k3 = bld.finish(device=0)
+    assert bld.add(*parts[0].arrays()[1:]) == 6
+    k = bld.finish(device=0)
+    assert k.info()["num_nodes"] == k3.info()["num_nodes"] and k.num_roots == 9
+    p = leaf_probs(5, B, V, ("uniform", 0.0, 1.0))
+    rng = np.random.default_rng(5)
+    dout = rng.normal(size=(B, 9)).astype(np.float32)
+    levels = k.num_layers // 2
+    for s in (LOG, REAL):
+        w32 = as_inputs(p, s == LOG)
+        got, gd = gpu_eval(k, w32, s, dout)
+        grad = np.zeros((B, V)); mass = np.zeros((B, V)); rel = 0.0
+        for c, col in zip(parts + [parts[0]], first + [6]):
+            r = c.roots.shape[0]
+            ref, rd = oracle_eval(c, w32, s, dout[:, col:col + r], or_levels=levels)
+            (assert_log_close if s == LOG else assert_real_close)(got[:, col:col + r], ref, "builder block %d" % col)
+            grad += np.asarray(rd); mass += rd.mass; rel = max(rel, rd.rel)
+        assert_grad_close(gd, GradRef(grad, mass, rel), "builder grad", real=(s == REAL))
+    k.close(); k3.close()

@@ -311,3 +311,73 @@ def test_merging_keeps_multiplicity():
     assert k.info()["num_merged_nodes"] == 1
     row_ptr, child = k.layer_csr(2)
     assert child.tolist() == [0, 0] and k.layer_sizes()[0].tolist() == [2, 1, 1]
+
+
+def _fig3_parts():
+    """the two circuits of Figure 3 as separate inputs over the variables a..e"""
+    A, B_, C, D, E = range(5)
+    b1 = CircuitBuilder(5)
+    n30 = b1.and_(b1.lit(C), b1.lit(D))
+    n20 = b1.or_(n30, b1.lit(C, False))
+    n21 = b1.or_(n30, b1.lit(D, False))
+    n10 = b1.and_(b1.lit(B_, False), b1.lit(A, False))
+    n11 = b1.and_(b1.lit(A, False), b1.lit(B_), n20)
+    n12 = b1.and_(n21, b1.lit(A))
+    c1 = b1.finish([b1.or_(n10, n11, n12)])
+    b2 = CircuitBuilder(5)
+    m14 = b2.and_(b2.lit(D), b2.lit(C))
+    m24 = b2.or_(b2.lit(D, False), m14)
+    m32 = b2.and_(b2.lit(A), m24)
+    m17 = b2.and_(b2.lit(A, False), b2.lit(E))
+    c2 = b2.finish([b2.or_(m17, m32)])
+    return c1, c2
+
+
+def test_builder_merges_circuits_added_one_at_a_time(golden):
+    """Section 3.2: adding Figure 1(b) and then Figure 3(a) to one builder gives the two-rooted layered
+    circuit of Figure 3(b); finishing after the first circuit alone gives Figure 2's layers."""
+    from paper_2410_11415_amd import Builder
+    c1, c2 = _fig3_parts()
+    ref = golden("fig3_multiroot.txt")
+    fig2 = golden("fig1b_ddnnf.txt")
+    bld = Builder(5)
+    with pytest.raises(KlayError) as e:
+        bld.finish(device=-1)
+    assert e.value.status == KLAY_ESTATE
+    assert bld.add(*c1.arrays()[1:]) == 0
+    k1 = bld.finish(device=-1)
+    assert k1.layer_sizes()[0].tolist() == ints(fig2.meta["layer_nodes"])
+    assert bld.add(*c2.arrays()[1:]) == 1
+    k = bld.finish(device=-1)
+    nodes, edges = k.layer_sizes()
+    assert nodes.tolist() == ints(ref.meta["layer_nodes"]) and edges[1:].tolist() == ints(ref.meta["layer_edges"])
+    assert k.info()["num_roots"] == 2
+    # the earlier handle is independent of what was added later
+    assert k1.layer_sizes()[0].tolist() == ints(fig2.meta["layer_nodes"]) and k1.info()["num_roots"] == 1
+    # the other order only swaps the output columns
+    bld2 = Builder(5)
+    bld2.add(*c2.arrays()[1:]); bld2.add(*c1.arrays()[1:])
+    assert bld2.finish(device=-1).layer_sizes()[0].tolist() == nodes.tolist()
+
+
+def test_builder_rejects_bad_input_and_stays_usable():
+    from paper_2410_11415_amd import Builder
+    c1, c2 = _fig3_parts()
+    bld = Builder(5)
+    bld.add(*c1.arrays()[1:])
+    _, t, l, p, i, r = c2.arrays()
+    bad = np.array(i).copy(); bad[0] = len(t)
+    with pytest.raises(KlayError) as e:
+        bld.add(t, l, p, bad, r)
+    assert e.value.status == KLAY_EINVAL
+    with pytest.raises(KlayError):
+        bld.add(t, l, p, i, [len(t)])
+    assert bld.add(t, l, p, i, r) == 1          # the failed calls left nothing behind
+    assert bld.finish(device=-1).info()["num_roots"] == 2
+    # a literal outside the builder's variables is found when the circuits are layerized
+    b3 = CircuitBuilder(6)
+    c3 = b3.finish([b3.and_(b3.lit(5), b3.lit(0))])
+    bld.add(*c3.arrays()[1:])
+    with pytest.raises(KlayError) as e:
+        bld.finish(device=-1)
+    assert e.value.status == KLAY_EINVAL
