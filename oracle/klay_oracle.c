@@ -10,14 +10,18 @@
  * the ORIGINAL linked-node DAG; nothing here knows about layers, unary padding
  * nodes, hashing or index vectors.  The log-domain variant follows Section 4 /
  * Appendix C (Alg. 4): AND adds, OR is a max-shifted logsumexp, with epsilon
- * read as 0 (an all -inf OR gives -inf).
+ * read as 0 (an all -inf OR gives -inf).  Section 4 closes with the remark that any
+ * pair of operations forming a semiring may be used; S_MAXLOG is the (max, +) semiring
+ * on log weights (AND adds, OR takes the maximum: the log weight of the heaviest proof
+ * tree, i.e. of the most probable model for a smooth d-DNNF), forward only.
  *
  * The backward pass is plain reverse-mode differentiation of exactly that
  * traversal (the paper delegates it to autograd, Section 6).
  *
  * Pins (see tests): closed forms of the paper's worked circuits, brute-force
  * weighted model counting, the tautology invariant, finite differences,
- * cross-semiring identities, scipy's logsumexp.  Parity unpinned: nothing.
+ * cross-semiring identities, scipy's logsumexp; for (max, +): enumeration of all
+ * proof trees and of all models of a smooth d-DNNF.  Parity unpinned: nothing.
  *
  * Circuit encoding (all host memory, read-only):
  *   node_type[n]  0 literal, 1 AND, 2 OR, 3 TRUE, 4 FALSE
@@ -36,7 +40,7 @@
 #endif
 
 enum { T_LIT = 0, T_AND = 1, T_OR = 2, T_TRUE = 3, T_FALSE = 4 };
-enum { S_REAL = 0, S_LOG = 1 };
+enum { S_REAL = 0, S_LOG = 1, S_MAXLOG = 2 };
 
 /* log(1 - exp(x)) for x <= 0, the usual two-branch form. */
 static double log1mexp(double x) {
@@ -101,7 +105,10 @@ static void eval_column(int semiring, const uint8_t* node_type, const int32_t* n
             break;
         default: /* T_OR */
             if (semiring == S_REAL) { v = 0.0; for (int64_t j = a; j < e; ++j) v += val[child_idx[j]]; }
-            else {
+            else if (semiring == S_MAXLOG) {
+                v = -INFINITY;
+                for (int64_t j = a; j < e; ++j) if (val[child_idx[j]] > v) v = val[child_idx[j]];
+            } else {
                 double m = -INFINITY;
                 for (int64_t j = a; j < e; ++j) if (val[child_idx[j]] > m) m = val[child_idx[j]];
                 if (m == -INFINITY) v = -INFINITY;
@@ -174,6 +181,7 @@ int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* nod
                          const int32_t* child_idx, int32_t num_roots, const int32_t* roots,
                          int32_t B, const double* w, int semiring, const double* dout,
                          double* dleaf, int nthreads, int abs_mode) {
+    if (semiring != S_REAL && semiring != S_LOG) return -3;   /* (max, +) is not differentiated */
     int32_t* order = (int32_t*)malloc(sizeof(int32_t) * ((size_t)num_nodes + 1));
     if (!order) return -2;
     int64_t n_order = klay_oracle_postorder(num_nodes, child_ptr, child_idx, num_roots, roots, order);

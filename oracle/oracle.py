@@ -19,6 +19,7 @@ import numpy as np
 
 REAL = 0
 LOG = 1
+MAXLOG = 2     # (max, +) on log weights, forward only
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "klay_oracle.c")
@@ -93,10 +94,12 @@ def forward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights,
             nthreads: int = 1, return_node_values: bool = False):
     """Root values ``out[B,R]`` (fp64) for leaf weights ``weights[B,V]``.
 
-    ``weights`` holds p (REAL) or log p (LOG); it is widened to fp64 as given.
+    ``weights`` holds p (REAL) or log p (LOG, MAXLOG); it is widened to fp64 as given.
     With ``return_node_values`` also returns ``vals[B,num_nodes]`` (NaN where unreachable).
     """
     lib = _load()
+    if int(semiring) not in (REAL, LOG, MAXLOG):
+        raise ValueError("unknown semiring")
     node_type, node_lit, child_ptr, child_idx, roots = _circuit_arrays(
         num_vars, node_type, node_lit, child_ptr, child_idx, roots)
     w = np.ascontiguousarray(weights, dtype=np.float64)
@@ -122,6 +125,8 @@ def backward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights
     With ``path_mass`` the sweep runs on absolute values and returns the sum over all root-to-leaf
     paths of |contribution| (>= |dleaf|): the scale of the cancellation in the gradient."""
     lib = _load()
+    if int(semiring) not in (REAL, LOG):
+        raise ValueError("only the real and the log semiring are differentiated")
     node_type, node_lit, child_ptr, child_idx, roots = _circuit_arrays(
         num_vars, node_type, node_lit, child_ptr, child_idx, roots)
     w = np.ascontiguousarray(weights, dtype=np.float64)

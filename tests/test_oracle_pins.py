@@ -314,3 +314,127 @@ def test_path_mass_bounds_the_gradient_and_equals_it_without_cancellation():
     pp = np.array([[0.3]])
     np.testing.assert_allclose(bwd(cc, pp, REAL, np.ones((1, 1))), 0.0, atol=1e-15)
     np.testing.assert_allclose(oracle.backward(*cc.arrays(), pp, REAL, np.ones((1, 1)), path_mass=True), 2.0, rtol=1e-14)
+
+
+# ----------------------------------------------------------------------------- (max, +) semiring
+MAXLOG = oracle.MAXLOG
+
+
+def proof_tree_values(c, w):
+    """log weights [n_trees, B] of all proof trees below each root, straight from the semiring
+    reading of Section 4: an OR offers its children as alternatives, an AND joins one tree of
+    every child, a tree's weight is the sum of its leaves' log weights."""
+    memo = {}
+
+    def trees(n):
+        if n in memo:
+            return memo[n]
+        t = c.node_type[n]
+        if t == LIT:
+            l = int(c.node_lit[n])
+            x = w[:, abs(l) - 1]
+            r = (x if l > 0 else np.log(-np.expm1(x)))[None, :]
+        elif t == TRUE:
+            r = np.zeros((1, w.shape[0]))
+        elif t == FALSE:
+            r = np.zeros((0, w.shape[0]))
+        elif t == AND:
+            r = np.zeros((1, w.shape[0]))
+            for k in c.children(n):
+                tk = trees(int(k))
+                r = (r[:, None, :] + tk[None, :, :]).reshape(-1, w.shape[0])
+        else:
+            r = np.concatenate([trees(int(k)) for k in c.children(n)], axis=0)
+        memo[n] = r
+        return r
+    return [trees(int(r)) for r in c.roots]
+
+
+@pytest.mark.parametrize("name", ["fig1b_ddnnf.txt", "fig3_multiroot.txt", "fig3a_single.txt", "appD_mnist_add.txt"])
+def test_maxlog_is_the_heaviest_proof_tree_worked_examples(golden, name):
+    c = golden(name)
+    w = np.log(leaf_probs(3, 6, c.num_vars, ("uniform", 0.05, 0.95)))
+    out = fwd(c, w, MAXLOG)
+    for r, t in enumerate(proof_tree_values(c, w)):
+        np.testing.assert_allclose(out[:, r], t.max(axis=0), rtol=0, atol=1e-13)
+    # and the log semiring sums the same trees
+    lg = fwd(c, w, LOG)
+    for r, t in enumerate(proof_tree_values(c, w)):
+        np.testing.assert_allclose(lg[:, r], logsumexp(t, axis=0), atol=1e-12)
+        assert np.all(out[:, r] <= lg[:, r] + 1e-12) and np.all(lg[:, r] <= out[:, r] + np.log(t.shape[0]) + 1e-12)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_maxlog_is_the_heaviest_proof_tree_random(seed):
+    c = layered_random(seed, num_vars=10, depth=4, num_gates=24, fanin=("geom", 1.0), groups=1, num_roots=2)
+    w = np.log(leaf_probs(seed, 5, 10, ("uniform", 0.05, 0.95)))
+    out = fwd(c, w, MAXLOG)
+    for r, t in enumerate(proof_tree_values(c, w)):
+        assert t.shape[0] >= 2
+        np.testing.assert_allclose(out[:, r], t.max(axis=0), rtol=0, atol=1e-13)
+
+
+def _smooth_obdd(nv, clauses):
+    """full Shannon expansion in variable order, branching on every variable (so every model sets
+    every variable: smooth, deterministic, decomposable); clauses: list of [(var, positive)]"""
+    b = CircuitBuilder(nv)
+    memo = {}
+
+    def go(i, rest):
+        if any(len(cl) == 0 for cl in rest):
+            return None
+        if i == nv:
+            return "true"
+        key = (i, rest)
+        if key in memo:
+            return memo[key]
+        branches = []
+        for val in (True, False):
+            nxt = []
+            for cl in rest:
+                if (i, val) in cl:
+                    continue
+                nxt.append(tuple(l for l in cl if l[0] != i))
+            sub = go(i + 1, tuple(sorted(set(nxt))))
+            if sub is None:
+                continue
+            lit = b.lit(i, val)
+            branches.append(lit if sub == "true" else b.and_(lit, sub))
+        node = None if not branches else (branches[0] if len(branches) == 1 else b.or_(*branches))
+        memo[key] = node
+        return node
+    root = go(0, tuple(sorted(set(tuple(sorted(cl)) for cl in clauses))))
+    assert root is not None and root != "true"
+    return b.finish([root])
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_maxlog_on_a_smooth_ddnnf_is_the_most_probable_model(seed):
+    rng = np.random.default_rng(100 + seed)
+    nv, ncl = 9, 14
+    clauses = [[(int(v), bool(rng.integers(2))) for v in rng.choice(nv, 3, replace=False)] for _ in range(ncl)]
+    c = _smooth_obdd(nv, clauses)
+    p = leaf_probs(seed, 7, nv, ("uniform", 0.05, 0.95))
+    bits = ((np.arange(2 ** nv)[:, None] >> np.arange(nv)[None, :]) & 1).astype(bool)
+    sat = np.ones(2 ** nv, dtype=bool)
+    for cl in clauses:
+        sat &= np.any([bits[:, v] == pos for v, pos in cl], axis=0)
+    assert 0 < sat.sum() < 2 ** nv
+    logw = np.where(bits[None, sat, :], np.log(p)[:, None, :], np.log1p(-p)[:, None, :]).sum(axis=2)   # [B, nsat]
+    np.testing.assert_allclose(fwd(c, np.log(p), MAXLOG)[:, 0], logw.max(axis=1), atol=1e-12)
+    np.testing.assert_allclose(fwd(c, np.log(p), LOG)[:, 0], logsumexp(logw, axis=1), atol=1e-12)
+
+
+def test_maxlog_single_gates_and_impossible_branches():
+    b = CircuitBuilder(6)
+    c = b.finish([b.or_(*[b.lit(v) for v in range(6)]), b.and_(*[b.lit(v, v % 2 == 0) for v in range(6)])])
+    p = leaf_probs(4, 5, 6, ("uniform", 0.05, 0.95))
+    out = fwd(c, np.log(p), MAXLOG)
+    np.testing.assert_allclose(out[:, 0], np.log(p).max(axis=1), atol=0)
+    np.testing.assert_allclose(out[:, 1], np.where(np.arange(6) % 2 == 0, np.log(p), np.log1p(-p)).sum(axis=1), atol=1e-13)
+    p[:, :] = 0.0
+    with np.errstate(divide="ignore"):
+        out = fwd(c, np.log(p), MAXLOG)
+    assert np.all(out == -np.inf)
+    with pytest.raises(ValueError):
+        bwd(c, np.log(np.full((1, 6), 0.5)), MAXLOG, np.ones((1, 2)))
