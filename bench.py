@@ -68,7 +68,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--semiring", choices=("log", "real"), default=None, help="default: log where the workload lists it")
+    ap.add_argument("--semiring", choices=("log", "real", "maxlog"), default=None,
+                    help="default: log where the workload lists it; maxlog = (max, +), forward only")
     ap.add_argument("--backward", choices=("on", "off"), default=None, help="default: as the workload specifies")
     ap.add_argument("--no-tail", action="store_true", help="one launch per layer also for the narrow top layers")
     ap.add_argument("--graph", action="store_true",
@@ -118,10 +119,13 @@ def main():
     B = p.shape[0]
     backward = bool(spec["backward"]) if args.backward is None else args.backward == "on"
     if args.semiring is not None:
-        semiring = pkg.KLAY_LOG if args.semiring == "log" else pkg.KLAY_REAL
+        semiring = {"log": pkg.KLAY_LOG, "real": pkg.KLAY_REAL, "maxlog": pkg.KLAY_MAXLOG}[args.semiring]
     else:
         semiring = pkg.KLAY_LOG if "log" in spec["semirings"] else pkg.KLAY_REAL
-    w32 = as_inputs(p, semiring == pkg.KLAY_LOG)
+    if semiring == pkg.KLAY_MAXLOG:
+        backward = False
+    semiring_name = {pkg.KLAY_LOG: "log", pkg.KLAY_REAL: "real", pkg.KLAY_MAXLOG: "maxlog"}[semiring]
+    w32 = as_inputs(p, semiring != pkg.KLAY_REAL)
 
     t0 = time.perf_counter()
     k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, alias_chains=args.alias_chains)
@@ -195,6 +199,7 @@ def main():
     k.set_profiling(False)
     # every class below except "split" is one kernel (one template instance) launched once per layer
     kernel_of = {"fwd_sum": "stream_kernel<OP_SUM>", "fwd_prod": "stream_kernel<OP_PROD>", "fwd_lse": "stream_kernel<OP_LSE>",
+                 "fwd_max": "stream_kernel<OP_MAX>",
                  "bwd_sum": "stream_kernel<OP_SUM>", "bwd_softmax": "stream_kernel<OP_SOFTMAX_BWD>",
                  "split": "pass_kernel (segments and combine rows of split rows)", "tail_fwd": "tail_fwd_kernel",
                  "tail_bwd": "tail_bwd_kernel", "leaf": "leaf_fwd_kernel", "bwd_leaf": "leaf_bwd_kernel",
@@ -224,11 +229,12 @@ def main():
         cols = args.cpu_columns or (2 * threads if backward else 4 * threads)
         cols = min(cols, B)
         sample = np.ascontiguousarray(w32[:cols]).astype(np.float64)
+        oracle_semiring = {pkg.KLAY_LOG: oracle.LOG, pkg.KLAY_REAL: oracle.REAL, pkg.KLAY_MAXLOG: oracle.MAXLOG}[semiring]
         t0 = time.perf_counter()
-        ref = oracle.forward(*circ.arrays(), sample, oracle.LOG if semiring == pkg.KLAY_LOG else oracle.REAL,
+        ref = oracle.forward(*circ.arrays(), sample, oracle_semiring,
                              nthreads=threads)
         if backward:
-            rgrad = oracle.backward(*circ.arrays(), sample, oracle.LOG if semiring == pkg.KLAY_LOG else oracle.REAL,
+            rgrad = oracle.backward(*circ.arrays(), sample, oracle_semiring,
                                     np.ones_like(ref), nthreads=threads)
         t_cpu = time.perf_counter() - t0
         got = out[:cols].cpu().numpy()
@@ -253,7 +259,7 @@ def main():
         "ms_per_step": ms_per_step, "ms_per_step_hip_events": ms_events / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": B, "semiring": "log" if semiring == pkg.KLAY_LOG else "real",
+        "config": {"workload": args.workload, "batch": B, "semiring": semiring_name,
                    "pass": "forward+backward" if backward else "forward", "seed": args.seed,
                    "launch": "hip graph replay" if args.graph else "eager",
                    "layerization": "alias_chains (no unary chain nodes)" if args.alias_chains else

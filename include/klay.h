@@ -37,8 +37,11 @@ typedef enum {
 } klay_status;
 
 /* Semiring of the evaluation (Section 4): REAL = (+, x) on probabilities, LOG = (logsumexp, +)
- * on log-probabilities (Alg. 4 with epsilon = 0). */
-typedef enum { KLAY_REAL = 0, KLAY_LOG = 1 } klay_semiring;
+ * on log-probabilities (Alg. 4 with epsilon = 0).  Section 4 closes by noting that any semiring
+ * whose operations are reductions will do; MAXLOG = (max, +) on log-probabilities is the one
+ * offered beyond the paper's two: the log weight of the heaviest proof tree (for a smooth d-DNNF
+ * the most probable model).  MAXLOG is evaluated forward only. */
+typedef enum { KLAY_REAL = 0, KLAY_LOG = 1, KLAY_MAXLOG = 2 } klay_semiring;
 
 /* node_type codes of the input DAG */
 enum { KLAY_LIT = 0, KLAY_AND = 1, KLAY_OR = 2, KLAY_TRUE = 3, KLAY_FALSE = 4 };
@@ -83,7 +86,7 @@ typedef struct klay_info_t {
  * PROD_EDGES the per-edge products of the real-semiring reverse sweep. */
 enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
-       KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_COUNT };
+       KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_FWD_MAX, KLAY_K_COUNT };
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];
@@ -127,7 +130,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
 
 /*
  * klay_forward -- evaluate all layers (Alg. 1 for KLAY_REAL, Alg. 4 for KLAY_LOG).
- *   leaf_weights  device [B, V] row-major fp32: p_v (REAL) or log p_v (LOG).  The negated literal
+ *   leaf_weights  device [B, V] row-major fp32: p_v (REAL) or log p_v (LOG, MAXLOG).  The negated literal
  *                 of v gets 1 - p_v resp. log(1 - exp(x_v)).
  *   B             batch size >= 1
  *   out           device [B, R] row-major fp32; out[b, r] = value of roots[r] on sample b
@@ -148,7 +151,8 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
  * Uses B, the semiring and the activations of that forward call; the caller must not have run
  * another forward in between.  The first real-semiring call on a handle uploads extra index
  * arrays and allocates a per-edge buffer (hipMalloc, which synchronises); later calls only
- * enqueue.  The real semiring is not differentiated on handles built with alias_chains.  A literal whose adjoint is exactly 0 contributes 0 even where the
+ * enqueue.  The real semiring is not differentiated on handles built with alias_chains, MAXLOG
+ * not at all (KLAY_EINVAL).  A literal whose adjoint is exactly 0 contributes 0 even where the
  * derivative of its weight is infinite (log-domain negated literal at p = 1).
  * Errors: KLAY_ESTATE if no forward was run, KLAY_EINVAL, KLAY_EHIP.
  */

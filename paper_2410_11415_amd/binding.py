@@ -16,10 +16,10 @@ import numpy as np
 from . import build as _build
 
 KLAY_OK, KLAY_EINVAL, KLAY_ECYCLE, KLAY_ENOMEM, KLAY_EHIP, KLAY_ESTATE = range(6)
-KLAY_REAL, KLAY_LOG = 0, 1
+KLAY_REAL, KLAY_LOG, KLAY_MAXLOG = 0, 1, 2
 KLAY_LIT, KLAY_AND, KLAY_OR, KLAY_TRUE, KLAY_FALSE = range(5)
 KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf",
-                  "tail_fwd", "tail_bwd", "split", "prod_edges")
+                  "tail_fwd", "tail_bwd", "split", "prod_edges", "fwd_max")
 
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
@@ -49,7 +49,7 @@ class klay_info_t(ctypes.Structure):
 
 
 class klay_profile_t(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_float * 13), ("launches", ctypes.c_int32 * 13), ("alg_bytes", ctypes.c_double * 13)]
+    _fields_ = [("ms", ctypes.c_float * 14), ("launches", ctypes.c_int32 * 14), ("alg_bytes", ctypes.c_double * 14)]
 
 
 _lib = None

@@ -192,6 +192,7 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
     case klay::OP_SUM: launch_op<klay::OP_SUM>(a, g, grid, s); break;
     case klay::OP_PROD: launch_op<klay::OP_PROD>(a, g, grid, s); break;
     case klay::OP_LSE: launch_op<klay::OP_LSE>(a, g, grid, s); break;
+    case klay::OP_MAX: launch_op<klay::OP_MAX>(a, g, grid, s); break;
     default: launch_op<klay::OP_SOFTMAX_BWD>(a, g, grid, s); break;
     }
 }
@@ -222,6 +223,7 @@ void launch_stream(int op, const DevPass& dp, bool segments, const Geometry& g, 
     case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, segments, g, src, src2, own, dst, B, s); break;
     case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, segments, g, src, src2, own, dst, B, s); break;
     case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, segments, g, src, src2, own, dst, B, s); break;
+    case klay::OP_MAX: launch_stream_op<klay::OP_MAX>(dp, segments, g, src, src2, own, dst, B, s); break;
     default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, segments, g, src, src2, own, dst, B, s); break;
     }
 }
@@ -543,7 +545,7 @@ bool enable_tail_lds() {
     return true;
 }
 
-void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int B, int ld, bool log_domain,
+void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int B, int ld, int semiring,
                      hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
@@ -553,7 +555,7 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int
     dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
 #define KLAY_TAIL_FWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::tail_fwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
-                       n_layers, first_is_and, c->d_index, act, B, ld, log_domain ? 1 : 0, t.nmax)
+                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax)
     switch (t.ct) {
     case 8: KLAY_TAIL_FWD(8); break;
     case 4: KLAY_TAIL_FWD(4); break;
@@ -930,12 +932,13 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
     if (!c || !leaf_weights || !out) return fail(KLAY_EINVAL, "klay_forward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_forward: host-only handle (built with device = -1)");
     if (B < 1) return fail(KLAY_EINVAL, "klay_forward: B must be >= 1");
-    if (semiring != KLAY_REAL && semiring != KLAY_LOG) return fail(KLAY_EINVAL, "klay_forward: unknown semiring");
+    if (semiring != KLAY_REAL && semiring != KLAY_LOG && semiring != KLAY_MAXLOG)
+        return fail(KLAY_EINVAL, "klay_forward: unknown semiring");
     KLAY_HIP(hipSetDevice(c->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
     const klay::CircuitPlan& p = c->plan;
     const Geometry g = geometry(B);
-    const bool log_domain = semiring == KLAY_LOG;
+    const bool log_domain = semiring != KLAY_REAL;      // leaf weights are log p in both log-domain semirings
     if (c->profiling && !c->ev_pool.empty()) release_events(c);
 
     float* ws = nullptr;
@@ -975,8 +978,11 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
     for (int l = 1; l <= last_regular; ++l) {
         const DevLayer& d = c->dl[(size_t)l];
         const bool is_and = (l & 1) != 0;
-        const int op = log_domain ? (is_and ? klay::OP_SUM : klay::OP_LSE) : (is_and ? klay::OP_PROD : klay::OP_SUM);
-        const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM : (op == klay::OP_PROD ? KLAY_K_FWD_PROD : KLAY_K_FWD_LSE);
+        const int or_op = semiring == KLAY_MAXLOG ? klay::OP_MAX : klay::OP_LSE;
+        const int op = log_domain ? (is_and ? klay::OP_SUM : or_op) : (is_and ? klay::OP_PROD : klay::OP_SUM);
+        const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM
+                        : op == klay::OP_PROD ? KLAY_K_FWD_PROD
+                        : op == klay::OP_MAX ? KLAY_K_FWD_MAX : KLAY_K_FWD_LSE;
         // alias mode: child entries are rows of the whole buffer, otherwise of the layer below
         const float* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
         run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, scratch, g, B, s, prof, cls);
@@ -984,7 +990,7 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
 
     if (tail.first > 0) {
         prof.begin(KLAY_K_TAIL_FWD, tail_alg_bytes(c, tail.first, B, false));
-        launch_tail_fwd(c, tail, act, B, g.ld, log_domain, s);
+        launch_tail_fwd(c, tail, act, B, g.ld, (int)semiring, s);
         prof.end();
     }
 
@@ -1010,6 +1016,8 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward: host-only handle");
     if (!c->have_fwd) return fail(KLAY_ESTATE, "klay_backward: no forward pass to differentiate");
+    if (c->last_semiring == KLAY_MAXLOG)
+        return fail(KLAY_EINVAL, "klay_backward: the (max, +) semiring is not differentiated");
     const bool real = c->last_semiring == KLAY_REAL;
     if (real && c->plan.alias)
         return fail(KLAY_EINVAL, "klay_backward: the real semiring is not differentiated in alias_chains mode");

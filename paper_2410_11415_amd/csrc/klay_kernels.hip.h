@@ -13,7 +13,7 @@
 
 namespace klay {
 
-enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3 };
+enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4 };
 
 // Index entries: bits 0..29 = source row, bit 31 = last edge of its output row, bit 30 = weighted
 // edge (reverse sweep only: the parent is an OR node with more than one child, so the adjoint
@@ -95,6 +95,7 @@ __device__ __forceinline__ int xcd_block(int bid, int nblocks) { return (bid & 7
 
 // One step of the streaming reductions.  acc/mx carry the state of the current output row:
 //   OP_SUM / OP_PROD  acc = running sum / product
+//   OP_MAX            acc = running maximum (OR layers of the (max, +) semiring)
 //   OP_LSE            (mx, acc) = (running max, sum of exp(x - mx)); one exp per element:
 //                     a new maximum rescales the sum by exp(mx - x), otherwise exp(x - mx) is added
 //   OP_SOFTMAX_BWD    acc += g * exp(own - parent value) on weighted edges (a parent at -inf
@@ -103,6 +104,7 @@ template <int OP>
 __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc, bool weighted = true) {
     if (OP == OP_SUM) acc += x;
     else if (OP == OP_PROD) acc *= x;
+    else if (OP == OP_MAX) acc = fmaxf(acc, x);
     else if (OP == OP_LSE) {
         const float d = x - mx;                                   // +inf on the first finite element
         const float e = (x == -INFINITY) ? 0.0f : fexp(-fabsf(d));
@@ -121,7 +123,7 @@ __device__ __forceinline__ float finish(float acc, float mx) {
 }
 
 template <int OP>
-__device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : 0.0f; }
+__device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : (OP == OP_MAX ? -INFINITY : 0.0f); }
 
 // ---------------------------------------------------------------------------------------------
 // Streaming segmented gather-reduce for B > 32 (one wave spans the batch tile, VEC columns per
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
             }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                const float dead = OP == OP_PROD ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
+                const float dead = OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
                 const float xv = live ? x[i][v] : dead;
                 const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
                 accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], (ids[i] & kWeighted) != 0);
@@ -295,7 +297,7 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
                 const bool live = i < n;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
-                    const float dead = OP == OP_PROD ? 1.0f : (OP == OP_LSE ? -INFINITY : 0.0f);
+                    const float dead = OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
                     const float xv = live ? x[i][v] : dead;
                     const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
                     accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], wt[i]);
@@ -372,7 +374,7 @@ __device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib,
 template <int CT>
 __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer* __restrict__ layers, int n_layers,
                                                                 int first_is_and, const int32_t* __restrict__ ibase,
-                                                                float* act, int B, int ld, int log_domain,
+                                                                float* act, int B, int ld, int semiring,
                                                                 int nmax) {
     extern __shared__ float smem[];
     float* prev = smem;
@@ -412,7 +414,10 @@ __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer*
         const float* below = act + (size_t)L.row0_below * ld + col;
         float* out = act + (size_t)L.row0 * ld + col;
         const bool fg = t == 0;
-        if (log_domain) {
+        if (semiring == 2) {           // (max, +) on log weights
+            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+            else tail_fwd_rows<OP_MAX, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+        } else if (semiring == 1) {    // (logsumexp, +)
             if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
             else tail_fwd_rows<OP_LSE, CT>(L, ib, prev, cur, below, fg, out, ld, active);
         } else {

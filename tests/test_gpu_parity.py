@@ -502,3 +502,65 @@ def test_builder_circuits_share_nodes_and_keep_their_values(klay):
             grad += np.asarray(rd); mass += rd.mass; rel = max(rel, rd.rel)
         assert_grad_close(gd, GradRef(grad, mass, rel), "builder grad", real=(s == REAL))
     k.close(); k3.close()
+
+
+# ------------------------------------------------------------------ (max, +) semiring, forward only
+MAXLOG = 2
+
+
+def check_max(klay, c, p, what="", **kw):
+    k = build(klay, c, **kw)
+    with np.errstate(divide="ignore"):
+        w32 = as_inputs(p, True)
+    got, _ = gpu_eval(k, w32, MAXLOG)
+    ref, _ = oracle_eval(c, w32, MAXLOG)
+    e = assert_log_close(got, ref, what + " maxlog")
+    k.close()
+    return e
+
+
+def test_maxlog_worked_examples_and_small_batches(klay, golden):
+    for name, nv in (("fig1b_ddnnf.txt", 4), ("fig3_multiroot.txt", 5), ("appD_mnist_add.txt", 2)):
+        for B in (1, 5, 70):
+            check_max(klay, golden(name), leaf_probs(B, B, nv, ("uniform", 0.01, 0.99)), what=name)
+    c = layered_random(4, num_vars=48, depth=8, num_gates=1500, fanin=("geom", 2.0), groups=2, num_roots=7)
+    for B in (1, 3, 17, 32, 33, 64, 65, 128, 129, 257, 513):
+        check_max(klay, c, leaf_probs(B, B, 48), what="B=%d" % B)
+
+
+@pytest.mark.parametrize("name,scale,B", [("layered_1m", 0.05, 256), ("powerlaw_10m", 0.08, 64),
+                                           ("layered_3m_fwd_bwd", 0.02, 256), ("layered_100k", 1.0, 128)])
+def test_maxlog_configs(klay, name, scale, B):
+    c, p, spec = make_config(name, seed=1, scale=scale, batch=B)
+    print(name, "maxlog max|dlog| %.2e" % check_max(klay, c, p, what=name))
+    check_max(klay, c, p, what=name + " no_tail", no_tail=True)
+    check_max(klay, c, p, what=name + " alias", alias_chains=True)
+
+
+@pytest.mark.parametrize("B", [3, 64, 256])
+def test_maxlog_split_rows_and_impossible_branches(klay, B):
+    c = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
+    p = leaf_probs(5, B, 64, ("beta", 0.5, 0.5))
+    p[:, ::7] = 0.0
+    p[:, 3::11] = 1.0
+    for heavy, seg in ((2, 1), (8, 4), (64, 16)):
+        check_max(klay, c, p, what="split", heavy_fan=heavy, min_segment=seg)
+
+
+def test_maxlog_is_not_differentiated_and_leaves_the_handle_usable(klay):
+    import torch
+    c = layered_random(9, num_vars=32, depth=10, num_gates=3000, fanin=("geom", 2.0), groups=2, num_roots=9)
+    p = leaf_probs(1, 40, 32)
+    w32 = as_inputs(p, True)
+    k = build(klay, c)
+    got, _ = gpu_eval(k, w32, MAXLOG)
+    with pytest.raises(klay.KlayError) as e:
+        k.backward(torch.ones((40, 9), dtype=torch.float32, device="cuda"))
+    assert e.value.status == 1
+    dout = np.ones((40, 9), dtype=np.float32)
+    got2, gd = gpu_eval(k, w32, LOG, dout)
+    ref2, rd = oracle_eval(c, w32, LOG, dout, or_levels=k.num_layers // 2)
+    assert_log_close(got2, ref2, "log after maxlog")
+    assert_grad_close(gd, rd, "grad after maxlog")
+    assert np.all(got <= got2 + 1e-4)
+    k.close()
