@@ -217,6 +217,12 @@ class Circuit:
         from .nnf import load_nnf
         return cls(*load_nnf(path), **kw)
 
+    @classmethod
+    def from_sdd(cls, path: str, num_vars=None, **kw):
+        """Build from an SDD text file (see :mod:`.sdd`)."""
+        from .sdd import load_sdd
+        return cls(*load_sdd(path, num_vars), **kw)
+
     # -- inspection
     def info(self) -> dict:
         s = klay_info_t()
