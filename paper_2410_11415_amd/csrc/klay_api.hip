@@ -155,18 +155,7 @@ void launch_op(const klay::PassArgs& a, const Geometry& g, dim3 grid, hipStream_
         else launch_one<OP, 1, 64>(a, grid, s);
         return;
     }
-    if (g.vec == 4) {
-        switch (g.w) {
-        case 32: launch_one<OP, 4, 32>(a, grid, s); break;
-        case 16: launch_one<OP, 4, 16>(a, grid, s); break;
-        case 8: launch_one<OP, 4, 8>(a, grid, s); break;
-        case 4: launch_one<OP, 4, 4>(a, grid, s); break;
-        case 2: launch_one<OP, 4, 2>(a, grid, s); break;
-        default: launch_one<OP, 4, 1>(a, grid, s); break;
-        }
-        return;
-    }
-    switch (g.w) {
+    switch (g.w) {                      // B <= 32: one column per lane, a lane group per row
     case 32: launch_one<OP, 1, 32>(a, grid, s); break;
     case 16: launch_one<OP, 1, 16>(a, grid, s); break;
     case 8: launch_one<OP, 1, 8>(a, grid, s); break;
@@ -336,14 +325,8 @@ klay_status upload(klay_circuit* c) {
     const klay::CircuitPlan& p = c->plan;
     Packer pk;
     const int L = p.num_layers;
-    std::vector<PassOffsets> fo((size_t)L + 1), bo((size_t)L + 1);
-    for (int l = 1; l <= L; ++l) {
-        fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
-        bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
-    }
-    PassOffsets to{};
-    if (p.alias) to = pack_pass(pk, p.top_bwd);
-    // tail candidates: plain index vectors by parent and by child, then the descriptor array
+    // tail candidates first (their descriptors hold 32-bit offsets, and these arrays are small):
+    // plain index vectors by parent and by child, then the descriptor array
     size_t o_tail = 0;
     if (p.tail_first > 0) {
         std::vector<klay::TailLayer> descs;
@@ -369,6 +352,13 @@ klay_status upload(klay_circuit* c) {
         static_assert(sizeof(klay::TailLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
         o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::TailLayer) / sizeof(int32_t));
     }
+    std::vector<PassOffsets> fo((size_t)L + 1), bo((size_t)L + 1);
+    for (int l = 1; l <= L; ++l) {
+        fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
+        bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
+    }
+    PassOffsets to{};
+    if (p.alias) to = pack_pass(pk, p.top_bwd);
     const size_t o_pos = pk.add(p.pos_row), o_neg = pk.add(p.neg_row), o_root = pk.add(p.root_pos);
     const size_t o_tptr = pk.add(p.top_ptr), o_troot = pk.add(p.top_root);
 
@@ -633,7 +623,12 @@ klay_status ensure_real_bwd(klay_circuit* c, int ld) {
             (void)hipGetLastError();
             return fail(KLAY_ENOMEM, "klay_backward: hipMalloc of the real-semiring index arrays failed");
         }
-        KLAY_HIP(hipMemcpy(c->d_real_index, pk.buf.data(), bytes, hipMemcpyHostToDevice));
+        if (hipError_t e = hipMemcpy(c->d_real_index, pk.buf.data(), bytes, hipMemcpyHostToDevice); e != hipSuccess) {
+            (void)hipFree(c->d_real_index);
+            c->d_real_index = nullptr;
+            return fail(KLAY_EHIP, std::string("klay_backward: upload of the real-semiring index arrays: ") +
+                                       hipGetErrorString(e));
+        }
         c->real_layers.resize((size_t)L + 1);
         for (int l = 1; l <= L; l += 2) {
             klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
@@ -665,15 +660,6 @@ void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* bel
         if (g.vec == 4) KLAY_PE(4, 64);
         else if (g.vec == 2) KLAY_PE(2, 64);
         else KLAY_PE(1, 64);
-    } else if (g.vec == 4) {
-        switch (g.w) {
-        case 32: KLAY_PE(4, 32); break;
-        case 16: KLAY_PE(4, 16); break;
-        case 8: KLAY_PE(4, 8); break;
-        case 4: KLAY_PE(4, 4); break;
-        case 2: KLAY_PE(4, 2); break;
-        default: KLAY_PE(4, 1); break;
-        }
     } else {
         switch (g.w) {
         case 32: KLAY_PE(1, 32); break;
@@ -927,8 +913,8 @@ klay_status klay_get_profile(klay_circuit* c, klay_profile_t* prof) {
     return KLAY_OK;
 }
 
-klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
-                         klay_semiring semiring, void* stream) {
+static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
+                                klay_semiring semiring, void* stream) {
     if (!c || !leaf_weights || !out) return fail(KLAY_EINVAL, "klay_forward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_forward: host-only handle (built with device = -1)");
     if (B < 1) return fail(KLAY_EINVAL, "klay_forward: B must be >= 1");
@@ -1012,7 +998,7 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
     return KLAY_OK;
 }
 
-klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void* stream) {
+static klay_status backward_impl(klay_circuit* c, const float* dout, float* dleaf, void* stream) {
     if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward: host-only handle");
     if (!c->have_fwd) return fail(KLAY_ESTATE, "klay_backward: no forward pass to differentiate");
@@ -1145,6 +1131,26 @@ klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void
     prof.end();
     KLAY_HIP(hipGetLastError());
     return KLAY_OK;
+}
+
+// No C++ exception crosses the C boundary: host allocations of the launch sequences (event records,
+// the index arrays of the real-semiring reverse sweep) report KLAY_ENOMEM instead.
+klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
+                         klay_semiring semiring, void* stream) {
+    try {
+        return forward_impl(c, leaf_weights, B, out, semiring, stream);
+    } catch (const std::bad_alloc&) {
+        if (c) c->have_fwd = false;
+        return fail(KLAY_ENOMEM, "klay_forward: out of host memory");
+    }
+}
+
+klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void* stream) {
+    try {
+        return backward_impl(c, dout, dleaf, stream);
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_backward: out of host memory");
+    }
 }
 
 }  // extern "C"
