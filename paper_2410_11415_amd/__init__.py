@@ -9,3 +9,11 @@ from .binding import (KLAY_AND, KLAY_FALSE, KLAY_LIT, KLAY_LOG, KLAY_MAXLOG, KLA
 __all__ = ["KLAY_AND", "KLAY_FALSE", "KLAY_LIT", "KLAY_LOG", "KLAY_MAXLOG", "KLAY_OR", "KLAY_REAL", "KLAY_TRUE", "Builder", "Circuit",
            "KlayError", "klay_backward", "klay_build", "klay_destroy", "klay_forward", "klay_last_error",
            "library_path", "load"]
+
+
+def __getattr__(name):
+    # the torch layer is imported on first use, so that the binding alone does not need torch
+    if name == "CircuitLayer":
+        from .autograd import CircuitLayer
+        return CircuitLayer
+    raise AttributeError(name)

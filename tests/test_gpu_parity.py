@@ -564,3 +564,53 @@ def test_maxlog_is_not_differentiated_and_leaves_the_handle_usable(klay):
     assert_grad_close(gd, rd, "grad after maxlog")
     assert np.all(got <= got2 + 1e-4)
     k.close()
+
+
+# ------------------------------------------------------------------ the circuit as a torch layer
+def test_circuit_layer_backpropagates_into_a_network(klay):
+    """autograd through the layer gives the oracle's gradient, chains into upstream parameters, and
+    refuses to differentiate a forward pass whose activations have been overwritten"""
+    import torch
+    c = layered_random(9, num_vars=32, depth=10, num_gates=3000, fanin=("geom", 2.0), groups=2, num_roots=9)
+    k = build(klay, c)
+    layer = klay.CircuitLayer(k, klay.KLAY_LOG)
+    B = 70
+    torch.manual_seed(0)
+    logits = torch.randn(B, 32, device="cuda", requires_grad=True)
+    w = torch.nn.functional.logsigmoid(logits)                 # log p of every variable
+    out = layer(w)
+    coef = torch.linspace(-1.0, 1.0, 9, device="cuda")
+    (out * coef).sum().backward()
+    w32 = w.detach().cpu().numpy()
+    dout = np.tile(coef.cpu().numpy(), (B, 1)).astype(np.float32)
+    ref, rd = oracle_eval(c, w32, LOG, dout, or_levels=k.num_layers // 2)
+    assert_log_close(out.detach().cpu().numpy(), ref, "layer")
+    # chain rule through logsigmoid: d/dlogit = dleaf * (1 - p)
+    p = np.exp(w32.astype(np.float64))
+    from tests.gpu_util import GradRef
+    want = GradRef(np.asarray(rd) * (1 - p), rd.mass * (1 - p), rd.rel)
+    assert_grad_close(logits.grad.cpu().numpy(), want, "layer grad")
+    # a few optimiser steps raise the log-probability of root 0
+    net = torch.nn.Linear(4, 32).cuda()
+    opt = torch.optim.SGD(net.parameters(), lr=0.05)
+    x = torch.randn(B, 4, device="cuda")
+    losses = []
+    for _ in range(5):
+        opt.zero_grad()
+        loss = -layer(torch.nn.functional.logsigmoid(net(x)))[:, 0].mean()
+        loss.backward()
+        opt.step()
+        losses.append(float(loss.detach()))
+    assert losses[-1] < losses[0]
+    # stale graph
+    o1 = layer(torch.nn.functional.logsigmoid(logits))
+    with torch.no_grad():
+        layer(w.detach())
+    with pytest.raises(RuntimeError):
+        o1.sum().backward()
+    with pytest.raises(RuntimeError):
+        klay.CircuitLayer(k, klay.KLAY_MAXLOG)(torch.nn.functional.logsigmoid(logits))
+    with torch.no_grad():
+        m = klay.CircuitLayer(k, klay.KLAY_MAXLOG)(w.detach())
+    assert torch.all(m <= out.detach() + 1e-4)
+    k.close()
