@@ -283,9 +283,10 @@ def test_profile_reports_kernel_classes(klay):
     k.close()
 
 
-@pytest.mark.parametrize("B", [1, 3, 8, 37, 256])
+@pytest.mark.parametrize("B", [1, 3, 8, 37, 256, 300, 700, 1100, 2100])
 def test_persistent_top_kernel_matches_per_layer_launches(klay, B):
-    """the narrow top layers run in one LDS-resident kernel; with no_tail every layer is its own launch"""
+    """the narrow top layers run in one LDS-resident kernel (1, 2, 4 or 8 batch columns per workgroup as
+    the batch grows past 256, 512, 1024); with no_tail every layer is its own launch"""
     c, p, _ = make_config("layered_100k", seed=5, scale=0.3, batch=B)
     w32 = as_inputs(p, True)
     d = np.random.default_rng(5).normal(size=(B, c.roots.shape[0])).astype(np.float32)
