@@ -186,34 +186,38 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
     }
 }
 
+// Streaming kernel over the main rows of a pass and / or the segments of its split rows (batch
+// tiles of one wave: B > 32).  dst_seg is the scratch base shifted by -n_main rows: segment rows are
+// numbered after the main rows.
 template <int OP>
-void launch_stream_op(const DevPass& dp, bool segments, const Geometry& g, const float* src, const float* src2,
-                      const float* own, float* dst, int B, hipStream_t s) {
-    const int n_tasks = segments ? dp.n_seg_tasks : dp.n_tasks;
-    int64_t blocks = ((int64_t)n_tasks + 3) / 4;
+void launch_stream_op(const DevPass& dp, bool main_rows, bool segments, const Geometry& g, const float* src,
+                      const float* src2, const float* own, float* dst, float* dst_seg, int B, hipStream_t s) {
+    const int2* tasks = reinterpret_cast<const int2*>(dp.tasks);
+    const int2* seg_tasks = reinterpret_cast<const int2*>(dp.seg_tasks);
+    int n_tasks = main_rows ? dp.n_tasks : 0;
+    int n_seg_tasks = segments ? dp.n_seg_tasks : 0;
+    int64_t blocks = ((int64_t)n_tasks + n_seg_tasks + 3) / 4;
     blocks = (blocks + 7) / 8 * 8;
     // outputs larger than the L2s together (8 x 4 MB) are written with streaming stores
-    const int nt = !segments && (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
+    const int nt = (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
-    const int2* tasks = reinterpret_cast<const int2*>(segments ? dp.seg_tasks : dp.tasks);
     if (g.vec == 4)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg);
     else if (g.vec == 2)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg);
     else
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg);
 }
 
-// Streaming kernel over the main rows of a pass (batch tiles of one wave: B > 32).
-void launch_stream(int op, const DevPass& dp, bool segments, const Geometry& g, const float* src,
-                   const float* src2, const float* own, float* dst, int B, hipStream_t s) {
-    if ((segments ? dp.n_seg_tasks : dp.n_tasks) <= 0) return;
+void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, const Geometry& g, const float* src,
+                   const float* src2, const float* own, float* dst, float* dst_seg, int B, hipStream_t s) {
+    if ((main_rows ? dp.n_tasks : 0) + (segments ? dp.n_seg_tasks : 0) <= 0) return;
     switch (op) {
-    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, segments, g, src, src2, own, dst, B, s); break;
-    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, segments, g, src, src2, own, dst, B, s); break;
-    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, segments, g, src, src2, own, dst, B, s); break;
-    case klay::OP_MAX: launch_stream_op<klay::OP_MAX>(dp, segments, g, src, src2, own, dst, B, s); break;
-    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, segments, g, src, src2, own, dst, B, s); break;
+    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_MAX: launch_stream_op<klay::OP_MAX>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     }
 }
 
@@ -423,20 +427,20 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     a.ld = g.ld;
     const double light_rows = (double)dp.n_main - dp.n_heavy;
     if (g.w == 64) {
-        prof.begin(cls, pass_bytes(op, (double)dp.main_entries, light_rows, B));
-        launch_stream(op, dp, false, g, src, src2, own, dst, B, s);
+        // float4 tiles: the segments of split rows ride in the same launch as the main rows (same
+        // streaming walk, output to scratch rows).  The softmax adjoint's segments need their owner's
+        // value row and narrower tiles measured faster through the generic kernel: separate launch.
+        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec == 4;
+        float* seg_base = scratch - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
+        double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
+        if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
+        prof.begin(cls, bytes);
+        launch_stream(op, dp, true, merged, g, src, src2, own, dst, seg_base, B, s);
         prof.end();
-        if (dp.n_seg > 0) {
+        if (dp.n_seg > 0 && !merged) {
             prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B));
-            if (op != klay::OP_SOFTMAX_BWD && g.vec == 4) {
-                // segment row n_main + i writes scratch row i: same streaming kernel, shifted output base
-                // (the shifted pointer is only ever indexed with rows >= n_main).  Narrower batch tiles
-                // (one or two columns per lane) measured faster through the generic kernel.
-                launch_stream(op, dp, true, g, src, src2, own, scratch - (ptrdiff_t)dp.n_main * g.ld, B, s);
-            } else {
-                a.row_begin = dp.n_main;         // the softmax adjoint needs each segment's owner row
-                launch_pass(op, a, g, s);
-            }
+            a.row_begin = dp.n_main;
+            launch_pass(op, a, g, s);
             prof.end();
         }
     } else {

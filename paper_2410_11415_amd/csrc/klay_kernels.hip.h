@@ -139,7 +139,9 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                                                      const float* __restrict__ src,
                                                      const float* __restrict__ src2,
                                                      const float* __restrict__ own, float* __restrict__ dst,
-                                                     int B, int ld, int stream_stores) {
+                                                     int B, int ld, int stream_stores,
+                                                     const int2* __restrict__ seg_tasks, int n_seg_tasks,
+                                                     float* __restrict__ dst_seg) {
     // entries per chunk: measured on the headline workload, 4 (2 for the softmax adjoint, which loads
     // three rows per entry) beat 8 / 4 by 2%: the kernel is bandwidth-bound, fewer registers per wave
     // buy more resident waves
@@ -148,8 +150,12 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = ((int)blockIdx.y * 64 + lane) * VEC;
     if (col >= B) return;
-    const int t = xcd_block((int)blockIdx.x, (int)gridDim.x) * 4 + wave;
-    if (t >= n_tasks) return;
+    int t = xcd_block((int)blockIdx.x, (int)gridDim.x) * 4 + wave;
+    if (t >= n_tasks + n_seg_tasks) return;
+    // tasks past the main list are segments of split rows: same walk, output rows go to scratch
+    // (dst_seg is shifted so that segment row numbers, which continue after the main rows, index it)
+    const bool seg = t >= n_tasks;
+    if (seg) { t -= n_tasks; tasks = seg_tasks; dst = dst_seg; stream_stores = 0; }
     const int2 t0 = tasks[t], t1 = tasks[t + 1];
     int row = t0.x;
     int j = t0.y;
