@@ -226,7 +226,8 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle
         threads = min(oracle.max_threads(), 16)
-        cols = args.cpu_columns or (2 * threads if backward else 4 * threads)
+        # a bounded sample: about 1.3e9 edge evaluations, 10-20 s for the oracle on 16 threads
+        cols = args.cpu_columns or max(threads, int(1.3e9 / max(1, E)) // threads * threads)
         cols = min(cols, B)
         sample = np.ascontiguousarray(w32[:cols]).astype(np.float64)
         oracle_semiring = {pkg.KLAY_LOG: oracle.LOG, pkg.KLAY_REAL: oracle.REAL, pkg.KLAY_MAXLOG: oracle.MAXLOG}[semiring]
