@@ -29,7 +29,9 @@
  *   child_ptr[n+1], child_idx[]  children of gate i are child_idx[child_ptr[i]..child_ptr[i+1])
  *   roots[R]
  * Leaf weights: w[b*V+v] is p_v (REAL) or log p_v (LOG); the negative literal
- * gets 1-p resp. log(1-exp(x)).
+ * gets 1-p resp. log(1-exp(x)), unless a second array wneg[b*V+v] gives the negative
+ * literals weights of their own (weighted model counting with arbitrary literal weights;
+ * the two arrays are then independent inputs with a gradient each).
  */
 #include <math.h>
 #include <stdint.h>
@@ -84,7 +86,8 @@ int64_t klay_oracle_postorder(int64_t num_nodes, const int64_t* child_ptr,
 /* Value of every node in `order` for one batch column; w points at V weights. */
 static void eval_column(int semiring, const uint8_t* node_type, const int32_t* node_lit,
                         const int64_t* child_ptr, const int32_t* child_idx,
-                        const int32_t* order, int64_t n_order, const double* w, double* val) {
+                        const int32_t* order, int64_t n_order, const double* w, const double* wn,
+                        double* val) {
     for (int64_t i = 0; i < n_order; ++i) {
         int32_t n = order[i];
         int64_t a = child_ptr[n], e = child_ptr[n + 1];
@@ -93,7 +96,8 @@ static void eval_column(int semiring, const uint8_t* node_type, const int32_t* n
         case T_LIT: {
             int32_t l = node_lit[n];
             double x = w[(l > 0 ? l : -l) - 1];
-            if (semiring == S_REAL) v = l > 0 ? x : 1.0 - x;
+            if (l < 0 && wn) v = wn[-l - 1];
+            else if (semiring == S_REAL) v = l > 0 ? x : 1.0 - x;
             else v = l > 0 ? x : log1mexp(x);
             break;
         }
@@ -133,7 +137,7 @@ static void eval_column(int semiring, const uint8_t* node_type, const int32_t* n
 int klay_oracle_forward(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
                         const int32_t* node_lit, const int64_t* child_ptr,
                         const int32_t* child_idx, int32_t num_roots, const int32_t* roots,
-                        int32_t B, const double* w, int semiring, double* out,
+                        int32_t B, const double* w, const double* wneg, int semiring, double* out,
                         double* node_vals, int nthreads) {
     int32_t* order = (int32_t*)malloc(sizeof(int32_t) * ((size_t)num_nodes + 1));
     if (!order) return -2;
@@ -153,7 +157,7 @@ int klay_oracle_forward(int32_t num_vars, int64_t num_nodes, const uint8_t* node
             if (!val) continue;
             if (node_vals) for (int64_t i = 0; i < num_nodes; ++i) val[i] = NAN;
             eval_column(semiring, node_type, node_lit, child_ptr, child_idx, order, n_order,
-                        w + (size_t)b * num_vars, val);
+                        w + (size_t)b * num_vars, wneg ? wneg + (size_t)b * num_vars : NULL, val);
             for (int32_t r = 0; r < num_roots; ++r) out[(size_t)b * num_roots + r] = val[roots[r]];
             if (node_vals) memcpy(node_vals + (size_t)b * num_nodes, val, sizeof(double) * (size_t)num_nodes);
         }
@@ -172,6 +176,7 @@ int klay_oracle_forward(int32_t num_vars, int64_t num_nodes, const uint8_t* node
  *   literal +v       : dleaf += adj
  *   literal -v       : dleaf += adj * d(neg weight)/dw = -adj (REAL), -adj / expm1(-x) (LOG);
  *                      a zero adjoint contributes 0 even where that derivative is infinite.
+ *                      With wneg given: dneg += adj instead (dleaf then holds the positive literals only).
  * With abs_mode != 0 the same sweep runs on |dout| and adds |adj * d(neg weight)/dw| at negated
  * literals, so that dleaf becomes the sum over all root-to-leaf paths of |contribution|: the
  * scale against which a floating-point gradient's cancellation error has to be judged.
@@ -179,8 +184,9 @@ int klay_oracle_forward(int32_t num_vars, int64_t num_nodes, const uint8_t* node
 int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
                          const int32_t* node_lit, const int64_t* child_ptr,
                          const int32_t* child_idx, int32_t num_roots, const int32_t* roots,
-                         int32_t B, const double* w, int semiring, const double* dout,
-                         double* dleaf, int nthreads, int abs_mode) {
+                         int32_t B, const double* w, const double* wneg, int semiring, const double* dout,
+                         double* dleaf, double* dneg, int nthreads, int abs_mode) {
+    if ((wneg == NULL) != (dneg == NULL)) return -3;
     if (semiring != S_REAL && semiring != S_LOG) return -3;   /* (max, +) is not differentiated */
     int32_t* order = (int32_t*)malloc(sizeof(int32_t) * ((size_t)num_nodes + 1));
     if (!order) return -2;
@@ -205,9 +211,12 @@ int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* nod
             if (!val || !adj || !pre) continue;
             const double* wb = w + (size_t)b * num_vars;
             double* gb = dleaf + (size_t)b * num_vars;
-            eval_column(semiring, node_type, node_lit, child_ptr, child_idx, order, n_order, wb, val);
+            const double* wnb = wneg ? wneg + (size_t)b * num_vars : NULL;
+            double* gnb = dneg ? dneg + (size_t)b * num_vars : NULL;
+            eval_column(semiring, node_type, node_lit, child_ptr, child_idx, order, n_order, wb, wnb, val);
             for (int64_t i = 0; i < n_order; ++i) adj[order[i]] = 0.0;
             for (int32_t v = 0; v < num_vars; ++v) gb[v] = 0.0;
+            if (gnb) for (int32_t v = 0; v < num_vars; ++v) gnb[v] = 0.0;
             for (int32_t r = 0; r < num_roots; ++r) {
                 double d = dout[(size_t)b * num_roots + r];
                 adj[roots[r]] += abs_mode ? fabs(d) : d;
@@ -221,6 +230,7 @@ int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* nod
                     int32_t l = node_lit[n];
                     int32_t v = (l > 0 ? l : -l) - 1;
                     if (l > 0) gb[v] += g;
+                    else if (gnb) gnb[v] += g;          /* a weight of its own: adj passes straight through */
                     else if (g != 0.0) {
                         double t = semiring == S_REAL ? -g : -g / expm1(-wb[v]);
                         gb[v] += abs_mode ? fabs(t) : t;

@@ -50,9 +50,9 @@ def _load():
             lib.klay_oracle_postorder.restype = i64
             lib.klay_oracle_postorder.argtypes = [i64, p, p, i32, p, p]
             lib.klay_oracle_forward.restype = ctypes.c_int
-            lib.klay_oracle_forward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, ctypes.c_int, p, p, ctypes.c_int]
+            lib.klay_oracle_forward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, p, ctypes.c_int, p, p, ctypes.c_int]
             lib.klay_oracle_backward.restype = ctypes.c_int
-            lib.klay_oracle_backward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, ctypes.c_int, p, p, ctypes.c_int, ctypes.c_int]
+            lib.klay_oracle_backward.argtypes = [i32, i64, p, p, p, p, i32, p, i32, p, p, ctypes.c_int, p, p, p, ctypes.c_int, ctypes.c_int]
             lib.klay_oracle_max_threads.restype = ctypes.c_int
             _lib = lib
             del dbl
@@ -91,11 +91,12 @@ def max_threads() -> int:
 
 
 def forward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights, semiring,
-            nthreads: int = 1, return_node_values: bool = False):
+            nthreads: int = 1, return_node_values: bool = False, neg_weights=None):
     """Root values ``out[B,R]`` (fp64) for leaf weights ``weights[B,V]``.
 
     ``weights`` holds p (REAL) or log p (LOG, MAXLOG); it is widened to fp64 as given.
     With ``return_node_values`` also returns ``vals[B,num_nodes]`` (NaN where unreachable).
+    ``neg_weights[B,V]`` gives the negated literals weights of their own instead of 1-p / log(1-e^x).
     """
     lib = _load()
     if int(semiring) not in (REAL, LOG, MAXLOG):
@@ -108,8 +109,14 @@ def forward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights,
     B, R, n = w.shape[0], roots.shape[0], node_type.shape[0]
     out = np.empty((B, R), dtype=np.float64)
     vals = np.empty((B, n), dtype=np.float64) if return_node_values else None
+    wn = None
+    if neg_weights is not None:
+        wn = np.ascontiguousarray(neg_weights, dtype=np.float64)
+        if wn.shape != w.shape:
+            raise ValueError("neg_weights must have the shape of weights")
     rc = lib.klay_oracle_forward(num_vars, n, _ptr(node_type), _ptr(node_lit), _ptr(child_ptr),
-                                 _ptr(child_idx), R, _ptr(roots), B, _ptr(w), int(semiring),
+                                 _ptr(child_idx), R, _ptr(roots), B, _ptr(w), _ptr(wn) if wn is not None else None,
+                                 int(semiring),
                                  _ptr(out), _ptr(vals) if vals is not None else None, int(nthreads))
     if rc == -1:
         raise ValueError("circuit has a cycle")
@@ -119,11 +126,13 @@ def forward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights,
 
 
 def backward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights, semiring,
-             dout, nthreads: int = 1, path_mass: bool = False):
+             dout, nthreads: int = 1, path_mass: bool = False, neg_weights=None):
     """``dleaf[B,V] = sum_r dout[b,r] * d out[b,r] / d weights[b,v]`` (fp64, reverse mode).
 
     With ``path_mass`` the sweep runs on absolute values and returns the sum over all root-to-leaf
-    paths of |contribution| (>= |dleaf|): the scale of the cancellation in the gradient."""
+    paths of |contribution| (>= |dleaf|): the scale of the cancellation in the gradient.
+    With ``neg_weights`` the two weight arrays are independent inputs and the result is the pair
+    ``(dpos[B,V], dneg[B,V])``."""
     lib = _load()
     if int(semiring) not in (REAL, LOG):
         raise ValueError("only the real and the log semiring are differentiated")
@@ -135,11 +144,18 @@ def backward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights
     if w.ndim != 2 or w.shape[1] != num_vars or g.shape != (B, R):
         raise ValueError("weights must be [B,V] and dout [B,R]")
     dleaf = np.empty((B, num_vars), dtype=np.float64)
+    wn = dneg = None
+    if neg_weights is not None:
+        wn = np.ascontiguousarray(neg_weights, dtype=np.float64)
+        if wn.shape != w.shape:
+            raise ValueError("neg_weights must have the shape of weights")
+        dneg = np.empty((B, num_vars), dtype=np.float64)
     rc = lib.klay_oracle_backward(num_vars, n, _ptr(node_type), _ptr(node_lit), _ptr(child_ptr),
-                                  _ptr(child_idx), R, _ptr(roots), B, _ptr(w), int(semiring),
-                                  _ptr(g), _ptr(dleaf), int(nthreads), int(bool(path_mass)))
+                                  _ptr(child_idx), R, _ptr(roots), B, _ptr(w), _ptr(wn) if wn is not None else None,
+                                  int(semiring), _ptr(g), _ptr(dleaf), _ptr(dneg) if dneg is not None else None,
+                                  int(nthreads), int(bool(path_mass)))
     if rc == -1:
         raise ValueError("circuit has a cycle")
     if rc != 0:
         raise MemoryError("oracle backward failed (%d)" % rc)
-    return dleaf
+    return dleaf if dneg is None else (dleaf, dneg)

@@ -438,3 +438,69 @@ def test_maxlog_single_gates_and_impossible_branches():
     assert np.all(out == -np.inf)
     with pytest.raises(ValueError):
         bwd(c, np.log(np.full((1, 6), 0.5)), MAXLOG, np.ones((1, 2)))
+
+
+# ----------------------------------------------------------------------------- literal weights of their own
+def test_negative_literal_weights_fig1b_polynomial(golden):
+    """Figure 1(b) read as a polynomial in the eight literal weights:
+    -b -a  +  -a b (c d + -c)  +  (c d + -d) a"""
+    c = golden("fig1b_ddnnf.txt")
+    rng = np.random.default_rng(3)
+    wp, wn = rng.uniform(0.1, 2.0, size=(5, 4)), rng.uniform(0.1, 2.0, size=(5, 4))
+    a, b, cc, d = (wp[:, i] for i in range(4))
+    na, nb, nc, nd = (wn[:, i] for i in range(4))
+    ref = nb * na + na * b * (cc * d + nc) + (cc * d + nd) * a
+    np.testing.assert_allclose(fwd(c, wp, REAL, neg_weights=wn)[:, 0], ref, rtol=1e-13)
+    np.testing.assert_allclose(fwd(c, np.log(wp), LOG, neg_weights=np.log(wn))[:, 0], np.log(ref), atol=1e-12)
+    # gradients of the polynomial, by hand
+    dout = rng.normal(size=(5, 1))
+    dp, dn = bwd(c, wp, REAL, dout, neg_weights=wn)
+    np.testing.assert_allclose(dp[:, 0], dout[:, 0] * (cc * d + nd), rtol=1e-12)                 # d/da
+    np.testing.assert_allclose(dn[:, 0], dout[:, 0] * (nb + b * (cc * d + nc)), rtol=1e-12)      # d/d(-a)
+    np.testing.assert_allclose(dp[:, 3], dout[:, 0] * (na * b * cc + cc * a), rtol=1e-12)        # d/dd
+    np.testing.assert_allclose(dn[:, 3], dout[:, 0] * a, rtol=1e-12)                             # d/d(-d)
+    # log domain: d log f / d log w = w df/dw / f
+    lp, ln = bwd(c, np.log(wp), LOG, dout, neg_weights=np.log(wn))
+    np.testing.assert_allclose(lp, dp * wp / ref[:, None], rtol=1e-11)
+    np.testing.assert_allclose(ln, dn * wn / ref[:, None], rtol=1e-11)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_negative_literal_weights_weighted_model_count(seed):
+    """smooth d-DNNF: the value is the sum over models of the product of arbitrary literal weights"""
+    rng = np.random.default_rng(200 + seed)
+    nv = 9
+    clauses = [[(int(v), bool(rng.integers(2))) for v in rng.choice(nv, 3, replace=False)] for _ in range(14)]
+    c = _smooth_obdd(nv, clauses)
+    wp, wn = rng.uniform(0.2, 3.0, size=(4, nv)), rng.uniform(0.2, 3.0, size=(4, nv))
+    bits = ((np.arange(2 ** nv)[:, None] >> np.arange(nv)[None, :]) & 1).astype(bool)
+    sat = np.ones(2 ** nv, dtype=bool)
+    for cl in clauses:
+        sat &= np.any([bits[:, v] == pos for v, pos in cl], axis=0)
+    ref = np.prod(np.where(bits[None, sat, :], wp[:, None, :], wn[:, None, :]), axis=2).sum(axis=1)
+    np.testing.assert_allclose(fwd(c, wp, REAL, neg_weights=wn)[:, 0], ref, rtol=1e-12)
+    np.testing.assert_allclose(fwd(c, np.log(wp), LOG, neg_weights=np.log(wn))[:, 0], np.log(ref), atol=1e-11)
+    heaviest = np.log(np.where(bits[None, sat, :], wp[:, None, :], wn[:, None, :])).sum(axis=2).max(axis=1)
+    np.testing.assert_allclose(fwd(c, np.log(wp), MAXLOG, neg_weights=np.log(wn))[:, 0], heaviest, atol=1e-11)
+
+
+def test_negative_literal_weights_default_and_finite_differences():
+    c = layered_random(5, num_vars=12, depth=6, num_gates=200, fanin=("geom", 2.0), groups=1, num_roots=3)
+    p = leaf_probs(5, 3, 12, ("uniform", 0.1, 0.9))
+    # 1 - p given explicitly is the default
+    np.testing.assert_allclose(fwd(c, p, REAL, neg_weights=1 - p), fwd(c, p, REAL), rtol=1e-14)
+    np.testing.assert_allclose(fwd(c, np.log(p), LOG, neg_weights=np.log1p(-p)), fwd(c, np.log(p), LOG), atol=1e-13)
+    rng = np.random.default_rng(6)
+    dout = rng.normal(size=(3, 3))
+    for sem, a, b in ((REAL, p, rng.uniform(0.1, 0.9, size=p.shape)), (LOG, np.log(p), np.log(rng.uniform(0.1, 0.9, size=p.shape)))):
+        dp, dn = bwd(c, a, sem, dout, neg_weights=b)
+        h = 1e-6
+        for v in (0, 5, 11):
+            e = np.zeros_like(a); e[:, v] = h
+            fd_p = ((fwd(c, a + e, sem, neg_weights=b) - fwd(c, a - e, sem, neg_weights=b)) * dout).sum(1) / (2 * h)
+            fd_n = ((fwd(c, a, sem, neg_weights=b + e) - fwd(c, a, sem, neg_weights=b - e)) * dout).sum(1) / (2 * h)
+            np.testing.assert_allclose(dp[:, v], fd_p, rtol=1e-5, atol=1e-8)
+            np.testing.assert_allclose(dn[:, v], fd_n, rtol=1e-5, atol=1e-8)
+    # the default's gradient is the chain rule over the two: dpos - dneg (REAL, neg = 1 - p)
+    dp, dn = bwd(c, p, REAL, dout, neg_weights=1 - p)
+    np.testing.assert_allclose(bwd(c, p, REAL, dout), dp - dn, rtol=1e-10, atol=1e-12)
