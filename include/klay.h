@@ -158,6 +158,21 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
  */
 klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void* stream);
 
+/*
+ * klay_forward_lits / klay_backward_lits -- the same two passes with weights of their own for the
+ * negated literals (weighted model counting with arbitrary literal weights, Section 2: every leaf
+ * of the arithmetic circuit carries a weight).
+ *   pos_weights   device [B, V]: weight of literal v (probability, or its log in the log-domain semirings)
+ *   neg_weights   device [B, V]: weight of literal -v, same domain; NULL makes the call klay_forward
+ *   dpos, dneg    device [B, V]: adjoints of the two arrays, treated as independent inputs; dneg may
+ *                 be NULL when only dpos is wanted.  Every entry is written.
+ * A forward pass with neg_weights must be differentiated by klay_backward_lits and one without by
+ * klay_backward (KLAY_ESTATE otherwise).  Everything else is as for klay_forward / klay_backward.
+ */
+klay_status klay_forward_lits(klay_circuit* c, const float* pos_weights, const float* neg_weights, int32_t B,
+                              float* out, klay_semiring semiring, void* stream);
+klay_status klay_backward_lits(klay_circuit* c, const float* dout, float* dpos, float* dneg, void* stream);
+
 /* Structure of the layered circuit. */
 klay_status klay_info(const klay_circuit* c, klay_info_t* info);
 

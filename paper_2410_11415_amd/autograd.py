@@ -16,11 +16,12 @@ from .binding import KLAY_LOG, KLAY_MAXLOG, Circuit
 
 class _Evaluate(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, weights, layer):
+    def forward(ctx, weights, neg_weights, layer):
         w = weights.contiguous()
-        out = layer.circuit.forward(w, layer.semiring)
+        wn = None if neg_weights is None else neg_weights.contiguous()
+        out = layer.circuit.forward(w, layer.semiring, neg_weights=wn)
         layer._ticket += 1
-        ctx.layer, ctx.ticket = layer, layer._ticket
+        ctx.layer, ctx.ticket, ctx.lits = layer, layer._ticket, wn is not None
         return out
 
     @staticmethod
@@ -29,14 +30,19 @@ class _Evaluate(torch.autograd.Function):
         if ctx.ticket != layer._ticket:
             raise RuntimeError("this circuit was evaluated again after the forward pass being differentiated; "
                                "its activations are gone (use one CircuitLayer per concurrent graph)")
-        return layer.circuit.backward(dout.contiguous()), None
+        if ctx.lits:
+            dpos, dneg = layer.circuit.backward(dout.contiguous())
+            return dpos, dneg, None
+        return layer.circuit.backward(dout.contiguous()), None, None
 
 
 class CircuitLayer(torch.nn.Module):
     """``out[B, R] = circuit(weights[B, V])`` with gradients to ``weights`` (float32, CUDA).
 
     ``semiring``: ``KLAY_LOG`` (weights are log-probabilities) or ``KLAY_REAL`` (probabilities);
-    ``KLAY_MAXLOG`` can be evaluated under ``torch.no_grad()`` only.
+    ``KLAY_MAXLOG`` can be evaluated under ``torch.no_grad()`` only.  ``neg_weights`` gives the negated
+    literals weights of their own (default: ``1 - p``, in the log domain ``log(1 - exp(x))``); both
+    arrays then receive gradients.
     """
 
     def __init__(self, circuit: Circuit, semiring: int = KLAY_LOG):
@@ -45,10 +51,13 @@ class CircuitLayer(torch.nn.Module):
         self.semiring = int(semiring)
         self._ticket = 0
 
-    def forward(self, weights):
-        if self.semiring == KLAY_MAXLOG and torch.is_grad_enabled() and weights.requires_grad:
+    def forward(self, weights, neg_weights=None):
+        needs_grad = torch.is_grad_enabled() and (
+            weights.requires_grad or (neg_weights is not None and neg_weights.requires_grad))
+        if self.semiring == KLAY_MAXLOG and needs_grad:
             raise RuntimeError("the (max, +) semiring is not differentiated; evaluate it under torch.no_grad()")
-        if not (torch.is_grad_enabled() and weights.requires_grad):
+        if not needs_grad:
             self._ticket += 1
-            return self.circuit.forward(weights.contiguous(), self.semiring)
-        return _Evaluate.apply(weights, self)
+            return self.circuit.forward(weights.contiguous(), self.semiring,
+                                        neg_weights=None if neg_weights is None else neg_weights.contiguous())
+        return _Evaluate.apply(weights, neg_weights, self)

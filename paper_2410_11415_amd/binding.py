@@ -24,7 +24,7 @@ KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
            "klay_set_profiling", "klay_get_profile", "klay_destroy", "klay_last_error", "klay_builder_create",
-           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy")
+           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy", "klay_forward_lits", "klay_backward_lits")
 
 
 class KlayError(RuntimeError):
@@ -77,6 +77,10 @@ def load():
     lib.klay_forward.argtypes = [vp, vp, i32, vp, ctypes.c_int, vp]
     lib.klay_backward.restype = ctypes.c_int
     lib.klay_backward.argtypes = [vp, vp, vp, vp]
+    lib.klay_forward_lits.restype = ctypes.c_int
+    lib.klay_forward_lits.argtypes = [vp, vp, vp, i32, vp, ctypes.c_int, vp]
+    lib.klay_backward_lits.restype = ctypes.c_int
+    lib.klay_backward_lits.argtypes = [vp, vp, vp, vp, vp]
     lib.klay_info.restype = ctypes.c_int
     lib.klay_info.argtypes = [vp, ctypes.POINTER(klay_info_t)]
     lib.klay_layer_sizes.restype = ctypes.c_int
@@ -143,6 +147,14 @@ def klay_forward(handle, leaf_weights_ptr, B, out_ptr, semiring, stream=0):
 
 def klay_backward(handle, dout_ptr, dleaf_ptr, stream=0):
     _check(load().klay_backward(handle, dout_ptr, dleaf_ptr, stream))
+
+
+def klay_forward_lits(handle, pos_weights_ptr, neg_weights_ptr, B, out_ptr, semiring, stream=0):
+    _check(load().klay_forward_lits(handle, pos_weights_ptr, neg_weights_ptr, B, out_ptr, semiring, stream))
+
+
+def klay_backward_lits(handle, dout_ptr, dpos_ptr, dneg_ptr, stream=0):
+    _check(load().klay_backward_lits(handle, dout_ptr, dpos_ptr, dneg_ptr, stream))
 
 
 def klay_destroy(handle):
@@ -279,36 +291,57 @@ class Circuit:
         s = torch.cuda.current_stream() if stream is None else stream
         return s.cuda_stream
 
-    def forward(self, leaf_weights, semiring=KLAY_LOG, out=None, stream=None):
-        """leaf_weights: torch float32 CUDA tensor [B, V], contiguous.  Returns out [B, R]."""
+    def forward(self, leaf_weights, semiring=KLAY_LOG, out=None, stream=None, neg_weights=None):
+        """leaf_weights: torch float32 CUDA tensor [B, V], contiguous.  Returns out [B, R].
+        neg_weights (same shape) gives the negated literals weights of their own."""
         import torch
-        if leaf_weights.dtype != torch.float32 or not leaf_weights.is_cuda or not leaf_weights.is_contiguous():
-            raise ValueError("leaf_weights must be a contiguous float32 CUDA tensor")
-        if leaf_weights.dim() != 2 or leaf_weights.shape[1] != self.num_vars:
-            raise ValueError("leaf_weights must be [B, %d]" % self.num_vars)
+        for t, name in ((leaf_weights, "leaf_weights"), (neg_weights, "neg_weights")):
+            if t is None:
+                continue
+            if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+                raise ValueError(name + " must be a contiguous float32 CUDA tensor")
+            if t.dim() != 2 or t.shape[1] != self.num_vars:
+                raise ValueError(name + " must be [B, %d]" % self.num_vars)
+        if neg_weights is not None and neg_weights.shape != leaf_weights.shape:
+            raise ValueError("neg_weights must have the shape of leaf_weights")
         B = leaf_weights.shape[0]
         if out is None:
             out = torch.empty((B, self.num_roots), dtype=torch.float32, device=leaf_weights.device)
         elif out.shape != (B, self.num_roots) or out.dtype != torch.float32 or not out.is_contiguous():
             raise ValueError("out must be a contiguous float32 tensor [B, R]")
-        klay_forward(self._h, leaf_weights.data_ptr(), B, out.data_ptr(), int(semiring), self._stream(stream))
+        if neg_weights is None:
+            klay_forward(self._h, leaf_weights.data_ptr(), B, out.data_ptr(), int(semiring), self._stream(stream))
+        else:
+            klay_forward_lits(self._h, leaf_weights.data_ptr(), neg_weights.data_ptr(), B, out.data_ptr(),
+                              int(semiring), self._stream(stream))
         self._last_B = B
+        self._last_lits = neg_weights is not None
         return out
 
-    def backward(self, dout, dleaf=None, stream=None):
-        """dout: [B, R] float32 CUDA.  Returns dleaf [B, V]."""
+    def backward(self, dout, dleaf=None, stream=None, dneg=None):
+        """dout: [B, R] float32 CUDA.  Returns dleaf [B, V]; after a forward pass with neg_weights
+        the pair (dpos, dneg)."""
         import torch
         B = getattr(self, "_last_B", None)
         if B is None:
             raise KlayError(KLAY_ESTATE, "backward before forward")
         if dout.dtype != torch.float32 or not dout.is_cuda or not dout.is_contiguous() or dout.shape != (B, self.num_roots):
             raise ValueError("dout must be a contiguous float32 CUDA tensor [B, R]")
-        if dleaf is None:
-            dleaf = torch.empty((B, self.num_vars), dtype=torch.float32, device=dout.device)
-        elif dleaf.shape != (B, self.num_vars) or dleaf.dtype != torch.float32 or not dleaf.is_contiguous():
-            raise ValueError("dleaf must be a contiguous float32 tensor [B, V]")
-        klay_backward(self._h, dout.data_ptr(), dleaf.data_ptr(), self._stream(stream))
-        return dleaf
+        lits = getattr(self, "_last_lits", False)
+        outs = []
+        for t, name in ((dleaf, "dleaf"), (dneg, "dneg")):
+            if t is None:
+                t = torch.empty((B, self.num_vars), dtype=torch.float32, device=dout.device)
+            elif t.shape != (B, self.num_vars) or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError(name + " must be a contiguous float32 CUDA tensor [B, V]")
+            outs.append(t)
+            if not lits:
+                break
+        if not lits:
+            klay_backward(self._h, dout.data_ptr(), outs[0].data_ptr(), self._stream(stream))
+            return outs[0]
+        klay_backward_lits(self._h, dout.data_ptr(), outs[0].data_ptr(), outs[1].data_ptr(), self._stream(stream))
+        return outs[0], outs[1]
 
     def close(self):
         if self._h is not None:

@@ -112,6 +112,7 @@ struct klay_circuit {
     bool have_fwd = false;
     int32_t last_B = 0;
     int last_semiring = 0;
+    bool last_neg_explicit = false;            // the negated literals had weights of their own
     bool last_ws_has_bwd = false;
     // profiling
     bool profiling = false;
@@ -917,8 +918,8 @@ klay_status klay_get_profile(klay_circuit* c, klay_profile_t* prof) {
     return KLAY_OK;
 }
 
-static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
-                                klay_semiring semiring, void* stream) {
+static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, const float* neg_weights, int32_t B,
+                                float* out, klay_semiring semiring, void* stream) {
     if (!c || !leaf_weights || !out) return fail(KLAY_EINVAL, "klay_forward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_forward: host-only handle (built with device = -1)");
     if (B < 1) return fail(KLAY_EINVAL, "klay_forward: B must be >= 1");
@@ -951,7 +952,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, int3
     prof.begin(KLAY_K_LEAF, 4.0 * B * V + 4.0 * B * (double)(V + p.layers[0].n));
     if (V > 0) {
         dim3 grid((unsigned)((V + 31) / 32), (unsigned)((g.ld + 63) / 64));
-        hipLaunchKernelGGL(klay::leaf_fwd_kernel, grid, dim3(256), 0, s, leaf_weights, (int)B, V, g.ld,
+        hipLaunchKernelGGL(klay::leaf_fwd_kernel, grid, dim3(256), 0, s, leaf_weights, neg_weights, (int)B, V, g.ld,
                            c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);
     }
     if (c->true_row >= 0)
@@ -997,15 +998,20 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, int3
     c->have_fwd = true;
     c->last_B = B;
     c->last_semiring = semiring;
+    c->last_neg_explicit = neg_weights != nullptr;
     c->last_ws_has_bwd = with_bwd;
     c->last_tail_first = tail.first;
     return KLAY_OK;
 }
 
-static klay_status backward_impl(klay_circuit* c, const float* dout, float* dleaf, void* stream) {
+static klay_status backward_impl(klay_circuit* c, const float* dout, float* dleaf, float* dneg, bool lits,
+                                 void* stream) {
     if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward: host-only handle");
     if (!c->have_fwd) return fail(KLAY_ESTATE, "klay_backward: no forward pass to differentiate");
+    if (lits != c->last_neg_explicit)
+        return fail(KLAY_ESTATE, lits ? "klay_backward_lits: the forward pass was not run by klay_forward_lits with neg_weights"
+                                      : "klay_backward: the forward pass had weights for the negated literals; use klay_backward_lits");
     if (c->last_semiring == KLAY_MAXLOG)
         return fail(KLAY_EINVAL, "klay_backward: the (max, +) semiring is not differentiated");
     const bool real = c->last_semiring == KLAY_REAL;
@@ -1059,7 +1065,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (V > 0) {
             dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
             hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B, V,
-                               g.ld, 0, dleaf);
+                               g.ld, lits ? 2 : 0, dleaf, dneg);
         }
         prof.end();
         KLAY_HIP(hipGetLastError());
@@ -1088,7 +1094,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (V > 0) {
             dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
             hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B, V,
-                               g.ld, 1, dleaf);
+                               g.ld, lits ? 2 : 1, dleaf, dneg);
         }
         prof.end();
         KLAY_HIP(hipGetLastError());
@@ -1130,7 +1136,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     if (V > 0) {
         dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
         hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B,
-                           V, g.ld, 1, dleaf);
+                           V, g.ld, lits ? 2 : 1, dleaf, dneg);
     }
     prof.end();
     KLAY_HIP(hipGetLastError());
@@ -1141,8 +1147,13 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
 // the index arrays of the real-semiring reverse sweep) report KLAY_ENOMEM instead.
 klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
                          klay_semiring semiring, void* stream) {
+    return klay_forward_lits(c, leaf_weights, nullptr, B, out, semiring, stream);
+}
+
+klay_status klay_forward_lits(klay_circuit* c, const float* pos_weights, const float* neg_weights, int32_t B,
+                              float* out, klay_semiring semiring, void* stream) {
     try {
-        return forward_impl(c, leaf_weights, B, out, semiring, stream);
+        return forward_impl(c, pos_weights, neg_weights, B, out, semiring, stream);
     } catch (const std::bad_alloc&) {
         if (c) c->have_fwd = false;
         return fail(KLAY_ENOMEM, "klay_forward: out of host memory");
@@ -1151,9 +1162,17 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
 
 klay_status klay_backward(klay_circuit* c, const float* dout, float* dleaf, void* stream) {
     try {
-        return backward_impl(c, dout, dleaf, stream);
+        return backward_impl(c, dout, dleaf, nullptr, false, stream);
     } catch (const std::bad_alloc&) {
         return fail(KLAY_ENOMEM, "klay_backward: out of host memory");
+    }
+}
+
+klay_status klay_backward_lits(klay_circuit* c, const float* dout, float* dpos, float* dneg, void* stream) {
+    try {
+        return backward_impl(c, dout, dpos, dneg, true, stream);
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_backward_lits: out of host memory");
     }
 }
 

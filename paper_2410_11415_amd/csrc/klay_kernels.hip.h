@@ -601,18 +601,25 @@ __device__ __forceinline__ float log1mexp_f(float x) {
     return x > -0.69314718f ? logf(-expm1f(x)) : log1pf(-expf(x));
 }
 
-__global__ __launch_bounds__(256) void leaf_fwd_kernel(const float* __restrict__ w, int B, int V, int ld,
+// Leaf layer: transposes leaf weights [B, V] into rows [*, ld] through an LDS tile.  The negated
+// literal of v gets wneg[b, v] when the caller supplies weights of its own for the negated literals,
+// otherwise 1 - w (real semiring) or log(1 - exp(w)) (log domain).
+__global__ __launch_bounds__(256) void leaf_fwd_kernel(const float* __restrict__ w, const float* __restrict__ wneg,
+                                                       int B, int V, int ld,
                                                        const int32_t* __restrict__ pos_row,
                                                        const int32_t* __restrict__ neg_row,
                                                        float* __restrict__ wT, float* __restrict__ act0,
                                                        int log_domain) {
     __shared__ float tile[32][65];
+    __shared__ float tile_neg[32][65];
     const int v0 = blockIdx.x * 32, b0 = blockIdx.y * 64;
     {
         const int vx = threadIdx.x & 31, by = threadIdx.x >> 5;
         for (int k = 0; k < 8; ++k) {
             const int b = b0 + by + 8 * k, v = v0 + vx;
-            tile[vx][by + 8 * k] = (b < B && v < V) ? w[(size_t)b * V + v] : 0.0f;
+            const bool in = b < B && v < V;
+            tile[vx][by + 8 * k] = in ? w[(size_t)b * V + v] : 0.0f;
+            if (wneg) tile_neg[vx][by + 8 * k] = in ? wneg[(size_t)b * V + v] : 0.0f;
         }
     }
     __syncthreads();
@@ -626,7 +633,13 @@ __global__ __launch_bounds__(256) void leaf_fwd_kernel(const float* __restrict__
         wT[(size_t)v * ld + b] = x;
         const int pr = pos_row[v], nr = neg_row[v];
         if (pr >= 0) act0[(size_t)pr * ld + b] = x;
-        if (nr >= 0) act0[(size_t)nr * ld + b] = (b >= B) ? 0.0f : (log_domain ? log1mexp_f(x) : 1.0f - x);
+        if (nr >= 0) {
+            float y;
+            if (b >= B) y = 0.0f;
+            else if (wneg) y = tile_neg[vy + 4 * k][bx];
+            else y = log_domain ? log1mexp_f(x) : 1.0f - x;
+            act0[(size_t)nr * ld + b] = y;
+        }
     }
 }
 
@@ -663,34 +676,43 @@ __global__ void seed_rows_kernel(const float* __restrict__ dout, int B, int R, i
 }
 
 // dleaf[b, v] = G0[+v, b] + G0[-v, b] * d(negated weight)/d(weight); tile transposed through LDS.
+// mode 0: negated weight 1 - w, mode 1: log(1 - exp(w)), mode 2: the negated literals have weights
+// of their own, so dleaf holds G0[+v, b] and dneg (may be null) receives G0[-v, b].
 __global__ __launch_bounds__(256) void leaf_bwd_kernel(const float* __restrict__ g0, const float* __restrict__ wT,
                                                        const int32_t* __restrict__ pos_row,
                                                        const int32_t* __restrict__ neg_row, int B, int V,
-                                                       int ld, int log_domain, float* __restrict__ dleaf) {
+                                                       int ld, int mode, float* __restrict__ dleaf,
+                                                       float* __restrict__ dneg) {
     __shared__ float tile[32][65];
+    __shared__ float tile_neg[32][65];
     const int v0 = blockIdx.x * 32, b0 = blockIdx.y * 64;
     {
         const int bx = threadIdx.x & 63, vy = threadIdx.x >> 6;
         const int b = b0 + bx;
         for (int k = 0; k < 8; ++k) {
             const int v = v0 + vy + 4 * k;
-            float d = 0.0f;
+            float d = 0.0f, dn = 0.0f;
             if (v < V && b < B) {
                 const int pr = pos_row[v], nr = neg_row[v];
                 if (pr >= 0) d = g0[(size_t)pr * ld + b];
                 if (nr >= 0) {
                     const float gn = g0[(size_t)nr * ld + b];
-                    if (gn != 0.0f) d += log_domain ? -gn / expm1f(-wT[(size_t)v * ld + b]) : -gn;
+                    if (mode == 2) dn = gn;
+                    else if (gn != 0.0f) d += mode == 1 ? -gn / expm1f(-wT[(size_t)v * ld + b]) : -gn;
                 }
             }
             tile[vy + 4 * k][bx] = d;
+            tile_neg[vy + 4 * k][bx] = dn;
         }
     }
     __syncthreads();
     const int vx = threadIdx.x & 31, by = threadIdx.x >> 5;
     for (int k = 0; k < 8; ++k) {
         const int b = b0 + by + 8 * k, v = v0 + vx;
-        if (b < B && v < V) dleaf[(size_t)b * V + v] = tile[vx][by + 8 * k];
+        if (b < B && v < V) {
+            dleaf[(size_t)b * V + v] = tile[vx][by + 8 * k];
+            if (mode == 2 && dneg) dneg[(size_t)b * V + v] = tile_neg[vx][by + 8 * k];
+        }
     }
 }
 

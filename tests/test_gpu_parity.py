@@ -615,3 +615,87 @@ def test_circuit_layer_backpropagates_into_a_network(klay):
         m = klay.CircuitLayer(k, klay.KLAY_MAXLOG)(w.detach())
     assert torch.all(m <= out.detach() + 1e-4)
     k.close()
+
+
+# ------------------------------------------------------------------ weights of their own for the negated literals
+def _lits_case(klay, c, B, seed, semirings=(REAL, LOG), **kw):
+    import torch
+    from tests.gpu_util import GradRef, U32
+    from oracle import oracle
+    rng = np.random.default_rng(seed)
+    V, R = c.num_vars, c.roots.shape[0]
+    wp = rng.uniform(0.2, 1.0, size=(B, V)).astype(np.float32)
+    wn = rng.uniform(0.2, 1.0, size=(B, V)).astype(np.float32)
+    dout = rng.normal(size=(B, R)).astype(np.float32)
+    k = build(klay, c, **kw)
+    levels = k.num_layers // 2
+    for s in semirings:
+        a, b = (wp, wn) if s == REAL else (np.log(wp), np.log(wn))
+        ta, tb, td = (torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in (a, b, dout))
+        out = k.forward(ta, s, neg_weights=tb)
+        can_bwd = s == LOG or not kw.get("alias_chains")
+        if can_bwd:
+            dp, dn = (t.cpu().numpy() for t in k.backward(td))
+        got = out.cpu().numpy()
+        a64, b64, d64 = a.astype(np.float64), b.astype(np.float64), dout.astype(np.float64)
+        with np.errstate(all="ignore"):
+            ref, vals = oracle.forward(*c.arrays(), a64, s, nthreads=8, return_node_values=True, neg_weights=b64)
+        (assert_log_close if s == LOG else assert_real_close)(got, ref, "lits")
+        if not can_bwd:
+            continue
+        with np.errstate(all="ignore"):
+            rp, rn = oracle.backward(*c.arrays(), a64, s, d64, nthreads=8, neg_weights=b64)
+            mp, mn = oracle.backward(*c.arrays(), a64, s, d64, nthreads=8, neg_weights=b64, path_mass=True)
+        fin = np.isfinite(vals)
+        maxabs = float(np.abs(vals[fin]).max())
+        rel = 64 * U32 + 4 * U32 * levels * maxabs if s == LOG else (64 + 16 * levels) * U32
+        assert_grad_close(dp, GradRef(rp, mp, rel), "lits dpos", real=(s == REAL))
+        assert_grad_close(dn, GradRef(rn, mn, rel), "lits dneg", real=(s == REAL))
+    # (max, +) forward with the same weights
+    ta, tb = (torch.from_numpy(np.ascontiguousarray(np.log(x))).cuda() for x in (wp, wn))
+    got = k.forward(ta, MAXLOG, neg_weights=tb).cpu().numpy()
+    ref = oracle.forward(*c.arrays(), np.log(wp).astype(np.float64), oracle.MAXLOG, nthreads=8,
+                         neg_weights=np.log(wn).astype(np.float64))
+    assert_log_close(got, ref, "lits maxlog")
+    k.close()
+
+
+def test_negative_literal_weights(klay, golden):
+    for B in (1, 5, 70):
+        _lits_case(klay, golden("fig1b_ddnnf.txt"), B, seed=B)
+    c = layered_random(9, num_vars=32, depth=10, num_gates=3000, fanin=("geom", 2.0), groups=2, num_roots=9)
+    for B in (3, 70, 300):
+        _lits_case(klay, c, B, seed=10 + B)
+    _lits_case(klay, c, 130, seed=1, no_tail=True)
+    _lits_case(klay, c, 130, seed=2, alias_chains=True)
+
+
+def test_negative_literal_weights_default_and_call_pairing(klay):
+    """1 - p passed explicitly gives the default's values; each forward flavour has its own backward"""
+    import torch
+    c = layered_random(9, num_vars=32, depth=10, num_gates=3000, fanin=("geom", 2.0), groups=2, num_roots=9)
+    k = build(klay, c)
+    p = torch.rand(40, 32, device="cuda") * 0.8 + 0.1
+    a = k.forward(p, REAL)
+    b = k.forward(p, REAL, neg_weights=(1 - p).contiguous())
+    assert torch.equal(a, b)
+    d = torch.ones(40, 9, device="cuda")
+    with pytest.raises(klay.KlayError) as e:
+        klay.klay_backward(k._h, d.data_ptr(), torch.empty(40, 32, device="cuda").data_ptr())
+    assert e.value.status == 5
+    dp, dn = k.backward(d)
+    k.forward(p, REAL)
+    g = k.backward(d)
+    torch.testing.assert_close(g, dp - dn, rtol=1e-4, atol=1e-6)
+    with pytest.raises(klay.KlayError) as e:
+        klay.klay_backward_lits(k._h, d.data_ptr(), dp.data_ptr(), dn.data_ptr())
+    assert e.value.status == 5
+    # the torch layer differentiates both arrays
+    layer = klay.CircuitLayer(k, klay.KLAY_LOG)
+    lp = torch.log(p).requires_grad_(True)
+    ln = torch.log(1 - p).requires_grad_(True)
+    layer(lp, ln).sum().backward()
+    k.forward(torch.log(p), LOG, neg_weights=torch.log(1 - p))
+    rp, rn = k.backward(d)
+    assert torch.equal(lp.grad, rp) and torch.equal(ln.grad, rn)
+    k.close()
