@@ -235,6 +235,12 @@ class Circuit:
         from .sdd import load_sdd
         return cls(*load_sdd(path, num_vars), **kw)
 
+    @classmethod
+    def from_d4(cls, path: str, num_vars=None, **kw):
+        """Build from a d4 decision-DNNF text file (see :mod:`.d4`)."""
+        from .d4 import load_d4
+        return cls(*load_d4(path, num_vars), **kw)
+
     # -- inspection
     def info(self) -> dict:
         s = klay_info_t()
