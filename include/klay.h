@@ -193,6 +193,13 @@ klay_status klay_layer_csr(const klay_circuit* c, int32_t layer, int64_t* row_pt
  */
 klay_status klay_layer_nodes(const klay_circuit* c, int32_t layer, int32_t* origin, uint8_t* is_pad);
 
+/*
+ * position[r] (host array of num_roots entries) = row of the top layer L that holds roots[r]'s value
+ * (Section 3.2: all roots sit in the last layer); with alias_chains the row of the whole activation
+ * buffer, as for klay_layer_csr.
+ */
+klay_status klay_root_positions(const klay_circuit* c, int32_t* position);
+
 /* Bytes of device workspace a forward (and, if need_backward, backward) call with batch B needs. */
 size_t klay_workspace_bytes(const klay_circuit* c, int32_t B, int need_backward);
 

@@ -24,7 +24,7 @@ KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
            "klay_set_profiling", "klay_get_profile", "klay_destroy", "klay_last_error", "klay_builder_create",
-           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy", "klay_forward_lits", "klay_backward_lits")
+           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy", "klay_forward_lits", "klay_backward_lits", "klay_root_positions")
 
 
 class KlayError(RuntimeError):
@@ -89,6 +89,8 @@ def load():
     lib.klay_layer_csr.argtypes = [vp, i32, vp, vp]
     lib.klay_layer_nodes.restype = ctypes.c_int
     lib.klay_layer_nodes.argtypes = [vp, i32, vp, vp]
+    lib.klay_root_positions.restype = ctypes.c_int
+    lib.klay_root_positions.argtypes = [vp, vp]
     lib.klay_workspace_bytes.restype = ctypes.c_size_t
     lib.klay_workspace_bytes.argtypes = [vp, i32, ctypes.c_int]
     lib.klay_set_workspace.restype = ctypes.c_int
@@ -269,6 +271,11 @@ class Circuit:
         is_pad = np.zeros(max(int(nodes[layer]), 1), dtype=np.uint8)
         _check(load().klay_layer_nodes(self._h, layer, _np_ptr(origin), _np_ptr(is_pad)))
         return origin[: int(nodes[layer])], is_pad[: int(nodes[layer])].astype(bool)
+
+    def root_positions(self):
+        pos = np.zeros(self.num_roots, dtype=np.int32)
+        _check(load().klay_root_positions(self._h, _np_ptr(pos)))
+        return pos
 
     def workspace_bytes(self, B: int, need_backward: bool = True) -> int:
         return int(load().klay_workspace_bytes(self._h, int(B), int(need_backward)))

@@ -878,6 +878,12 @@ klay_status klay_layer_nodes(const klay_circuit* c, int32_t layer, int32_t* orig
     return KLAY_OK;
 }
 
+klay_status klay_root_positions(const klay_circuit* c, int32_t* position) {
+    if (!c || !position) return fail(KLAY_EINVAL, "klay_root_positions: null argument");
+    std::copy(c->plan.root_pos.begin(), c->plan.root_pos.end(), position);
+    return KLAY_OK;
+}
+
 size_t klay_workspace_bytes(const klay_circuit* c, int32_t B, int need_backward) {
     if (!c || B < 1) return 0;
     return workspace_layout(c, B, need_backward != 0).total * sizeof(float);

@@ -381,3 +381,67 @@ def test_builder_rejects_bad_input_and_stays_usable():
     with pytest.raises(KlayError) as e:
         bld.finish(device=-1)
     assert e.value.status == KLAY_EINVAL
+
+
+# ---------------------------------------------------------------- the index vectors evaluate to the circuit
+def eval_layered(c, k, w, semiring):
+    """Alg. 1 (real) / Alg. 4 (log, epsilon = 0) in numpy, on the index vectors the library built:
+    E_l = N_{l-1}[S_l]; N_l = scatter(E_l, R_l, sum / product / logsumexp), then the root rows.
+    With alias_chains the child entries index the concatenation of all layers so far."""
+    from klay_synth import FALSE, TRUE
+    log = semiring == 1
+    nodes, _ = k.layer_sizes()
+    origin, _ = k.layer_nodes(0)
+    B = w.shape[0]
+    N = np.empty((len(origin), B))
+    for i, o in enumerate(origin):
+        t = c.node_type[o]
+        if t == LIT:
+            l = int(c.node_lit[o]); x = w[:, abs(l) - 1]
+            with np.errstate(divide="ignore"):
+                N[i] = x if l > 0 else (np.log(-np.expm1(x)) if log else 1 - x)
+        elif t == TRUE:
+            N[i] = 0.0 if log else 1.0
+        else:
+            assert t == FALSE
+            N[i] = -np.inf if log else 0.0
+    whole = N
+    for l in range(1, k.num_layers + 1):
+        row_ptr, S = k.layer_csr(l)
+        R = np.repeat(np.arange(nodes[l]), np.diff(row_ptr))
+        src = whole if k._alias else N
+        E = src[S]
+        is_and = l % 2 == 1
+        if not log:
+            out = np.ones((nodes[l], B)) if is_and else np.zeros((nodes[l], B))
+            (np.multiply if is_and else np.add).at(out, R, E)
+        elif is_and:
+            out = np.zeros((nodes[l], B)); np.add.at(out, R, E)
+        else:
+            M = np.full((nodes[l], B), -np.inf); np.maximum.at(M, R, E)
+            with np.errstate(invalid="ignore", divide="ignore"):
+                T = np.zeros((nodes[l], B)); np.add.at(T, R, np.where(np.isneginf(E), 0.0, np.exp(E - M[R])))
+                out = np.where(np.isneginf(M), -np.inf, np.log(T) + M)
+        N = out
+        whole = np.concatenate([whole, N], axis=0)
+    pos = k.root_positions()
+    return (whole if k._alias else N)[pos].T
+
+
+@pytest.mark.parametrize("opts", [dict(), dict(no_merge=True), dict(no_reorder=True), dict(alias_chains=True),
+                                  dict(heavy_fan=2, min_segment=1)])
+def test_index_vectors_evaluate_to_the_oracle_values(golden, opts):
+    """host check of klay_build end to end: the per-layer index vectors, run through the paper's
+    Alg. 1 / Alg. 4 in numpy, give the oracle's root values"""
+    from klay_synth import leaf_probs
+    from oracle import oracle
+    cases = [golden("fig1b_ddnnf.txt"), golden("fig3_multiroot.txt"), golden("appD_mnist_add.txt"), tiny_ddnnf(3, 12, 30)[0],
+             layered_random(4, num_vars=48, depth=8, num_gates=1500, fanin=("geom", 2.0), groups=2, num_roots=7),
+             layered_random(2, num_vars=64, depth=6, num_gates=600, fanin=("zipf", 1.3, 200), groups=1, num_roots=5)]
+    for c in cases:
+        k = host(c, **opts)
+        k._alias = bool(opts.get("alias_chains"))
+        p = leaf_probs(1, 3, c.num_vars, ("uniform", 0.05, 0.95))
+        np.testing.assert_allclose(eval_layered(c, k, p, 0), oracle.forward(*c.arrays(), p, 0), rtol=1e-11)
+        np.testing.assert_allclose(eval_layered(c, k, np.log(p), 1), oracle.forward(*c.arrays(), np.log(p), 1),
+                                   rtol=0, atol=1e-10)
