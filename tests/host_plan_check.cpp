@@ -1,0 +1,197 @@
+// Host check of the launch plans klay_build hands to the kernels, with no GPU: random DAGs are
+// layerized with many option sets and every pass plan (main rows as tasks, segments of split rows,
+// combine lists) is executed here in plain C++ on integer "values", in the same order of steps the
+// device kernels take, and compared with the sums over the plain per-layer index vectors
+// (paper Section 4: E_l = N_{l-1}[S_l], N_l = scatter(E_l, R_l)).  Built with the address and
+// undefined-behaviour sanitizers by tests/test_host_plans.py.
+#include <cstdio>
+#include <cstdlib>
+#include <random>
+#include <string>
+#include <vector>
+
+#include "../paper_2410_11415_amd/csrc/layerize.h"
+
+using klay::PassPlan;
+using u64 = unsigned long long;
+
+static u64 mix(u64 x) { x += 0x9E3779B97F4A7C15ull; x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull; x = (x ^ (x >> 27)) * 0x94D049BB133111EBull; return x ^ (x >> 31); }
+static constexpr uint32_t kMask = 0x3FFFFFFFu;
+
+#define CHECK(cond, ...) do { if (!(cond)) { std::printf("FAILED %s:%d: ", __FILE__, __LINE__); std::printf(__VA_ARGS__); std::printf("\n"); std::exit(1); } } while (0)
+
+// value of source row i, and weight tag of an entry (so that a wrong weighted flag changes the sum)
+static u64 val(int64_t i) { return mix((u64)i); }
+static u64 entry(uint32_t id) { return val(id & kMask) * ((id & klay::kWeightedEdge) ? 3u : 1u); }
+
+// the walk of the streaming kernel over a task list: rows advance on the end-of-row bit
+static void walk_tasks(const PassPlan& p, const std::vector<int32_t>& tasks, int n_tasks, int64_t n_src,
+                       std::vector<u64>& out, std::vector<int>& written, int64_t row_shift) {
+    CHECK((int)tasks.size() == 2 * (n_tasks + 1), "task array size");
+    for (int t = 0; t < n_tasks; ++t) {
+        int row = tasks[2 * t], j = tasks[2 * t + 1];
+        const int row_end = tasks[2 * t + 2], e1 = tasks[2 * t + 3];
+        CHECK(j < e1 && row < row_end, "empty task %d", t);
+        u64 acc = 0;
+        for (; j < e1; ++j) {
+            const uint32_t id = p.idx[(size_t)j];
+            if (id == klay::kSkipRow) { CHECK(acc == 0, "skip entry inside a row"); ++row; continue; }
+            CHECK((int64_t)(id & kMask) < n_src, "source %u out of range %lld", id & kMask, (long long)n_src);
+            acc += entry(id);
+            if (id & klay::kLastEdge) {
+                CHECK(row - row_shift >= 0 && row - row_shift < (int64_t)out.size(), "row out of range");
+                out[(size_t)(row - row_shift)] = acc; ++written[(size_t)(row - row_shift)];
+                acc = 0; ++row;
+            }
+        }
+        CHECK(acc == 0, "task %d ends inside a row", t);
+        CHECK(row == row_end, "task %d covers rows up to %d, next task starts at %d", t, row, row_end);
+    }
+}
+
+// the walk of the generic kernel: rows by ptr
+static void walk_rows(const PassPlan& p, int row_begin, int row_end, int64_t n_src, std::vector<u64>& main_out,
+                      std::vector<int>& main_written, std::vector<u64>& seg_out, std::vector<int>& seg_written) {
+    for (int row = row_begin; row < row_end; ++row) {
+        const int beg = p.ptr[(size_t)row], end = p.ptr[(size_t)row + 1];
+        CHECK(end > beg, "empty row %d", row);
+        if (p.idx[(size_t)beg] == klay::kSkipRow) { CHECK(end == beg + 1 && row < p.n_main, "skip row shape"); continue; }
+        u64 acc = 0;
+        for (int j = beg; j < end; ++j) {
+            const uint32_t id = p.idx[(size_t)j];
+            CHECK((int64_t)(id & kMask) < n_src, "source out of range");
+            CHECK(((id & klay::kLastEdge) != 0) == (j == end - 1), "end-of-row bit of row %d", row);
+            acc += entry(id);
+        }
+        if (row < p.n_main) { main_out[(size_t)row] = acc; ++main_written[(size_t)row]; }
+        else { seg_out[(size_t)(row - p.n_main)] = acc; ++seg_written[(size_t)(row - p.n_main)]; }
+    }
+}
+
+// runs one plan both ways and compares with `want` (one value per output row)
+static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what) {
+    CHECK(p.n_main == n_out, "%s: n_main", what);
+    CHECK((int64_t)p.ptr.size() == (int64_t)p.n_main + p.n_seg + 1, "%s: ptr size", what);
+    const int64_t entries = p.ptr.back();
+    CHECK((int64_t)p.idx.size() == entries + klay::kIdxPad, "%s: idx size", what);
+    for (int i = 0; i < klay::kIdxPad; ++i) CHECK(p.idx[(size_t)entries + i] == 0u, "%s: idx padding", what);
+    CHECK((int64_t)p.seg_owner.size() == p.n_seg && (int64_t)p.comb_row.size() == p.n_heavy, "%s: sizes", what);
+    if (p.n_heavy > 0) CHECK((int64_t)p.comb_idx.size() == (int64_t)p.n_seg + klay::kIdxPad, "%s: comb_idx size", what);
+    else CHECK(p.n_seg == 0, "%s: segments without split rows", what);
+    for (int variant = 0; variant < 2; ++variant) {
+        std::vector<u64> out((size_t)n_out, 0), seg((size_t)p.n_seg, 0);
+        std::vector<int> wr((size_t)n_out, 0), swr((size_t)p.n_seg, 0);
+        if (variant == 0) {
+            walk_tasks(p, p.tasks, p.n_tasks, n_src, out, wr, 0);
+            if (p.n_seg > 0) walk_tasks(p, p.seg_tasks, p.n_seg_tasks, n_src, seg, swr, p.n_main);
+        } else {
+            walk_rows(p, 0, p.n_main + p.n_seg, n_src, out, wr, seg, swr);
+        }
+        for (int s = 0; s < p.n_seg; ++s) CHECK(swr[(size_t)s] == 1, "%s: segment %d written %d times", what, s, swr[(size_t)s]);
+        std::vector<int> seg_used((size_t)p.n_seg, 0);
+        for (int h = 0; h < p.n_heavy; ++h) {
+            const int row = p.comb_row[(size_t)h];
+            CHECK(row >= 0 && row < n_out && wr[(size_t)row] == 0, "%s: split row %d also written by the main pass", what, row);
+            u64 acc = 0;
+            for (int j = p.comb_ptr[(size_t)h]; j < p.comb_ptr[(size_t)h + 1]; ++j) {
+                const uint32_t s = p.comb_idx[(size_t)j] & kMask;
+                CHECK((int)s < p.n_seg && p.seg_owner[(size_t)s] == row, "%s: segment %u of split row %d", what, s, row);
+                acc += seg[(size_t)s]; ++seg_used[(size_t)s];
+            }
+            out[(size_t)row] = acc; ++wr[(size_t)row];
+        }
+        for (int s = 0; s < p.n_seg; ++s) CHECK(seg_used[(size_t)s] == 1, "%s: segment %d combined %d times", what, s, seg_used[(size_t)s]);
+        for (int64_t i = 0; i < n_out; ++i) {
+            CHECK(wr[(size_t)i] == 1, "%s: row %lld written %d times (variant %d)", what, (long long)i, wr[(size_t)i], variant);
+            CHECK(out[(size_t)i] == want[(size_t)i], "%s: row %lld value (variant %d)", what, (long long)i, variant);
+        }
+    }
+}
+
+int main(int argc, char** argv) {
+    const int trials = argc > 1 ? std::atoi(argv[1]) : 120;
+    std::mt19937_64 rng(12345);
+    long plans = 0;
+    for (int trial = 0; trial < trials; ++trial) {
+        const int V = 1 + (int)(rng() % 12), nl = 2 * V;
+        const int ng = 1 + (int)(rng() % 400);
+        const int N = nl + 2 + ng;
+        std::vector<uint8_t> type((size_t)N);
+        std::vector<int32_t> lit((size_t)N, 0), idx;
+        std::vector<int64_t> ptr((size_t)N + 1, 0);
+        for (int v = 0; v < V; ++v) { type[2 * v] = 0; lit[2 * v] = v + 1; type[2 * v + 1] = 0; lit[2 * v + 1] = -(v + 1); }
+        type[(size_t)nl] = 3; type[(size_t)nl + 1] = 4;
+        for (int g = 0; g < ng; ++g) {
+            const int id = nl + 2 + g;
+            type[(size_t)id] = (uint8_t)(1 + rng() % 2);
+            const int k = 1 + (int)(rng() % (trial % 5 == 0 ? 150 : 5));
+            std::vector<int> kids;
+            for (int j = 0; j < k; ++j) {
+                // a few hub nodes give rows of high fan-out
+                const int c = (rng() % 4 == 0) ? (int)(rng() % (nl < 6 ? nl : 6)) : (int)(rng() % id);
+                bool dup = false;
+                for (int x : kids) dup |= x == c;
+                if (!dup) kids.push_back(c);
+            }
+            for (int c : kids) idx.push_back(c);
+            ptr[(size_t)id + 1] = (int64_t)idx.size();
+        }
+        for (int i = 0; i < nl + 2; ++i) ptr[(size_t)i + 1] = 0;
+        for (int g = 0; g < ng; ++g) if (ptr[(size_t)nl + 2 + g + 1] < ptr[(size_t)nl + 2 + g]) ptr[(size_t)nl + 2 + g + 1] = ptr[(size_t)nl + 2 + g];
+        const int R = 1 + (int)(rng() % 4);
+        std::vector<int32_t> roots((size_t)R);
+        for (auto& r : roots) r = (int32_t)(rng() % N);
+        for (int mode = 0; mode < 8; ++mode) {
+            klay::Options o;
+            o.alias_chains = mode & 1; o.no_merge = mode & 2; o.no_reorder = mode & 4;
+            o.heavy_fan = 1 + (int)(rng() % 40); o.min_segment = 1 + (int)(rng() % 8);
+            klay::CircuitPlan plan;
+            std::string err;
+            const int st = klay::layerize(V, N, type.data(), lit.data(), ptr.data(), idx.data(), R, roots.data(), o, plan, err);
+            if (st == 1) continue;                  // a repeated literal child after leaf merging: rejected input
+            CHECK(st == 0, "layerize status %d: %s", st, err.c_str());
+            const int L = plan.num_layers;
+            if (!plan.alias) {
+                for (int l = 1; l <= L; ++l) {
+                    const klay::LayerPlan& lay = plan.layers[(size_t)l];
+                    const int64_t nb = plan.layers[(size_t)l - 1].n;
+                    std::vector<u64> fwd((size_t)lay.n, 0), bwd((size_t)nb, 0);
+                    for (int64_t r = 0; r < lay.n; ++r) {
+                        const bool weighted = (l % 2 == 0) && lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1;
+                        for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
+                            fwd[(size_t)r] += val(lay.child[(size_t)j]);
+                            bwd[(size_t)lay.child[(size_t)j]] += val(r) * (weighted ? 3u : 1u);
+                        }
+                    }
+                    check_plan(lay.fwd, lay.n, nb, fwd, "forward plan"); ++plans;
+                    check_plan(lay.bwd, nb, lay.n, bwd, "backward plan"); ++plans;
+                }
+            } else {
+                const int64_t NR = plan.row0[(size_t)L + 1];
+                std::vector<u64> adj((size_t)NR, 0);
+                for (int l = 1; l <= L; ++l) {
+                    const klay::LayerPlan& lay = plan.layers[(size_t)l];
+                    std::vector<u64> fwd((size_t)lay.n, 0);
+                    for (int64_t r = 0; r < lay.n; ++r) {
+                        const bool weighted = (l % 2 == 0) && lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1;
+                        for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
+                            const int32_t ch = lay.child[(size_t)j];
+                            CHECK(ch < plan.row0[(size_t)l], "alias child must sit in a lower layer");
+                            fwd[(size_t)r] += val(ch);
+                            adj[(size_t)ch] += val(plan.row0[(size_t)l] + r) * (weighted ? 3u : 1u);
+                        }
+                    }
+                    check_plan(lay.fwd, lay.n, plan.row0[(size_t)l], fwd, "alias forward plan"); ++plans;
+                }
+                for (int r = 0; r < R; ++r) adj[(size_t)plan.root_pos[(size_t)r]] += val(NR + r);
+                for (int l = 0; l <= L; ++l) {
+                    const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;
+                    std::vector<u64> want(adj.begin() + a, adj.begin() + a + n);
+                    check_plan(l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd, n, NR + R, want, "alias backward plan"); ++plans;
+                }
+            }
+        }
+    }
+    std::printf("ok: %ld plans checked\n", plans);
+    return 0;
+}
