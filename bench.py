@@ -33,6 +33,13 @@ MEASURED_TRAFFIC_PER_LAUNCH = {
 }
 
 
+# HBM bytes of a whole step from the same counter runs (sum over all dispatches of one step), keyed by
+# (workload, batch, forward+backward?, alias_chains?)
+MEASURED_TRAFFIC_PER_STEP = {
+    ("layered_3m_fwd_bwd", 256, True, False): 27.1e9,
+}
+
+
 class HipEvents:
     """hipEvent timing on an explicit stream, straight from the HIP runtime."""
 
@@ -209,6 +216,15 @@ def main():
     achieved = d["alg_bytes"] / (d["ms"] * 1e-3) / 1e9 if d["ms"] > 0 else 0.0
     kernel_ms_total = sum(c["ms"] for c in classes.values()) / prof_steps
     alg_bytes_step = sum(c["alg_bytes"] for c in classes.values()) / prof_steps
+    # compulsory bytes: every row written once and read once per consuming sweep (forward: all rows but
+    # the top layer's; backward: adjoint rows written and read once, value rows read once), plus indices
+    n_top = k.layer_sizes()[0][-1]
+    compulsory = 4.0 * B * (2 * N - n_top) + 4.0 * (E + N)
+    if backward:
+        compulsory += 4.0 * B * 3 * N + 4.0 * (E + N)
+    step_traffic = MEASURED_TRAFFIC_PER_STEP.get((args.workload, B, backward, bool(args.alias_chains)))
+    if semiring != pkg.KLAY_LOG or args.no_tail:
+        step_traffic = None
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -218,7 +234,12 @@ def main():
         "kernel_alg_bytes_per_launch": round(d["alg_bytes"] / max(1, d["launches"])),
         "whole_step": {"alg_bytes": round(alg_bytes_step), "kernel_ms": round(kernel_ms_total, 3),
                        "achieved_GBs": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
-                       "frac": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                       "frac": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "compulsory_bytes": round(compulsory),
+                       "compulsory_frac": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "measured_traffic_bytes": step_traffic,
+                       "measured_traffic_frac": None if step_traffic is None else
+                       round(step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "per_class_ms": {n: round(c["ms"] / prof_steps, 3) for n, c in classes.items() if c["launches"]},
     }
 
