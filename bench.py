@@ -83,6 +83,8 @@ def main():
                     help="capture one step in a HIP graph (torch.cuda.graph) and time its replays")
     ap.add_argument("--alias-chains", action="store_true",
                     help="padding-free evaluation: no unary chain nodes, edges read the child's own row")
+    ap.add_argument("--f64", action="store_true",
+                    help="also time the double-precision kernels on the same workload (extra object \"f64\")")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="first run 5 plain device-to-device copies of this many MiB (calibrates the "
@@ -294,6 +296,31 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }
+    if args.f64:
+        # the double-precision accuracy build: same launch plans, 8-byte values (not profiled per class)
+        w64 = w.double()
+        d64 = torch.ones((B, k.num_roots), dtype=torch.float64, device="cuda")
+        bwd64 = backward and semiring == pkg.KLAY_LOG
+
+        def step64():
+            o = k.forward_f64(w64, semiring)
+            if bwd64:
+                k.backward_f64(d64)
+            return o
+        for _ in range(2):
+            o64 = step64()
+        torch.cuda.synchronize()
+        n64 = max(2, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(n64):
+            step64()
+        torch.cuda.synchronize()
+        t64 = (time.perf_counter() - t0) / n64
+        fwd_share = 1.0 if (bwd64 or not backward) else None
+        result["f64"] = {"ms_per_step": t64 * 1e3, "value": B * E / t64, "pass": "forward+backward" if bwd64 else "forward",
+                         "max_abs_diff_fp32_vs_f64": float((out.double() - o64).abs().nan_to_num(0.0).max()),
+                         "achieved_GBs": None if fwd_share is None else round(2 * alg_bytes_step / t64 / 1e9, 1),
+                         "frac": None if fwd_share is None else round(2 * alg_bytes_step / t64 / 1e9 / HBM_PEAK_GBS, 4)}
     if copy_probe:
         result["copy_probe"] = copy_probe
     print(json.dumps(result))

@@ -173,6 +173,23 @@ klay_status klay_forward_lits(klay_circuit* c, const float* pos_weights, const f
                               float* out, klay_semiring semiring, void* stream);
 klay_status klay_backward_lits(klay_circuit* c, const float* dout, float* dpos, float* dneg, void* stream);
 
+/*
+ * klay_forward_f64 / klay_backward_f64 -- the same evaluation in double precision, for circuits whose
+ * log-values outgrow what fp32 resolves and as an on-device accuracy reference for the fp32 kernels.
+ * Same launch plans, a plain (untuned) gather-reduce kernel, the full-precision exp / log.
+ *   pos_weights, neg_weights, out, dout, dpos, dneg   as for klay_forward_lits / klay_backward_lits,
+ *                 in double; neg_weights = NULL derives the negated literals from pos_weights, and
+ *                 dneg must then be NULL as well.
+ * All three semirings are evaluated; only KLAY_LOG is differentiated (KLAY_EINVAL otherwise).
+ * The activations live in a library-owned workspace of their own (klay_set_workspace and
+ * klay_workspace_bytes do not cover it) and are independent of the fp32 state: a handle can hold
+ * one fp32 and one double-precision forward pass at the same time.  Profiling does not cover
+ * these calls.
+ */
+klay_status klay_forward_f64(klay_circuit* c, const double* pos_weights, const double* neg_weights, int32_t B,
+                             double* out, klay_semiring semiring, void* stream);
+klay_status klay_backward_f64(klay_circuit* c, const double* dout, double* dpos, double* dneg, void* stream);
+
 /* Structure of the layered circuit. */
 klay_status klay_info(const klay_circuit* c, klay_info_t* info);
 

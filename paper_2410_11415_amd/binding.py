@@ -24,7 +24,8 @@ KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
            "klay_set_profiling", "klay_get_profile", "klay_destroy", "klay_last_error", "klay_builder_create",
-           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy", "klay_forward_lits", "klay_backward_lits", "klay_root_positions")
+           "klay_builder_add", "klay_builder_finish", "klay_builder_destroy", "klay_forward_lits", "klay_backward_lits", "klay_root_positions", "klay_forward_f64",
+           "klay_backward_f64")
 
 
 class KlayError(RuntimeError):
@@ -89,6 +90,10 @@ def load():
     lib.klay_layer_csr.argtypes = [vp, i32, vp, vp]
     lib.klay_layer_nodes.restype = ctypes.c_int
     lib.klay_layer_nodes.argtypes = [vp, i32, vp, vp]
+    lib.klay_forward_f64.restype = ctypes.c_int
+    lib.klay_forward_f64.argtypes = [vp, vp, vp, i32, vp, ctypes.c_int, vp]
+    lib.klay_backward_f64.restype = ctypes.c_int
+    lib.klay_backward_f64.argtypes = [vp, vp, vp, vp, vp]
     lib.klay_root_positions.restype = ctypes.c_int
     lib.klay_root_positions.argtypes = [vp, vp]
     lib.klay_workspace_bytes.restype = ctypes.c_size_t
@@ -157,6 +162,14 @@ def klay_forward_lits(handle, pos_weights_ptr, neg_weights_ptr, B, out_ptr, semi
 
 def klay_backward_lits(handle, dout_ptr, dpos_ptr, dneg_ptr, stream=0):
     _check(load().klay_backward_lits(handle, dout_ptr, dpos_ptr, dneg_ptr, stream))
+
+
+def klay_forward_f64(handle, pos_weights_ptr, neg_weights_ptr, B, out_ptr, semiring, stream=0):
+    _check(load().klay_forward_f64(handle, pos_weights_ptr, neg_weights_ptr, B, out_ptr, semiring, stream))
+
+
+def klay_backward_f64(handle, dout_ptr, dpos_ptr, dneg_ptr, stream=0):
+    _check(load().klay_backward_f64(handle, dout_ptr, dpos_ptr, dneg_ptr, stream))
 
 
 def klay_destroy(handle):
@@ -355,6 +368,36 @@ class Circuit:
             return outs[0]
         klay_backward_lits(self._h, dout.data_ptr(), outs[0].data_ptr(), outs[1].data_ptr(), self._stream(stream))
         return outs[0], outs[1]
+
+    def forward_f64(self, leaf_weights, semiring=KLAY_LOG, stream=None, neg_weights=None):
+        """Double-precision evaluation: leaf_weights (and neg_weights) torch float64 CUDA [B, V]."""
+        import torch
+        for t in (leaf_weights, neg_weights):
+            if t is not None and (t.dtype != torch.float64 or not t.is_cuda or not t.is_contiguous()
+                                  or t.dim() != 2 or t.shape[1] != self.num_vars):
+                raise ValueError("weights must be contiguous float64 CUDA tensors [B, %d]" % self.num_vars)
+        if neg_weights is not None and neg_weights.shape != leaf_weights.shape:
+            raise ValueError("neg_weights must have the shape of leaf_weights")
+        B = leaf_weights.shape[0]
+        out = torch.empty((B, self.num_roots), dtype=torch.float64, device=leaf_weights.device)
+        klay_forward_f64(self._h, leaf_weights.data_ptr(), None if neg_weights is None else neg_weights.data_ptr(), B,
+                         out.data_ptr(), int(semiring), self._stream(stream))
+        self._last64 = (B, neg_weights is not None)
+        return out
+
+    def backward_f64(self, dout, stream=None):
+        """dout float64 CUDA [B, R]; returns dleaf, or (dpos, dneg) after a forward pass with neg_weights."""
+        import torch
+        B, lits = getattr(self, "_last64", (None, False))
+        if B is None:
+            raise KlayError(KLAY_ESTATE, "backward_f64 before forward_f64")
+        if dout.dtype != torch.float64 or not dout.is_cuda or not dout.is_contiguous() or dout.shape != (B, self.num_roots):
+            raise ValueError("dout must be a contiguous float64 CUDA tensor [B, R]")
+        dpos = torch.empty((B, self.num_vars), dtype=torch.float64, device=dout.device)
+        dneg = torch.empty_like(dpos) if lits else None
+        klay_backward_f64(self._h, dout.data_ptr(), dpos.data_ptr(), None if dneg is None else dneg.data_ptr(),
+                          self._stream(stream))
+        return (dpos, dneg) if lits else dpos
 
     def close(self):
         if self._h is not None:

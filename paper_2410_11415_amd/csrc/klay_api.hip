@@ -13,6 +13,7 @@
 
 #include "../../include/klay.h"
 #include "klay_kernels.hip.h"
+#include "klay_kernels_f64.hip.h"
 #include "layerize.h"
 
 namespace {
@@ -114,6 +115,13 @@ struct klay_circuit {
     int last_semiring = 0;
     bool last_neg_explicit = false;            // the negated literals had weights of their own
     bool last_ws_has_bwd = false;
+    // double-precision evaluation (its own library-owned workspace)
+    void* ws64 = nullptr;
+    size_t ws64_bytes = 0;
+    bool have_fwd64 = false;
+    int32_t last64_B = 0;
+    int last64_semiring = 0;
+    bool last64_neg_explicit = false;
     // profiling
     bool profiling = false;
     std::vector<EventRec> ev_fwd, ev_bwd;
@@ -678,6 +686,194 @@ void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* bel
 #undef KLAY_PE
 }
 
+// ---- double-precision evaluation ---------------------------------------------------------------
+struct Workspace64 {
+    size_t act = 0, wT = 0, scratch = 0, g0 = 0, g1 = 0, total = 0;   // offsets in doubles
+};
+
+Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
+    const klay::CircuitPlan& p = c->plan;
+    Workspace64 w;
+    size_t off = 0;
+    auto take = [&](size_t n) { const size_t o = off; off += (n + 31) / 32 * 32; return o; };
+    w.act = take((size_t)p.num_nodes * ld);
+    w.wT = take((size_t)std::max(1, p.num_vars) * ld);
+    w.scratch = take((size_t)std::max<int64_t>(std::max(p.max_fwd_seg, p.max_bwd_seg), 1) * ld);
+    if (p.alias) {
+        w.g0 = take((size_t)(p.num_nodes + p.num_roots) * ld);
+        w.g1 = w.g0;
+    } else {
+        w.g0 = take((size_t)p.max_layer_nodes * ld);
+        w.g1 = take((size_t)p.max_layer_nodes * ld);
+    }
+    w.total = off;
+    return w;
+}
+
+template <int OP>
+void launch_pass64(const klay::f64::PassArgs& a, hipStream_t s) {
+    if (a.n_total <= 0) return;
+    dim3 grid((unsigned)(((int64_t)a.n_total + 3) / 4), (unsigned)((a.B + 63) / 64));
+    hipLaunchKernelGGL((klay::f64::pass_kernel<OP>), grid, dim3(256), 0, s, a);
+}
+
+void launch_pass64(int op, const klay::f64::PassArgs& a, hipStream_t s) {
+    switch (op) {
+    case klay::OP_SUM: launch_pass64<klay::OP_SUM>(a, s); break;
+    case klay::OP_PROD: launch_pass64<klay::OP_PROD>(a, s); break;
+    case klay::OP_LSE: launch_pass64<klay::OP_LSE>(a, s); break;
+    case klay::OP_MAX: launch_pass64<klay::OP_MAX>(a, s); break;
+    default: launch_pass64<klay::OP_SOFTMAX_BWD>(a, s); break;
+    }
+}
+
+// main rows and segments in one launch, then the combine rows of split rows
+void run_pass_set64(int op, int combine_op, const DevPass& dp, const double* src, const double* src2,
+                    const double* own, double* dst, double* scratch, int B, int ld, hipStream_t s) {
+    klay::f64::PassArgs a{};
+    a.ptr = dp.ptr;
+    a.idx = dp.idx;
+    a.src = src;
+    a.src2 = src2;
+    a.own = own;
+    a.seg_owner = dp.seg_owner;
+    a.out_row = nullptr;
+    a.dst = dst;
+    a.dst_seg = scratch;
+    a.n_main = dp.n_main;
+    a.n_total = dp.n_main + dp.n_seg;
+    a.B = B;
+    a.ld = ld;
+    launch_pass64(op, a, s);
+    if (dp.n_heavy > 0) {
+        klay::f64::PassArgs cmb{};
+        cmb.ptr = dp.comb_ptr;
+        cmb.idx = dp.comb_idx;
+        cmb.src = scratch;
+        cmb.out_row = dp.comb_row;
+        cmb.dst = dst;
+        cmb.n_main = dp.n_heavy;
+        cmb.n_total = dp.n_heavy;
+        cmb.B = B;
+        cmb.ld = ld;
+        launch_pass64(combine_op, cmb, s);
+    }
+}
+
+klay_status forward64_impl(klay_circuit* c, const double* w, const double* wneg, int32_t B, double* out,
+                           klay_semiring semiring, void* stream) {
+    if (!c || !w || !out) return fail(KLAY_EINVAL, "klay_forward_f64: null argument");
+    if (c->device < 0) return fail(KLAY_ESTATE, "klay_forward_f64: host-only handle (built with device = -1)");
+    if (B < 1) return fail(KLAY_EINVAL, "klay_forward_f64: B must be >= 1");
+    if (semiring != KLAY_REAL && semiring != KLAY_LOG && semiring != KLAY_MAXLOG)
+        return fail(KLAY_EINVAL, "klay_forward_f64: unknown semiring");
+    KLAY_HIP(hipSetDevice(c->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const klay::CircuitPlan& p = c->plan;
+    const int ld = B;
+    c->have_fwd64 = false;
+    const Workspace64 lay = workspace_layout64(c, ld);
+    const size_t bytes = lay.total * sizeof(double);
+    if (bytes > c->ws64_bytes) {
+        if (c->ws64) { KLAY_HIP(hipFree(c->ws64)); c->ws64 = nullptr; c->ws64_bytes = 0; }
+        if (hipMalloc(&c->ws64, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(KLAY_ENOMEM, "hipMalloc of " + std::to_string(bytes) + " workspace bytes failed");
+        }
+        c->ws64_bytes = bytes;
+    }
+    double* ws = static_cast<double*>(c->ws64);
+    double* act = ws + lay.act;
+    double* wT = ws + lay.wT;
+    double* scratch = ws + lay.scratch;
+    const int L = p.num_layers, V = p.num_vars;
+    const bool log_domain = semiring != KLAY_REAL;
+    const dim3 row_grid((unsigned)((ld + 255) / 256));
+    if (V > 0)
+        hipLaunchKernelGGL(klay::f64::leaf_fwd_kernel, dim3((unsigned)V, (unsigned)((ld + 255) / 256)), dim3(256), 0, s, w,
+                           wneg, (int)B, V, ld, c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);
+    if (c->true_row >= 0)
+        hipLaunchKernelGGL(klay::f64::fill_row_kernel, row_grid, dim3(256), 0, s, act + (size_t)c->true_row * ld, ld,
+                           log_domain ? 0.0 : 1.0);
+    if (c->false_row >= 0)
+        hipLaunchKernelGGL(klay::f64::fill_row_kernel, row_grid, dim3(256), 0, s, act + (size_t)c->false_row * ld, ld,
+                           log_domain ? (double)-INFINITY : 0.0);
+    for (int l = 1; l <= L; ++l) {
+        const DevLayer& d = c->dl[(size_t)l];
+        const bool is_and = (l & 1) != 0;
+        const int or_op = semiring == KLAY_MAXLOG ? klay::OP_MAX : klay::OP_LSE;
+        const int op = log_domain ? (is_and ? klay::OP_SUM : or_op) : (is_and ? klay::OP_PROD : klay::OP_SUM);
+        const double* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * ld;
+        run_pass_set64(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * ld, scratch, B, ld, s);
+    }
+    hipLaunchKernelGGL(klay::f64::root_out_kernel, dim3((unsigned)p.num_roots), dim3(256), 0, s,
+                       p.alias ? act : act + (size_t)c->dl[(size_t)L].row0 * ld, c->d_root_pos, (int)B, p.num_roots, ld,
+                       out);
+    KLAY_HIP(hipGetLastError());
+    c->have_fwd64 = true;
+    c->last64_B = B;
+    c->last64_semiring = semiring;
+    c->last64_neg_explicit = wneg != nullptr;
+    return KLAY_OK;
+}
+
+klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, double* dneg, void* stream) {
+    if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward_f64: null argument");
+    if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward_f64: host-only handle");
+    if (!c->have_fwd64) return fail(KLAY_ESTATE, "klay_backward_f64: no double-precision forward pass to differentiate");
+    if (c->last64_semiring != KLAY_LOG)
+        return fail(KLAY_EINVAL, "klay_backward_f64: only the log semiring is differentiated in double precision");
+    if (dneg && !c->last64_neg_explicit)
+        return fail(KLAY_ESTATE, "klay_backward_f64: dneg given, but the forward pass had no weights for the negated literals");
+    KLAY_HIP(hipSetDevice(c->device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const klay::CircuitPlan& p = c->plan;
+    const int B = c->last64_B, ld = B;
+    const Workspace64 lay = workspace_layout64(c, ld);
+    double* ws = static_cast<double*>(c->ws64);
+    double* act = ws + lay.act;
+    double* wT = ws + lay.wT;
+    double* scratch = ws + lay.scratch;
+    double* gcur = ws + lay.g0;
+    double* gnext = ws + lay.g1;
+    const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
+    const int leaf_mode = c->last64_neg_explicit ? 2 : 1;
+    const dim3 leaf_grid((unsigned)std::max(V, 1), (unsigned)((B + 255) / 256));
+    if (p.alias) {
+        double* G = gcur;
+        hipLaunchKernelGGL(klay::f64::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, ld,
+                           G + (size_t)p.num_nodes * ld);
+        for (int l = L; l >= 0; --l) {
+            const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
+            const DevLayer& d = c->dl[(size_t)l];
+            run_pass_set64(dp.has_weighted ? klay::OP_SOFTMAX_BWD : klay::OP_SUM, klay::OP_SUM, dp, G, act,
+                           act + (size_t)d.row0 * ld, G + (size_t)d.row0 * ld, scratch, B, ld, s);
+        }
+        if (V > 0)
+            hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B,
+                               V, ld, leaf_mode, dleaf, dneg);
+        KLAY_HIP(hipGetLastError());
+        return KLAY_OK;
+    }
+    hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
+                       c->d_top_root, B, R, ld, gcur);
+    for (int l = L; l >= 1; --l) {
+        const DevLayer& d = c->dl[(size_t)l];
+        const DevLayer& below = c->dl[(size_t)l - 1];
+        if ((l & 1) != 0 || !d.bwd.has_weighted)
+            run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, B, ld, s);
+        else
+            run_pass_set64(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * ld,
+                           act + (size_t)below.row0 * ld, gnext, scratch, B, ld, s);
+        std::swap(gcur, gnext);
+    }
+    if (V > 0)
+        hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B, V,
+                           ld, leaf_mode, dleaf, dneg);
+    KLAY_HIP(hipGetLastError());
+    return KLAY_OK;
+}
+
 }  // namespace
 
 // Circuits collected for a joint layerization: node arrays concatenated, ids shifted.
@@ -824,6 +1020,7 @@ void klay_destroy(klay_circuit* c) {
         if (c->ws_own) (void)hipFree(c->ws_own);
         if (c->d_real_index) (void)hipFree(c->d_real_index);
         if (c->real_buf) (void)hipFree(c->real_buf);
+        if (c->ws64) (void)hipFree(c->ws64);
     }
     delete c;
 }
@@ -1179,6 +1376,24 @@ klay_status klay_backward_lits(klay_circuit* c, const float* dout, float* dpos, 
         return backward_impl(c, dout, dpos, dneg, true, stream);
     } catch (const std::bad_alloc&) {
         return fail(KLAY_ENOMEM, "klay_backward_lits: out of host memory");
+    }
+}
+
+klay_status klay_forward_f64(klay_circuit* c, const double* pos_weights, const double* neg_weights, int32_t B,
+                             double* out, klay_semiring semiring, void* stream) {
+    try {
+        return forward64_impl(c, pos_weights, neg_weights, B, out, semiring, stream);
+    } catch (const std::bad_alloc&) {
+        if (c) c->have_fwd64 = false;
+        return fail(KLAY_ENOMEM, "klay_forward_f64: out of host memory");
+    }
+}
+
+klay_status klay_backward_f64(klay_circuit* c, const double* dout, double* dpos, double* dneg, void* stream) {
+    try {
+        return backward64_impl(c, dout, dpos, dneg, stream);
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_backward_f64: out of host memory");
     }
 }
 

@@ -699,3 +699,91 @@ def test_negative_literal_weights_default_and_call_pairing(klay):
     rp, rn = k.backward(d)
     assert torch.equal(lp.grad, rp) and torch.equal(ln.grad, rn)
     k.close()
+
+
+# ------------------------------------------------------------------ double-precision evaluation
+def _f64_case(klay, c, p, what, backward=True, neg=False, **kw):
+    import torch
+    from oracle import oracle
+    k = build(klay, c, **kw)
+    rng = np.random.default_rng(17)
+    B, R = p.shape[0], c.roots.shape[0]
+    dout = rng.normal(size=(B, R))
+    pn = rng.uniform(0.1, 0.9, size=p.shape) if neg else None
+    for s, name in ((LOG, "log"), (REAL, "real"), (MAXLOG, "maxlog")):
+        with np.errstate(divide="ignore"):
+            w = p if s == REAL else np.log(p)
+            wn = None if pn is None else (pn if s == REAL else np.log(pn))
+        tw = torch.from_numpy(np.ascontiguousarray(w)).cuda()
+        tn = None if wn is None else torch.from_numpy(np.ascontiguousarray(wn)).cuda()
+        got = k.forward_f64(tw, s, neg_weights=tn).cpu().numpy()
+        with np.errstate(all="ignore"):
+            ref = oracle.forward(*c.arrays(), w, s, nthreads=8, neg_weights=wn)
+        inf = np.isinf(ref)
+        np.testing.assert_array_equal(got[inf], ref[inf])
+        if s == REAL:
+            np.testing.assert_allclose(got[~inf], ref[~inf], rtol=1e-12, atol=1e-300, err_msg=what + " f64 " + name)
+        else:
+            np.testing.assert_allclose(got[~inf], ref[~inf], rtol=0, atol=1e-11 * max(1.0, np.abs(ref[~inf]).max()),
+                                       err_msg=what + " f64 " + name)
+        if s == LOG and backward:
+            g = k.backward_f64(torch.from_numpy(dout).cuda())
+            with np.errstate(all="ignore"):
+                r = oracle.backward(*c.arrays(), w, s, dout, nthreads=8, neg_weights=wn)
+                m = oracle.backward(*c.arrays(), w, s, dout, nthreads=8, neg_weights=wn, path_mass=True)
+            for gg, rr, mm in zip(g if neg else (g,), r if neg else (r,), m if neg else (m,)):
+                gg = gg.cpu().numpy()
+                fin = np.isfinite(rr)
+                np.testing.assert_array_equal(gg[~fin], rr[~fin])
+                assert np.all(np.abs(gg[fin] - rr[fin]) <= 1e-10 * np.maximum(1.0, mm[fin])), what + " f64 grad"
+    k.close()
+
+
+def test_f64_small_circuits_and_options(klay, golden):
+    for name, nv in (("fig1b_ddnnf.txt", 4), ("fig3_multiroot.txt", 5), ("appD_mnist_add.txt", 2)):
+        for B in (1, 70):
+            _f64_case(klay, golden(name), leaf_probs(B, B, nv, ("uniform", 0.01, 0.99)), name)
+    c = layered_random(4, num_vars=48, depth=8, num_gates=1500, fanin=("geom", 2.0), groups=2, num_roots=7)
+    for B in (3, 64, 65, 300):
+        _f64_case(klay, c, leaf_probs(B, B, 48), "B=%d" % B)
+    _f64_case(klay, c, leaf_probs(9, 40, 48), "alias", alias_chains=True)
+    _f64_case(klay, c, leaf_probs(9, 40, 48), "neg", neg=True)
+    _f64_case(klay, c, leaf_probs(9, 40, 48), "alias neg", neg=True, alias_chains=True)
+    z = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
+    pz = leaf_probs(5, 70, 64, ("beta", 0.5, 0.5)); pz[:, ::7] = 0.0; pz[:, 3::11] = 1.0
+    _f64_case(klay, z, pz, "split", backward=False, heavy_fan=8, min_segment=4)
+    _f64_case(klay, z, leaf_probs(5, 70, 64, ("beta", 0.5, 0.5)), "split grad", heavy_fan=8, min_segment=4)
+
+
+@pytest.mark.parametrize("name,scale,B", [("powerlaw_10m", 0.08, 64), ("layered_3m_fwd_bwd", 0.02, 256)])
+def test_f64_configs_reduced_size(klay, name, scale, B):
+    c, p, spec = make_config(name, seed=1, scale=scale, batch=B)
+    _f64_case(klay, c, p, name)
+
+
+def test_fp32_against_f64_on_every_output_at_full_size(klay):
+    """headline workload at full size: the double-precision kernels agree with the oracle on sampled
+    batch columns, and the fp32 kernels with the double-precision kernels on every output and every
+    gradient entry"""
+    import torch
+    from oracle import oracle
+    c, p, spec = make_config("layered_3m_fwd_bwd", seed=0)
+    B = 64                                                  # 3.6e6 rows x 64 columns in double: 1.9 GB
+    w32 = as_inputs(p[:B], True)
+    k = build(klay, c)
+    w64 = torch.from_numpy(w32.astype(np.float64)).cuda()
+    out64 = k.forward_f64(w64, LOG)
+    d64 = k.backward_f64(torch.ones_like(out64))
+    cols = np.array([0, 21, 63])
+    with np.errstate(all="ignore"):
+        ref = oracle.forward(*c.arrays(), w32[cols].astype(np.float64), oracle.LOG, nthreads=3)
+        rgrad = oracle.backward(*c.arrays(), w32[cols].astype(np.float64), oracle.LOG, np.ones_like(ref), nthreads=3)
+    np.testing.assert_allclose(out64.cpu().numpy()[cols], ref, rtol=0, atol=1e-10)
+    np.testing.assert_allclose(d64.cpu().numpy()[cols], rgrad, rtol=1e-9, atol=1e-9)
+    got, gd = gpu_eval(k, w32, LOG, np.ones((B, c.roots.shape[0]), dtype=np.float32))
+    assert_log_close(got, out64.cpu().numpy(), "fp32 vs f64, all outputs")
+    r64 = d64.cpu().numpy()
+    err = np.abs(gd - r64) / np.maximum(1.0, np.abs(r64))
+    print("fp32 vs f64 at full size: max|dlog| %.2e, max grad err %.2e" % (np.abs(got - out64.cpu().numpy()).max(), err.max()))
+    assert err.max() <= 1e-4
+    k.close()
