@@ -710,11 +710,16 @@ Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
     return w;
 }
 
+// two columns per lane (16-byte loads) once the batch is wider than a wave; ld is even then
 template <int OP>
 void launch_pass64(const klay::f64::PassArgs& a, hipStream_t s) {
     if (a.n_total <= 0) return;
-    dim3 grid((unsigned)(((int64_t)a.n_total + 3) / 4), (unsigned)((a.B + 63) / 64));
-    hipLaunchKernelGGL((klay::f64::pass_kernel<OP>), grid, dim3(256), 0, s, a);
+    const unsigned rows = (unsigned)(((int64_t)a.n_total + 3) / 4);
+    if (a.B > 64) {
+        hipLaunchKernelGGL((klay::f64::pass_kernel<OP, 2>), dim3(rows, (unsigned)((a.B + 127) / 128)), dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((klay::f64::pass_kernel<OP, 1>), dim3(rows, 1), dim3(256), 0, s, a);
+    }
 }
 
 void launch_pass64(int op, const klay::f64::PassArgs& a, hipStream_t s) {
@@ -770,7 +775,7 @@ klay_status forward64_impl(klay_circuit* c, const double* w, const double* wneg,
     KLAY_HIP(hipSetDevice(c->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
     const klay::CircuitPlan& p = c->plan;
-    const int ld = B;
+    const int ld = B > 64 ? (B + 1) / 2 * 2 : B;       // even rows for two columns per lane
     c->have_fwd64 = false;
     const Workspace64 lay = workspace_layout64(c, ld);
     const size_t bytes = lay.total * sizeof(double);
@@ -828,7 +833,7 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     KLAY_HIP(hipSetDevice(c->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
     const klay::CircuitPlan& p = c->plan;
-    const int B = c->last64_B, ld = B;
+    const int B = c->last64_B, ld = B > 64 ? (B + 1) / 2 * 2 : B;
     const Workspace64 lay = workspace_layout64(c, ld);
     double* ws = static_cast<double*>(c->ws64);
     double* act = ws + lay.act;

@@ -1,5 +1,5 @@
 // Double-precision evaluation of the same launch plans (accuracy build): one generic gather-reduce
-// kernel, a wave per output row and a lane per batch column, plus the small leaf / root / seed
+// kernel, a wave per output row and one or two batch columns per lane, plus the small leaf / root / seed
 // kernels.  Same index arrays, same order of layers and the same split-row scheme as the fp32
 // kernels (paper Section 4, Alg. 1 / Appendix C, Alg. 4); exp and log are the full-precision
 // library routines.  Not tuned: the rows are twice as long and OR layers pay a double-precision
@@ -56,27 +56,40 @@ __device__ __forceinline__ double finish(double acc, double mx) {
     return acc;
 }
 
-template <int OP>
+template <int VEC>
+__device__ __forceinline__ void load_vec(double (&x)[VEC], const double* p) {
+    if (VEC == 2) {
+        const double2 t = *reinterpret_cast<const double2*>(p);
+        x[0] = t.x;
+        x[VEC - 1] = t.y;
+    } else {
+        x[0] = *p;
+    }
+}
+
+// VEC batch columns per lane (2 needs an even ld): a wave spans 64 * VEC columns of one row
+template <int OP, int VEC>
 __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
     constexpr int CH = 4;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int col = (int)blockIdx.y * 64 + lane;
+    const int col = ((int)blockIdx.y * 64 + lane) * VEC;
     if (col >= a.B) return;
     const int64_t row64 = (int64_t)blockIdx.x * 4 + wave;
     if (row64 >= a.n_total) return;
     const int row = (int)row64;
     const int beg = a.ptr[row], end = a.ptr[row + 1];
     if (a.idx[beg] == kSkip) return;                  // split row: evaluated by segments + combine
-    double nc = 0.0;
+    double nc[VEC], acc[VEC], mx[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { nc[v] = 0.0; acc[v] = identity<OP>(); mx[v] = -INFINITY; }
     if (OP == OP_SOFTMAX_BWD) {
         const int owner = row < a.n_main ? row : a.seg_owner[row - a.n_main];
-        nc = a.own[(size_t)owner * a.ld + col];
+        load_vec<VEC>(nc, a.own + (size_t)owner * a.ld + col);
     }
-    double acc = identity<OP>(), mx = -INFINITY;
     for (int j = beg; j < end; j += CH) {
         const int n = end - j;
-        double x[CH], y[CH];
+        double x[CH][VEC], y[CH][VEC];
         bool wt[CH];
         // entries past the row's end are valid entries of later rows (or zero padding): the gathers
         // are issued unconditionally and their data ignored
@@ -85,20 +98,24 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
             const uint32_t raw = a.idx[j + i];
             const uint32_t id = raw == kSkip ? 0u : (raw & kIdMask);
             wt[i] = (raw & kWeighted) != 0;
-            x[i] = a.src[(size_t)id * a.ld + col];
-            y[i] = OP == OP_SOFTMAX_BWD ? (wt[i] ? a.src2 : a.src)[(size_t)id * a.ld + col] : 0.0;
+            load_vec<VEC>(x[i], a.src + (size_t)id * a.ld + col);
+            if (OP == OP_SOFTMAX_BWD) load_vec<VEC>(y[i], (wt[i] ? a.src2 : a.src) + (size_t)id * a.ld + col);
         }
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const bool live = i < n;
             const double dead = OP == OP_PROD ? 1.0 : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0);
-            accumulate<OP>(acc, mx, live ? x[i] : dead, live ? y[i] : -INFINITY, nc, wt[i]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                accumulate<OP>(acc[v], mx[v], live ? x[i][v] : dead,
+                               OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0, nc[v], wt[i]);
         }
     }
     double* out;
     if (row < a.n_main) out = a.dst + (size_t)(a.out_row ? a.out_row[row] : row) * a.ld + col;
     else out = a.dst_seg + (size_t)(row - a.n_main) * a.ld + col;
-    *out = finish<OP>(acc, mx);
+    if (VEC == 2) *reinterpret_cast<double2*>(out) = make_double2(finish<OP>(acc[0], mx[0]), finish<OP>(acc[VEC - 1], mx[VEC - 1]));
+    else *out = finish<OP>(acc[0], mx[0]);
 }
 
 __device__ __forceinline__ double log1mexp(double x) {
