@@ -243,6 +243,9 @@ def main():
                        "measured_traffic_frac": None if step_traffic is None else
                        round(step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "per_class_ms": {n: round(c["ms"] / prof_steps, 3) for n, c in classes.items() if c["launches"]},
+        # no-reuse GB/s of every class (its algorithmic bytes over its summed launch durations)
+        "per_class_GBs": {n: round(c["alg_bytes"] / (c["ms"] * 1e-3) / 1e9) for n, c in classes.items()
+                          if c["launches"] and c["ms"] > 0},
     }
 
     cpu_baseline = None
