@@ -73,7 +73,7 @@ Geometry geometry(int B) {
 size_t align_floats(size_t n) { return (n + 63) / 64 * 64; }
 
 struct Workspace {
-    size_t act = 0, wT = 0, scratch = 0, g0 = 0, g1 = 0, total = 0;   // offsets in floats
+    size_t act = 0, wT = 0, scratch = 0, g0 = 0, g1 = 0, tb = 0, total = 0;   // offsets in floats
 };
 
 struct EventRec {
@@ -96,6 +96,7 @@ struct klay_circuit {
     int32_t true_row = -1, false_row = -1;
     const klay::TailLayer* d_tail = nullptr;   // descriptors of layers plan.tail_first .. L
     bool tail_lds_ok = false;                  // the large-LDS attribute was accepted for the tail kernels
+    int64_t tail_rows = 0;                     // T: rows of all tail candidate layers (one column of the tail buffer)
     int32_t last_tail_first = 0;               // first layer the last forward ran in the tail kernel (0: none)
     // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
     // vectors and a by-child pass whose entries are edge positions, plus the per-edge buffer M
@@ -139,6 +140,8 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     w.wT = off; off += align_floats((size_t)std::max(1, p.num_vars) * g.ld);
     const int64_t seg = std::max(p.max_fwd_seg, need_bwd ? p.max_bwd_seg : 0);
     w.scratch = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
+    // values of the tail layers, one run of tail_rows floats per batch column
+    w.tb = off; off += align_floats((size_t)c->tail_rows * (size_t)B);
     if (need_bwd && p.alias) {
         // adjoints of every row plus one row per root column for the transposed dout
         w.g0 = off; off += align_floats((size_t)(p.num_nodes + p.num_roots) * g.ld);
@@ -343,7 +346,7 @@ klay_status upload(klay_circuit* c) {
     size_t o_tail = 0;
     if (p.tail_first > 0) {
         std::vector<klay::TailLayer> descs;
-        int64_t row0 = 0;
+        int64_t row0 = 0, tb_off = 0;
         for (int l = 0; l < p.tail_first; ++l) row0 += p.layers[(size_t)l].n;
         for (int l = p.tail_first; l <= L; ++l) {
             const klay::LayerPlan& lay = p.layers[(size_t)l];
@@ -359,9 +362,12 @@ klay_status upload(klay_circuit* c) {
             t.bwd_off = (int32_t)pk.add(b);
             t.row0 = row0;
             t.row0_below = row0 - t.n_below;
+            t.tb_off = (int32_t)tb_off;
+            tb_off += lay.n;
             row0 += lay.n;
             descs.push_back(t);
         }
+        c->tail_rows = tb_off;
         static_assert(sizeof(klay::TailLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
         o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::TailLayer) / sizeof(int32_t));
     }
@@ -548,7 +554,7 @@ bool enable_tail_lds() {
     return true;
 }
 
-void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int B, int ld, int semiring,
+void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, float* tb, int B, int ld, int semiring,
                      hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
@@ -558,7 +564,7 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int
     dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
 #define KLAY_TAIL_FWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::tail_fwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
-                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax)
+                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax, tb, (int)c->tail_rows)
     switch (t.ct) {
     case 8: KLAY_TAIL_FWD(8); break;
     case 4: KLAY_TAIL_FWD(4); break;
@@ -568,7 +574,7 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, int
 #undef KLAY_TAIL_FWD
 }
 
-void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* act, const float* dout,
+void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* act, const float* tb, const float* dout,
                      float* g_out, int B, int ld, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
@@ -579,7 +585,7 @@ void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* ac
 #define KLAY_TAIL_BWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::tail_bwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
                        n_layers, first_is_and, c->d_index, act, dout, c->d_top_ptr, c->d_top_root,     \
-                       p.num_roots, g_out, B, ld, t.nmax)
+                       p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows)
     switch (t.ct) {
     case 8: KLAY_TAIL_BWD(8); break;
     case 4: KLAY_TAIL_BWD(4); break;
@@ -1189,7 +1195,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
 
     if (tail.first > 0) {
         prof.begin(KLAY_K_TAIL_FWD, tail_alg_bytes(c, tail.first, B, false));
-        launch_tail_fwd(c, tail, act, B, g.ld, (int)semiring, s);
+        launch_tail_fwd(c, tail, act, ws + lay.tb, B, g.ld, (int)semiring, s);
         prof.end();
     }
 
@@ -1316,7 +1322,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         TailChoice tail = choose_tail(c, B, 3);
         if (tail.first != c->last_tail_first) return fail(KLAY_ESTATE, "klay_backward: tail layout changed since forward");
         prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R);
-        launch_tail_bwd(c, tail, act, dout, gcur, B, g.ld, s);
+        launch_tail_bwd(c, tail, act, ws + lay.tb, dout, gcur, B, g.ld, s);
         prof.end();
         top = tail.first;
     } else {

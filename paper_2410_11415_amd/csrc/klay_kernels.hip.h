@@ -328,13 +328,19 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
 // layer's index vectors are staged into LDS first.  Values are also written to the activation
 // buffer, because the backward pass reads them.
 //   LDS (floats): forward 2 * nmax * CT values, backward 3 * nmax * CT, then nmax + 1 + emax ints.
+// A thread owns rows of one batch column, so writing the values into the row-major activation
+// buffer costs one cache line per lane.  The values the reverse kernel needs therefore go to a
+// tail value buffer tb[column][T] (T = rows of all tail layers), where consecutive threads write
+// consecutive floats; only the first and the top tail layer (read by the regular reverse pass and
+// by the root kernel) and, in the real semiring
+// (whose reverse sweep runs layer by layer), every layer is also written to the activation buffer.
 // ---------------------------------------------------------------------------------------------
 struct TailLayer {
     int32_t n, e;          // nodes and edges of this layer
     int32_t n_below;       // nodes of the layer below
     int32_t fwd_off;       // [row_ptr (n+1) | child (e)] by parent, offset in ints into the index buffer
     int32_t bwd_off;       // [col_ptr (n_below+1) | parent (e)] by child
-    int32_t pad_;
+    int32_t tb_off;        // first entry of this layer in a column of the tail value buffer
     int64_t row0;          // first activation row of this layer
     int64_t row0_below;
 };
@@ -345,7 +351,7 @@ constexpr int kTailStash = 20;          // index entries per thread: covers rows
 template <int OP, int CT>
 __device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib, const float* prev, float* cur,
                                               const float* below, bool from_global, float* act_out, int ld,
-                                              bool active) {
+                                              bool active, float* tb_out, bool write_act) {
     constexpr int RS = kTailThreads / CT;
     const int c = threadIdx.x % CT;
     for (int r = threadIdx.x / CT; r < L.n; r += RS) {
@@ -373,7 +379,10 @@ __device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib,
         }
         const float o = finish<OP>(acc, mx);
         cur[r * CT + c] = o;
-        if (active) act_out[(size_t)r * ld] = o;
+        if (active) {
+            tb_out[r] = o;
+            if (write_act) act_out[(size_t)r * ld] = o;
+        }
     }
 }
 
@@ -381,7 +390,7 @@ template <int CT>
 __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer* __restrict__ layers, int n_layers,
                                                                 int first_is_and, const int32_t* __restrict__ ibase,
                                                                 float* act, int B, int ld, int semiring,
-                                                                int nmax) {
+                                                                int nmax, float* __restrict__ tb, int T) {
     extern __shared__ float smem[];
     float* prev = smem;
     float* cur = smem + (size_t)nmax * CT;
@@ -420,15 +429,18 @@ __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer*
         const float* below = act + (size_t)L.row0_below * ld + col;
         float* out = act + (size_t)L.row0 * ld + col;
         const bool fg = t == 0;
+        float* tbo = tb + (size_t)(active ? col : 0) * T + L.tb_off;
+        // the first tail layer is read by the regular reverse pass below it, the top layer by the root kernel
+        const bool wa = semiring == 0 || t == 0 || t == n_layers - 1;
         if (semiring == 2) {           // (max, +) on log weights
-            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
-            else tail_fwd_rows<OP_MAX, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
+            else tail_fwd_rows<OP_MAX, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
         } else if (semiring == 1) {    // (logsumexp, +)
-            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
-            else tail_fwd_rows<OP_LSE, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
+            else tail_fwd_rows<OP_LSE, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
         } else {
-            if (is_and) tail_fwd_rows<OP_PROD, CT>(L, ib, prev, cur, below, fg, out, ld, active);
-            else tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active);
+            if (is_and) tail_fwd_rows<OP_PROD, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
+            else tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
         }
         __syncthreads();
         float* tmp = prev; prev = cur; cur = tmp;
@@ -444,7 +456,8 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
                                                                 const float* __restrict__ dout,
                                                                 const int32_t* __restrict__ top_ptr,
                                                                 const int32_t* __restrict__ top_root, int R,
-                                                                float* __restrict__ g_out, int B, int ld, int nmax) {
+                                                                float* __restrict__ g_out, int B, int ld, int nmax,
+                                                                const float* __restrict__ tb, int T) {
     extern __shared__ float smem[];
     constexpr int RS = kTailThreads / CT;
     float* cur = smem;
@@ -494,16 +507,17 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
         if (!is_and)
             for (int i = threadIdx.x; i < L.n * CT; i += kTailThreads) {
                 const int cc = col0 + i % CT;
-                nl[i] = cc < B ? act[((size_t)L.row0 + i / CT) * ld + cc] : 0.0f;
+                nl[i] = cc < B ? tb[(size_t)cc * T + L.tb_off + i / CT] : 0.0f;
             }
         __syncthreads();
+        const int off_below = layers[t - 1].tb_off;
         for (int r = threadIdx.x / CT; r < L.n_below; r += RS) {
             const int beg = ib[r], end = ib[r + 1];
             float acc = 0.0f, mx = 0.0f;
             if (is_and) {
                 for (int j = beg; j < end; ++j) acc += cur[ib[L.n_below + 1 + j] * CT + c];
             } else {
-                const float own = active ? act[((size_t)L.row0_below + r) * ld + col] : 0.0f;
+                const float own = active ? tb[(size_t)col * T + off_below + r] : 0.0f;
                 for (int j = beg; j < end; ++j) {
                     const int p = ib[L.n_below + 1 + j];
                     accumulate<OP_SOFTMAX_BWD>(acc, mx, cur[p * CT + c], nl[p * CT + c], own);
