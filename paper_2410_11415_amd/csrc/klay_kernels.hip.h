@@ -397,18 +397,18 @@ __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer*
     int* ib = reinterpret_cast<int*>(smem + (size_t)2 * nmax * CT);
     const int col = (int)blockIdx.x * CT + (int)(threadIdx.x % CT);
     const bool active = col < B;
-    // index vectors of the next layer travel to registers while the current layer is evaluated
-    int stash[kTailStash];
-    {
-        const TailLayer L0 = layers[0];
-        const int32_t* g = ibase + L0.fwd_off;
+    // The index vectors of a layer travel from global memory to registers two layers ahead (two
+    // register stashes used in turn), so their latency is covered by two layers of evaluation.
+    auto fetch = [&](int (&stash)[kTailStash], int t) {
+        const TailLayer Lf = layers[t];
+        const int32_t* g = ibase + Lf.fwd_off;
 #pragma unroll
         for (int u = 0; u < kTailStash; ++u) {
             const int i = threadIdx.x + u * kTailThreads;
-            stash[u] = i < L0.n + 1 + L0.e ? g[i] : 0;
+            stash[u] = i < Lf.n + 1 + Lf.e ? g[i] : 0;
         }
-    }
-    for (int t = 0; t < n_layers; ++t) {
+    };
+    auto layer = [&](int (&stash)[kTailStash], int t) {
         const TailLayer L = layers[t];
 #pragma unroll
         for (int u = 0; u < kTailStash; ++u) {
@@ -416,15 +416,7 @@ __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer*
             if (i < L.n + 1 + L.e) ib[i] = stash[u];
         }
         __syncthreads();
-        if (t + 1 < n_layers) {
-            const TailLayer Ln = layers[t + 1];
-            const int32_t* g = ibase + Ln.fwd_off;
-#pragma unroll
-            for (int u = 0; u < kTailStash; ++u) {
-                const int i = threadIdx.x + u * kTailThreads;
-                stash[u] = i < Ln.n + 1 + Ln.e ? g[i] : 0;
-            }
-        }
+        if (t + 2 < n_layers) fetch(stash, t + 2);
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
         const float* below = act + (size_t)L.row0_below * ld + col;
         float* out = act + (size_t)L.row0 * ld + col;
@@ -444,6 +436,13 @@ __global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer*
         }
         __syncthreads();
         float* tmp = prev; prev = cur; cur = tmp;
+    };
+    int stash_a[kTailStash], stash_b[kTailStash];
+    fetch(stash_a, 0);
+    if (n_layers > 1) fetch(stash_b, 1);
+    for (int t = 0; t < n_layers; t += 2) {
+        layer(stash_a, t);
+        if (t + 1 < n_layers) layer(stash_b, t + 1);
     }
 }
 
@@ -477,17 +476,18 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
             cur[i * CT + c] = acc;
         }
     }
-    int stash[kTailStash];
-    if (n_layers > 1) {
-        const TailLayer Lt = layers[n_layers - 1];
-        const int32_t* g = ibase + Lt.bwd_off;
+    // step t (adjoints of layer t -> layer t-1) uses the by-child index vectors of layer t; they are
+    // fetched two steps ahead into two register stashes used in turn
+    auto fetch = [&](int (&stash)[kTailStash], int t) {
+        const TailLayer Lf = layers[t];
+        const int32_t* g = ibase + Lf.bwd_off;
 #pragma unroll
         for (int u = 0; u < kTailStash; ++u) {
             const int i = threadIdx.x + u * kTailThreads;
-            stash[u] = i < Lt.n_below + 1 + Lt.e ? g[i] : 0;
+            stash[u] = i < Lf.n_below + 1 + Lf.e ? g[i] : 0;
         }
-    }
-    for (int t = n_layers - 1; t >= 1; --t) {          // step t: adjoints of layer t -> layer t-1
+    };
+    auto step = [&](int (&stash)[kTailStash], int t) {
         const TailLayer L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
 #pragma unroll
@@ -495,15 +495,7 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
             const int i = threadIdx.x + u * kTailThreads;
             if (i < L.n_below + 1 + L.e) ib[i] = stash[u];
         }
-        if (t > 1) {
-            const TailLayer Ln = layers[t - 1];
-            const int32_t* g = ibase + Ln.bwd_off;
-#pragma unroll
-            for (int u = 0; u < kTailStash; ++u) {
-                const int i = threadIdx.x + u * kTailThreads;
-                stash[u] = i < Ln.n_below + 1 + Ln.e ? g[i] : 0;
-            }
-        }
+        if (t - 2 >= 1) fetch(stash, t - 2);
         if (!is_and)
             for (int i = threadIdx.x; i < L.n * CT; i += kTailThreads) {
                 const int cc = col0 + i % CT;
@@ -527,6 +519,13 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
         }
         __syncthreads();
         float* tmp = cur; cur = nxt; nxt = tmp;
+    };
+    int stash_a[kTailStash], stash_b[kTailStash];
+    if (n_layers - 1 >= 1) fetch(stash_a, n_layers - 1);
+    if (n_layers - 2 >= 1) fetch(stash_b, n_layers - 2);
+    for (int t = n_layers - 1; t >= 1; t -= 2) {
+        step(stash_a, t);
+        if (t - 1 >= 1) step(stash_b, t - 1);
     }
     const int n_first = layers[0].n;
     if (active)

@@ -443,6 +443,32 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             std::vector<int32_t> order((size_t)lay.n);
             std::iota(order.begin(), order.end(), 0);
             std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[(size_t)a] < key[(size_t)b]; });
+            if (lay.n <= kTailRowsCap && !alias && !opt.no_tail) {
+                // A layer small enough for the persistent top-of-circuit kernels: there a thread walks a whole
+                // row and a wave waits for its longest one, while locality is irrelevant (the layer sits in
+                // LDS).  Group rows by fan-in (powers of two) and order each group by fan-out, so that the 64
+                // rows of a wave have similar lengths in the forward and in the reverse sweep.
+                std::vector<int32_t> fan_in((size_t)lay.n), fan_out((size_t)lay.n, 0);
+                for (int64_t s2 = 0; s2 < lay.n; ++s2) {
+                    const int32_t c = lay.origin[(size_t)s2];
+                    fan_in[(size_t)s2] = lay.is_pad[(size_t)s2] ? 1 : (int32_t)(child_ptr[c + 1] - child_ptr[c]);
+                }
+                if (l < L) {
+                    const LayerPlan& up = plan.layers[(size_t)l + 1];
+                    for (int64_t s2 = 0; s2 < up.n; ++s2) {
+                        const int32_t c = up.origin[(size_t)s2];
+                        if (up.is_pad[(size_t)s2]) ++fan_out[(size_t)at(c, l)];
+                        else
+                            for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) ++fan_out[(size_t)at(child_idx[j], l)];
+                    }
+                }
+                auto bucket = [](int32_t k) { int b = 0; while ((1 << b) < k) ++b; return b; };
+                std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+                    const int ba = bucket(fan_in[(size_t)a]), bb = bucket(fan_in[(size_t)b]);
+                    if (ba != bb) return ba > bb;
+                    return fan_out[(size_t)a] > fan_out[(size_t)b];
+                });
+            }
             apply_order(l, order);
         }
     }
