@@ -180,7 +180,9 @@ klay_status klay_backward_lits(klay_circuit* c, const float* dout, float* dpos, 
  *   pos_weights, neg_weights, out, dout, dpos, dneg   as for klay_forward_lits / klay_backward_lits,
  *                 in double; neg_weights = NULL derives the negated literals from pos_weights, and
  *                 dneg must then be NULL as well.
- * All three semirings are evaluated; only KLAY_LOG is differentiated (KLAY_EINVAL otherwise).
+ * All three semirings are evaluated; KLAY_LOG and KLAY_REAL are differentiated (the real semiring not on
+ * alias_chains handles, KLAY_MAXLOG not at all: KLAY_EINVAL).  In double the real semiring reaches
+ * circuits whose values underflow fp32.
  * The activations live in a library-owned workspace of their own (klay_set_workspace and
  * klay_workspace_bytes do not cover it) and are independent of the fp32 state: a handle can hold
  * one fp32 and one double-precision forward pass at the same time.  Profiling does not cover

@@ -119,6 +119,8 @@ struct klay_circuit {
     // double-precision evaluation (its own library-owned workspace)
     void* ws64 = nullptr;
     size_t ws64_bytes = 0;
+    double* real_buf64 = nullptr;              // per-edge buffer of the real-semiring reverse sweep in double
+    size_t real_buf64_bytes = 0;
     bool have_fwd64 = false;
     int32_t last64_B = 0;
     int last64_semiring = 0;
@@ -832,8 +834,11 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     if (!c || !dout || !dleaf) return fail(KLAY_EINVAL, "klay_backward_f64: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_backward_f64: host-only handle");
     if (!c->have_fwd64) return fail(KLAY_ESTATE, "klay_backward_f64: no double-precision forward pass to differentiate");
-    if (c->last64_semiring != KLAY_LOG)
-        return fail(KLAY_EINVAL, "klay_backward_f64: only the log semiring is differentiated in double precision");
+    if (c->last64_semiring == KLAY_MAXLOG)
+        return fail(KLAY_EINVAL, "klay_backward_f64: the (max, +) semiring is not differentiated");
+    const bool real = c->last64_semiring == KLAY_REAL;
+    if (real && c->plan.alias)
+        return fail(KLAY_EINVAL, "klay_backward_f64: the real semiring is not differentiated in alias_chains mode");
     if (dneg && !c->last64_neg_explicit)
         return fail(KLAY_ESTATE, "klay_backward_f64: dneg given, but the forward pass had no weights for the negated literals");
     KLAY_HIP(hipSetDevice(c->device));
@@ -848,8 +853,45 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     double* gcur = ws + lay.g0;
     double* gnext = ws + lay.g1;
     const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
-    const int leaf_mode = c->last64_neg_explicit ? 2 : 1;
+    const int leaf_mode = c->last64_neg_explicit ? 2 : (real ? 0 : 1);
     const dim3 leaf_grid((unsigned)std::max(V, 1), (unsigned)((B + 255) / 256));
+    if (real) {
+        // as the fp32 real-semiring sweep: sum layers pass adjoints through, product layers go through
+        // the per-edge buffer M, summed by child (index arrays shared with the fp32 path)
+        klay_status rs = ensure_real_bwd(c, 1);
+        if (rs != KLAY_OK) return rs;
+        const size_t need = (size_t)(c->real_max_edges + std::max<int64_t>(c->real_max_seg, 1) + 1) * ld * sizeof(double);
+        if (need > c->real_buf64_bytes) {
+            if (c->real_buf64) { KLAY_HIP(hipFree(c->real_buf64)); c->real_buf64 = nullptr; c->real_buf64_bytes = 0; }
+            if (hipMalloc(reinterpret_cast<void**>(&c->real_buf64), need) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(KLAY_ENOMEM, "klay_backward_f64: hipMalloc of the per-edge buffer failed");
+            }
+            c->real_buf64_bytes = need;
+        }
+        double* M = c->real_buf64;
+        double* rscratch = c->real_buf64 + (size_t)(c->real_max_edges + 1) * ld;
+        hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
+                           c->d_top_root, B, R, ld, gcur);
+        for (int l = L; l >= 1; --l) {
+            const DevLayer& d = c->dl[(size_t)l];
+            const DevLayer& below = c->dl[(size_t)l - 1];
+            if ((l & 1) == 0) {
+                run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, B, ld, s);
+            } else {
+                const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
+                hipLaunchKernelGGL(klay::f64::prod_edge_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
+                                   dim3(256), 0, s, r.ptr, r.child, act + (size_t)below.row0 * ld, gcur, M, (int)d.n, B, ld);
+                run_pass_set64(klay::OP_SUM, klay::OP_SUM, r.by_child, M, nullptr, nullptr, gnext, rscratch, B, ld, s);
+            }
+            std::swap(gcur, gnext);
+        }
+        if (V > 0)
+            hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B,
+                               V, ld, leaf_mode, dleaf, dneg);
+        KLAY_HIP(hipGetLastError());
+        return KLAY_OK;
+    }
     if (p.alias) {
         double* G = gcur;
         hipLaunchKernelGGL(klay::f64::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, ld,
@@ -1032,6 +1074,7 @@ void klay_destroy(klay_circuit* c) {
         if (c->d_real_index) (void)hipFree(c->d_real_index);
         if (c->real_buf) (void)hipFree(c->real_buf);
         if (c->ws64) (void)hipFree(c->ws64);
+        if (c->real_buf64) (void)hipFree(c->real_buf64);
     }
     delete c;
 }

@@ -170,7 +170,35 @@ __global__ void seed_rows_kernel(const double* __restrict__ dout, int B, int R, 
     for (int b = threadIdx.x; b < ld; b += blockDim.x) rows[(size_t)r * ld + b] = b < B ? dout[(size_t)b * R + r] : 0.0;
 }
 
-// mode 1: negated weight log(1 - exp(w)); mode 2: the negated literals have weights of their own
+// Real-semiring reverse sweep of a product layer, per edge: M[j] = adjoint of the parent times the
+// product of its other children, formed from the product q of the non-zero children and the number
+// z of zero ones (exact when children are zero).  A wave per parent row, a lane per batch column.
+__global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ child,
+                                                        const double* __restrict__ below, const double* __restrict__ g,
+                                                        double* __restrict__ M, int n, int B, int ld) {
+    const int lane = threadIdx.x & 63;
+    const int col = (int)blockIdx.y * 64 + lane;
+    if (col >= B) return;
+    const int64_t row64 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row64 >= n) return;
+    const int row = (int)row64;
+    const int beg = ptr[row], end = ptr[row + 1];
+    const double gr = g[(size_t)row * ld + col];
+    double q = 1.0;
+    int z = 0;
+    for (int j = beg; j < end; ++j) {
+        const double x = below[(size_t)child[j] * ld + col];
+        if (x == 0.0) ++z;
+        else q *= x;
+    }
+    for (int j = beg; j < end; ++j) {
+        const double x = below[(size_t)child[j] * ld + col];
+        const double others = x != 0.0 ? (z == 0 ? q / x : 0.0) : (z == 1 ? q : 0.0);
+        M[(size_t)j * ld + col] = gr * others;
+    }
+}
+
+// mode 0: negated weight 1 - w; mode 1: log(1 - exp(w)); mode 2: the negated literals have weights of their own
 __global__ void leaf_bwd_kernel(const double* __restrict__ g0, const double* __restrict__ wT,
                                 const int32_t* __restrict__ pos_row, const int32_t* __restrict__ neg_row, int B,
                                 int V, int ld, int mode, double* __restrict__ dleaf, double* __restrict__ dneg) {
@@ -183,7 +211,7 @@ __global__ void leaf_bwd_kernel(const double* __restrict__ g0, const double* __r
     if (nr >= 0) {
         const double gn = g0[(size_t)nr * ld + b];
         if (mode == 2) dn = gn;
-        else if (gn != 0.0) d += -gn / expm1(-wT[(size_t)v * ld + b]);
+        else if (gn != 0.0) d += mode == 1 ? -gn / expm1(-wT[(size_t)v * ld + b]) : -gn;
     }
     dleaf[(size_t)b * V + v] = d;
     if (mode == 2 && dneg) dneg[(size_t)b * V + v] = dn;

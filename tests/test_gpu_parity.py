@@ -726,7 +726,7 @@ def _f64_case(klay, c, p, what, backward=True, neg=False, **kw):
         else:
             np.testing.assert_allclose(got[~inf], ref[~inf], rtol=0, atol=1e-11 * max(1.0, np.abs(ref[~inf]).max()),
                                        err_msg=what + " f64 " + name)
-        if s == LOG and backward:
+        if backward and (s == LOG or (s == REAL and not kw.get("alias_chains"))):
             g = k.backward_f64(torch.from_numpy(dout).cuda())
             with np.errstate(all="ignore"):
                 r = oracle.backward(*c.arrays(), w, s, dout, nthreads=8, neg_weights=wn)
@@ -735,7 +735,7 @@ def _f64_case(klay, c, p, what, backward=True, neg=False, **kw):
                 gg = gg.cpu().numpy()
                 fin = np.isfinite(rr)
                 np.testing.assert_array_equal(gg[~fin], rr[~fin])
-                assert np.all(np.abs(gg[fin] - rr[fin]) <= 1e-10 * np.maximum(1.0, mm[fin])), what + " f64 grad"
+                assert np.all(np.abs(gg[fin] - rr[fin]) <= 1e-10 * np.maximum(1.0, mm[fin])), what + " f64 grad " + name
     k.close()
 
 
@@ -786,4 +786,29 @@ def test_fp32_against_f64_on_every_output_at_full_size(klay):
     err = np.abs(gd - r64) / np.maximum(1.0, np.abs(r64))
     print("fp32 vs f64 at full size: max|dlog| %.2e, max grad err %.2e" % (np.abs(got - out64.cpu().numpy()).max(), err.max()))
     assert err.max() <= 1e-4
+    k.close()
+
+
+def test_f64_real_semiring_reaches_below_the_fp32_range(klay):
+    """deep products of small probabilities: the fp32 real semiring underflows to 0, the double-precision
+    one still agrees with the oracle to rounding, values and gradients"""
+    import torch
+    from oracle import oracle
+    b = CircuitBuilder(40)
+    node = b.and_(b.lit(0), b.lit(1))
+    for v in range(2, 40, 2):
+        alt = b.and_(node, b.lit(v, False))                   # a second, even smaller alternative
+        node = b.and_(b.or_(node, alt), b.lit(v), b.lit(v + 1))
+    c = b.finish([node])
+    p = np.full((3, 40), 1e-3); p[1] *= 2; p[2, ::3] = 0.5
+    k = build(klay, c)
+    out32, _ = gpu_eval(k, p.astype(np.float32), REAL)
+    tw = torch.from_numpy(p).cuda()
+    out64 = k.forward_f64(tw, REAL).cpu().numpy()
+    ref = oracle.forward(*c.arrays(), p, oracle.REAL)
+    assert np.all(ref > 0) and ref.min() < 1e-100 and np.all(out32[ref < 1e-60] == 0.0)
+    np.testing.assert_allclose(out64, ref, rtol=1e-12)
+    g = k.backward_f64(torch.ones(3, 1, dtype=torch.float64, device="cuda")).cpu().numpy()
+    rg = oracle.backward(*c.arrays(), p, oracle.REAL, np.ones((3, 1)))
+    np.testing.assert_allclose(g, rg, rtol=1e-10, atol=0)
     k.close()
