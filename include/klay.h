@@ -151,8 +151,8 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
  * Uses B, the semiring and the activations of that forward call; the caller must not have run
  * another forward in between.  The first real-semiring call on a handle uploads extra index
  * arrays and allocates a per-edge buffer (hipMalloc, which synchronises); later calls only
- * enqueue.  The real semiring is not differentiated on handles built with alias_chains, MAXLOG
- * not at all (KLAY_EINVAL).  A literal whose adjoint is exactly 0 contributes 0 even where the
+ * enqueue (on an alias_chains handle the buffer holds a row per node and per AND-layer edge).
+ * MAXLOG is not differentiated (KLAY_EINVAL).  A literal whose adjoint is exactly 0 contributes 0 even where the
  * derivative of its weight is infinite (log-domain negated literal at p = 1).
  * Errors: KLAY_ESTATE if no forward was run, KLAY_EINVAL, KLAY_EHIP.
  */

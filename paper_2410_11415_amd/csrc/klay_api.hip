@@ -104,6 +104,10 @@ struct klay_circuit {
     std::vector<RealLayer> real_layers;
     int32_t* d_real_index = nullptr;
     int64_t real_max_edges = 0, real_max_seg = 0;
+    // alias mode: the reverse sweep reads one combined buffer [adjoint rows | dout rows | per-edge rows of
+    // every AND layer]; real_edge_base[l] = first per-edge row of AND layer l in it
+    std::vector<int64_t> real_edge_base;
+    int64_t real_and_edges = 0;
     float* real_buf = nullptr;                 // M [max e_l, ld] followed by scratch rows for split rows
     size_t real_buf_bytes = 0;
     void* ws_own = nullptr;
@@ -622,7 +626,53 @@ klay_status ensure_real_bwd(klay_circuit* c, int ld) {
         struct Off { size_t ptr = 0, child = 0; PassOffsets pass{}; klay::PassPlan plan; };
         std::vector<Off> offs((size_t)L + 1);
         klay::Options opt;
-        for (int l = 1; l <= L; l += 2) {                       // AND layers
+        if (p.alias) {
+            // Every row of the activation buffer gathers from its parents in any higher layer: an OR
+            // parent passes its adjoint row, an AND parent the per-edge row of that edge, a root column
+            // its dout row.  All three live in one buffer, so a plain sum over row ids does it.
+            const int64_t NR = p.row0[(size_t)L + 1], R = p.num_roots;
+            c->real_edge_base.assign((size_t)L + 2, 0);
+            int64_t eb = NR + R;
+            for (int l = 1; l <= L; ++l) {
+                c->real_edge_base[(size_t)l] = eb;
+                if (l & 1) eb += p.layers[(size_t)l].e;
+            }
+            c->real_and_edges = eb - (NR + R);
+            if (eb >= ((int64_t)1 << 30)) return fail(KLAY_EINVAL, "klay_backward: more than 2^30 rows in the real-semiring reverse sweep");
+            std::vector<int32_t> gptr((size_t)NR + 1, 0);
+            for (int l = 1; l <= L; ++l)
+                for (int32_t ch : p.layers[(size_t)l].child) ++gptr[(size_t)ch + 1];
+            for (int32_t r = 0; r < R; ++r) ++gptr[(size_t)p.root_pos[(size_t)r] + 1];
+            for (int64_t i = 0; i < NR; ++i) gptr[(size_t)i + 1] += gptr[(size_t)i];
+            std::vector<int32_t> gsrc((size_t)gptr[(size_t)NR]);
+            {
+                std::vector<int32_t> fill(gptr.begin(), gptr.end() - 1);
+                for (int l = 1; l <= L; ++l) {
+                    const klay::LayerPlan& lay = p.layers[(size_t)l];
+                    for (int64_t r = 0; r < lay.n; ++r)
+                        for (int32_t j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j)
+                            gsrc[(size_t)fill[(size_t)lay.child[(size_t)j]]++] =
+                                (l & 1) ? (int32_t)(c->real_edge_base[(size_t)l] + j) : (int32_t)(p.row0[(size_t)l] + r);
+                }
+                for (int32_t r = 0; r < R; ++r) gsrc[(size_t)fill[(size_t)p.root_pos[(size_t)r]]++] = (int32_t)(NR + r);
+            }
+            for (int l = 0; l <= L; ++l) {
+                const klay::LayerPlan& lay = p.layers[(size_t)l];
+                Off& o = offs[(size_t)l];
+                if (l & 1) {
+                    o.ptr = pk.add(lay.row_ptr);
+                    o.child = pk.add(lay.child);
+                }
+                const int64_t a = p.row0[(size_t)l];
+                std::vector<int32_t> lptr((size_t)lay.n + 1);
+                for (int64_t i = 0; i <= lay.n; ++i) lptr[(size_t)i] = gptr[(size_t)(a + i)] - gptr[(size_t)a];
+                klay::make_pass_plan(lay.n, lptr.data(), gsrc.data() + gptr[(size_t)a], opt, o.plan);
+                o.pass = pack_pass(pk, o.plan);
+                c->real_max_seg = std::max<int64_t>(c->real_max_seg, o.plan.n_seg);
+            }
+            c->real_max_edges = eb;          // rows of the combined buffer
+        }
+        for (int l = 1; l <= L && !p.alias; l += 2) {           // AND layers
             const klay::LayerPlan& lay = p.layers[(size_t)l];
             Off& o = offs[(size_t)l];
             o.ptr = pk.add(lay.row_ptr);
@@ -651,10 +701,12 @@ klay_status ensure_real_bwd(klay_circuit* c, int ld) {
                                        hipGetErrorString(e));
         }
         c->real_layers.resize((size_t)L + 1);
-        for (int l = 1; l <= L; l += 2) {
+        for (int l = p.alias ? 0 : 1; l <= L; l += p.alias ? 1 : 2) {
             klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
-            r.ptr = c->d_real_index + offs[(size_t)l].ptr;
-            r.child = c->d_real_index + offs[(size_t)l].child;
+            if (l & 1) {
+                r.ptr = c->d_real_index + offs[(size_t)l].ptr;
+                r.child = c->d_real_index + offs[(size_t)l].child;
+            }
             bind_pass(r.by_child, offs[(size_t)l].plan, offs[(size_t)l].pass, c->d_real_index);
         }
     }
@@ -672,6 +724,7 @@ klay_status ensure_real_bwd(klay_circuit* c, int ld) {
 
 void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* below, const float* gl, float* M,
                        const Geometry& g, int B, hipStream_t s) {
+    if (n <= 0) return;                               // a layer can be empty in alias mode
     const int rpw = 64 / g.w;
     const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
@@ -1272,8 +1325,6 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     if (c->last_semiring == KLAY_MAXLOG)
         return fail(KLAY_EINVAL, "klay_backward: the (max, +) semiring is not differentiated");
     const bool real = c->last_semiring == KLAY_REAL;
-    if (real && c->plan.alias)
-        return fail(KLAY_EINVAL, "klay_backward: the real semiring is not differentiated in alias_chains mode");
     if (!c->last_ws_has_bwd) return fail(KLAY_ENOMEM, "klay_backward: caller workspace has no room for adjoints");
     KLAY_HIP(hipSetDevice(c->device));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1299,6 +1350,36 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (rs != KLAY_OK) return rs;
         float* M = c->real_buf;
         float* rscratch = c->real_buf + (size_t)(c->real_max_edges + 1) * g.ld;
+        if (p.alias) {
+            // one buffer X = [adjoint rows | dout rows | per-edge rows]; layers from the top: gather the
+            // adjoints of the layer's rows, then (product layer) write the per-edge rows of its edges
+            float* X = c->real_buf;
+            prof.begin(KLAY_K_SEED, 8.0 * B * R);
+            hipLaunchKernelGGL(klay::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, g.ld,
+                               X + (size_t)p.num_nodes * g.ld);
+            prof.end();
+            for (int l = L; l >= 0; --l) {
+                const DevLayer& d = c->dl[(size_t)l];
+                float* gl = X + (size_t)d.row0 * g.ld;
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr, nullptr, gl,
+                             rscratch, g, B, s, prof, KLAY_K_BWD_SUM);
+                if (l & 1) {
+                    prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n));
+                    launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act, gl,
+                                      X + (size_t)c->real_edge_base[(size_t)l] * g.ld, g, B, s);
+                    prof.end();
+                }
+            }
+            prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
+            if (V > 0) {
+                dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
+                hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, X, wT, c->d_pos_row, c->d_neg_row, B, V,
+                                   g.ld, lits ? 2 : 0, dleaf, dneg);
+            }
+            prof.end();
+            KLAY_HIP(hipGetLastError());
+            return KLAY_OK;
+        }
         prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
         hipLaunchKernelGGL(klay::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
                            c->d_top_root, B, R, g.ld, gcur);

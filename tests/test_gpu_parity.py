@@ -33,7 +33,7 @@ def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", **kw):
     levels = k.num_layers // 2
     for s in semirings:
         w32 = as_inputs(p, s == LOG)
-        can_bwd = backward and (s == LOG or not kw.get("alias_chains"))
+        can_bwd = backward
         dout = rng.normal(size=(p.shape[0], c.roots.shape[0])).astype(np.float32) if can_bwd else None
         got, gd = gpu_eval(k, w32, s, dout)
         ref, rd = oracle_eval(c, w32, s, dout, or_levels=levels)
@@ -264,10 +264,10 @@ def test_call_order_errors(klay):
     assert e.value.status == 5
     k.close()
     ka = build(klay, c, alias_chains=True)
-    ka.forward(torch.from_numpy(as_inputs(p, False)).cuda(), REAL)
+    ka.forward_f64(torch.from_numpy(as_inputs(p, False).astype(np.float64)).cuda(), REAL)
     with pytest.raises(klay.KlayError) as e:
-        klay.klay_backward(ka._h, d.data_ptr(), g.data_ptr(), 0)
-    assert e.value.status == 1                       # real semiring + alias_chains: not differentiated
+        ka.backward_f64(d.double())
+    assert e.value.status == 1          # double precision, real semiring, alias_chains: not differentiated
     ka.close()
 
 
@@ -633,7 +633,7 @@ def _lits_case(klay, c, B, seed, semirings=(REAL, LOG), **kw):
         a, b = (wp, wn) if s == REAL else (np.log(wp), np.log(wn))
         ta, tb, td = (torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in (a, b, dout))
         out = k.forward(ta, s, neg_weights=tb)
-        can_bwd = s == LOG or not kw.get("alias_chains")
+        can_bwd = True
         if can_bwd:
             dp, dn = (t.cpu().numpy() for t in k.backward(td))
         got = out.cpu().numpy()
