@@ -173,6 +173,11 @@ int klay_oracle_forward(int32_t num_vars, int64_t num_nodes, const uint8_t* node
  *   AND-LOG, OR-REAL : adj(c) += adj(n)
  *   OR-LOG           : adj(c) += adj(n) * exp(val(c) - val(n)); nothing if val(n) = -inf
  *   AND-REAL         : adj(c) += adj(n) * prod of the other children (prefix/suffix products)
+ *   OR gate (LOG)    : child += adj * exp(child value - gate value); a gate at -inf (every child
+ *                      impossible, weights 0/0) passes nothing, except that a gate with a single child
+ *                      is the identity and passes adj unchanged whatever its value: Section 3.1 builds
+ *                      its chains out of exactly such unary gates, so an input gate with one child must
+ *                      behave like a chain node, which is transparent.
  *   literal +v       : dleaf += adj
  *   literal -v       : dleaf += adj * d(neg weight)/dw = -adj (REAL), -adj / expm1(-x) (LOG);
  *                      a zero adjoint contributes 0 even where that derivative is infinite.
@@ -252,6 +257,7 @@ int klay_oracle_backward(int32_t num_vars, int64_t num_nodes, const uint8_t* nod
                     break;
                 case T_OR:
                     if (semiring == S_REAL) { for (int64_t j = a; j < e; ++j) adj[child_idx[j]] += g; }
+                    else if (e - a == 1) adj[child_idx[a]] += g;   /* a unary OR is the identity, also at -inf */
                     else if (val[n] != -INFINITY) {
                         for (int64_t j = a; j < e; ++j) adj[child_idx[j]] += g * exp(val[child_idx[j]] - val[n]);
                     }

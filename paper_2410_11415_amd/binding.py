@@ -67,6 +67,13 @@ def load():
         return _lib
     if not os.path.exists(_build.LIB_PATH):
         _build.build()
+    # PyTorch ships a HIP runtime of its own.  If libklay.so is loaded first it binds to the system
+    # runtime, torch later brings its copy, and whichever of the two initialises the device second
+    # finds none.  With torch imported first the library resolves to the runtime torch has loaded.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_build.LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.klay_build.restype = ctypes.c_int

@@ -507,12 +507,14 @@ __global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer*
             const int beg = ib[r], end = ib[r + 1];
             float acc = 0.0f, mx = 0.0f;
             if (is_and) {
-                for (int j = beg; j < end; ++j) acc += cur[ib[L.n_below + 1 + j] * CT + c];
+                for (int j = beg; j < end; ++j) acc += cur[(ib[L.n_below + 1 + j] & (int)kIdMask) * CT + c];
             } else {
                 const float own = active ? tb[(size_t)col * T + off_below + r] : 0.0f;
                 for (int j = beg; j < end; ++j) {
-                    const int p = ib[L.n_below + 1 + j];
-                    accumulate<OP_SOFTMAX_BWD>(acc, mx, cur[p * CT + c], nl[p * CT + c], own);
+                    // an unweighted edge (chain node or single-child OR above) passes the adjoint unchanged
+                    const uint32_t pe = (uint32_t)ib[L.n_below + 1 + j];
+                    const int p = (int)(pe & kIdMask);
+                    accumulate<OP_SOFTMAX_BWD>(acc, mx, cur[p * CT + c], nl[p * CT + c], own, (pe & kWeighted) != 0);
                 }
             }
             nxt[r * CT + c] = acc;

@@ -528,6 +528,8 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         for (int64_t i = 0; i < lay.n; ++i) layer_fan = std::max<int64_t>(layer_fan, lay.row_ptr[(size_t)i + 1] - lay.row_ptr[(size_t)i]);
         for (int64_t i = 0; i < nc; ++i) layer_fan = std::max<int64_t>(layer_fan, cptr[(size_t)i + 1] - cptr[(size_t)i]);
         if (lay.n <= kTailRowsCap && nc <= kTailRowsCap && e <= kTailEdgesCap && layer_fan <= kTailFanCap) {
+            // the persistent kernels read these plain vectors; parent entries keep the weighted-edge bit
+            for (int64_t j = 0; j < e; ++j) cpar[(size_t)j] = (int32_t)((uint32_t)cpar[(size_t)j] | cflag[(size_t)j]);
             lay.col_ptr.swap(cptr);
             lay.parent.swap(cpar);
         }

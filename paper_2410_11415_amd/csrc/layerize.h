@@ -60,7 +60,7 @@ struct LayerPlan {
     std::vector<int32_t> origin;     // [n] input node id the row stands for
     std::vector<uint8_t> is_pad;     // [n] 1 for unary chain nodes
     std::vector<int32_t> col_ptr;    // [n_below + 1] by child (kept for tail candidates only)
-    std::vector<int32_t> parent;     // [e]
+    std::vector<int32_t> parent;     // [e] parent row, with kWeightedEdge set as in bwd
     PassPlan fwd;                    // outputs = nodes of this layer, sources = layer - 1
     PassPlan bwd;                    // outputs = nodes of layer - 1, sources = this layer
 };

@@ -812,3 +812,47 @@ def test_f64_real_semiring_reaches_below_the_fp32_range(klay):
     rg = oracle.backward(*c.arrays(), p, oracle.REAL, np.ones((3, 1)))
     np.testing.assert_allclose(g, rg, rtol=1e-10, atol=0)
     k.close()
+
+
+# ------------------------------------------------------------------ random DAGs x random build options
+def _random_dag(rng, V, n_gates, hub_share, max_fan):
+    """arbitrary NNF DAG: gate types at random (no alternation), children anywhere below, a few hub
+    nodes with many parents, constants included; children of a gate are distinct nodes"""
+    b = CircuitBuilder(V)
+    nodes = [b.lit(v, bool(s)) for v in range(V) for s in (1, 0)] + [b.true(), b.false()]
+    lits_of = {n: i // 2 for i, n in enumerate(nodes[:2 * V])}
+    for _ in range(n_gates):
+        k = int(rng.integers(1, max_fan + 1))
+        kids, seen_vars = [], set()
+        for _ in range(k):
+            c = int(nodes[int(rng.integers(0, min(len(nodes), 8)))] if rng.random() < hub_share else nodes[int(rng.integers(0, len(nodes)))])
+            if c in kids:
+                continue
+            if c in lits_of:                      # the same literal twice (after leaf merging) is rejected input
+                if (lits_of[c], c) in seen_vars:
+                    continue
+                seen_vars.add((lits_of[c], c))
+            kids.append(c)
+        nodes.append(b.and_(*kids) if rng.random() < 0.5 else b.or_(*kids))
+    roots = [int(nodes[int(rng.integers(2 * V, len(nodes)))]) for _ in range(int(rng.integers(1, 5)))]
+    return b.finish(roots)
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_dags_with_random_options(klay, seed):
+    rng = np.random.default_rng(1000 + seed)
+    V = int(rng.integers(2, 14))
+    c = _random_dag(rng, V, int(rng.integers(5, 400)), hub_share=0.25, max_fan=int(rng.choice([3, 6, 40])))
+    opts = dict(alias_chains=bool(rng.integers(2)), no_merge=bool(rng.integers(2)), no_reorder=bool(rng.integers(2)),
+                no_tail=bool(rng.integers(2)), heavy_fan=int(rng.choice([0, 2, 5, 17])), min_segment=int(rng.choice([0, 1, 3])))
+    B = int(rng.choice([1, 2, 7, 33, 64, 100, 257]))
+    # probabilities near 1/2 keep the real semiring inside fp32 whatever the random structure multiplies up
+    p = rng.uniform(0.35, 0.65, size=(B, V))
+    print("seed", seed, "V", V, "nodes", c.num_nodes, "B", B, opts, flush=True)
+    try:
+        k = build(klay, c, **opts)
+    except klay.KlayError as e:
+        assert e.status == 1, e                      # a structurally invalid draw is rejected, never mis-evaluated
+        pytest.skip("rejected input: " + str(e))
+    k.close()
+    check_both(klay, c, p, what="random dag %d" % seed, **opts)

@@ -504,3 +504,37 @@ def test_negative_literal_weights_default_and_finite_differences():
     # the default's gradient is the chain rule over the two: dpos - dneg (REAL, neg = 1 - p)
     dp, dn = bwd(c, p, REAL, dout, neg_weights=1 - p)
     np.testing.assert_allclose(bwd(c, p, REAL, dout), dp - dn, rtol=1e-10, atol=1e-12)
+
+
+def test_unary_gates_are_identities_for_values_and_gradients():
+    """Section 3.1 pads with single-child gates, so a single-child gate in the input must be transparent:
+    wrapping any node in OR(.) / AND(.) changes neither values nor gradients, also where the value is
+    log 0 = -inf (a softmax over one element has weight 1, not 0/0)."""
+    def circuit(wrap):
+        b = CircuitBuilder(3)
+        x, y, z, nz = b.lit(0), b.lit(1), b.lit(2), b.lit(2, False)
+        u = b.and_(x, y)
+        if wrap:
+            u = b.or_(b.and_(b.or_(u)))
+        dead = b.and_(z, nz, x)                       # impossible once p(z) is 0 or 1
+        if wrap:
+            dead = b.or_(dead)
+        return b.finish([b.or_(u, b.and_(z, y)), dead, b.or_(dead, b.and_(dead, y))])
+    p = np.array([[0.3, 0.6, 0.2], [0.5, 0.1, 1.0], [0.9, 0.4, 0.0]])
+    dout = np.array([[1.0, -2.0, 0.5]] * 3)
+    with np.errstate(divide="ignore"):
+        w = np.log(p)
+    plain, wrapped = circuit(False), circuit(True)
+    np.testing.assert_array_equal(fwd(plain, w, LOG), fwd(wrapped, w, LOG))
+    g0, g1 = bwd(plain, w, LOG, dout), bwd(wrapped, w, LOG, dout)
+    assert not np.isnan(g0[0]).any() and np.all(np.isfinite(g0[0]))
+    np.testing.assert_allclose(g1[0], g0[0], rtol=1e-14)
+    # rows 1 and 2: root 1 is -inf; its adjoint still reaches the leaves through the unary gate exactly as
+    # it does without it (the AND below passes it on), while the two-child OR at -inf (root 2) passes nothing
+    for r in (1, 2):
+        fin = np.isfinite(g0[r])
+        np.testing.assert_array_equal(np.isfinite(g1[r]), fin)
+        np.testing.assert_allclose(g1[r][fin], g0[r][fin], rtol=1e-14)
+    only_root2 = bwd(plain, w, LOG, np.array([[0.0, 0.0, 1.0]] * 3))
+    assert np.all(only_root2[1:][np.isfinite(only_root2[1:])] == 0.0)
+    np.testing.assert_allclose(bwd(plain, p, REAL, dout), bwd(wrapped, p, REAL, dout), rtol=1e-14)
