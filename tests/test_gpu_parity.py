@@ -724,8 +724,8 @@ def _f64_case(klay, c, p, what, backward=True, neg=False, **kw):
         if s == REAL:
             np.testing.assert_allclose(got[~inf], ref[~inf], rtol=1e-12, atol=1e-300, err_msg=what + " f64 " + name)
         else:
-            np.testing.assert_allclose(got[~inf], ref[~inf], rtol=0, atol=1e-11 * max(1.0, np.abs(ref[~inf]).max()),
-                                       err_msg=what + " f64 " + name)
+            scale = max(1.0, np.abs(ref[~inf]).max()) if (~inf).any() else 1.0
+            np.testing.assert_allclose(got[~inf], ref[~inf], rtol=0, atol=1e-11 * scale, err_msg=what + " f64 " + name)
         if backward and (s == LOG or (s == REAL and not kw.get("alias_chains"))):
             g = k.backward_f64(torch.from_numpy(dout).cuda())
             with np.errstate(all="ignore"):
@@ -855,4 +855,9 @@ def test_random_dags_with_random_options(klay, seed):
         assert e.status == 1, e                      # a structurally invalid draw is rejected, never mis-evaluated
         pytest.skip("rejected input: " + str(e))
     k.close()
-    check_both(klay, c, p, what="random dag %d" % seed, **opts)
+    # an arbitrary DAG can push real-semiring values beyond the fp32 range (inf, then inf * 0): no claim there
+    from oracle import oracle
+    with np.errstate(all="ignore"):
+        _, vals = oracle.forward(*c.arrays(), p, oracle.REAL, return_node_values=True)
+    in_range = np.nanmax(np.abs(vals)) < 1e30
+    check_both(klay, c, p, what="random dag %d" % seed, semirings=(REAL, LOG) if in_range else (LOG,), **opts)
