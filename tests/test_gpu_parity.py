@@ -647,7 +647,7 @@ def _lits_case(klay, c, B, seed, semirings=(REAL, LOG), **kw):
             rp, rn = oracle.backward(*c.arrays(), a64, s, d64, nthreads=8, neg_weights=b64)
             mp, mn = oracle.backward(*c.arrays(), a64, s, d64, nthreads=8, neg_weights=b64, path_mass=True)
         fin = np.isfinite(vals)
-        maxabs = float(np.abs(vals[fin]).max())
+        maxabs = float(np.abs(vals[fin]).max()) if fin.any() else 0.0
         rel = 64 * U32 + 4 * U32 * levels * maxabs if s == LOG else (64 + 16 * levels) * U32
         assert_grad_close(dp, GradRef(rp, mp, rel), "lits dpos", real=(s == REAL))
         assert_grad_close(dn, GradRef(rn, mn, rel), "lits dneg", real=(s == REAL))
