@@ -400,6 +400,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     // order): every row of the layer below is then first read in storage order, a sequential
     // stream, and only the remaining reads of a row are scattered.  (Measured on the headline
     // circuit: 12% faster than input order, 2% faster than ordering by the mean child position.)
+    // AND layers are then re-ordered by their first parent (see below).
     auto apply_order = [&](int32_t l, const std::vector<int32_t>& order /* new position -> old slot */) {
         LayerPlan& lay = plan.layers[(size_t)l];
         std::vector<int32_t> origin(lay.origin.size());
@@ -428,7 +429,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         apply_order(0, order);
     }
     if (!opt.no_reorder) {
-        for (int32_t l = 1; l <= L; ++l) {
+        auto order_by_children = [&](int32_t l) {
             LayerPlan& lay = plan.layers[(size_t)l];
             std::vector<double> key((size_t)lay.n);
             for (int64_t s = 0; s < lay.n; ++s) {
@@ -470,7 +471,36 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 });
             }
             apply_order(l, order);
-        }
+        };
+        for (int32_t l = 1; l <= L; ++l) order_by_children(l);
+        // Second sweep, from the top, over the AND layers only: a row moves next to the first of its
+        // parents, so the children of an OR node sit together.  The reverse sweep of an OR layer reads two
+        // rows per edge (adjoint and value of the parent) against one in every other pass, so that pass
+        // gets the locality: its gathers of a parent's rows then hit in L2 for the siblings.  (Measured on
+        // the headline circuit: 2.4% of the step; doing the same for the OR layers, or iterating the two
+        // sweeps, gains nothing more.)
+        auto order_by_parents = [&](int32_t l) {
+            LayerPlan& lay = plan.layers[(size_t)l];
+            if (lay.n <= kTailRowsCap && !opt.no_tail) return;       // keep the fan-sorted order of small layers
+            const LayerPlan& up = plan.layers[(size_t)l + 1];
+            std::vector<int32_t> key((size_t)lay.n, INT32_MAX);
+            for (int64_t p2 = 0; p2 < up.n; ++p2) {
+                const int32_t c = up.origin[(size_t)p2];
+                if (up.is_pad[(size_t)p2]) { int32_t& k2 = key[(size_t)at(c, l)]; k2 = std::min<int32_t>(k2, (int32_t)p2); }
+                else
+                    for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) {
+                        int32_t& k2 = key[(size_t)at(child_idx[j], l)];
+                        k2 = std::min<int32_t>(k2, (int32_t)p2);
+                    }
+            }
+            std::vector<int32_t> order((size_t)lay.n);
+            std::iota(order.begin(), order.end(), 0);
+            std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[(size_t)a] < key[(size_t)b]; });
+            apply_order(l, order);
+        };
+        if (!alias)
+            for (int32_t l = L - 1; l >= 1; --l)
+                if (l & 1) order_by_parents(l);
     }
 
     // ---------------------------------------------------------------- index vectors per layer (Alg. 3), CSR by parent
