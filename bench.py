@@ -28,15 +28,15 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # script (scaled by the copy probe: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), see
 # profiles/stream_kernels_layered_3m_fwd_bwd_hbm_traffic.md.  Keyed by (workload, batch, class).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 489.8e6,    # 398.6 MB fetched + 91.2 MB written
-    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 237.3e6,        # 161.9 MB fetched + 75.4 MB written
+    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 422.9e6,    # 331.7 MB fetched + 91.2 MB written
+    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 236.6e6,        # 161.2 MB fetched + 75.4 MB written
 }
 
 
 # HBM bytes of a whole step from the same counter runs (sum over all dispatches of one step), keyed by
 # (workload, batch, forward+backward?, alias_chains?)
 MEASURED_TRAFFIC_PER_STEP = {
-    ("layered_3m_fwd_bwd", 256, True, False): 26.8e9,
+    ("layered_3m_fwd_bwd", 256, True, False): 25.5e9,
 }
 
 
