@@ -501,6 +501,27 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         if (!alias)
             for (int32_t l = L - 1; l >= 1; --l)
                 if (l & 1) order_by_parents(l);
+        if (alias) {
+            // the same idea without chain nodes: parents sit in any higher layer, so one sweep from the
+            // top keeps, per node, the smallest relative position among its parents seen so far
+            std::vector<double> pkey((size_t)N, 2.0);
+            for (int32_t l = L; l >= 1; --l) {
+                LayerPlan& lay = plan.layers[(size_t)l];
+                if ((l & 1) && l < L) {
+                    std::vector<int32_t> order((size_t)lay.n);
+                    std::iota(order.begin(), order.end(), 0);
+                    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+                        return pkey[(size_t)lay.origin[(size_t)a]] < pkey[(size_t)lay.origin[(size_t)b]];
+                    });
+                    apply_order(l, order);
+                }
+                for (int64_t s2 = 0; s2 < lay.n; ++s2) {
+                    const int32_t c = lay.origin[(size_t)s2];
+                    const double rel = ((double)s2 + 0.5) / (double)lay.n;
+                    for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) pkey[(size_t)child_idx[j]] = std::min(pkey[(size_t)child_idx[j]], rel);
+                }
+            }
+        }
     }
 
     // ---------------------------------------------------------------- index vectors per layer (Alg. 3), CSR by parent
