@@ -448,10 +448,11 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     a.ld = g.ld;
     const double light_rows = (double)dp.n_main - dp.n_heavy;
     if (g.w == 64) {
-        // float4 tiles: the segments of split rows ride in the same launch as the main rows (same
-        // streaming walk, output to scratch rows).  The softmax adjoint's segments need their owner's
-        // value row and narrower tiles measured faster through the generic kernel: separate launch.
-        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec == 4;
+        // Tiles of two or four columns per lane: the segments of split rows ride in the same launch as
+        // the main rows (same streaming walk, output to scratch rows).  The softmax adjoint's segments
+        // need their owner's value row, and one-column tiles (B <= 64) measured 9% faster through the
+        // generic kernel: separate launch.
+        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec >= 2;
         float* seg_base = scratch - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
