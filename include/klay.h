@@ -143,6 +143,26 @@ klay_status klay_forward(klay_circuit* c, const float* leaf_weights, int32_t B, 
                          klay_semiring semiring, void* stream);
 
 /*
+ * klay_forward_static -- klay_forward for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results as
+ * klay_forward, but the layer values, the partial rows of split rows and the transposed leaf weights
+ * live in a fixed array in device memory that is part of the library image (KLAY_STATIC_WORKSPACE_BYTES
+ * per GPU, held until the process ends) instead of the handle's workspace.  The call allocates
+ * nothing (no hipMalloc / hipFree, no events: profiling is not recorded) and only enqueues kernels.
+ *   - A circuit / batch size whose forward workspace, klay_workspace_bytes(c, B, 0), exceeds
+ *     KLAY_STATIC_WORKSPACE_BYTES is refused with KLAY_ENOMEM before anything is launched.
+ *   - Forward only: nothing is kept for klay_backward, and the handle's own state (a previous
+ *     klay_forward that is still to be differentiated) is left untouched.
+ *   - All handles on one GPU share the one array: calls that overlap in time on the same GPU (two
+ *     streams, two threads, two handles) race.  Calls on one stream are ordered and safe; nothing in
+ *     the array has to survive from one call to the next, and nothing is assumed to start at zero.
+ * Errors: as klay_forward.
+ */
+#define KLAY_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+klay_status klay_forward_static(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
+                                klay_semiring semiring, void* stream);
+
+/*
  * klay_backward -- reverse-mode derivative of the most recent klay_forward on this handle
  * (the paper obtains it from autograd, Section 6; here it is a reverse sweep over the layers).
  *   dout          device [B, R] fp32, adjoint of `out`

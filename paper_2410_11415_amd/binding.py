@@ -18,6 +18,7 @@ from . import build as _build
 KLAY_OK, KLAY_EINVAL, KLAY_ECYCLE, KLAY_ENOMEM, KLAY_EHIP, KLAY_ESTATE = range(6)
 KLAY_REAL, KLAY_LOG, KLAY_MAXLOG = 0, 1, 2
 KLAY_LIT, KLAY_AND, KLAY_OR, KLAY_TRUE, KLAY_FALSE = range(5)
+KLAY_STATIC_WORKSPACE_BYTES = 64 << 20
 KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf",
                   "tail_fwd", "tail_bwd", "split", "prod_edges", "fwd_max")
 
@@ -25,7 +26,7 @@ EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
            "klay_set_profiling", "klay_get_profile", "klay_destroy", "klay_last_error", "klay_builder_create",
            "klay_builder_add", "klay_builder_finish", "klay_builder_destroy", "klay_forward_lits", "klay_backward_lits", "klay_root_positions", "klay_forward_f64",
-           "klay_backward_f64")
+           "klay_backward_f64", "klay_forward_static")
 
 
 class KlayError(RuntimeError):
@@ -85,6 +86,8 @@ def load():
     lib.klay_forward.argtypes = [vp, vp, i32, vp, ctypes.c_int, vp]
     lib.klay_backward.restype = ctypes.c_int
     lib.klay_backward.argtypes = [vp, vp, vp, vp]
+    lib.klay_forward_static.restype = ctypes.c_int
+    lib.klay_forward_static.argtypes = [vp, vp, i32, vp, ctypes.c_int, vp]
     lib.klay_forward_lits.restype = ctypes.c_int
     lib.klay_forward_lits.argtypes = [vp, vp, vp, i32, vp, ctypes.c_int, vp]
     lib.klay_backward_lits.restype = ctypes.c_int
@@ -157,6 +160,10 @@ def klay_build(num_vars, num_nodes, node_type_ptr, node_lit_ptr, child_ptr_ptr, 
 
 def klay_forward(handle, leaf_weights_ptr, B, out_ptr, semiring, stream=0):
     _check(load().klay_forward(handle, leaf_weights_ptr, B, out_ptr, semiring, stream))
+
+
+def klay_forward_static(handle, leaf_weights_ptr, B, out_ptr, semiring, stream=0):
+    _check(load().klay_forward_static(handle, leaf_weights_ptr, B, out_ptr, semiring, stream))
 
 
 def klay_backward(handle, dout_ptr, dleaf_ptr, stream=0):
@@ -349,6 +356,21 @@ class Circuit:
                               int(semiring), self._stream(stream))
         self._last_B = B
         self._last_lits = neg_weights is not None
+        return out
+
+    def forward_static(self, leaf_weights, semiring=KLAY_LOG, out=None, stream=None):
+        """klay_forward_static: the forward pass in the library's fixed device array (no allocation by the
+        library; ``out`` should be passed in by a caller that must not allocate either)."""
+        import torch
+        if (leaf_weights.dtype != torch.float32 or not leaf_weights.is_cuda or not leaf_weights.is_contiguous()
+                or leaf_weights.dim() != 2 or leaf_weights.shape[1] != self.num_vars):
+            raise ValueError("leaf_weights must be a contiguous float32 CUDA tensor [B, %d]" % self.num_vars)
+        B = leaf_weights.shape[0]
+        if out is None:
+            out = torch.empty((B, self.num_roots), dtype=torch.float32, device=leaf_weights.device)
+        elif out.shape != (B, self.num_roots) or out.dtype != torch.float32 or not out.is_contiguous():
+            raise ValueError("out must be a contiguous float32 tensor [B, R]")
+        klay_forward_static(self._h, leaf_weights.data_ptr(), B, out.data_ptr(), int(semiring), self._stream(stream))
         return out
 
     def backward(self, dout, dleaf=None, stream=None, dneg=None):

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -16,9 +17,34 @@
 #include "klay_kernels_f64.hip.h"
 #include "layerize.h"
 
+// Workspace of klay_forward_static, the entry point that allocates nothing: a fixed array in device
+// memory.  Every GPU the library runs on holds its own copy at its own address until the process
+// ends.  In host code the name below is only a handle for hipGetSymbolAddress; the kernels get the
+// address that call returned (kept per device in g_static_ws).
+constexpr size_t kStaticWorkspaceBytes = KLAY_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
 namespace {
 
 thread_local std::string g_err;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+float* g_static_ws[kMaxDevices] = {};      // device address of `scratch` on each device
+
+// Looks the array's address up once per device; `device` must be the current device.
+hipError_t static_workspace(int device, float** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ws[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_static_ws[device] = static_cast<float*>(ptr);
+    }
+    *out = g_static_ws[device];
+    return hipSuccess;
+}
 
 klay_status fail(klay_status s, const std::string& msg) {
     g_err = msg;
@@ -73,7 +99,7 @@ Geometry geometry(int B) {
 size_t align_floats(size_t n) { return (n + 63) / 64 * 64; }
 
 struct Workspace {
-    size_t act = 0, wT = 0, scratch = 0, g0 = 0, g1 = 0, tb = 0, total = 0;   // offsets in floats
+    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, tb = 0, total = 0;   // offsets in floats
 };
 
 struct EventRec {
@@ -108,7 +134,7 @@ struct klay_circuit {
     // every AND layer]; real_edge_base[l] = first per-edge row of AND layer l in it
     std::vector<int64_t> real_edge_base;
     int64_t real_and_edges = 0;
-    float* real_buf = nullptr;                 // M [max e_l, ld] followed by scratch rows for split rows
+    float* real_buf = nullptr;                 // M [max e_l, ld] followed by the partial rows of split rows
     size_t real_buf_bytes = 0;
     void* ws_own = nullptr;
     size_t ws_own_bytes = 0;
@@ -145,7 +171,7 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     w.act = off; off += align_floats((size_t)p.num_nodes * g.ld);
     w.wT = off; off += align_floats((size_t)std::max(1, p.num_vars) * g.ld);
     const int64_t seg = std::max(p.max_fwd_seg, need_bwd ? p.max_bwd_seg : 0);
-    w.scratch = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
+    w.seg_rows = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
     // values of the tail layers, one run of tail_rows floats per batch column
     w.tb = off; off += align_floats((size_t)c->tail_rows * (size_t)B);
     if (need_bwd && p.alias) {
@@ -205,7 +231,7 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
 }
 
 // Streaming kernel over the main rows of a pass and / or the segments of its split rows (batch
-// tiles of one wave: B > 32).  dst_seg is the scratch base shifted by -n_main rows: segment rows are
+// tiles of one wave: B > 32).  dst_seg is the base of the partial rows shifted by -n_main rows: segment rows are
 // numbered after the main rows.
 template <int OP>
 void launch_stream_op(const DevPass& dp, bool main_rows, bool segments, const Geometry& g, const float* src,
@@ -245,7 +271,8 @@ struct Profiler {
     hipStream_t s;
     size_t next = 0;
     bool on;
-    Profiler(klay_circuit* c_, std::vector<EventRec>* r, hipStream_t s_) : c(c_), recs(r), s(s_), on(c_->profiling) {
+    Profiler(klay_circuit* c_, std::vector<EventRec>* r, hipStream_t s_, bool enable = true)
+        : c(c_), recs(r), s(s_), on(enable && c_->profiling) {
         if (on) recs->clear();
     }
     hipEvent_t get() {
@@ -388,6 +415,10 @@ klay_status upload(klay_circuit* c) {
     const size_t o_tptr = pk.add(p.top_ptr), o_troot = pk.add(p.top_root);
 
     KLAY_HIP(hipSetDevice(c->device));
+    {
+        float* static_ws = nullptr;      // klay_forward_static's workspace on this device
+        KLAY_HIP(static_workspace(c->device, &static_ws));
+    }
     c->index_bytes = pk.buf.size() * sizeof(int32_t);
     if (hipMalloc(reinterpret_cast<void**>(&c->d_index), c->index_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -430,7 +461,7 @@ double pass_bytes(int op, double entries, double rows, int B) {
 // One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.  The main
 // launch is timed under `cls`, the launches that serve split rows under KLAY_K_SPLIT.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
-                  const float* own, float* dst, float* scratch, const Geometry& g, int B, hipStream_t s,
+                  const float* own, float* dst, float* seg_rows, const Geometry& g, int B, hipStream_t s,
                   Profiler& prof, int cls) {
     klay::PassArgs a{};
     a.ptr = dp.ptr;
@@ -441,7 +472,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     a.seg_owner = dp.seg_owner;
     a.out_row = nullptr;
     a.dst = dst;
-    a.dst_seg = scratch;
+    a.dst_seg = seg_rows;
     a.n_main = dp.n_main;
     a.n_total = dp.n_main + dp.n_seg;
     a.B = B;
@@ -449,11 +480,11 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     const double light_rows = (double)dp.n_main - dp.n_heavy;
     if (g.w == 64) {
         // Tiles of two or four columns per lane: the segments of split rows ride in the same launch as
-        // the main rows (same streaming walk, output to scratch rows).  The softmax adjoint's segments
+        // the main rows (same streaming walk, output to partial rows).  The softmax adjoint's segments
         // need their owner's value row, and one-column tiles (B <= 64) measured 9% faster through the
         // generic kernel: separate launch.
         const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec >= 2;
-        float* seg_base = scratch - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
+        float* seg_base = seg_rows - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
         prof.begin(cls, bytes);
@@ -475,7 +506,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         klay::PassArgs cmb{};
         cmb.ptr = dp.comb_ptr;
         cmb.idx = dp.comb_idx;
-        cmb.src = scratch;
+        cmb.src = seg_rows;
         cmb.out_row = dp.comb_row;
         cmb.dst = dst;
         cmb.dst_seg = nullptr;
@@ -750,7 +781,7 @@ void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* bel
 
 // ---- double-precision evaluation ---------------------------------------------------------------
 struct Workspace64 {
-    size_t act = 0, wT = 0, scratch = 0, g0 = 0, g1 = 0, total = 0;   // offsets in doubles
+    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, total = 0;   // offsets in doubles
 };
 
 Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
@@ -760,7 +791,7 @@ Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
     auto take = [&](size_t n) { const size_t o = off; off += (n + 31) / 32 * 32; return o; };
     w.act = take((size_t)p.num_nodes * ld);
     w.wT = take((size_t)std::max(1, p.num_vars) * ld);
-    w.scratch = take((size_t)std::max<int64_t>(std::max(p.max_fwd_seg, p.max_bwd_seg), 1) * ld);
+    w.seg_rows = take((size_t)std::max<int64_t>(std::max(p.max_fwd_seg, p.max_bwd_seg), 1) * ld);
     if (p.alias) {
         w.g0 = take((size_t)(p.num_nodes + p.num_roots) * ld);
         w.g1 = w.g0;
@@ -796,7 +827,7 @@ void launch_pass64(int op, const klay::f64::PassArgs& a, hipStream_t s) {
 
 // main rows and segments in one launch, then the combine rows of split rows
 void run_pass_set64(int op, int combine_op, const DevPass& dp, const double* src, const double* src2,
-                    const double* own, double* dst, double* scratch, int B, int ld, hipStream_t s) {
+                    const double* own, double* dst, double* seg_rows, int B, int ld, hipStream_t s) {
     klay::f64::PassArgs a{};
     a.ptr = dp.ptr;
     a.idx = dp.idx;
@@ -806,7 +837,7 @@ void run_pass_set64(int op, int combine_op, const DevPass& dp, const double* src
     a.seg_owner = dp.seg_owner;
     a.out_row = nullptr;
     a.dst = dst;
-    a.dst_seg = scratch;
+    a.dst_seg = seg_rows;
     a.n_main = dp.n_main;
     a.n_total = dp.n_main + dp.n_seg;
     a.B = B;
@@ -816,7 +847,7 @@ void run_pass_set64(int op, int combine_op, const DevPass& dp, const double* src
         klay::f64::PassArgs cmb{};
         cmb.ptr = dp.comb_ptr;
         cmb.idx = dp.comb_idx;
-        cmb.src = scratch;
+        cmb.src = seg_rows;
         cmb.out_row = dp.comb_row;
         cmb.dst = dst;
         cmb.n_main = dp.n_heavy;
@@ -852,7 +883,7 @@ klay_status forward64_impl(klay_circuit* c, const double* w, const double* wneg,
     double* ws = static_cast<double*>(c->ws64);
     double* act = ws + lay.act;
     double* wT = ws + lay.wT;
-    double* scratch = ws + lay.scratch;
+    double* seg_rows = ws + lay.seg_rows;
     const int L = p.num_layers, V = p.num_vars;
     const bool log_domain = semiring != KLAY_REAL;
     const dim3 row_grid((unsigned)((ld + 255) / 256));
@@ -871,7 +902,7 @@ klay_status forward64_impl(klay_circuit* c, const double* w, const double* wneg,
         const int or_op = semiring == KLAY_MAXLOG ? klay::OP_MAX : klay::OP_LSE;
         const int op = log_domain ? (is_and ? klay::OP_SUM : or_op) : (is_and ? klay::OP_PROD : klay::OP_SUM);
         const double* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * ld;
-        run_pass_set64(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * ld, scratch, B, ld, s);
+        run_pass_set64(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * ld, seg_rows, B, ld, s);
     }
     hipLaunchKernelGGL(klay::f64::root_out_kernel, dim3((unsigned)p.num_roots), dim3(256), 0, s,
                        p.alias ? act : act + (size_t)c->dl[(size_t)L].row0 * ld, c->d_root_pos, (int)B, p.num_roots, ld,
@@ -903,7 +934,7 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     double* ws = static_cast<double*>(c->ws64);
     double* act = ws + lay.act;
     double* wT = ws + lay.wT;
-    double* scratch = ws + lay.scratch;
+    double* seg_rows = ws + lay.seg_rows;
     double* gcur = ws + lay.g0;
     double* gnext = ws + lay.g1;
     const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
@@ -924,19 +955,19 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
             c->real_buf64_bytes = need;
         }
         double* M = c->real_buf64;
-        double* rscratch = c->real_buf64 + (size_t)(c->real_max_edges + 1) * ld;
+        double* real_seg_rows = c->real_buf64 + (size_t)(c->real_max_edges + 1) * ld;
         hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
                            c->d_top_root, B, R, ld, gcur);
         for (int l = L; l >= 1; --l) {
             const DevLayer& d = c->dl[(size_t)l];
             const DevLayer& below = c->dl[(size_t)l - 1];
             if ((l & 1) == 0) {
-                run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, B, ld, s);
+                run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, B, ld, s);
             } else {
                 const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
                 hipLaunchKernelGGL(klay::f64::prod_edge_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
                                    dim3(256), 0, s, r.ptr, r.child, act + (size_t)below.row0 * ld, gcur, M, (int)d.n, B, ld);
-                run_pass_set64(klay::OP_SUM, klay::OP_SUM, r.by_child, M, nullptr, nullptr, gnext, rscratch, B, ld, s);
+                run_pass_set64(klay::OP_SUM, klay::OP_SUM, r.by_child, M, nullptr, nullptr, gnext, real_seg_rows, B, ld, s);
             }
             std::swap(gcur, gnext);
         }
@@ -954,7 +985,7 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
             const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
             const DevLayer& d = c->dl[(size_t)l];
             run_pass_set64(dp.has_weighted ? klay::OP_SOFTMAX_BWD : klay::OP_SUM, klay::OP_SUM, dp, G, act,
-                           act + (size_t)d.row0 * ld, G + (size_t)d.row0 * ld, scratch, B, ld, s);
+                           act + (size_t)d.row0 * ld, G + (size_t)d.row0 * ld, seg_rows, B, ld, s);
         }
         if (V > 0)
             hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B,
@@ -968,10 +999,10 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
         const DevLayer& d = c->dl[(size_t)l];
         const DevLayer& below = c->dl[(size_t)l - 1];
         if ((l & 1) != 0 || !d.bwd.has_weighted)
-            run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, B, ld, s);
+            run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, B, ld, s);
         else
             run_pass_set64(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * ld,
-                           act + (size_t)below.row0 * ld, gnext, scratch, B, ld, s);
+                           act + (size_t)below.row0 * ld, gnext, seg_rows, B, ld, s);
         std::swap(gcur, gnext);
     }
     if (V > 0)
@@ -1229,8 +1260,10 @@ klay_status klay_get_profile(klay_circuit* c, klay_profile_t* prof) {
     return KLAY_OK;
 }
 
+// static_ws: run in the fixed device array instead of the handle's workspace (klay_forward_static):
+// no allocation, no event, nothing kept for a backward pass.
 static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, const float* neg_weights, int32_t B,
-                                float* out, klay_semiring semiring, void* stream) {
+                                float* out, klay_semiring semiring, void* stream, bool static_ws = false) {
     if (!c || !leaf_weights || !out) return fail(KLAY_EINVAL, "klay_forward: null argument");
     if (c->device < 0) return fail(KLAY_ESTATE, "klay_forward: host-only handle (built with device = -1)");
     if (B < 1) return fail(KLAY_EINVAL, "klay_forward: B must be >= 1");
@@ -1241,23 +1274,33 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     const klay::CircuitPlan& p = c->plan;
     const Geometry g = geometry(B);
     const bool log_domain = semiring != KLAY_REAL;      // leaf weights are log p in both log-domain semirings
-    if (c->profiling && !c->ev_pool.empty()) release_events(c);
+    if (!static_ws && c->profiling && !c->ev_pool.empty()) release_events(c);
 
     float* ws = nullptr;
     Workspace lay;
-    c->have_fwd = false;
+    if (!static_ws) c->have_fwd = false;     // a static call leaves the handle's own forward state alone
     // the backward regions are part of the layout whenever the workspace can hold them
     bool with_bwd = true;
-    if (c->ws_user && workspace_layout(c, B, true).total * sizeof(float) > c->ws_user_bytes) with_bwd = false;
-    klay_status st = get_workspace(c, B, with_bwd, &ws, &lay);
-    if (st != KLAY_OK) return st;
+    if (static_ws) {
+        with_bwd = false;
+        lay = workspace_layout(c, B, false);
+        if (lay.total * sizeof(float) > kStaticWorkspaceBytes)
+            return fail(KLAY_ENOMEM, "klay_forward_static: this circuit at B = " + std::to_string(B) + " needs " +
+                                         std::to_string(lay.total * sizeof(float)) + " workspace bytes, the fixed buffer holds " +
+                                         std::to_string(kStaticWorkspaceBytes));
+        KLAY_HIP(static_workspace(c->device, &ws));
+    } else {
+        if (c->ws_user && workspace_layout(c, B, true).total * sizeof(float) > c->ws_user_bytes) with_bwd = false;
+        klay_status st = get_workspace(c, B, with_bwd, &ws, &lay);
+        if (st != KLAY_OK) return st;
+    }
 
     float* act = ws + lay.act;
     float* wT = ws + lay.wT;
-    float* scratch = ws + lay.scratch;
+    float* seg_rows = ws + lay.seg_rows;
     const int L = p.num_layers;
     const int V = p.num_vars;
-    Profiler prof(c, &c->ev_fwd, s);
+    Profiler prof(c, &c->ev_fwd, s, !static_ws);
 
     // leaf layer
     prof.begin(KLAY_K_LEAF, 4.0 * B * V + 4.0 * B * (double)(V + p.layers[0].n));
@@ -1287,7 +1330,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
                         : op == klay::OP_MAX ? KLAY_K_FWD_MAX : KLAY_K_FWD_LSE;
         // alias mode: child entries are rows of the whole buffer, otherwise of the layer below
         const float* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
-        run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, scratch, g, B, s, prof, cls);
+        run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
     }
 
     if (tail.first > 0) {
@@ -1306,6 +1349,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     }
     prof.end();
     KLAY_HIP(hipGetLastError());
+    if (static_ws) return KLAY_OK;       // the values live in the shared array: nothing to differentiate later
     c->have_fwd = true;
     c->last_B = B;
     c->last_semiring = semiring;
@@ -1338,7 +1382,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     if (st != KLAY_OK) return st;
     float* act = ws + lay.act;
     float* wT = ws + lay.wT;
-    float* scratch = ws + lay.scratch;
+    float* seg_rows = ws + lay.seg_rows;
     float* gcur = ws + lay.g0;
     float* gnext = ws + lay.g1;
     const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
@@ -1350,7 +1394,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         klay_status rs = ensure_real_bwd(c, g.ld);
         if (rs != KLAY_OK) return rs;
         float* M = c->real_buf;
-        float* rscratch = c->real_buf + (size_t)(c->real_max_edges + 1) * g.ld;
+        float* real_seg_rows = c->real_buf + (size_t)(c->real_max_edges + 1) * g.ld;
         if (p.alias) {
             // one buffer X = [adjoint rows | dout rows | per-edge rows]; layers from the top: gather the
             // adjoints of the layer's rows, then (product layer) write the per-edge rows of its edges
@@ -1363,7 +1407,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
                 const DevLayer& d = c->dl[(size_t)l];
                 float* gl = X + (size_t)d.row0 * g.ld;
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr, nullptr, gl,
-                             rscratch, g, B, s, prof, KLAY_K_BWD_SUM);
+                             real_seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
                 if (l & 1) {
                     prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n));
                     launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act, gl,
@@ -1389,14 +1433,14 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             const DevLayer& d = c->dl[(size_t)l];
             const DevLayer& below = c->dl[(size_t)l - 1];
             if ((l & 1) == 0) {
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s, prof,
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, g, B, s, prof,
                              KLAY_K_BWD_SUM);
             } else {
                 prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n));
                 launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, M, g, B, s);
                 prof.end();
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, M, nullptr, nullptr, gnext,
-                             rscratch, g, B, s, prof, KLAY_K_BWD_SUM);
+                             real_seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
             }
             std::swap(gcur, gnext);
         }
@@ -1424,9 +1468,9 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             const DevLayer& d = c->dl[(size_t)l];
             if (dp.has_weighted)
                 run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, act + (size_t)d.row0 * g.ld,
-                             G + (size_t)d.row0 * g.ld, scratch, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
+                             G + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
             else
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, G + (size_t)d.row0 * g.ld, scratch,
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, G + (size_t)d.row0 * g.ld, seg_rows,
                              g, B, s, prof, KLAY_K_BWD_SUM);
         }
         prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
@@ -1463,11 +1507,11 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         const DevLayer& below = c->dl[(size_t)l - 1];
         const bool is_and = (l & 1) != 0 || !d.bwd.has_weighted;   // no weighted edge: plain sums
         if (is_and)
-            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, scratch, g, B, s, prof,
+            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, g, B, s, prof,
                          KLAY_K_BWD_SUM);
         else
             run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld,
-                         act + (size_t)below.row0 * g.ld, gnext, scratch, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
+                         act + (size_t)below.row0 * g.ld, gnext, seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
         std::swap(gcur, gnext);
     }
 
@@ -1496,6 +1540,15 @@ klay_status klay_forward_lits(klay_circuit* c, const float* pos_weights, const f
     } catch (const std::bad_alloc&) {
         if (c) c->have_fwd = false;
         return fail(KLAY_ENOMEM, "klay_forward: out of host memory");
+    }
+}
+
+klay_status klay_forward_static(klay_circuit* c, const float* leaf_weights, int32_t B, float* out,
+                                klay_semiring semiring, void* stream) {
+    try {
+        return forward_impl(c, leaf_weights, nullptr, B, out, semiring, stream, true);
+    } catch (const std::bad_alloc&) {
+        return fail(KLAY_ENOMEM, "klay_forward_static: out of host memory");
     }
 }
 
