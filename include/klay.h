@@ -90,7 +90,10 @@ enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];
-    double  alg_bytes[KLAY_K_COUNT];   /* algorithmic bytes moved by those launches (no-reuse model) */
+    double  alg_bytes[KLAY_K_COUNT];   /* algorithmic bytes moved by those launches (no-reuse model:
+                                          every index entry gathers its row from memory)             */
+    double  min_bytes[KLAY_K_COUNT];   /* compulsory bytes of those launches: every distinct source row
+                                          read once, every output row written once, plus the indices */
 } klay_profile_t;
 
 /*
@@ -115,8 +118,10 @@ typedef struct klay_profile_t {
  * under an AND) are lifted one layer so that odd layers hold AND and even layers OR (Section 3.1).
  * Layer-skipping edges get one chain of unary nodes per (child, layer); all roots are extended to
  * the height of the tallest (Section 3.2).
- * Errors: KLAY_EINVAL (bad sizes, index or literal out of range, a gate without children, a child
- * listed twice under one gate, a leaf with children, no roots), KLAY_ECYCLE, KLAY_ENOMEM, KLAY_EHIP.
+ * Errors: KLAY_EINVAL (bad sizes, index or literal out of range, a gate without children, a gate of the
+ * circuit that lists the same node id twice, a leaf with children, no roots), KLAY_ECYCLE, KLAY_ENOMEM,
+ * KLAY_EHIP.  Two different leaf nodes with the same literal under one gate, or two gates that turn out
+ * identical, are two children and count twice (Eq. 1).
  */
 klay_status klay_build(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type,
                        const int32_t* node_lit, const int64_t* child_ptr, const int32_t* child_idx,

@@ -51,7 +51,8 @@ class klay_info_t(ctypes.Structure):
 
 
 class klay_profile_t(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_float * 14), ("launches", ctypes.c_int32 * 14), ("alg_bytes", ctypes.c_double * 14)]
+    _fields_ = [("ms", ctypes.c_float * 14), ("launches", ctypes.c_int32 * 14), ("alg_bytes", ctypes.c_double * 14),
+                ("min_bytes", ctypes.c_double * 14)]
 
 
 _lib = None
@@ -321,7 +322,8 @@ class Circuit:
     def get_profile(self) -> dict:
         p = klay_profile_t()
         _check(load().klay_get_profile(self._h, ctypes.byref(p)))
-        return {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i]), "alg_bytes": float(p.alg_bytes[i])}
+        return {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i]), "alg_bytes": float(p.alg_bytes[i]),
+                       "min_bytes": float(p.min_bytes[i])}
                 for i, name in enumerate(KERNEL_CLASSES)}
 
     # -- evaluation

@@ -10,7 +10,6 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libklay.so")
 SOURCES = ["klay_api.hip", "layerize.cpp"]
-HEADERS = ["klay_kernels.hip.h", "layerize.h", os.path.join("..", "..", "include", "klay.h")]
 
 
 def hipcc() -> str:
@@ -18,13 +17,6 @@ def hipcc() -> str:
     if not os.path.exists(exe):
         raise RuntimeError("hipcc not found; the GPU library cannot be built")
     return exe
-
-
-def is_stale() -> bool:
-    if not os.path.exists(LIB_PATH):
-        return True
-    t = os.path.getmtime(LIB_PATH)
-    return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
 
 
 def build(verbose: bool = False) -> str:

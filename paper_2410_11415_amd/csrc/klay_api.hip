@@ -68,6 +68,7 @@ struct DevPass {
     bool has_weighted = false;
     int64_t edges = 0;
     int64_t main_entries = 0, seg_entries = 0;   // index entries of light main rows / of segments
+    int64_t n_src = 0;                           // distinct source rows the pass reads
 };
 
 struct DevLayer {
@@ -105,7 +106,7 @@ struct Workspace {
 struct EventRec {
     int cls;
     hipEvent_t start, stop;
-    double bytes;
+    double bytes, min_bytes;
 };
 
 }  // namespace
@@ -282,9 +283,10 @@ struct Profiler {
         c->ev_pool.push_back(e);
         return e;
     }
-    void begin(int cls, double bytes) {
+    // bytes: no-reuse model; min_bytes: compulsory bytes (every distinct row once); < 0: same as bytes
+    void begin(int cls, double bytes, double min_bytes = -1.0) {
         if (!on) return;
-        EventRec r{cls, get(), get(), bytes};
+        EventRec r{cls, get(), get(), bytes, min_bytes < 0 ? bytes : min_bytes};
         if (r.start) (void)hipEventRecord(r.start, s);
         recs->push_back(r);
     }
@@ -368,6 +370,14 @@ void bind_pass(DevPass& d, const klay::PassPlan& p, const PassOffsets& o, const 
     d.n_seg = p.n_seg;
     d.n_heavy = p.n_heavy;
     d.edges = p.edges;
+    // distinct source rows (for the compulsory-byte count of the profile)
+    uint32_t max_id = 0;
+    const size_t n_entries = (size_t)p.ptr[(size_t)p.n_main + (size_t)p.n_seg];
+    for (size_t j = 0; j < n_entries; ++j)
+        if (p.idx[j] != klay::kSkipRow) max_id = std::max(max_id, p.idx[j] & klay::kIdMask);
+    std::vector<uint8_t> seen((size_t)max_id + 1, 0);
+    for (size_t j = 0; j < n_entries; ++j)
+        if (p.idx[j] != klay::kSkipRow && !seen[p.idx[j] & klay::kIdMask]) { seen[p.idx[j] & klay::kIdMask] = 1; ++d.n_src; }
 }
 
 klay_status upload(klay_circuit* c) {
@@ -458,6 +468,12 @@ double pass_bytes(int op, double entries, double rows, int B) {
     return 4.0 * B * (per_entry * entries + per_row * rows) + 4.0 * (entries + rows);
 }
 
+// Compulsory bytes of the same pass: every distinct source row and every output row moves once.
+double pass_min_bytes(int op, double entries, double rows, double n_src, int B) {
+    const double f = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
+    return 4.0 * B * f * (n_src + rows) + 4.0 * (entries + rows);
+}
+
 // One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.  The main
 // launch is timed under `cls`, the launches that serve split rows under KLAY_K_SPLIT.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
@@ -487,18 +503,24 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         float* seg_base = seg_rows - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
-        prof.begin(cls, bytes);
+        // the distinct source rows are charged to the main launch, a separate segment launch only
+        // adds its index entries and the partial rows it writes
+        double min_bytes = pass_min_bytes(op, (double)dp.main_entries, light_rows, (double)dp.n_src, B);
+        if (merged) min_bytes += pass_min_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, 0.0, B);
+        prof.begin(cls, bytes, min_bytes);
         launch_stream(op, dp, true, merged, g, src, src2, own, dst, seg_base, B, s);
         prof.end();
         if (dp.n_seg > 0 && !merged) {
-            prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B));
+            prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B),
+                       pass_min_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, 0.0, B));
             a.row_begin = dp.n_main;
             launch_pass(op, a, g, s);
             prof.end();
         }
     } else {
         a.row_begin = 0;                         // small batches: main rows and segments in one launch
-        prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B));
+        prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B),
+                   pass_min_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, (double)dp.n_src, B));
         launch_pass(op, a, g, s);
         prof.end();
     }
@@ -716,6 +738,8 @@ klay_status ensure_real_bwd(klay_circuit* c, int ld) {
             for (int64_t i = 0; i < nc; ++i) cptr[(size_t)i + 1] += cptr[(size_t)i];
             std::vector<int32_t> fill(cptr.begin(), cptr.end() - 1);
             for (int64_t j = 0; j < lay.e; ++j) cedge[(size_t)fill[(size_t)lay.child[(size_t)j]]++] = (int32_t)j;
+            // entries are edge positions: they share the 30-bit id field of the index entries
+            if (lay.e >= ((int64_t)1 << 30)) return fail(KLAY_EINVAL, "klay_backward: an AND layer has 2^30 edges or more");
             klay::make_pass_plan(nc, cptr.data(), cedge.data(), opt, o.plan);
             o.pass = pack_pass(pk, o.plan);
             c->real_max_edges = std::max<int64_t>(c->real_max_edges, lay.e);
@@ -1256,6 +1280,7 @@ klay_status klay_get_profile(klay_circuit* c, klay_profile_t* prof) {
             prof->ms[r.cls] += ms;
             prof->launches[r.cls] += 1;
             prof->alg_bytes[r.cls] += r.bytes;
+            prof->min_bytes[r.cls] += r.min_bytes;
         }
     return KLAY_OK;
 }
@@ -1409,7 +1434,8 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr, nullptr, gl,
                              real_seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
                 if (l & 1) {
-                    prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n));
+                    prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n),
+                               4.0 * B * ((double)d.e + 2.0 * (double)d.n));
                     launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act, gl,
                                       X + (size_t)c->real_edge_base[(size_t)l] * g.ld, g, B, s);
                     prof.end();
@@ -1436,7 +1462,8 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, g, B, s, prof,
                              KLAY_K_BWD_SUM);
             } else {
-                prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n));
+                prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n),
+                               4.0 * B * ((double)d.e + 2.0 * (double)d.n));
                 launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, M, g, B, s);
                 prof.end();
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, M, nullptr, nullptr, gnext,

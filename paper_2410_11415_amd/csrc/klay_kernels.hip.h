@@ -39,6 +39,10 @@ struct PassArgs {
     int32_t iters;             // row groups per wave
 };
 
+// s_waitcnt immediate (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8) that waits
+// for vmcnt = 0 only: expcnt and lgkmcnt keep their maxima (7 and 15), so scalar loads stay in flight.
+constexpr int kWaitVmcnt0 = 0x0F70;
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
         for (int i = 0; i < CH; ++i) nxt[i] = idx[j + CH + i];       // padded: always readable
         // s_waitcnt vmcnt(0) (scalar prefetch left in flight): the gathers are complete on every
         // path from here on, so no later register reuse has to wait on them again.
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             // branch-free accumulation: a dead entry contributes the identity

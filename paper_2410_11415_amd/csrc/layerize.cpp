@@ -196,13 +196,6 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         for (int32_t r = 0; r < R; ++r) croots[(size_t)r] = canon[(size_t)roots[r]];
         child_idx = cidx.data();
         roots = croots.data();
-        std::vector<int32_t> stamp((size_t)N, -1);
-        for (int64_t i = 0; i < N; ++i)
-            for (int64_t j = child_ptr[i]; j < child_ptr[i + 1]; ++j) {
-                int32_t c = child_idx[j];
-                if (stamp[(size_t)c] == (int32_t)i) { err = "klay_build: gate " + std::to_string(i) + " lists a child twice"; return ST_INVAL; }
-                stamp[(size_t)c] = (int32_t)i;
-            }
     }
 
     // ---------------------------------------------------------------- parents of every node
@@ -308,6 +301,20 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             for (int64_t j = child_ptr[n]; j < child_ptr[n + 1]; ++j) {
                 int32_t c = child_idx[j];
                 if (!reach[(size_t)c]) { reach[(size_t)c] = 1; stack.push_back(c); }
+            }
+        }
+    }
+    // A gate that is part of the circuit must not name the same input node twice (the children of a
+    // gate are a set, Eq. 1).  Checked on the ids as given: two different leaf nodes that carry the same
+    // literal, or two gates that turn out identical, are two children and count twice, as in Eq. 1.
+    {
+        std::vector<int32_t> stamp((size_t)N, -1);
+        for (int64_t i = 0; i < N; ++i) {
+            if (!reach[(size_t)i]) continue;
+            for (int64_t j = child_ptr[i]; j < child_ptr[i + 1]; ++j) {
+                const int32_t c = child_idx_in[j];
+                if (stamp[(size_t)c] == (int32_t)i) { err = "klay_build: gate " + std::to_string(i) + " lists a child twice"; return ST_INVAL; }
+                stamp[(size_t)c] = (int32_t)i;
             }
         }
     }

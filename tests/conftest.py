@@ -22,3 +22,13 @@ def golden():
         with open(os.path.join(GOLDEN, name)) as f:
             return parse_text_circuit(f.read())
     return load
+
+
+def pytest_terminal_summary(terminalreporter):
+    try:
+        from tests import gpu_util
+    except Exception:
+        return
+    if gpu_util.WORST_PLAIN_RATIO[0] > 0:
+        terminalreporter.write_line("gradients under random dout: worst error / (1e-4 max(1, |ref|)) = %.3g "
+                                    "(the cancellation-aware bound is what those tests assert)" % gpu_util.WORST_PLAIN_RATIO[0])

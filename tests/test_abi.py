@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported():
 def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.klay_options) == 32
     assert ctypes.sizeof(binding.klay_info_t) == 16 + 12 * 8
-    assert ctypes.sizeof(binding.klay_profile_t) == 14 * 4 + 14 * 4 + 14 * 8
+    assert ctypes.sizeof(binding.klay_profile_t) == 14 * 4 + 14 * 4 + 14 * 8 + 14 * 8
     assert len(binding.KERNEL_CLASSES) == 14
 
 

@@ -1,12 +1,16 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
 on the same seeded inputs.  Tolerances: |delta log| <= 1e-4 (fp32 log semiring), relative 1e-5
-(fp32 real semiring), gradients |delta| <= 1e-4 max(1, |ref|)."""
+(fp32 real semiring).  Gradients: with the adjoint seed dout = 1 the plain bound
+|delta| <= 1e-4 max(1, |ref|) (assert_grad_plain); with a random dout of mixed signs the same bound plus
+a cancellation term proportional to the path mass (assert_grad_close, derivation in tests/gpu_util.py);
+the session summary prints how far above the plain bound the worst such case was."""
 import numpy as np
 import pytest
 
 from klay_synth import (CircuitBuilder, as_inputs, layered_random, leaf_probs, make_config,
                         parse_text_circuit, tautology)
-from tests.gpu_util import (assert_grad_close, assert_log_close, assert_real_close, gpu_eval, oracle_eval)
+from tests.gpu_util import (assert_grad_close, assert_grad_plain, assert_log_close, assert_real_close, gpu_eval,
+                            oracle_eval)
 
 pytestmark = pytest.mark.gpu
 
@@ -26,7 +30,7 @@ def build(klay, c, **kw):
     return klay.Circuit(*c.arrays(), device=0, **kw)
 
 
-def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", **kw):
+def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", plain=False, **kw):
     k = build(klay, c, **kw)
     rng = np.random.default_rng(123)
     stats = {}
@@ -41,6 +45,14 @@ def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", **kw):
             stats["log"] = assert_log_close(got, ref, what + " log")
             if dout is not None:
                 stats["grad"] = assert_grad_close(gd, rd, what + " grad")
+                if plain:
+                    # adjoint seed 1: the plain bound, no cancellation term
+                    ones = np.ones_like(dout)
+                    _, g1 = gpu_eval(k, w32, s, ones)
+                    from oracle import oracle
+                    with np.errstate(all="ignore"):
+                        r1 = oracle.backward(*c.arrays(), w32.astype(np.float64), oracle.LOG, ones.astype(np.float64), nthreads=8)
+                    stats["grad_plain"] = assert_grad_plain(g1, r1, what + " grad, dout = 1")
         else:
             stats["real"] = assert_real_close(got, ref, what + " real")
             if dout is not None:
@@ -58,12 +70,49 @@ def test_worked_examples(klay, golden, name, nv):
         check_both(klay, c, leaf_probs(B, B, nv, ("uniform", 0.01, 0.99)), what=name)
 
 
+# ------------------------------------------------------------------ circuits loaded from text files
+def test_loaded_files_evaluate_on_the_gpu(klay):
+    """the d-DNNF .nnf file of Fig. 1b, the hand-written .sdd and the d4 file, through Circuit.from_*,
+    against the oracle on the arrays the readers return"""
+    import os
+    from oracle import oracle
+    from paper_2410_11415_amd.d4 import load_d4
+    from paper_2410_11415_amd.nnf import load_nnf
+    from paper_2410_11415_amd.sdd import load_sdd
+    from tests.conftest import GOLDEN
+    cases = (("fig1b_ddnnf.nnf", klay.Circuit.from_nnf, load_nnf), ("a_and_b_or_c.sdd", klay.Circuit.from_sdd, load_sdd),
+             ("a_and_b_or_c.d4", klay.Circuit.from_d4, load_d4))
+    for fname, ctor, loader in cases:
+        path = os.path.join(GOLDEN, fname)
+        arr = loader(path)
+        k = ctor(path, device=0)
+        for B in (1, 5, 70):
+            p = leaf_probs(B, B, arr[0], ("uniform", 0.02, 0.98))
+            dout = np.ones((B, k.num_roots), dtype=np.float32)
+            for s, osem in ((LOG, oracle.LOG), (REAL, oracle.REAL)):
+                w32 = as_inputs(p, s == LOG)
+                got, gd = gpu_eval(k, w32, s, dout)
+                w64 = w32.astype(np.float64)
+                ref = oracle.forward(*arr, w64, osem)
+                rd = oracle.backward(*arr, w64, osem, dout.astype(np.float64))
+                if s == LOG:
+                    assert_log_close(got, ref, fname)
+                    assert_grad_plain(gd, rd, fname + " grad")
+                else:
+                    assert_real_close(got, ref, fname)
+                    np.testing.assert_allclose(gd, rd, rtol=2e-5, atol=1e-6, err_msg=fname + " real grad")
+        if fname == "fig1b_ddnnf.nnf":      # 13 of 16 models at p = 1/2
+            half = as_inputs(np.full((1, 4), 0.5), False)
+            assert gpu_eval(k, half, REAL)[0][0, 0] == pytest.approx(13 / 16, rel=1e-6)
+        k.close()
+
+
 # ------------------------------------------------------------------ config 1
 @pytest.mark.parametrize("seed", [0, 1])
 def test_tiny_ddnnf_batch4(klay, seed):
     c, p, spec = make_config("tiny_ddnnf", seed=seed)
     assert p.shape[0] == 4
-    check_both(klay, c, p, what="tiny_ddnnf")
+    check_both(klay, c, p, what="tiny_ddnnf", plain=True)
     # and against brute-force model counting over the CNF (4096 assignments)
     cv, cp = spec["cnf"]
     bits = ((np.arange(4096)[:, None] >> np.arange(12)[None, :]) & 1).astype(bool)
@@ -83,8 +132,8 @@ def test_tiny_ddnnf_batch4(klay, seed):
 def test_layered_100k_full_size_log_forward(klay):
     c, p, spec = make_config("layered_100k", seed=0)
     assert p.shape[0] == 128
-    stats = check_both(klay, c, p, backward=False, semirings=(LOG,), what="layered_100k")
-    print("layered_100k max|dlog| %.2e" % stats["log"])
+    stats = check_both(klay, c, p, backward=True, semirings=(LOG,), what="layered_100k", plain=True)
+    print("layered_100k", stats)
 
 
 # ------------------------------------------------------------------ configs 3-5 at reduced size, element by element
@@ -97,36 +146,60 @@ def test_configs_reduced_size(klay, name, scale, batches):
     for B in batches:
         c, p, spec = make_config(name, seed=1, scale=scale, batch=B)
         sem = tuple(REAL if s == "real" else LOG for s in spec["semirings"])
-        stats = check_both(klay, c, p, backward=True, semirings=sem, what="%s B=%d" % (name, B))
+        stats = check_both(klay, c, p, backward=True, semirings=sem, what="%s B=%d" % (name, B), plain=True)
         print(name, B, stats)
 
 
-# ------------------------------------------------------------------ full sizes, sampled batch columns
-@pytest.mark.parametrize("name,semiring,backward", [
-    ("layered_1m", REAL, False), ("layered_1m", LOG, False), ("powerlaw_10m", LOG, False),
-    ("layered_3m_fwd_bwd", LOG, True),
+# ------------------------------------------------------------------ full sizes, every batch column
+def _oracle_columns(c, w32, semiring, dout, chunk=64, nthreads=16):
+    """oracle values (and gradients for the adjoint seed dout) of every batch column, a chunk of columns at
+    a time so that the oracle's per-column node arrays stay small"""
+    from oracle import oracle
+    refs, grads = [], []
+    for a in range(0, w32.shape[0], chunk):
+        w64 = w32[a:a + chunk].astype(np.float64)
+        with np.errstate(all="ignore"):
+            refs.append(oracle.forward(*c.arrays(), w64, semiring, nthreads=nthreads))
+            if dout is not None:
+                grads.append(oracle.backward(*c.arrays(), w64, semiring, dout[a:a + chunk].astype(np.float64),
+                                             nthreads=nthreads))
+    return np.concatenate(refs), (np.concatenate(grads) if grads else None)
+
+
+@pytest.mark.parametrize("name,semiring", [
+    ("layered_1m", REAL), ("layered_1m", LOG), ("powerlaw_10m", LOG), ("layered_3m_fwd_bwd", LOG),
 ])
-def test_configs_full_size_sampled_columns(klay, name, semiring, backward):
-    """The launch configuration the benchmark times; the oracle evaluates 4 of the B columns."""
+def test_configs_full_size_every_column(klay, name, semiring):
+    """The workloads at full size in the launch configuration the benchmark times (same batch, same build
+    options): every output and, with dout = 1, every gradient entry of every batch column against the
+    oracle.  Log-semiring gradients are held to the plain bound 1e-4 max(1, |ref|)."""
     c, p, spec = make_config(name, seed=0)
     B = p.shape[0]
+    assert B == {"layered_1m": 256, "powerlaw_10m": 64, "layered_3m_fwd_bwd": 256}[name]
     w32 = as_inputs(p, semiring == LOG)
-    dout = np.ones((B, c.roots.shape[0]), dtype=np.float32) if backward else None
+    dout = np.ones((B, c.roots.shape[0]), dtype=np.float32)
     k = build(klay, c)
     got, gd = gpu_eval(k, w32, semiring, dout)
-    cols = np.array([0, B // 3, B // 2 + 1, B - 1])
-    ref, rd = oracle_eval(c, w32[cols], semiring, None if dout is None else dout[cols], nthreads=4,
-                          or_levels=k.num_layers // 2)
     if semiring == LOG:
-        e = assert_log_close(got[cols], ref, name)
-        print("%s: max|dlog| %.2e, max|log ref| %.1f" % (name, e, np.abs(ref[np.isfinite(ref)]).max()))
+        ref, rd = _oracle_columns(c, w32, LOG, dout)
+        e = assert_log_close(got, ref, name)
+        ratio = assert_grad_plain(gd, rd, name + " grad, dout = 1")
+        print("%s B=%d, all columns: max|dlog| %.2e (max|log ref| %.1f); gradient error %.3g x the plain bound, max|grad ref| %.2e"
+              % (name, B, e, np.abs(ref[np.isfinite(ref)]).max(), ratio, np.abs(rd).max()))
     else:
-        print("%s: max rel %.2e" % (name, assert_real_close(got[cols], ref, name)))
-    if backward:
-        print("%s: grad err %.2e, max|grad ref| %.2e" % (name, assert_grad_close(gd[cols], rd, name), np.abs(rd).max()))
-    if name == "layered_1m" and semiring == LOG:      # B = 1 latency case on the same circuit
-        got1, _ = gpu_eval(k, w32[:1], LOG)
-        assert_log_close(got1, ref[:1], name + " B=1")
+        ref, _ = _oracle_columns(c, w32, REAL, None)
+        print("%s B=%d real, all columns: max rel %.2e" % (name, B, assert_real_close(got, ref, name)))
+        # the real-semiring gradient is a difference of products: bound with the cancellation term, sampled columns
+        cols = np.array([0, B // 3, B // 2 + 1, B - 1])
+        _, rdc = oracle_eval(c, w32[cols], REAL, dout[cols], nthreads=4, or_levels=k.num_layers // 2)
+        print("%s real grad: %.3g x the bound" % (name, assert_grad_close(gd[cols], rdc, name + " real grad", real=True)))
+    if name == "layered_1m":      # B = 1 latency case on the same circuit, both semirings
+        got1, gd1 = gpu_eval(k, w32[:1], semiring, dout[:1])
+        if semiring == LOG:
+            assert_log_close(got1, ref[:1], name + " B=1")
+            assert_grad_plain(gd1, rd[:1], name + " B=1 grad")
+        else:
+            assert_real_close(got1, ref[:1], name + " real B=1")
     k.close()
 
 
@@ -333,7 +406,7 @@ def test_alias_chains_mode_on_odd_shapes(klay, golden):
                heavy_fan=4, min_segment=2)
 
 
-def test_alias_chains_full_size_sampled_columns(klay):
+def test_alias_chains_full_size_every_column(klay):
     c, p, spec = make_config("layered_3m_fwd_bwd", seed=0)
     B = p.shape[0]
     w32 = as_inputs(p, True)
@@ -342,9 +415,9 @@ def test_alias_chains_full_size_sampled_columns(klay):
     info = k.info()
     assert info["num_edges"] == info["dag_edges"] and info["num_pad_nodes"] == 0
     got, gd = gpu_eval(k, w32, LOG, dout)
-    cols = np.array([0, B // 3, B // 2 + 1, B - 1])
-    ref, rd = oracle_eval(c, w32[cols], LOG, dout[cols], nthreads=4, or_levels=k.num_layers // 2)
-    print("alias full size: max|dlog| %.2e grad %.2e" % (assert_log_close(got[cols], ref), assert_grad_close(gd[cols], rd)))
+    ref, rd = _oracle_columns(c, w32, LOG, dout)
+    print("alias full size, all columns: max|dlog| %.2e, gradient error %.3g x the plain bound" % (
+        assert_log_close(got, ref), assert_grad_plain(gd, rd, "alias grad, dout = 1")))
     k.close()
 
 
@@ -761,31 +834,44 @@ def test_f64_configs_reduced_size(klay, name, scale, B):
     _f64_case(klay, c, p, name)
 
 
-def test_fp32_against_f64_on_every_output_at_full_size(klay):
-    """headline workload at full size: the double-precision kernels agree with the oracle on sampled
-    batch columns, and the fp32 kernels with the double-precision kernels on every output and every
-    gradient entry"""
+@pytest.mark.parametrize("name,semiring", [("layered_3m_fwd_bwd", LOG), ("layered_1m", LOG), ("layered_1m", REAL),
+                                           ("powerlaw_10m", LOG)])
+def test_fp32_against_f64_on_every_output_at_full_size(klay, name, semiring):
+    """The workloads at full size and at the batch the benchmark times (headline: B = 256, the four-column
+    tiles): the double-precision kernels agree with the oracle on sampled batch columns, and the fp32
+    kernels with the double-precision kernels on every output and every gradient entry.  The
+    double-precision path shares the host layerizer and the launch plans with the fp32 path, so only
+    its oracle-checked columns are evidence of their own; the all-columns comparison is a relay."""
     import torch
     from oracle import oracle
-    c, p, spec = make_config("layered_3m_fwd_bwd", seed=0)
-    B = 64                                                  # 3.6e6 rows x 64 columns in double: 1.9 GB
-    w32 = as_inputs(p[:B], True)
+    c, p, spec = make_config(name, seed=0)
+    B = p.shape[0]
+    w32 = as_inputs(p, semiring == LOG)
     k = build(klay, c)
     w64 = torch.from_numpy(w32.astype(np.float64)).cuda()
-    out64 = k.forward_f64(w64, LOG)
+    out64 = k.forward_f64(w64, semiring)
     d64 = k.backward_f64(torch.ones_like(out64))
-    cols = np.array([0, 21, 63])
+    cols = np.array([0, B // 3, B - 1])
+    osem = oracle.LOG if semiring == LOG else oracle.REAL
     with np.errstate(all="ignore"):
-        ref = oracle.forward(*c.arrays(), w32[cols].astype(np.float64), oracle.LOG, nthreads=3)
-        rgrad = oracle.backward(*c.arrays(), w32[cols].astype(np.float64), oracle.LOG, np.ones_like(ref), nthreads=3)
-    np.testing.assert_allclose(out64.cpu().numpy()[cols], ref, rtol=0, atol=1e-10)
-    np.testing.assert_allclose(d64.cpu().numpy()[cols], rgrad, rtol=1e-9, atol=1e-9)
-    got, gd = gpu_eval(k, w32, LOG, np.ones((B, c.roots.shape[0]), dtype=np.float32))
-    assert_log_close(got, out64.cpu().numpy(), "fp32 vs f64, all outputs")
-    r64 = d64.cpu().numpy()
-    err = np.abs(gd - r64) / np.maximum(1.0, np.abs(r64))
-    print("fp32 vs f64 at full size: max|dlog| %.2e, max grad err %.2e" % (np.abs(got - out64.cpu().numpy()).max(), err.max()))
-    assert err.max() <= 1e-4
+        ref = oracle.forward(*c.arrays(), w32[cols].astype(np.float64), osem, nthreads=3)
+        rgrad = oracle.backward(*c.arrays(), w32[cols].astype(np.float64), osem, np.ones_like(ref), nthreads=3)
+    o64, g64 = out64.cpu().numpy(), d64.cpu().numpy()
+    del out64, d64
+    if semiring == LOG:
+        np.testing.assert_allclose(o64[cols], ref, rtol=0, atol=1e-10)
+        np.testing.assert_allclose(g64[cols], rgrad, rtol=1e-9, atol=1e-9)
+    else:
+        np.testing.assert_allclose(o64[cols], ref, rtol=1e-11, atol=1e-300)
+        np.testing.assert_allclose(g64[cols], rgrad, rtol=1e-9, atol=1e-12 * np.abs(rgrad).max())
+    got, gd = gpu_eval(k, w32, semiring, np.ones((B, c.roots.shape[0]), dtype=np.float32))
+    if semiring == LOG:
+        assert_log_close(got, o64, "fp32 vs f64, all outputs")
+        ratio = assert_grad_plain(gd, g64, "fp32 vs f64, all gradient entries")
+        print("%s B=%d fp32 vs f64: max|dlog| %.2e, gradient error %.3g x the plain bound" % (
+            name, B, np.abs(got - o64).max(), ratio))
+    else:
+        print("%s B=%d real fp32 vs f64: max rel %.2e" % (name, B, assert_real_close(got, o64, "fp32 vs f64 real")))
     k.close()
 
 
@@ -828,7 +914,7 @@ def _random_dag(rng, V, n_gates, hub_share, max_fan):
             c = int(nodes[int(rng.integers(0, min(len(nodes), 8)))] if rng.random() < hub_share else nodes[int(rng.integers(0, len(nodes)))])
             if c in kids:
                 continue
-            if c in lits_of:                      # the same literal twice (after leaf merging) is rejected input
+            if c in lits_of:                      # one leaf node per literal here, so this never draws a literal twice
                 if (lits_of[c], c) in seen_vars:
                     continue
                 seen_vars.add((lits_of[c], c))

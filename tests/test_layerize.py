@@ -188,7 +188,6 @@ def test_split_plans_cover_every_edge_once():
 @pytest.mark.parametrize("mutate,status", [
     ("cycle", KLAY_ECYCLE), ("empty_gate", KLAY_EINVAL), ("dup_child", KLAY_EINVAL), ("bad_child", KLAY_EINVAL),
     ("bad_lit", KLAY_EINVAL), ("bad_root", KLAY_EINVAL), ("leaf_with_child", KLAY_EINVAL), ("bad_type", KLAY_EINVAL),
-    ("dup_literal_child", KLAY_EINVAL),
 ])
 def test_invalid_circuits_are_rejected(mutate, status):
     node_type = np.array([LIT, LIT, AND, OR], dtype=np.uint8)
@@ -213,8 +212,6 @@ def test_invalid_circuits_are_rejected(mutate, status):
         child_ptr = np.array([0, 1, 1, 3, 5], dtype=np.int64); child_idx = np.array([1, 0, 1, 2, 1], dtype=np.int32)
     elif mutate == "bad_type":
         node_type = np.array([LIT, 9, AND, OR], dtype=np.uint8)
-    elif mutate == "dup_literal_child":
-        node_lit = np.array([1, 1, 0, 0], dtype=np.int32)      # both leaves are x0: AND(x0, x0)
     with pytest.raises(KlayError) as e:
         Circuit(V, node_type, node_lit, child_ptr, child_idx, roots, device=-1)
     assert e.value.status == status and len(str(e.value)) > 20
@@ -311,6 +308,29 @@ def test_merging_keeps_multiplicity():
     assert k.info()["num_merged_nodes"] == 1
     row_ptr, child = k.layer_csr(2)
     assert child.tolist() == [0, 0] and k.layer_sizes()[0].tolist() == [2, 1, 1]
+
+
+def test_two_leaf_nodes_with_one_literal_under_a_gate_count_twice():
+    """AND(x0, x0') with two leaf nodes that carry the same literal is a well-formed input (no node id is
+    listed twice); the leaves become one row and the gate keeps both edges, so it evaluates to p0^2 as
+    Eq. 1 says; an unreachable gate that repeats a child does not invalidate the circuit"""
+    from oracle import oracle
+    node_type = np.array([LIT, LIT, AND, OR, OR], dtype=np.uint8)
+    node_lit = np.array([1, 1, 0, 0, 0], dtype=np.int32)
+    child_ptr = np.array([0, 0, 0, 2, 4, 6], dtype=np.int64)
+    child_idx = np.array([0, 1, 2, 1, 0, 0], dtype=np.int32)      # node 4 = OR(0, 0) is not reachable
+    roots = np.array([3], dtype=np.int32)
+    k = Circuit(1, node_type, node_lit, child_ptr, child_idx, roots, device=-1)
+    assert k.layer_sizes()[0][0] == 1
+    row_ptr, child = k.layer_csr(1)
+    assert sorted(np.diff(row_ptr).tolist()) == [1, 2] and set(child.tolist()) == {0}
+    p = np.array([[0.3], [0.9]])
+    ref = oracle.forward(1, node_type, node_lit, child_ptr, child_idx, roots, p, oracle.REAL)
+    np.testing.assert_allclose(ref[:, 0], p[:, 0] ** 2 + p[:, 0], rtol=1e-15)
+    from klay_synth import Circuit as Dag
+    k._alias = False
+    got = eval_layered(Dag(1, node_type, node_lit, child_ptr, child_idx, roots), k, p, 0)
+    np.testing.assert_allclose(got, ref, rtol=1e-14)
 
 
 def _fig3_parts():
