@@ -23,21 +23,60 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
-
-# HBM bytes per launch of a kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script (scaled by the copy probe: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000), see
-# profiles/stream_kernels_layered_3m_fwd_bwd_hbm_traffic.md.  Keyed by (workload, batch, class).
-MEASURED_TRAFFIC_PER_LAUNCH = {
-    ("layered_3m_fwd_bwd", 256, "bwd_softmax"): 422.9e6,    # 331.7 MB fetched + 91.2 MB written
-    ("layered_3m_fwd_bwd", 256, "fwd_lse"): 236.6e6,        # 161.2 MB fetched + 75.4 MB written
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "bench_traffic.json")
+FINGERPRINT_FILES = ("paper_2410_11415_amd/csrc/klay_api.hip", "paper_2410_11415_amd/csrc/klay_kernels.hip.h",
+                     "paper_2410_11415_amd/csrc/layerize.cpp", "paper_2410_11415_amd/csrc/layerize.h",
+                     "klay_synth/circuits.py", "klay_synth/configs.py", "klay_synth/weights.py")
 
 
-# HBM bytes of a whole step from the same counter runs (sum over all dispatches of one step), keyed by
-# (workload, batch, forward+backward?, alias_chains?)
-MEASURED_TRAFFIC_PER_STEP = {
-    ("layered_3m_fwd_bwd", 256, True, False): 25.5e9,
-}
+def source_fingerprint() -> str:
+    """Hash of the sources that decide what the kernels move (kernels, launch plans, node order, input
+    generators).  The measured-traffic table carries the fingerprint it was measured at; figures from a
+    table with another fingerprint are reported as null."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in FINGERPRINT_FILES:
+        with open(os.path.join(ROOT, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def load_traffic(workload, batch, semiring, backward, alias):
+    """HBM bytes per dispatch and per step from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs that
+    bench_traffic.py folded into bench_traffic.json; None unless measured on these very sources."""
+    try:
+        with open(TRAFFIC_TABLE) as fh:
+            table = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    if table.get("fingerprint") != source_fingerprint():
+        return None
+    key = "%s|B=%d|%s|%s|%s" % (workload, batch, semiring, "fwd+bwd" if backward else "fwd", "alias" if alias else "chains")
+    return table.get("runs", {}).get(key)
+
+
+def kernel_symbol(cls, B):
+    """rocprofv3's name for the kernel behind a profiling class (template arguments as it prints them)."""
+    vec = 4 if B > 128 else (2 if B > 64 else 1)
+    if B > 32:
+        ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4}
+        if cls in ops:
+            return "klay::stream_kernel<%d, %d>" % (ops[cls], vec)
+    else:
+        w = 1
+        while w < B:
+            w *= 2
+        ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4}
+        if cls in ops:
+            return "klay::pass_kernel<%d, 1, %d>" % (ops[cls], w)
+    ct = 1
+    while ct < 8 and (B + ct - 1) // ct > 256:
+        ct *= 2
+    fixed = {"tail_fwd": "klay::tail_fwd_kernel<%d>" % ct, "tail_bwd": "klay::tail_bwd_kernel<%d>" % ct,
+             "leaf": "klay::leaf_fwd_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
+             "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments and combine rows of split rows)",
+             "prod_edges": "klay::prod_edge_kernel<%d, %d>" % (vec, 64)}
+    return fixed.get(cls, cls)
 
 
 class HipEvents:
@@ -86,9 +125,10 @@ def main():
     ap.add_argument("--f64", action="store_true",
                     help="also time the double-precision kernels on the same workload (extra object \"f64\")")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
-    ap.add_argument("--copy-probe-mib", type=int, default=0,
-                    help="first run 5 plain device-to-device copies of this many MiB (calibrates the "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters and gives the achievable copy rate)")
+    ap.add_argument("--copy-probe-mib", type=int, default=1024,
+                    help="first run 5 plain device-to-device copies of this many MiB: the achievable copy rate of "
+                         "this box, and the dispatches that calibrate the rocprofv3 FETCH_SIZE / WRITE_SIZE counters "
+                         "(0: skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (batch columns are independent, so more GPUs "
@@ -118,7 +158,8 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / 5
-        copy_probe = {"mib": args.copy_probe_mib, "read_plus_write_GBs": round(2 * n * 4 / dt / 1e9, 1)}
+        copy_probe = {"mib": args.copy_probe_mib, "read_plus_write_GBs": round(2 * n * 4 / dt / 1e9, 1),
+                      "what": "device-to-device copy, bytes read + bytes written over wall time"}
         del a, b
         torch.cuda.empty_cache()
 
@@ -202,80 +243,126 @@ def main():
         step()
         torch.cuda.synchronize()
         for name, rec in k.get_profile().items():
-            c = classes.setdefault(name, {"ms": 0.0, "launches": 0, "alg_bytes": 0.0})
+            c = classes.setdefault(name, {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0})
             for f in c:
                 c[f] += rec[f]
     k.set_profiling(False)
-    # every class below except "split" is one kernel (one template instance) launched once per layer
-    kernel_of = {"fwd_sum": "stream_kernel<OP_SUM>", "fwd_prod": "stream_kernel<OP_PROD>", "fwd_lse": "stream_kernel<OP_LSE>",
-                 "fwd_max": "stream_kernel<OP_MAX>",
-                 "bwd_sum": "stream_kernel<OP_SUM>", "bwd_softmax": "stream_kernel<OP_SOFTMAX_BWD>",
-                 "split": "pass_kernel (segments and combine rows of split rows)", "tail_fwd": "tail_fwd_kernel",
-                 "tail_bwd": "tail_bwd_kernel", "leaf": "leaf_fwd_kernel", "bwd_leaf": "leaf_bwd_kernel",
-                 "root": "root_out_kernel", "seed": "seed_kernel", "prod_edges": "prod_edge_kernel"}
-    dom = max(classes, key=lambda n: classes[n]["ms"])
-    d = classes[dom]
-    achieved = d["alg_bytes"] / (d["ms"] * 1e-3) / 1e9 if d["ms"] > 0 else 0.0
+    # ---- roofline: the kernel that takes most time, by symbol (a symbol can serve several classes:
+    # the log-domain AND layers forward and backward are both stream_kernel<OP_SUM>)
+    by_symbol = {}
+    for name, c in classes.items():
+        if not c["launches"]:
+            continue
+        g = by_symbol.setdefault(kernel_symbol(name, B), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
+                                                          "classes": []})
+        for f in ("ms", "launches", "alg_bytes", "min_bytes"):
+            g[f] += c[f]
+        g["classes"].append(name)
+    dom = max(by_symbol, key=lambda n: by_symbol[n]["ms"])
+    d = by_symbol[dom]
     kernel_ms_total = sum(c["ms"] for c in classes.values()) / prof_steps
     alg_bytes_step = sum(c["alg_bytes"] for c in classes.values()) / prof_steps
-    # compulsory bytes: every row written once and read once per consuming sweep (forward: all rows but
-    # the top layer's; backward: adjoint rows written and read once, value rows read once), plus indices
-    n_top = k.layer_sizes()[0][-1]
-    compulsory = 4.0 * B * (2 * N - n_top) + 4.0 * (E + N)
-    if backward:
-        compulsory += 4.0 * B * 3 * N + 4.0 * (E + N)
-    step_traffic = MEASURED_TRAFFIC_PER_STEP.get((args.workload, B, backward, bool(args.alias_chains)))
-    if semiring != pkg.KLAY_LOG or args.no_tail:
-        step_traffic = None
+    min_bytes_step = sum(c["min_bytes"] for c in classes.values()) / prof_steps
+    measured = None
+    if not args.no_tail and not args.graph:
+        measured = load_traffic(args.workload, B, semiring_name, backward, bool(args.alias_chains))
+    per_launch_s = d["ms"] * 1e-3 / max(1, d["launches"])
+    traffic = None
+    if measured and dom in measured["per_kernel"]:
+        traffic = measured["per_kernel"][dom]["fetch_bytes"] + measured["per_kernel"][dom]["write_bytes"]
+    no_reuse_GBs = d["alg_bytes"] / max(1, d["launches"]) / per_launch_s / 1e9 if per_launch_s > 0 else 0.0
+    compulsory_GBs = d["min_bytes"] / max(1, d["launches"]) / per_launch_s / 1e9 if per_launch_s > 0 else 0.0
+    if traffic is not None:
+        achieved, basis = traffic / per_launch_s / 1e9, \
+            "HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (bench_traffic.json) over the HIP-event launch time"
+    else:
+        achieved, basis = compulsory_GBs, \
+            "compulsory bytes per launch (no counter figures for these sources: lower bound on the traffic)"
+    step_s = ms_per_step * 1e-3
+    step_traffic = measured["step_bytes"] if measured else None
+
+    def per_kernel_entry(sym, g):
+        t = g["ms"] * 1e-3
+        e = {"classes": g["classes"], "ms_per_step": round(g["ms"] / prof_steps, 4), "launches_per_step": g["launches"] // prof_steps,
+             "no_reuse_model_GBs": round(g["alg_bytes"] / t / 1e9) if t > 0 else None,
+             "compulsory_GBs": round(g["min_bytes"] / t / 1e9) if t > 0 else None, "traffic_GBs": None}
+        if measured and sym in measured["per_kernel"] and t > 0:
+            m = measured["per_kernel"][sym]
+            e["traffic_GBs"] = round((m["fetch_bytes"] + m["write_bytes"]) * g["launches"] / t / 1e9)
+        if e["no_reuse_model_GBs"] and e["no_reuse_model_GBs"] > HBM_PEAK_GBS:
+            e["note"] = "the no-reuse model counts L2 hits as memory reads: above the HBM peak, so not a traffic figure"
+        return e
+
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((args.workload, B, dom)),
-        "kernel": kernel_of.get(dom, dom) + " [" + dom + "]", "kernel_avg_launch_us": round(d["ms"] * 1e3 / max(1, d["launches"]), 2),
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "basis": basis,
+        "kernel": dom, "kernel_classes": d["classes"],
+        "kernel_avg_launch_us": round(per_launch_s * 1e6, 2),
         "kernel_launches_per_step": d["launches"] // prof_steps,
-        "kernel_alg_bytes_per_launch": round(d["alg_bytes"] / max(1, d["launches"])),
-        "whole_step": {"alg_bytes": round(alg_bytes_step), "kernel_ms": round(kernel_ms_total, 3),
-                       "achieved_GBs": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
-                       "frac": round(alg_bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                       "compulsory_bytes": round(compulsory),
-                       "compulsory_frac": round(compulsory / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                       "measured_traffic_bytes": step_traffic,
-                       "measured_traffic_frac": None if step_traffic is None else
-                       round(step_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-        "per_class_ms": {n: round(c["ms"] / prof_steps, 3) for n, c in classes.items() if c["launches"]},
-        # no-reuse GB/s of every class (its algorithmic bytes over its summed launch durations)
-        "per_class_GBs": {n: round(c["alg_bytes"] / (c["ms"] * 1e-3) / 1e9) for n, c in classes.items()
-                          if c["launches"] and c["ms"] > 0},
+        "kernel_share_of_kernel_time": round(d["ms"] / prof_steps / kernel_ms_total, 3) if kernel_ms_total > 0 else None,
+        "kernel_no_reuse_bytes_per_launch": round(d["alg_bytes"] / max(1, d["launches"])),
+        "kernel_compulsory_bytes_per_launch": round(d["min_bytes"] / max(1, d["launches"])),
+        "model_no_reuse_frac": round(no_reuse_GBs / HBM_PEAK_GBS, 4),
+        "compulsory_frac": round(compulsory_GBs / HBM_PEAK_GBS, 4),
+        "achievable_GBs": copy_probe["read_plus_write_GBs"] if copy_probe else None,
+        "traffic_table": None if measured is None else {"fingerprint": source_fingerprint(), "measured_ms_per_step": measured.get("ms_per_step")},
+        "whole_step": {"kernel_ms": round(kernel_ms_total, 3),
+                       "traffic_bytes": step_traffic,
+                       "traffic_frac": None if step_traffic is None else round(step_traffic / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                       "no_reuse_model_bytes": round(alg_bytes_step),
+                       "model_no_reuse_frac": round(alg_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                       "compulsory_bytes": round(min_bytes_step),
+                       "compulsory_frac": round(min_bytes_step / step_s / 1e9 / HBM_PEAK_GBS, 4)},
+        "per_kernel": {sym: per_kernel_entry(sym, g) for sym, g in sorted(by_symbol.items(), key=lambda kv: -kv[1]["ms"])},
     }
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import oracle
-        threads = min(oracle.max_threads(), 16)
+        host = {"os_cpu_count": os.cpu_count(), "affinity": len(os.sched_getaffinity(0)), "omp_max_threads": oracle.max_threads()}
+        threads = max(1, min(host["omp_max_threads"], host["affinity"], 16))
         # a bounded sample: about 1.3e9 edge evaluations, 10-20 s for the oracle on 16 threads
         cols = args.cpu_columns or max(threads, int(1.3e9 / max(1, E)) // threads * threads)
         cols = min(cols, B)
         sample = np.ascontiguousarray(w32[:cols]).astype(np.float64)
         oracle_semiring = {pkg.KLAY_LOG: oracle.LOG, pkg.KLAY_REAL: oracle.REAL, pkg.KLAY_MAXLOG: oracle.MAXLOG}[semiring]
+        arrays = circ.arrays()
+        ones = np.ones((cols, k.num_roots))
+
+        def oracle_pass(x, nthreads):
+            # one evaluation of the workload: forward, or forward + reverse sweep (the oracle's backward
+            # evaluates the column forward itself before it sweeps back)
+            t0 = time.perf_counter()
+            if backward:
+                r = oracle.backward(*arrays, x, oracle_semiring, ones[:x.shape[0]], nthreads=nthreads)
+            else:
+                r = oracle.forward(*arrays, x, oracle_semiring, nthreads=nthreads)
+            return r, time.perf_counter() - t0
+        # the oracle sorts the DAG (post-order) inside every call; like klay_build on the GPU side the sort is
+        # not part of an evaluation, so it is timed by itself and taken out
         t0 = time.perf_counter()
-        ref = oracle.forward(*circ.arrays(), sample, oracle_semiring,
-                             nthreads=threads)
-        if backward:
-            rgrad = oracle.backward(*circ.arrays(), sample, oracle_semiring,
-                                    np.ones_like(ref), nthreads=threads)
-        t_cpu = time.perf_counter() - t0
+        oracle.postorder(*arrays[1:])
+        t_sort = time.perf_counter() - t0
+        res, t_all = oracle_pass(sample, threads)
+        cols1 = max(1, cols // 16)
+        _, t_one = oracle_pass(sample[:cols1], 1)
+        t_all_eval, t_one_eval = max(t_all - t_sort, 1e-9), max(t_one - t_sort, 1e-9)
+        ref = oracle.forward(*arrays, sample, oracle_semiring, nthreads=threads) if backward else res
         got = out[:cols].cpu().numpy()
         err = float(np.abs(got - ref).max())
         cpu_baseline = {
-            "value": cols * E / t_cpu, "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
+            "value": cols * E / t_all_eval, "unit": "edge-evals/s", "cores": threads, "kind": "oracle",
             "sample": "%d of %d batch columns of the same workload, %s, fp64 post-order over the unlayered DAG "
-                      "(%d nodes, %d edges); counted in layered edges like the GPU figure; %.1f s" % (
+                      "(%d nodes, %d edges); counted in layered edges like the GPU figure; %.1f s of evaluation "
+                      "(+ %.2f s for the oracle's own topological sort, excluded like klay_build)" % (
                           cols, B, "forward+backward" if backward else "forward", info["dag_nodes"],
-                          info["dag_edges"], t_cpu),
+                          info["dag_edges"], t_all_eval, t_sort),
+            "single_thread": {"value": cols1 * E / t_one_eval, "columns": cols1, "seconds": round(t_one_eval, 2)},
+            "host": host,
             "max_abs_err_vs_gpu": err,
         }
         if backward:
-            gerr = np.abs(dleaf[:cols].cpu().numpy() - rgrad) / np.maximum(1.0, np.abs(rgrad))
+            gerr = np.abs(dleaf[:cols].cpu().numpy() - res) / np.maximum(1.0, np.abs(res))
             cpu_baseline["max_grad_err_vs_gpu"] = float(gerr.max())
         cpu_baseline["max_abs_log_ref"] = float(np.abs(ref[np.isfinite(ref)]).max())
 
@@ -295,7 +382,8 @@ def main():
                    "dag_nodes": info["dag_nodes"], "dag_edges": info["dag_edges"],
                    "pad_nodes": info["num_pad_nodes"], "num_vars": info["num_vars"], "num_roots": info["num_roots"],
                    "max_fan_in": info["max_fan_in"], "max_fan_out": info["max_fan_out"],
-                   "build_seconds": round(t_build, 2), "generate_seconds": round(t_gen, 2)},
+                   "build_seconds": round(t_build, 2), "generate_seconds": round(t_gen, 2),
+                   "sources_fingerprint": source_fingerprint()},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }

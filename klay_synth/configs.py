@@ -26,6 +26,11 @@ CONFIGS = {
     "powerlaw_10m": dict(kind="layered", num_vars=4096, depth=30, num_nodes=290_000,
                          fanin=("zipf", 1.5, 10_000), groups=2, batch=64, semirings=("log",),
                          backward=False, weights=("beta", 0.5, 0.5)),
+    # the same configuration read the other way: 1e6 nodes AND ~1e7 edges, which a Zipf exponent of 1.77
+    # (mean fan-in ~10 under the cap of 1e4) gives; the stated exponent 1.5 cannot (its mean is ~77)
+    "powerlaw_1m_nodes": dict(kind="layered", num_vars=4096, depth=30, num_nodes=1_000_000,
+                              fanin=("zipf", 1.77, 10_000), groups=2, batch=64, semirings=("log",),
+                              backward=False, weights=("beta", 0.5, 0.5)),
     # headline: 3e6 nodes, 1e7 edges, depth 60, forward + backward
     "layered_3m_fwd_bwd": dict(kind="layered", num_vars=8192, depth=60, num_nodes=3_000_000,
                                fanin=("geom", 2.3), groups=4, batch=256, semirings=("log",),

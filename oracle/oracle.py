@@ -90,6 +90,22 @@ def max_threads() -> int:
     return int(_load().klay_oracle_max_threads())
 
 
+def postorder(node_type, node_lit, child_ptr, child_idx, roots):
+    """The oracle's evaluation order: every node reachable from the roots, children before parents."""
+    lib = _load()
+    child_ptr = np.ascontiguousarray(child_ptr, dtype=np.int64)
+    child_idx = np.ascontiguousarray(child_idx, dtype=np.int32)
+    roots = np.ascontiguousarray(roots, dtype=np.int32)
+    n = child_ptr.shape[0] - 1
+    order = np.empty(n + 1, dtype=np.int32)
+    count = lib.klay_oracle_postorder(n, _ptr(child_ptr), _ptr(child_idx), roots.shape[0], _ptr(roots), _ptr(order))
+    if count == -1:
+        raise ValueError("circuit has a cycle")
+    if count < 0:
+        raise MemoryError("oracle postorder failed (%d)" % count)
+    return order[:count]
+
+
 def forward(num_vars, node_type, node_lit, child_ptr, child_idx, roots, weights, semiring,
             nthreads: int = 1, return_node_values: bool = False, neg_weights=None):
     """Root values ``out[B,R]`` (fp64) for leaf weights ``weights[B,V]``.

@@ -140,6 +140,7 @@ def test_layered_100k_full_size_log_forward(klay):
 @pytest.mark.parametrize("name,scale,batches", [
     ("layered_1m", 0.05, (1, 256)),
     ("powerlaw_10m", 0.08, (64,)),
+    ("powerlaw_1m_nodes", 0.03, (64,)),
     ("layered_3m_fwd_bwd", 0.02, (256,)),
 ])
 def test_configs_reduced_size(klay, name, scale, batches):
@@ -167,7 +168,8 @@ def _oracle_columns(c, w32, semiring, dout, chunk=64, nthreads=16):
 
 
 @pytest.mark.parametrize("name,semiring", [
-    ("layered_1m", REAL), ("layered_1m", LOG), ("powerlaw_10m", LOG), ("layered_3m_fwd_bwd", LOG),
+    ("layered_1m", REAL), ("layered_1m", LOG), ("powerlaw_10m", LOG), ("powerlaw_1m_nodes", LOG),
+    ("layered_3m_fwd_bwd", LOG),
 ])
 def test_configs_full_size_every_column(klay, name, semiring):
     """The workloads at full size in the launch configuration the benchmark times (same batch, same build
@@ -175,7 +177,7 @@ def test_configs_full_size_every_column(klay, name, semiring):
     oracle.  Log-semiring gradients are held to the plain bound 1e-4 max(1, |ref|)."""
     c, p, spec = make_config(name, seed=0)
     B = p.shape[0]
-    assert B == {"layered_1m": 256, "powerlaw_10m": 64, "layered_3m_fwd_bwd": 256}[name]
+    assert B == {"layered_1m": 256, "powerlaw_10m": 64, "powerlaw_1m_nodes": 64, "layered_3m_fwd_bwd": 256}[name]
     w32 = as_inputs(p, semiring == LOG)
     dout = np.ones((B, c.roots.shape[0]), dtype=np.float32)
     k = build(klay, c)
