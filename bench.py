@@ -72,7 +72,7 @@ def kernel_symbol(cls, B):
     ct = 1
     while ct < 8 and (B + ct - 1) // ct > 256:
         ct *= 2
-    fixed = {"tail_fwd": "klay::tail_fwd_kernel<%d>" % ct, "tail_bwd": "klay::tail_bwd_kernel<%d>" % ct,
+    fixed = {"tail_fwd": "klay::slab_fwd_kernel<%d>" % ct, "tail_bwd": "klay::slab_bwd_kernel<%d>" % ct,
              "leaf": "klay::leaf_fwd_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
              "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments and combine rows of split rows)",
              "prod_edges": "klay::prod_edge_kernel<%d, %d>" % (vec, 64)}

@@ -24,6 +24,14 @@
 constexpr size_t kStaticWorkspaceBytes = KLAY_STATIC_WORKSPACE_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
 
+// 1: batches of at most 32 columns run the lanes = edges kernel, 0: a lane group per row (for comparison)
+#ifndef KLAY_EDGE_SMALL_B
+#define KLAY_EDGE_SMALL_B 1
+#endif
+#ifndef KLAY_MERGE_VEC1
+#define KLAY_MERGE_VEC1 0
+#endif
+
 namespace {
 
 thread_local std::string g_err;
@@ -121,10 +129,11 @@ struct klay_circuit {
     const int32_t *d_pos_row = nullptr, *d_neg_row = nullptr, *d_root_pos = nullptr, *d_top_ptr = nullptr,
                   *d_top_root = nullptr;
     int32_t true_row = -1, false_row = -1;
-    const klay::TailLayer* d_tail = nullptr;   // descriptors of layers plan.tail_first .. L
-    bool tail_lds_ok = false;                  // the large-LDS attribute was accepted for the tail kernels
+    const klay::SlabLayer* d_tail = nullptr;   // descriptors of layers plan.tail_first .. L
+    const int32_t* d_leaf_code = nullptr;      // layer 0: literal / constant code of every row
+    size_t tail_lds_bytes = 0;                 // LDS a workgroup of the persistent kernels may use (0: kernels unusable)
     int64_t tail_rows = 0;                     // T: rows of all tail candidate layers (one column of the tail buffer)
-    int32_t last_tail_first = 0;               // first layer the last forward ran in the tail kernel (0: none)
+    int32_t last_tail_first = 0;               // first layer the last forward ran in the persistent kernel (0: none)
     // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
     // vectors and a by-child pass whose entries are edge positions, plus the per-edge buffer M
     struct RealLayer { const int32_t* ptr = nullptr; const int32_t* child = nullptr; DevPass by_child; };
@@ -228,6 +237,48 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
     case klay::OP_LSE: launch_op<klay::OP_LSE>(a, g, grid, s); break;
     case klay::OP_MAX: launch_op<klay::OP_MAX>(a, g, grid, s); break;
     default: launch_op<klay::OP_SOFTMAX_BWD>(a, g, grid, s); break;
+    }
+}
+
+// Small batches (B <= 32): the lanes = edges kernel over the main rows and the segments of a pass.
+template <int OP, int LPR>
+void launch_edge_one(const DevPass& dp, const float* src, const float* src2, const float* own, float* dst,
+                     float* dst_seg, int B, int ld, hipStream_t s) {
+    constexpr int EPW = 64 / LPR, CH = EPW >= 16 ? 4 : 8;
+    const int64_t entries = dp.main_entries + dp.n_heavy;
+    // a wave takes about two rounds of its gathers: CH steps of EPW entries each
+    const double per_task = dp.n_tasks > 0 ? (double)entries / dp.n_tasks : 16.0;
+    int span = (int)(2.0 * CH * EPW / std::max(1.0, per_task) + 0.5);
+    span = std::max(1, span);
+    const int64_t waves = ((int64_t)dp.n_tasks + span - 1) / span + ((int64_t)dp.n_seg_tasks + span - 1) / span;
+    if (waves <= 0) return;
+    dim3 grid((unsigned)((waves + 3) / 4));
+    hipLaunchKernelGGL((klay::edge_kernel<OP, LPR>), grid, dim3(256), 0, s, reinterpret_cast<const int2*>(dp.tasks),
+                       dp.n_tasks, span, dp.idx, src, src2, own, dst, B, ld, reinterpret_cast<const int2*>(dp.seg_tasks),
+                       dp.n_seg_tasks, dp.seg_owner, dp.n_main, dst_seg);
+}
+
+template <int OP>
+void launch_edge_op(const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
+                    float* dst, float* dst_seg, int B, hipStream_t s) {
+    switch (g.w) {
+    case 32: launch_edge_one<OP, 32>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    case 16: launch_edge_one<OP, 16>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    case 8: launch_edge_one<OP, 8>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    case 4: launch_edge_one<OP, 4>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    case 2: launch_edge_one<OP, 2>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    default: launch_edge_one<OP, 1>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    }
+}
+
+void launch_edge(int op, const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
+                 float* dst, float* dst_seg, int B, hipStream_t s) {
+    switch (op) {
+    case klay::OP_SUM: launch_edge_op<klay::OP_SUM>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_PROD: launch_edge_op<klay::OP_PROD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_LSE: launch_edge_op<klay::OP_LSE>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_MAX: launch_edge_op<klay::OP_MAX>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    default: launch_edge_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     }
 }
 
@@ -388,21 +439,20 @@ klay_status upload(klay_circuit* c) {
     // plain index vectors by parent and by child, then the descriptor array
     size_t o_tail = 0;
     if (p.tail_first > 0) {
-        std::vector<klay::TailLayer> descs;
+        std::vector<klay::SlabLayer> descs;
         int64_t row0 = 0, tb_off = 0;
         for (int l = 0; l < p.tail_first; ++l) row0 += p.layers[(size_t)l].n;
+        auto add_slab = [&](const klay::SlabPlan& sp, int32_t& ent_off, int32_t (&line)[klay::kSlabWaves + 1]) {
+            ent_off = (int32_t)pk.add(sp.ent);
+            for (int w = 0; w <= klay::kSlabWaves; ++w) line[w] = sp.wave_line[w];
+        };
         for (int l = p.tail_first; l <= L; ++l) {
             const klay::LayerPlan& lay = p.layers[(size_t)l];
-            klay::TailLayer t{};
+            klay::SlabLayer t{};
             t.n = (int32_t)lay.n;
-            t.e = (int32_t)lay.e;
             t.n_below = (int32_t)p.layers[(size_t)l - 1].n;
-            std::vector<int32_t> f(lay.row_ptr);
-            f.insert(f.end(), lay.child.begin(), lay.child.end());
-            t.fwd_off = (int32_t)pk.add(f);
-            std::vector<int32_t> b(lay.col_ptr);
-            b.insert(b.end(), lay.parent.begin(), lay.parent.end());
-            t.bwd_off = (int32_t)pk.add(b);
+            add_slab(lay.slab_fwd, t.fwd_ent, t.fwd_line);
+            if (lay.tail_bwd_ok) add_slab(lay.slab_bwd, t.bwd_ent, t.bwd_line);
             t.row0 = row0;
             t.row0_below = row0 - t.n_below;
             t.tb_off = (int32_t)tb_off;
@@ -411,9 +461,10 @@ klay_status upload(klay_circuit* c) {
             descs.push_back(t);
         }
         c->tail_rows = tb_off;
-        static_assert(sizeof(klay::TailLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
-        o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::TailLayer) / sizeof(int32_t));
+        static_assert(sizeof(klay::SlabLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
+        o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::SlabLayer) / sizeof(int32_t));
     }
+    const size_t o_leaf_code = pk.add(p.leaf_code);
     std::vector<PassOffsets> fo((size_t)L + 1), bo((size_t)L + 1);
     for (int l = 1; l <= L; ++l) {
         fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
@@ -455,7 +506,8 @@ klay_status upload(klay_circuit* c) {
     c->d_root_pos = base + o_root;
     c->d_top_ptr = base + o_tptr;
     c->d_top_root = base + o_troot;
-    if (p.tail_first > 0) c->d_tail = reinterpret_cast<const klay::TailLayer*>(base + o_tail);
+    if (p.tail_first > 0) c->d_tail = reinterpret_cast<const klay::SlabLayer*>(base + o_tail);
+    c->d_leaf_code = base + o_leaf_code;
     return KLAY_OK;
 }
 
@@ -499,7 +551,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         // the main rows (same streaming walk, output to partial rows).  The softmax adjoint's segments
         // need their owner's value row, and one-column tiles (B <= 64) measured 9% faster through the
         // generic kernel: separate launch.
-        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec >= 2;
+        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && (g.vec >= 2 || KLAY_MERGE_VEC1);
         float* seg_base = seg_rows - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
@@ -518,10 +570,15 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
             prof.end();
         }
     } else {
-        a.row_begin = 0;                         // small batches: main rows and segments in one launch
+        // small batches: main rows and segments in one launch, lanes = edges
         prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B),
                    pass_min_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, (double)dp.n_src, B));
+#if KLAY_EDGE_SMALL_B
+        launch_edge(op, dp, g, src, src2, own, dst, seg_rows - (ptrdiff_t)dp.n_main * g.ld, B, s);
+#else
+        a.row_begin = 0;
         launch_pass(op, a, g, s);
+#endif
         prof.end();
     }
     if (dp.n_heavy > 0) {
@@ -543,43 +600,39 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     }
 }
 
-// ---- persistent kernels for the narrow top layers --------------------------------------------
-constexpr int kTailLdsWords = 32768;       // 128 KB of the 160 KB LDS of a CU
-
+// ---- persistent kernels for the top layers -----------------------------------------------------
 struct TailChoice {
-    int first = 0;       // first layer run by the tail kernels (0: tail not used)
+    int first = 0;       // first layer run by the persistent kernel (0: not used)
     int ct = 1;          // batch columns per workgroup
     int nmax = 0;        // LDS rows per buffer
 };
 
 // Batch columns per workgroup: one column per workgroup until the batch needs more workgroups
-// than the chip has compute units; few columns mean few rows per thread and a short layer time.
+// than the chip has compute units; few columns mean few rows per lane and a short layer time.
 int tail_ct(int B) {
     int ct = 1;
     while (ct < 8 && (B + ct - 1) / ct > 256) ct *= 2;
     return ct;
 }
 
-// Largest suffix of the tail candidates whose buffers fit the LDS budget for `buffers` value
-// arrays of CT columns; at least two layers, otherwise the tail is not worth a kernel of its own.
-TailChoice choose_tail(const klay_circuit* c, int B, int buffers) {
+// Largest suffix of the candidate layers, not starting below `lowest`, whose `buffers` value arrays of
+// CT columns fit the LDS of a workgroup.  The arrays hold the layers first .. L, and layer 0 as well
+// when the kernel starts at layer 1 and evaluates the leaf layer itself.  At least two layers,
+// otherwise a kernel of its own is not worth it.
+TailChoice choose_tail(const klay_circuit* c, int B, int buffers, int lowest) {
     TailChoice t;
     const klay::CircuitPlan& p = c->plan;
-    if (p.tail_first <= 0 || !c->tail_lds_ok) return t;
+    if (lowest <= 0 || c->tail_lds_bytes == 0) return t;
     t.ct = tail_ct(B);
     const int L = p.num_layers;
-    int64_t nmax = 0, imax = 0;
+    const int64_t words = (int64_t)(c->tail_lds_bytes / sizeof(float));
+    int64_t nmax = 0;
     int first = 0;
-    for (int l = L; l >= p.tail_first; --l) {
-        const klay::LayerPlan& lay = p.layers[(size_t)l];
-        const int64_t n2 = std::max(nmax, lay.n);
-        const int64_t below = p.layers[(size_t)l - 1].n;
-        const int64_t i2 = std::max(imax, std::max(lay.n, below) + 1 + lay.e);
-        if ((int64_t)buffers * n2 * t.ct + i2 > kTailLdsWords) break;
-        // the reverse sweep also holds the adjoints of layer l-1 when l is not the first tail layer;
-        // that layer is then a tail layer itself and is checked in the next iteration
+    for (int l = L; l >= lowest; --l) {
+        int64_t n2 = std::max(nmax, p.layers[(size_t)l].n);
+        if (l == 1) n2 = std::max(n2, p.layers[0].n);
+        if ((int64_t)buffers * (n2 + 1) * t.ct > words) break;      // + 1: the padding slot of every array
         nmax = n2;
-        imax = i2;
         first = l;
     }
     if (first == 0 || L - first + 1 < 2) return t;
@@ -588,43 +641,50 @@ TailChoice choose_tail(const klay_circuit* c, int B, int buffers) {
     return t;
 }
 
-size_t tail_lds_bytes(const klay_circuit* c, const TailChoice& t, int buffers) {
-    const klay::CircuitPlan& p = c->plan;
-    int64_t imax = 0;
-    for (int l = t.first; l <= p.num_layers; ++l)
-        imax = std::max(imax, std::max(p.layers[(size_t)l].n, p.layers[(size_t)l - 1].n) + 1 + p.layers[(size_t)l].e);
-    return (size_t)((int64_t)buffers * t.nmax * t.ct + imax) * sizeof(float);
+// the layers the forward sweep runs in the persistent kernel ...
+TailChoice choose_tail_fwd(const klay_circuit* c, int B) { return choose_tail(c, B, 2, c->plan.tail_first); }
+// ... and the (possibly fewer) layers the reverse sweep does, given the forward choice
+TailChoice choose_tail_bwd(const klay_circuit* c, int B, int fwd_first) {
+    if (fwd_first <= 0 || c->plan.tail_bwd_first <= 0) return TailChoice();
+    return choose_tail(c, B, 4, std::max(fwd_first, c->plan.tail_bwd_first));
 }
 
 template <int CT>
-hipError_t tail_attr() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&klay::tail_fwd_kernel<CT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kTailLdsWords * 4);
+hipError_t tail_attr(int bytes) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&klay::slab_fwd_kernel<CT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&klay::tail_bwd_kernel<CT>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kTailLdsWords * 4);
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&klay::slab_bwd_kernel<CT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-bool enable_tail_lds() {
-    hipError_t e = tail_attr<8>();
-    if (e == hipSuccess) e = tail_attr<4>();
-    if (e == hipSuccess) e = tail_attr<2>();
-    if (e == hipSuccess) e = tail_attr<1>();
-    if (e != hipSuccess) { (void)hipGetLastError(); return false; }
-    return true;
+// LDS bytes a workgroup of the persistent kernels may use: the largest of 160, 128 and 64 KB that the
+// runtime accepts for all of them (gfx950 has 160 KB per compute unit), 0 if none.
+size_t enable_tail_lds() {
+    for (int kb : {160, 128, 64}) {
+        const int bytes = kb * 1024;
+        hipError_t e = tail_attr<8>(bytes);
+        if (e == hipSuccess) e = tail_attr<4>(bytes);
+        if (e == hipSuccess) e = tail_attr<2>(bytes);
+        if (e == hipSuccess) e = tail_attr<1>(bytes);
+        if (e == hipSuccess) return (size_t)bytes;
+        (void)hipGetLastError();
+    }
+    return 0;
 }
 
-void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, float* tb, int B, int ld, int semiring,
-                     hipStream_t s) {
+void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* act, float* tb, int B, int ld, int semiring,
+                     const klay::SlabLeaf& leaf, float* out, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
-    const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
+    const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
     const int first_is_and = t.first & 1;
-    const size_t lds = tail_lds_bytes(c, t, 2);
+    const size_t lds = (size_t)2 * (t.nmax + 1) * t.ct * sizeof(float);
     dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
 #define KLAY_TAIL_FWD(CT)                                                                              \
-    hipLaunchKernelGGL((klay::tail_fwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
-                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax, tb, (int)c->tail_rows)
+    hipLaunchKernelGGL((klay::slab_fwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
+                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax, tb, (int)c->tail_rows, leaf, \
+                       c->d_root_pos, p.num_roots, out)
     switch (t.ct) {
     case 8: KLAY_TAIL_FWD(8); break;
     case 4: KLAY_TAIL_FWD(4); break;
@@ -634,17 +694,17 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, float* act, flo
 #undef KLAY_TAIL_FWD
 }
 
-void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* act, const float* tb, const float* dout,
+void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb, const float* dout,
                      float* g_out, int B, int ld, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
-    const klay::TailLayer* descs = c->d_tail + (t.first - p.tail_first);
+    const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
     const int first_is_and = t.first & 1;
-    const size_t lds = tail_lds_bytes(c, t, 3);
+    const size_t lds = (size_t)4 * (t.nmax + 1) * t.ct * sizeof(float);
     dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
 #define KLAY_TAIL_BWD(CT)                                                                              \
-    hipLaunchKernelGGL((klay::tail_bwd_kernel<CT>), grid, dim3(klay::kTailThreads), lds, s, descs,     \
-                       n_layers, first_is_and, c->d_index, act, dout, c->d_top_ptr, c->d_top_root,     \
+    hipLaunchKernelGGL((klay::slab_bwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
+                       n_layers, first_is_and, c->d_index, dout, c->d_top_ptr, c->d_top_root,          \
                        p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows)
     switch (t.ct) {
     case 8: KLAY_TAIL_BWD(8); break;
@@ -653,6 +713,19 @@ void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* ac
     default: KLAY_TAIL_BWD(1); break;
     }
 #undef KLAY_TAIL_BWD
+}
+
+// Values of layers first .. last (all run by the persistent forward kernel) from the column-major
+// buffer into their rows of the activation buffer, for the ordinary launches of a reverse sweep.
+void launch_tb_to_rows(const klay_circuit* c, int first, int last, const float* tb, float* act, int B, int ld, hipStream_t s) {
+    const klay::CircuitPlan& p = c->plan;
+    int64_t tb_first = 0, n_rows = 0;
+    for (int l = p.tail_first; l < first; ++l) tb_first += p.layers[(size_t)l].n;
+    for (int l = first; l <= last; ++l) n_rows += p.layers[(size_t)l].n;
+    if (n_rows <= 0) return;
+    dim3 grid((unsigned)((n_rows + 31) / 32), (unsigned)((ld + 31) / 32));
+    hipLaunchKernelGGL(klay::tb_to_rows_kernel, grid, dim3(256), 0, s, tb, (int)c->tail_rows, (int)tb_first, (int)n_rows, B,
+                       ld, act + (size_t)c->dl[(size_t)first].row0 * ld);
 }
 
 double tail_alg_bytes(const klay_circuit* c, int first, int B, bool backward) {
@@ -667,6 +740,18 @@ double tail_alg_bytes(const klay_circuit* c, int first, int B, bool backward) {
                      4.0 * ((double)lay.e + below);
         }
     }
+    return bytes;
+}
+
+// what a persistent launch has to move through memory: the values it writes (forward) or reads (reverse)
+// once, its index vectors, the rows it reads from or leaves in the activation buffer
+double tail_min_bytes(const klay_circuit* c, int first, int B, bool backward) {
+    double bytes = 0;
+    for (int l = first; l <= c->plan.num_layers; ++l) {
+        const klay::LayerPlan& lay = c->plan.layers[(size_t)l];
+        bytes += 4.0 * B * (double)lay.n + 4.0 * (double)(backward ? lay.slab_bwd.ent.size() : lay.slab_fwd.ent.size());
+    }
+    bytes += 4.0 * B * (double)(backward ? c->plan.layers[(size_t)first].n : c->plan.layers[(size_t)first - 1].n);
     return bytes;
 }
 
@@ -1098,7 +1183,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
             if (c->d_index) (void)hipFree(c->d_index);
             return st;
         }
-        c->tail_lds_ok = c->plan.tail_first > 0 && enable_tail_lds();
+        c->tail_lds_bytes = c->plan.tail_first > 0 ? enable_tail_lds() : 0;
     }
     *out = c.release();
     return KLAY_OK;
@@ -1327,23 +1412,29 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     const int V = p.num_vars;
     Profiler prof(c, &c->ev_fwd, s, !static_ws);
 
-    // leaf layer
-    prof.begin(KLAY_K_LEAF, 4.0 * B * V + 4.0 * B * (double)(V + p.layers[0].n));
-    if (V > 0) {
-        dim3 grid((unsigned)((V + 31) / 32), (unsigned)((g.ld + 63) / 64));
-        hipLaunchKernelGGL(klay::leaf_fwd_kernel, grid, dim3(256), 0, s, leaf_weights, neg_weights, (int)B, V, g.ld,
-                           c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);
-    }
-    if (c->true_row >= 0)
-        hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((g.ld + 255) / 256)), dim3(256), 0, s,
-                           act + (size_t)c->true_row * g.ld, g.ld, log_domain ? 0.0f : 1.0f);
-    if (c->false_row >= 0)
-        hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((g.ld + 255) / 256)), dim3(256), 0, s,
-                           act + (size_t)c->false_row * g.ld, g.ld, log_domain ? -INFINITY : 0.0f);
-    prof.end();
+    // the top layers run in one persistent kernel; when that kernel starts at layer 1 it evaluates the
+    // leaf layer itself (a workgroup reads its own rows of the weight arrays)
+    const TailChoice tail = choose_tail_fwd(c, B);
+    const bool fused_leaf = tail.first == 1;
 
-    // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4); the narrow top runs in one persistent kernel
-    const TailChoice tail = choose_tail(c, B, with_bwd ? 3 : 2);
+    // leaf layer
+    if (!fused_leaf) {
+        prof.begin(KLAY_K_LEAF, 4.0 * B * V + 4.0 * B * (double)(V + p.layers[0].n));
+        if (V > 0) {
+            dim3 grid((unsigned)((V + 31) / 32), (unsigned)((g.ld + 63) / 64));
+            hipLaunchKernelGGL(klay::leaf_fwd_kernel, grid, dim3(256), 0, s, leaf_weights, neg_weights, (int)B, V, g.ld,
+                               c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);
+        }
+        if (c->true_row >= 0)
+            hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((g.ld + 255) / 256)), dim3(256), 0, s,
+                               act + (size_t)c->true_row * g.ld, g.ld, log_domain ? 0.0f : 1.0f);
+        if (c->false_row >= 0)
+            hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((g.ld + 255) / 256)), dim3(256), 0, s,
+                               act + (size_t)c->false_row * g.ld, g.ld, log_domain ? -INFINITY : 0.0f);
+        prof.end();
+    }
+
+    // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4)
     const int last_regular = tail.first > 0 ? tail.first - 1 : L;
     for (int l = 1; l <= last_regular; ++l) {
         const DevLayer& d = c->dl[(size_t)l];
@@ -1359,20 +1450,29 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     }
 
     if (tail.first > 0) {
-        prof.begin(KLAY_K_TAIL_FWD, tail_alg_bytes(c, tail.first, B, false));
-        launch_tail_fwd(c, tail, act, ws + lay.tb, B, g.ld, (int)semiring, s);
+        // the persistent kernel also writes out[B, R]: the top layer is in its LDS
+        klay::SlabLeaf leaf{};
+        if (fused_leaf) {
+            leaf.w = leaf_weights;
+            leaf.wneg = neg_weights;
+            leaf.leaf_code = c->d_leaf_code;
+            leaf.wT = wT;
+            leaf.act0 = act;
+            leaf.V = V;
+            leaf.n0 = (int32_t)p.layers[0].n;
+        }
+        prof.begin(KLAY_K_TAIL_FWD, tail_alg_bytes(c, tail.first, B, false) + 8.0 * B * p.num_roots,
+                   tail_min_bytes(c, tail.first, B, false) + 4.0 * B * p.num_roots);
+        launch_tail_fwd(c, tail, act, ws + lay.tb, B, g.ld, (int)semiring, leaf, out, s);
         prof.end();
-    }
-
-    // roots
-    prof.begin(KLAY_K_ROOT, 8.0 * B * p.num_roots);
-    {
+    } else {
+        prof.begin(KLAY_K_ROOT, 8.0 * B * p.num_roots);
         dim3 grid((unsigned)p.num_roots);
         hipLaunchKernelGGL(klay::root_out_kernel, grid, dim3(256), 0, s,
                            p.alias ? act : act + (size_t)c->dl[(size_t)L].row0 * g.ld, c->d_root_pos, (int)B,
                            p.num_roots, g.ld, out);
+        prof.end();
     }
-    prof.end();
     KLAY_HIP(hipGetLastError());
     if (static_ws) return KLAY_OK;       // the values live in the shared array: nothing to differentiate later
     c->have_fwd = true;
@@ -1418,6 +1518,9 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         // buffer M (adjoint times the product of the other children), summed by child.
         klay_status rs = ensure_real_bwd(c, g.ld);
         if (rs != KLAY_OK) return rs;
+        // this sweep runs layer by layer on rows of the activation buffer: bring back the values the
+        // persistent forward kernel kept column-major
+        if (c->last_tail_first > 0) launch_tb_to_rows(c, c->last_tail_first, L, ws + lay.tb, act, B, g.ld, s);
         float* M = c->real_buf;
         float* real_seg_rows = c->real_buf + (size_t)(c->real_max_edges + 1) * g.ld;
         if (p.alias) {
@@ -1514,11 +1617,17 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
     // which seeds the adjoints itself and leaves those of its first layer in gcur
     int top = L;
+    const TailChoice tail = choose_tail_bwd(c, B, c->last_tail_first);
     if (c->last_tail_first > 0) {
-        TailChoice tail = choose_tail(c, B, 3);
-        if (tail.first != c->last_tail_first) return fail(KLAY_ESTATE, "klay_backward: tail layout changed since forward");
-        prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R);
-        launch_tail_bwd(c, tail, act, ws + lay.tb, dout, gcur, B, g.ld, s);
+        // the ordinary launches below read values of layers last_tail_first .. top as rows of the
+        // activation buffer; the persistent forward kernel kept them column-major
+        const int last_needed = tail.first > 0 ? tail.first : L;
+        launch_tb_to_rows(c, c->last_tail_first, last_needed, ws + lay.tb, act, B, g.ld, s);
+    }
+    if (tail.first > 0) {
+        prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R,
+                   tail_min_bytes(c, tail.first, B, true) + 4.0 * B * R);
+        launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, B, g.ld, s);
         prof.end();
         top = tail.first;
     } else {

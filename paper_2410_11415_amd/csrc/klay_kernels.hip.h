@@ -11,6 +11,14 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "layerize.h"
+
+// gathers in flight per lane in the streaming kernel when a lane holds one batch column (B <= 64): rows
+// are 256 bytes then, and it takes more of them in flight to cover the latency
+#ifndef KLAY_CH_VEC1
+#define KLAY_CH_VEC1 4
+#endif
+
 namespace klay {
 
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4 };
@@ -129,6 +137,12 @@ __device__ __forceinline__ float finish(float acc, float mx) {
 template <int OP>
 __device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : (OP == OP_MAX ? -INFINITY : 0.0f); }
 
+// what an index entry that is not part of the row contributes: nothing
+template <int OP>
+__device__ __forceinline__ float dead_value() {
+    return OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Streaming segmented gather-reduce for B > 32 (one wave spans the batch tile, VEC columns per
 // lane).  A task is a run of consecutive output rows with a bounded number of edges, fixed at
@@ -149,7 +163,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
     // entries per chunk: measured on the headline workload, 4 (2 for the softmax adjoint, which loads
     // three rows per entry) beat 8 / 4 by 2%: the kernel is bandwidth-bound, fewer registers per wave
     // buy more resident waves
-    constexpr int CH = (OP == OP_SOFTMAX_BWD) ? 2 : 4;
+    constexpr int CH = (OP == OP_SOFTMAX_BWD) ? (VEC == 1 ? KLAY_CH_VEC1 / 2 : 2) : (VEC == 1 ? KLAY_CH_VEC1 : 4);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = ((int)blockIdx.y * 64 + lane) * VEC;
@@ -247,6 +261,161 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
 }
 
 // ---------------------------------------------------------------------------------------------
+// Small batches (B <= 32): lanes = edges.  A lane group of LPR lanes (B rounded up to a power of two)
+// holds one index entry, its lanes the batch columns, so a wave takes EPW = 64 / LPR consecutive entries
+// per step (all 64 at B = 1): one coalesced read of the entries, one gather of their rows, and the
+// entries of an output row, which sit in neighbouring lane groups, are reduced across the wave:
+//   - a step in which no row ends only accumulates, every lane group into a partial of its own;
+//   - a step in which rows end folds those partials into one (butterfly over the lane groups), adds
+//     it to the first lane group, and runs a segmented inclusive scan over the lane groups (wave
+//     shuffles; a lane knows its segment's start from the ballot of the end-of-row bits, so only values
+//     travel); the lane groups that hold a row's last entry store the row, the part of a row that is
+//     still open stays behind as the last lane group's partial.
+// Same task lists and index entries as the streaming kernel (a wave takes `span` consecutive tasks);
+// tasks past the main list are the segments of split rows.  The log-domain OR reduction travels as
+// (maximum, sum of exp(x - maximum)) pairs.
+// ---------------------------------------------------------------------------------------------
+template <int OP>
+__device__ __forceinline__ void edge_combine(float& am, float& as, float bm, float bs) {
+    if (OP == OP_SUM || OP == OP_SOFTMAX_BWD) am += bm;
+    else if (OP == OP_PROD) am *= bm;
+    else if (OP == OP_MAX) am = fmaxf(am, bm);
+    else {
+        const float M = fmaxf(am, bm);
+        const float ea = (am == -INFINITY) ? 0.0f : fexp(am - M);
+        const float eb = (bm == -INFINITY) ? 0.0f : fexp(bm - M);
+        as = as * ea + bs * eb;
+        am = M;
+    }
+}
+
+template <int OP, int LPR>
+__global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ tasks, int n_tasks, int span,
+                                                   const uint32_t* __restrict__ idx, const float* __restrict__ src,
+                                                   const float* __restrict__ src2, const float* __restrict__ own,
+                                                   float* __restrict__ dst, int B, int ld,
+                                                   const int2* __restrict__ seg_tasks, int n_seg_tasks,
+                                                   const int32_t* __restrict__ seg_owner, int n_main,
+                                                   float* __restrict__ dst_seg) {
+    constexpr int EPW = 64 / LPR;                 // entries per step
+    constexpr int CH = EPW >= 16 ? 4 : 8;         // steps whose gathers are in flight together
+    constexpr bool LSE = OP == OP_LSE;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int sub = lane / LPR, c = lane % LPR;
+    const bool active = c < B;
+    const int cc = active ? c : B - 1;            // lanes past the batch re-read its last column and store nothing
+    const int n_main_waves = (n_tasks + span - 1) / span;
+    int wt = (int)blockIdx.x * 4 + wave;
+    bool seg = false;
+    if (wt >= n_main_waves) {
+        wt -= n_main_waves;
+        seg = true;
+        tasks = seg_tasks;
+        n_tasks = n_seg_tasks;
+        dst = dst_seg;
+    }
+    const int t0 = wt * span;
+    if (t0 >= n_tasks) return;
+    const int t1 = t0 + span < n_tasks ? t0 + span : n_tasks;
+    const int2 ta = tasks[t0], tb = tasks[t1];
+    int row = ta.x;
+    const int e1 = tb.y;
+    float accm = identity<OP>(), accs = 0.0f;     // this lane group's partial of the open row
+    if (LSE) accm = -INFINITY;
+    int state = 0;     // partials: 0 none holds anything, 1 only the last lane group's does, 2 any may
+    for (int j = ta.y; j < e1; j += CH * EPW) {
+        uint32_t id[CH];
+        bool in[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int pos = j + i * EPW + sub;
+            in[i] = pos < e1;
+            id[i] = idx[in[i] ? pos : e1 - 1];
+        }
+        // rows of the entries: the open row plus the rows that end before them
+        unsigned long long lm[CH], below[CH];
+        int rowidx[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool last = in[i] && (id[i] & kLast) != 0;
+            lm[i] = __builtin_amdgcn_ballot_w64(last && c == 0);
+            below[i] = lm[i] & ((1ull << (sub * LPR)) - 1ull);
+            rowidx[i] = row + __builtin_popcountll(below[i]);
+            row += __builtin_popcountll(lm[i]);
+        }
+        float x[CH], y[CH], z[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool live = in[i] && id[i] != kSkip;
+            const size_t off = (size_t)(live ? (id[i] & kIdMask) : 0u) * (size_t)ld + cc;
+            x[i] = src[off];
+            y[i] = 0.0f;
+            z[i] = 0.0f;
+            if (OP == OP_SOFTMAX_BWD) {
+                const bool weighted = live && (id[i] & kWeighted) != 0;
+                // value of the parent, and of the row the entry belongs to (a segment: of its owner)
+                y[i] = (weighted ? src2 : src)[off];
+                int orow = live ? rowidx[i] : (seg ? n_main : 0);      // an entry past the task's end has no row
+                if (seg) orow = seg_owner[orow - n_main];
+                z[i] = own[(size_t)orow * (size_t)ld + cc];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool live = in[i] && id[i] != kSkip;
+            const bool last = in[i] && (id[i] & kLast) != 0;
+            float vm, vs = 0.0f;
+            if (OP == OP_SOFTMAX_BWD) {
+                const bool weighted = live && (id[i] & kWeighted) != 0;
+                const float wgt = !weighted ? 1.0f : ((y[i] == -INFINITY) ? 0.0f : fexp(z[i] - y[i]));
+                vm = live ? x[i] * wgt : 0.0f;
+            } else if (LSE) {
+                vm = live ? x[i] : -INFINITY;
+                vs = live ? 1.0f : 0.0f;
+            } else {
+                vm = live ? x[i] : dead_value<OP>();
+            }
+            if (lm[i] == 0ull) {                      // no row ends in this step
+                edge_combine<OP>(accm, accs, vm, vs);
+                state = 2;
+                continue;
+            }
+            if (state == 2) {                         // fold the partials of all lane groups
+#pragma unroll
+                for (int d = LPR; d < 64; d <<= 1) {
+                    const float om = __shfl_xor(accm, d), os = LSE ? __shfl_xor(accs, d) : 0.0f;
+                    edge_combine<OP>(accm, accs, om, os);
+                }
+            } else if (state == 1) {                  // only the last lane group holds one
+                accm = __shfl(accm, (EPW - 1) * LPR + c);
+                if (LSE) accs = __shfl(accs, (EPW - 1) * LPR + c);
+            }
+            if (sub == 0) edge_combine<OP>(vm, vs, accm, accs);
+            // segmented inclusive scan over the lane groups: a segment starts after every end of row
+            const int start = below[i] ? (63 - __builtin_clzll(below[i])) / LPR + 1 : 0;
+            const int dist = sub - start;
+#pragma unroll
+            for (int d = 1; d < EPW; d <<= 1) {
+                const float om = __shfl_up(vm, d * LPR), os = LSE ? __shfl_up(vs, d * LPR) : 0.0f;
+                if (dist >= d) edge_combine<OP>(vm, vs, om, os);
+            }
+            if (last && live && active) {
+                float o = vm;
+                if (LSE) o = (vm == -INFINITY) ? -INFINITY : vm + flog(vs);
+                dst[(size_t)rowidx[i] * (size_t)ld + c] = o;
+            }
+            // the open row's part stays with the last lane group
+            const bool tail_last = ((lm[i] >> ((EPW - 1) * LPR)) & 1ull) != 0ull;
+            const bool keep = sub == EPW - 1 && !tail_last;
+            accm = keep ? vm : (LSE ? -INFINITY : identity<OP>());
+            accs = keep ? vs : 0.0f;
+            state = tail_last ? 0 : 1;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Generic gather-reduce: a lane group of W lanes owns one output row (W < 64: several rows per
 // wave, for small batches).  Also evaluates the segments of split rows (rows >= n_main, written
 // to scratch rows) and the combine pass (out_row map).
@@ -325,217 +494,436 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Persistent kernels for the narrow top of the circuit (layers that taper to the roots): instead
-// of one launch per layer, a workgroup owns CT batch columns, keeps the values (forward) or the
-// adjoints (backward) of the current and the previous layer in LDS and walks the layers with a
-// barrier in between; batch columns are independent, so no grid-wide barrier is needed.  Each
-// layer's index vectors are staged into LDS first.  Values are also written to the activation
-// buffer, because the backward pass reads them.
-//   LDS (floats): forward 2 * nmax * CT values, backward 3 * nmax * CT, then nmax + 1 + emax ints.
-// A thread owns rows of one batch column, so writing the values into the row-major activation
-// buffer costs one cache line per lane.  The values the reverse kernel needs therefore go to a
-// tail value buffer tb[column][T] (T = rows of all tail layers), where consecutive threads write
-// consecutive floats; only the first and the top tail layer (read by the regular reverse pass and
-// by the root kernel) and, in the real semiring
-// (whose reverse sweep runs layer by layer), every layer is also written to the activation buffer.
+// Persistent kernels for the top of the circuit (the layers that taper to the roots; for a small
+// circuit every layer): instead of one launch per layer, a workgroup owns CT batch columns, keeps
+// the values (forward) or the adjoints (reverse) of the current and the previous layer in LDS and
+// walks the layers with a barrier in between.  Batch columns are independent, so no grid-wide
+// barrier is needed.
+//   Index vectors stay in global memory, in the form the host builds for these layers: rows in chunks
+// of 64 (one row per lane), a chunk as long as its longest row, and the lines of 64 words that make
+// up the chunks of one wave stored back to back.  A wave therefore streams through one contiguous
+// run of lines per layer, a block of kSlabBlock lines at a time, fetches the next block (at the end
+// of a run: the first block of the next layer's run, so the fetch is in flight across the barrier)
+// before it works on the one in hand, and learns from the end-of-chunk bit of a line, which is the
+// same in all its words, when to close the 64 rows it is working on.  Padding words name the slot one
+// past the last source row, where the identity of the layer's operation is kept, so the inner loop has
+// no test for them.  The rows of these layers are stored sorted by fan-in group, so the rows of a
+// chunk have similar lengths; the 16 waves take the chunks round-robin.
+//   One compute unit evaluates a whole column, so the instruction count per line, not memory, bounds
+// these kernels: a line costs its fetch, one LDS gather and the accumulation.
+//   A lane owns rows of one batch column, so writing values into the row-major activation buffer
+// would cost one cache line per lane.  The values go to a column-major buffer tb[column][T] instead
+// (T = rows of all candidate layers), where consecutive lanes write consecutive floats; the reverse
+// kernel reads it the same way, and rows that an ordinary launch needs are transposed back on demand
+// (tb_to_rows_kernel).
+//   LDS (floats): forward 2 * (nmax + 1) * CT, reverse 4 * (nmax + 1) * CT.
 // ---------------------------------------------------------------------------------------------
-struct TailLayer {
-    int32_t n, e;          // nodes and edges of this layer
-    int32_t n_below;       // nodes of the layer below
-    int32_t fwd_off;       // [row_ptr (n+1) | child (e)] by parent, offset in ints into the index buffer
-    int32_t bwd_off;       // [col_ptr (n_below+1) | parent (e)] by child
-    int32_t tb_off;        // first entry of this layer in a column of the tail value buffer
-    int64_t row0;          // first activation row of this layer
-    int64_t row0_below;
+constexpr int kSlabThreads = 64 * kSlabWaves;      // kSlabWaves, kSlabBlock: the plan's format constants (layerize.h)
+constexpr int kSlabD = kSlabBlock;
+
+struct SlabLayer {
+    int32_t n, n_below;            // nodes of this layer and of the layer below
+    int32_t tb_off;                // first entry of this layer in a column of tb
+    int32_t fwd_ent;               // by parent: offset (in ints) of the lines, then first line of each wave's run
+    int32_t fwd_line[kSlabWaves + 1];
+    int32_t bwd_ent;               // by child: rows are the nodes of the layer below
+    int32_t bwd_line[kSlabWaves + 1];
+    int32_t reserved[2];
+    int64_t row0, row0_below;      // first activation rows
 };
 
-constexpr int kTailThreads = 1024;
-constexpr int kTailStash = 20;          // index entries per thread: covers rows + 1 + edges <= 20480
+// identity of a layer's forward operation: the value kept in the padding slot of its source array
+__device__ __forceinline__ float slab_identity(int semiring, bool is_and) {
+    if (semiring == 0) return is_and ? 1.0f : 0.0f;
+    return is_and ? 0.0f : -INFINITY;
+}
 
-template <int OP, int CT>
-__device__ __forceinline__ void tail_fwd_rows(const TailLayer& L, const int* ib, const float* prev, float* cur,
-                                              const float* below, bool from_global, float* act_out, int ld,
-                                              bool active, float* tb_out, bool write_act) {
-    constexpr int RS = kTailThreads / CT;
-    const int c = threadIdx.x % CT;
-    for (int r = threadIdx.x / CT; r < L.n; r += RS) {
-        const int beg = ib[r], end = ib[r + 1];
-        float acc = identity<OP>(), mx = -INFINITY;
-        const int* kids = ib + L.n + 1;
-        int j = beg;
-        for (; j + 4 <= end; j += 4) {                 // four independent reads in flight
-            float x[4];
+// A wave's run of lines for one layer: sp points at this lane's word of the first line.
+struct SlabRun {
+    const uint32_t* sp;
+    int n;                         // lines, a multiple of kSlabD
+};
+
+__device__ __forceinline__ SlabRun slab_run(const int32_t* __restrict__ ibase, int ent, const int32_t* line, int wave, int lane) {
+    SlabRun r;
+    const int first = line[wave];
+    r.n = line[wave + 1] - first;
+    // a wave without lines in this layer still fetches (from the start of the index buffer, always
+    // readable) and ignores what it gets: loads under branches would be waited for one by one
+    r.sp = reinterpret_cast<const uint32_t*>(ibase) + (r.n > 0 ? ent + (size_t)first * 64 : (size_t)0) + lane;
+    return r;
+}
+
+// what a wave fetches when no layer follows: the start of the index buffer (readable, ignored)
+__device__ __forceinline__ SlabRun slab_no_run(const int32_t* __restrict__ ibase, int lane) {
+    SlabRun r;
+    r.n = 0;
+    r.sp = reinterpret_cast<const uint32_t*>(ibase) + lane;
+    return r;
+}
+
+// one block of lines starting at p (this lane's word of the first of them)
+__device__ __forceinline__ void slab_fetch(uint32_t (&a)[kSlabD], const uint32_t* p) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int ch = kids[j + u];
-                if (from_global) x[u] = active ? below[(size_t)ch * ld] : identity<OP>();
-                else x[u] = prev[ch * CT + c];
+    for (int u = 0; u < kSlabD; ++u) a[u] = p[u * 64];
+}
+
+// where the block after block i of `run` comes from: the run itself, or the first block of `next`
+__device__ __forceinline__ const uint32_t* slab_after(const SlabRun& run, int i, const SlabRun& next) {
+    return i + kSlabD < run.n ? run.sp + (size_t)(i + kSlabD) * 64 : next.sp;
+}
+
+// One block of one layer, forward: works on the lines in `a` while the block at `fetch` travels into `b`.
+template <int OP, int CT, bool FG>
+__device__ __forceinline__ void slab_fwd_block(const uint32_t (&a)[kSlabD], uint32_t (&b)[kSlabD], const uint32_t* fetch,
+                                               int n_rows, int n_below, int& q, float (&acc)[CT], float (&mx)[CT],
+                                               const float* prev, float* cur, const float* __restrict__ below, int ld,
+                                               int nact, float* __restrict__ tb_col, int T) {
+    slab_fetch(b, fetch);
+    float x[kSlabD][CT];
+#pragma unroll
+    for (int u = 0; u < kSlabD; ++u) {
+        const int ch = (int)(a[u] & kIdMask);
+#pragma unroll
+        for (int k = 0; k < CT; ++k) {
+            if (FG) {
+                // sources in global memory: a padding word (source n_below) must not be followed
+                const bool live = ch != n_below && k < nact;
+                const float v = below[(size_t)(live ? ch : 0) * ld + (live ? k : 0)];
+                x[u][k] = live ? v : dead_value<OP>();
+            } else {
+                x[u][k] = prev[ch * CT + k];
+            }
+        }
+    }
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < kSlabD; ++u) {
+#pragma unroll
+        for (int k = 0; k < CT; ++k) accumulate<OP>(acc[k], mx[k], x[u][k], 0.0f, 0.0f);
+        // the end-of-chunk bit is the same in all words of a line
+        if (__builtin_amdgcn_readfirstlane((int)a[u]) & (int)kLast) {
+            const int r = q * 64 + lane;
+            if (r < n_rows) {
+#pragma unroll
+                for (int k = 0; k < CT; ++k) {
+                    const float o = finish<OP>(acc[k], mx[k]);
+                    cur[r * CT + k] = o;
+                    if (k < nact) tb_col[(size_t)k * T + r] = o;
+                }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) accumulate<OP>(acc, mx, x[u], 0.0f, 0.0f);
-        }
-        for (; j < end; ++j) {
-            const int ch = kids[j];
-            float x;
-            if (from_global) x = active ? below[(size_t)ch * ld] : identity<OP>();
-            else x = prev[ch * CT + c];
-            accumulate<OP>(acc, mx, x, 0.0f, 0.0f);
-        }
-        const float o = finish<OP>(acc, mx);
-        cur[r * CT + c] = o;
-        if (active) {
-            tb_out[r] = o;
-            if (write_act) act_out[(size_t)r * ld] = o;
+            for (int k = 0; k < CT; ++k) { acc[k] = identity<OP>(); mx[k] = -INFINITY; }
+            q += kSlabWaves;
         }
     }
 }
 
+// One layer, forward.  `a` holds the first block of this wave's run on entry and the first block of
+// `next` on exit.  FG: the sources are rows of the activation buffer in global memory (the layer below
+// the first persistent one), otherwise the previous layer's values in LDS.
+template <int OP, int CT, bool FG>
+__device__ __forceinline__ void slab_fwd_rows(const SlabLayer& L, const SlabRun& run, const SlabRun& next,
+                                              uint32_t (&a)[kSlabD], const float* prev, float* cur,
+                                              const float* __restrict__ below, int ld, int nact,
+                                              float* __restrict__ tb_col, int T) {
+    if (run.n <= 0) { slab_fetch(a, next.sp); return; }
+    int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // chunk in hand
+    const int n_rows = L.n, n_below = L.n_below;
+    float acc[CT], mx[CT];
+#pragma unroll
+    for (int k = 0; k < CT; ++k) { acc[k] = identity<OP>(); mx[k] = -INFINITY; }
+    uint32_t b[kSlabD];
+    int i = 0;
+    for (;;) {       // two blocks per turn, the two register sets change roles
+        slab_fwd_block<OP, CT, FG>(a, b, slab_after(run, i, next), n_rows, n_below, q, acc, mx, prev, cur, below, ld, nact, tb_col, T);
+        i += kSlabD;
+        if (i >= run.n) {
+#pragma unroll
+            for (int u = 0; u < kSlabD; ++u) a[u] = b[u];
+            break;
+        }
+        slab_fwd_block<OP, CT, FG>(b, a, slab_after(run, i, next), n_rows, n_below, q, acc, mx, prev, cur, below, ld, nact, tb_col, T);
+        i += kSlabD;
+        if (i >= run.n) break;
+    }
+}
+
+template <int CT, bool FG>
+__device__ __forceinline__ void slab_fwd_layer(int semiring, bool is_and, const SlabLayer& L, const SlabRun& run,
+                                               const SlabRun& next, uint32_t (&a)[kSlabD], const float* prev, float* cur,
+                                               const float* __restrict__ below, int ld, int nact,
+                                               float* __restrict__ tb_col, int T) {
+    if (semiring == 2) {           // (max, +) on log weights
+        if (is_and) slab_fwd_rows<OP_SUM, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+        else slab_fwd_rows<OP_MAX, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+    } else if (semiring == 1) {    // (logsumexp, +)
+        if (is_and) slab_fwd_rows<OP_SUM, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+        else slab_fwd_rows<OP_LSE, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+    } else {
+        if (is_and) slab_fwd_rows<OP_PROD, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+        else slab_fwd_rows<OP_SUM, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+    }
+}
+
+__device__ __forceinline__ float log1mexp_f(float x) {
+    return x > -0.69314718f ? logf(-expm1f(x)) : log1pf(-expf(x));
+}
+
+// Arguments of the leaf layer when the persistent kernel evaluates it itself (its first layer is
+// layer 1): a workgroup reads its own rows of the leaf-weight arrays, which are contiguous.
+struct SlabLeaf {
+    const float* w;             // [B, V] leaf weights (null: the leaf layer was evaluated by leaf_fwd_kernel)
+    const float* wneg;          // [B, V] weights of the negated literals, or null
+    const int32_t* leaf_code;   // [n_0] +(v+1), -(v+1), INT32_MAX (true), INT32_MIN (false)
+    float* wT;                  // [V, ld] transposed leaf weights kept for the reverse sweep
+    float* act0;                // [n_0, ld] rows of layer 0 in the activation buffer
+    int32_t V, n0;
+};
+
 template <int CT>
-__global__ __launch_bounds__(kTailThreads) void tail_fwd_kernel(const TailLayer* __restrict__ layers, int n_layers,
+__global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer* __restrict__ layers, int n_layers,
                                                                 int first_is_and, const int32_t* __restrict__ ibase,
-                                                                float* act, int B, int ld, int semiring,
-                                                                int nmax, float* __restrict__ tb, int T) {
+                                                                const float* __restrict__ act, int B, int ld,
+                                                                int semiring, int nmax, float* __restrict__ tb, int T,
+                                                                SlabLeaf leaf, const int32_t* __restrict__ root_pos,
+                                                                int R, float* __restrict__ out) {
     extern __shared__ float smem[];
     float* prev = smem;
-    float* cur = smem + (size_t)nmax * CT;
-    int* ib = reinterpret_cast<int*>(smem + (size_t)2 * nmax * CT);
-    const int col = (int)blockIdx.x * CT + (int)(threadIdx.x % CT);
-    const bool active = col < B;
-    // The index vectors of a layer travel from global memory to registers two layers ahead (two
-    // register stashes used in turn), so their latency is covered by two layers of evaluation.
-    auto fetch = [&](int (&stash)[kTailStash], int t) {
-        const TailLayer Lf = layers[t];
-        const int32_t* g = ibase + Lf.fwd_off;
+    float* cur = smem + (size_t)(nmax + 1) * CT;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int col0 = (int)blockIdx.x * CT;
+    const int nact = B - col0 < CT ? B - col0 : CT;          // active columns of this workgroup (>= 1)
+    float* tb0 = tb + (size_t)col0 * T;
+    const bool log_domain = semiring != 0;
+    // the first block of the first layer's lines is on its way while the leaf layer is evaluated
+    SlabRun run = slab_run(ibase, layers[0].fwd_ent, layers[0].fwd_line, wave, lane);
+    uint32_t a[kSlabD];
+    slab_fetch(a, run.sp);
+    if (leaf.w) {
+        // leaf layer into LDS; the transposed weights and the rows of layer 0 also go to global memory
+        // for the reverse sweep (every column of [0, ld): the last workgroup zeroes the padding columns)
+        for (int i = threadIdx.x; i < leaf.n0; i += kSlabThreads) {
+            const int code = leaf.leaf_code[i];
 #pragma unroll
-        for (int u = 0; u < kTailStash; ++u) {
-            const int i = threadIdx.x + u * kTailThreads;
-            stash[u] = i < Lf.n + 1 + Lf.e ? g[i] : 0;
+            for (int k = 0; k < CT; ++k) {
+                float v = 0.0f;
+                if (k < nact) {
+                    if (code == INT32_MAX) v = log_domain ? 0.0f : 1.0f;
+                    else if (code == INT32_MIN) v = log_domain ? -INFINITY : 0.0f;
+                    else {
+                        const int var = (code > 0 ? code : -code) - 1;
+                        const size_t at = (size_t)(col0 + k) * leaf.V + var;
+                        if (code > 0) v = leaf.w[at];
+                        else if (leaf.wneg) v = leaf.wneg[at];
+                        else v = log_domain ? log1mexp_f(leaf.w[at]) : 1.0f - leaf.w[at];
+                    }
+                    leaf.act0[(size_t)i * ld + col0 + k] = v;
+                }
+                prev[i * CT + k] = v;
+            }
+            if (blockIdx.x == gridDim.x - 1)
+                for (int b = B; b < ld; ++b) leaf.act0[(size_t)i * ld + b] = 0.0f;
         }
-    };
-    auto layer = [&](int (&stash)[kTailStash], int t) {
-        const TailLayer L = layers[t];
-#pragma unroll
-        for (int u = 0; u < kTailStash; ++u) {
-            const int i = threadIdx.x + u * kTailThreads;
-            if (i < L.n + 1 + L.e) ib[i] = stash[u];
+        for (int v = threadIdx.x; v < leaf.V; v += kSlabThreads) {
+            for (int k = 0; k < nact; ++k) leaf.wT[(size_t)v * ld + col0 + k] = leaf.w[(size_t)(col0 + k) * leaf.V + v];
+            if (blockIdx.x == gridDim.x - 1)
+                for (int b = B; b < ld; ++b) leaf.wT[(size_t)v * ld + b] = 0.0f;
         }
+        if (threadIdx.x < CT) prev[leaf.n0 * CT + threadIdx.x] = slab_identity(semiring, first_is_and != 0);
         __syncthreads();
-        if (t + 2 < n_layers) fetch(stash, t + 2);
+    }
+    for (int t = 0; t < n_layers; ++t) {
+        const SlabLayer& L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
-        const float* below = act + (size_t)L.row0_below * ld + col;
-        float* out = act + (size_t)L.row0 * ld + col;
-        const bool fg = t == 0;
-        float* tbo = tb + (size_t)(active ? col : 0) * T + L.tb_off;
-        // the first tail layer is read by the regular reverse pass below it, the top layer by the root kernel
-        const bool wa = semiring == 0 || t == 0 || t == n_layers - 1;
-        if (semiring == 2) {           // (max, +) on log weights
-            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
-            else tail_fwd_rows<OP_MAX, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
-        } else if (semiring == 1) {    // (logsumexp, +)
-            if (is_and) tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
-            else tail_fwd_rows<OP_LSE, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
-        } else {
-            if (is_and) tail_fwd_rows<OP_PROD, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
-            else tail_fwd_rows<OP_SUM, CT>(L, ib, prev, cur, below, fg, out, ld, active, tbo, wa);
-        }
+        float* tb_col = tb0 + L.tb_off;
+        const SlabRun next = t + 1 < n_layers ? slab_run(ibase, layers[t + 1].fwd_ent, layers[t + 1].fwd_line, wave, lane)
+                                              : slab_no_run(ibase, lane);
+        // the padding slot of this layer's values, for the layer above (the other operation)
+        if (threadIdx.x < CT) cur[L.n * CT + threadIdx.x] = slab_identity(semiring, !is_and);
+        if (t == 0 && !leaf.w)
+            slab_fwd_layer<CT, true>(semiring, is_and, L, run, next, a, prev, cur, act + (size_t)L.row0_below * ld + col0, ld, nact, tb_col, T);
+        else
+            slab_fwd_layer<CT, false>(semiring, is_and, L, run, next, a, prev, cur, nullptr, ld, nact, tb_col, T);
+        run = next;
         __syncthreads();
         float* tmp = prev; prev = cur; cur = tmp;
-    };
-    int stash_a[kTailStash], stash_b[kTailStash];
-    fetch(stash_a, 0);
-    if (n_layers > 1) fetch(stash_b, 1);
-    for (int t = 0; t < n_layers; t += 2) {
-        layer(stash_a, t);
-        if (t + 1 < n_layers) layer(stash_b, t + 1);
+    }
+    // roots: the top layer is in LDS
+    for (int i = threadIdx.x; i < R * CT; i += kSlabThreads) {
+        const int r = i / CT, k = i % CT;
+        if (k < nact) out[(size_t)(col0 + k) * R + r] = prev[root_pos[r] * CT + k];
     }
 }
 
-// Reverse sweep over the same layers (log semiring): seeds the top layer's adjoints from dout,
-// walks down to the first tail layer and leaves that layer's adjoints in g_out[n_first, ld].
+// One block of one step of the reverse sweep.  OR: the step goes through an OR layer (weighted edges
+// carry the softmax weight exp(child value - parent value)); otherwise every edge passes the adjoint on.
+template <int CT, bool OR>
+__device__ __forceinline__ void slab_bwd_block(const uint32_t (&a)[kSlabD], uint32_t (&b)[kSlabD], const uint32_t* fetch,
+                                               int n_below, int& q, float (&acc)[CT], float (&own)[CT],
+                                               const float* cur, float* nxt, const float* nl, const float* nb) {
+    slab_fetch(b, fetch);
+    float g[kSlabD][CT], y[kSlabD][CT];
+#pragma unroll
+    for (int u = 0; u < kSlabD; ++u) {
+        const int p = (int)(a[u] & kIdMask);          // a padding word names the slot past the last parent: adjoint 0
+#pragma unroll
+        for (int k = 0; k < CT; ++k) {
+            g[u][k] = cur[p * CT + k];
+            y[u][k] = OR ? nl[p * CT + k] : 0.0f;
+        }
+    }
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < kSlabD; ++u) {
+        // an unweighted edge (chain node or single-child OR above) passes the adjoint unchanged
+        const bool weighted = OR && (a[u] & kWeighted) != 0;
+#pragma unroll
+        for (int k = 0; k < CT; ++k) {
+            if (OR) {
+                const float wgt = !weighted ? 1.0f : ((y[u][k] == -INFINITY) ? 0.0f : fexp(own[k] - y[u][k]));
+                acc[k] = fmaf(g[u][k], wgt, acc[k]);
+            } else {
+                acc[k] += g[u][k];
+            }
+        }
+        if (__builtin_amdgcn_readfirstlane((int)a[u]) & (int)kLast) {
+            const int r = q * 64 + lane;
+            if (r < n_below) {
+#pragma unroll
+                for (int k = 0; k < CT; ++k) nxt[r * CT + k] = acc[k];
+            }
+            q += kSlabWaves;
+            const int r2 = q * 64 + lane;
+#pragma unroll
+            for (int k = 0; k < CT; ++k) {
+                acc[k] = 0.0f;
+                if (OR) own[k] = nb[(r2 < n_below ? r2 : 0) * CT + k];
+            }
+        }
+    }
+}
+
+template <int CT, bool OR>
+__device__ __forceinline__ void slab_bwd_rows(const SlabLayer& L, const SlabRun& run, const SlabRun& next,
+                                              uint32_t (&a)[kSlabD], const float* cur, float* nxt, const float* nl,
+                                              const float* nb) {
+    if (run.n <= 0) { slab_fetch(a, next.sp); return; }
+    int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_below = L.n_below;
+    const int lane = threadIdx.x & 63;
+    float acc[CT], own[CT];
+#pragma unroll
+    for (int k = 0; k < CT; ++k) {
+        acc[k] = 0.0f;
+        const int r = q * 64 + lane;
+        own[k] = OR ? nb[(r < n_below ? r : 0) * CT + k] : 0.0f;
+    }
+    uint32_t b[kSlabD];
+    int i = 0;
+    for (;;) {
+        slab_bwd_block<CT, OR>(a, b, slab_after(run, i, next), n_below, q, acc, own, cur, nxt, nl, nb);
+        i += kSlabD;
+        if (i >= run.n) {
+#pragma unroll
+            for (int u = 0; u < kSlabD; ++u) a[u] = b[u];
+            break;
+        }
+        slab_bwd_block<CT, OR>(b, a, slab_after(run, i, next), n_below, q, acc, own, cur, nxt, nl, nb);
+        i += kSlabD;
+        if (i >= run.n) break;
+    }
+}
+
+// Reverse sweep over the same layers (log semiring): seeds the top layer's adjoints from dout, walks
+// down to the first layer of the launch and leaves that layer's adjoints in g_out[n_first, ld].
+// LDS: adjoints of the layer in hand and of the one below, and, for a step through an OR layer, the
+// values of both (loaded from tb at the start of the step).
 template <int CT>
-__global__ __launch_bounds__(kTailThreads) void tail_bwd_kernel(const TailLayer* __restrict__ layers, int n_layers,
+__global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer* __restrict__ layers, int n_layers,
                                                                 int first_is_and, const int32_t* __restrict__ ibase,
-                                                                const float* __restrict__ act,
                                                                 const float* __restrict__ dout,
                                                                 const int32_t* __restrict__ top_ptr,
                                                                 const int32_t* __restrict__ top_root, int R,
                                                                 float* __restrict__ g_out, int B, int ld, int nmax,
                                                                 const float* __restrict__ tb, int T) {
     extern __shared__ float smem[];
-    constexpr int RS = kTailThreads / CT;
+    const size_t stride = (size_t)(nmax + 1) * CT;
     float* cur = smem;
-    float* nxt = smem + (size_t)nmax * CT;
-    float* nl = smem + (size_t)2 * nmax * CT;
-    int* ib = reinterpret_cast<int*>(smem + (size_t)3 * nmax * CT);
-    const int c = threadIdx.x % CT;
+    float* nxt = smem + stride;
+    float* nl = smem + 2 * stride;          // values of the layer in hand (parents)
+    float* nb = smem + 3 * stride;          // values of the layer below (the rows of the step)
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int col0 = (int)blockIdx.x * CT;
-    const int col = col0 + c;
-    const bool active = col < B;
+    const int nact = B - col0 < CT ? B - col0 : CT;
+    const float* tb0 = tb + (size_t)col0 * T;
+    SlabRun run = n_layers > 1 ? slab_run(ibase, layers[n_layers - 1].bwd_ent, layers[n_layers - 1].bwd_line, wave, lane)
+                               : slab_no_run(ibase, lane);
+    uint32_t a[kSlabD];
+    slab_fetch(a, run.sp);
     {   // adjoint seed of the top layer
-        const TailLayer L = layers[n_layers - 1];
-        for (int i = threadIdx.x / CT; i < L.n; i += RS) {
-            float acc = 0.0f;
-            if (active)
-                for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)col * R + top_root[t]];
-            cur[i * CT + c] = acc;
+        const SlabLayer& L = layers[n_layers - 1];
+        for (int i = threadIdx.x; i < L.n; i += kSlabThreads) {
+#pragma unroll
+            for (int k = 0; k < CT; ++k) {
+                float acc = 0.0f;
+                if (k < nact)
+                    for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)(col0 + k) * R + top_root[t]];
+                cur[i * CT + k] = acc;
+            }
         }
+        if (threadIdx.x < CT) cur[L.n * CT + threadIdx.x] = 0.0f;       // padding slot: adjoint 0
     }
-    // step t (adjoints of layer t -> layer t-1) uses the by-child index vectors of layer t; they are
-    // fetched two steps ahead into two register stashes used in turn
-    auto fetch = [&](int (&stash)[kTailStash], int t) {
-        const TailLayer Lf = layers[t];
-        const int32_t* g = ibase + Lf.bwd_off;
-#pragma unroll
-        for (int u = 0; u < kTailStash; ++u) {
-            const int i = threadIdx.x + u * kTailThreads;
-            stash[u] = i < Lf.n_below + 1 + Lf.e ? g[i] : 0;
-        }
-    };
-    auto step = [&](int (&stash)[kTailStash], int t) {
-        const TailLayer L = layers[t];
+    for (int t = n_layers - 1; t >= 1; --t) {      // adjoints of layer t -> layer t - 1
+        const SlabLayer& L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
+        const SlabRun next = t - 1 >= 1 ? slab_run(ibase, layers[t - 1].bwd_ent, layers[t - 1].bwd_line, wave, lane)
+                                        : slab_no_run(ibase, lane);
+        if (!is_and) {
+            const int off_below = layers[t - 1].tb_off;
+            for (int i = threadIdx.x; i < L.n; i += kSlabThreads)
 #pragma unroll
-        for (int u = 0; u < kTailStash; ++u) {
-            const int i = threadIdx.x + u * kTailThreads;
-            if (i < L.n_below + 1 + L.e) ib[i] = stash[u];
+                for (int k = 0; k < CT; ++k) nl[i * CT + k] = k < nact ? tb0[(size_t)k * T + L.tb_off + i] : 0.0f;
+            if (threadIdx.x < CT) nl[L.n * CT + threadIdx.x] = 0.0f;
+            for (int i = threadIdx.x; i < L.n_below; i += kSlabThreads)
+#pragma unroll
+                for (int k = 0; k < CT; ++k) nb[i * CT + k] = k < nact ? tb0[(size_t)k * T + off_below + i] : 0.0f;
         }
-        if (t - 2 >= 1) fetch(stash, t - 2);
-        if (!is_and)
-            for (int i = threadIdx.x; i < L.n * CT; i += kTailThreads) {
-                const int cc = col0 + i % CT;
-                nl[i] = cc < B ? tb[(size_t)cc * T + L.tb_off + i / CT] : 0.0f;
-            }
         __syncthreads();
-        const int off_below = layers[t - 1].tb_off;
-        for (int r = threadIdx.x / CT; r < L.n_below; r += RS) {
-            const int beg = ib[r], end = ib[r + 1];
-            float acc = 0.0f, mx = 0.0f;
-            if (is_and) {
-                for (int j = beg; j < end; ++j) acc += cur[(ib[L.n_below + 1 + j] & (int)kIdMask) * CT + c];
-            } else {
-                const float own = active ? tb[(size_t)col * T + off_below + r] : 0.0f;
-                for (int j = beg; j < end; ++j) {
-                    // an unweighted edge (chain node or single-child OR above) passes the adjoint unchanged
-                    const uint32_t pe = (uint32_t)ib[L.n_below + 1 + j];
-                    const int p = (int)(pe & kIdMask);
-                    accumulate<OP_SOFTMAX_BWD>(acc, mx, cur[p * CT + c], nl[p * CT + c], own, (pe & kWeighted) != 0);
-                }
-            }
-            nxt[r * CT + c] = acc;
-        }
+        if (is_and) slab_bwd_rows<CT, false>(L, run, next, a, cur, nxt, nl, nb);
+        else slab_bwd_rows<CT, true>(L, run, next, a, cur, nxt, nl, nb);
+        if (threadIdx.x < CT) nxt[L.n_below * CT + threadIdx.x] = 0.0f;  // padding slot of the next step
+        run = next;
         __syncthreads();
         float* tmp = cur; cur = nxt; nxt = tmp;
-    };
-    int stash_a[kTailStash], stash_b[kTailStash];
-    if (n_layers - 1 >= 1) fetch(stash_a, n_layers - 1);
-    if (n_layers - 2 >= 1) fetch(stash_b, n_layers - 2);
-    for (int t = n_layers - 1; t >= 1; t -= 2) {
-        step(stash_a, t);
-        if (t - 1 >= 1) step(stash_b, t - 1);
     }
     const int n_first = layers[0].n;
-    if (active)
-        for (int r = threadIdx.x / CT; r < n_first; r += RS) g_out[(size_t)r * ld + col] = cur[r * CT + c];
+    for (int r = threadIdx.x; r < n_first; r += kSlabThreads)
+#pragma unroll
+        for (int k = 0; k < CT; ++k)
+            if (k < nact) g_out[(size_t)r * ld + col0 + k] = cur[r * CT + k];
+}
+
+// rows[r, b] = tb[b, first + r] for r < n_rows: values that the persistent forward kernel left in the
+// column-major buffer, transposed into rows of the activation buffer through a 32 x 33 LDS tile.
+__global__ __launch_bounds__(256) void tb_to_rows_kernel(const float* __restrict__ tb, int T, int first, int n_rows,
+                                                         int B, int ld, float* __restrict__ rows) {
+    __shared__ float tile[32][33];
+    const int r0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int b = b0 + ty + 8 * j, r = r0 + tx;
+        tile[ty + 8 * j][tx] = (b < B && r < n_rows) ? tb[(size_t)b * T + first + r] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = r0 + ty + 8 * j, b = b0 + tx;
+        if (r < n_rows && b < ld) rows[(size_t)r * ld + b] = tile[tx][ty + 8 * j];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -616,10 +1004,6 @@ __global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restric
 // literal rows of layer 0; the negated literal gets 1-p (REAL) or log(1-exp(x)) (LOG).
 // Tile = 32 variables x 64 batch columns through LDS.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float log1mexp_f(float x) {
-    return x > -0.69314718f ? logf(-expm1f(x)) : log1pf(-expf(x));
-}
-
 // Leaf layer: transposes leaf weights [B, V] into rows [*, ld] through an LDS tile.  The negated
 // literal of v gets wneg[b, v] when the caller supplies weights of its own for the negated literals,
 // otherwise 1 - w (real semiring) or log(1 - exp(w)) (log domain).

@@ -131,6 +131,38 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
     out.n_seg_tasks = cut_tasks(n, n + n_seg, out.seg_tasks);
 }
 
+namespace {
+// chunked, lane-interleaved index vectors of a CSR with n_src source rows, one run of lines per wave
+// (see SlabPlan)
+void make_slab(int64_t n, int64_t n_src, const int32_t* ptr, const int32_t* idx, const uint32_t* flags, SlabPlan& out) {
+    const int64_t chunks = (n + 63) / 64;
+    std::vector<int32_t> width((size_t)chunks, 0);
+    for (int64_t q = 0; q < chunks; ++q)
+        for (int64_t r = q * 64; r < std::min<int64_t>(n, q * 64 + 64); ++r)
+            width[(size_t)q] = std::max(width[(size_t)q], ptr[r + 1] - ptr[r]);
+    for (int32_t& w : width) w = std::max(w, 1);      // every chunk has a last line, also one of empty rows
+    int64_t lines = 0;
+    for (int w = 0; w < kSlabWaves; ++w) {
+        out.wave_line[w] = (int32_t)lines;
+        for (int64_t q = w; q < chunks; q += kSlabWaves) lines += width[(size_t)q];
+        lines = (lines + kSlabBlock - 1) / kSlabBlock * kSlabBlock;
+    }
+    out.wave_line[kSlabWaves] = (int32_t)lines;
+    out.ent.assign((size_t)lines * 64, (uint32_t)n_src);
+    for (int w = 0; w < kSlabWaves; ++w) {
+        int64_t line = out.wave_line[w];
+        for (int64_t q = w; q < chunks; q += kSlabWaves) {
+            const int32_t wq = width[(size_t)q];
+            for (int64_t r = q * 64; r < std::min<int64_t>(n, q * 64 + 64); ++r)
+                for (int32_t j = ptr[r]; j < ptr[r + 1]; ++j)
+                    out.ent[(size_t)(line + (j - ptr[r])) * 64 + (size_t)(r - q * 64)] = (uint32_t)idx[j] | (flags ? flags[j] : 0u);
+            for (int lane = 0; lane < 64; ++lane) out.ent[(size_t)(line + wq - 1) * 64 + (size_t)lane] |= kLastEdge;
+            line += wq;
+        }
+    }
+}
+}  // namespace
+
 int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node_lit,
              const int64_t* child_ptr, const int32_t* child_idx_in, int32_t R, const int32_t* roots_in,
              const Options& opt, CircuitPlan& plan, std::string& err) {
@@ -582,14 +614,18 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 }
         }
         make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd, cflag.data());
-        int64_t layer_fan = 0;
-        for (int64_t i = 0; i < lay.n; ++i) layer_fan = std::max<int64_t>(layer_fan, lay.row_ptr[(size_t)i + 1] - lay.row_ptr[(size_t)i]);
-        for (int64_t i = 0; i < nc; ++i) layer_fan = std::max<int64_t>(layer_fan, cptr[(size_t)i + 1] - cptr[(size_t)i]);
-        if (lay.n <= kTailRowsCap && nc <= kTailRowsCap && e <= kTailEdgesCap && layer_fan <= kTailFanCap) {
-            // the persistent kernels read these plain vectors; parent entries keep the weighted-edge bit
-            for (int64_t j = 0; j < e; ++j) cpar[(size_t)j] = (int32_t)((uint32_t)cpar[(size_t)j] | cflag[(size_t)j]);
-            lay.col_ptr.swap(cptr);
-            lay.parent.swap(cpar);
+        if (!opt.no_tail && lay.n <= kTailRowsCap && nc <= kTailRowsCap) {
+            int64_t fan_in = 0, fan_out = 0;
+            for (int64_t i = 0; i < lay.n; ++i) fan_in = std::max<int64_t>(fan_in, lay.row_ptr[(size_t)i + 1] - lay.row_ptr[(size_t)i]);
+            for (int64_t i = 0; i < nc; ++i) fan_out = std::max<int64_t>(fan_out, cptr[(size_t)i + 1] - cptr[(size_t)i]);
+            if (fan_in <= kTailFanCap) {
+                make_slab(lay.n, nc, lay.row_ptr.data(), lay.child.data(), nullptr, lay.slab_fwd);
+                lay.tail_fwd_ok = true;
+                if (fan_out <= kTailFanCap) {
+                    make_slab(nc, lay.n, cptr.data(), cpar.data(), cflag.data(), lay.slab_bwd);
+                    lay.tail_bwd_ok = true;
+                }
+            }
         }
         plan.num_split_rows += lay.bwd.n_heavy;
         plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, lay.bwd.n_seg);
@@ -642,11 +678,14 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     }
 
     // the narrow top: the longest suffix of layers that all kept their plain index vectors
-    plan.tail_first = 0;
+    plan.tail_first = plan.tail_bwd_first = 0;
     if (!opt.no_tail && !alias) {
         int32_t t = L + 1;
-        while (t - 1 >= 1 && !plan.layers[(size_t)t - 1].col_ptr.empty()) --t;
+        while (t - 1 >= 1 && plan.layers[(size_t)t - 1].tail_fwd_ok) --t;
         if (t <= L) plan.tail_first = t;
+        t = L + 1;
+        while (t - 1 >= 1 && plan.layers[(size_t)t - 1].tail_bwd_ok) --t;
+        if (t <= L) plan.tail_bwd_first = t;
     }
 
     // ---------------------------------------------------------------- leaf layer and roots

@@ -18,11 +18,30 @@ struct Options {
     bool no_merge = false;      // keep structurally identical gates apart
 };
 
-// Layers at the top of the circuit with at most this many nodes (and 4x as many edges) keep
-// plain by-parent and by-child index vectors for the persistent LDS kernels.
-constexpr int64_t kTailRowsCap = 4096;
-constexpr int64_t kTailEdgesCap = 16000;              // rows + 1 + edges must stay <= 20480 (kernel stash)
-constexpr int64_t kTailFanCap = 64;                   // no row with more sources than this (one thread walks a row)
+// Layers at the top of the circuit with at most this many nodes are candidates for the persistent
+// kernels, which keep two (forward) or three (reverse) layers of one batch column in LDS: 20000 rows
+// is what two value arrays of 160 KB hold.  In those kernels a lane walks a whole row, so a candidate
+// layer has no row with more sources than kTailFanCap (the reverse plan: no node with more parents).
+constexpr int64_t kTailRowsCap = 20000;
+constexpr int64_t kTailFanCap = 64;
+
+// Index vectors of one layer for the persistent kernels.  Rows are taken in chunks of 64 consecutive
+// rows (one per lane of a wave); a chunk has as many steps as its longest row, and step i of a chunk
+// is one line of 64 words: lane j holds the i-th source of row 64 * chunk + j, or a padding word when
+// that row is shorter or does not exist.  A padding word names source n_src, one past the last source
+// row: the kernels keep the identity of the layer's operation in that slot, so padding needs no test.
+// The 16 waves of the workgroup take the chunks round-robin, and the lines of the chunks of one wave
+// are stored back to back in the order the wave walks them, so a wave streams through one contiguous
+// run of lines and can fetch them far ahead.  Every word of the last line of a chunk carries
+// kLastEdge: the wave then closes the 64 rows of the chunk and moves on to its next one (16 chunks
+// further).  Runs are padded with lines of padding words to a multiple of kSlabBlock lines, the unit
+// the kernels fetch.
+constexpr int kSlabWaves = 16;
+constexpr int kSlabBlock = 8;
+struct SlabPlan {
+    int32_t wave_line[kSlabWaves + 1] = {};   // first line of each wave's run (wave_line[16] = all lines)
+    std::vector<uint32_t> ent;                // 64 words per line: source row | flags
+};
 
 // One gather-reduce pass set over a CSR whose rows are the outputs.
 //   rows [0, n_main)                 write output row i; a split row holds the single entry kSkip
@@ -59,8 +78,10 @@ struct LayerPlan {
     std::vector<int32_t> child;      // [e]    S_l: position of the child in layer - 1
     std::vector<int32_t> origin;     // [n] input node id the row stands for
     std::vector<uint8_t> is_pad;     // [n] 1 for unary chain nodes
-    std::vector<int32_t> col_ptr;    // [n_below + 1] by child (kept for tail candidates only)
-    std::vector<int32_t> parent;     // [e] parent row, with kWeightedEdge set as in bwd
+    bool tail_fwd_ok = false;        // slab_fwd is built: the layer may run in the persistent forward kernel
+    bool tail_bwd_ok = false;        // slab_bwd is built as well
+    SlabPlan slab_fwd;               // rows = nodes of this layer, sources = positions in layer - 1
+    SlabPlan slab_bwd;               // rows = nodes of layer - 1, sources = parents in this layer (| kWeightedEdge)
     PassPlan fwd;                    // outputs = nodes of this layer, sources = layer - 1
     PassPlan bwd;                    // outputs = nodes of layer - 1, sources = this layer
 };
@@ -76,7 +97,8 @@ struct CircuitPlan {
     int64_t max_layer_nodes = 0, max_fan_in = 0, max_fan_out = 0, num_split_rows = 0;
     int64_t num_merged = 0;              // input gates identified with an identical gate
     int64_t max_fwd_seg = 0, max_bwd_seg = 0;   // scratch rows needed by split passes
-    int32_t tail_first = 0;              // layers tail_first..num_layers are tail candidates (0: none)
+    int32_t tail_first = 0;              // layers tail_first..num_layers may run in the persistent forward kernel (0: none)
+    int32_t tail_bwd_first = 0;          // layers tail_bwd_first..num_layers also in the reverse one (>= tail_first; 0: none)
     // alias mode (Options::alias_chains): child entries, root_pos and the reverse-sweep sources are
     // rows of the whole activation buffer (row0[l] = first row of layer l); layers[l].bwd gathers
     // the adjoints of layer l-1 from parents in any higher layer, top_bwd those of the top layer;

@@ -108,6 +108,48 @@ static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const st
     }
 }
 
+// the walk of the persistent kernels over a chunked plan: each of the 16 waves streams through its run
+// of lines, one word per lane; the end-of-chunk bit (the same in all 64 words of a line) closes the 64
+// rows of the chunk in hand, and the wave's next chunk is 16 chunks further; padding words add nothing
+static void check_slab(const klay::SlabPlan& sp, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what) {
+    const int64_t chunks = (n_out + 63) / 64;
+    CHECK(sp.wave_line[0] == 0 && (int64_t)sp.ent.size() == (int64_t)sp.wave_line[klay::kSlabWaves] * 64, "%s: sizes", what);
+    std::vector<int> written((size_t)n_out, 0);
+    for (int w = 0; w < klay::kSlabWaves; ++w) {
+        int64_t q = w;
+        std::vector<u64> acc(64, 0);
+        std::vector<int> ended(64, 0);
+        CHECK(sp.wave_line[w + 1] >= sp.wave_line[w], "%s: run bounds", what);
+        CHECK((sp.wave_line[w + 1] - sp.wave_line[w]) % klay::kSlabBlock == 0, "%s: run is not a whole number of blocks", what);
+        for (int64_t line = sp.wave_line[w]; line < sp.wave_line[w + 1]; ++line) {
+            const uint32_t* e = sp.ent.data() + (size_t)line * 64;
+            if (q >= chunks) {       // lines that fill the run up to a whole block: padding only, no end-of-chunk bit
+                for (int lane = 0; lane < 64; ++lane) CHECK((int64_t)e[lane] == n_src, "%s: filler line of wave %d", what, w);
+                continue;
+            }
+            for (int lane = 0; lane < 64; ++lane) {
+                CHECK((e[lane] & klay::kLastEdge) == (e[0] & klay::kLastEdge), "%s: end-of-chunk bit differs within a line", what);
+                const uint32_t src = e[lane] & kMask;
+                if ((int64_t)src == n_src) { CHECK(!(e[lane] & klay::kWeightedEdge), "%s: flag on padding", what); ended[(size_t)lane] = 1; continue; }
+                CHECK(!ended[(size_t)lane], "%s: source after padding", what);
+                CHECK(q * 64 + lane < n_out, "%s: source in a lane past the last row", what);
+                CHECK((int64_t)src < n_src, "%s: source out of range", what);
+                acc[(size_t)lane] += entry(e[lane] & ~klay::kLastEdge);
+            }
+            if (e[0] & klay::kLastEdge) {
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int64_t r = q * 64 + lane;
+                    if (r < n_out) { CHECK(acc[(size_t)lane] == want[(size_t)r], "%s: row %lld value", what, (long long)r); ++written[(size_t)r]; }
+                    acc[(size_t)lane] = 0; ended[(size_t)lane] = 0;
+                }
+                q += klay::kSlabWaves;
+            }
+        }
+        CHECK(q >= chunks && q < chunks + klay::kSlabWaves, "%s: wave %d ends at chunk %lld of %lld", what, w, (long long)q, (long long)chunks);
+    }
+    for (int64_t r = 0; r < n_out; ++r) CHECK(written[(size_t)r] == 1, "%s: row %lld closed %d times", what, (long long)r, written[(size_t)r]);
+}
+
 int main(int argc, char** argv) {
     const int trials = argc > 1 ? std::atoi(argv[1]) : 120;
     std::mt19937_64 rng(12345);
@@ -165,6 +207,11 @@ int main(int argc, char** argv) {
                     }
                     check_plan(lay.fwd, lay.n, nb, fwd, "forward plan"); ++plans;
                     check_plan(lay.bwd, nb, lay.n, bwd, "backward plan"); ++plans;
+                    CHECK(!lay.tail_bwd_ok || lay.tail_fwd_ok, "reverse persistent plan without the forward one");
+                    if (lay.tail_fwd_ok) { check_slab(lay.slab_fwd, lay.n, nb, fwd, "persistent forward plan"); ++plans; }
+                    if (lay.tail_bwd_ok) { check_slab(lay.slab_bwd, nb, lay.n, bwd, "persistent reverse plan"); ++plans; }
+                    if (plan.tail_first > 0 && l >= plan.tail_first) CHECK(lay.tail_fwd_ok, "candidate suffix");
+                    if (plan.tail_bwd_first > 0 && l >= plan.tail_bwd_first) CHECK(lay.tail_bwd_ok && plan.tail_bwd_first >= plan.tail_first, "reverse candidate suffix");
                 }
             } else {
                 const int64_t NR = plan.row0[(size_t)L + 1];
