@@ -55,7 +55,7 @@ def load_traffic(workload, batch, semiring, backward, alias):
     return table.get("runs", {}).get(key)
 
 
-def kernel_symbol(cls, B):
+def kernel_symbol(cls, B, edges=False):
     """rocprofv3's name for the kernel behind a profiling class (template arguments as it prints them)."""
     vec = 4 if B > 128 else (2 if B > 64 else 1)
     if B > 32:
@@ -68,7 +68,7 @@ def kernel_symbol(cls, B):
             w *= 2
         ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4}
         if cls in ops:
-            return "klay::pass_kernel<%d, 1, %d>" % (ops[cls], w)
+            return ("klay::edge_kernel<%d, %d>" if edges else "klay::pass_kernel<%d, 1, %d>") % (ops[cls], w)
     ct = 1
     while ct < 8 and (B + ct - 1) // ct > 256:
         ct *= 2
@@ -122,6 +122,8 @@ def main():
                     help="capture one step in a HIP graph (torch.cuda.graph) and time its replays")
     ap.add_argument("--alias-chains", action="store_true",
                     help="padding-free evaluation: no unary chain nodes, edges read the child's own row")
+    ap.add_argument("--small-batch-edges", action="store_true",
+                    help="B <= 32: the lanes = edges kernel instead of a lane group per row (for comparison)")
     ap.add_argument("--f64", action="store_true",
                     help="also time the double-precision kernels on the same workload (extra object \"f64\")")
     ap.add_argument("--cpu-columns", type=int, default=0, help="oracle sample size in batch columns (0: auto)")
@@ -178,7 +180,8 @@ def main():
     w32 = as_inputs(p, semiring != pkg.KLAY_REAL)
 
     t0 = time.perf_counter()
-    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, alias_chains=args.alias_chains)
+    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, alias_chains=args.alias_chains,
+                    small_batch_edges=args.small_batch_edges)
     t_build = time.perf_counter() - t0
     info = k.info()
     E, N = info["num_edges"], info["num_nodes"]
@@ -253,7 +256,7 @@ def main():
     for name, c in classes.items():
         if not c["launches"]:
             continue
-        g = by_symbol.setdefault(kernel_symbol(name, B), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
+        g = by_symbol.setdefault(kernel_symbol(name, B, args.small_batch_edges), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
                                                           "classes": []})
         for f in ("ms", "launches", "alg_bytes", "min_bytes"):
             g[f] += c[f]
@@ -264,7 +267,7 @@ def main():
     alg_bytes_step = sum(c["alg_bytes"] for c in classes.values()) / prof_steps
     min_bytes_step = sum(c["min_bytes"] for c in classes.values()) / prof_steps
     measured = None
-    if not args.no_tail and not args.graph:
+    if not args.no_tail and not args.graph and not args.small_batch_edges:
         measured = load_traffic(args.workload, B, semiring_name, backward, bool(args.alias_chains))
     per_launch_s = d["ms"] * 1e-3 / max(1, d["launches"])
     traffic = None

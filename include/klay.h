@@ -56,7 +56,11 @@ typedef struct klay_options {
                                 child's own row (same values, fewer rows and edges; klay_layer_csr
                                 then returns rows of the whole activation buffer, layer 0 first)    */
     int32_t no_merge;        /* 1: do not identify structurally identical gates (Section 3.2)         */
-    int32_t reserved[2];
+    int32_t small_batch_edges; /* 1: batches of at most 32 columns run the lanes = edges kernel (a wave takes
+                                64 / B index entries per step and reduces the entries of a row across its
+                                lanes with a segmented scan) instead of the default, a lane group per row,
+                                which measures about twice as fast at B = 1 and B = 4; same results        */
+    int32_t reserved[1];
 } klay_options;
 
 typedef struct klay_info_t {

@@ -38,7 +38,7 @@ class KlayError(RuntimeError):
 class klay_options(ctypes.Structure):
     _fields_ = [("no_reorder", ctypes.c_int32), ("heavy_fan", ctypes.c_int32), ("min_segment", ctypes.c_int32),
                 ("no_tail", ctypes.c_int32), ("alias_chains", ctypes.c_int32), ("no_merge", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2)]
+                ("small_batch_edges", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
 
 
 class klay_info_t(ctypes.Structure):
@@ -222,7 +222,7 @@ class Circuit:
 
     def __init__(self, num_vars, node_type, node_lit, child_ptr, child_idx, roots, device=0,
                  no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False,
-                 alias_chains=False, no_merge=False):
+                 alias_chains=False, no_merge=False, small_batch_edges=False):
         node_type = np.ascontiguousarray(node_type, dtype=np.uint8)
         node_lit = np.ascontiguousarray(node_lit, dtype=np.int32)
         child_ptr = np.ascontiguousarray(child_ptr, dtype=np.int64)
@@ -233,7 +233,7 @@ class Circuit:
         if child_ptr.shape[0] and child_idx.shape[0] != child_ptr[-1]:
             raise ValueError("child_idx must have child_ptr[-1] entries")
         opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail), int(alias_chains),
-                            int(no_merge))
+                            int(no_merge), int(small_batch_edges))
         self._h = None
         self._h = klay_build(int(num_vars), node_type.shape[0], _np_ptr(node_type), _np_ptr(node_lit),
                              _np_ptr(child_ptr), _np_ptr(child_idx) if child_idx.size else None,
@@ -465,9 +465,9 @@ class Builder:
                                 roots.shape[0], _np_ptr(roots))
 
     def finish(self, device=0, no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False,
-               alias_chains=False, no_merge=False) -> Circuit:
+               alias_chains=False, no_merge=False, small_batch_edges=False) -> Circuit:
         opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail), int(alias_chains),
-                            int(no_merge))
+                            int(no_merge), int(small_batch_edges))
         return Circuit._from_handle(klay_builder_finish(self._b, int(device), opts), device)
 
     def close(self):

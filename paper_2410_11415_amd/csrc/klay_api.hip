@@ -24,14 +24,6 @@
 constexpr size_t kStaticWorkspaceBytes = KLAY_STATIC_WORKSPACE_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
 
-// 1: batches of at most 32 columns run the lanes = edges kernel, 0: a lane group per row (for comparison)
-#ifndef KLAY_EDGE_SMALL_B
-#define KLAY_EDGE_SMALL_B 1
-#endif
-#ifndef KLAY_MERGE_VEC1
-#define KLAY_MERGE_VEC1 0
-#endif
-
 namespace {
 
 thread_local std::string g_err;
@@ -122,6 +114,7 @@ struct EventRec {
 struct klay_circuit {
     klay::CircuitPlan plan;
     int device = -1;
+    bool small_batch_edges = false;      // klay_options.small_batch_edges
     std::vector<DevLayer> dl;
     DevPass top_bwd;                     // alias mode: adjoints of the top layer (from the dout rows)
     int32_t* d_index = nullptr;          // one allocation holding every index array
@@ -442,17 +435,11 @@ klay_status upload(klay_circuit* c) {
         std::vector<klay::SlabLayer> descs;
         int64_t row0 = 0, tb_off = 0;
         for (int l = 0; l < p.tail_first; ++l) row0 += p.layers[(size_t)l].n;
-        auto add_slab = [&](const klay::SlabPlan& sp, int32_t& ent_off, int32_t (&line)[klay::kSlabWaves + 1]) {
-            ent_off = (int32_t)pk.add(sp.ent);
-            for (int w = 0; w <= klay::kSlabWaves; ++w) line[w] = sp.wave_line[w];
-        };
         for (int l = p.tail_first; l <= L; ++l) {
             const klay::LayerPlan& lay = p.layers[(size_t)l];
             klay::SlabLayer t{};
             t.n = (int32_t)lay.n;
             t.n_below = (int32_t)p.layers[(size_t)l - 1].n;
-            add_slab(lay.slab_fwd, t.fwd_ent, t.fwd_line);
-            if (lay.tail_bwd_ok) add_slab(lay.slab_bwd, t.bwd_ent, t.bwd_line);
             t.row0 = row0;
             t.row0_below = row0 - t.n_below;
             t.tb_off = (int32_t)tb_off;
@@ -460,6 +447,38 @@ klay_status upload(klay_circuit* c) {
             row0 += lay.n;
             descs.push_back(t);
         }
+        // One stream of lines per wave and direction: the wave's runs of all candidate layers back to
+        // back, in the order the sweep visits them, closed by a block of padding lines (the kernels fetch
+        // one block ahead of the one they work on).
+        auto add_streams = [&](bool backward) {
+            const int lo = backward ? p.tail_bwd_first : p.tail_first;
+            if (lo <= 0) return;
+            std::vector<uint32_t> stream;
+            std::vector<int64_t> start((size_t)(L + 1) * klay::kSlabWaves, 0);
+            for (int w = 0; w < klay::kSlabWaves; ++w) {
+                for (int step = 0; step <= L - lo; ++step) {
+                    const int l = backward ? L - step : lo + step;
+                    const klay::SlabPlan& sp = backward ? p.layers[(size_t)l].slab_bwd : p.layers[(size_t)l].slab_fwd;
+                    start[(size_t)l * klay::kSlabWaves + w] = (int64_t)stream.size();
+                    stream.insert(stream.end(), sp.ent.begin() + (size_t)sp.wave_line[w] * 64,
+                                  sp.ent.begin() + (size_t)sp.wave_line[w + 1] * 64);
+                }
+                stream.insert(stream.end(), (size_t)klay::kSlabBlock * 64, 0u);
+            }
+            const size_t base_off = pk.add(stream);
+            for (int l = lo; l <= L; ++l) {
+                klay::SlabLayer& t = descs[(size_t)(l - p.tail_first)];
+                const klay::SlabPlan& sp = backward ? p.layers[(size_t)l].slab_bwd : p.layers[(size_t)l].slab_fwd;
+                for (int w = 0; w < klay::kSlabWaves; ++w) {
+                    const int32_t at = (int32_t)(base_off + (size_t)start[(size_t)l * klay::kSlabWaves + w]);
+                    const int32_t cnt = sp.wave_line[w + 1] - sp.wave_line[w];
+                    if (backward) { t.bwd_start[w] = at; t.bwd_count[w] = cnt; }
+                    else { t.fwd_start[w] = at; t.fwd_count[w] = cnt; }
+                }
+            }
+        };
+        add_streams(false);
+        add_streams(true);
         c->tail_rows = tb_off;
         static_assert(sizeof(klay::SlabLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
         o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::SlabLayer) / sizeof(int32_t));
@@ -531,6 +550,7 @@ double pass_min_bytes(int op, double entries, double rows, double n_src, int B) 
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
                   const float* own, float* dst, float* seg_rows, const Geometry& g, int B, hipStream_t s,
                   Profiler& prof, int cls) {
+    const bool edges = prof.c->small_batch_edges;
     klay::PassArgs a{};
     a.ptr = dp.ptr;
     a.idx = dp.idx;
@@ -551,7 +571,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         // the main rows (same streaming walk, output to partial rows).  The softmax adjoint's segments
         // need their owner's value row, and one-column tiles (B <= 64) measured 9% faster through the
         // generic kernel: separate launch.
-        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && (g.vec >= 2 || KLAY_MERGE_VEC1);
+        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec >= 2;
         float* seg_base = seg_rows - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
@@ -570,15 +590,15 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
             prof.end();
         }
     } else {
-        // small batches: main rows and segments in one launch, lanes = edges
+        // small batches: main rows and segments in one launch (a lane group per row, or lanes = edges)
         prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B),
                    pass_min_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, (double)dp.n_src, B));
-#if KLAY_EDGE_SMALL_B
-        launch_edge(op, dp, g, src, src2, own, dst, seg_rows - (ptrdiff_t)dp.n_main * g.ld, B, s);
-#else
-        a.row_begin = 0;
-        launch_pass(op, a, g, s);
-#endif
+        if (edges) {
+            launch_edge(op, dp, g, src, src2, own, dst, seg_rows - (ptrdiff_t)dp.n_main * g.ld, B, s);
+        } else {
+            a.row_begin = 0;
+            launch_pass(op, a, g, s);
+        }
         prof.end();
     }
     if (dp.n_heavy > 0) {
@@ -1151,6 +1171,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
         o.no_tail = opts->no_tail != 0;
         o.alias_chains = opts->alias_chains != 0;
         o.no_merge = opts->no_merge != 0;
+        o.small_batch_edges = opts->small_batch_edges != 0;
     }
     std::unique_ptr<klay_circuit> c;
     try {
@@ -1167,6 +1188,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
         if (c->plan.leaf_code[(size_t)i] == INT32_MIN) c->false_row = (int32_t)i;
     }
     c->device = device;
+    c->small_batch_edges = o.small_batch_edges;
     if (device >= 0) {
         int ndev = 0;
         if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {

@@ -13,12 +13,6 @@
 
 #include "layerize.h"
 
-// gathers in flight per lane in the streaming kernel when a lane holds one batch column (B <= 64): rows
-// are 256 bytes then, and it takes more of them in flight to cover the latency
-#ifndef KLAY_CH_VEC1
-#define KLAY_CH_VEC1 4
-#endif
-
 namespace klay {
 
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4 };
@@ -163,7 +157,9 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
     // entries per chunk: measured on the headline workload, 4 (2 for the softmax adjoint, which loads
     // three rows per entry) beat 8 / 4 by 2%: the kernel is bandwidth-bound, fewer registers per wave
     // buy more resident waves
-    constexpr int CH = (OP == OP_SOFTMAX_BWD) ? (VEC == 1 ? KLAY_CH_VEC1 / 2 : 2) : (VEC == 1 ? KLAY_CH_VEC1 : 4);
+    // With one column per lane (B <= 64) a row is 256 bytes and twice as many have to be in flight:
+    // 8 (4) measured 3% faster on the power-law workload at B = 64, 4% on the headline circuit at B = 64.
+    constexpr int CH = (OP == OP_SOFTMAX_BWD) ? (VEC == 1 ? 4 : 2) : (VEC == 1 ? 8 : 4);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = ((int)blockIdx.y * 64 + lane) * VEC;
@@ -524,11 +520,13 @@ constexpr int kSlabD = kSlabBlock;
 struct SlabLayer {
     int32_t n, n_below;            // nodes of this layer and of the layer below
     int32_t tb_off;                // first entry of this layer in a column of tb
-    int32_t fwd_ent;               // by parent: offset (in ints) of the lines, then first line of each wave's run
-    int32_t fwd_line[kSlabWaves + 1];
-    int32_t bwd_ent;               // by child: rows are the nodes of the layer below
-    int32_t bwd_line[kSlabWaves + 1];
-    int32_t reserved[2];
+    int32_t reserved;
+    // Per wave: where its run of lines for this layer starts (offset in ints into the index buffer) and
+    // how many lines it has (a multiple of kSlabD).  The runs of one wave for consecutive layers are
+    // stored back to back, bottom-up for the forward sweep and top-down for the reverse one, with a
+    // block of padding lines after the last, so a wave fetches ahead through one contiguous stream.
+    int32_t fwd_start[kSlabWaves], fwd_count[kSlabWaves];
+    int32_t bwd_start[kSlabWaves], bwd_count[kSlabWaves];
     int64_t row0, row0_below;      // first activation rows
 };
 
@@ -538,39 +536,10 @@ __device__ __forceinline__ float slab_identity(int semiring, bool is_and) {
     return is_and ? 0.0f : -INFINITY;
 }
 
-// A wave's run of lines for one layer: sp points at this lane's word of the first line.
-struct SlabRun {
-    const uint32_t* sp;
-    int n;                         // lines, a multiple of kSlabD
-};
-
-__device__ __forceinline__ SlabRun slab_run(const int32_t* __restrict__ ibase, int ent, const int32_t* line, int wave, int lane) {
-    SlabRun r;
-    const int first = line[wave];
-    r.n = line[wave + 1] - first;
-    // a wave without lines in this layer still fetches (from the start of the index buffer, always
-    // readable) and ignores what it gets: loads under branches would be waited for one by one
-    r.sp = reinterpret_cast<const uint32_t*>(ibase) + (r.n > 0 ? ent + (size_t)first * 64 : (size_t)0) + lane;
-    return r;
-}
-
-// what a wave fetches when no layer follows: the start of the index buffer (readable, ignored)
-__device__ __forceinline__ SlabRun slab_no_run(const int32_t* __restrict__ ibase, int lane) {
-    SlabRun r;
-    r.n = 0;
-    r.sp = reinterpret_cast<const uint32_t*>(ibase) + lane;
-    return r;
-}
-
 // one block of lines starting at p (this lane's word of the first of them)
 __device__ __forceinline__ void slab_fetch(uint32_t (&a)[kSlabD], const uint32_t* p) {
 #pragma unroll
     for (int u = 0; u < kSlabD; ++u) a[u] = p[u * 64];
-}
-
-// where the block after block i of `run` comes from: the run itself, or the first block of `next`
-__device__ __forceinline__ const uint32_t* slab_after(const SlabRun& run, int i, const SlabRun& next) {
-    return i + kSlabD < run.n ? run.sp + (size_t)(i + kSlabD) * 64 : next.sp;
 }
 
 // One block of one layer, forward: works on the lines in `a` while the block at `fetch` travels into `b`.
@@ -619,50 +588,49 @@ __device__ __forceinline__ void slab_fwd_block(const uint32_t (&a)[kSlabD], uint
     }
 }
 
-// One layer, forward.  `a` holds the first block of this wave's run on entry and the first block of
-// `next` on exit.  FG: the sources are rows of the activation buffer in global memory (the layer below
-// the first persistent one), otherwise the previous layer's values in LDS.
+// One layer, forward: the `lines` lines at sp (this wave's run).  `a` holds the first block on entry and
+// the block that follows the run (the next layer's first, or padding) on exit.  FG: the sources are rows
+// of the activation buffer in global memory (the layer below the first persistent one), otherwise the
+// previous layer's values in LDS.
 template <int OP, int CT, bool FG>
-__device__ __forceinline__ void slab_fwd_rows(const SlabLayer& L, const SlabRun& run, const SlabRun& next,
+__device__ __forceinline__ void slab_fwd_rows(int n_rows, int n_below, const uint32_t* sp, int lines,
                                               uint32_t (&a)[kSlabD], const float* prev, float* cur,
                                               const float* __restrict__ below, int ld, int nact,
                                               float* __restrict__ tb_col, int T) {
-    if (run.n <= 0) { slab_fetch(a, next.sp); return; }
+    if (lines <= 0) return;
     int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // chunk in hand
-    const int n_rows = L.n, n_below = L.n_below;
     float acc[CT], mx[CT];
 #pragma unroll
     for (int k = 0; k < CT; ++k) { acc[k] = identity<OP>(); mx[k] = -INFINITY; }
     uint32_t b[kSlabD];
-    int i = 0;
-    for (;;) {       // two blocks per turn, the two register sets change roles
-        slab_fwd_block<OP, CT, FG>(a, b, slab_after(run, i, next), n_rows, n_below, q, acc, mx, prev, cur, below, ld, nact, tb_col, T);
+    for (int i = 0;;) {       // two blocks per turn, the two register sets change roles
+        slab_fwd_block<OP, CT, FG>(a, b, sp + (size_t)(i + kSlabD) * 64, n_rows, n_below, q, acc, mx, prev, cur, below, ld, nact, tb_col, T);
         i += kSlabD;
-        if (i >= run.n) {
+        if (i >= lines) {
 #pragma unroll
             for (int u = 0; u < kSlabD; ++u) a[u] = b[u];
             break;
         }
-        slab_fwd_block<OP, CT, FG>(b, a, slab_after(run, i, next), n_rows, n_below, q, acc, mx, prev, cur, below, ld, nact, tb_col, T);
+        slab_fwd_block<OP, CT, FG>(b, a, sp + (size_t)(i + kSlabD) * 64, n_rows, n_below, q, acc, mx, prev, cur, below, ld, nact, tb_col, T);
         i += kSlabD;
-        if (i >= run.n) break;
+        if (i >= lines) break;
     }
 }
 
 template <int CT, bool FG>
-__device__ __forceinline__ void slab_fwd_layer(int semiring, bool is_and, const SlabLayer& L, const SlabRun& run,
-                                               const SlabRun& next, uint32_t (&a)[kSlabD], const float* prev, float* cur,
+__device__ __forceinline__ void slab_fwd_layer(int semiring, bool is_and, int n_rows, int n_below, const uint32_t* sp,
+                                               int lines, uint32_t (&a)[kSlabD], const float* prev, float* cur,
                                                const float* __restrict__ below, int ld, int nact,
                                                float* __restrict__ tb_col, int T) {
     if (semiring == 2) {           // (max, +) on log weights
-        if (is_and) slab_fwd_rows<OP_SUM, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
-        else slab_fwd_rows<OP_MAX, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+        if (is_and) slab_fwd_rows<OP_SUM, CT, FG>(n_rows, n_below, sp, lines, a, prev, cur, below, ld, nact, tb_col, T);
+        else slab_fwd_rows<OP_MAX, CT, FG>(n_rows, n_below, sp, lines, a, prev, cur, below, ld, nact, tb_col, T);
     } else if (semiring == 1) {    // (logsumexp, +)
-        if (is_and) slab_fwd_rows<OP_SUM, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
-        else slab_fwd_rows<OP_LSE, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+        if (is_and) slab_fwd_rows<OP_SUM, CT, FG>(n_rows, n_below, sp, lines, a, prev, cur, below, ld, nact, tb_col, T);
+        else slab_fwd_rows<OP_LSE, CT, FG>(n_rows, n_below, sp, lines, a, prev, cur, below, ld, nact, tb_col, T);
     } else {
-        if (is_and) slab_fwd_rows<OP_PROD, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
-        else slab_fwd_rows<OP_SUM, CT, FG>(L, run, next, a, prev, cur, below, ld, nact, tb_col, T);
+        if (is_and) slab_fwd_rows<OP_PROD, CT, FG>(n_rows, n_below, sp, lines, a, prev, cur, below, ld, nact, tb_col, T);
+        else slab_fwd_rows<OP_SUM, CT, FG>(n_rows, n_below, sp, lines, a, prev, cur, below, ld, nact, tb_col, T);
     }
 }
 
@@ -697,10 +665,10 @@ __global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer*
     const int nact = B - col0 < CT ? B - col0 : CT;          // active columns of this workgroup (>= 1)
     float* tb0 = tb + (size_t)col0 * T;
     const bool log_domain = semiring != 0;
-    // the first block of the first layer's lines is on its way while the leaf layer is evaluated
-    SlabRun run = slab_run(ibase, layers[0].fwd_ent, layers[0].fwd_line, wave, lane);
+    // this wave's stream of lines; its first block is on its way while the leaf layer is evaluated
+    const uint32_t* sp = reinterpret_cast<const uint32_t*>(ibase) + layers[0].fwd_start[wave] + lane;
     uint32_t a[kSlabD];
-    slab_fetch(a, run.sp);
+    slab_fetch(a, sp);
     if (leaf.w) {
         // leaf layer into LDS; the transposed weights and the rows of layer 0 also go to global memory
         // for the reverse sweep (every column of [0, ld): the last workgroup zeroes the padding columns)
@@ -734,19 +702,23 @@ __global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer*
         if (threadIdx.x < CT) prev[leaf.n0 * CT + threadIdx.x] = slab_identity(semiring, first_is_and != 0);
         __syncthreads();
     }
+    // the few numbers a layer needs are read a layer ahead
+    int lines = layers[0].fwd_count[wave], n_rows = layers[0].n, n_below = layers[0].n_below, tb_off = layers[0].tb_off;
     for (int t = 0; t < n_layers; ++t) {
-        const SlabLayer& L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
-        float* tb_col = tb0 + L.tb_off;
-        const SlabRun next = t + 1 < n_layers ? slab_run(ibase, layers[t + 1].fwd_ent, layers[t + 1].fwd_line, wave, lane)
-                                              : slab_no_run(ibase, lane);
+        const int tn = t + 1 < n_layers ? t + 1 : t;
+        const int lines2 = layers[tn].fwd_count[wave], n_rows2 = layers[tn].n, n_below2 = layers[tn].n_below,
+                  tb_off2 = layers[tn].tb_off;
+        float* tb_col = tb0 + tb_off;
         // the padding slot of this layer's values, for the layer above (the other operation)
-        if (threadIdx.x < CT) cur[L.n * CT + threadIdx.x] = slab_identity(semiring, !is_and);
+        if (threadIdx.x < CT) cur[n_rows * CT + threadIdx.x] = slab_identity(semiring, !is_and);
         if (t == 0 && !leaf.w)
-            slab_fwd_layer<CT, true>(semiring, is_and, L, run, next, a, prev, cur, act + (size_t)L.row0_below * ld + col0, ld, nact, tb_col, T);
+            slab_fwd_layer<CT, true>(semiring, is_and, n_rows, n_below, sp, lines, a, prev, cur,
+                                     act + (size_t)layers[0].row0_below * ld + col0, ld, nact, tb_col, T);
         else
-            slab_fwd_layer<CT, false>(semiring, is_and, L, run, next, a, prev, cur, nullptr, ld, nact, tb_col, T);
-        run = next;
+            slab_fwd_layer<CT, false>(semiring, is_and, n_rows, n_below, sp, lines, a, prev, cur, nullptr, ld, nact, tb_col, T);
+        sp += (size_t)lines * 64;
+        lines = lines2; n_rows = n_rows2; n_below = n_below2; tb_off = tb_off2;
         __syncthreads();
         float* tmp = prev; prev = cur; cur = tmp;
     }
@@ -806,12 +778,10 @@ __device__ __forceinline__ void slab_bwd_block(const uint32_t (&a)[kSlabD], uint
 }
 
 template <int CT, bool OR>
-__device__ __forceinline__ void slab_bwd_rows(const SlabLayer& L, const SlabRun& run, const SlabRun& next,
-                                              uint32_t (&a)[kSlabD], const float* cur, float* nxt, const float* nl,
-                                              const float* nb) {
-    if (run.n <= 0) { slab_fetch(a, next.sp); return; }
+__device__ __forceinline__ void slab_bwd_rows(int n_below, const uint32_t* sp, int lines, uint32_t (&a)[kSlabD],
+                                              const float* cur, float* nxt, const float* nl, const float* nb) {
+    if (lines <= 0) return;
     int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int n_below = L.n_below;
     const int lane = threadIdx.x & 63;
     float acc[CT], own[CT];
 #pragma unroll
@@ -821,18 +791,17 @@ __device__ __forceinline__ void slab_bwd_rows(const SlabLayer& L, const SlabRun&
         own[k] = OR ? nb[(r < n_below ? r : 0) * CT + k] : 0.0f;
     }
     uint32_t b[kSlabD];
-    int i = 0;
-    for (;;) {
-        slab_bwd_block<CT, OR>(a, b, slab_after(run, i, next), n_below, q, acc, own, cur, nxt, nl, nb);
+    for (int i = 0;;) {
+        slab_bwd_block<CT, OR>(a, b, sp + (size_t)(i + kSlabD) * 64, n_below, q, acc, own, cur, nxt, nl, nb);
         i += kSlabD;
-        if (i >= run.n) {
+        if (i >= lines) {
 #pragma unroll
             for (int u = 0; u < kSlabD; ++u) a[u] = b[u];
             break;
         }
-        slab_bwd_block<CT, OR>(b, a, slab_after(run, i, next), n_below, q, acc, own, cur, nxt, nl, nb);
+        slab_bwd_block<CT, OR>(b, a, sp + (size_t)(i + kSlabD) * 64, n_below, q, acc, own, cur, nxt, nl, nb);
         i += kSlabD;
-        if (i >= run.n) break;
+        if (i >= lines) break;
     }
 }
 
@@ -859,10 +828,10 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
     const int col0 = (int)blockIdx.x * CT;
     const int nact = B - col0 < CT ? B - col0 : CT;
     const float* tb0 = tb + (size_t)col0 * T;
-    SlabRun run = n_layers > 1 ? slab_run(ibase, layers[n_layers - 1].bwd_ent, layers[n_layers - 1].bwd_line, wave, lane)
-                               : slab_no_run(ibase, lane);
+    // this wave's stream of lines, from the top layer's step downwards
+    const uint32_t* sp = reinterpret_cast<const uint32_t*>(ibase) + layers[n_layers - 1].bwd_start[wave] + lane;
     uint32_t a[kSlabD];
-    slab_fetch(a, run.sp);
+    slab_fetch(a, sp);
     {   // adjoint seed of the top layer
         const SlabLayer& L = layers[n_layers - 1];
         for (int i = threadIdx.x; i < L.n; i += kSlabThreads) {
@@ -879,8 +848,7 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
     for (int t = n_layers - 1; t >= 1; --t) {      // adjoints of layer t -> layer t - 1
         const SlabLayer& L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
-        const SlabRun next = t - 1 >= 1 ? slab_run(ibase, layers[t - 1].bwd_ent, layers[t - 1].bwd_line, wave, lane)
-                                        : slab_no_run(ibase, lane);
+        const int lines = L.bwd_count[wave];
         if (!is_and) {
             const int off_below = layers[t - 1].tb_off;
             for (int i = threadIdx.x; i < L.n; i += kSlabThreads)
@@ -892,10 +860,10 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
                 for (int k = 0; k < CT; ++k) nb[i * CT + k] = k < nact ? tb0[(size_t)k * T + off_below + i] : 0.0f;
         }
         __syncthreads();
-        if (is_and) slab_bwd_rows<CT, false>(L, run, next, a, cur, nxt, nl, nb);
-        else slab_bwd_rows<CT, true>(L, run, next, a, cur, nxt, nl, nb);
+        if (is_and) slab_bwd_rows<CT, false>(L.n_below, sp, lines, a, cur, nxt, nl, nb);
+        else slab_bwd_rows<CT, true>(L.n_below, sp, lines, a, cur, nxt, nl, nb);
+        sp += (size_t)lines * 64;
         if (threadIdx.x < CT) nxt[L.n_below * CT + threadIdx.x] = 0.0f;  // padding slot of the next step
-        run = next;
         __syncthreads();
         float* tmp = cur; cur = nxt; nxt = tmp;
     }

@@ -16,6 +16,7 @@ struct Options {
     bool no_tail = false;       // never use the persistent kernels for the narrow top layers
     bool alias_chains = false;  // no unary chain nodes: edges index the rows of any lower layer
     bool no_merge = false;      // keep structurally identical gates apart
+    bool small_batch_edges = false;   // evaluator option (not used by the layerizer): lanes = edges kernel for B <= 32
 };
 
 // Layers at the top of the circuit with at most this many nodes are candidates for the persistent

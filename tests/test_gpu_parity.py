@@ -212,6 +212,21 @@ def test_batch_sizes(klay, B):
     check_both(klay, c, leaf_probs(B, B, 48), what="B=%d" % B)
 
 
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 9, 16, 17, 31, 32])
+def test_small_batches_with_the_lanes_equal_edges_kernel(klay, B):
+    """the alternative kernel for B <= 32 (a wave takes 64 / B index entries per step, rows are reduced
+    across the lanes with a segmented scan): same results, with and without split rows, both sweeps,
+    every layer a launch of its own so that no layer bypasses it"""
+    c = layered_random(4, num_vars=48, depth=8, num_gates=1500, fanin=("geom", 2.0), groups=2, num_roots=7)
+    check_both(klay, c, leaf_probs(B, B, 48), what="edges B=%d" % B, small_batch_edges=True, no_tail=True)
+    z = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
+    pz = leaf_probs(5, B, 64, ("beta", 0.5, 0.5))
+    for heavy, seg in ((2, 1), (8, 4), (0, 0)):
+        check_both(klay, z, pz, what="edges split B=%d" % B, small_batch_edges=True, no_tail=True, heavy_fan=heavy,
+                   min_segment=seg)
+    check_max(klay, z, pz, what="edges maxlog", small_batch_edges=True, no_tail=True, heavy_fan=3, min_segment=2)
+
+
 # ------------------------------------------------------------------ split rows (high fan-in / fan-out)
 @pytest.mark.parametrize("heavy,seg", [(2, 1), (3, 2), (8, 4), (64, 16)])
 @pytest.mark.parametrize("B", [3, 64, 256])
@@ -932,7 +947,8 @@ def test_random_dags_with_random_options(klay, seed):
     V = int(rng.integers(2, 14))
     c = _random_dag(rng, V, int(rng.integers(5, 400)), hub_share=0.25, max_fan=int(rng.choice([3, 6, 40])))
     opts = dict(alias_chains=bool(rng.integers(2)), no_merge=bool(rng.integers(2)), no_reorder=bool(rng.integers(2)),
-                no_tail=bool(rng.integers(2)), heavy_fan=int(rng.choice([0, 2, 5, 17])), min_segment=int(rng.choice([0, 1, 3])))
+                no_tail=bool(rng.integers(2)), heavy_fan=int(rng.choice([0, 2, 5, 17])), min_segment=int(rng.choice([0, 1, 3])),
+                small_batch_edges=bool(seed % 3 == 0))
     B = int(rng.choice([1, 2, 7, 33, 64, 100, 257]))
     # probabilities near 1/2 keep the real semiring inside fp32 whatever the random structure multiplies up
     p = rng.uniform(0.35, 0.65, size=(B, V))
