@@ -87,7 +87,8 @@ typedef struct klay_info_t {
  * profiling is enabled.  Durations come from HIP events recorded on the caller's stream around
  * every single launch.  FWD_x / BWD_x are the main-row launches of a layer (one kernel each:
  * the streaming kernel for B > 32), SPLIT the segment and combine launches of split rows,
- * PROD_EDGES the per-edge products of the real-semiring reverse sweep. */
+ * PROD_EDGES the per-parent pass of the real-semiring reverse sweep over a product layer (adjoint
+ * times the product of the non-zero children, in place). */
 enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
        KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_FWD_MAX, KLAY_K_COUNT };
@@ -179,8 +180,7 @@ klay_status klay_forward_static(klay_circuit* c, const float* leaf_weights, int3
  *                 every entry is written (0 for variables the circuit does not use)
  * Uses B, the semiring and the activations of that forward call; the caller must not have run
  * another forward in between.  The first real-semiring call on a handle uploads extra index
- * arrays and allocates a per-edge buffer (hipMalloc, which synchronises); later calls only
- * enqueue (on an alias_chains handle the buffer holds a row per node and per AND-layer edge).
+ * arrays (hipMalloc, which synchronises); later calls only enqueue.
  * MAXLOG is not differentiated (KLAY_EINVAL).  A literal whose adjoint is exactly 0 contributes 0 even where the
  * derivative of its weight is infinite (log-domain negated literal at p = 1).
  * Errors: KLAY_ESTATE if no forward was run, KLAY_EINVAL, KLAY_EHIP.
@@ -209,9 +209,8 @@ klay_status klay_backward_lits(klay_circuit* c, const float* dout, float* dpos, 
  *   pos_weights, neg_weights, out, dout, dpos, dneg   as for klay_forward_lits / klay_backward_lits,
  *                 in double; neg_weights = NULL derives the negated literals from pos_weights, and
  *                 dneg must then be NULL as well.
- * All three semirings are evaluated; KLAY_LOG and KLAY_REAL are differentiated (the real semiring not on
- * alias_chains handles, KLAY_MAXLOG not at all: KLAY_EINVAL).  In double the real semiring reaches
- * circuits whose values underflow fp32.
+ * All three semirings are evaluated; KLAY_LOG and KLAY_REAL are differentiated (KLAY_MAXLOG is not:
+ * KLAY_EINVAL).  In double the real semiring reaches circuits whose values underflow fp32.
  * The activations live in a library-owned workspace of their own (klay_set_workspace and
  * klay_workspace_bytes do not cover it) and are independent of the fp32 state: a handle can hold
  * one fp32 and one double-precision forward pass at the same time.  Profiling does not cover

@@ -24,6 +24,11 @@
 constexpr size_t kStaticWorkspaceBytes = KLAY_STATIC_WORKSPACE_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
 
+// Layers with split rows and at most this many index entries run main rows and segments in one generic
+// launch (measured on the power-law workload at B = 64: 60000 and 150000 both give 0.73 ms against
+// 0.81 ms without, 400000 gives 0.76 ms).
+constexpr int64_t kSmallPassEntries = 100000;
+
 namespace {
 
 thread_local std::string g_err;
@@ -71,10 +76,14 @@ struct DevPass {
     int64_t n_src = 0;                           // distinct source rows the pass reads
 };
 
+// Log-semiring reverse sweep (handles without aliasing): adjoints of OR layers in the one-gather form.
+constexpr bool kOneGather = true;
+
 struct DevLayer {
     int64_t n = 0, e = 0;
     int64_t row0 = 0;        // first row of this layer in the activation buffer
     DevPass fwd, bwd;
+    const uint32_t* multi = nullptr;   // OR layers: bit r = node r has more than one child
 };
 
 struct Geometry {            // how a batch of B columns is mapped onto lanes
@@ -128,17 +137,11 @@ struct klay_circuit {
     int64_t tail_rows = 0;                     // T: rows of all tail candidate layers (one column of the tail buffer)
     int32_t last_tail_first = 0;               // first layer the last forward ran in the persistent kernel (0: none)
     // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
-    // vectors and a by-child pass whose entries are edge positions, plus the per-edge buffer M
+    // vectors (for prod_parent_kernel); on an alias_chains handle also, per layer, the by-child pass over
+    // the parents in all higher layers whose entries tell AND parents from plain adjoint rows
     struct RealLayer { const int32_t* ptr = nullptr; const int32_t* child = nullptr; DevPass by_child; };
     std::vector<RealLayer> real_layers;
     int32_t* d_real_index = nullptr;
-    int64_t real_max_edges = 0, real_max_seg = 0;
-    // alias mode: the reverse sweep reads one combined buffer [adjoint rows | dout rows | per-edge rows of
-    // every AND layer]; real_edge_base[l] = first per-edge row of AND layer l in it
-    std::vector<int64_t> real_edge_base;
-    int64_t real_and_edges = 0;
-    float* real_buf = nullptr;                 // M [max e_l, ld] followed by the partial rows of split rows
-    size_t real_buf_bytes = 0;
     void* ws_own = nullptr;
     size_t ws_own_bytes = 0;
     void* ws_user = nullptr;
@@ -152,8 +155,6 @@ struct klay_circuit {
     // double-precision evaluation (its own library-owned workspace)
     void* ws64 = nullptr;
     size_t ws64_bytes = 0;
-    double* real_buf64 = nullptr;              // per-edge buffer of the real-semiring reverse sweep in double
-    size_t real_buf64_bytes = 0;
     bool have_fwd64 = false;
     int32_t last64_B = 0;
     int last64_semiring = 0;
@@ -229,6 +230,9 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
     case klay::OP_PROD: launch_op<klay::OP_PROD>(a, g, grid, s); break;
     case klay::OP_LSE: launch_op<klay::OP_LSE>(a, g, grid, s); break;
     case klay::OP_MAX: launch_op<klay::OP_MAX>(a, g, grid, s); break;
+    case klay::OP_PROD_BWD: launch_op<klay::OP_PROD_BWD>(a, g, grid, s); break;
+    case klay::OP_SUM_H: launch_op<klay::OP_SUM_H>(a, g, grid, s); break;
+    case klay::OP_SOFTMAX_H: launch_op<klay::OP_SOFTMAX_H>(a, g, grid, s); break;
     default: launch_op<klay::OP_SOFTMAX_BWD>(a, g, grid, s); break;
     }
 }
@@ -271,6 +275,9 @@ void launch_edge(int op, const DevPass& dp, const Geometry& g, const float* src,
     case klay::OP_PROD: launch_edge_op<klay::OP_PROD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_LSE: launch_edge_op<klay::OP_LSE>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_MAX: launch_edge_op<klay::OP_MAX>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_PROD_BWD: launch_edge_op<klay::OP_PROD_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SUM_H: launch_edge_op<klay::OP_SUM_H>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SOFTMAX_H: launch_edge_op<klay::OP_SOFTMAX_H>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     default: launch_edge_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     }
 }
@@ -306,6 +313,9 @@ void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, con
     case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_MAX: launch_stream_op<klay::OP_MAX>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_PROD_BWD: launch_stream_op<klay::OP_PROD_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SUM_H: launch_stream_op<klay::OP_SUM_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SOFTMAX_H: launch_stream_op<klay::OP_SOFTMAX_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     }
 }
@@ -489,6 +499,8 @@ klay_status upload(klay_circuit* c) {
         fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
         bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
     }
+    std::vector<size_t> mo((size_t)L + 1, 0);
+    for (int l = 2; l <= L; l += 2) mo[(size_t)l] = pk.add(p.layers[(size_t)l].multi);
     PassOffsets to{};
     if (p.alias) to = pack_pass(pk, p.top_bwd);
     const size_t o_pos = pk.add(p.pos_row), o_neg = pk.add(p.neg_row), o_root = pk.add(p.root_pos);
@@ -517,6 +529,7 @@ klay_status upload(klay_circuit* c) {
         if (l >= 1) {
             bind_pass(d.fwd, p.layers[(size_t)l].fwd, fo[(size_t)l], base);
             bind_pass(d.bwd, p.layers[(size_t)l].bwd, bo[(size_t)l], base);
+            if ((l & 1) == 0) d.multi = reinterpret_cast<const uint32_t*>(base + mo[(size_t)l]);
         }
     }
     if (p.alias) bind_pass(c->top_bwd, p.top_bwd, to, base);
@@ -535,7 +548,7 @@ klay_status upload(klay_circuit* c) {
 // (and, in the softmax adjoint, reads its own value row), plus the index entries themselves.
 double pass_bytes(int op, double entries, double rows, int B) {
     const double per_entry = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
-    const double per_row = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
+    const double per_row = (op == klay::OP_SUM || op == klay::OP_PROD || op == klay::OP_LSE || op == klay::OP_MAX) ? 1.0 : 2.0;
     return 4.0 * B * (per_entry * entries + per_row * rows) + 4.0 * (entries + rows);
 }
 
@@ -571,8 +584,18 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         // the main rows (same streaming walk, output to partial rows).  The softmax adjoint's segments
         // need their owner's value row, and one-column tiles (B <= 64) measured 9% faster through the
         // generic kernel: separate launch.
-        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && g.vec >= 2;
+        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && op != klay::OP_SOFTMAX_H && op != klay::OP_PROD_BWD && g.vec >= 2;
         float* seg_base = seg_rows - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
+        if (!merged && dp.n_seg > 0 && dp.main_entries + dp.seg_entries <= kSmallPassEntries) {
+            // A small layer with split rows whose segments cannot ride in the streaming launch: main rows
+            // and segments in one launch of the generic kernel (a wave per row) instead of two launches.
+            // Such layers are bound by their launches, not by what the kernels move.
+            prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B),
+                       pass_min_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, (double)dp.n_src, B));
+            a.row_begin = 0;
+            launch_pass(op, a, g, s);
+            prof.end();
+        } else {
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
         // the distinct source rows are charged to the main launch, a separate segment launch only
@@ -588,6 +611,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
             a.row_begin = dp.n_main;
             launch_pass(op, a, g, s);
             prof.end();
+        }
         }
     } else {
         // small batches: main rows and segments in one launch (a lane group per row, or lanes = edges)
@@ -606,6 +630,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         cmb.ptr = dp.comb_ptr;
         cmb.idx = dp.comb_idx;
         cmb.src = seg_rows;
+        cmb.own = own;               // OP_SUM_H: the value rows of the nodes the combine pass writes
         cmb.out_row = dp.comb_row;
         cmb.dst = dst;
         cmb.dst_seg = nullptr;
@@ -715,7 +740,7 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* ac
 }
 
 void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb, const float* dout,
-                     float* g_out, int B, int ld, hipStream_t s) {
+                     float* g_out, const uint32_t* first_multi, int B, int ld, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
@@ -725,7 +750,7 @@ void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb
 #define KLAY_TAIL_BWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::slab_bwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
                        n_layers, first_is_and, c->d_index, dout, c->d_top_ptr, c->d_top_root,          \
-                       p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows)
+                       p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows, first_multi)
     switch (t.ct) {
     case 8: KLAY_TAIL_BWD(8); break;
     case 4: KLAY_TAIL_BWD(4); break;
@@ -777,135 +802,107 @@ double tail_min_bytes(const klay_circuit* c, int first, int B, bool backward) {
 
 
 // ---- real-semiring reverse sweep -----------------------------------------------------------------
-klay_status ensure_real_bwd(klay_circuit* c, int ld) {
+klay_status ensure_real_bwd(klay_circuit* c) {
     const klay::CircuitPlan& p = c->plan;
     const int L = p.num_layers;
-    if (c->real_layers.empty()) {
-        Packer pk;
-        struct Off { size_t ptr = 0, child = 0; PassOffsets pass{}; klay::PassPlan plan; };
-        std::vector<Off> offs((size_t)L + 1);
-        klay::Options opt;
-        if (p.alias) {
-            // Every row of the activation buffer gathers from its parents in any higher layer: an OR
-            // parent passes its adjoint row, an AND parent the per-edge row of that edge, a root column
-            // its dout row.  All three live in one buffer, so a plain sum over row ids does it.
-            const int64_t NR = p.row0[(size_t)L + 1], R = p.num_roots;
-            c->real_edge_base.assign((size_t)L + 2, 0);
-            int64_t eb = NR + R;
+    if (!c->real_layers.empty()) return KLAY_OK;
+    Packer pk;
+    struct Off { size_t ptr = 0, child = 0; PassOffsets pass{}; klay::PassPlan plan; };
+    std::vector<Off> offs((size_t)L + 1);
+    klay::Options opt;
+    for (int l = 1; l <= L; l += 2) {           // AND layers: plain index vectors by parent
+        offs[(size_t)l].ptr = pk.add(p.layers[(size_t)l].row_ptr);
+        offs[(size_t)l].child = pk.add(p.layers[(size_t)l].child);
+    }
+    if (p.alias) {
+        // Every row of the activation buffer gathers from its parents in any higher layer and, a root,
+        // from its dout row.  An AND parent's row holds P (see prod_parent_kernel); a sum node's row and a
+        // dout row hold plain adjoints: those entries carry the weighted bit, which OP_PROD_BWD reads as
+        // "add as it is".
+        const int64_t NR = p.row0[(size_t)L + 1], R = p.num_roots;
+        std::vector<int32_t> gptr((size_t)NR + 1, 0);
+        for (int l = 1; l <= L; ++l)
+            for (int32_t ch : p.layers[(size_t)l].child) ++gptr[(size_t)ch + 1];
+        for (int32_t r = 0; r < R; ++r) ++gptr[(size_t)p.root_pos[(size_t)r] + 1];
+        for (int64_t i = 0; i < NR; ++i) gptr[(size_t)i + 1] += gptr[(size_t)i];
+        std::vector<int32_t> gsrc((size_t)gptr[(size_t)NR]);
+        std::vector<uint32_t> gflag((size_t)gptr[(size_t)NR], 0u);
+        {
+            std::vector<int32_t> fill(gptr.begin(), gptr.end() - 1);
             for (int l = 1; l <= L; ++l) {
-                c->real_edge_base[(size_t)l] = eb;
-                if (l & 1) eb += p.layers[(size_t)l].e;
-            }
-            c->real_and_edges = eb - (NR + R);
-            if (eb >= ((int64_t)1 << 30)) return fail(KLAY_EINVAL, "klay_backward: more than 2^30 rows in the real-semiring reverse sweep");
-            std::vector<int32_t> gptr((size_t)NR + 1, 0);
-            for (int l = 1; l <= L; ++l)
-                for (int32_t ch : p.layers[(size_t)l].child) ++gptr[(size_t)ch + 1];
-            for (int32_t r = 0; r < R; ++r) ++gptr[(size_t)p.root_pos[(size_t)r] + 1];
-            for (int64_t i = 0; i < NR; ++i) gptr[(size_t)i + 1] += gptr[(size_t)i];
-            std::vector<int32_t> gsrc((size_t)gptr[(size_t)NR]);
-            {
-                std::vector<int32_t> fill(gptr.begin(), gptr.end() - 1);
-                for (int l = 1; l <= L; ++l) {
-                    const klay::LayerPlan& lay = p.layers[(size_t)l];
-                    for (int64_t r = 0; r < lay.n; ++r)
-                        for (int32_t j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j)
-                            gsrc[(size_t)fill[(size_t)lay.child[(size_t)j]]++] =
-                                (l & 1) ? (int32_t)(c->real_edge_base[(size_t)l] + j) : (int32_t)(p.row0[(size_t)l] + r);
-                }
-                for (int32_t r = 0; r < R; ++r) gsrc[(size_t)fill[(size_t)p.root_pos[(size_t)r]]++] = (int32_t)(NR + r);
-            }
-            for (int l = 0; l <= L; ++l) {
                 const klay::LayerPlan& lay = p.layers[(size_t)l];
-                Off& o = offs[(size_t)l];
-                if (l & 1) {
-                    o.ptr = pk.add(lay.row_ptr);
-                    o.child = pk.add(lay.child);
-                }
-                const int64_t a = p.row0[(size_t)l];
-                std::vector<int32_t> lptr((size_t)lay.n + 1);
-                for (int64_t i = 0; i <= lay.n; ++i) lptr[(size_t)i] = gptr[(size_t)(a + i)] - gptr[(size_t)a];
-                klay::make_pass_plan(lay.n, lptr.data(), gsrc.data() + gptr[(size_t)a], opt, o.plan);
-                o.pass = pack_pass(pk, o.plan);
-                c->real_max_seg = std::max<int64_t>(c->real_max_seg, o.plan.n_seg);
+                for (int64_t r = 0; r < lay.n; ++r)
+                    for (int32_t j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
+                        const int32_t slot = fill[(size_t)lay.child[(size_t)j]]++;
+                        gsrc[(size_t)slot] = (int32_t)(p.row0[(size_t)l] + r);
+                        if ((l & 1) == 0) gflag[(size_t)slot] = klay::kWeightedEdge;
+                    }
             }
-            c->real_max_edges = eb;          // rows of the combined buffer
+            for (int32_t r = 0; r < R; ++r) {
+                const int32_t slot = fill[(size_t)p.root_pos[(size_t)r]]++;
+                gsrc[(size_t)slot] = (int32_t)(NR + r);
+                gflag[(size_t)slot] = klay::kWeightedEdge;
+            }
         }
-        for (int l = 1; l <= L && !p.alias; l += 2) {           // AND layers
+        for (int l = 0; l <= L; ++l) {
             const klay::LayerPlan& lay = p.layers[(size_t)l];
             Off& o = offs[(size_t)l];
-            o.ptr = pk.add(lay.row_ptr);
-            o.child = pk.add(lay.child);
-            // by child: rows = nodes of layer l-1, entries = positions of their edges in `child`
-            const int64_t nc = p.layers[(size_t)l - 1].n;
-            std::vector<int32_t> cptr((size_t)nc + 1, 0), cedge((size_t)lay.e);
-            for (int64_t j = 0; j < lay.e; ++j) ++cptr[(size_t)lay.child[(size_t)j] + 1];
-            for (int64_t i = 0; i < nc; ++i) cptr[(size_t)i + 1] += cptr[(size_t)i];
-            std::vector<int32_t> fill(cptr.begin(), cptr.end() - 1);
-            for (int64_t j = 0; j < lay.e; ++j) cedge[(size_t)fill[(size_t)lay.child[(size_t)j]]++] = (int32_t)j;
-            // entries are edge positions: they share the 30-bit id field of the index entries
-            if (lay.e >= ((int64_t)1 << 30)) return fail(KLAY_EINVAL, "klay_backward: an AND layer has 2^30 edges or more");
-            klay::make_pass_plan(nc, cptr.data(), cedge.data(), opt, o.plan);
+            const int64_t a = p.row0[(size_t)l];
+            std::vector<int32_t> lptr((size_t)lay.n + 1);
+            for (int64_t i = 0; i <= lay.n; ++i) lptr[(size_t)i] = gptr[(size_t)(a + i)] - gptr[(size_t)a];
+            klay::make_pass_plan(lay.n, lptr.data(), gsrc.data() + gptr[(size_t)a], opt, o.plan, gflag.data() + gptr[(size_t)a]);
+            if (o.plan.n_seg > p.max_bwd_seg)
+                return fail(KLAY_EINVAL, "klay_backward: split plan of the real-semiring sweep exceeds the workspace");
             o.pass = pack_pass(pk, o.plan);
-            c->real_max_edges = std::max<int64_t>(c->real_max_edges, lay.e);
-            c->real_max_seg = std::max<int64_t>(c->real_max_seg, o.plan.n_seg);
-        }
-        const size_t bytes = pk.buf.size() * sizeof(int32_t);
-        if (hipMalloc(reinterpret_cast<void**>(&c->d_real_index), bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return fail(KLAY_ENOMEM, "klay_backward: hipMalloc of the real-semiring index arrays failed");
-        }
-        if (hipError_t e = hipMemcpy(c->d_real_index, pk.buf.data(), bytes, hipMemcpyHostToDevice); e != hipSuccess) {
-            (void)hipFree(c->d_real_index);
-            c->d_real_index = nullptr;
-            return fail(KLAY_EHIP, std::string("klay_backward: upload of the real-semiring index arrays: ") +
-                                       hipGetErrorString(e));
-        }
-        c->real_layers.resize((size_t)L + 1);
-        for (int l = p.alias ? 0 : 1; l <= L; l += p.alias ? 1 : 2) {
-            klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
-            if (l & 1) {
-                r.ptr = c->d_real_index + offs[(size_t)l].ptr;
-                r.child = c->d_real_index + offs[(size_t)l].child;
-            }
-            bind_pass(r.by_child, offs[(size_t)l].plan, offs[(size_t)l].pass, c->d_real_index);
         }
     }
-    const size_t need = (size_t)(c->real_max_edges + std::max<int64_t>(c->real_max_seg, 1) + 1) * ld * sizeof(float);
-    if (need > c->real_buf_bytes) {
-        if (c->real_buf) { KLAY_HIP(hipFree(c->real_buf)); c->real_buf = nullptr; c->real_buf_bytes = 0; }
-        if (hipMalloc(reinterpret_cast<void**>(&c->real_buf), need) != hipSuccess) {
-            (void)hipGetLastError();
-            return fail(KLAY_ENOMEM, "klay_backward: hipMalloc of the per-edge buffer failed");
+    const size_t bytes = pk.buf.size() * sizeof(int32_t);
+    if (hipMalloc(reinterpret_cast<void**>(&c->d_real_index), bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(KLAY_ENOMEM, "klay_backward: hipMalloc of the real-semiring index arrays failed");
+    }
+    if (hipError_t e = hipMemcpy(c->d_real_index, pk.buf.data(), bytes, hipMemcpyHostToDevice); e != hipSuccess) {
+        (void)hipFree(c->d_real_index);
+        c->d_real_index = nullptr;
+        return fail(KLAY_EHIP, std::string("klay_backward: upload of the real-semiring index arrays: ") +
+                                   hipGetErrorString(e));
+    }
+    c->real_layers.resize((size_t)L + 1);
+    for (int l = 0; l <= L; ++l) {
+        klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
+        if (l & 1) {
+            r.ptr = c->d_real_index + offs[(size_t)l].ptr;
+            r.child = c->d_real_index + offs[(size_t)l].child;
         }
-        c->real_buf_bytes = need;
+        if (p.alias) bind_pass(r.by_child, offs[(size_t)l].plan, offs[(size_t)l].pass, c->d_real_index);
     }
     return KLAY_OK;
 }
 
-void launch_prod_edges(const klay_circuit::RealLayer& r, int n, const float* below, const float* gl, float* M,
-                       const Geometry& g, int B, hipStream_t s) {
+// adjoint rows of an AND layer -> P rows, in place (see prod_parent_kernel)
+void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* below, float* gl, const Geometry& g, int B,
+                        hipStream_t s) {
     if (n <= 0) return;                               // a layer can be empty in alias mode
     const int rpw = 64 / g.w;
     const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
-#define KLAY_PE(VEC, W) \
-    hipLaunchKernelGGL((klay::prod_edge_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, M, n, B, g.ld)
+#define KLAY_PP(VEC, W) \
+    hipLaunchKernelGGL((klay::prod_parent_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, n, B, g.ld)
     if (g.w == 64) {
-        if (g.vec == 4) KLAY_PE(4, 64);
-        else if (g.vec == 2) KLAY_PE(2, 64);
-        else KLAY_PE(1, 64);
+        if (g.vec == 4) KLAY_PP(4, 64);
+        else if (g.vec == 2) KLAY_PP(2, 64);
+        else KLAY_PP(1, 64);
     } else {
         switch (g.w) {
-        case 32: KLAY_PE(1, 32); break;
-        case 16: KLAY_PE(1, 16); break;
-        case 8: KLAY_PE(1, 8); break;
-        case 4: KLAY_PE(1, 4); break;
-        case 2: KLAY_PE(1, 2); break;
-        default: KLAY_PE(1, 1); break;
+        case 32: KLAY_PP(1, 32); break;
+        case 16: KLAY_PP(1, 16); break;
+        case 8: KLAY_PP(1, 8); break;
+        case 4: KLAY_PP(1, 4); break;
+        case 2: KLAY_PP(1, 2); break;
+        default: KLAY_PP(1, 1); break;
         }
     }
-#undef KLAY_PE
+#undef KLAY_PP
 }
 
 // ---- double-precision evaluation ---------------------------------------------------------------
@@ -950,6 +947,7 @@ void launch_pass64(int op, const klay::f64::PassArgs& a, hipStream_t s) {
     case klay::OP_PROD: launch_pass64<klay::OP_PROD>(a, s); break;
     case klay::OP_LSE: launch_pass64<klay::OP_LSE>(a, s); break;
     case klay::OP_MAX: launch_pass64<klay::OP_MAX>(a, s); break;
+    case klay::OP_PROD_BWD: launch_pass64<klay::OP_PROD_BWD>(a, s); break;
     default: launch_pass64<klay::OP_SOFTMAX_BWD>(a, s); break;
     }
 }
@@ -1051,8 +1049,6 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     if (c->last64_semiring == KLAY_MAXLOG)
         return fail(KLAY_EINVAL, "klay_backward_f64: the (max, +) semiring is not differentiated");
     const bool real = c->last64_semiring == KLAY_REAL;
-    if (real && c->plan.alias)
-        return fail(KLAY_EINVAL, "klay_backward_f64: the real semiring is not differentiated in alias_chains mode");
     if (dneg && !c->last64_neg_explicit)
         return fail(KLAY_ESTATE, "klay_backward_f64: dneg given, but the forward pass had no weights for the negated literals");
     KLAY_HIP(hipSetDevice(c->device));
@@ -1070,21 +1066,33 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     const int leaf_mode = c->last64_neg_explicit ? 2 : (real ? 0 : 1);
     const dim3 leaf_grid((unsigned)std::max(V, 1), (unsigned)((B + 255) / 256));
     if (real) {
-        // as the fp32 real-semiring sweep: sum layers pass adjoints through, product layers go through
-        // the per-edge buffer M, summed by child (index arrays shared with the fp32 path)
-        klay_status rs = ensure_real_bwd(c, 1);
+        // as the fp32 real-semiring sweep: sum layers pass adjoints through; the adjoint rows of a product
+        // layer become P rows in place and the by-child pass OP_PROD_BWD shares them out (index arrays
+        // shared with the fp32 path)
+        klay_status rs = ensure_real_bwd(c);
         if (rs != KLAY_OK) return rs;
-        const size_t need = (size_t)(c->real_max_edges + std::max<int64_t>(c->real_max_seg, 1) + 1) * ld * sizeof(double);
-        if (need > c->real_buf64_bytes) {
-            if (c->real_buf64) { KLAY_HIP(hipFree(c->real_buf64)); c->real_buf64 = nullptr; c->real_buf64_bytes = 0; }
-            if (hipMalloc(reinterpret_cast<void**>(&c->real_buf64), need) != hipSuccess) {
-                (void)hipGetLastError();
-                return fail(KLAY_ENOMEM, "klay_backward_f64: hipMalloc of the per-edge buffer failed");
+        const dim3 pp_block(256);
+        if (p.alias) {
+            double* X = gcur;
+            hipLaunchKernelGGL(klay::f64::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, ld,
+                               X + (size_t)p.num_nodes * ld);
+            for (int l = L; l >= 0; --l) {
+                const DevLayer& d = c->dl[(size_t)l];
+                double* gl = X + (size_t)d.row0 * ld;
+                run_pass_set64(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr,
+                               act + (size_t)d.row0 * ld, gl, seg_rows, B, ld, s);
+                if ((l & 1) && d.n > 0) {
+                    const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
+                    hipLaunchKernelGGL(klay::f64::prod_parent_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
+                                       pp_block, 0, s, r.ptr, r.child, act, gl, (int)d.n, B, ld);
+                }
             }
-            c->real_buf64_bytes = need;
+            if (V > 0)
+                hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, X, wT, c->d_pos_row, c->d_neg_row, B,
+                                   V, ld, leaf_mode, dleaf, dneg);
+            KLAY_HIP(hipGetLastError());
+            return KLAY_OK;
         }
-        double* M = c->real_buf64;
-        double* real_seg_rows = c->real_buf64 + (size_t)(c->real_max_edges + 1) * ld;
         hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
                            c->d_top_root, B, R, ld, gcur);
         for (int l = L; l >= 1; --l) {
@@ -1094,9 +1102,10 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
                 run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, B, ld, s);
             } else {
                 const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
-                hipLaunchKernelGGL(klay::f64::prod_edge_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
-                                   dim3(256), 0, s, r.ptr, r.child, act + (size_t)below.row0 * ld, gcur, M, (int)d.n, B, ld);
-                run_pass_set64(klay::OP_SUM, klay::OP_SUM, r.by_child, M, nullptr, nullptr, gnext, real_seg_rows, B, ld, s);
+                hipLaunchKernelGGL(klay::f64::prod_parent_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
+                                   pp_block, 0, s, r.ptr, r.child, act + (size_t)below.row0 * ld, gcur, (int)d.n, B, ld);
+                run_pass_set64(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, act + (size_t)below.row0 * ld, gnext,
+                               seg_rows, B, ld, s);
             }
             std::swap(gcur, gnext);
         }
@@ -1288,9 +1297,7 @@ void klay_destroy(klay_circuit* c) {
         if (c->d_index) (void)hipFree(c->d_index);
         if (c->ws_own) (void)hipFree(c->ws_own);
         if (c->d_real_index) (void)hipFree(c->d_real_index);
-        if (c->real_buf) (void)hipFree(c->real_buf);
         if (c->ws64) (void)hipFree(c->ws64);
-        if (c->real_buf64) (void)hipFree(c->real_buf64);
     }
     delete c;
 }
@@ -1536,19 +1543,20 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     Profiler prof(c, &c->ev_bwd, s);
 
     if (real) {
-        // Real semiring: sum layers pass adjoints through; product layers go through the per-edge
-        // buffer M (adjoint times the product of the other children), summed by child.
-        klay_status rs = ensure_real_bwd(c, g.ld);
+        // Real semiring: a sum layer passes adjoints through (plain by-child sums).  For a product layer
+        // the adjoint rows of its nodes are first turned, in place, into P rows (adjoint times the product
+        // of the non-zero children, prod_parent_kernel), and the by-child pass OP_PROD_BWD hands every
+        // child its share, using the child's own value.  Nothing is stored per edge.
+        klay_status rs = ensure_real_bwd(c);
         if (rs != KLAY_OK) return rs;
         // this sweep runs layer by layer on rows of the activation buffer: bring back the values the
         // persistent forward kernel kept column-major
         if (c->last_tail_first > 0) launch_tb_to_rows(c, c->last_tail_first, L, ws + lay.tb, act, B, g.ld, s);
-        float* M = c->real_buf;
-        float* real_seg_rows = c->real_buf + (size_t)(c->real_max_edges + 1) * g.ld;
         if (p.alias) {
-            // one buffer X = [adjoint rows | dout rows | per-edge rows]; layers from the top: gather the
-            // adjoints of the layer's rows, then (product layer) write the per-edge rows of its edges
-            float* X = c->real_buf;
+            // one adjoint row per activation row plus a dout row per root column; layers from the top:
+            // gather the adjoints of the layer's rows from all their parents, then (product layer) turn
+            // them into P rows for the layers below
+            float* X = gcur;
             prof.begin(KLAY_K_SEED, 8.0 * B * R);
             hipLaunchKernelGGL(klay::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, g.ld,
                                X + (size_t)p.num_nodes * g.ld);
@@ -1556,13 +1564,11 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             for (int l = L; l >= 0; --l) {
                 const DevLayer& d = c->dl[(size_t)l];
                 float* gl = X + (size_t)d.row0 * g.ld;
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr, nullptr, gl,
-                             real_seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
+                run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr,
+                             act + (size_t)d.row0 * g.ld, gl, seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
                 if (l & 1) {
-                    prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n),
-                               4.0 * B * ((double)d.e + 2.0 * (double)d.n));
-                    launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act, gl,
-                                      X + (size_t)c->real_edge_base[(size_t)l] * g.ld, g, B, s);
+                    prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
+                    launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, act, gl, g, B, s);
                     prof.end();
                 }
             }
@@ -1578,7 +1584,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         }
         prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
         hipLaunchKernelGGL(klay::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
-                           c->d_top_root, B, R, g.ld, gcur);
+                           c->d_top_root, B, R, g.ld, gcur, (const uint32_t*)nullptr, (const float*)nullptr);
         prof.end();
         for (int l = L; l >= 1; --l) {
             const DevLayer& d = c->dl[(size_t)l];
@@ -1587,12 +1593,12 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, g, B, s, prof,
                              KLAY_K_BWD_SUM);
             } else {
-                prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * (3.0 * (double)d.e + (double)d.n),
-                               4.0 * B * ((double)d.e + 2.0 * (double)d.n));
-                launch_prod_edges(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, M, g, B, s);
+                prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
+                launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, g, B, s);
                 prof.end();
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, c->real_layers[(size_t)l].by_child, M, nullptr, nullptr, gnext,
-                             real_seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
+                // the by-child plan of an AND layer carries no weighted bit: every entry is a P row
+                run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, act + (size_t)below.row0 * g.ld, gnext,
+                             seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
             }
             std::swap(gcur, gnext);
         }
@@ -1636,6 +1642,12 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         return KLAY_OK;
     }
 
+    // The adjoint rows of an OR layer with weighted edges travel in the one-gather form (encode_h): the
+    // step that produces them (OP_SUM_H, the seed, or the persistent kernel's last write) folds the
+    // node's own value in, and the step through the OR layer (OP_SOFTMAX_H) gathers that one row per
+    // edge instead of the adjoint row and the parent's value row.
+    auto one_gather = [&](int l) { return kOneGather && l >= 2 && (l & 1) == 0 && c->dl[(size_t)l].bwd.has_weighted; };
+
     // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
     // which seeds the adjoints itself and leaves those of its first layer in gcur
     int top = L;
@@ -1649,14 +1661,17 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     if (tail.first > 0) {
         prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R,
                    tail_min_bytes(c, tail.first, B, true) + 4.0 * B * R);
-        launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, B, g.ld, s);
+        launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, one_gather(tail.first) ? c->dl[(size_t)tail.first].multi : nullptr,
+                        B, g.ld, s);
         prof.end();
         top = tail.first;
     } else {
-        prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
+        const bool enc = one_gather(L);
+        prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n * (enc ? 2.0 : 1.0));
         dim3 grid((unsigned)c->dl[(size_t)L].n);
         hipLaunchKernelGGL(klay::seed_kernel, grid, dim3(256), 0, s, dout, c->d_top_ptr, c->d_top_root, B, R,
-                           g.ld, gcur);
+                           g.ld, gcur, enc ? c->dl[(size_t)L].multi : (const uint32_t*)nullptr,
+                           enc ? act + (size_t)c->dl[(size_t)L].row0 * g.ld : (const float*)nullptr);
         prof.end();
     }
 
@@ -1664,12 +1679,18 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         const DevLayer& d = c->dl[(size_t)l];
         const DevLayer& below = c->dl[(size_t)l - 1];
         const bool is_and = (l & 1) != 0 || !d.bwd.has_weighted;   // no weighted edge: plain sums
-        if (is_and)
-            run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, g, B, s, prof,
-                         KLAY_K_BWD_SUM);
-        else
-            run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld,
-                         act + (size_t)below.row0 * g.ld, gnext, seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
+        const float* own_below = act + (size_t)below.row0 * g.ld;
+        if (is_and) {
+            const bool enc = one_gather(l - 1);
+            run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SUM, enc ? klay::OP_SUM_H : klay::OP_SUM, d.bwd, gcur, nullptr,
+                         enc ? own_below : nullptr, gnext, seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
+        } else if (kOneGather) {
+            run_pass_set(klay::OP_SOFTMAX_H, klay::OP_SUM, d.bwd, gcur, nullptr, own_below, gnext, seg_rows, g, B, s,
+                         prof, KLAY_K_BWD_SOFTMAX);
+        } else {
+            run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld, own_below, gnext,
+                         seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
+        }
         std::swap(gcur, gnext);
     }
 

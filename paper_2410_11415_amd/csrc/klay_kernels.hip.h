@@ -15,13 +15,15 @@
 
 namespace klay {
 
-enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4 };
+enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4, OP_PROD_BWD = 5, OP_SUM_H = 6, OP_SOFTMAX_H = 7 };
 
-// Index entries: bits 0..29 = source row, bit 31 = last edge of its output row, bit 30 = weighted
+// Index entries: bits 0..28 = source row, bit 31 = last edge of its output row, bit 30 = weighted
 // edge (reverse sweep only: the parent is an OR node with more than one child, so the adjoint
-// passes through the softmax weight exp(child - parent); an unweighted edge passes it unchanged).
+// passes through the softmax weight exp(child - parent); an unweighted edge passes it unchanged),
+// bit 29 (on the last entry of a row only) = the output row is an OR node with more than one child, whose
+// adjoint is stored in the one-gather form (see encode_h).
 // kSkip (all ones) stands for a whole output row that this pass leaves untouched (a split row).
-constexpr uint32_t kLast = 0x80000000u, kWeighted = 0x40000000u, kSkip = 0xFFFFFFFFu, kIdMask = 0x3FFFFFFFu;
+constexpr uint32_t kLast = kLastEdge, kWeighted = kWeightedEdge, kSkip = kSkipRow, kIdMask = kRowFlag - 1u;
 
 struct PassArgs {
     const int32_t* ptr;        // [n_total + 1] CSR offsets into idx
@@ -106,8 +108,42 @@ __device__ __forceinline__ int xcd_block(int bid, int nblocks) { return (bid & 7
 //                     a new maximum rescales the sum by exp(mx - x), otherwise exp(x - mx) is added
 //   OP_SOFTMAX_BWD    acc += g * exp(own - parent value) on weighted edges (a parent at -inf
 //                     passes nothing down), acc += g on unweighted ones
+//   OP_PROD_BWD       real-semiring reverse sweep: x is the row that prod_parent_kernel left for an AND
+//                     parent r, P_r = G_r * (product of r's non-zero children), with the lowest mantissa
+//                     bit telling whether r has exactly one zero child (rows with more are all zero).
+//                     The child with value `own` gets P_r / own when r has no zero child, P_r when the
+//                     child is r's one zero, nothing otherwise.  A weighted entry is a plain adjoint row
+//                     (a sum node above, or a root's dout row) and is added as it is.
+// One-gather form of the softmax adjoint (log semiring, reverse sweep through an OR layer).  The adjoint
+// G_r of an OR node r with more than one child only ever reaches its children as G_r exp(N_c - N_r), so
+// the pass that produces G_r (OP_SUM_H: a plain sum, finished with the node's own value N_r) stores
+//   H_r = log|G_r| - N_r, with the sign of G_r in the lowest mantissa bit (-inf when G_r = 0 or N_r = -inf),
+// and the pass through the OR layer (OP_SOFTMAX_H) gathers that one row per edge and adds
+// +-exp(H_r + N_c): N_c <= N_r, so nothing overflows.  Rows of single-child OR nodes (and chain nodes)
+// keep the plain adjoint; their edges are the unweighted ones and pass it unchanged.
+__device__ __forceinline__ float encode_h(float g, float n) {
+    const bool none = g == 0.0f || n == -INFINITY;
+    const float h = none ? -INFINITY : flog(fabsf(g)) - n;
+    return __uint_as_float((__float_as_uint(h) & ~1u) | ((g < 0.0f && !none) ? 1u : 0u));
+}
+__device__ __forceinline__ float decode_h(float hbits, float nc) {
+    const uint32_t b = __float_as_uint(hbits);
+    const float v = fexp(__uint_as_float(b & ~1u) + nc);
+    return (b & 1u) ? -v : v;
+}
+
 template <int OP>
 __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc, bool weighted = true) {
+    if (OP == OP_SUM_H) { acc += x; return; }
+    if (OP == OP_SOFTMAX_H) { acc += weighted ? decode_h(x, nc) : x; return; }
+    if (OP == OP_PROD_BWD) {
+        const uint32_t bits = __float_as_uint(x);
+        const float val = __uint_as_float(bits & ~1u);
+        const bool one_zero = (bits & 1u) != 0;
+        const float part = one_zero ? (nc == 0.0f ? val : 0.0f) : (nc != 0.0f ? val / nc : 0.0f);
+        acc += weighted ? x : part;
+        return;
+    }
     if (OP == OP_SUM) acc += x;
     else if (OP == OP_PROD) acc *= x;
     else if (OP == OP_MAX) acc = fmaxf(acc, x);
@@ -160,6 +196,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
     // With one column per lane (B <= 64) a row is 256 bytes and twice as many have to be in flight:
     // 8 (4) measured 3% faster on the power-law workload at B = 64, 4% on the headline circuit at B = 64.
     constexpr int CH = (OP == OP_SOFTMAX_BWD) ? (VEC == 1 ? 4 : 2) : (VEC == 1 ? 8 : 4);
+    // the walk needs the output row's own value
+    constexpr bool OWN = OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = ((int)blockIdx.y * 64 + lane) * VEC;
@@ -213,7 +251,10 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
             if (OP == OP_SOFTMAX_BWD) {
                 // an unweighted edge needs no parent value: re-read the row just requested (an L1 hit)
                 load_vec<VEC>(y[i], ((ids[i] & kWeighted) && ids[i] != kSkip ? src2c : srcc) + off);
-                const int orow = rws[i] < last_row ? rws[i] : last_row;
+            }
+            if (OWN) {
+                // (segments of split rows have no value row of their own: they need none, any row will do)
+                const int orow = seg ? 0 : (rws[i] < last_row ? rws[i] : last_row);
                 load_vec<VEC>(z[i], ownc + (size_t)orow * (size_t)ld);
             }
         }
@@ -227,7 +268,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
         for (int i = 0; i < CH; ++i) {
             // branch-free accumulation: a dead entry contributes the identity
             const bool live = (i < n) && (ids[i] != kSkip);
-            if (OP == OP_SOFTMAX_BWD) {
+            if (OWN) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) nc[v] = (live && first[i]) ? z[i][v] : nc[v];
             }
@@ -236,13 +277,15 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                 const float dead = OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
                 const float xv = live ? x[i][v] : dead;
                 const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
-                accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], (ids[i] & kWeighted) != 0);
+                accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], live && (ids[i] & kWeighted) != 0);
             }
             if (live && (ids[i] & kLast)) {
                 float o[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     o[v] = finish<OP>(acc[v], mx[v]);
+                    // the adjoint of an OR node with more than one child leaves in the one-gather form
+                    if (OP == OP_SUM_H && !seg && (ids[i] & kRowFlag)) o[v] = encode_h(o[v], nc[v]);
                     acc[v] = identity<OP>();
                     mx[v] = -INFINITY;
                 }
@@ -273,7 +316,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
 // ---------------------------------------------------------------------------------------------
 template <int OP>
 __device__ __forceinline__ void edge_combine(float& am, float& as, float bm, float bs) {
-    if (OP == OP_SUM || OP == OP_SOFTMAX_BWD) am += bm;
+    if (OP == OP_SUM || OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H) am += bm;
     else if (OP == OP_PROD) am *= bm;
     else if (OP == OP_MAX) am = fmaxf(am, bm);
     else {
@@ -348,10 +391,10 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
             x[i] = src[off];
             y[i] = 0.0f;
             z[i] = 0.0f;
-            if (OP == OP_SOFTMAX_BWD) {
+            if (OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H) {
                 const bool weighted = live && (id[i] & kWeighted) != 0;
                 // value of the parent, and of the row the entry belongs to (a segment: of its owner)
-                y[i] = (weighted ? src2 : src)[off];
+                if (OP == OP_SOFTMAX_BWD) y[i] = (weighted ? src2 : src)[off];
                 int orow = live ? rowidx[i] : (seg ? n_main : 0);      // an entry past the task's end has no row
                 if (seg) orow = seg_owner[orow - n_main];
                 z[i] = own[(size_t)orow * (size_t)ld + cc];
@@ -366,6 +409,12 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
                 const bool weighted = live && (id[i] & kWeighted) != 0;
                 const float wgt = !weighted ? 1.0f : ((y[i] == -INFINITY) ? 0.0f : fexp(z[i] - y[i]));
                 vm = live ? x[i] * wgt : 0.0f;
+            } else if (OP == OP_SOFTMAX_H) {
+                vm = live ? ((id[i] & kWeighted) ? decode_h(x[i], z[i]) : x[i]) : 0.0f;
+            } else if (OP == OP_PROD_BWD) {
+                float part = 0.0f, unused = 0.0f;
+                accumulate<OP_PROD_BWD>(part, unused, x[i], 0.0f, z[i], (id[i] & kWeighted) != 0);
+                vm = live ? part : 0.0f;
             } else if (LSE) {
                 vm = live ? x[i] : -INFINITY;
                 vs = live ? 1.0f : 0.0f;
@@ -399,6 +448,7 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
             if (last && live && active) {
                 float o = vm;
                 if (LSE) o = (vm == -INFINITY) ? -INFINITY : vm + flog(vs);
+                if (OP == OP_SUM_H && !seg && (id[i] & kRowFlag)) o = encode_h(o, z[i]);
                 dst[(size_t)rowidx[i] * (size_t)ld + c] = o;
             }
             // the open row's part stays with the last lane group
@@ -420,6 +470,7 @@ template <int OP, int VEC, int W>
 __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
     constexpr int RPW = 64 / W;                       // rows per wave
     constexpr int CH = (OP == OP_SOFTMAX_BWD) ? 4 : 8;    // sources in flight per lane
+    constexpr bool OWN = OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H;
     const int lane = threadIdx.x & 63;
     int wave = threadIdx.x >> 6;
     if (W == 64) wave = __builtin_amdgcn_readfirstlane(wave);
@@ -439,8 +490,9 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
         float nc[VEC];                                // OP_SOFTMAX_BWD: own value
 #pragma unroll
         for (int v = 0; v < VEC; ++v) nc[v] = 0.0f;
-        if (OP == OP_SOFTMAX_BWD) {
-            const int owner = row < a.n_main ? row : a.seg_owner[row - a.n_main];
+        if (OWN) {
+            // the row whose value this output belongs to: itself, the row a combine pass writes, or a segment's owner
+            const int owner = row < a.n_main ? (a.out_row ? a.out_row[row] : row) : a.seg_owner[row - a.n_main];
             load_vec<VEC>(nc, a.own + (size_t)owner * a.ld + col);
         }
         float acc[VEC], mx[VEC];
@@ -475,13 +527,17 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
                     const float dead = OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
                     const float xv = live ? x[i][v] : dead;
                     const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
-                    accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], wt[i]);
+                    accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], live && wt[i]);
                 }
             }
         }
         float o[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) o[v] = finish<OP>(acc[v], mx[v]);
+        if (OP == OP_SUM_H && row < a.n_main && (a.idx[end - 1] & kRowFlag)) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) o[v] = encode_h(o[v], nc[v]);
+        }
         float* out;
         if (row < a.n_main) out = a.dst + (size_t)(a.out_row ? a.out_row[row] : row) * a.ld + col;
         else out = a.dst_seg + (size_t)(row - a.n_main) * a.ld + col;
@@ -816,7 +872,8 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
                                                                 const int32_t* __restrict__ top_ptr,
                                                                 const int32_t* __restrict__ top_root, int R,
                                                                 float* __restrict__ g_out, int B, int ld, int nmax,
-                                                                const float* __restrict__ tb, int T) {
+                                                                const float* __restrict__ tb, int T,
+                                                                const uint32_t* __restrict__ first_multi) {
     extern __shared__ float smem[];
     const size_t stride = (size_t)(nmax + 1) * CT;
     float* cur = smem;
@@ -867,11 +924,19 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
         __syncthreads();
         float* tmp = cur; cur = nxt; nxt = tmp;
     }
+    // first_multi (or null): the launch's lowest layer is an OR layer whose step follows as an ordinary
+    // launch in the one-gather form; bit r = node r has more than one child and leaves as encode_h
     const int n_first = layers[0].n;
-    for (int r = threadIdx.x; r < n_first; r += kSlabThreads)
+    for (int r = threadIdx.x; r < n_first; r += kSlabThreads) {
+        const bool enc = first_multi && ((first_multi[r >> 5] >> (r & 31)) & 1u);
 #pragma unroll
         for (int k = 0; k < CT; ++k)
-            if (k < nact) g_out[(size_t)r * ld + col0 + k] = cur[r * CT + k];
+            if (k < nact) {
+                float o = cur[r * CT + k];
+                if (enc) o = encode_h(o, tb0[(size_t)k * T + layers[0].tb_off + r]);
+                g_out[(size_t)r * ld + col0 + k] = o;
+            }
+    }
 }
 
 // rows[r, b] = tb[b, first + r] for r < n_rows: values that the persistent forward kernel left in the
@@ -895,19 +960,21 @@ __global__ __launch_bounds__(256) void tb_to_rows_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-// Reverse sweep of a product (AND) layer in the real semiring.  The adjoint of child j of parent r
-// is G[r] times the product of r's other children.  Per parent the kernel forms, per batch column,
-// the product q of the non-zero children and the number z of zero children, and writes per edge
-//   M[j] = G[r] * (x_j != 0 ? (z == 0 ? q / x_j : 0) : (z == 1 ? q : 0)),
-// which is exact also when children are zero (p = 0 or p = 1 leaves).  A by-child sum over M then
-// gives the adjoints of the layer below.  A lane group of W lanes owns one parent row.
+// Reverse sweep of a product (AND) layer in the real semiring, first half.  The adjoint of child c of
+// parent r is G[r] times the product of r's other children.  Per parent the kernel forms, per batch
+// column, the product q of the non-zero children and the number z of zero ones, and replaces the
+// parent's adjoint row in place by
+//   P[r] = G[r] * q  (0 when z >= 2),  lowest mantissa bit = (z == 1),
+// from which the by-child pass (OP_PROD_BWD) gives every child its share: P / value for a parent
+// without zero children, P itself for the one zero child of a parent with z = 1.  Exact also when
+// children are zero (leaves with p = 0 or p = 1); nothing is stored per edge.  A lane group of W lanes
+// owns one parent row.
 // ---------------------------------------------------------------------------------------------
 template <int VEC, int W>
-__global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restrict__ ptr,
-                                                        const int32_t* __restrict__ child,
-                                                        const float* __restrict__ below,
-                                                        const float* __restrict__ g, float* __restrict__ M, int n,
-                                                        int B, int ld) {
+__global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restrict__ ptr,
+                                                          const int32_t* __restrict__ child,
+                                                          const float* __restrict__ below, float* __restrict__ g, int n,
+                                                          int B, int ld) {
     constexpr int RPW = 64 / W;
     const int lane = threadIdx.x & 63;
     const int col = ((int)blockIdx.y * W + (lane % W)) * VEC;
@@ -922,8 +989,7 @@ __global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restric
     load_vec<VEC>(gr, g + (size_t)row * ld + col);
     constexpr int CH = 8;
     float x[CH][VEC];
-    // first pass: 8 gathers in flight (entries past the row's end re-read its last child), product of
-    // the non-zero children and count of the zero ones
+    // 8 gathers in flight (entries past the row's end re-read its last child)
     for (int j = beg; j < end; j += CH) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -941,30 +1007,13 @@ __global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restric
             }
         }
     }
-    // second pass: per-edge products; a row of at most 8 children still has them in registers
-    const bool short_row = end - beg <= CH;
-    for (int j = beg; j < end; j += CH) {
-        if (!short_row) {
+    float p[VEC];
 #pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                const int jj = j + i < end ? j + i : end - 1;
-                load_vec<VEC>(x[i], below + (size_t)child[jj] * ld + col);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            if (j + i < end) {
-                float m[VEC];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    const float xv = x[i][v];
-                    const float others = xv != 0.0f ? (z[v] == 0.0f ? q[v] / xv : 0.0f) : (z[v] == 1.0f ? q[v] : 0.0f);
-                    m[v] = gr[v] * others;
-                }
-                store_vec<VEC>(M + (size_t)(j + i) * ld + col, m);
-            }
-        }
+    for (int v = 0; v < VEC; ++v) {
+        const float val = z[v] >= 2.0f ? 0.0f : gr[v] * q[v];
+        p[v] = __uint_as_float((__float_as_uint(val) & ~1u) | (z[v] == 1.0f ? 1u : 0u));
     }
+    store_vec<VEC>(g + (size_t)row * ld + col, p);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1028,14 +1077,18 @@ __global__ void root_out_kernel(const float* __restrict__ top, const int32_t* __
 }
 
 // G_top[i, b] = sum of dout[b, r] over the root columns r that read top-layer node i
+// multi (or null) with the top layer's values: nodes flagged there leave in the one-gather form (encode_h)
 __global__ void seed_kernel(const float* __restrict__ dout, const int32_t* __restrict__ top_ptr,
                             const int32_t* __restrict__ top_root, int B, int R, int ld,
-                            float* __restrict__ g) {
+                            float* __restrict__ g, const uint32_t* __restrict__ multi,
+                            const float* __restrict__ top_values) {
     const int i = blockIdx.x;
+    const bool enc = multi && ((multi[i >> 5] >> (i & 31)) & 1u);
     for (int b = threadIdx.x; b < ld; b += blockDim.x) {
         float acc = 0.0f;
         if (b < B)
             for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)b * R + top_root[t]];
+        if (enc) acc = encode_h(acc, top_values[(size_t)i * ld + b]);
         g[(size_t)i * ld + b] = acc;
     }
 }

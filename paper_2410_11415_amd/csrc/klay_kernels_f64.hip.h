@@ -36,6 +36,14 @@ __device__ __forceinline__ double identity() { return OP == OP_PROD ? 1.0 : (OP 
 // same streaming forms as the fp32 accumulate: (mx, acc) = (running max, sum of exp(x - mx))
 template <int OP>
 __device__ __forceinline__ void accumulate(double& acc, double& mx, double x, double y, double nc, bool weighted) {
+    if (OP == OP_PROD_BWD) {       // as the fp32 form: x is an AND parent's P row (lowest bit: one zero child)
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(x);
+        const double val = __longlong_as_double((long long)(bits & ~1ull));
+        const bool one_zero = (bits & 1ull) != 0;
+        const double part = one_zero ? (nc == 0.0 ? val : 0.0) : (nc != 0.0 ? val / nc : 0.0);
+        acc += weighted ? x : part;
+        return;
+    }
     if (OP == OP_SUM) acc += x;
     else if (OP == OP_PROD) acc *= x;
     else if (OP == OP_MAX) acc = fmax(acc, x);
@@ -83,7 +91,7 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
     double nc[VEC], acc[VEC], mx[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { nc[v] = 0.0; acc[v] = identity<OP>(); mx[v] = -INFINITY; }
-    if (OP == OP_SOFTMAX_BWD) {
+    if (OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD) {
         const int owner = row < a.n_main ? row : a.seg_owner[row - a.n_main];
         load_vec<VEC>(nc, a.own + (size_t)owner * a.ld + col);
     }
@@ -170,12 +178,13 @@ __global__ void seed_rows_kernel(const double* __restrict__ dout, int B, int R, 
     for (int b = threadIdx.x; b < ld; b += blockDim.x) rows[(size_t)r * ld + b] = b < B ? dout[(size_t)b * R + r] : 0.0;
 }
 
-// Real-semiring reverse sweep of a product layer, per edge: M[j] = adjoint of the parent times the
-// product of its other children, formed from the product q of the non-zero children and the number
-// z of zero ones (exact when children are zero).  A wave per parent row, a lane per batch column.
-__global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ child,
-                                                        const double* __restrict__ below, const double* __restrict__ g,
-                                                        double* __restrict__ M, int n, int B, int ld) {
+// Real-semiring reverse sweep of a product layer, first half, as the fp32 kernel of the same name: the
+// adjoint row of every AND parent is replaced in place by P = G * (product of the non-zero children),
+// 0 with two or more zero children, lowest mantissa bit = exactly one zero child.  A wave per parent
+// row, a lane per batch column.
+__global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restrict__ ptr, const int32_t* __restrict__ child,
+                                                          const double* __restrict__ below, double* __restrict__ g,
+                                                          int n, int B, int ld) {
     const int lane = threadIdx.x & 63;
     const int col = (int)blockIdx.y * 64 + lane;
     if (col >= B) return;
@@ -183,7 +192,6 @@ __global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restric
     if (row64 >= n) return;
     const int row = (int)row64;
     const int beg = ptr[row], end = ptr[row + 1];
-    const double gr = g[(size_t)row * ld + col];
     double q = 1.0;
     int z = 0;
     for (int j = beg; j < end; ++j) {
@@ -191,11 +199,9 @@ __global__ __launch_bounds__(256) void prod_edge_kernel(const int32_t* __restric
         if (x == 0.0) ++z;
         else q *= x;
     }
-    for (int j = beg; j < end; ++j) {
-        const double x = below[(size_t)child[j] * ld + col];
-        const double others = x != 0.0 ? (z == 0 ? q / x : 0.0) : (z == 1 ? q : 0.0);
-        M[(size_t)j * ld + col] = gr * others;
-    }
+    const double val = z >= 2 ? 0.0 : g[(size_t)row * ld + col] * q;
+    const unsigned long long bits = ((unsigned long long)__double_as_longlong(val) & ~1ull) | (z == 1 ? 1ull : 0ull);
+    g[(size_t)row * ld + col] = __longlong_as_double((long long)bits);
 }
 
 // mode 0: negated weight 1 - w; mode 1: log(1 - exp(w)); mode 2: the negated literals have weights of their own

@@ -33,7 +33,8 @@ int32_t segment_len(int64_t k, const Options& opt) {
 }  // namespace
 
 void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out,
-                    const uint32_t* flags) {
+                    const uint32_t* flags, const uint32_t* row_bits) {
+    auto row_flag = [&](int64_t r) -> uint32_t { return row_bits && ((row_bits[(size_t)r >> 5] >> (r & 31)) & 1u) ? kRowFlag : 0u; };
     const int64_t e = ptr[n];
     out = PassPlan();
     if (flags)
@@ -65,7 +66,7 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
         int64_t k = ptr[r + 1] - ptr[r];
         if (k <= heavy) {
             for (int64_t j = ptr[r]; j < ptr[r + 1]; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j] | (flags ? flags[j] : 0u);
-            if (k > 0) out.idx[(size_t)w - 1] |= kLastEdge;
+            if (k > 0) out.idx[(size_t)w - 1] |= kLastEdge | row_flag(r);
         } else {
             out.idx[(size_t)w++] = kSkipRow;
         }
@@ -128,6 +129,8 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
         out.ptr[(size_t)n + sidx + 1] = w;
         out.comb_idx[(size_t)fill[(size_t)owner_slot[(size_t)sg.owner]]++] = (uint32_t)sidx;
     }
+    for (int64_t hh = 0; hh < n_heavy; ++hh)
+        out.comb_idx[(size_t)out.comb_ptr[(size_t)hh + 1] - 1] |= row_flag(out.comb_row[(size_t)hh]);
     out.n_seg_tasks = cut_tasks(n, n + n_seg, out.seg_tasks);
 }
 
@@ -413,7 +416,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     }
     plan.row0.assign((size_t)L + 2, 0);
     for (int32_t l = 0; l <= L; ++l) plan.row0[(size_t)l + 1] = plan.row0[(size_t)l] + count[(size_t)l];
-    if (plan.row0[(size_t)L + 1] + R >= (int64_t)1 << 30) { err = "klay_build: more than 2^30 rows"; return ST_INVAL; }
+    if (plan.row0[(size_t)L + 1] + R >= kMaxRows) { err = "klay_build: more than 2^29 rows"; return ST_INVAL; }
     // position of the stand-in of node c at `level` (h[c] <= level <= need[c]); in alias mode the
     // row of c itself in the whole activation buffer
     auto at = [&](int32_t c, int32_t level) -> int32_t {
@@ -587,6 +590,9 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             plan.max_fan_in = std::max<int64_t>(plan.max_fan_in, w - lay.row_ptr[(size_t)p]);
         }
         lay.row_ptr[(size_t)lay.n] = w;
+        lay.multi.assign((size_t)(lay.n + 31) / 32, 0u);
+        for (int64_t p = 0; p < lay.n; ++p)
+            if (lay.row_ptr[(size_t)p + 1] - lay.row_ptr[(size_t)p] > 1) lay.multi[(size_t)p >> 5] |= 1u << (p & 31);
         make_pass_plan(lay.n, lay.row_ptr.data(), lay.child.data(), popt, lay.fwd);
 
         plan.num_edges += e;
@@ -613,7 +619,10 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                     if ((l & 1) == 0 && lay.row_ptr[(size_t)p + 1] - lay.row_ptr[(size_t)p] > 1) cflag[(size_t)slot] = kWeightedEdge;
                 }
         }
-        make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd, cflag.data());
+        // the rows of this pass are the nodes of layer l - 1: below an AND layer they are OR nodes, and those
+        // with more than one child are flagged (their adjoints are stored in the one-gather form)
+        make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd, cflag.data(),
+                       (l & 1) && l >= 3 ? plan.layers[(size_t)l - 1].multi.data() : nullptr);
         if (!opt.no_tail && lay.n <= kTailRowsCap && nc <= kTailRowsCap) {
             int64_t fan_in = 0, fan_out = 0;
             for (int64_t i = 0; i < lay.n; ++i) fan_in = std::max<int64_t>(fan_in, lay.row_ptr[(size_t)i + 1] - lay.row_ptr[(size_t)i]);

@@ -48,11 +48,14 @@ struct SlabPlan {
 //   rows [0, n_main)                 write output row i; a split row holds the single entry kSkip
 //   rows [n_main, n_main + n_seg)    are segments of split rows, writing scratch row (i - n_main)
 //   combine: output row comb_row[h] reduces scratch rows comb_idx[comb_ptr[h] .. comb_ptr[h+1])
-// Index entries carry the source row in bits 0..29, "last edge of its row" in bit 31 and, in the
-// reverse sweep, "weighted edge" in bit 30 (the parent is an OR node with more than one child).
+// Index entries carry the source row in bits 0..28, "last edge of its row" in bit 31, in the
+// reverse sweep "weighted edge" in bit 30 (the parent is an OR node with more than one child), and on
+// the last entry of a row bit 29 may flag the output row itself (reverse sweep into an OR layer: the row
+// is an OR node with more than one child, whose adjoint is stored in the one-gather form).
 // tasks: runs of consecutive main rows with a bounded edge count, as (first row, first edge)
 // pairs with a closing (n_main, main edge count) pair: the unit of work of one wave.
-constexpr uint32_t kLastEdge = 0x80000000u, kWeightedEdge = 0x40000000u, kSkipRow = 0xFFFFFFFFu;
+constexpr uint32_t kLastEdge = 0x80000000u, kWeightedEdge = 0x40000000u, kRowFlag = 0x20000000u, kSkipRow = 0xFFFFFFFFu;
+constexpr int64_t kMaxRows = (int64_t)1 << 29;      // row ids fit the 29-bit source field
 constexpr int kIdxPad = 16;
 struct PassPlan {
     int32_t n_main = 0;
@@ -79,6 +82,8 @@ struct LayerPlan {
     std::vector<int32_t> child;      // [e]    S_l: position of the child in layer - 1
     std::vector<int32_t> origin;     // [n] input node id the row stands for
     std::vector<uint8_t> is_pad;     // [n] 1 for unary chain nodes
+    std::vector<uint32_t> multi;     // [(n + 31) / 32] bit i: row i has more than one child (OR layers: the rows
+                                     // whose edges carry a softmax weight in the reverse sweep)
     bool tail_fwd_ok = false;        // slab_fwd is built: the layer may run in the persistent forward kernel
     bool tail_bwd_ok = false;        // slab_bwd is built as well
     SlabPlan slab_fwd;               // rows = nodes of this layer, sources = positions in layer - 1
@@ -116,7 +121,9 @@ int layerize(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type, cons
 
 // Split a CSR (n rows, ptr[n+1], idx) into main rows, segments and combine rows.
 // `flags` (optional, one per edge) is OR-ed into the entries.
+// `row_bits` (optional, a bit per output row) puts kRowFlag on the last entry of the flagged rows (for a
+// split row: on the last entry of its combine list).
 void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out,
-                    const uint32_t* flags = nullptr);
+                    const uint32_t* flags = nullptr, const uint32_t* row_bits = nullptr);
 
 }  // namespace klay

@@ -16,7 +16,7 @@ using klay::PassPlan;
 using u64 = unsigned long long;
 
 static u64 mix(u64 x) { x += 0x9E3779B97F4A7C15ull; x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull; x = (x ^ (x >> 27)) * 0x94D049BB133111EBull; return x ^ (x >> 31); }
-static constexpr uint32_t kMask = 0x3FFFFFFFu;
+static constexpr uint32_t kMask = klay::kRowFlag - 1u;
 
 #define CHECK(cond, ...) do { if (!(cond)) { std::printf("FAILED %s:%d: ", __FILE__, __LINE__); std::printf(__VA_ARGS__); std::printf("\n"); std::exit(1); } } while (0)
 
@@ -69,8 +69,26 @@ static void walk_rows(const PassPlan& p, int row_begin, int row_end, int64_t n_s
 }
 
 // runs one plan both ways and compares with `want` (one value per output row)
-static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what) {
+static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what,
+                       const std::vector<uint32_t>* row_bits = nullptr) {
     CHECK(p.n_main == n_out, "%s: n_main", what);
+    // the row flag sits on the last entry of exactly the flagged rows (a split row: on the last entry of its
+    // combine list) and nowhere else
+    {
+        auto flagged = [&](int64_t r) { return row_bits && (((*row_bits)[(size_t)r >> 5] >> (r & 31)) & 1u); };
+        for (int64_t r = 0; r < (int64_t)p.n_main + p.n_seg; ++r)
+            for (int j = p.ptr[(size_t)r]; j < p.ptr[(size_t)r + 1]; ++j) {
+                const uint32_t id = p.idx[(size_t)j];
+                if (id == klay::kSkipRow) continue;
+                const bool expect = r < p.n_main && j == p.ptr[(size_t)r + 1] - 1 && flagged(r);
+                CHECK(((id & klay::kRowFlag) != 0) == expect, "%s: row flag of row %lld", what, (long long)r);
+            }
+        for (int h = 0; h < p.n_heavy; ++h)
+            for (int j = p.comb_ptr[(size_t)h]; j < p.comb_ptr[(size_t)h + 1]; ++j) {
+                const bool expect = j == p.comb_ptr[(size_t)h + 1] - 1 && flagged(p.comb_row[(size_t)h]);
+                CHECK(((p.comb_idx[(size_t)j] & klay::kRowFlag) != 0) == expect, "%s: row flag of split row %d", what, h);
+            }
+    }
     CHECK((int64_t)p.ptr.size() == (int64_t)p.n_main + p.n_seg + 1, "%s: ptr size", what);
     const int64_t entries = p.ptr.back();
     CHECK((int64_t)p.idx.size() == entries + klay::kIdxPad, "%s: idx size", what);
@@ -206,7 +224,9 @@ int main(int argc, char** argv) {
                         }
                     }
                     check_plan(lay.fwd, lay.n, nb, fwd, "forward plan"); ++plans;
-                    check_plan(lay.bwd, nb, lay.n, bwd, "backward plan"); ++plans;
+                    check_plan(lay.bwd, nb, lay.n, bwd, "backward plan", (l % 2 == 1 && l >= 3) ? &plan.layers[(size_t)l - 1].multi : nullptr); ++plans;
+                    for (int64_t r = 0; r < lay.n; ++r)
+                        CHECK(((lay.multi[(size_t)r >> 5] >> (r & 31)) & 1u) == (lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1 ? 1u : 0u), "multi-child bit");
                     CHECK(!lay.tail_bwd_ok || lay.tail_fwd_ok, "reverse persistent plan without the forward one");
                     if (lay.tail_fwd_ok) { check_slab(lay.slab_fwd, lay.n, nb, fwd, "persistent forward plan"); ++plans; }
                     if (lay.tail_bwd_ok) { check_slab(lay.slab_bwd, nb, lay.n, bwd, "persistent reverse plan"); ++plans; }
