@@ -58,24 +58,25 @@ def load_traffic(workload, batch, semiring, backward, alias):
 def kernel_symbol(cls, B, edges=False):
     """rocprofv3's name for the kernel behind a profiling class (template arguments as it prints them)."""
     vec = 4 if B > 128 else (2 if B > 64 else 1)
-    if B > 32:
-        ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4}
-        if cls in ops:
+    ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4, "bwd_prod": 5,
+           "bwd_sum_enc": 6, "bwd_softmax_one": 7}
+    if cls in ops:
+        if B > 32:
             return "klay::stream_kernel<%d, %d>" % (ops[cls], vec)
-    else:
         w = 1
         while w < B:
             w *= 2
-        ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4}
-        if cls in ops:
-            return ("klay::edge_kernel<%d, %d>" if edges else "klay::pass_kernel<%d, 1, %d>") % (ops[cls], w)
+        return ("klay::edge_kernel<%d, %d>" if edges else "klay::pass_kernel<%d, 1, %d>") % (ops[cls], w)
+    w_small = 1
+    while w_small < B:
+        w_small *= 2
     ct = 1
     while ct < 8 and (B + ct - 1) // ct > 256:
         ct *= 2
     fixed = {"tail_fwd": "klay::slab_fwd_kernel<%d>" % ct, "tail_bwd": "klay::slab_bwd_kernel<%d>" % ct,
              "leaf": "klay::leaf_fwd_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
              "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments and combine rows of split rows)",
-             "prod_edges": "klay::prod_edge_kernel<%d, %d>" % (vec, 64)}
+             "prod_edges": "klay::prod_parent_kernel<%d, %d>" % (vec, 64 if B > 32 else w_small)}
     return fixed.get(cls, cls)
 
 

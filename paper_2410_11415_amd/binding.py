@@ -20,7 +20,8 @@ KLAY_REAL, KLAY_LOG, KLAY_MAXLOG = 0, 1, 2
 KLAY_LIT, KLAY_AND, KLAY_OR, KLAY_TRUE, KLAY_FALSE = range(5)
 KLAY_STATIC_WORKSPACE_BYTES = 64 << 20
 KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf",
-                  "tail_fwd", "tail_bwd", "split", "prod_edges", "fwd_max")
+                  "tail_fwd", "tail_bwd", "split", "prod_edges", "fwd_max", "bwd_sum_enc", "bwd_softmax_one",
+                  "bwd_prod")
 
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
@@ -51,8 +52,8 @@ class klay_info_t(ctypes.Structure):
 
 
 class klay_profile_t(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_float * 14), ("launches", ctypes.c_int32 * 14), ("alg_bytes", ctypes.c_double * 14),
-                ("min_bytes", ctypes.c_double * 14)]
+    _fields_ = [("ms", ctypes.c_float * len(KERNEL_CLASSES)), ("launches", ctypes.c_int32 * len(KERNEL_CLASSES)),
+                ("alg_bytes", ctypes.c_double * len(KERNEL_CLASSES)), ("min_bytes", ctypes.c_double * len(KERNEL_CLASSES))]
 
 
 _lib = None

@@ -84,6 +84,7 @@ struct DevLayer {
     int64_t row0 = 0;        // first row of this layer in the activation buffer
     DevPass fwd, bwd;
     const uint32_t* multi = nullptr;   // OR layers: bit r = node r has more than one child
+    bool has_multi = false;
 };
 
 struct Geometry {            // how a batch of B columns is mapped onto lanes
@@ -124,6 +125,7 @@ struct klay_circuit {
     klay::CircuitPlan plan;
     int device = -1;
     bool small_batch_edges = false;      // klay_options.small_batch_edges
+    bool alias_one_gather = false;       // handles with aliased chains: the log reverse sweep may use the one-gather form
     std::vector<DevLayer> dl;
     DevPass top_bwd;                     // alias mode: adjoints of the top layer (from the dout rows)
     int32_t* d_index = nullptr;          // one allocation holding every index array
@@ -529,10 +531,22 @@ klay_status upload(klay_circuit* c) {
         if (l >= 1) {
             bind_pass(d.fwd, p.layers[(size_t)l].fwd, fo[(size_t)l], base);
             bind_pass(d.bwd, p.layers[(size_t)l].bwd, bo[(size_t)l], base);
-            if ((l & 1) == 0) d.multi = reinterpret_cast<const uint32_t*>(base + mo[(size_t)l]);
+            if ((l & 1) == 0) {
+                d.multi = reinterpret_cast<const uint32_t*>(base + mo[(size_t)l]);
+                for (uint32_t w : p.layers[(size_t)l].multi) d.has_multi = d.has_multi || w != 0;
+            }
         }
     }
-    if (p.alias) bind_pass(c->top_bwd, p.top_bwd, to, base);
+    if (p.alias) {
+        bind_pass(c->top_bwd, p.top_bwd, to, base);
+        // the one-gather form needs every layer to either store encoded rows or read weighted edges, not
+        // both: OR rows have AND parents only, so this holds for every circuit the layerizer accepts
+        c->alias_one_gather = true;
+        for (int l = 2; l <= L; l += 2) {
+            const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
+            if (c->dl[(size_t)l].has_multi && dp.has_weighted) c->alias_one_gather = false;
+        }
+    }
     c->d_pos_row = base + o_pos;
     c->d_neg_row = base + o_neg;
     c->d_root_pos = base + o_root;
@@ -1565,7 +1579,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
                 const DevLayer& d = c->dl[(size_t)l];
                 float* gl = X + (size_t)d.row0 * g.ld;
                 run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr,
-                             act + (size_t)d.row0 * g.ld, gl, seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
+                             act + (size_t)d.row0 * g.ld, gl, seg_rows, g, B, s, prof, KLAY_K_BWD_PROD);
                 if (l & 1) {
                     prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
                     launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, act, gl, g, B, s);
@@ -1598,7 +1612,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
                 prof.end();
                 // the by-child plan of an AND layer carries no weighted bit: every entry is a P row
                 run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, act + (size_t)below.row0 * g.ld, gnext,
-                             seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
+                             seg_rows, g, B, s, prof, KLAY_K_BWD_PROD);
             }
             std::swap(gcur, gnext);
         }
@@ -1624,8 +1638,17 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         for (int l = L; l >= 0; --l) {
             const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
             const DevLayer& d = c->dl[(size_t)l];
-            if (dp.has_weighted)
-                run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, act + (size_t)d.row0 * g.ld,
+            const float* own = act + (size_t)d.row0 * g.ld;
+            // one-gather form: the adjoint rows of OR nodes with more than one child (rows of even layers,
+            // whose parents are AND nodes or roots: plain sums) are stored encoded, and every weighted edge
+            // (rows of odd layers and leaves) decodes the one row it gathers
+            const bool enc = kOneGather && l >= 2 && (l & 1) == 0 && d.has_multi && !dp.has_weighted;
+            if (kOneGather && c->alias_one_gather && (enc || dp.has_weighted))
+                run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SOFTMAX_H, enc ? klay::OP_SUM_H : klay::OP_SUM, dp, G, nullptr,
+                             own, G + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof,
+                             enc ? KLAY_K_BWD_SUM_ENC : KLAY_K_BWD_SOFTMAX_ONE);
+            else if (dp.has_weighted)
+                run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, own,
                              G + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
             else
                 run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, G + (size_t)d.row0 * g.ld, seg_rows,
@@ -1646,7 +1669,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     // step that produces them (OP_SUM_H, the seed, or the persistent kernel's last write) folds the
     // node's own value in, and the step through the OR layer (OP_SOFTMAX_H) gathers that one row per
     // edge instead of the adjoint row and the parent's value row.
-    auto one_gather = [&](int l) { return kOneGather && l >= 2 && (l & 1) == 0 && c->dl[(size_t)l].bwd.has_weighted; };
+    auto one_gather = [&](int l) { return kOneGather && l >= 2 && (l & 1) == 0 && c->dl[(size_t)l].has_multi; };
 
     // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
     // which seeds the adjoints itself and leaves those of its first layer in gcur
@@ -1683,10 +1706,11 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (is_and) {
             const bool enc = one_gather(l - 1);
             run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SUM, enc ? klay::OP_SUM_H : klay::OP_SUM, d.bwd, gcur, nullptr,
-                         enc ? own_below : nullptr, gnext, seg_rows, g, B, s, prof, KLAY_K_BWD_SUM);
+                         enc ? own_below : nullptr, gnext, seg_rows, g, B, s, prof,
+                         enc ? KLAY_K_BWD_SUM_ENC : KLAY_K_BWD_SUM);
         } else if (kOneGather) {
             run_pass_set(klay::OP_SOFTMAX_H, klay::OP_SUM, d.bwd, gcur, nullptr, own_below, gnext, seg_rows, g, B, s,
-                         prof, KLAY_K_BWD_SOFTMAX);
+                         prof, KLAY_K_BWD_SOFTMAX_ONE);
         } else {
             run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld, own_below, gnext,
                          seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);

@@ -676,7 +676,9 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             std::vector<int32_t> lptr((size_t)n + 1);
             for (int64_t i = 0; i <= n; ++i) lptr[(size_t)i] = gptr[(size_t)(a + i)] - gptr[(size_t)a];
             PassPlan& dst = l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd;
-            make_pass_plan(n, lptr.data(), gsrc.data() + gptr[(size_t)a], popt, dst, gflag.data() + gptr[(size_t)a]);
+            // rows that are OR nodes with more than one child are flagged, as in the layer-by-layer plans
+            make_pass_plan(n, lptr.data(), gsrc.data() + gptr[(size_t)a], popt, dst, gflag.data() + gptr[(size_t)a],
+                           (l & 1) == 0 && l >= 2 ? plan.layers[(size_t)l].multi.data() : nullptr);
             plan.num_split_rows += dst.n_heavy;
             plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, dst.n_seg);
         }

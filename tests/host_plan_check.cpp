@@ -254,7 +254,8 @@ int main(int argc, char** argv) {
                 for (int l = 0; l <= L; ++l) {
                     const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;
                     std::vector<u64> want(adj.begin() + a, adj.begin() + a + n);
-                    check_plan(l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd, n, NR + R, want, "alias backward plan"); ++plans;
+                    check_plan(l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd, n, NR + R, want, "alias backward plan",
+                               (l % 2 == 0 && l >= 2) ? &plan.layers[(size_t)l].multi : nullptr); ++plans;
                 }
             }
         }

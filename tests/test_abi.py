@@ -26,8 +26,16 @@ def test_every_declared_symbol_is_exported():
 def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.klay_options) == 32
     assert ctypes.sizeof(binding.klay_info_t) == 16 + 12 * 8
-    assert ctypes.sizeof(binding.klay_profile_t) == 14 * 4 + 14 * 4 + 14 * 8 + 14 * 8
-    assert len(binding.KERNEL_CLASSES) == 14
+    # the profile arrays have one slot per kernel class of the header's enum
+    with open(os.path.join(ROOT, "include", "klay.h")) as fh:
+        header = fh.read()
+    enum = re.search(r"enum\s*\{\s*(KLAY_K_LEAF[^}]*)\}", header).group(1)
+    classes = [t.split("=")[0].strip() for t in enum.split(",") if t.strip()]
+    assert classes[-1] == "KLAY_K_COUNT"
+    k = len(classes) - 1
+    assert len(binding.KERNEL_CLASSES) == k == 17
+    assert [c[len("KLAY_K_"):].lower() for c in classes[:-1]] == list(binding.KERNEL_CLASSES)
+    assert ctypes.sizeof(binding.klay_profile_t) == k * 4 + k * 4 + k * 8 + k * 8
 
 
 def test_last_error_is_a_string():

@@ -368,9 +368,17 @@ def test_profile_reports_kernel_classes(klay):
     gpu_eval(k, as_inputs(p, True), LOG, np.ones((64, c.roots.shape[0]), np.float32))
     prof = k.get_profile()
     assert prof["fwd_lse"]["launches"] >= 10 and prof["fwd_lse"]["ms"] > 0
-    assert prof["bwd_softmax"]["launches"] >= 10 and prof["bwd_softmax"]["alg_bytes"] > 0
+    assert prof["bwd_softmax_one"]["launches"] >= 10 and prof["bwd_softmax_one"]["alg_bytes"] > 0
+    assert prof["bwd_sum_enc"]["launches"] >= 9 and prof["bwd_softmax"]["launches"] == 0
     k.set_profiling(False)
     k.close()
+    ka = build(klay, c, no_tail=True, alias_chains=True)
+    ka.set_profiling(True)
+    gpu_eval(ka, as_inputs(p, True), LOG, np.ones((64, c.roots.shape[0]), np.float32))
+    prof = ka.get_profile()
+    assert prof["bwd_softmax_one"]["launches"] >= 10 and prof["bwd_sum_enc"]["launches"] >= 9
+    assert prof["bwd_softmax"]["launches"] == 0
+    ka.close()
 
 
 @pytest.mark.parametrize("B", [1, 3, 8, 37, 256, 300, 700, 1100, 2100])
