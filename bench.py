@@ -41,7 +41,7 @@ def source_fingerprint() -> str:
     return h.hexdigest()[:16]
 
 
-def load_traffic(workload, batch, semiring, backward, alias):
+def load_traffic(workload, batch, semiring, backward, chains):
     """HBM bytes per dispatch and per step from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs that
     bench_traffic.py folded into bench_traffic.json; None unless measured on these very sources."""
     try:
@@ -51,7 +51,7 @@ def load_traffic(workload, batch, semiring, backward, alias):
         return None
     if table.get("fingerprint") != source_fingerprint():
         return None
-    key = "%s|B=%d|%s|%s|%s" % (workload, batch, semiring, "fwd+bwd" if backward else "fwd", "alias" if alias else "chains")
+    key = "%s|B=%d|%s|%s|%s" % (workload, batch, semiring, "fwd+bwd" if backward else "fwd", "chains" if chains else "default")
     return table.get("runs", {}).get(key)
 
 
@@ -121,8 +121,9 @@ def main():
     ap.add_argument("--no-tail", action="store_true", help="one launch per layer also for the narrow top layers")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph (torch.cuda.graph) and time its replays")
-    ap.add_argument("--alias-chains", action="store_true",
-                    help="padding-free evaluation: no unary chain nodes, edges read the child's own row")
+    ap.add_argument("--unary-chains", action="store_true",
+                    help="the paper's layerization throughout (one unary chain node per node and layer an edge skips) "
+                         "instead of the default, which is padding-free below the narrow top of the circuit")
     ap.add_argument("--small-batch-edges", action="store_true",
                     help="B <= 32: the lanes = edges kernel instead of a lane group per row (for comparison)")
     ap.add_argument("--f64", action="store_true",
@@ -181,7 +182,7 @@ def main():
     w32 = as_inputs(p, semiring != pkg.KLAY_REAL)
 
     t0 = time.perf_counter()
-    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, alias_chains=args.alias_chains,
+    k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, unary_chains=args.unary_chains,
                     small_batch_edges=args.small_batch_edges)
     t_build = time.perf_counter() - t0
     info = k.info()
@@ -269,7 +270,7 @@ def main():
     min_bytes_step = sum(c["min_bytes"] for c in classes.values()) / prof_steps
     measured = None
     if not args.no_tail and not args.graph and not args.small_batch_edges:
-        measured = load_traffic(args.workload, B, semiring_name, backward, bool(args.alias_chains))
+        measured = load_traffic(args.workload, B, semiring_name, backward, bool(args.unary_chains))
     per_launch_s = d["ms"] * 1e-3 / max(1, d["launches"])
     traffic = None
     if measured and dom in measured["per_kernel"]:
@@ -380,8 +381,10 @@ def main():
         "config": {"workload": args.workload, "batch": B, "semiring": semiring_name,
                    "pass": "forward+backward" if backward else "forward", "seed": args.seed,
                    "launch": "hip graph replay" if args.graph else "eager",
-                   "layerization": "alias_chains (no unary chain nodes)" if args.alias_chains else
-                                   "unary chain nodes per (node, layer)",
+                   "layerization": "unary chain nodes per (node, layer) throughout" if args.unary_chains else
+                                   "padding-free up to layer %d of %d, unary chain nodes above" % (
+                                       info["alias_top_layer"], info["num_layers"]),
+                   "padding_free_layers": info["alias_top_layer"],
                    "layers": info["num_layers"], "layered_nodes": N, "layered_edges": E,
                    "dag_nodes": info["dag_nodes"], "dag_edges": info["dag_edges"],
                    "pad_nodes": info["num_pad_nodes"], "num_vars": info["num_vars"], "num_roots": info["num_roots"],

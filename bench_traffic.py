@@ -37,7 +37,7 @@ PROBE_MIB = 1024
 # tag -> extra bench.py arguments (the workload's own batch, semiring and pass unless overridden)
 RUNS = collections.OrderedDict([
     ("layered_3m_fwd_bwd", []),
-    ("layered_3m_fwd_bwd_alias", ["--alias-chains"]),
+    ("layered_3m_fwd_bwd_chains", ["--unary-chains"]),
     ("layered_1m_log", ["--workload", "layered_1m"]),
     ("layered_1m_real", ["--workload", "layered_1m", "--semiring", "real"]),
     ("layered_1m_real_fwd_bwd", ["--workload", "layered_1m", "--semiring", "real", "--backward", "on"]),
@@ -122,9 +122,9 @@ def fold():
             print("fold: %s was measured on other sources (%s), left out" % (tag, cfg["sources_fingerprint"]))
             continue
         backward = cfg["pass"] == "forward+backward"
-        alias = cfg["layerization"].startswith("alias")
+        chains = cfg["layerization"].startswith("unary")
         key = "%s|B=%d|%s|%s|%s" % (cfg["workload"], cfg["batch"], cfg["semiring"], "fwd+bwd" if backward else "fwd",
-                                    "alias" if alias else "chains")
+                                    "chains" if chains else "default")
         # kernel trace
         stats = {}
         for r in csv.DictReader(open(os.path.join(d, "kt", "kt_kernel_stats.csv"))):
@@ -205,7 +205,7 @@ def fold():
                 "Dominant kernel by time: %s, %.2f us average under the tracer; bench.py's HIP events give %s %.2f us." % (
                     dom.replace("klay::", ""), stats[dom][2] / 1e3, roof["kernel"].replace("klay::", ""), roof["kernel_avg_launch_us"]),
                 ""]
-        name = "%s_b%d_%s_%s%s.md" % (cfg["workload"], cfg["batch"], cfg["semiring"], "fwd_bwd" if backward else "fwd", "_alias" if alias else "")
+        name = "%s_b%d_%s_%s%s.md" % (cfg["workload"], cfg["batch"], cfg["semiring"], "fwd_bwd" if backward else "fwd", "_chains" if chains else "")
         with open(os.path.join(ROOT, "profiles", name), "w") as fh:
             fh.write("\n".join(out))
         print("fold:", key, "->", "profiles/" + name, "step %.3f GB" % (step_bytes / 1e9))

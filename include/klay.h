@@ -52,15 +52,24 @@ typedef struct klay_options {
     int32_t heavy_fan;       /* rows with more sources than this are split (default 48)           */
     int32_t min_segment;     /* smallest split segment, in edges (default 24)                     */
     int32_t no_tail;         /* 1: one launch per layer also for the narrow top layers            */
-    int32_t alias_chains;    /* 1: insert no unary chain nodes; an edge that skips layers reads the
-                                child's own row (same values, fewer rows and edges; klay_layer_csr
-                                then returns rows of the whole activation buffer, layer 0 first)    */
+    int32_t unary_chains;    /* 1: the paper's layerization throughout: an edge that skips layers goes through
+                                one unary chain node per layer (Section 3.1).  Default (0): padding-free
+                                below the narrow top of the circuit.  Chain nodes only copy a value, so in
+                                the layers 1 .. A (A = klay_info_t.alias_top_layer) none are made and an edge
+                                reads the child's own row wherever it lives; layer A is complete (it holds
+                                a stand-in for every node read from above), and the layers above it, the
+                                ones the persistent kernels may take, are as in the paper.  Same values
+                                and gradients, fewer rows and edges.  klay_layer_csr returns, for the layers
+                                up to A, rows of the whole activation buffer (layer 0 first).  A = 0 when
+                                the whole circuit is narrow, A = L when no layer is (or with no_tail)   */
     int32_t no_merge;        /* 1: do not identify structurally identical gates (Section 3.2)         */
     int32_t small_batch_edges; /* 1: batches of at most 32 columns run the lanes = edges kernel (a wave takes
                                 64 / B index entries per step and reduces the entries of a row across its
                                 lanes with a segmented scan) instead of the default, a lane group per row,
                                 which measures about twice as fast at B = 1 and B = 4; same results        */
-    int32_t reserved[1];
+    int32_t tail_rows_cap;   /* > 0: layers with more nodes than this are no candidates for the persistent
+                                kernels (at most 20000, the default; smaller values move the boundary
+                                between the two parts of the layerization up: for tests)                 */
 } klay_options;
 
 typedef struct klay_info_t {
@@ -81,6 +90,7 @@ typedef struct klay_info_t {
     int64_t tail_first_layer; /* first layer that may run in the persistent top-of-circuit kernel
                                  (0: none); the layers actually taken depend on the batch size       */
     int64_t num_merged_nodes; /* input gates identified with a structurally identical gate          */
+    int64_t alias_top_layer;  /* A: the layers 1 .. A are padding-free (see klay_options.unary_chains)  */
 } klay_info_t;
 
 /* Per-kernel-class timing of the most recent forward / backward call, filled only while
@@ -89,9 +99,10 @@ typedef struct klay_info_t {
  * the streaming kernel for B > 32), SPLIT the segment and combine launches of split rows,
  * PROD_EDGES the per-parent pass of the real-semiring reverse sweep over a product layer (adjoint
  * times the product of the non-zero children, in place), BWD_PROD the by-child pass that follows
- * it.  Log-semiring reverse sweep: BWD_SOFTMAX is the two-gather step through an OR layer (handles
- * with aliased chains), BWD_SOFTMAX_ONE the one-gather step, BWD_SUM_ENC the step through an AND
- * layer that leaves the adjoints of the OR layer below in the one-gather form. */
+ * it.  Log-semiring reverse sweep: BWD_SOFTMAX_ONE is the step through an OR layer that gathers one
+ * row per edge, BWD_SUM_ENC the step through an AND layer that leaves the adjoints of the OR layer
+ * below in the form that step reads; BWD_SOFTMAX, the two-gather step, only runs where that form
+ * cannot be used. */
 enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
        KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_FWD_MAX, KLAY_K_BWD_SUM_ENC,
@@ -234,6 +245,8 @@ klay_status klay_layer_sizes(const klay_circuit* c, int64_t* nodes, int64_t* edg
  * Host copy of layer l's index vectors (Section 4 / Alg. 3), 1 <= l <= L, in CSR form:
  * row_ptr [n_l + 1], child [e_l].  child is the paper's S_l (position in layer l-1); the paper's
  * R_l is row_ptr expanded (edge j belongs to parent r iff row_ptr[r] <= j < row_ptr[r+1]).
+ * For l <= klay_info_t.alias_top_layer child holds rows of the whole activation buffer instead
+ * (the rows of layer 0, then those of layer 1, ...), always of a layer below l.
  */
 klay_status klay_layer_csr(const klay_circuit* c, int32_t layer, int64_t* row_ptr, int32_t* child);
 
@@ -246,8 +259,7 @@ klay_status klay_layer_nodes(const klay_circuit* c, int32_t layer, int32_t* orig
 
 /*
  * position[r] (host array of num_roots entries) = row of the top layer L that holds roots[r]'s value
- * (Section 3.2: all roots sit in the last layer); with alias_chains the row of the whole activation
- * buffer, as for klay_layer_csr.
+ * (Section 3.2: all roots sit in the last layer, a root of lower height through a stand-in).
  */
 klay_status klay_root_positions(const klay_circuit* c, int32_t* position);
 

@@ -110,7 +110,7 @@ Geometry geometry(int B) {
 size_t align_floats(size_t n) { return (n + 63) / 64 * 64; }
 
 struct Workspace {
-    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, tb = 0, total = 0;   // offsets in floats
+    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, g2 = 0, tb = 0, total = 0;   // offsets in floats
 };
 
 struct EventRec {
@@ -125,9 +125,8 @@ struct klay_circuit {
     klay::CircuitPlan plan;
     int device = -1;
     bool small_batch_edges = false;      // klay_options.small_batch_edges
-    bool alias_one_gather = false;       // handles with aliased chains: the log reverse sweep may use the one-gather form
+    bool one_gather = false;             // the log reverse sweep may use the one-gather form (see upload)
     std::vector<DevLayer> dl;
-    DevPass top_bwd;                     // alias mode: adjoints of the top layer (from the dout rows)
     int32_t* d_index = nullptr;          // one allocation holding every index array
     size_t index_bytes = 0;
     const int32_t *d_pos_row = nullptr, *d_neg_row = nullptr, *d_root_pos = nullptr, *d_top_ptr = nullptr,
@@ -139,8 +138,8 @@ struct klay_circuit {
     int64_t tail_rows = 0;                     // T: rows of all tail candidate layers (one column of the tail buffer)
     int32_t last_tail_first = 0;               // first layer the last forward ran in the persistent kernel (0: none)
     // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
-    // vectors (for prod_parent_kernel); on an alias_chains handle also, per layer, the by-child pass over
-    // the parents in all higher layers whose entries tell AND parents from plain adjoint rows
+    // vectors (for prod_parent_kernel); for the layers below alias_top also the by-child pass over the
+    // parents in all higher layers up to alias_top, whose entries tell AND parents from plain adjoint rows
     struct RealLayer { const int32_t* ptr = nullptr; const int32_t* child = nullptr; DevPass by_child; };
     std::vector<RealLayer> real_layers;
     int32_t* d_real_index = nullptr;
@@ -169,6 +168,14 @@ struct klay_circuit {
 
 namespace {
 
+// widest layer above the padding-free part (1 if there is none): the size of the two adjoint buffers
+// that the layer-by-layer part of the reverse sweep alternates between
+int64_t top_layer_rows(const klay::CircuitPlan& p) {
+    int64_t n = 1;
+    for (int l = p.alias_top + 1; l <= p.num_layers; ++l) n = std::max(n, p.layers[(size_t)l].n);
+    return n;
+}
+
 Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     const Geometry g = geometry(B);
     const klay::CircuitPlan& p = c->plan;
@@ -180,13 +187,12 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     w.seg_rows = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
     // values of the tail layers, one run of tail_rows floats per batch column
     w.tb = off; off += align_floats((size_t)c->tail_rows * (size_t)B);
-    if (need_bwd && p.alias) {
-        // adjoints of every row plus one row per root column for the transposed dout
-        w.g0 = off; off += align_floats((size_t)(p.num_nodes + p.num_roots) * g.ld);
-        w.g1 = w.g0;
-    } else if (need_bwd) {
-        w.g0 = off; off += align_floats((size_t)p.max_layer_nodes * g.ld);
-        w.g1 = off; off += align_floats((size_t)p.max_layer_nodes * g.ld);
+    if (need_bwd) {
+        // adjoints: one row per node of the layers 0 .. alias_top, and two buffers of the widest layer above
+        // them that the layer-by-layer part of the sweep alternates between
+        w.g0 = off; off += align_floats((size_t)p.row0[(size_t)p.alias_top + 1] * g.ld);
+        w.g1 = off; off += align_floats((size_t)top_layer_rows(p) * g.ld);
+        w.g2 = off; off += align_floats((size_t)top_layer_rows(p) * g.ld);
     }
     w.total = off;
     return w;
@@ -503,8 +509,6 @@ klay_status upload(klay_circuit* c) {
     }
     std::vector<size_t> mo((size_t)L + 1, 0);
     for (int l = 2; l <= L; l += 2) mo[(size_t)l] = pk.add(p.layers[(size_t)l].multi);
-    PassOffsets to{};
-    if (p.alias) to = pack_pass(pk, p.top_bwd);
     const size_t o_pos = pk.add(p.pos_row), o_neg = pk.add(p.neg_row), o_root = pk.add(p.root_pos);
     const size_t o_tptr = pk.add(p.top_ptr), o_troot = pk.add(p.top_root);
 
@@ -537,16 +541,11 @@ klay_status upload(klay_circuit* c) {
             }
         }
     }
-    if (p.alias) {
-        bind_pass(c->top_bwd, p.top_bwd, to, base);
-        // the one-gather form needs every layer to either store encoded rows or read weighted edges, not
-        // both: OR rows have AND parents only, so this holds for every circuit the layerizer accepts
-        c->alias_one_gather = true;
-        for (int l = 2; l <= L; l += 2) {
-            const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
-            if (c->dl[(size_t)l].has_multi && dp.has_weighted) c->alias_one_gather = false;
-        }
-    }
+    // The one-gather form needs every layer below alias_top to either store encoded rows or read weighted
+    // edges, not both: OR rows have AND parents only, so this holds for every circuit the layerizer accepts.
+    c->one_gather = true;
+    for (int l = 2; l < p.alias_top; l += 2)
+        if (c->dl[(size_t)l].has_multi && c->dl[(size_t)l + 1].bwd.has_weighted) c->one_gather = false;
     c->d_pos_row = base + o_pos;
     c->d_neg_row = base + o_neg;
     c->d_root_pos = base + o_root;
@@ -828,22 +827,21 @@ klay_status ensure_real_bwd(klay_circuit* c) {
         offs[(size_t)l].ptr = pk.add(p.layers[(size_t)l].row_ptr);
         offs[(size_t)l].child = pk.add(p.layers[(size_t)l].child);
     }
-    if (p.alias) {
-        // Every row of the activation buffer gathers from its parents in any higher layer and, a root,
-        // from its dout row.  An AND parent's row holds P (see prod_parent_kernel); a sum node's row and a
-        // dout row hold plain adjoints: those entries carry the weighted bit, which OP_PROD_BWD reads as
-        // "add as it is".
-        const int64_t NR = p.row0[(size_t)L + 1], R = p.num_roots;
+    const int B0 = p.alias_top;
+    if (B0 > 0) {
+        // Every row below layer B0 gathers from its parents in any higher layer up to B0.  An AND parent's
+        // row holds P (see prod_parent_kernel); a sum node's row holds plain adjoints: those entries carry
+        // the weighted bit, which OP_PROD_BWD reads as "add as it is".
+        const int64_t NR = p.row0[(size_t)B0];
         std::vector<int32_t> gptr((size_t)NR + 1, 0);
-        for (int l = 1; l <= L; ++l)
+        for (int l = 1; l <= B0; ++l)
             for (int32_t ch : p.layers[(size_t)l].child) ++gptr[(size_t)ch + 1];
-        for (int32_t r = 0; r < R; ++r) ++gptr[(size_t)p.root_pos[(size_t)r] + 1];
         for (int64_t i = 0; i < NR; ++i) gptr[(size_t)i + 1] += gptr[(size_t)i];
         std::vector<int32_t> gsrc((size_t)gptr[(size_t)NR]);
         std::vector<uint32_t> gflag((size_t)gptr[(size_t)NR], 0u);
         {
             std::vector<int32_t> fill(gptr.begin(), gptr.end() - 1);
-            for (int l = 1; l <= L; ++l) {
+            for (int l = 1; l <= B0; ++l) {
                 const klay::LayerPlan& lay = p.layers[(size_t)l];
                 for (int64_t r = 0; r < lay.n; ++r)
                     for (int32_t j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
@@ -852,13 +850,8 @@ klay_status ensure_real_bwd(klay_circuit* c) {
                         if ((l & 1) == 0) gflag[(size_t)slot] = klay::kWeightedEdge;
                     }
             }
-            for (int32_t r = 0; r < R; ++r) {
-                const int32_t slot = fill[(size_t)p.root_pos[(size_t)r]]++;
-                gsrc[(size_t)slot] = (int32_t)(NR + r);
-                gflag[(size_t)slot] = klay::kWeightedEdge;
-            }
         }
-        for (int l = 0; l <= L; ++l) {
+        for (int l = 0; l < B0; ++l) {
             const klay::LayerPlan& lay = p.layers[(size_t)l];
             Off& o = offs[(size_t)l];
             const int64_t a = p.row0[(size_t)l];
@@ -888,7 +881,7 @@ klay_status ensure_real_bwd(klay_circuit* c) {
             r.ptr = c->d_real_index + offs[(size_t)l].ptr;
             r.child = c->d_real_index + offs[(size_t)l].child;
         }
-        if (p.alias) bind_pass(r.by_child, offs[(size_t)l].plan, offs[(size_t)l].pass, c->d_real_index);
+        if (l < B0) bind_pass(r.by_child, offs[(size_t)l].plan, offs[(size_t)l].pass, c->d_real_index);
     }
     return KLAY_OK;
 }
@@ -921,7 +914,7 @@ void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* be
 
 // ---- double-precision evaluation ---------------------------------------------------------------
 struct Workspace64 {
-    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, total = 0;   // offsets in doubles
+    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, g2 = 0, total = 0;   // offsets in doubles
 };
 
 Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
@@ -932,13 +925,10 @@ Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
     w.act = take((size_t)p.num_nodes * ld);
     w.wT = take((size_t)std::max(1, p.num_vars) * ld);
     w.seg_rows = take((size_t)std::max<int64_t>(std::max(p.max_fwd_seg, p.max_bwd_seg), 1) * ld);
-    if (p.alias) {
-        w.g0 = take((size_t)(p.num_nodes + p.num_roots) * ld);
-        w.g1 = w.g0;
-    } else {
-        w.g0 = take((size_t)p.max_layer_nodes * ld);
-        w.g1 = take((size_t)p.max_layer_nodes * ld);
-    }
+    // adjoints: one row per node of the layers 0 .. alias_top, two rows sets for the layers above
+    w.g0 = take((size_t)p.row0[(size_t)p.alias_top + 1] * ld);
+    w.g1 = take((size_t)top_layer_rows(p) * ld);
+    w.g2 = take((size_t)top_layer_rows(p) * ld);
     w.total = off;
     return w;
 }
@@ -1042,12 +1032,12 @@ klay_status forward64_impl(klay_circuit* c, const double* w, const double* wneg,
         const bool is_and = (l & 1) != 0;
         const int or_op = semiring == KLAY_MAXLOG ? klay::OP_MAX : klay::OP_LSE;
         const int op = log_domain ? (is_and ? klay::OP_SUM : or_op) : (is_and ? klay::OP_PROD : klay::OP_SUM);
-        const double* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * ld;
+        // up to alias_top child entries are rows of the whole buffer, above it of the layer below
+        const double* below = l <= p.alias_top ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * ld;
         run_pass_set64(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * ld, seg_rows, B, ld, s);
     }
     hipLaunchKernelGGL(klay::f64::root_out_kernel, dim3((unsigned)p.num_roots), dim3(256), 0, s,
-                       p.alias ? act : act + (size_t)c->dl[(size_t)L].row0 * ld, c->d_root_pos, (int)B, p.num_roots, ld,
-                       out);
+                       act + (size_t)c->dl[(size_t)L].row0 * ld, c->d_root_pos, (int)B, p.num_roots, ld, out);
     KLAY_HIP(hipGetLastError());
     c->have_fwd64 = true;
     c->last64_B = B;
@@ -1074,91 +1064,70 @@ klay_status backward64_impl(klay_circuit* c, const double* dout, double* dleaf, 
     double* act = ws + lay.act;
     double* wT = ws + lay.wT;
     double* seg_rows = ws + lay.seg_rows;
-    double* gcur = ws + lay.g0;
-    double* gnext = ws + lay.g1;
-    const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
+    double* G = ws + lay.g0;
+    double* gcur = ws + lay.g1;
+    double* gnext = ws + lay.g2;
+    const int L = p.num_layers, V = p.num_vars, R = p.num_roots, B0 = p.alias_top;
     const int leaf_mode = c->last64_neg_explicit ? 2 : (real ? 0 : 1);
     const dim3 leaf_grid((unsigned)std::max(V, 1), (unsigned)((B + 255) / 256));
+    auto grow = [&](int l) { return G + (size_t)c->dl[(size_t)l].row0 * ld; };   // adjoint rows of a layer <= B0
+    // Same course as the fp32 sweep (see klay_backward's implementation): the layers above B0 one by one,
+    // alternating between two buffers, the last of these steps writing the rows of layer B0 into G; then
+    // the rows of the layers below B0, each gathering from its parents anywhere in G.
     if (real) {
-        // as the fp32 real-semiring sweep: sum layers pass adjoints through; the adjoint rows of a product
-        // layer become P rows in place and the by-child pass OP_PROD_BWD shares them out (index arrays
-        // shared with the fp32 path)
         klay_status rs = ensure_real_bwd(c);
         if (rs != KLAY_OK) return rs;
         const dim3 pp_block(256);
-        if (p.alias) {
-            double* X = gcur;
-            hipLaunchKernelGGL(klay::f64::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, ld,
-                               X + (size_t)p.num_nodes * ld);
-            for (int l = L; l >= 0; --l) {
-                const DevLayer& d = c->dl[(size_t)l];
-                double* gl = X + (size_t)d.row0 * ld;
-                run_pass_set64(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr,
-                               act + (size_t)d.row0 * ld, gl, seg_rows, B, ld, s);
-                if ((l & 1) && d.n > 0) {
-                    const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
-                    hipLaunchKernelGGL(klay::f64::prod_parent_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
-                                       pp_block, 0, s, r.ptr, r.child, act, gl, (int)d.n, B, ld);
-                }
-            }
-            if (V > 0)
-                hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, X, wT, c->d_pos_row, c->d_neg_row, B,
-                                   V, ld, leaf_mode, dleaf, dneg);
-            KLAY_HIP(hipGetLastError());
-            return KLAY_OK;
-        }
+        auto prod_parent = [&](int l, const double* below, double* gl) {
+            const DevLayer& d = c->dl[(size_t)l];
+            if (d.n <= 0) return;
+            const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
+            hipLaunchKernelGGL(klay::f64::prod_parent_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
+                               pp_block, 0, s, r.ptr, r.child, below, gl, (int)d.n, B, ld);
+        };
         hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
-                           c->d_top_root, B, R, ld, gcur);
-        for (int l = L; l >= 1; --l) {
+                           c->d_top_root, B, R, ld, L == B0 ? grow(L) : gcur);
+        for (int l = L; l > B0; --l) {
             const DevLayer& d = c->dl[(size_t)l];
             const DevLayer& below = c->dl[(size_t)l - 1];
+            double* dst = l - 1 == B0 ? grow(B0) : gnext;
             if ((l & 1) == 0) {
-                run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, B, ld, s);
+                run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, dst, seg_rows, B, ld, s);
             } else {
-                const klay_circuit::RealLayer& r = c->real_layers[(size_t)l];
-                hipLaunchKernelGGL(klay::f64::prod_parent_kernel, dim3((unsigned)((d.n + 3) / 4), (unsigned)((B + 63) / 64)),
-                                   pp_block, 0, s, r.ptr, r.child, act + (size_t)below.row0 * ld, gcur, (int)d.n, B, ld);
-                run_pass_set64(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, act + (size_t)below.row0 * ld, gnext,
+                prod_parent(l, act + (size_t)below.row0 * ld, gcur);
+                run_pass_set64(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, act + (size_t)below.row0 * ld, dst,
                                seg_rows, B, ld, s);
             }
             std::swap(gcur, gnext);
         }
-        if (V > 0)
-            hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B,
-                               V, ld, leaf_mode, dleaf, dneg);
-        KLAY_HIP(hipGetLastError());
-        return KLAY_OK;
-    }
-    if (p.alias) {
-        double* G = gcur;
-        hipLaunchKernelGGL(klay::f64::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, ld,
-                           G + (size_t)p.num_nodes * ld);
-        for (int l = L; l >= 0; --l) {
-            const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
-            const DevLayer& d = c->dl[(size_t)l];
-            run_pass_set64(dp.has_weighted ? klay::OP_SOFTMAX_BWD : klay::OP_SUM, klay::OP_SUM, dp, G, act,
-                           act + (size_t)d.row0 * ld, G + (size_t)d.row0 * ld, seg_rows, B, ld, s);
+        if (B0 > 0 && (B0 & 1)) prod_parent(B0, act, grow(B0));
+        for (int l = B0 - 1; l >= 0; --l) {
+            run_pass_set64(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, G, nullptr,
+                           act + (size_t)c->dl[(size_t)l].row0 * ld, grow(l), seg_rows, B, ld, s);
+            if (l & 1) prod_parent(l, act, grow(l));
         }
-        if (V > 0)
-            hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B,
-                               V, ld, leaf_mode, dleaf, dneg);
-        KLAY_HIP(hipGetLastError());
-        return KLAY_OK;
-    }
-    hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
-                       c->d_top_root, B, R, ld, gcur);
-    for (int l = L; l >= 1; --l) {
-        const DevLayer& d = c->dl[(size_t)l];
-        const DevLayer& below = c->dl[(size_t)l - 1];
-        if ((l & 1) != 0 || !d.bwd.has_weighted)
-            run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, B, ld, s);
-        else
-            run_pass_set64(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * ld,
-                           act + (size_t)below.row0 * ld, gnext, seg_rows, B, ld, s);
-        std::swap(gcur, gnext);
+    } else {
+        hipLaunchKernelGGL(klay::f64::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
+                           c->d_top_root, B, R, ld, L == B0 ? grow(L) : gcur);
+        for (int l = L; l > B0; --l) {
+            const DevLayer& d = c->dl[(size_t)l];
+            const DevLayer& below = c->dl[(size_t)l - 1];
+            double* dst = l - 1 == B0 ? grow(B0) : gnext;
+            if ((l & 1) != 0 || !d.bwd.has_weighted)
+                run_pass_set64(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, dst, seg_rows, B, ld, s);
+            else
+                run_pass_set64(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * ld,
+                               act + (size_t)below.row0 * ld, dst, seg_rows, B, ld, s);
+            std::swap(gcur, gnext);
+        }
+        for (int l = B0 - 1; l >= 0; --l) {
+            const DevPass& dp = c->dl[(size_t)l + 1].bwd;
+            run_pass_set64(dp.has_weighted ? klay::OP_SOFTMAX_BWD : klay::OP_SUM, klay::OP_SUM, dp, G, act,
+                           act + (size_t)c->dl[(size_t)l].row0 * ld, grow(l), seg_rows, B, ld, s);
+        }
     }
     if (V > 0)
-        hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B, V,
+        hipLaunchKernelGGL(klay::f64::leaf_bwd_kernel, leaf_grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B, V,
                            ld, leaf_mode, dleaf, dneg);
     KLAY_HIP(hipGetLastError());
     return KLAY_OK;
@@ -1187,12 +1156,14 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
     if (!out) return fail(KLAY_EINVAL, "klay_build: out is null");
     *out = nullptr;
     klay::Options o;
+    o.alias_chains = true;                    // the default: padding-free below the narrow top
     if (opts) {
         o.no_reorder = opts->no_reorder != 0;
         if (opts->heavy_fan > 0) o.heavy_fan = opts->heavy_fan;
         if (opts->min_segment > 0) o.min_segment = opts->min_segment;
         o.no_tail = opts->no_tail != 0;
-        o.alias_chains = opts->alias_chains != 0;
+        o.alias_chains = opts->unary_chains == 0;
+        if (opts->tail_rows_cap > 0) o.tail_rows_cap = opts->tail_rows_cap;
         o.no_merge = opts->no_merge != 0;
         o.small_batch_edges = opts->small_batch_edges != 0;
     }
@@ -1336,6 +1307,7 @@ klay_status klay_info(const klay_circuit* c, klay_info_t* info) {
     info->index_bytes = (int64_t)c->index_bytes;
     info->tail_first_layer = p.tail_first;
     info->num_merged_nodes = p.num_merged;
+    info->alias_top_layer = p.alias_top;
     return KLAY_OK;
 }
 
@@ -1487,8 +1459,8 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
         const int cls = op == klay::OP_SUM ? KLAY_K_FWD_SUM
                         : op == klay::OP_PROD ? KLAY_K_FWD_PROD
                         : op == klay::OP_MAX ? KLAY_K_FWD_MAX : KLAY_K_FWD_LSE;
-        // alias mode: child entries are rows of the whole buffer, otherwise of the layer below
-        const float* below = p.alias ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
+        // up to alias_top child entries are rows of the whole buffer, above it of the layer below
+        const float* below = l <= p.alias_top ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
         run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
     }
 
@@ -1512,8 +1484,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
         prof.begin(KLAY_K_ROOT, 8.0 * B * p.num_roots);
         dim3 grid((unsigned)p.num_roots);
         hipLaunchKernelGGL(klay::root_out_kernel, grid, dim3(256), 0, s,
-                           p.alias ? act : act + (size_t)c->dl[(size_t)L].row0 * g.ld, c->d_root_pos, (int)B,
-                           p.num_roots, g.ld, out);
+                           act + (size_t)c->dl[(size_t)L].row0 * g.ld, c->d_root_pos, (int)B, p.num_roots, g.ld, out);
         prof.end();
     }
     KLAY_HIP(hipGetLastError());
@@ -1551,10 +1522,18 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     float* act = ws + lay.act;
     float* wT = ws + lay.wT;
     float* seg_rows = ws + lay.seg_rows;
-    float* gcur = ws + lay.g0;
-    float* gnext = ws + lay.g1;
-    const int L = p.num_layers, V = p.num_vars, R = p.num_roots;
+    float* G = ws + lay.g0;
+    float* gcur = ws + lay.g1;
+    float* gnext = ws + lay.g2;
+    const int L = p.num_layers, V = p.num_vars, R = p.num_roots, B0 = p.alias_top;
     Profiler prof(c, &c->ev_bwd, s);
+    // Course of the sweep.  The layers above B0 = alias_top are taken one by one, every step gathering the
+    // adjoints of layer l - 1 from those of layer l, alternating between two buffers; the step into layer
+    // B0 writes into G, which holds one adjoint row per node of the layers 0 .. B0, numbered like the rows
+    // of the activation buffer.  Below B0 a layer's rows gather from their parents anywhere in G (all
+    // final by then).  The leaf kernel reads the rows of layer 0 at the start of G.
+    auto grow = [&](int l) { return G + (size_t)c->dl[(size_t)l].row0 * g.ld; };
+    auto values = [&](int l) { return act + (size_t)c->dl[(size_t)l].row0 * g.ld; };
 
     if (real) {
         // Real semiring: a sum layer passes adjoints through (plain by-child sums).  For a product layer
@@ -1566,163 +1545,112 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         // this sweep runs layer by layer on rows of the activation buffer: bring back the values the
         // persistent forward kernel kept column-major
         if (c->last_tail_first > 0) launch_tb_to_rows(c, c->last_tail_first, L, ws + lay.tb, act, B, g.ld, s);
-        if (p.alias) {
-            // one adjoint row per activation row plus a dout row per root column; layers from the top:
-            // gather the adjoints of the layer's rows from all their parents, then (product layer) turn
-            // them into P rows for the layers below
-            float* X = gcur;
-            prof.begin(KLAY_K_SEED, 8.0 * B * R);
-            hipLaunchKernelGGL(klay::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, g.ld,
-                               X + (size_t)p.num_nodes * g.ld);
+        auto prod_parent = [&](int l, const float* below, float* gl) {
+            const DevLayer& d = c->dl[(size_t)l];
+            prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
+            launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, below, gl, g, B, s);
             prof.end();
-            for (int l = L; l >= 0; --l) {
-                const DevLayer& d = c->dl[(size_t)l];
-                float* gl = X + (size_t)d.row0 * g.ld;
-                run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, X, nullptr,
-                             act + (size_t)d.row0 * g.ld, gl, seg_rows, g, B, s, prof, KLAY_K_BWD_PROD);
-                if (l & 1) {
-                    prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
-                    launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, act, gl, g, B, s);
-                    prof.end();
-                }
-            }
-            prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
-            if (V > 0) {
-                dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
-                hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, X, wT, c->d_pos_row, c->d_neg_row, B, V,
-                                   g.ld, lits ? 2 : 0, dleaf, dneg);
-            }
-            prof.end();
-            KLAY_HIP(hipGetLastError());
-            return KLAY_OK;
-        }
+        };
         prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
         hipLaunchKernelGGL(klay::seed_kernel, dim3((unsigned)c->dl[(size_t)L].n), dim3(256), 0, s, dout, c->d_top_ptr,
-                           c->d_top_root, B, R, g.ld, gcur, (const uint32_t*)nullptr, (const float*)nullptr);
+                           c->d_top_root, B, R, g.ld, L == B0 ? grow(L) : gcur, (const uint32_t*)nullptr,
+                           (const float*)nullptr);
         prof.end();
-        for (int l = L; l >= 1; --l) {
+        for (int l = L; l > B0; --l) {
             const DevLayer& d = c->dl[(size_t)l];
-            const DevLayer& below = c->dl[(size_t)l - 1];
+            float* dst = l - 1 == B0 ? grow(B0) : gnext;
             if ((l & 1) == 0) {
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, gnext, seg_rows, g, B, s, prof,
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, dst, seg_rows, g, B, s, prof,
                              KLAY_K_BWD_SUM);
             } else {
-                prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
-                launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, act + (size_t)below.row0 * g.ld, gcur, g, B, s);
-                prof.end();
+                prod_parent(l, values(l - 1), gcur);
                 // the by-child plan of an AND layer carries no weighted bit: every entry is a P row
-                run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, act + (size_t)below.row0 * g.ld, gnext,
-                             seg_rows, g, B, s, prof, KLAY_K_BWD_PROD);
+                run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, values(l - 1), dst, seg_rows, g, B, s,
+                             prof, KLAY_K_BWD_PROD);
             }
             std::swap(gcur, gnext);
         }
-        prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
-        if (V > 0) {
-            dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
-            hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B, V,
-                               g.ld, lits ? 2 : 0, dleaf, dneg);
+        // below B0 the entries of a by-child plan tell P rows (AND parents) from plain adjoint rows
+        if (B0 > 0 && (B0 & 1)) prod_parent(B0, act, grow(B0));
+        for (int l = B0 - 1; l >= 0; --l) {
+            run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, G, nullptr, values(l),
+                         grow(l), seg_rows, g, B, s, prof, KLAY_K_BWD_PROD);
+            if (l & 1) prod_parent(l, act, grow(l));
         }
-        prof.end();
-        KLAY_HIP(hipGetLastError());
-        return KLAY_OK;
-    }
-
-    if (p.alias) {
-        // One adjoint row per activation row; rows N .. N+R-1 hold dout transposed.  Layer by layer
-        // from the top, every row gathers from its parents, wherever they live (all final by then).
-        float* G = gcur;
-        prof.begin(KLAY_K_SEED, 8.0 * B * R);
-        hipLaunchKernelGGL(klay::seed_rows_kernel, dim3((unsigned)R), dim3(256), 0, s, dout, B, R, g.ld,
-                           G + (size_t)p.num_nodes * g.ld);
-        prof.end();
-        for (int l = L; l >= 0; --l) {
-            const DevPass& dp = l == L ? c->top_bwd : c->dl[(size_t)l + 1].bwd;
-            const DevLayer& d = c->dl[(size_t)l];
-            const float* own = act + (size_t)d.row0 * g.ld;
-            // one-gather form: the adjoint rows of OR nodes with more than one child (rows of even layers,
-            // whose parents are AND nodes or roots: plain sums) are stored encoded, and every weighted edge
-            // (rows of odd layers and leaves) decodes the one row it gathers
-            const bool enc = kOneGather && l >= 2 && (l & 1) == 0 && d.has_multi && !dp.has_weighted;
-            if (kOneGather && c->alias_one_gather && (enc || dp.has_weighted))
-                run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SOFTMAX_H, enc ? klay::OP_SUM_H : klay::OP_SUM, dp, G, nullptr,
-                             own, G + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof,
-                             enc ? KLAY_K_BWD_SUM_ENC : KLAY_K_BWD_SOFTMAX_ONE);
-            else if (dp.has_weighted)
-                run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, own,
-                             G + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
-            else
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, G + (size_t)d.row0 * g.ld, seg_rows,
-                             g, B, s, prof, KLAY_K_BWD_SUM);
-        }
-        prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
-        if (V > 0) {
-            dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
-            hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B, V,
-                               g.ld, lits ? 2 : 1, dleaf, dneg);
-        }
-        prof.end();
-        KLAY_HIP(hipGetLastError());
-        return KLAY_OK;
-    }
-
-    // The adjoint rows of an OR layer with weighted edges travel in the one-gather form (encode_h): the
-    // step that produces them (OP_SUM_H, the seed, or the persistent kernel's last write) folds the
-    // node's own value in, and the step through the OR layer (OP_SOFTMAX_H) gathers that one row per
-    // edge instead of the adjoint row and the parent's value row.
-    auto one_gather = [&](int l) { return kOneGather && l >= 2 && (l & 1) == 0 && c->dl[(size_t)l].has_multi; };
-
-    // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
-    // which seeds the adjoints itself and leaves those of its first layer in gcur
-    int top = L;
-    const TailChoice tail = choose_tail_bwd(c, B, c->last_tail_first);
-    if (c->last_tail_first > 0) {
-        // the ordinary launches below read values of layers last_tail_first .. top as rows of the
-        // activation buffer; the persistent forward kernel kept them column-major
-        const int last_needed = tail.first > 0 ? tail.first : L;
-        launch_tb_to_rows(c, c->last_tail_first, last_needed, ws + lay.tb, act, B, g.ld, s);
-    }
-    if (tail.first > 0) {
-        prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R,
-                   tail_min_bytes(c, tail.first, B, true) + 4.0 * B * R);
-        launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, one_gather(tail.first) ? c->dl[(size_t)tail.first].multi : nullptr,
-                        B, g.ld, s);
-        prof.end();
-        top = tail.first;
     } else {
-        const bool enc = one_gather(L);
-        prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n * (enc ? 2.0 : 1.0));
-        dim3 grid((unsigned)c->dl[(size_t)L].n);
-        hipLaunchKernelGGL(klay::seed_kernel, grid, dim3(256), 0, s, dout, c->d_top_ptr, c->d_top_root, B, R,
-                           g.ld, gcur, enc ? c->dl[(size_t)L].multi : (const uint32_t*)nullptr,
-                           enc ? act + (size_t)c->dl[(size_t)L].row0 * g.ld : (const float*)nullptr);
-        prof.end();
-    }
+        // The adjoint rows of an OR layer with weighted edges travel in the one-gather form (encode_h): the
+        // step that produces them (OP_SUM_H, the seed, or the persistent kernel's last write) folds the
+        // node's own value in, and the step through the OR layer (OP_SOFTMAX_H) gathers that one row per
+        // edge instead of the adjoint row and the parent's value row.
+        const bool one = kOneGather && c->one_gather;
+        auto encoded = [&](int l) { return one && l >= 2 && (l & 1) == 0 && c->dl[(size_t)l].has_multi; };
 
-    for (int l = top; l >= 1; --l) {
-        const DevLayer& d = c->dl[(size_t)l];
-        const DevLayer& below = c->dl[(size_t)l - 1];
-        const bool is_and = (l & 1) != 0 || !d.bwd.has_weighted;   // no weighted edge: plain sums
-        const float* own_below = act + (size_t)below.row0 * g.ld;
-        if (is_and) {
-            const bool enc = one_gather(l - 1);
-            run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SUM, enc ? klay::OP_SUM_H : klay::OP_SUM, d.bwd, gcur, nullptr,
-                         enc ? own_below : nullptr, gnext, seg_rows, g, B, s, prof,
-                         enc ? KLAY_K_BWD_SUM_ENC : KLAY_K_BWD_SUM);
-        } else if (kOneGather) {
-            run_pass_set(klay::OP_SOFTMAX_H, klay::OP_SUM, d.bwd, gcur, nullptr, own_below, gnext, seg_rows, g, B, s,
-                         prof, KLAY_K_BWD_SOFTMAX_ONE);
-        } else {
-            run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, act + (size_t)d.row0 * g.ld, own_below, gnext,
-                         seg_rows, g, B, s, prof, KLAY_K_BWD_SOFTMAX);
+        // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
+        // which seeds the adjoints itself and leaves those of its first layer in gcur
+        int top = L;
+        const TailChoice tail = choose_tail_bwd(c, B, c->last_tail_first);
+        if (c->last_tail_first > 0) {
+            // the ordinary launches below read values of layers last_tail_first .. top as rows of the
+            // activation buffer; the persistent forward kernel kept them column-major
+            const int last_needed = tail.first > 0 ? tail.first : L;
+            launch_tb_to_rows(c, c->last_tail_first, last_needed, ws + lay.tb, act, B, g.ld, s);
         }
-        std::swap(gcur, gnext);
+        if (tail.first > 0) {
+            prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R,
+                       tail_min_bytes(c, tail.first, B, true) + 4.0 * B * R);
+            launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, encoded(tail.first) ? c->dl[(size_t)tail.first].multi : nullptr,
+                            B, g.ld, s);
+            prof.end();
+            top = tail.first;
+        } else {
+            const bool enc = encoded(L);
+            prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n * (enc ? 2.0 : 1.0));
+            dim3 grid((unsigned)c->dl[(size_t)L].n);
+            hipLaunchKernelGGL(klay::seed_kernel, grid, dim3(256), 0, s, dout, c->d_top_ptr, c->d_top_root, B, R, g.ld,
+                               L == B0 ? grow(L) : gcur, enc ? c->dl[(size_t)L].multi : (const uint32_t*)nullptr,
+                               enc ? values(L) : (const float*)nullptr);
+            prof.end();
+        }
+        for (int l = top; l > B0; --l) {
+            const DevLayer& d = c->dl[(size_t)l];
+            float* dst = l - 1 == B0 ? grow(B0) : gnext;
+            const bool is_and = (l & 1) != 0 || !d.bwd.has_weighted;   // no weighted edge: plain sums
+            if (is_and) {
+                const bool enc = encoded(l - 1);
+                run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SUM, enc ? klay::OP_SUM_H : klay::OP_SUM, d.bwd, gcur, nullptr,
+                             enc ? values(l - 1) : nullptr, dst, seg_rows, g, B, s, prof,
+                             enc ? KLAY_K_BWD_SUM_ENC : KLAY_K_BWD_SUM);
+            } else if (one) {
+                run_pass_set(klay::OP_SOFTMAX_H, klay::OP_SUM, d.bwd, gcur, nullptr, values(l - 1), dst, seg_rows, g, B, s,
+                             prof, KLAY_K_BWD_SOFTMAX_ONE);
+            } else {
+                run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, d.bwd, gcur, values(l), values(l - 1), dst, seg_rows, g, B,
+                             s, prof, KLAY_K_BWD_SOFTMAX);
+            }
+            std::swap(gcur, gnext);
+        }
+        for (int l = B0 - 1; l >= 0; --l) {
+            // rows of even layers are OR nodes, whose parents are AND nodes (plain sums; encoded on the way
+            // out where the node has more than one child); rows of odd layers and leaves read weighted edges
+            const DevPass& dp = c->dl[(size_t)l + 1].bwd;
+            const bool enc = encoded(l);
+            if (one && (enc || dp.has_weighted))
+                run_pass_set(enc ? klay::OP_SUM_H : klay::OP_SOFTMAX_H, enc ? klay::OP_SUM_H : klay::OP_SUM, dp, G, nullptr,
+                             values(l), grow(l), seg_rows, g, B, s, prof, enc ? KLAY_K_BWD_SUM_ENC : KLAY_K_BWD_SOFTMAX_ONE);
+            else if (dp.has_weighted)
+                run_pass_set(klay::OP_SOFTMAX_BWD, klay::OP_SUM, dp, G, act, values(l), grow(l), seg_rows, g, B, s, prof,
+                             KLAY_K_BWD_SOFTMAX);
+            else
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, dp, G, nullptr, nullptr, grow(l), seg_rows, g, B, s, prof,
+                             KLAY_K_BWD_SUM);
+        }
     }
 
     prof.begin(KLAY_K_BWD_LEAF, 4.0 * B * (3.0 * V));
     if (V > 0) {
         dim3 grid((unsigned)((V + 31) / 32), (unsigned)((B + 63) / 64));
-        hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, gcur, wT, c->d_pos_row, c->d_neg_row, B,
-                           V, g.ld, lits ? 2 : 1, dleaf, dneg);
+        hipLaunchKernelGGL(klay::leaf_bwd_kernel, grid, dim3(256), 0, s, G, wT, c->d_pos_row, c->d_neg_row, B, V, g.ld,
+                           lits ? 2 : (real ? 0 : 1), dleaf, dneg);
     }
     prof.end();
     KLAY_HIP(hipGetLastError());

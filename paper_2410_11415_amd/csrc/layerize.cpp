@@ -358,22 +358,49 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
 
     // ---------------------------------------------------------------- unary chains (Section 3.1; one per (child, layer))
     // need[c] = highest layer at which a stand-in for c is read: parent height - 1, or L for roots.
-    // With alias_chains no stand-ins are made: an edge reads the child's own row wherever it lives.
-    const bool alias = opt.alias_chains;
-    plan.alias = alias;
     std::vector<int32_t> need(h);
+    std::vector<int32_t> max_fan((size_t)L + 1, 0);       // largest fan-in among the gates of a layer
     for (int64_t p = 0; p < N; ++p) {
         if (!reach[(size_t)p]) continue;
         plan.dag_nodes++;
         plan.dag_edges += child_ptr[p + 1] - child_ptr[p];
-        if (alias) continue;
+        max_fan[(size_t)h[(size_t)p]] = (int32_t)std::max<int64_t>(max_fan[(size_t)h[(size_t)p]], child_ptr[p + 1] - child_ptr[p]);
         for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) {
             int32_t c = child_idx[j];
             need[(size_t)c] = std::max(need[(size_t)c], h[(size_t)p] - 1);
         }
     }
-    if (!alias)
-        for (int32_t r = 0; r < R; ++r) need[(size_t)roots[r]] = L;
+    for (int32_t r = 0; r < R; ++r) need[(size_t)roots[r]] = L;
+
+    // Padding-free lower part (Options::alias_chains): the layers 1 .. B0 (B0 = plan.alias_top) hold no
+    // stand-ins except that layer B0 is complete: it holds a stand-in for every node that a layer above
+    // reads.  The edges of the layers up to B0 name the child's own row in the whole activation buffer,
+    // wherever it lives; from layer B0 + 1 on every edge goes to the layer directly below, as in the
+    // paper.  B0 is chosen so that the layers above it are exactly the narrow top of the circuit that the
+    // persistent kernels can take (they need complete layers); B0 = 0 is the paper's layerization, B0 = L
+    // has no chain nodes at all except the stand-ins that bring every root to the top layer.
+    const int64_t rows_cap = opt.tail_rows_cap > 0 ? std::min<int64_t>(opt.tail_rows_cap, kTailRowsCap) : kTailRowsCap;
+    int32_t B0 = 0;
+    {
+        std::vector<int64_t> full((size_t)L + 1, 0);       // layer sizes with all chain nodes
+        for (int64_t c = 0; c < N; ++c)
+            if (reach[(size_t)c])
+                for (int32_t l = h[(size_t)c]; l <= need[(size_t)c]; ++l) ++full[(size_t)l];
+        if (opt.alias_chains) {
+            B0 = L;
+            if (!opt.no_tail) {
+                int32_t t = L + 1;
+                while (t - 1 >= 1 && full[(size_t)t - 1] <= rows_cap && full[(size_t)t - 2] <= rows_cap &&
+                       max_fan[(size_t)t - 1] <= kTailFanCap)
+                    --t;
+                if (L - t + 1 >= 2) B0 = t - 1;            // a persistent kernel takes two layers or more
+            }
+        }
+    }
+    plan.alias_top = B0;
+    plan.alias = B0 > 0;
+    // lowest level at which c has a stand-in (none if that is above need[c])
+    auto lo = [&](int64_t c) { return std::max(h[(size_t)c] + 1, B0); };
 
     std::vector<int64_t> count((size_t)L + 1, 0);
     std::vector<int64_t> pad_base((size_t)N + 1, 0);
@@ -381,9 +408,9 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         pad_base[(size_t)c + 1] = pad_base[(size_t)c];
         if (!reach[(size_t)c]) continue;
         ++count[(size_t)h[(size_t)c]];
-        const int32_t pads = need[(size_t)c] - h[(size_t)c];
+        const int32_t pads = std::max(0, need[(size_t)c] - lo(c) + 1);
         pad_base[(size_t)c + 1] += pads;
-        for (int32_t l = h[(size_t)c] + 1; l <= need[(size_t)c]; ++l) ++count[(size_t)l];
+        for (int32_t l = lo(c); l <= need[(size_t)c]; ++l) ++count[(size_t)l];
     }
     plan.num_pad_nodes = pad_base[(size_t)N];
     for (int32_t l = 0; l <= L; ++l)
@@ -408,8 +435,8 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             }
         for (int64_t c = 0; c < N; ++c)
             if (reach[(size_t)c])
-                for (int32_t l = h[(size_t)c] + 1; l <= need[(size_t)c]; ++l) {
-                    pos_pad[(size_t)(pad_base[(size_t)c] + l - h[(size_t)c] - 1)] = (int32_t)fill[(size_t)l];
+                for (int32_t l = lo(c); l <= need[(size_t)c]; ++l) {
+                    pos_pad[(size_t)(pad_base[(size_t)c] + l - lo(c))] = (int32_t)fill[(size_t)l];
                     plan.layers[(size_t)l].origin[(size_t)fill[(size_t)l]] = (int32_t)c;
                     plan.layers[(size_t)l].is_pad[(size_t)fill[(size_t)l]++] = 1;
                 }
@@ -417,23 +444,26 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     plan.row0.assign((size_t)L + 2, 0);
     for (int32_t l = 0; l <= L; ++l) plan.row0[(size_t)l + 1] = plan.row0[(size_t)l] + count[(size_t)l];
     if (plan.row0[(size_t)L + 1] + R >= kMaxRows) { err = "klay_build: more than 2^29 rows"; return ST_INVAL; }
-    // position of the stand-in of node c at `level` (h[c] <= level <= need[c]); in alias mode the
-    // row of c itself in the whole activation buffer
+    // position, within layer `level`, of node c or of its stand-in there (c is present at that level)
     auto at = [&](int32_t c, int32_t level) -> int32_t {
-        if (alias) return (int32_t)(plan.row0[(size_t)h[(size_t)c]] + pos_real[(size_t)c]);
-        return level == h[(size_t)c] ? pos_real[(size_t)c]
-                                     : pos_pad[(size_t)(pad_base[(size_t)c] + level - h[(size_t)c] - 1)];
+        return level == h[(size_t)c] ? pos_real[(size_t)c] : pos_pad[(size_t)(pad_base[(size_t)c] + level - lo(c))];
+    };
+    // what an edge from layer level + 1 down to c holds: below B0 the row of c itself in the whole
+    // activation buffer, from B0 on the position of c (or of its stand-in) in layer `level`
+    auto src_at = [&](int32_t c, int32_t level) -> int32_t {
+        if (level < B0) return (int32_t)(plan.row0[(size_t)h[(size_t)c]] + pos_real[(size_t)c]);
+        return at(c, level);
     };
     // ordering key of a child: its position in the layer below, or (alias mode) its relative
     // position within its own layer scaled to the width of the layer below
     auto child_key = [&](int32_t c, int32_t level) -> double {
-        if (!alias) return (double)at(c, level);
+        if (level >= B0) return (double)at(c, level);
         const int32_t hc = h[(size_t)c];
         return (double)pos_real[(size_t)c] / (double)std::max<int64_t>(1, count[(size_t)hc]) * (double)count[(size_t)level];
     };
     auto set_at = [&](int32_t c, int32_t level, int32_t p) {
         if (level == h[(size_t)c]) pos_real[(size_t)c] = p;
-        else pos_pad[(size_t)(pad_base[(size_t)c] + level - h[(size_t)c] - 1)] = p;
+        else pos_pad[(size_t)(pad_base[(size_t)c] + level - lo(c))] = p;
     };
 
     // ---------------------------------------------------------------- node order within layers (Section 4: arbitrary)
@@ -486,7 +516,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             std::vector<int32_t> order((size_t)lay.n);
             std::iota(order.begin(), order.end(), 0);
             std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[(size_t)a] < key[(size_t)b]; });
-            if (lay.n <= kTailRowsCap && !alias && !opt.no_tail) {
+            if (lay.n <= rows_cap && l >= B0 && !opt.no_tail) {
                 // A layer small enough for the persistent top-of-circuit kernels: there a thread walks a whole
                 // row and a wave waits for its longest one, while locality is irrelevant (the layer sits in
                 // LDS).  Group rows by fan-in (powers of two) and order each group by fan-out, so that the 64
@@ -523,7 +553,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         // sweeps, gains nothing more.)
         auto order_by_parents = [&](int32_t l) {
             LayerPlan& lay = plan.layers[(size_t)l];
-            if (lay.n <= kTailRowsCap && !opt.no_tail) return;       // keep the fan-sorted order of small layers
+            if (lay.n <= rows_cap && !opt.no_tail) return;       // keep the fan-sorted order of small layers
             const LayerPlan& up = plan.layers[(size_t)l + 1];
             std::vector<int32_t> key((size_t)lay.n, INT32_MAX);
             for (int64_t p2 = 0; p2 < up.n; ++p2) {
@@ -540,16 +570,16 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[(size_t)a] < key[(size_t)b]; });
             apply_order(l, order);
         };
-        if (!alias)
-            for (int32_t l = L - 1; l >= 1; --l)
-                if (l & 1) order_by_parents(l);
-        if (alias) {
-            // the same idea without chain nodes: parents sit in any higher layer, so one sweep from the
-            // top keeps, per node, the smallest relative position among its parents seen so far
+        // (layers from B0 on: their parents sit in the layer directly above)
+        for (int32_t l = L - 1; l >= std::max(B0, 1); --l)
+            if (l & 1) order_by_parents(l);
+        if (B0 > 0) {
+            // the same idea for the layers below B0, whose parents sit in any higher layer up to B0: one sweep
+            // from the top keeps, per node, the smallest relative position among its parents seen so far
             std::vector<double> pkey((size_t)N, 2.0);
-            for (int32_t l = L; l >= 1; --l) {
+            for (int32_t l = B0; l >= 1; --l) {
                 LayerPlan& lay = plan.layers[(size_t)l];
-                if ((l & 1) && l < L) {
+                if ((l & 1) && l < B0) {
                     std::vector<int32_t> order((size_t)lay.n);
                     std::iota(order.begin(), order.end(), 0);
                     std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
@@ -560,6 +590,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 for (int64_t s2 = 0; s2 < lay.n; ++s2) {
                     const int32_t c = lay.origin[(size_t)s2];
                     const double rel = ((double)s2 + 0.5) / (double)lay.n;
+                    if (lay.is_pad[(size_t)s2]) { pkey[(size_t)c] = std::min(pkey[(size_t)c], rel); continue; }
                     for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) pkey[(size_t)child_idx[j]] = std::min(pkey[(size_t)child_idx[j]], rel);
                 }
             }
@@ -581,10 +612,10 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         for (int64_t p = 0; p < lay.n; ++p) {
             lay.row_ptr[(size_t)p] = w;
             int32_t c = lay.origin[(size_t)p];
-            if (lay.is_pad[(size_t)p]) lay.child[(size_t)w++] = at(c, l - 1);
+            if (lay.is_pad[(size_t)p]) lay.child[(size_t)w++] = src_at(c, l - 1);
             else {
                 const int32_t w0 = w;
-                for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) lay.child[(size_t)w++] = at(child_idx[j], l - 1);
+                for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) lay.child[(size_t)w++] = src_at(child_idx[j], l - 1);
                 std::sort(lay.child.begin() + w0, lay.child.begin() + w);
             }
             plan.max_fan_in = std::max<int64_t>(plan.max_fan_in, w - lay.row_ptr[(size_t)p]);
@@ -598,7 +629,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         plan.num_edges += e;
         plan.num_split_rows += lay.fwd.n_heavy;
         plan.max_fwd_seg = std::max<int64_t>(plan.max_fwd_seg, lay.fwd.n_seg);
-        if (alias) continue;
+        if (l <= B0) continue;             // their reverse plans are built below, over the whole lower part
 
         // by child (for the reverse sweep): rows = nodes of layer l-1, sources = parents in layer l;
         // an edge is weighted when its parent is an OR node with more than one child
@@ -623,7 +654,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         // with more than one child are flagged (their adjoints are stored in the one-gather form)
         make_pass_plan(nc, cptr.data(), cpar.data(), popt, lay.bwd, cflag.data(),
                        (l & 1) && l >= 3 ? plan.layers[(size_t)l - 1].multi.data() : nullptr);
-        if (!opt.no_tail && lay.n <= kTailRowsCap && nc <= kTailRowsCap) {
+        if (!opt.no_tail && lay.n <= rows_cap && nc <= rows_cap) {
             int64_t fan_in = 0, fan_out = 0;
             for (int64_t i = 0; i < lay.n; ++i) fan_in = std::max<int64_t>(fan_in, lay.row_ptr[(size_t)i + 1] - lay.row_ptr[(size_t)i]);
             for (int64_t i = 0; i < nc; ++i) fan_out = std::max<int64_t>(fan_out, cptr[(size_t)i + 1] - cptr[(size_t)i]);
@@ -639,15 +670,13 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         plan.num_split_rows += lay.bwd.n_heavy;
         plan.max_bwd_seg = std::max<int64_t>(plan.max_bwd_seg, lay.bwd.n_seg);
     }
-    if (alias) {
-        // Reverse-sweep sources of every row of the activation buffer: its parents (rows of any
-        // higher layer) and, for a root, the adjoint rows that hold the transposed dout.
-        const int64_t NR = plan.row0[(size_t)L + 1];
+    if (B0 > 0) {
+        // Reverse-sweep sources of every row below layer B0: its parents, which are rows of any higher
+        // layer up to B0 (adjoint rows are numbered like the rows of the activation buffer).
+        const int64_t NR = plan.row0[(size_t)B0];
         std::vector<int32_t> gptr((size_t)NR + 1, 0);
-        for (int32_t l = 1; l <= L; ++l)
+        for (int32_t l = 1; l <= B0; ++l)
             for (int32_t ch : plan.layers[(size_t)l].child) ++gptr[(size_t)ch + 1];
-        std::vector<int32_t> root_row((size_t)R);
-        for (int32_t r = 0; r < R; ++r) { root_row[(size_t)r] = at(roots[r], L); ++gptr[(size_t)root_row[(size_t)r] + 1]; }
         for (int64_t i = 0; i < NR; ++i) {
             plan.max_fan_out = std::max<int64_t>(plan.max_fan_out, gptr[(size_t)i + 1]);
             if ((int64_t)gptr[(size_t)i] + gptr[(size_t)i + 1] >= INT32_MAX - 64) { err = "klay_build: more than 2^31 edges"; return ST_INVAL; }
@@ -657,7 +686,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         std::vector<uint32_t> gflag((size_t)gptr[(size_t)NR], 0u);
         {
             std::vector<int32_t> fill(gptr.begin(), gptr.end() - 1);
-            for (int32_t l = 1; l <= L; ++l) {
+            for (int32_t l = 1; l <= B0; ++l) {
                 const LayerPlan& lay = plan.layers[(size_t)l];
                 for (int64_t p = 0; p < lay.n; ++p) {
                     const bool weighted = (l & 1) == 0 && lay.row_ptr[(size_t)p + 1] - lay.row_ptr[(size_t)p] > 1;
@@ -668,14 +697,13 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                     }
                 }
             }
-            for (int32_t r = 0; r < R; ++r) gsrc[(size_t)fill[(size_t)root_row[(size_t)r]]++] = (int32_t)(NR + r);
         }
-        for (int32_t l = 0; l <= L; ++l) {
+        for (int32_t l = 0; l < B0; ++l) {
             // rows of layer l: a CSR slice rebased to start at 0
             const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;
             std::vector<int32_t> lptr((size_t)n + 1);
             for (int64_t i = 0; i <= n; ++i) lptr[(size_t)i] = gptr[(size_t)(a + i)] - gptr[(size_t)a];
-            PassPlan& dst = l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd;
+            PassPlan& dst = plan.layers[(size_t)l + 1].bwd;
             // rows that are OR nodes with more than one child are flagged, as in the layer-by-layer plans
             make_pass_plan(n, lptr.data(), gsrc.data() + gptr[(size_t)a], popt, dst, gflag.data() + gptr[(size_t)a],
                            (l & 1) == 0 && l >= 2 ? plan.layers[(size_t)l].multi.data() : nullptr);
@@ -690,7 +718,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
 
     // the narrow top: the longest suffix of layers that all kept their plain index vectors
     plan.tail_first = plan.tail_bwd_first = 0;
-    if (!opt.no_tail && !alias) {
+    if (!opt.no_tail) {
         int32_t t = L + 1;
         while (t - 1 >= 1 && plan.layers[(size_t)t - 1].tail_fwd_ok) --t;
         if (t <= L) plan.tail_first = t;
@@ -718,10 +746,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     }
     plan.root_pos.resize((size_t)R);
     for (int32_t r = 0; r < R; ++r) plan.root_pos[(size_t)r] = at(roots[r], L);
-    if (alias) {
-        plan.top_ptr.assign(2, 0);
-        plan.top_root.assign(1, 0);
-    } else {
+    {
         const int64_t nt = plan.layers[(size_t)L].n;
         plan.top_ptr.assign((size_t)nt + 1, 0);
         plan.top_root.resize((size_t)R);

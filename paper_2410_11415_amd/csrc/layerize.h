@@ -14,8 +14,10 @@ struct Options {
     int32_t heavy_fan = 48;     // rows with more sources than this are evaluated in split passes
     int32_t min_segment = 24;   // smallest segment of a split row, in edges
     bool no_tail = false;       // never use the persistent kernels for the narrow top layers
-    bool alias_chains = false;  // no unary chain nodes: edges index the rows of any lower layer
+    bool alias_chains = false;  // no unary chain nodes below the narrow top of the circuit: edges index the rows of any lower layer
     bool no_merge = false;      // keep structurally identical gates apart
+    int32_t tail_rows_cap = 0;  // > 0: layers with more nodes than this are no candidates for the persistent kernels
+                                // (at most kTailRowsCap; for tests of the boundary between the two parts)
     bool small_batch_edges = false;   // evaluator option (not used by the layerizer): lanes = edges kernel for B <= 32
 };
 
@@ -105,13 +107,16 @@ struct CircuitPlan {
     int64_t max_fwd_seg = 0, max_bwd_seg = 0;   // scratch rows needed by split passes
     int32_t tail_first = 0;              // layers tail_first..num_layers may run in the persistent forward kernel (0: none)
     int32_t tail_bwd_first = 0;          // layers tail_bwd_first..num_layers also in the reverse one (>= tail_first; 0: none)
-    // alias mode (Options::alias_chains): child entries, root_pos and the reverse-sweep sources are
-    // rows of the whole activation buffer (row0[l] = first row of layer l); layers[l].bwd gathers
-    // the adjoints of layer l-1 from parents in any higher layer, top_bwd those of the top layer;
-    // adjoint rows num_nodes .. num_nodes + R - 1 hold the transposed dout (one per root column)
-    bool alias = false;
+    // Padding-free lower part (Options::alias_chains): layers 1 .. alias_top hold no chain nodes, except
+    // that layer alias_top holds a stand-in for every node read from above it.  Their child entries are
+    // rows of the whole activation buffer (row0[l] = first row of layer l), and layers[l].bwd for
+    // l <= alias_top gathers the adjoints of layer l-1 from parents in any layer up to alias_top (adjoint
+    // rows numbered like activation rows).  Layers above alias_top are as in the paper: child entries and
+    // reverse-sweep sources are positions in the neighbouring layer.  0: the paper's layerization
+    // throughout; num_layers: no chain nodes except the stand-ins of roots in the top layer.
+    int32_t alias_top = 0;
+    bool alias = false;                  // alias_top > 0
     std::vector<int64_t> row0;
-    PassPlan top_bwd;
 };
 
 // Status codes mirror klay_status (0 ok, 1 invalid, 2 cycle, 3 no memory).

@@ -171,7 +171,7 @@ static void check_slab(const klay::SlabPlan& sp, int64_t n_out, int64_t n_src, c
 int main(int argc, char** argv) {
     const int trials = argc > 1 ? std::atoi(argv[1]) : 120;
     std::mt19937_64 rng(12345);
-    long plans = 0;
+    long plans = 0, b0_seen[3] = {0, 0, 0};
     for (int trial = 0; trial < trials; ++trial) {
         const int V = 1 + (int)(rng() % 12), nl = 2 * V;
         const int ng = 1 + (int)(rng() % 400);
@@ -204,6 +204,8 @@ int main(int argc, char** argv) {
         for (int mode = 0; mode < 8; ++mode) {
             klay::Options o;
             o.alias_chains = mode & 1; o.no_merge = mode & 2; o.no_reorder = mode & 4;
+            o.no_tail = (rng() % 4) == 0;
+            o.tail_rows_cap = (rng() % 3) == 0 ? 0 : 2 + (int)(rng() % 12);
             o.heavy_fan = 1 + (int)(rng() % 40); o.min_segment = 1 + (int)(rng() % 8);
             klay::CircuitPlan plan;
             std::string err;
@@ -211,55 +213,69 @@ int main(int argc, char** argv) {
             if (st == 1) continue;                  // a repeated literal child after leaf merging: rejected input
             CHECK(st == 0, "layerize status %d: %s", st, err.c_str());
             const int L = plan.num_layers;
-            if (!plan.alias) {
-                for (int l = 1; l <= L; ++l) {
-                    const klay::LayerPlan& lay = plan.layers[(size_t)l];
-                    const int64_t nb = plan.layers[(size_t)l - 1].n;
-                    std::vector<u64> fwd((size_t)lay.n, 0), bwd((size_t)nb, 0);
-                    for (int64_t r = 0; r < lay.n; ++r) {
-                        const bool weighted = (l % 2 == 0) && lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1;
-                        for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
-                            fwd[(size_t)r] += val(lay.child[(size_t)j]);
-                            bwd[(size_t)lay.child[(size_t)j]] += val(r) * (weighted ? 3u : 1u);
-                        }
+            const int B0 = plan.alias_top;
+            CHECK(B0 >= 0 && B0 <= L && plan.alias == (B0 > 0), "alias_top %d of %d layers", B0, L);
+            if (!o.alias_chains) CHECK(B0 == 0, "chains asked for");
+            if (o.alias_chains && o.no_tail) CHECK(B0 == L, "no persistent top: padding-free throughout");
+            ++b0_seen[B0 == 0 ? 0 : (B0 == L ? 2 : 1)];
+            // layers above B0: edges to the layer directly below, reverse plans layer by layer
+            for (int l = B0 + 1; l <= L; ++l) {
+                const klay::LayerPlan& lay = plan.layers[(size_t)l];
+                const int64_t nb = plan.layers[(size_t)l - 1].n;
+                std::vector<u64> fwd((size_t)lay.n, 0), bwd((size_t)nb, 0);
+                for (int64_t r = 0; r < lay.n; ++r) {
+                    const bool weighted = (l % 2 == 0) && lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1;
+                    for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
+                        CHECK(lay.child[(size_t)j] >= 0 && lay.child[(size_t)j] < nb, "child position in the layer below");
+                        fwd[(size_t)r] += val(lay.child[(size_t)j]);
+                        bwd[(size_t)lay.child[(size_t)j]] += val(r) * (weighted ? 3u : 1u);
                     }
-                    check_plan(lay.fwd, lay.n, nb, fwd, "forward plan"); ++plans;
-                    check_plan(lay.bwd, nb, lay.n, bwd, "backward plan", (l % 2 == 1 && l >= 3) ? &plan.layers[(size_t)l - 1].multi : nullptr); ++plans;
-                    for (int64_t r = 0; r < lay.n; ++r)
-                        CHECK(((lay.multi[(size_t)r >> 5] >> (r & 31)) & 1u) == (lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1 ? 1u : 0u), "multi-child bit");
-                    CHECK(!lay.tail_bwd_ok || lay.tail_fwd_ok, "reverse persistent plan without the forward one");
-                    if (lay.tail_fwd_ok) { check_slab(lay.slab_fwd, lay.n, nb, fwd, "persistent forward plan"); ++plans; }
-                    if (lay.tail_bwd_ok) { check_slab(lay.slab_bwd, nb, lay.n, bwd, "persistent reverse plan"); ++plans; }
-                    if (plan.tail_first > 0 && l >= plan.tail_first) CHECK(lay.tail_fwd_ok, "candidate suffix");
-                    if (plan.tail_bwd_first > 0 && l >= plan.tail_bwd_first) CHECK(lay.tail_bwd_ok && plan.tail_bwd_first >= plan.tail_first, "reverse candidate suffix");
                 }
-            } else {
-                const int64_t NR = plan.row0[(size_t)L + 1];
+                check_plan(lay.fwd, lay.n, nb, fwd, "forward plan"); ++plans;
+                check_plan(lay.bwd, nb, lay.n, bwd, "backward plan", (l % 2 == 1 && l >= 3) ? &plan.layers[(size_t)l - 1].multi : nullptr); ++plans;
+                CHECK(!lay.tail_bwd_ok || lay.tail_fwd_ok, "reverse persistent plan without the forward one");
+                if (lay.tail_fwd_ok) { check_slab(lay.slab_fwd, lay.n, nb, fwd, "persistent forward plan"); ++plans; }
+                if (lay.tail_bwd_ok) { check_slab(lay.slab_bwd, nb, lay.n, bwd, "persistent reverse plan"); ++plans; }
+            }
+            for (int l = 1; l <= L; ++l) {
+                const klay::LayerPlan& lay = plan.layers[(size_t)l];
+                for (int64_t r = 0; r < lay.n; ++r)
+                    CHECK(((lay.multi[(size_t)r >> 5] >> (r & 31)) & 1u) == (lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1 ? 1u : 0u), "multi-child bit");
+                if (plan.tail_first > 0 && l >= plan.tail_first) CHECK(lay.tail_fwd_ok && l > B0, "candidate suffix");
+                if (plan.tail_bwd_first > 0 && l >= plan.tail_bwd_first) CHECK(lay.tail_bwd_ok && plan.tail_bwd_first >= plan.tail_first, "reverse candidate suffix");
+                if (l < B0) for (int64_t r = 0; r < lay.n; ++r) CHECK(!lay.is_pad[(size_t)r], "chain node below the boundary layer");
+            }
+            if (B0 > 0) {
+                // layers up to B0: edges name rows of the whole buffer; reverse plans of the rows below B0 gather
+                // from parents in any layer up to B0
+                const int64_t NR = plan.row0[(size_t)B0];
                 std::vector<u64> adj((size_t)NR, 0);
-                for (int l = 1; l <= L; ++l) {
+                for (int l = 1; l <= B0; ++l) {
                     const klay::LayerPlan& lay = plan.layers[(size_t)l];
                     std::vector<u64> fwd((size_t)lay.n, 0);
                     for (int64_t r = 0; r < lay.n; ++r) {
                         const bool weighted = (l % 2 == 0) && lay.row_ptr[(size_t)r + 1] - lay.row_ptr[(size_t)r] > 1;
                         for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
                             const int32_t ch = lay.child[(size_t)j];
-                            CHECK(ch < plan.row0[(size_t)l], "alias child must sit in a lower layer");
+                            CHECK(ch >= 0 && ch < plan.row0[(size_t)l], "aliased child must sit in a lower layer");
                             fwd[(size_t)r] += val(ch);
                             adj[(size_t)ch] += val(plan.row0[(size_t)l] + r) * (weighted ? 3u : 1u);
                         }
                     }
                     check_plan(lay.fwd, lay.n, plan.row0[(size_t)l], fwd, "alias forward plan"); ++plans;
                 }
-                for (int r = 0; r < R; ++r) adj[(size_t)plan.root_pos[(size_t)r]] += val(NR + r);
-                for (int l = 0; l <= L; ++l) {
+                for (int l = 0; l < B0; ++l) {
                     const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;
                     std::vector<u64> want(adj.begin() + a, adj.begin() + a + n);
-                    check_plan(l == L ? plan.top_bwd : plan.layers[(size_t)l + 1].bwd, n, NR + R, want, "alias backward plan",
+                    check_plan(plan.layers[(size_t)l + 1].bwd, n, plan.row0[(size_t)B0 + 1], want, "alias backward plan",
                                (l % 2 == 0 && l >= 2) ? &plan.layers[(size_t)l].multi : nullptr); ++plans;
                 }
             }
+            // every root reads a row of the top layer
+            for (int r = 0; r < R; ++r) CHECK(plan.root_pos[(size_t)r] >= 0 && plan.root_pos[(size_t)r] < plan.layers[(size_t)L].n, "root position");
         }
     }
+    CHECK(b0_seen[0] > 0 && b0_seen[1] > 0 && b0_seen[2] > 0, "boundary layer cases seen: %ld %ld %ld", b0_seen[0], b0_seen[1], b0_seen[2]);
     std::printf("ok: %ld plans checked\n", plans);
     return 0;
 }

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.klay_options) == 32
-    assert ctypes.sizeof(binding.klay_info_t) == 16 + 12 * 8
+    assert ctypes.sizeof(binding.klay_info_t) == 16 + 13 * 8
     # the profile arrays have one slot per kernel class of the header's enum
     with open(os.path.join(ROOT, "include", "klay.h")) as fh:
         header = fh.read()

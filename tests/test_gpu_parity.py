@@ -30,6 +30,17 @@ def build(klay, c, **kw):
     return klay.Circuit(*c.arrays(), device=0, **kw)
 
 
+def layer_modes(klay, c):
+    """Builds of one circuit that differ in where the padding-free lower part of the layerization ends:
+    nowhere (the paper's layerization throughout), at the top layer (no persistent kernels), and at layers
+    in between (layers wider than a cap are no candidates for the persistent kernels)."""
+    kh = klay.Circuit(*c.arrays(), device=-1, unary_chains=True)
+    nodes, _ = kh.layer_sizes()
+    kh.close()
+    caps = sorted({max(int(x), 1) for x in np.quantile(np.asarray(nodes[1:]), [0.3, 0.7])}) if len(nodes) > 2 else []
+    return [dict(unary_chains=True), dict(no_tail=True)] + [dict(tail_rows_cap=cap) for cap in caps]
+
+
 def check_both(klay, c, p, backward=True, semirings=(REAL, LOG), what="", plain=False, **kw):
     k = build(klay, c, **kw)
     rng = np.random.default_rng(123)
@@ -353,7 +364,7 @@ def test_call_order_errors(klay):
         klay.klay_backward(k._h, d.data_ptr(), g.data_ptr(), 0)
     assert e.value.status == 5
     k.close()
-    ka = build(klay, c, alias_chains=True)
+    ka = build(klay, c, unary_chains=True)
     ka.forward_f64(torch.from_numpy(as_inputs(p, True).astype(np.float64)).cuda(), MAXLOG)
     with pytest.raises(klay.KlayError) as e:
         ka.backward_f64(d.double())
@@ -372,7 +383,7 @@ def test_profile_reports_kernel_classes(klay):
     assert prof["bwd_sum_enc"]["launches"] >= 9 and prof["bwd_softmax"]["launches"] == 0
     k.set_profiling(False)
     k.close()
-    ka = build(klay, c, no_tail=True, alias_chains=True)
+    ka = build(klay, c, no_tail=True, unary_chains=True)
     ka.set_profiling(True)
     gpu_eval(ka, as_inputs(p, True), LOG, np.ones((64, c.roots.shape[0]), np.float32))
     prof = ka.get_profile()
@@ -407,42 +418,54 @@ def test_persistent_top_kernel_matches_per_layer_launches(klay, B):
     k_tail.close(); k_flat.close()
 
 
-# ------------------------------------------------------------------ padding-free evaluation (alias_chains)
+# ------------------------------------------------------------------ the paper's layerization throughout (unary_chains), and the boundary
+# ------------------------------------------------------------------ between the padding-free lower part and the top at various layers
 @pytest.mark.parametrize("name,scale,B", [("tiny_ddnnf", 1.0, 4), ("layered_100k", 0.3, 128), ("layered_1m", 0.05, 1),
                                           ("powerlaw_10m", 0.08, 64), ("layered_3m_fwd_bwd", 0.02, 256)])
-def test_alias_chains_mode_matches_the_oracle(klay, name, scale, B):
+def test_unary_chains_mode_matches_the_oracle(klay, name, scale, B):
     c, p, spec = make_config(name, seed=2, scale=scale, batch=B)
     sem = tuple(REAL if s == "real" else LOG for s in spec["semirings"])      # real underflows fp32 on powerlaw
-    stats = check_both(klay, c, p, semirings=sem, what=name + " alias", alias_chains=True)
-    print(name, stats)
+    tops = set()
+    for mode in layer_modes(klay, c):
+        kh = klay.Circuit(*c.arrays(), device=-1, **mode)
+        tops.add((kh.info()["alias_top_layer"], kh.num_layers))
+        kh.close()
+        print(name, mode, check_both(klay, c, p, semirings=sem, what="%s %s" % (name, mode), **mode))
+    # the boundary was seen at layer 0, at the top and strictly in between
+    assert any(a == 0 for a, L in tops) and any(a == L for a, L in tops), tops
+    if name.startswith("layered"):            # (the power-law circuit has wide fan-ins at the top: no persistent kernels)
+        assert any(0 < a < L for a, L in tops), tops
 
 
-def test_alias_chains_mode_on_odd_shapes(klay, golden):
+def test_unary_chains_mode_on_odd_shapes(klay, golden):
     for f, nv in (("fig1b_ddnnf.txt", 4), ("fig3_multiroot.txt", 5), ("appD_mnist_add.txt", 2)):
-        check_both(klay, golden(f), leaf_probs(1, 5, nv, ("uniform", 0.05, 0.95)), what=f + " alias", alias_chains=True)
+        for mode in layer_modes(klay, golden(f)) + [dict(tail_rows_cap=1), dict(tail_rows_cap=2)]:
+            check_both(klay, golden(f), leaf_probs(1, 5, nv, ("uniform", 0.05, 0.95)), what="%s %s" % (f, mode), **mode)
     b = CircuitBuilder(3)
     x, y, z = b.lit(0), b.lit(1), b.lit(2)
     o = b.or_(x, y)                       # OR directly over leaves: lifted to layer 2, layer 1 stays empty
     a = b.and_(o, z)
     c = b.finish([a, o, x, a, b.lit(2, False)])
-    check_both(klay, c, leaf_probs(2, 9, 3, ("uniform", 0.05, 0.95)), what="lifted alias", alias_chains=True)
+    for mode in layer_modes(klay, c) + [dict(tail_rows_cap=1), dict(tail_rows_cap=2), dict(tail_rows_cap=3)]:
+        check_both(klay, c, leaf_probs(2, 9, 3, ("uniform", 0.05, 0.95)), what="lifted %s" % mode, **mode)
     c = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
-    check_both(klay, c, leaf_probs(5, 70, 64, ("beta", 0.5, 0.5)), what="split alias", alias_chains=True,
-               heavy_fan=4, min_segment=2)
+    for mode in layer_modes(klay, c):
+        check_both(klay, c, leaf_probs(5, 70, 64, ("beta", 0.5, 0.5)), what="split %s" % mode, heavy_fan=4, min_segment=2,
+                   **mode)
 
 
-def test_alias_chains_full_size_every_column(klay):
+def test_unary_chains_full_size_every_column(klay):
     c, p, spec = make_config("layered_3m_fwd_bwd", seed=0)
     B = p.shape[0]
     w32 = as_inputs(p, True)
     dout = np.ones((B, c.roots.shape[0]), dtype=np.float32)
-    k = build(klay, c, alias_chains=True)
+    k = build(klay, c, unary_chains=True)
     info = k.info()
-    assert info["num_edges"] == info["dag_edges"] and info["num_pad_nodes"] == 0
+    assert info["alias_top_layer"] == 0 and info["num_pad_nodes"] > 10 ** 6
     got, gd = gpu_eval(k, w32, LOG, dout)
     ref, rd = _oracle_columns(c, w32, LOG, dout)
-    print("alias full size, all columns: max|dlog| %.2e, gradient error %.3g x the plain bound" % (
-        assert_log_close(got, ref), assert_grad_plain(gd, rd, "alias grad, dout = 1")))
+    print("unary chains, full size, all columns: max|dlog| %.2e, gradient error %.3g x the plain bound" % (
+        assert_log_close(got, ref), assert_grad_plain(gd, rd, "chains grad, dout = 1")))
     k.close()
 
 
@@ -632,8 +655,8 @@ def test_maxlog_worked_examples_and_small_batches(klay, golden):
 def test_maxlog_configs(klay, name, scale, B):
     c, p, spec = make_config(name, seed=1, scale=scale, batch=B)
     print(name, "maxlog max|dlog| %.2e" % check_max(klay, c, p, what=name))
-    check_max(klay, c, p, what=name + " no_tail", no_tail=True)
-    check_max(klay, c, p, what=name + " alias", alias_chains=True)
+    for mode in layer_modes(klay, c):
+        check_max(klay, c, p, what="%s %s" % (name, mode), **mode)
 
 
 @pytest.mark.parametrize("B", [3, 64, 256])
@@ -765,7 +788,9 @@ def test_negative_literal_weights(klay, golden):
     for B in (3, 70, 300):
         _lits_case(klay, c, B, seed=10 + B)
     _lits_case(klay, c, 130, seed=1, no_tail=True)
-    _lits_case(klay, c, 130, seed=2, alias_chains=True)
+    _lits_case(klay, c, 130, seed=2, unary_chains=True)
+    _lits_case(klay, c, 130, seed=3, tail_rows_cap=250)
+    _lits_case(klay, c, 70, seed=4, tail_rows_cap=100, no_merge=True)
 
 
 def test_negative_literal_weights_default_and_call_pairing(klay):
@@ -844,9 +869,10 @@ def test_f64_small_circuits_and_options(klay, golden):
     c = layered_random(4, num_vars=48, depth=8, num_gates=1500, fanin=("geom", 2.0), groups=2, num_roots=7)
     for B in (3, 64, 65, 300):
         _f64_case(klay, c, leaf_probs(B, B, 48), "B=%d" % B)
-    _f64_case(klay, c, leaf_probs(9, 40, 48), "alias", alias_chains=True)
     _f64_case(klay, c, leaf_probs(9, 40, 48), "neg", neg=True)
-    _f64_case(klay, c, leaf_probs(9, 40, 48), "alias neg", neg=True, alias_chains=True)
+    for mode in layer_modes(klay, c):
+        _f64_case(klay, c, leaf_probs(9, 40, 48), str(mode), **mode)
+        _f64_case(klay, c, leaf_probs(9, 40, 48), "neg %s" % mode, neg=True, **mode)
     z = layered_random(2, num_vars=64, depth=6, num_gates=1200, fanin=("zipf", 1.3, 400), groups=1, num_roots=5)
     pz = leaf_probs(5, 70, 64, ("beta", 0.5, 0.5)); pz[:, ::7] = 0.0; pz[:, 3::11] = 1.0
     _f64_case(klay, z, pz, "split", backward=False, heavy_fan=8, min_segment=4)
@@ -954,7 +980,7 @@ def test_random_dags_with_random_options(klay, seed):
     rng = np.random.default_rng(1000 + seed)
     V = int(rng.integers(2, 14))
     c = _random_dag(rng, V, int(rng.integers(5, 400)), hub_share=0.25, max_fan=int(rng.choice([3, 6, 40])))
-    opts = dict(alias_chains=bool(rng.integers(2)), no_merge=bool(rng.integers(2)), no_reorder=bool(rng.integers(2)),
+    opts = dict(unary_chains=bool(rng.integers(3) == 0), tail_rows_cap=int(rng.choice([0, 0, 3, 6, 12, 30])), no_merge=bool(rng.integers(2)), no_reorder=bool(rng.integers(2)),
                 no_tail=bool(rng.integers(2)), heavy_fan=int(rng.choice([0, 2, 5, 17])), min_segment=int(rng.choice([0, 1, 3])),
                 small_batch_edges=bool(seed % 3 == 0))
     B = int(rng.choice([1, 2, 7, 33, 64, 100, 257]))
