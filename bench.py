@@ -59,7 +59,7 @@ def kernel_symbol(cls, B, edges=False):
     """rocprofv3's name for the kernel behind a profiling class (template arguments as it prints them)."""
     vec = 4 if B > 128 else (2 if B > 64 else 1)
     ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4, "bwd_prod": 5,
-           "bwd_sum_enc": 6, "bwd_softmax_one": 7}
+           "bwd_sum_enc": 6, "bwd_softmax_one": 7, "bwd_sum_mul": 8, "bwd_prod_mul": 9}
     if cls in ops:
         if B > 32:
             return "klay::stream_kernel<%d, %d>" % (ops[cls], vec)

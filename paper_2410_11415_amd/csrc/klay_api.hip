@@ -241,6 +241,8 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
     case klay::OP_PROD_BWD: launch_op<klay::OP_PROD_BWD>(a, g, grid, s); break;
     case klay::OP_SUM_H: launch_op<klay::OP_SUM_H>(a, g, grid, s); break;
     case klay::OP_SOFTMAX_H: launch_op<klay::OP_SOFTMAX_H>(a, g, grid, s); break;
+    case klay::OP_SUM_P: launch_op<klay::OP_SUM_P>(a, g, grid, s); break;
+    case klay::OP_PROD_BWD_P: launch_op<klay::OP_PROD_BWD_P>(a, g, grid, s); break;
     default: launch_op<klay::OP_SOFTMAX_BWD>(a, g, grid, s); break;
     }
 }
@@ -286,6 +288,8 @@ void launch_edge(int op, const DevPass& dp, const Geometry& g, const float* src,
     case klay::OP_PROD_BWD: launch_edge_op<klay::OP_PROD_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_SUM_H: launch_edge_op<klay::OP_SUM_H>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_SOFTMAX_H: launch_edge_op<klay::OP_SOFTMAX_H>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SUM_P: launch_edge_op<klay::OP_SUM_P>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_PROD_BWD_P: launch_edge_op<klay::OP_PROD_BWD_P>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     default: launch_edge_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
     }
 }
@@ -306,11 +310,11 @@ void launch_stream_op(const DevPass& dp, bool main_rows, bool segments, const Ge
     const int nt = (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
     if (g.vec == 4)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main);
     else if (g.vec == 2)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main);
     else
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main);
 }
 
 void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, const Geometry& g, const float* src,
@@ -324,6 +328,8 @@ void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, con
     case klay::OP_PROD_BWD: launch_stream_op<klay::OP_PROD_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_SUM_H: launch_stream_op<klay::OP_SUM_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     case klay::OP_SOFTMAX_H: launch_stream_op<klay::OP_SOFTMAX_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SUM_P: launch_stream_op<klay::OP_SUM_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_PROD_BWD_P: launch_stream_op<klay::OP_PROD_BWD_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
     }
 }
@@ -594,10 +600,9 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
     const double light_rows = (double)dp.n_main - dp.n_heavy;
     if (g.w == 64) {
         // Tiles of two or four columns per lane: the segments of split rows ride in the same launch as
-        // the main rows (same streaming walk, output to partial rows).  The softmax adjoint's segments
-        // need their owner's value row, and one-column tiles (B <= 64) measured 9% faster through the
-        // generic kernel: separate launch.
-        const bool merged = dp.n_seg > 0 && op != klay::OP_SOFTMAX_BWD && op != klay::OP_SOFTMAX_H && op != klay::OP_PROD_BWD && g.vec >= 2;
+        // the main rows (same streaming walk, output to partial rows).  One-column tiles (B <= 64) measured
+        // 9% faster through the generic kernel: separate launch.
+        const bool merged = dp.n_seg > 0 && g.vec >= 2;
         float* seg_base = seg_rows - (ptrdiff_t)dp.n_main * g.ld;     // only indexed with rows >= n_main
         if (!merged && dp.n_seg > 0 && dp.main_entries + dp.seg_entries <= kSmallPassEntries) {
             // A small layer with split rows whose segments cannot ride in the streaming launch: main rows
@@ -887,14 +892,14 @@ klay_status ensure_real_bwd(klay_circuit* c) {
 }
 
 // adjoint rows of an AND layer -> P rows, in place (see prod_parent_kernel)
-void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* below, float* gl, const Geometry& g, int B,
-                        hipStream_t s) {
+void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* below, float* gl, const float* own,
+                        const Geometry& g, int B, hipStream_t s) {
     if (n <= 0) return;                               // a layer can be empty in alias mode
     const int rpw = 64 / g.w;
     const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
 #define KLAY_PP(VEC, W) \
-    hipLaunchKernelGGL((klay::prod_parent_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, n, B, g.ld)
+    hipLaunchKernelGGL((klay::prod_parent_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, n, B, g.ld, own)
     if (g.w == 64) {
         if (g.vec == 4) KLAY_PP(4, 64);
         else if (g.vec == 2) KLAY_PP(2, 64);
@@ -1545,10 +1550,12 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         // this sweep runs layer by layer on rows of the activation buffer: bring back the values the
         // persistent forward kernel kept column-major
         if (c->last_tail_first > 0) launch_tb_to_rows(c, c->last_tail_first, L, ws + lay.tb, act, B, g.ld, s);
-        auto prod_parent = [&](int l, const float* below, float* gl) {
+        // `pre`: the rows arrive premultiplied by the pass that produced them (OP_SUM_P, OP_PROD_BWD_P), and the
+        // kernel only repairs the columns whose node value is zero; the seed's rows are plain adjoints
+        auto prod_parent = [&](int l, const float* below, float* gl, bool pre) {
             const DevLayer& d = c->dl[(size_t)l];
-            prof.begin(KLAY_K_PROD_EDGES, 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
-            launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, below, gl, g, B, s);
+            prof.begin(KLAY_K_PROD_EDGES, pre ? 4.0 * B * (double)d.n : 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
+            launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, below, gl, pre ? values(l) : nullptr, g, B, s);
             prof.end();
         };
         prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
@@ -1560,10 +1567,11 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             const DevLayer& d = c->dl[(size_t)l];
             float* dst = l - 1 == B0 ? grow(B0) : gnext;
             if ((l & 1) == 0) {
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.bwd, gcur, nullptr, nullptr, dst, seg_rows, g, B, s, prof,
-                             KLAY_K_BWD_SUM);
+                // into an AND layer: plain sums, leaving premultiplied by the nodes' own values
+                run_pass_set(klay::OP_SUM_P, klay::OP_SUM_P, d.bwd, gcur, nullptr, values(l - 1), dst, seg_rows, g, B, s,
+                             prof, KLAY_K_BWD_SUM_MUL);
             } else {
-                prod_parent(l, values(l - 1), gcur);
+                prod_parent(l, values(l - 1), gcur, l != L);
                 // the by-child plan of an AND layer carries no weighted bit: every entry is a P row
                 run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, d.bwd, gcur, nullptr, values(l - 1), dst, seg_rows, g, B, s,
                              prof, KLAY_K_BWD_PROD);
@@ -1571,11 +1579,13 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             std::swap(gcur, gnext);
         }
         // below B0 the entries of a by-child plan tell P rows (AND parents) from plain adjoint rows
-        if (B0 > 0 && (B0 & 1)) prod_parent(B0, act, grow(B0));
+        if (B0 > 0 && (B0 & 1)) prod_parent(B0, act, grow(B0), B0 != L);
         for (int l = B0 - 1; l >= 0; --l) {
-            run_pass_set(klay::OP_PROD_BWD, klay::OP_SUM, c->real_layers[(size_t)l].by_child, G, nullptr, values(l),
-                         grow(l), seg_rows, g, B, s, prof, KLAY_K_BWD_PROD);
-            if (l & 1) prod_parent(l, act, grow(l));
+            const bool and_rows = (l & 1) != 0;
+            run_pass_set(and_rows ? klay::OP_PROD_BWD_P : klay::OP_PROD_BWD, and_rows ? klay::OP_SUM_P : klay::OP_SUM,
+                         c->real_layers[(size_t)l].by_child, G, nullptr, values(l), grow(l), seg_rows, g, B, s, prof,
+                         and_rows ? KLAY_K_BWD_PROD_MUL : KLAY_K_BWD_PROD);
+            if (and_rows) prod_parent(l, act, grow(l), true);
         }
     } else {
         // The adjoint rows of an OR layer with weighted edges travel in the one-gather form (encode_h): the

@@ -15,7 +15,16 @@
 
 namespace klay {
 
-enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4, OP_PROD_BWD = 5, OP_SUM_H = 6, OP_SOFTMAX_H = 7 };
+enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4, OP_PROD_BWD = 5, OP_SUM_H = 6, OP_SOFTMAX_H = 7,
+                    OP_SUM_P = 8, OP_PROD_BWD_P = 9 };
+// ops whose walk needs the value of the output row itself, and ops whose partial results add up
+template <int OP> struct OpTraits {
+    static constexpr bool own = OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H ||
+                                OP == OP_SUM_P || OP == OP_PROD_BWD_P;
+    static constexpr bool additive = OP == OP_SUM || own;
+    static constexpr bool premul = OP == OP_SUM_P || OP == OP_PROD_BWD_P;      // the row leaves multiplied by its own value
+    static constexpr bool shares = OP == OP_PROD_BWD || OP == OP_PROD_BWD_P;   // entries are P rows of AND parents
+};
 
 // Index entries: bits 0..28 = source row, bit 31 = last edge of its output row, bit 30 = weighted
 // edge (reverse sweep only: the parent is an OR node with more than one child, so the adjoint
@@ -114,6 +123,10 @@ __device__ __forceinline__ int xcd_block(int bid, int nblocks) { return (bid & 7
 //                     The child with value `own` gets P_r / own when r has no zero child, P_r when the
 //                     child is r's one zero, nothing otherwise.  A weighted entry is a plain adjoint row
 //                     (a sum node above, or a root's dout row) and is added as it is.
+//   OP_SUM_P, OP_PROD_BWD_P   OP_SUM / OP_PROD_BWD whose output rows are AND nodes: the finished adjoint G
+//                     leaves as G * (the node's own value), lowest mantissa bit clear, which is the row P
+//                     above whenever the node has no zero child; where the own value is zero G is left
+//                     as it is for prod_parent_kernel to deal with (see there).
 // One-gather form of the softmax adjoint (log semiring, reverse sweep through an OR layer).  The adjoint
 // G_r of an OR node r with more than one child only ever reaches its children as G_r exp(N_c - N_r), so
 // the pass that produces G_r (OP_SUM_H: a plain sum, finished with the node's own value N_r) stores
@@ -132,11 +145,15 @@ __device__ __forceinline__ float decode_h(float hbits, float nc) {
     return (b & 1u) ? -v : v;
 }
 
+__device__ __forceinline__ float premultiply(float g, float n) {
+    return n != 0.0f ? __uint_as_float(__float_as_uint(g * n) & ~1u) : g;
+}
+
 template <int OP>
 __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc, bool weighted = true) {
-    if (OP == OP_SUM_H) { acc += x; return; }
+    if (OP == OP_SUM_H || OP == OP_SUM_P) { acc += x; return; }
     if (OP == OP_SOFTMAX_H) { acc += weighted ? decode_h(x, nc) : x; return; }
-    if (OP == OP_PROD_BWD) {
+    if (OpTraits<OP>::shares) {
         const uint32_t bits = __float_as_uint(x);
         const float val = __uint_as_float(bits & ~1u);
         const bool one_zero = (bits & 1u) != 0;
@@ -189,7 +206,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                                                      const float* __restrict__ own, float* __restrict__ dst,
                                                      int B, int ld, int stream_stores,
                                                      const int2* __restrict__ seg_tasks, int n_seg_tasks,
-                                                     float* __restrict__ dst_seg) {
+                                                     float* __restrict__ dst_seg,
+                                                     const int32_t* __restrict__ seg_owner, int n_main) {
     // entries per chunk: measured on the headline workload, 4 (2 for the softmax adjoint, which loads
     // three rows per entry) beat 8 / 4 by 2%: the kernel is bandwidth-bound, fewer registers per wave
     // buy more resident waves
@@ -197,7 +215,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
     // 8 (4) measured 3% faster on the power-law workload at B = 64, 4% on the headline circuit at B = 64.
     constexpr int CH = (OP == OP_SOFTMAX_BWD) ? (VEC == 1 ? 4 : 2) : (VEC == 1 ? 8 : 4);
     // the walk needs the output row's own value
-    constexpr bool OWN = OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H;
+    constexpr bool OWN = OpTraits<OP>::own;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = ((int)blockIdx.y * 64 + lane) * VEC;
@@ -253,8 +271,9 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                 load_vec<VEC>(y[i], ((ids[i] & kWeighted) && ids[i] != kSkip ? src2c : srcc) + off);
             }
             if (OWN) {
-                // (segments of split rows have no value row of their own: they need none, any row will do)
-                const int orow = seg ? 0 : (rws[i] < last_row ? rws[i] : last_row);
+                // (a segment of a split row works with the value of the row that owns it)
+                int orow = rws[i] < last_row ? rws[i] : last_row;
+                if (seg) orow = seg_owner[orow - n_main];
                 load_vec<VEC>(z[i], ownc + (size_t)orow * (size_t)ld);
             }
         }
@@ -286,6 +305,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                     o[v] = finish<OP>(acc[v], mx[v]);
                     // the adjoint of an OR node with more than one child leaves in the one-gather form
                     if (OP == OP_SUM_H && !seg && (ids[i] & kRowFlag)) o[v] = encode_h(o[v], nc[v]);
+                    if (OpTraits<OP>::premul && !seg) o[v] = premultiply(o[v], nc[v]);
                     acc[v] = identity<OP>();
                     mx[v] = -INFINITY;
                 }
@@ -316,7 +336,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
 // ---------------------------------------------------------------------------------------------
 template <int OP>
 __device__ __forceinline__ void edge_combine(float& am, float& as, float bm, float bs) {
-    if (OP == OP_SUM || OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H) am += bm;
+    if (OpTraits<OP>::additive) am += bm;
     else if (OP == OP_PROD) am *= bm;
     else if (OP == OP_MAX) am = fmaxf(am, bm);
     else {
@@ -391,7 +411,7 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
             x[i] = src[off];
             y[i] = 0.0f;
             z[i] = 0.0f;
-            if (OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H) {
+            if (OpTraits<OP>::own) {
                 const bool weighted = live && (id[i] & kWeighted) != 0;
                 // value of the parent, and of the row the entry belongs to (a segment: of its owner)
                 if (OP == OP_SOFTMAX_BWD) y[i] = (weighted ? src2 : src)[off];
@@ -411,7 +431,7 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
                 vm = live ? x[i] * wgt : 0.0f;
             } else if (OP == OP_SOFTMAX_H) {
                 vm = live ? ((id[i] & kWeighted) ? decode_h(x[i], z[i]) : x[i]) : 0.0f;
-            } else if (OP == OP_PROD_BWD) {
+            } else if (OpTraits<OP>::shares) {
                 float part = 0.0f, unused = 0.0f;
                 accumulate<OP_PROD_BWD>(part, unused, x[i], 0.0f, z[i], (id[i] & kWeighted) != 0);
                 vm = live ? part : 0.0f;
@@ -449,6 +469,7 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
                 float o = vm;
                 if (LSE) o = (vm == -INFINITY) ? -INFINITY : vm + flog(vs);
                 if (OP == OP_SUM_H && !seg && (id[i] & kRowFlag)) o = encode_h(o, z[i]);
+                if (OpTraits<OP>::premul && !seg) o = premultiply(o, z[i]);
                 dst[(size_t)rowidx[i] * (size_t)ld + c] = o;
             }
             // the open row's part stays with the last lane group
@@ -470,7 +491,7 @@ template <int OP, int VEC, int W>
 __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
     constexpr int RPW = 64 / W;                       // rows per wave
     constexpr int CH = (OP == OP_SOFTMAX_BWD) ? 4 : 8;    // sources in flight per lane
-    constexpr bool OWN = OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H;
+    constexpr bool OWN = OpTraits<OP>::own;
     const int lane = threadIdx.x & 63;
     int wave = threadIdx.x >> 6;
     if (W == 64) wave = __builtin_amdgcn_readfirstlane(wave);
@@ -537,6 +558,10 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
         if (OP == OP_SUM_H && row < a.n_main && (a.idx[end - 1] & kRowFlag)) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = encode_h(o[v], nc[v]);
+        }
+        if (OpTraits<OP>::premul && row < a.n_main) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) o[v] = premultiply(o[v], nc[v]);
         }
         float* out;
         if (row < a.n_main) out = a.dst + (size_t)(a.out_row ? a.out_row[row] : row) * a.ld + col;
@@ -969,12 +994,15 @@ __global__ __launch_bounds__(256) void tb_to_rows_kernel(const float* __restrict
 // without zero children, P itself for the one zero child of a parent with z = 1.  Exact also when
 // children are zero (leaves with p = 0 or p = 1); nothing is stored per edge.  A lane group of W lanes
 // owns one parent row.
+//   With `own` (the values of the parents themselves) the rows arrive premultiplied (OP_SUM_P,
+// OP_PROD_BWD_P): G * value where the value is not zero, which is P already, and plain G where it is
+// zero.  Then only the waves that hold a zero value walk the children, and only those columns change.
 // ---------------------------------------------------------------------------------------------
 template <int VEC, int W>
 __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restrict__ ptr,
                                                           const int32_t* __restrict__ child,
                                                           const float* __restrict__ below, float* __restrict__ g, int n,
-                                                          int B, int ld) {
+                                                          int B, int ld, const float* __restrict__ own) {
     constexpr int RPW = 64 / W;
     const int lane = threadIdx.x & 63;
     const int col = ((int)blockIdx.y * W + (lane % W)) * VEC;
@@ -982,6 +1010,14 @@ __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restr
     const int64_t row64 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / W;
     if (row64 >= n) return;
     const int row = (int)row64;
+    float nv[VEC];
+    if (own) {
+        load_vec<VEC>(nv, own + (size_t)row * ld + col);
+        bool zero_here = false;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) zero_here = zero_here || nv[v] == 0.0f;
+        if (!__any(zero_here)) return;
+    }
     const int beg = ptr[row], end = ptr[row + 1];
     float q[VEC], z[VEC], gr[VEC];
 #pragma unroll
@@ -1012,6 +1048,7 @@ __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restr
     for (int v = 0; v < VEC; ++v) {
         const float val = z[v] >= 2.0f ? 0.0f : gr[v] * q[v];
         p[v] = __uint_as_float((__float_as_uint(val) & ~1u) | (z[v] == 1.0f ? 1u : 0u));
+        if (own && nv[v] != 0.0f) p[v] = gr[v];          // premultiplied already
     }
     store_vec<VEC>(g + (size_t)row * ld + col, p);
 }
