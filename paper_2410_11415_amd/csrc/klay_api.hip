@@ -76,7 +76,7 @@ struct DevPass {
     int64_t n_src = 0;                           // distinct source rows the pass reads
 };
 
-// Log-semiring reverse sweep (handles without aliasing): adjoints of OR layers in the one-gather form.
+// Log-semiring reverse sweep: adjoints of OR layers travel in the one-gather form (off: the two-gather step).
 constexpr bool kOneGather = true;
 
 struct DevLayer {
@@ -894,7 +894,7 @@ klay_status ensure_real_bwd(klay_circuit* c) {
 // adjoint rows of an AND layer -> P rows, in place (see prod_parent_kernel)
 void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* below, float* gl, const float* own,
                         const Geometry& g, int B, hipStream_t s) {
-    if (n <= 0) return;                               // a layer can be empty in alias mode
+    if (n <= 0) return;                               // a layer without chain nodes can be empty
     const int rpw = 64 / g.w;
     const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);

@@ -24,6 +24,8 @@ template <int OP> struct OpTraits {
     static constexpr bool additive = OP == OP_SUM || own;
     static constexpr bool premul = OP == OP_SUM_P || OP == OP_PROD_BWD_P;      // the row leaves multiplied by its own value
     static constexpr bool shares = OP == OP_PROD_BWD || OP == OP_PROD_BWD_P;   // entries are P rows of AND parents
+    // a segment of a split row needs the value of the row that owns it (the others only use it to finish a row)
+    static constexpr bool seg_own = OP == OP_SOFTMAX_BWD || OP == OP_SOFTMAX_H || shares;
 };
 
 // Index entries: bits 0..28 = source row, bit 31 = last edge of its output row, bit 30 = weighted
@@ -271,9 +273,9 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                 load_vec<VEC>(y[i], ((ids[i] & kWeighted) && ids[i] != kSkip ? src2c : srcc) + off);
             }
             if (OWN) {
-                // (a segment of a split row works with the value of the row that owns it)
+                // (a segment of a split row works with the value of the row that owns it, if with any)
                 int orow = rws[i] < last_row ? rws[i] : last_row;
-                if (seg) orow = seg_owner[orow - n_main];
+                if (seg) orow = OpTraits<OP>::seg_own ? seg_owner[orow - n_main] : 0;
                 load_vec<VEC>(z[i], ownc + (size_t)orow * (size_t)ld);
             }
         }

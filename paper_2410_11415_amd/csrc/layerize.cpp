@@ -454,7 +454,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         if (level < B0) return (int32_t)(plan.row0[(size_t)h[(size_t)c]] + pos_real[(size_t)c]);
         return at(c, level);
     };
-    // ordering key of a child: its position in the layer below, or (alias mode) its relative
+    // ordering key of a child: its position in the layer below, or (below the boundary layer) its relative
     // position within its own layer scaled to the width of the layer below
     auto child_key = [&](int32_t c, int32_t level) -> double {
         if (level >= B0) return (double)at(c, level);
