@@ -2,12 +2,14 @@
 
 ``binding`` holds the ctypes layer over ``lib/libklay.so``; ``build`` compiles it with hipcc.
 """
-from .binding import (KLAY_AND, KLAY_FALSE, KLAY_LIT, KLAY_LOG, KLAY_MAXLOG, KLAY_OR, KLAY_REAL, KLAY_TRUE, Builder, Circuit,
+from .binding import (KLAY_AND, KLAY_FALSE, KLAY_LIT, KLAY_LOG, KLAY_MAXLOG, KLAY_OR, KLAY_REAL, KLAY_STATIC_WORKSPACE_BYTES, KLAY_TRUE,
+                      Builder, Circuit,
                       KlayError, klay_backward, klay_backward_f64, klay_backward_lits, klay_build, klay_destroy, klay_forward,
                       klay_forward_f64, klay_forward_lits, klay_forward_static, klay_last_error,
                       library_path, load)
 
-__all__ = ["KLAY_AND", "KLAY_FALSE", "KLAY_LIT", "KLAY_LOG", "KLAY_MAXLOG", "KLAY_OR", "KLAY_REAL", "KLAY_TRUE", "Builder", "Circuit",
+__all__ = ["KLAY_AND", "KLAY_FALSE", "KLAY_LIT", "KLAY_LOG", "KLAY_MAXLOG", "KLAY_OR", "KLAY_REAL", "KLAY_STATIC_WORKSPACE_BYTES",
+           "KLAY_TRUE", "Builder", "Circuit",
            "KlayError", "klay_backward", "klay_backward_f64", "klay_backward_lits", "klay_build", "klay_destroy", "klay_forward",
            "klay_forward_f64", "klay_forward_lits", "klay_forward_static", "klay_last_error",
            "library_path", "load"]
