@@ -192,6 +192,10 @@ def test_configs_full_size_every_column(klay, name, semiring):
     w32 = as_inputs(p, semiring == LOG)
     dout = np.ones((B, c.roots.shape[0]), dtype=np.float32)
     k = build(klay, c)
+    # the default layerization: padding-free up to layer A, which lies strictly inside the layered circuits (their
+    # narrow top runs in the persistent kernels) and is the top layer of the power-law ones (no narrow fan-ins)
+    A, L = k.info()["alias_top_layer"], k.num_layers
+    assert (A == L and k.info()["tail_first_layer"] == 0) if name.startswith("powerlaw") else (0 < A < L and k.info()["tail_first_layer"] == A + 1)
     got, gd = gpu_eval(k, w32, semiring, dout)
     if semiring == LOG:
         ref, rd = _oracle_columns(c, w32, LOG, dout)
