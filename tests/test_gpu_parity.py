@@ -979,7 +979,7 @@ def _random_dag(rng, V, n_gates, hub_share, max_fan):
     return b.finish(roots)
 
 
-@pytest.mark.parametrize("seed", range(48))
+@pytest.mark.parametrize("seed", range(96))
 def test_random_dags_with_random_options(klay, seed):
     rng = np.random.default_rng(1000 + seed)
     V = int(rng.integers(2, 14))
