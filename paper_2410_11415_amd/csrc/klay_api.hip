@@ -25,8 +25,9 @@ constexpr size_t kStaticWorkspaceBytes = KLAY_STATIC_WORKSPACE_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
 
 // Layers with split rows and at most this many index entries run main rows and segments in one generic
-// launch (measured on the power-law workload at B = 64: 60000 and 150000 both give 0.73 ms against
-// 0.81 ms without, 400000 gives 0.76 ms).
+// launch (measured at B = 64 on the two power-law workloads, ms per step: this threshold 0.69 / 0.76, ten times
+// larger 0.66 / 0.80, every layer 0.68 / 0.92; with the layerization of unary chains throughout 60000 and
+// 150000 both gave 0.73 against 0.81 without the rule).
 constexpr int64_t kSmallPassEntries = 100000;
 
 namespace {
@@ -563,8 +564,9 @@ klay_status upload(klay_circuit* c) {
 }
 
 // Algorithmic bytes (no-reuse model) of a gather-reduce over `rows` output rows with `entries` index
-// entries: every entry gathers one row (two in the softmax adjoint), every output row is written once
-// (and, in the softmax adjoint, reads its own value row), plus the index entries themselves.
+// entries: every entry gathers one row (two in the two-gather softmax adjoint), every output row is written
+// once (and, in the reverse-sweep ops other than the plain sum, reads its own value row), plus the index
+// entries themselves.
 double pass_bytes(int op, double entries, double rows, int B) {
     const double per_entry = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
     const double per_row = (op == klay::OP_SUM || op == klay::OP_PROD || op == klay::OP_LSE || op == klay::OP_MAX) ? 1.0 : 2.0;
@@ -930,7 +932,7 @@ Workspace64 workspace_layout64(const klay_circuit* c, int ld) {
     w.act = take((size_t)p.num_nodes * ld);
     w.wT = take((size_t)std::max(1, p.num_vars) * ld);
     w.seg_rows = take((size_t)std::max<int64_t>(std::max(p.max_fwd_seg, p.max_bwd_seg), 1) * ld);
-    // adjoints: one row per node of the layers 0 .. alias_top, two rows sets for the layers above
+    // adjoints: one row per node of the layers 0 .. alias_top, two sets of rows for the layers above
     w.g0 = take((size_t)p.row0[(size_t)p.alias_top + 1] * ld);
     w.g1 = take((size_t)top_layer_rows(p) * ld);
     w.g2 = take((size_t)top_layer_rows(p) * ld);

@@ -17,7 +17,8 @@ namespace klay {
 
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4, OP_PROD_BWD = 5, OP_SUM_H = 6, OP_SOFTMAX_H = 7,
                     OP_SUM_P = 8, OP_PROD_BWD_P = 9 };
-// ops whose walk needs the value of the output row itself, and ops whose partial results add up
+// what the ops have in common: `own` = the walk needs the value of the output row itself, `additive` = partial
+// results add up
 template <int OP> struct OpTraits {
     static constexpr bool own = OP == OP_SOFTMAX_BWD || OP == OP_PROD_BWD || OP == OP_SUM_H || OP == OP_SOFTMAX_H ||
                                 OP == OP_SUM_P || OP == OP_PROD_BWD_P;
@@ -41,7 +42,7 @@ struct PassArgs {
     const uint32_t* idx;       // index entries (readable up to 16 entries past the end)
     const float* src;          // [*, ld] source rows (values of the layer below, adjoints, or partials)
     const float* src2;         // OP_SOFTMAX_BWD: values N_l of the parents, same row index as src
-    const float* own;          // OP_SOFTMAX_BWD: values N_{l-1} of the output rows
+    const float* own;          // ops with OpTraits::own: values of the output rows themselves
     const int32_t* seg_owner;  // output row owning segment i (rows >= n_main), may be null
     const int32_t* out_row;    // optional output row map for rows < n_main (combine pass)
     float* dst;                // output rows for rows < n_main
