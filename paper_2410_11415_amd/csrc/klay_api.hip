@@ -111,7 +111,7 @@ Geometry geometry(int B) {
 size_t align_floats(size_t n) { return (n + 63) / 64 * 64; }
 
 struct Workspace {
-    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, g2 = 0, tb = 0, total = 0;   // offsets in floats
+    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, g2 = 0, tb = 0, flags = 0, total = 0;   // offsets in floats
 };
 
 struct EventRec {
@@ -194,6 +194,8 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
         w.g0 = off; off += align_floats((size_t)p.row0[(size_t)p.alias_top + 1] * g.ld);
         w.g1 = off; off += align_floats((size_t)top_layer_rows(p) * g.ld);
         w.g2 = off; off += align_floats((size_t)top_layer_rows(p) * g.ld);
+        // one word per layer: the real-semiring sweep's "a node value of this product layer is zero" flags
+        w.flags = off; off += align_floats((size_t)p.num_layers + 1);
     }
     w.total = off;
     return w;
@@ -251,7 +253,7 @@ void launch_pass(int op, klay::PassArgs a, const Geometry& g, hipStream_t s) {
 // Small batches (B <= 32): the lanes = edges kernel over the main rows and the segments of a pass.
 template <int OP, int LPR>
 void launch_edge_one(const DevPass& dp, const float* src, const float* src2, const float* own, float* dst,
-                     float* dst_seg, int B, int ld, hipStream_t s) {
+                     float* dst_seg, int B, int ld, hipStream_t s, int* zf) {
     constexpr int EPW = 64 / LPR, CH = EPW >= 16 ? 4 : 8;
     const int64_t entries = dp.main_entries + dp.n_heavy;
     // a wave takes about two rounds of its gathers: CH steps of EPW entries each
@@ -263,35 +265,35 @@ void launch_edge_one(const DevPass& dp, const float* src, const float* src2, con
     dim3 grid((unsigned)((waves + 3) / 4));
     hipLaunchKernelGGL((klay::edge_kernel<OP, LPR>), grid, dim3(256), 0, s, reinterpret_cast<const int2*>(dp.tasks),
                        dp.n_tasks, span, dp.idx, src, src2, own, dst, B, ld, reinterpret_cast<const int2*>(dp.seg_tasks),
-                       dp.n_seg_tasks, dp.seg_owner, dp.n_main, dst_seg);
+                       dp.n_seg_tasks, dp.seg_owner, dp.n_main, dst_seg, zf);
 }
 
 template <int OP>
 void launch_edge_op(const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
-                    float* dst, float* dst_seg, int B, hipStream_t s) {
+                    float* dst, float* dst_seg, int B, hipStream_t s, int* zf) {
     switch (g.w) {
-    case 32: launch_edge_one<OP, 32>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
-    case 16: launch_edge_one<OP, 16>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
-    case 8: launch_edge_one<OP, 8>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
-    case 4: launch_edge_one<OP, 4>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
-    case 2: launch_edge_one<OP, 2>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
-    default: launch_edge_one<OP, 1>(dp, src, src2, own, dst, dst_seg, B, g.ld, s); break;
+    case 32: launch_edge_one<OP, 32>(dp, src, src2, own, dst, dst_seg, B, g.ld, s, zf); break;
+    case 16: launch_edge_one<OP, 16>(dp, src, src2, own, dst, dst_seg, B, g.ld, s, zf); break;
+    case 8: launch_edge_one<OP, 8>(dp, src, src2, own, dst, dst_seg, B, g.ld, s, zf); break;
+    case 4: launch_edge_one<OP, 4>(dp, src, src2, own, dst, dst_seg, B, g.ld, s, zf); break;
+    case 2: launch_edge_one<OP, 2>(dp, src, src2, own, dst, dst_seg, B, g.ld, s, zf); break;
+    default: launch_edge_one<OP, 1>(dp, src, src2, own, dst, dst_seg, B, g.ld, s, zf); break;
     }
 }
 
 void launch_edge(int op, const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
-                 float* dst, float* dst_seg, int B, hipStream_t s) {
+                 float* dst, float* dst_seg, int B, hipStream_t s, int* zf) {
     switch (op) {
-    case klay::OP_SUM: launch_edge_op<klay::OP_SUM>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_PROD: launch_edge_op<klay::OP_PROD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_LSE: launch_edge_op<klay::OP_LSE>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_MAX: launch_edge_op<klay::OP_MAX>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_PROD_BWD: launch_edge_op<klay::OP_PROD_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_SUM_H: launch_edge_op<klay::OP_SUM_H>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_SOFTMAX_H: launch_edge_op<klay::OP_SOFTMAX_H>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_SUM_P: launch_edge_op<klay::OP_SUM_P>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_PROD_BWD_P: launch_edge_op<klay::OP_PROD_BWD_P>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
-    default: launch_edge_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SUM: launch_edge_op<klay::OP_SUM>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_PROD: launch_edge_op<klay::OP_PROD>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_LSE: launch_edge_op<klay::OP_LSE>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_MAX: launch_edge_op<klay::OP_MAX>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_PROD_BWD: launch_edge_op<klay::OP_PROD_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SUM_H: launch_edge_op<klay::OP_SUM_H>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SOFTMAX_H: launch_edge_op<klay::OP_SOFTMAX_H>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SUM_P: launch_edge_op<klay::OP_SUM_P>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_PROD_BWD_P: launch_edge_op<klay::OP_PROD_BWD_P>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    default: launch_edge_op<klay::OP_SOFTMAX_BWD>(dp, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     }
 }
 
@@ -300,7 +302,7 @@ void launch_edge(int op, const DevPass& dp, const Geometry& g, const float* src,
 // numbered after the main rows.
 template <int OP>
 void launch_stream_op(const DevPass& dp, bool main_rows, bool segments, const Geometry& g, const float* src,
-                      const float* src2, const float* own, float* dst, float* dst_seg, int B, hipStream_t s) {
+                      const float* src2, const float* own, float* dst, float* dst_seg, int B, hipStream_t s, int* zf) {
     const int2* tasks = reinterpret_cast<const int2*>(dp.tasks);
     const int2* seg_tasks = reinterpret_cast<const int2*>(dp.seg_tasks);
     int n_tasks = main_rows ? dp.n_tasks : 0;
@@ -311,27 +313,27 @@ void launch_stream_op(const DevPass& dp, bool main_rows, bool segments, const Ge
     const int nt = (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
     if (g.vec == 4)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 4>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main, zf);
     else if (g.vec == 2)
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 2>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main, zf);
     else
-        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main);
+        hipLaunchKernelGGL((klay::stream_kernel<OP, 1>), grid, dim3(256), 0, s, tasks, n_tasks, dp.idx, src, src2, own, dst, B, g.ld, nt, seg_tasks, n_seg_tasks, dst_seg, dp.seg_owner, dp.n_main, zf);
 }
 
 void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, const Geometry& g, const float* src,
-                   const float* src2, const float* own, float* dst, float* dst_seg, int B, hipStream_t s) {
+                   const float* src2, const float* own, float* dst, float* dst_seg, int B, hipStream_t s, int* zf) {
     if ((main_rows ? dp.n_tasks : 0) + (segments ? dp.n_seg_tasks : 0) <= 0) return;
     switch (op) {
-    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_MAX: launch_stream_op<klay::OP_MAX>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_PROD_BWD: launch_stream_op<klay::OP_PROD_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_SUM_H: launch_stream_op<klay::OP_SUM_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_SOFTMAX_H: launch_stream_op<klay::OP_SOFTMAX_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_SUM_P: launch_stream_op<klay::OP_SUM_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    case klay::OP_PROD_BWD_P: launch_stream_op<klay::OP_PROD_BWD_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
-    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s); break;
+    case klay::OP_SUM: launch_stream_op<klay::OP_SUM>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_PROD: launch_stream_op<klay::OP_PROD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_LSE: launch_stream_op<klay::OP_LSE>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_MAX: launch_stream_op<klay::OP_MAX>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_PROD_BWD: launch_stream_op<klay::OP_PROD_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SUM_H: launch_stream_op<klay::OP_SUM_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SOFTMAX_H: launch_stream_op<klay::OP_SOFTMAX_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SUM_P: launch_stream_op<klay::OP_SUM_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_PROD_BWD_P: launch_stream_op<klay::OP_PROD_BWD_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     }
 }
 
@@ -583,9 +585,10 @@ double pass_min_bytes(int op, double entries, double rows, double n_src, int B) 
 // launch is timed under `cls`, the launches that serve split rows under KLAY_K_SPLIT.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
                   const float* own, float* dst, float* seg_rows, const Geometry& g, int B, hipStream_t s,
-                  Profiler& prof, int cls) {
+                  Profiler& prof, int cls, int* zero_flag = nullptr) {
     const bool edges = prof.c->small_batch_edges;
     klay::PassArgs a{};
+    a.zero_flag = zero_flag;
     a.ptr = dp.ptr;
     a.idx = dp.idx;
     a.src = src;
@@ -623,7 +626,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         double min_bytes = pass_min_bytes(op, (double)dp.main_entries, light_rows, (double)dp.n_src, B);
         if (merged) min_bytes += pass_min_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, 0.0, B);
         prof.begin(cls, bytes, min_bytes);
-        launch_stream(op, dp, true, merged, g, src, src2, own, dst, seg_base, B, s);
+        launch_stream(op, dp, true, merged, g, src, src2, own, dst, seg_base, B, s, zero_flag);
         prof.end();
         if (dp.n_seg > 0 && !merged) {
             prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B),
@@ -638,7 +641,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         prof.begin(cls, pass_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, B),
                    pass_min_bytes(op, (double)(dp.main_entries + dp.seg_entries), light_rows + dp.n_seg, (double)dp.n_src, B));
         if (edges) {
-            launch_edge(op, dp, g, src, src2, own, dst, seg_rows - (ptrdiff_t)dp.n_main * g.ld, B, s);
+            launch_edge(op, dp, g, src, src2, own, dst, seg_rows - (ptrdiff_t)dp.n_main * g.ld, B, s, zero_flag);
         } else {
             a.row_begin = 0;
             launch_pass(op, a, g, s);
@@ -650,7 +653,8 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         cmb.ptr = dp.comb_ptr;
         cmb.idx = dp.comb_idx;
         cmb.src = seg_rows;
-        cmb.own = own;               // OP_SUM_H: the value rows of the nodes the combine pass writes
+        cmb.own = own;               // OP_SUM_H, OP_SUM_P: the value rows of the nodes the combine pass writes
+        cmb.zero_flag = zero_flag;
         cmb.out_row = dp.comb_row;
         cmb.dst = dst;
         cmb.dst_seg = nullptr;
@@ -895,13 +899,13 @@ klay_status ensure_real_bwd(klay_circuit* c) {
 
 // adjoint rows of an AND layer -> P rows, in place (see prod_parent_kernel)
 void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* below, float* gl, const float* own,
-                        const Geometry& g, int B, hipStream_t s) {
+                        const int* zero_flag, const Geometry& g, int B, hipStream_t s) {
     if (n <= 0) return;                               // a layer without chain nodes can be empty
     const int rpw = 64 / g.w;
     const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
 #define KLAY_PP(VEC, W) \
-    hipLaunchKernelGGL((klay::prod_parent_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, n, B, g.ld, own)
+    hipLaunchKernelGGL((klay::prod_parent_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, n, B, g.ld, own, zero_flag)
     if (g.w == 64) {
         if (g.vec == 4) KLAY_PP(4, 64);
         else if (g.vec == 2) KLAY_PP(2, 64);
@@ -1554,10 +1558,13 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (c->last_tail_first > 0) launch_tb_to_rows(c, c->last_tail_first, L, ws + lay.tb, act, B, g.ld, s);
         // `pre`: the rows arrive premultiplied by the pass that produced them (OP_SUM_P, OP_PROD_BWD_P), and the
         // kernel only repairs the columns whose node value is zero; the seed's rows are plain adjoints
+        // flags[l]: raised by the pass that writes the rows of product layer l when it meets a node value of zero
+        int* flags = reinterpret_cast<int*>(ws + lay.flags);
+        hipLaunchKernelGGL(klay::fill_row_kernel, dim3((unsigned)((L + 256) / 256)), dim3(256), 0, s, ws + lay.flags, L + 1, 0.0f);
         auto prod_parent = [&](int l, const float* below, float* gl, bool pre) {
             const DevLayer& d = c->dl[(size_t)l];
-            prof.begin(KLAY_K_PROD_EDGES, pre ? 4.0 * B * (double)d.n : 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
-            launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, below, gl, pre ? values(l) : nullptr, g, B, s);
+            prof.begin(KLAY_K_PROD_EDGES, pre ? 4.0 : 4.0 * B * ((double)d.e + 2.0 * (double)d.n));
+            launch_prod_parent(c->real_layers[(size_t)l], (int)d.n, below, gl, pre ? values(l) : nullptr, flags + l, g, B, s);
             prof.end();
         };
         prof.begin(KLAY_K_SEED, 4.0 * B * R + 4.0 * B * (double)c->dl[(size_t)L].n);
@@ -1571,7 +1578,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             if ((l & 1) == 0) {
                 // into an AND layer: plain sums, leaving premultiplied by the nodes' own values
                 run_pass_set(klay::OP_SUM_P, klay::OP_SUM_P, d.bwd, gcur, nullptr, values(l - 1), dst, seg_rows, g, B, s,
-                             prof, KLAY_K_BWD_SUM_MUL);
+                             prof, KLAY_K_BWD_SUM_MUL, flags + (l - 1));
             } else {
                 prod_parent(l, values(l - 1), gcur, l != L);
                 // the by-child plan of an AND layer carries no weighted bit: every entry is a P row
@@ -1586,7 +1593,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
             const bool and_rows = (l & 1) != 0;
             run_pass_set(and_rows ? klay::OP_PROD_BWD_P : klay::OP_PROD_BWD, and_rows ? klay::OP_SUM_P : klay::OP_SUM,
                          c->real_layers[(size_t)l].by_child, G, nullptr, values(l), grow(l), seg_rows, g, B, s, prof,
-                         and_rows ? KLAY_K_BWD_PROD_MUL : KLAY_K_BWD_PROD);
+                         and_rows ? KLAY_K_BWD_PROD_MUL : KLAY_K_BWD_PROD, and_rows ? flags + l : nullptr);
             if (and_rows) prod_parent(l, act, grow(l), true);
         }
     } else {

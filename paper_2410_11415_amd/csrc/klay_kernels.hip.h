@@ -53,6 +53,7 @@ struct PassArgs {
     int32_t B;
     int32_t ld;
     int32_t iters;             // row groups per wave
+    int* zero_flag;            // OP_SUM_P, OP_PROD_BWD_P: set to 1 when an output row's own value is zero in some column
 };
 
 // s_waitcnt immediate (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8) that waits
@@ -210,7 +211,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                                                      int B, int ld, int stream_stores,
                                                      const int2* __restrict__ seg_tasks, int n_seg_tasks,
                                                      float* __restrict__ dst_seg,
-                                                     const int32_t* __restrict__ seg_owner, int n_main) {
+                                                     const int32_t* __restrict__ seg_owner, int n_main,
+                                                     int* __restrict__ zero_flag) {
     // entries per chunk: measured on the headline workload, 4 (2 for the softmax adjoint, which loads
     // three rows per entry) beat 8 / 4 by 2%: the kernel is bandwidth-bound, fewer registers per wave
     // buy more resident waves
@@ -308,7 +310,10 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
                     o[v] = finish<OP>(acc[v], mx[v]);
                     // the adjoint of an OR node with more than one child leaves in the one-gather form
                     if (OP == OP_SUM_H && !seg && (ids[i] & kRowFlag)) o[v] = encode_h(o[v], nc[v]);
-                    if (OpTraits<OP>::premul && !seg) o[v] = premultiply(o[v], nc[v]);
+                    if (OpTraits<OP>::premul && !seg) {
+                        if (nc[v] == 0.0f && zero_flag) *zero_flag = 1;          // this layer needs prod_parent_kernel's repair
+                        o[v] = premultiply(o[v], nc[v]);
+                    }
                     acc[v] = identity<OP>();
                     mx[v] = -INFINITY;
                 }
@@ -358,7 +363,7 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
                                                    float* __restrict__ dst, int B, int ld,
                                                    const int2* __restrict__ seg_tasks, int n_seg_tasks,
                                                    const int32_t* __restrict__ seg_owner, int n_main,
-                                                   float* __restrict__ dst_seg) {
+                                                   float* __restrict__ dst_seg, int* __restrict__ zero_flag) {
     constexpr int EPW = 64 / LPR;                 // entries per step
     constexpr int CH = EPW >= 16 ? 4 : 8;         // steps whose gathers are in flight together
     constexpr bool LSE = OP == OP_LSE;
@@ -472,7 +477,10 @@ __global__ __launch_bounds__(256) void edge_kernel(const int2* __restrict__ task
                 float o = vm;
                 if (LSE) o = (vm == -INFINITY) ? -INFINITY : vm + flog(vs);
                 if (OP == OP_SUM_H && !seg && (id[i] & kRowFlag)) o = encode_h(o, z[i]);
-                if (OpTraits<OP>::premul && !seg) o = premultiply(o, z[i]);
+                if (OpTraits<OP>::premul && !seg) {
+                    if (z[i] == 0.0f && zero_flag) *zero_flag = 1;
+                    o = premultiply(o, z[i]);
+                }
                 dst[(size_t)rowidx[i] * (size_t)ld + c] = o;
             }
             // the open row's part stays with the last lane group
@@ -564,7 +572,10 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
         }
         if (OpTraits<OP>::premul && row < a.n_main) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) o[v] = premultiply(o[v], nc[v]);
+            for (int v = 0; v < VEC; ++v) {
+                if (nc[v] == 0.0f && a.zero_flag) *a.zero_flag = 1;
+                o[v] = premultiply(o[v], nc[v]);
+            }
         }
         float* out;
         if (row < a.n_main) out = a.dst + (size_t)(a.out_row ? a.out_row[row] : row) * a.ld + col;
@@ -999,13 +1010,15 @@ __global__ __launch_bounds__(256) void tb_to_rows_kernel(const float* __restrict
 // owns one parent row.
 //   With `own` (the values of the parents themselves) the rows arrive premultiplied (OP_SUM_P,
 // OP_PROD_BWD_P): G * value where the value is not zero, which is P already, and plain G where it is
-// zero.  Then only the waves that hold a zero value walk the children, and only those columns change.
+// zero.  Then only the waves that hold a zero value walk the children, and only those columns change; that pass
+// also raises zero_flag when it meets a zero value, and a launch that finds it down returns at once.
 // ---------------------------------------------------------------------------------------------
 template <int VEC, int W>
 __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restrict__ ptr,
                                                           const int32_t* __restrict__ child,
                                                           const float* __restrict__ below, float* __restrict__ g, int n,
-                                                          int B, int ld, const float* __restrict__ own) {
+                                                          int B, int ld, const float* __restrict__ own,
+                                                          const int* __restrict__ zero_flag) {
     constexpr int RPW = 64 / W;
     const int lane = threadIdx.x & 63;
     const int col = ((int)blockIdx.y * W + (lane % W)) * VEC;
@@ -1014,6 +1027,7 @@ __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restr
     if (row64 >= n) return;
     const int row = (int)row64;
     float nv[VEC];
+    if (own && zero_flag && *zero_flag == 0) return;          // the pass that wrote the rows met no zero value: nothing to repair
     if (own) {
         load_vec<VEC>(nv, own + (size_t)row * ld + col);
         bool zero_here = false;
