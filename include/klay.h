@@ -49,7 +49,9 @@ enum { KLAY_LIT = 0, KLAY_AND = 1, KLAY_OR = 2, KLAY_TRUE = 3, KLAY_FALSE = 4 };
 /* Build-time options; zero-initialise and override.  0 means "library default". */
 typedef struct klay_options {
     int32_t no_reorder;      /* 1: keep nodes of a layer in input-id order (no locality sort)     */
-    int32_t heavy_fan;       /* rows with more sources than this are split (default 48)           */
+    int32_t heavy_fan;       /* rows with more sources than this are split (default 48); a pass that
+                                splits rows anyway and whose unsplit rows are few (under 2e5 entries) with a
+                                tenth or more of them in rows longer than half of it splits from half on */
     int32_t min_segment;     /* smallest split segment, in edges (default 24)                     */
     int32_t no_tail;         /* 1: one launch per layer also for the narrow top layers            */
     int32_t unary_chains;    /* 1: the paper's layerization throughout: an edge that skips layers goes through
