@@ -581,6 +581,31 @@ double pass_min_bytes(int op, double entries, double rows, double n_src, int B) 
     return 4.0 * B * f * (n_src + rows) + 4.0 * (entries + rows);
 }
 
+// Combine pass of the split rows: a workgroup per split row for batches wider than 32 columns
+// (combine_kernel), the generic kernel otherwise.
+template <int OP>
+void launch_combine_op(const klay::PassArgs& a, const Geometry& g, hipStream_t s) {
+    constexpr int NW = 8;
+    dim3 grid((unsigned)a.n_main, (unsigned)g.tiles);
+    if (g.vec == 4) hipLaunchKernelGGL((klay::combine_kernel<OP, 4, NW>), grid, dim3(NW * 64), 0, s, a);
+    else if (g.vec == 2) hipLaunchKernelGGL((klay::combine_kernel<OP, 2, NW>), grid, dim3(NW * 64), 0, s, a);
+    else hipLaunchKernelGGL((klay::combine_kernel<OP, 1, NW>), grid, dim3(NW * 64), 0, s, a);
+}
+
+void launch_combine(int op, const klay::PassArgs& a, const Geometry& g, hipStream_t s) {
+    if (a.n_main <= 0) return;
+    if (g.w != 64) { launch_pass(op, a, g, s); return; }
+    switch (op) {
+    case klay::OP_SUM: launch_combine_op<klay::OP_SUM>(a, g, s); break;
+    case klay::OP_PROD: launch_combine_op<klay::OP_PROD>(a, g, s); break;
+    case klay::OP_LSE: launch_combine_op<klay::OP_LSE>(a, g, s); break;
+    case klay::OP_MAX: launch_combine_op<klay::OP_MAX>(a, g, s); break;
+    case klay::OP_SUM_H: launch_combine_op<klay::OP_SUM_H>(a, g, s); break;
+    case klay::OP_SUM_P: launch_combine_op<klay::OP_SUM_P>(a, g, s); break;
+    default: launch_pass(op, a, g, s); break;
+    }
+}
+
 // One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.  The main
 // launch is timed under `cls`, the launches that serve split rows under KLAY_K_SPLIT.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
@@ -664,7 +689,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         cmb.B = B;
         cmb.ld = g.ld;
         prof.begin(KLAY_K_SPLIT, pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B));
-        launch_pass(combine_op, cmb, g, s);
+        launch_combine(combine_op, cmb, g, s);
         prof.end();
     }
 }

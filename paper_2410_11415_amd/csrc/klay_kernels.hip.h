@@ -585,6 +585,83 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Combine pass of split rows for B > 32: one workgroup of NW waves per split row.  The partial rows of a
+// split row (up to a few hundred for the widest rows) are dealt to the waves in chunks of 8, every wave
+// reduces its share with all its gathers of a chunk in flight, and wave 0 folds the NW states in wave
+// order (so the result does not depend on timing) and finishes the row like pass_kernel does.  A single
+// wave would walk the widest row 8 partial rows at a time, and the launch lasts as long as that walk.
+// Arguments as for pass_kernel's combine use: ptr / idx = combine lists, src = partial rows, out_row = the
+// rows to write, n_main = number of split rows.
+// ---------------------------------------------------------------------------------------------
+template <int OP, int VEC, int NW>
+__global__ __launch_bounds__(NW * 64) void combine_kernel(PassArgs a) {
+    constexpr int CH = 8;
+    constexpr bool LSE = OP == OP_LSE;
+    __shared__ float part_v[NW][64 * VEC];
+    __shared__ float part_m[LSE ? NW : 1][LSE ? 64 * VEC : 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int row = (int)blockIdx.x;
+    const int colu = ((int)blockIdx.y * 64 + lane) * VEC;
+    const int col = colu < a.B ? colu : 0;                 // lanes past the batch work on column 0 and store nothing
+    const int beg = a.ptr[row], end = a.ptr[row + 1];
+    float acc[VEC], mx[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { acc[v] = identity<OP>(); mx[v] = -INFINITY; }
+    for (int j = beg + wave * CH; j < end; j += NW * CH) {
+        float x[CH][VEC];
+#pragma unroll
+        for (int i = 0; i < CH; ++i)                         // padded list: always in bounds
+            load_vec<VEC>(x[i], a.src + (size_t)(a.idx[j + i] & kIdMask) * a.ld + col);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool live = j + i < end;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) accumulate<OP>(acc[v], mx[v], live ? x[i][v] : dead_value<OP>(), 0.0f, 0.0f, false);
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            part_v[wave][lane * VEC + v] = acc[v];
+            if (LSE) part_m[wave][lane * VEC + v] = mx[v];
+        }
+    }
+    __syncthreads();
+    if (wave > 0 || colu >= a.B) return;
+    for (int w = 1; w < NW; ++w) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const float ov = part_v[w][lane * VEC + v];
+            if (LSE) {
+                const float om = part_m[w][lane * VEC + v];
+                edge_combine<OP>(mx[v], acc[v], om, ov);
+            } else {
+                float unused = 0.0f;
+                edge_combine<OP>(acc[v], unused, ov, 0.0f);
+            }
+        }
+    }
+    const int out_row = a.out_row[row];
+    float o[VEC], nc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { o[v] = finish<OP>(acc[v], mx[v]); nc[v] = 0.0f; }
+    if (OP == OP_SUM_H || OP == OP_SUM_P) load_vec<VEC>(nc, a.own + (size_t)out_row * a.ld + col);
+    if (OP == OP_SUM_H && (a.idx[end - 1] & kRowFlag)) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) o[v] = encode_h(o[v], nc[v]);
+    }
+    if (OP == OP_SUM_P) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            if (nc[v] == 0.0f && a.zero_flag) *a.zero_flag = 1;
+            o[v] = premultiply(o[v], nc[v]);
+        }
+    }
+    store_vec<VEC>(a.dst + (size_t)out_row * a.ld + col, o);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Persistent kernels for the top of the circuit (the layers that taper to the roots; for a small
 // circuit every layer): instead of one launch per layer, a workgroup owns CT batch columns, keeps
 // the values (forward) or the adjoints (reverse) of the current and the previous layer in LDS and

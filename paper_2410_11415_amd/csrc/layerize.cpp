@@ -25,10 +25,13 @@ constexpr int64_t kTaskMin = KLAY_TASK_MIN, kTaskMax = KLAY_TASK_MAX, kTaskDiv =
 enum : uint8_t { T_LIT = 0, T_AND = 1, T_OR = 2, T_TRUE = 3, T_FALSE = 4 };
 constexpr int ST_OK = 0, ST_INVAL = 1, ST_CYCLE = 2;
 
-// Segment length for a split row of k sources: about sqrt(k), so that the segment pass and
-// the combine pass both see rows of that length.
+// Segment length for a split row of k sources: about sqrt(k), so that the segment pass and the combine
+// pass both see rows of that length, but at most kMaxSegment: a wave walks a segment 8 entries at a time
+// and the launch lasts as long as the longest walk, while the combine pass gives a row with many partial
+// rows a whole workgroup (combine_kernel).
+constexpr int64_t kMaxSegment = 32;
 int32_t segment_len(int64_t k, const Options& opt) {
-    int64_t s = (int64_t)std::ceil(std::sqrt((double)k));
+    int64_t s = std::min<int64_t>(kMaxSegment, (int64_t)std::ceil(std::sqrt((double)k)));
     return (int32_t)std::max<int64_t>(s, std::max(1, opt.min_segment));
 }
 }  // namespace
