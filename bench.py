@@ -75,7 +75,8 @@ def kernel_symbol(cls, B, edges=False):
         ct *= 2
     fixed = {"tail_fwd": "klay::slab_fwd_kernel<%d>" % ct, "tail_bwd": "klay::slab_bwd_kernel<%d>" % ct,
              "leaf": "klay::leaf_fwd_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
-             "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments and combine rows of split rows)",
+             "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments of split rows)",
+             "combine": "klay::combine_kernel<*>" if B > 32 else "klay::pass_kernel<*> (combine rows of split rows)",
              "prod_edges": "klay::prod_parent_kernel<%d, %d>" % (vec, 64 if B > 32 else w_small)}
     return fixed.get(cls, cls)
 

@@ -98,18 +98,21 @@ typedef struct klay_info_t {
 /* Per-kernel-class timing of the most recent forward / backward call, filled only while
  * profiling is enabled.  Durations come from HIP events recorded on the caller's stream around
  * every single launch.  FWD_x / BWD_x are the main-row launches of a layer (one kernel each:
- * the streaming kernel for B > 32), SPLIT the segment and combine launches of split rows,
+ * the streaming kernel for B > 32), SPLIT the segment launches of split rows, COMBINE their
+ * combine launches,
  * PROD_EDGES the per-parent pass of the real-semiring reverse sweep over a product layer (adjoint
  * times the product of the non-zero children, in place), BWD_PROD the by-child pass that follows
  * it, BWD_SUM_MUL / BWD_PROD_MUL the passes into a product layer, whose rows leave multiplied by
- * the nodes' own values (so that PROD_EDGES only has to repair columns whose value is zero).  Log-semiring reverse sweep: BWD_SOFTMAX_ONE is the step through an OR layer that gathers one
+ * the nodes' own values (so that PROD_EDGES only has to repair columns whose value is zero).
+ * Log-semiring reverse sweep: BWD_SOFTMAX_ONE is the step through an OR layer that gathers one
  * row per edge, BWD_SUM_ENC the step through an AND layer that leaves the adjoints of the OR layer
  * below in the form that step reads; BWD_SOFTMAX, the two-gather step, only runs where that form
  * cannot be used. */
 enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_ROOT,
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
        KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_FWD_MAX, KLAY_K_BWD_SUM_ENC,
-       KLAY_K_BWD_SOFTMAX_ONE, KLAY_K_BWD_PROD, KLAY_K_BWD_SUM_MUL, KLAY_K_BWD_PROD_MUL, KLAY_K_COUNT };
+       KLAY_K_BWD_SOFTMAX_ONE, KLAY_K_BWD_PROD, KLAY_K_BWD_SUM_MUL, KLAY_K_BWD_PROD_MUL,
+       KLAY_K_COMBINE, KLAY_K_COUNT };
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];

@@ -607,7 +607,7 @@ void launch_combine(int op, const klay::PassArgs& a, const Geometry& g, hipStrea
 }
 
 // One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.  The main
-// launch is timed under `cls`, the launches that serve split rows under KLAY_K_SPLIT.
+// launch is timed under `cls`, a separate segment launch under KLAY_K_SPLIT, the combine launch under KLAY_K_COMBINE.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
                   const float* own, float* dst, float* seg_rows, const Geometry& g, int B, hipStream_t s,
                   Profiler& prof, int cls, int* zero_flag = nullptr) {
@@ -688,7 +688,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         cmb.n_total = dp.n_heavy;
         cmb.B = B;
         cmb.ld = g.ld;
-        prof.begin(KLAY_K_SPLIT, pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B));
+        prof.begin(KLAY_K_COMBINE, pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B));
         launch_combine(combine_op, cmb, g, s);
         prof.end();
     }
