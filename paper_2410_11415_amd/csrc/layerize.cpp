@@ -29,7 +29,7 @@ constexpr int ST_OK = 0, ST_INVAL = 1, ST_CYCLE = 2;
 // pass both see rows of that length, but at most kMaxSegment: a wave walks a segment 8 entries at a time
 // and the launch lasts as long as the longest walk, while the combine pass gives a row with many partial
 // rows a whole workgroup (combine_kernel).
-constexpr int64_t kMaxSegment = 32;
+constexpr int64_t kMaxSegment = 24;      // measured: 24 beats 12, 16, 20, 32, 48 and 64 on the power-law and the headline workload
 int32_t segment_len(int64_t k, const Options& opt) {
     int64_t s = std::min<int64_t>(kMaxSegment, (int64_t)std::ceil(std::sqrt((double)k)));
     return (int32_t)std::max<int64_t>(s, std::max(1, opt.min_segment));
