@@ -205,7 +205,10 @@ def fold():
                 "Dominant kernel by time: %s, %.2f us average under the tracer; bench.py's HIP events give %s %.2f us." % (
                     dom.replace("klay::", ""), stats[dom][2] / 1e3, roof["kernel"].replace("klay::", ""), roof["kernel_avg_launch_us"]),
                 ""]
-        name = "%s_b%d_%s_%s%s.md" % (cfg["workload"], cfg["batch"], cfg["semiring"], "fwd_bwd" if backward else "fwd", "_chains" if chains else "")
+        # named for the kernel that dominates the run and for the workload
+        dom_name = re.sub(r"<.*", "", dom.replace("klay::", ""))
+        name = "%s_%s_b%d_%s_%s%s.md" % (dom_name, cfg["workload"], cfg["batch"], cfg["semiring"],
+                                         "fwd_bwd" if backward else "fwd", "_chains" if chains else "")
         with open(os.path.join(ROOT, "profiles", name), "w") as fh:
             fh.write("\n".join(out))
         print("fold:", key, "->", "profiles/" + name, "step %.3f GB" % (step_bytes / 1e9))
