@@ -737,10 +737,11 @@ TailChoice choose_tail(const klay_circuit* c, int B, int buffers, int lowest) {
 
 // the layers the forward sweep runs in the persistent kernel ...
 TailChoice choose_tail_fwd(const klay_circuit* c, int B) { return choose_tail(c, B, 2, c->plan.tail_first); }
-// ... and the (possibly fewer) layers the reverse sweep does, given the forward choice
+// ... and the layers the reverse sweep does, given the forward choice (fewer where a layer has a node with more
+// than kTailFanCap parents)
 TailChoice choose_tail_bwd(const klay_circuit* c, int B, int fwd_first) {
     if (fwd_first <= 0 || c->plan.tail_bwd_first <= 0) return TailChoice();
-    return choose_tail(c, B, 4, std::max(fwd_first, c->plan.tail_bwd_first));
+    return choose_tail(c, B, 2, std::max(fwd_first, c->plan.tail_bwd_first));
 }
 
 template <int CT>
@@ -789,17 +790,17 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* ac
 }
 
 void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb, const float* dout,
-                     float* g_out, const uint32_t* first_multi, int B, int ld, hipStream_t s) {
+                     float* g_out, const uint32_t* top_multi, int B, int ld, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
     const int first_is_and = t.first & 1;
-    const size_t lds = (size_t)4 * (t.nmax + 1) * t.ct * sizeof(float);
+    const size_t lds = (size_t)2 * (t.nmax + 1) * t.ct * sizeof(float);
     dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
 #define KLAY_TAIL_BWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::slab_bwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
                        n_layers, first_is_and, c->d_index, dout, c->d_top_ptr, c->d_top_root,          \
-                       p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows, first_multi)
+                       p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows, top_multi)
     switch (t.ct) {
     case 8: KLAY_TAIL_BWD(8); break;
     case 4: KLAY_TAIL_BWD(4); break;
@@ -1632,7 +1633,8 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         // the layers the forward pass ran in the persistent kernel are swept by its reverse counterpart,
         // which seeds the adjoints itself and leaves those of its first layer in gcur
         int top = L;
-        const TailChoice tail = choose_tail_bwd(c, B, c->last_tail_first);
+        // (its adjoints of OR nodes are in the one-gather form throughout, so it needs that form to be in use)
+        const TailChoice tail = one ? choose_tail_bwd(c, B, c->last_tail_first) : TailChoice();
         if (c->last_tail_first > 0) {
             // the ordinary launches below read values of layers last_tail_first .. top as rows of the
             // activation buffer; the persistent forward kernel kept them column-major
@@ -1642,8 +1644,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (tail.first > 0) {
             prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R,
                        tail_min_bytes(c, tail.first, B, true) + 4.0 * B * R);
-            launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, encoded(tail.first) ? c->dl[(size_t)tail.first].multi : nullptr,
-                            B, g.ld, s);
+            launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, encoded(L) ? c->dl[(size_t)L].multi : nullptr, B, g.ld, s);
             prof.end();
             top = tail.first;
         } else {

@@ -901,22 +901,24 @@ __global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer*
     }
 }
 
-// One block of one step of the reverse sweep.  OR: the step goes through an OR layer (weighted edges
-// carry the softmax weight exp(child value - parent value)); otherwise every edge passes the adjoint on.
+// One block of one step of the reverse sweep.  OR: the step goes through an OR layer; its weighted edges read the
+// parent's adjoint in the one-gather form (see encode_h) and need the value of the row they belong to.
+// Otherwise every edge passes the adjoint on, and a row that is an OR node with more than one child (kRowFlag
+// on the word the lane holds when the chunk closes) is stored in that form, again with the row's own value.
+// `own` is that value for the row in hand, read from the column-major value buffer (consecutive lanes,
+// consecutive floats) when a chunk opens.
 template <int CT, bool OR>
 __device__ __forceinline__ void slab_bwd_block(const uint32_t (&a)[kSlabD], uint32_t (&b)[kSlabD], const uint32_t* fetch,
                                                int n_below, int& q, float (&acc)[CT], float (&own)[CT],
-                                               const float* cur, float* nxt, const float* nl, const float* nb) {
+                                               const float* cur, float* nxt, const float* __restrict__ tb_below, int T,
+                                               int nact) {
     slab_fetch(b, fetch);
-    float g[kSlabD][CT], y[kSlabD][CT];
+    float g[kSlabD][CT];
 #pragma unroll
     for (int u = 0; u < kSlabD; ++u) {
         const int p = (int)(a[u] & kIdMask);          // a padding word names the slot past the last parent: adjoint 0
 #pragma unroll
-        for (int k = 0; k < CT; ++k) {
-            g[u][k] = cur[p * CT + k];
-            y[u][k] = OR ? nl[p * CT + k] : 0.0f;
-        }
+        for (int k = 0; k < CT; ++k) g[u][k] = cur[p * CT + k];
     }
     const int lane = threadIdx.x & 63;
 #pragma unroll
@@ -924,26 +926,20 @@ __device__ __forceinline__ void slab_bwd_block(const uint32_t (&a)[kSlabD], uint
         // an unweighted edge (chain node or single-child OR above) passes the adjoint unchanged
         const bool weighted = OR && (a[u] & kWeighted) != 0;
 #pragma unroll
-        for (int k = 0; k < CT; ++k) {
-            if (OR) {
-                const float wgt = !weighted ? 1.0f : ((y[u][k] == -INFINITY) ? 0.0f : fexp(own[k] - y[u][k]));
-                acc[k] = fmaf(g[u][k], wgt, acc[k]);
-            } else {
-                acc[k] += g[u][k];
-            }
-        }
+        for (int k = 0; k < CT; ++k) acc[k] += weighted ? decode_h(g[u][k], own[k]) : g[u][k];
         if (__builtin_amdgcn_readfirstlane((int)a[u]) & (int)kLast) {
             const int r = q * 64 + lane;
             if (r < n_below) {
+                const bool enc = !OR && (a[u] & kRowFlag) != 0;
 #pragma unroll
-                for (int k = 0; k < CT; ++k) nxt[r * CT + k] = acc[k];
+                for (int k = 0; k < CT; ++k) nxt[r * CT + k] = enc ? encode_h(acc[k], own[k]) : acc[k];
             }
             q += kSlabWaves;
             const int r2 = q * 64 + lane;
 #pragma unroll
             for (int k = 0; k < CT; ++k) {
                 acc[k] = 0.0f;
-                if (OR) own[k] = nb[(r2 < n_below ? r2 : 0) * CT + k];
+                own[k] = (r2 < n_below && k < nact) ? tb_below[(size_t)k * T + r2] : 0.0f;
             }
         }
     }
@@ -951,7 +947,8 @@ __device__ __forceinline__ void slab_bwd_block(const uint32_t (&a)[kSlabD], uint
 
 template <int CT, bool OR>
 __device__ __forceinline__ void slab_bwd_rows(int n_below, const uint32_t* sp, int lines, uint32_t (&a)[kSlabD],
-                                              const float* cur, float* nxt, const float* nl, const float* nb) {
+                                              const float* cur, float* nxt, const float* __restrict__ tb_below, int T,
+                                              int nact) {
     if (lines <= 0) return;
     int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
@@ -960,18 +957,18 @@ __device__ __forceinline__ void slab_bwd_rows(int n_below, const uint32_t* sp, i
     for (int k = 0; k < CT; ++k) {
         acc[k] = 0.0f;
         const int r = q * 64 + lane;
-        own[k] = OR ? nb[(r < n_below ? r : 0) * CT + k] : 0.0f;
+        own[k] = (r < n_below && k < nact) ? tb_below[(size_t)k * T + r] : 0.0f;
     }
     uint32_t b[kSlabD];
     for (int i = 0;;) {
-        slab_bwd_block<CT, OR>(a, b, sp + (size_t)(i + kSlabD) * 64, n_below, q, acc, own, cur, nxt, nl, nb);
+        slab_bwd_block<CT, OR>(a, b, sp + (size_t)(i + kSlabD) * 64, n_below, q, acc, own, cur, nxt, tb_below, T, nact);
         i += kSlabD;
         if (i >= lines) {
 #pragma unroll
             for (int u = 0; u < kSlabD; ++u) a[u] = b[u];
             break;
         }
-        slab_bwd_block<CT, OR>(b, a, sp + (size_t)(i + kSlabD) * 64, n_below, q, acc, own, cur, nxt, nl, nb);
+        slab_bwd_block<CT, OR>(b, a, sp + (size_t)(i + kSlabD) * 64, n_below, q, acc, own, cur, nxt, tb_below, T, nact);
         i += kSlabD;
         if (i >= lines) break;
     }
@@ -979,8 +976,10 @@ __device__ __forceinline__ void slab_bwd_rows(int n_below, const uint32_t* sp, i
 
 // Reverse sweep over the same layers (log semiring): seeds the top layer's adjoints from dout, walks
 // down to the first layer of the launch and leaves that layer's adjoints in g_out[n_first, ld].
-// LDS: adjoints of the layer in hand and of the one below, and, for a step through an OR layer, the
-// values of both (loaded from tb at the start of the step).
+// LDS: the adjoints of the layer in hand and of the one below (two arrays, as in the forward kernel, so both
+// kernels take the same layers); node values come from the column-major buffer tb, once per row.  The adjoints
+// of OR nodes with more than one child are kept in the one-gather form throughout, also in g_out; top_multi
+// (or null) flags such nodes of the top layer for the seed.
 template <int CT>
 __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer* __restrict__ layers, int n_layers,
                                                                 int first_is_and, const int32_t* __restrict__ ibase,
@@ -989,13 +988,11 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
                                                                 const int32_t* __restrict__ top_root, int R,
                                                                 float* __restrict__ g_out, int B, int ld, int nmax,
                                                                 const float* __restrict__ tb, int T,
-                                                                const uint32_t* __restrict__ first_multi) {
+                                                                const uint32_t* __restrict__ top_multi) {
     extern __shared__ float smem[];
     const size_t stride = (size_t)(nmax + 1) * CT;
     float* cur = smem;
     float* nxt = smem + stride;
-    float* nl = smem + 2 * stride;          // values of the layer in hand (parents)
-    float* nb = smem + 3 * stride;          // values of the layer below (the rows of the step)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int col0 = (int)blockIdx.x * CT;
@@ -1008,11 +1005,14 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
     {   // adjoint seed of the top layer
         const SlabLayer& L = layers[n_layers - 1];
         for (int i = threadIdx.x; i < L.n; i += kSlabThreads) {
+            const bool enc = top_multi && ((top_multi[i >> 5] >> (i & 31)) & 1u);
 #pragma unroll
             for (int k = 0; k < CT; ++k) {
                 float acc = 0.0f;
-                if (k < nact)
+                if (k < nact) {
                     for (int t = top_ptr[i]; t < top_ptr[i + 1]; ++t) acc += dout[(size_t)(col0 + k) * R + top_root[t]];
+                    if (enc) acc = encode_h(acc, tb0[(size_t)k * T + L.tb_off + i]);
+                }
                 cur[i * CT + k] = acc;
             }
         }
@@ -1022,37 +1022,20 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
         const SlabLayer& L = layers[t];
         const bool is_and = ((t & 1) == 0) == (first_is_and != 0);
         const int lines = L.bwd_count[wave];
-        if (!is_and) {
-            const int off_below = layers[t - 1].tb_off;
-            for (int i = threadIdx.x; i < L.n; i += kSlabThreads)
-#pragma unroll
-                for (int k = 0; k < CT; ++k) nl[i * CT + k] = k < nact ? tb0[(size_t)k * T + L.tb_off + i] : 0.0f;
-            if (threadIdx.x < CT) nl[L.n * CT + threadIdx.x] = 0.0f;
-            for (int i = threadIdx.x; i < L.n_below; i += kSlabThreads)
-#pragma unroll
-                for (int k = 0; k < CT; ++k) nb[i * CT + k] = k < nact ? tb0[(size_t)k * T + off_below + i] : 0.0f;
-        }
+        const float* tb_below = tb0 + layers[t - 1].tb_off;
         __syncthreads();
-        if (is_and) slab_bwd_rows<CT, false>(L.n_below, sp, lines, a, cur, nxt, nl, nb);
-        else slab_bwd_rows<CT, true>(L.n_below, sp, lines, a, cur, nxt, nl, nb);
+        if (is_and) slab_bwd_rows<CT, false>(L.n_below, sp, lines, a, cur, nxt, tb_below, T, nact);
+        else slab_bwd_rows<CT, true>(L.n_below, sp, lines, a, cur, nxt, tb_below, T, nact);
         sp += (size_t)lines * 64;
         if (threadIdx.x < CT) nxt[L.n_below * CT + threadIdx.x] = 0.0f;  // padding slot of the next step
         __syncthreads();
         float* tmp = cur; cur = nxt; nxt = tmp;
     }
-    // first_multi (or null): the launch's lowest layer is an OR layer whose step follows as an ordinary
-    // launch in the one-gather form; bit r = node r has more than one child and leaves as encode_h
     const int n_first = layers[0].n;
-    for (int r = threadIdx.x; r < n_first; r += kSlabThreads) {
-        const bool enc = first_multi && ((first_multi[r >> 5] >> (r & 31)) & 1u);
+    for (int r = threadIdx.x; r < n_first; r += kSlabThreads)
 #pragma unroll
         for (int k = 0; k < CT; ++k)
-            if (k < nact) {
-                float o = cur[r * CT + k];
-                if (enc) o = encode_h(o, tb0[(size_t)k * T + layers[0].tb_off + r]);
-                g_out[(size_t)r * ld + col0 + k] = o;
-            }
-    }
+            if (k < nact) g_out[(size_t)r * ld + col0 + k] = cur[r * CT + k];
 }
 
 // rows[r, b] = tb[b, first + r] for r < n_rows: values that the persistent forward kernel left in the

@@ -159,7 +159,8 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
 namespace {
 // chunked, lane-interleaved index vectors of a CSR with n_src source rows, one run of lines per wave
 // (see SlabPlan)
-void make_slab(int64_t n, int64_t n_src, const int32_t* ptr, const int32_t* idx, const uint32_t* flags, SlabPlan& out) {
+void make_slab(int64_t n, int64_t n_src, const int32_t* ptr, const int32_t* idx, const uint32_t* flags, SlabPlan& out,
+               const uint32_t* row_bits = nullptr) {
     const int64_t chunks = (n + 63) / 64;
     std::vector<int32_t> width((size_t)chunks, 0);
     for (int64_t q = 0; q < chunks; ++q)
@@ -181,7 +182,13 @@ void make_slab(int64_t n, int64_t n_src, const int32_t* ptr, const int32_t* idx,
             for (int64_t r = q * 64; r < std::min<int64_t>(n, q * 64 + 64); ++r)
                 for (int32_t j = ptr[r]; j < ptr[r + 1]; ++j)
                     out.ent[(size_t)(line + (j - ptr[r])) * 64 + (size_t)(r - q * 64)] = (uint32_t)idx[j] | (flags ? flags[j] : 0u);
-            for (int lane = 0; lane < 64; ++lane) out.ent[(size_t)(line + wq - 1) * 64 + (size_t)lane] |= kLastEdge;
+            for (int lane = 0; lane < 64; ++lane) {
+                uint32_t& last = out.ent[(size_t)(line + wq - 1) * 64 + (size_t)lane];
+                last |= kLastEdge;
+                // the word a lane holds when its chunk closes also tells whether its row is flagged
+                const int64_t r = q * 64 + lane;
+                if (row_bits && r < n && ((row_bits[(size_t)r >> 5] >> (r & 31)) & 1u)) last |= kRowFlag;
+            }
             line += wq;
         }
     }
@@ -684,7 +691,8 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 make_slab(lay.n, nc, lay.row_ptr.data(), lay.child.data(), nullptr, lay.slab_fwd);
                 lay.tail_fwd_ok = true;
                 if (fan_out <= kTailFanCap) {
-                    make_slab(nc, lay.n, cptr.data(), cpar.data(), cflag.data(), lay.slab_bwd);
+                    make_slab(nc, lay.n, cptr.data(), cpar.data(), cflag.data(), lay.slab_bwd,
+                              (l & 1) && l >= 3 ? plan.layers[(size_t)l - 1].multi.data() : nullptr);
                     lay.tail_bwd_ok = true;
                 }
             }

@@ -33,6 +33,8 @@ constexpr int64_t kTailFanCap = 64;
 // is one line of 64 words: lane j holds the i-th source of row 64 * chunk + j, or a padding word when
 // that row is shorter or does not exist.  A padding word names source n_src, one past the last source
 // row: the kernels keep the identity of the layer's operation in that slot, so padding needs no test.
+// In the reverse plan the word that a lane holds in the last line of a chunk carries kRowFlag when the lane's row
+// is an OR node with more than one child (its adjoint is stored in the one-gather form).
 // The 16 waves of the workgroup take the chunks round-robin, and the lines of the chunks of one wave
 // are stored back to back in the order the wave walks them, so a wave streams through one contiguous
 // run of lines and can fetch them far ahead.  Every word of the last line of a chunk carries

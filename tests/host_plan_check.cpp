@@ -129,7 +129,8 @@ static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const st
 // the walk of the persistent kernels over a chunked plan: each of the 16 waves streams through its run
 // of lines, one word per lane; the end-of-chunk bit (the same in all 64 words of a line) closes the 64
 // rows of the chunk in hand, and the wave's next chunk is 16 chunks further; padding words add nothing
-static void check_slab(const klay::SlabPlan& sp, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what) {
+static void check_slab(const klay::SlabPlan& sp, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what,
+                       const std::vector<uint32_t>* row_bits = nullptr) {
     const int64_t chunks = (n_out + 63) / 64;
     CHECK(sp.wave_line[0] == 0 && (int64_t)sp.ent.size() == (int64_t)sp.wave_line[klay::kSlabWaves] * 64, "%s: sizes", what);
     std::vector<int> written((size_t)n_out, 0);
@@ -147,6 +148,11 @@ static void check_slab(const klay::SlabPlan& sp, int64_t n_out, int64_t n_src, c
             }
             for (int lane = 0; lane < 64; ++lane) {
                 CHECK((e[lane] & klay::kLastEdge) == (e[0] & klay::kLastEdge), "%s: end-of-chunk bit differs within a line", what);
+                {   // the row flag sits on the word a lane holds when its chunk closes, for flagged rows only
+                    const int64_t r = q * 64 + lane;
+                    const bool expect = (e[0] & klay::kLastEdge) && row_bits && r < n_out && (((*row_bits)[(size_t)r >> 5] >> (r & 31)) & 1u);
+                    CHECK(((e[lane] & klay::kRowFlag) != 0) == expect, "%s: row flag of row %lld", what, (long long)r);
+                }
                 const uint32_t src = e[lane] & kMask;
                 if ((int64_t)src == n_src) { CHECK(!(e[lane] & klay::kWeightedEdge), "%s: flag on padding", what); ended[(size_t)lane] = 1; continue; }
                 CHECK(!ended[(size_t)lane], "%s: source after padding", what);
@@ -235,7 +241,8 @@ int main(int argc, char** argv) {
                 check_plan(lay.bwd, nb, lay.n, bwd, "backward plan", (l % 2 == 1 && l >= 3) ? &plan.layers[(size_t)l - 1].multi : nullptr); ++plans;
                 CHECK(!lay.tail_bwd_ok || lay.tail_fwd_ok, "reverse persistent plan without the forward one");
                 if (lay.tail_fwd_ok) { check_slab(lay.slab_fwd, lay.n, nb, fwd, "persistent forward plan"); ++plans; }
-                if (lay.tail_bwd_ok) { check_slab(lay.slab_bwd, nb, lay.n, bwd, "persistent reverse plan"); ++plans; }
+                if (lay.tail_bwd_ok) { check_slab(lay.slab_bwd, nb, lay.n, bwd, "persistent reverse plan",
+                                                  (l % 2 == 1 && l >= 3) ? &plan.layers[(size_t)l - 1].multi : nullptr); ++plans; }
             }
             for (int l = 1; l <= L; ++l) {
                 const klay::LayerPlan& lay = plan.layers[(size_t)l];
