@@ -22,8 +22,8 @@ struct Options {
 };
 
 // Layers at the top of the circuit with at most this many nodes are candidates for the persistent
-// kernels, which keep two (forward) or three (reverse) layers of one batch column in LDS: 20000 rows
-// is what two value arrays of 160 KB hold.  In those kernels a lane walks a whole row, so a candidate
+// kernels, which keep two layers of one batch column in LDS (values forward, adjoints in the reverse sweep):
+// 20000 rows is what two arrays in 160 KB hold.  In those kernels a lane walks a whole row, so a candidate
 // layer has no row with more sources than kTailFanCap (the reverse plan: no node with more parents).
 constexpr int64_t kTailRowsCap = 20000;
 constexpr int64_t kTailFanCap = 64;
