@@ -111,7 +111,7 @@ Geometry geometry(int B) {
 size_t align_floats(size_t n) { return (n + 63) / 64 * 64; }
 
 struct Workspace {
-    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, g2 = 0, tb = 0, flags = 0, total = 0;   // offsets in floats
+    size_t act = 0, wT = 0, seg_rows = 0, g0 = 0, g1 = 0, g2 = 0, tb = 0, stage = 0, flags = 0, total = 0;   // offsets in floats
 };
 
 struct EventRec {
@@ -137,6 +137,7 @@ struct klay_circuit {
     const int32_t* d_leaf_code = nullptr;      // layer 0: literal / constant code of every row
     size_t tail_lds_bytes = 0;                 // LDS a workgroup of the persistent kernels may use (0: kernels unusable)
     int64_t tail_rows = 0;                     // T: rows of all tail candidate layers (one column of the tail buffer)
+    int64_t stage_rows = 0;                    // widest layer that can sit directly below the persistent forward kernel
     int32_t last_tail_first = 0;               // first layer the last forward ran in the persistent kernel (0: none)
     // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
     // vectors (for prod_parent_kernel); for the layers below alias_top also the by-child pass over the
@@ -188,6 +189,8 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     w.seg_rows = off; off += align_floats((size_t)std::max<int64_t>(seg, 1) * g.ld);
     // values of the tail layers, one run of tail_rows floats per batch column
     w.tb = off; off += align_floats((size_t)c->tail_rows * (size_t)B);
+    // the layer below the persistent forward kernel's first one, column-major, for that kernel to read
+    w.stage = off; off += align_floats((size_t)c->stage_rows * (size_t)B);
     if (need_bwd) {
         // adjoints: one row per node of the layers 0 .. alias_top, and two buffers of the widest layer above
         // them that the layer-by-layer part of the sweep alternates between
@@ -507,6 +510,7 @@ klay_status upload(klay_circuit* c) {
         add_streams(false);
         add_streams(true);
         c->tail_rows = tb_off;
+        for (int l = std::max(1, p.tail_first - 1); l < L; ++l) c->stage_rows = std::max<int64_t>(c->stage_rows, p.layers[(size_t)l].n);
         static_assert(sizeof(klay::SlabLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
         o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::SlabLayer) / sizeof(int32_t));
     }
@@ -768,9 +772,21 @@ size_t enable_tail_lds() {
     return 0;
 }
 
-void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* act, float* tb, int B, int ld, int semiring,
-                     const klay::SlabLeaf& leaf, float* out, hipStream_t s) {
+// `stage`: room for the layer below the kernel's first one in column-major form.  When that layer fits the kernel's
+// LDS array it is transposed there first, so that a workgroup reads its column as one run instead of one float per row.
+void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* act, float* tb, float* stage, int B, int ld,
+                     int semiring, const klay::SlabLeaf& leaf, float* out, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
+    const float* staged = nullptr;
+    if (!leaf.w && t.first >= 2) {
+        const int64_t nb = p.layers[(size_t)t.first - 1].n;
+        if (nb <= t.nmax && nb <= c->stage_rows) {
+            dim3 tg((unsigned)((nb + 31) / 32), (unsigned)((B + 31) / 32));
+            hipLaunchKernelGGL(klay::rows_to_cols_kernel, tg, dim3(256), 0, s,
+                               act + (size_t)c->dl[(size_t)t.first - 1].row0 * ld, (int)nb, B, ld, stage);
+            staged = stage;
+        }
+    }
     const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
     const int first_is_and = t.first & 1;
@@ -779,7 +795,7 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* ac
 #define KLAY_TAIL_FWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::slab_fwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
                        n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax, tb, (int)c->tail_rows, leaf, \
-                       c->d_root_pos, p.num_roots, out)
+                       c->d_root_pos, p.num_roots, out, staged)
     switch (t.ct) {
     case 8: KLAY_TAIL_FWD(8); break;
     case 4: KLAY_TAIL_FWD(4); break;
@@ -789,8 +805,10 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* ac
 #undef KLAY_TAIL_FWD
 }
 
+// The kernel leaves the adjoints of its first layer column-major in `g_cols` (B runs of n_first floats); they are
+// transposed into the rows of g_out afterwards.
 void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb, const float* dout,
-                     float* g_out, const uint32_t* top_multi, int B, int ld, hipStream_t s) {
+                     float* g_cols, float* g_out, const uint32_t* top_multi, int B, int ld, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
@@ -800,7 +818,7 @@ void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb
 #define KLAY_TAIL_BWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::slab_bwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
                        n_layers, first_is_and, c->d_index, dout, c->d_top_ptr, c->d_top_root,          \
-                       p.num_roots, g_out, B, ld, t.nmax, tb, (int)c->tail_rows, top_multi)
+                       p.num_roots, g_cols, B, t.nmax, tb, (int)c->tail_rows, top_multi)
     switch (t.ct) {
     case 8: KLAY_TAIL_BWD(8); break;
     case 4: KLAY_TAIL_BWD(4); break;
@@ -808,6 +826,9 @@ void launch_tail_bwd(const klay_circuit* c, const TailChoice& t, const float* tb
     default: KLAY_TAIL_BWD(1); break;
     }
 #undef KLAY_TAIL_BWD
+    const int n_first = (int)p.layers[(size_t)t.first].n;
+    dim3 tgrid((unsigned)((n_first + 31) / 32), (unsigned)((ld + 31) / 32));
+    hipLaunchKernelGGL(klay::tb_to_rows_kernel, tgrid, dim3(256), 0, s, g_cols, n_first, 0, n_first, B, ld, g_out);
 }
 
 // Values of layers first .. last (all run by the persistent forward kernel) from the column-major
@@ -1515,7 +1536,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
         }
         prof.begin(KLAY_K_TAIL_FWD, tail_alg_bytes(c, tail.first, B, false) + 8.0 * B * p.num_roots,
                    tail_min_bytes(c, tail.first, B, false) + 4.0 * B * p.num_roots);
-        launch_tail_fwd(c, tail, act, ws + lay.tb, B, g.ld, (int)semiring, leaf, out, s);
+        launch_tail_fwd(c, tail, act, ws + lay.tb, ws + lay.stage, B, g.ld, (int)semiring, leaf, out, s);
         prof.end();
     } else {
         prof.begin(KLAY_K_ROOT, 8.0 * B * p.num_roots);
@@ -1644,7 +1665,7 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         if (tail.first > 0) {
             prof.begin(KLAY_K_TAIL_BWD, tail_alg_bytes(c, tail.first, B, true) + 4.0 * B * R,
                        tail_min_bytes(c, tail.first, B, true) + 4.0 * B * R);
-            launch_tail_bwd(c, tail, ws + lay.tb, dout, gcur, encoded(L) ? c->dl[(size_t)L].multi : nullptr, B, g.ld, s);
+            launch_tail_bwd(c, tail, ws + lay.tb, dout, gnext, gcur, encoded(L) ? c->dl[(size_t)L].multi : nullptr, B, g.ld, s);
             prof.end();
             top = tail.first;
         } else {

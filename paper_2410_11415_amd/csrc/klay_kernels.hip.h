@@ -827,7 +827,8 @@ __global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer*
                                                                 const float* __restrict__ act, int B, int ld,
                                                                 int semiring, int nmax, float* __restrict__ tb, int T,
                                                                 SlabLeaf leaf, const int32_t* __restrict__ root_pos,
-                                                                int R, float* __restrict__ out) {
+                                                                int R, float* __restrict__ out,
+                                                                const float* __restrict__ stage) {
     extern __shared__ float smem[];
     float* prev = smem;
     float* cur = smem + (size_t)(nmax + 1) * CT;
@@ -874,6 +875,16 @@ __global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer*
         if (threadIdx.x < CT) prev[leaf.n0 * CT + threadIdx.x] = slab_identity(semiring, first_is_and != 0);
         __syncthreads();
     }
+    if (!leaf.w && stage) {
+        // the layer below the first one, column-major in `stage` (B runs of n_below floats, written by
+        // rows_to_cols_kernel): into LDS with consecutive lanes reading consecutive floats
+        const int nb0 = layers[0].n_below;
+        for (int i = threadIdx.x; i < nb0; i += kSlabThreads)
+#pragma unroll
+            for (int k = 0; k < CT; ++k) prev[i * CT + k] = k < nact ? stage[(size_t)(col0 + k) * nb0 + i] : 0.0f;
+        if (threadIdx.x < CT) prev[nb0 * CT + threadIdx.x] = slab_identity(semiring, first_is_and != 0);
+        __syncthreads();
+    }
     // the few numbers a layer needs are read a layer ahead
     int lines = layers[0].fwd_count[wave], n_rows = layers[0].n, n_below = layers[0].n_below, tb_off = layers[0].tb_off;
     for (int t = 0; t < n_layers; ++t) {
@@ -884,7 +895,7 @@ __global__ __launch_bounds__(kSlabThreads) void slab_fwd_kernel(const SlabLayer*
         float* tb_col = tb0 + tb_off;
         // the padding slot of this layer's values, for the layer above (the other operation)
         if (threadIdx.x < CT) cur[n_rows * CT + threadIdx.x] = slab_identity(semiring, !is_and);
-        if (t == 0 && !leaf.w)
+        if (t == 0 && !leaf.w && !stage)
             slab_fwd_layer<CT, true>(semiring, is_and, n_rows, n_below, sp, lines, a, prev, cur,
                                      act + (size_t)layers[0].row0_below * ld + col0, ld, nact, tb_col, T);
         else
@@ -975,7 +986,7 @@ __device__ __forceinline__ void slab_bwd_rows(int n_below, const uint32_t* sp, i
 }
 
 // Reverse sweep over the same layers (log semiring): seeds the top layer's adjoints from dout, walks
-// down to the first layer of the launch and leaves that layer's adjoints in g_out[n_first, ld].
+// down to the first layer of the launch and leaves that layer's adjoints in g_out[B][n_first] (column-major).
 // LDS: the adjoints of the layer in hand and of the one below (two arrays, as in the forward kernel, so both
 // kernels take the same layers); node values come from the column-major buffer tb, once per row.  The adjoints
 // of OR nodes with more than one child are kept in the one-gather form throughout, also in g_out; top_multi
@@ -986,7 +997,7 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
                                                                 const float* __restrict__ dout,
                                                                 const int32_t* __restrict__ top_ptr,
                                                                 const int32_t* __restrict__ top_root, int R,
-                                                                float* __restrict__ g_out, int B, int ld, int nmax,
+                                                                float* __restrict__ g_out, int B, int nmax,
                                                                 const float* __restrict__ tb, int T,
                                                                 const uint32_t* __restrict__ top_multi) {
     extern __shared__ float smem[];
@@ -1031,11 +1042,33 @@ __global__ __launch_bounds__(kSlabThreads) void slab_bwd_kernel(const SlabLayer*
         __syncthreads();
         float* tmp = cur; cur = nxt; nxt = tmp;
     }
+    // column-major, like tb: a lane owns rows of one column, so row-major stores would be 4 bytes per cache line
+    // (measured: 40 us of 163 on the headline workload); tb_to_rows_kernel transposes afterwards
     const int n_first = layers[0].n;
     for (int r = threadIdx.x; r < n_first; r += kSlabThreads)
 #pragma unroll
         for (int k = 0; k < CT; ++k)
-            if (k < nact) g_out[(size_t)r * ld + col0 + k] = cur[r * CT + k];
+            if (k < nact) g_out[(size_t)(col0 + k) * n_first + r] = cur[r * CT + k];
+}
+
+// cols[b, r] = rows[r, b] for r < n_rows, b < B: the rows of a layer of the activation buffer into the column-major
+// form in which a workgroup of the persistent forward kernel reads its column (32 x 32 tiles through LDS).
+__global__ __launch_bounds__(256) void rows_to_cols_kernel(const float* __restrict__ rows, int n_rows, int B, int ld,
+                                                           float* __restrict__ cols) {
+    __shared__ float tile[32][33];
+    const int r0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = r0 + ty + 8 * j, b = b0 + tx;
+        tile[ty + 8 * j][tx] = (r < n_rows && b < B) ? rows[(size_t)r * ld + b] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int b = b0 + ty + 8 * j, r = r0 + tx;
+        if (b < B && r < n_rows) cols[(size_t)b * n_rows + r] = tile[tx][ty + 8 * j];
+    }
 }
 
 // rows[r, b] = tb[b, first + r] for r < n_rows: values that the persistent forward kernel left in the
