@@ -77,6 +77,7 @@ def kernel_symbol(cls, B, edges=False):
              "leaf": "klay::leaf_fwd_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
              "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments of split rows)",
              "combine": "klay::combine_kernel<*>" if B > 32 else "klay::pass_kernel<*> (combine rows of split rows)",
+             "main_combine": "klay::stream_combine_kernel<*>",
              "prod_edges": "klay::prod_parent_kernel<%d, %d>" % (vec, 64 if B > 32 else w_small)}
     return fixed.get(cls, cls)
 

@@ -99,7 +99,8 @@ typedef struct klay_info_t {
  * profiling is enabled.  Durations come from HIP events recorded on the caller's stream around
  * every single launch.  FWD_x / BWD_x are the main-row launches of a layer (one kernel each:
  * the streaming kernel for B > 32), SPLIT the segment launches of split rows, COMBINE their
- * combine launches,
+ * combine launches, MAIN_COMBINE (any operation) the launches that take the main rows and the combine
+ * rows of a layer together (32 < B <= 64, where the segments run in a launch of their own first),
  * PROD_EDGES the per-parent pass of the real-semiring reverse sweep over a product layer (adjoint
  * times the product of the non-zero children, in place), BWD_PROD the by-child pass that follows
  * it, BWD_SUM_MUL / BWD_PROD_MUL the passes into a product layer, whose rows leave multiplied by
@@ -112,7 +113,7 @@ enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
        KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_FWD_MAX, KLAY_K_BWD_SUM_ENC,
        KLAY_K_BWD_SOFTMAX_ONE, KLAY_K_BWD_PROD, KLAY_K_BWD_SUM_MUL, KLAY_K_BWD_PROD_MUL,
-       KLAY_K_COMBINE, KLAY_K_COUNT };
+       KLAY_K_COMBINE, KLAY_K_MAIN_COMBINE, KLAY_K_COUNT };
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];

@@ -21,7 +21,7 @@ KLAY_LIT, KLAY_AND, KLAY_OR, KLAY_TRUE, KLAY_FALSE = range(5)
 KLAY_STATIC_WORKSPACE_BYTES = 64 << 20
 KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf",
                   "tail_fwd", "tail_bwd", "split", "prod_edges", "fwd_max", "bwd_sum_enc", "bwd_softmax_one",
-                  "bwd_prod", "bwd_sum_mul", "bwd_prod_mul", "combine")
+                  "bwd_prod", "bwd_sum_mul", "bwd_prod_mul", "combine", "main_combine")
 
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",

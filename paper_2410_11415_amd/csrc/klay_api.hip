@@ -610,6 +610,66 @@ void launch_combine(int op, const klay::PassArgs& a, const Geometry& g, hipStrea
     }
 }
 
+// Main rows and combine rows in one launch (one column per lane; the segments have run in a launch before it).
+template <int OP, int COP>
+void launch_stream_combine_op(const DevPass& dp, const Geometry& g, const float* src, const float* src2, const float* own,
+                              float* dst, int B, hipStream_t s, int* zf, const klay::PassArgs& cmb) {
+    const int2* tasks = reinterpret_cast<const int2*>(dp.tasks);
+    int64_t blocks = ((int64_t)dp.n_tasks + 3) / 4;
+    blocks = (blocks + 7) / 8 * 8;
+    const int n_comb_blocks = (cmb.n_main + 7) / 8 * 8;
+    const int nt = (int64_t)dp.n_main * g.ld * 4 > (int64_t)64 << 20 ? 1 : 0;
+    dim3 grid((unsigned)(blocks + n_comb_blocks), (unsigned)g.tiles);
+    hipLaunchKernelGGL((klay::stream_combine_kernel<OP, COP, 1>), grid, dim3(256), 0, s, tasks, dp.n_tasks, dp.idx, src, src2,
+                       own, dst, B, g.ld, nt, dp.n_main, zf, n_comb_blocks, cmb);
+}
+
+// false: no such kernel for this pair of operations
+bool launch_stream_combine(int op, int combine_op, const DevPass& dp, const Geometry& g, const float* src,
+                           const float* src2, const float* own, float* dst, int B, hipStream_t s, int* zf,
+                           const klay::PassArgs& cmb) {
+    using namespace klay;
+#define KLAY_SC(A, C) \
+    if (op == A && combine_op == C) { launch_stream_combine_op<A, C>(dp, g, src, src2, own, dst, B, s, zf, cmb); return true; }
+    KLAY_SC(OP_SUM, OP_SUM)
+    KLAY_SC(OP_PROD, OP_PROD)
+    KLAY_SC(OP_LSE, OP_LSE)
+    KLAY_SC(OP_MAX, OP_MAX)
+    KLAY_SC(OP_SUM_H, OP_SUM_H)
+    KLAY_SC(OP_SOFTMAX_H, OP_SUM)
+    KLAY_SC(OP_SUM_P, OP_SUM_P)
+    KLAY_SC(OP_PROD_BWD, OP_SUM)
+    KLAY_SC(OP_PROD_BWD_P, OP_SUM_P)
+#undef KLAY_SC
+    return false;
+}
+
+klay::PassArgs combine_args(const DevPass& dp, const float* seg_rows, const float* own, float* dst, const Geometry& g,
+                            int B, int* zero_flag) {
+    klay::PassArgs cmb{};
+    cmb.ptr = dp.comb_ptr;
+    cmb.idx = dp.comb_idx;
+    cmb.src = seg_rows;
+    cmb.own = own;               // OP_SUM_H, OP_SUM_P: the value rows of the nodes the combine pass writes
+    cmb.zero_flag = zero_flag;
+    cmb.out_row = dp.comb_row;
+    cmb.dst = dst;
+    cmb.dst_seg = nullptr;
+    cmb.row_begin = 0;
+    cmb.n_main = dp.n_heavy;
+    cmb.n_total = dp.n_heavy;
+    cmb.B = B;
+    cmb.ld = g.ld;
+    return cmb;
+}
+
+bool stream_combine_pair(int op, int combine_op) {
+    using namespace klay;
+    return (op == combine_op && (op == OP_SUM || op == OP_PROD || op == OP_LSE || op == OP_MAX || op == OP_SUM_H || op == OP_SUM_P)) ||
+           (op == OP_SOFTMAX_H && combine_op == OP_SUM) || (op == OP_PROD_BWD && combine_op == OP_SUM) ||
+           (op == OP_PROD_BWD_P && combine_op == OP_SUM_P);
+}
+
 // One layer-level gather-reduce: main rows, segments of split rows, then the combine pass.  The main
 // launch is timed under `cls`, a separate segment launch under KLAY_K_SPLIT, the combine launch under KLAY_K_COMBINE.
 void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, const float* src2,
@@ -647,6 +707,22 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
             a.row_begin = 0;
             launch_pass(op, a, g, s);
             prof.end();
+        } else if (!merged && dp.n_seg > 0 && dp.n_heavy > 0 && dp.n_tasks > 0 && stream_combine_pair(op, combine_op)) {
+            // One column per lane and a layer too large for one generic launch: the segments first, then the
+            // main rows together with the combine rows (two launches instead of three).
+            prof.begin(KLAY_K_SPLIT, pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B),
+                       pass_min_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, 0.0, B));
+            a.row_begin = dp.n_main;
+            launch_pass(op, a, g, s);
+            prof.end();
+            prof.begin(KLAY_K_MAIN_COMBINE,
+                       pass_bytes(op, (double)dp.main_entries, light_rows, B) + pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B),
+                       pass_min_bytes(op, (double)dp.main_entries, light_rows, (double)dp.n_src, B) +
+                           pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B));
+            launch_stream_combine(op, combine_op, dp, g, src, src2, own, dst, B, s, zero_flag,
+                                  combine_args(dp, seg_rows, own, dst, g, B, zero_flag));
+            prof.end();
+            return;
         } else {
         double bytes = pass_bytes(op, (double)dp.main_entries, light_rows, B);
         if (merged) bytes += pass_bytes(op, (double)dp.seg_entries, (double)dp.n_seg, B);
@@ -678,20 +754,7 @@ void run_pass_set(int op, int combine_op, const DevPass& dp, const float* src, c
         prof.end();
     }
     if (dp.n_heavy > 0) {
-        klay::PassArgs cmb{};
-        cmb.ptr = dp.comb_ptr;
-        cmb.idx = dp.comb_idx;
-        cmb.src = seg_rows;
-        cmb.own = own;               // OP_SUM_H, OP_SUM_P: the value rows of the nodes the combine pass writes
-        cmb.zero_flag = zero_flag;
-        cmb.out_row = dp.comb_row;
-        cmb.dst = dst;
-        cmb.dst_seg = nullptr;
-        cmb.row_begin = 0;
-        cmb.n_main = dp.n_heavy;
-        cmb.n_total = dp.n_heavy;
-        cmb.B = B;
-        cmb.ld = g.ld;
+        const klay::PassArgs cmb = combine_args(dp, seg_rows, own, dst, g, B, zero_flag);
         prof.begin(KLAY_K_COMBINE, pass_bytes(combine_op, (double)dp.n_seg, (double)dp.n_heavy, B));
         launch_combine(combine_op, cmb, g, s);
         prof.end();

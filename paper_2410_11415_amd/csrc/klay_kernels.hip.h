@@ -202,17 +202,16 @@ __device__ __forceinline__ float dead_value() {
 // an entry carries the end-of-row bit.  Everything that steers control flow is wave-uniform.
 // Index entries past a task's end are valid entries of later rows (or zero padding).
 // ---------------------------------------------------------------------------------------------
+// bx of nbx: the workgroup's place among the workgroups that walk tasks (nbx a multiple of 8, bx mod 8 the XCD
+// the workgroup runs on).
 template <int OP, int VEC>
-__global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ tasks, int n_tasks,
-                                                     const uint32_t* __restrict__ idx,
-                                                     const float* __restrict__ src,
-                                                     const float* __restrict__ src2,
-                                                     const float* __restrict__ own, float* __restrict__ dst,
-                                                     int B, int ld, int stream_stores,
-                                                     const int2* __restrict__ seg_tasks, int n_seg_tasks,
-                                                     float* __restrict__ dst_seg,
-                                                     const int32_t* __restrict__ seg_owner, int n_main,
-                                                     int* __restrict__ zero_flag) {
+__device__ __forceinline__ void stream_body(int bx, int nbx, const int2* __restrict__ tasks, int n_tasks,
+                                            const uint32_t* __restrict__ idx, const float* __restrict__ src,
+                                            const float* __restrict__ src2, const float* __restrict__ own,
+                                            float* __restrict__ dst, int B, int ld, int stream_stores,
+                                            const int2* __restrict__ seg_tasks, int n_seg_tasks,
+                                            float* __restrict__ dst_seg, const int32_t* __restrict__ seg_owner,
+                                            int n_main, int* __restrict__ zero_flag) {
     // entries per chunk: measured on the headline workload, 4 (2 for the softmax adjoint, which loads
     // three rows per entry) beat 8 / 4 by 2%: the kernel is bandwidth-bound, fewer registers per wave
     // buy more resident waves
@@ -225,7 +224,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = ((int)blockIdx.y * 64 + lane) * VEC;
     if (col >= B) return;
-    int t = xcd_block((int)blockIdx.x, (int)gridDim.x) * 4 + wave;
+    int t = xcd_block(bx, nbx) * 4 + wave;
     if (t >= n_tasks + n_seg_tasks) return;
     // tasks past the main list are segments of split rows: same walk, output rows go to scratch
     // (dst_seg is shifted so that segment row numbers, which continue after the main rows, index it)
@@ -325,6 +324,21 @@ __global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ ta
         for (int i = 0; i < CH; ++i) ids[i] = nxt[i];
         j += CH;
     }
+}
+
+template <int OP, int VEC>
+__global__ __launch_bounds__(256) void stream_kernel(const int2* __restrict__ tasks, int n_tasks,
+                                                     const uint32_t* __restrict__ idx,
+                                                     const float* __restrict__ src,
+                                                     const float* __restrict__ src2,
+                                                     const float* __restrict__ own, float* __restrict__ dst,
+                                                     int B, int ld, int stream_stores,
+                                                     const int2* __restrict__ seg_tasks, int n_seg_tasks,
+                                                     float* __restrict__ dst_seg,
+                                                     const int32_t* __restrict__ seg_owner, int n_main,
+                                                     int* __restrict__ zero_flag) {
+    stream_body<OP, VEC>((int)blockIdx.x, (int)gridDim.x, tasks, n_tasks, idx, src, src2, own, dst, B, ld, stream_stores,
+                         seg_tasks, n_seg_tasks, dst_seg, seg_owner, n_main, zero_flag);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -594,14 +608,13 @@ __global__ __launch_bounds__(256) void pass_kernel(PassArgs a) {
 // rows to write, n_main = number of split rows.
 // ---------------------------------------------------------------------------------------------
 template <int OP, int VEC, int NW>
-__global__ __launch_bounds__(NW * 64) void combine_kernel(PassArgs a) {
+__device__ __forceinline__ void combine_body(int row, const PassArgs& a) {
     constexpr int CH = 8;
     constexpr bool LSE = OP == OP_LSE;
     __shared__ float part_v[NW][64 * VEC];
     __shared__ float part_m[LSE ? NW : 1][LSE ? 64 * VEC : 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int row = (int)blockIdx.x;
     const int colu = ((int)blockIdx.y * 64 + lane) * VEC;
     const int col = colu < a.B ? colu : 0;                 // lanes past the batch work on column 0 and store nothing
     const int beg = a.ptr[row], end = a.ptr[row + 1];
@@ -659,6 +672,32 @@ __global__ __launch_bounds__(NW * 64) void combine_kernel(PassArgs a) {
         }
     }
     store_vec<VEC>(a.dst + (size_t)out_row * a.ld + col, o);
+}
+
+template <int OP, int VEC, int NW>
+__global__ __launch_bounds__(NW * 64) void combine_kernel(PassArgs a) {
+    combine_body<OP, VEC, NW>((int)blockIdx.x, a);
+}
+
+// The main rows of a layer and the combine rows of its split rows in one launch, for the tiles whose segments
+// run in a launch of their own beforehand (one column per lane): the first n_comb_blocks workgroups (a multiple
+// of 8, so that the others keep their XCDs) take one combine row each, four waves per row, the rest walk the
+// tasks of the main rows.  One launch less per layer where the launches, not the bytes, set the time.
+template <int OP, int COP, int VEC>
+__global__ __launch_bounds__(256) void stream_combine_kernel(const int2* __restrict__ tasks, int n_tasks,
+                                                             const uint32_t* __restrict__ idx,
+                                                             const float* __restrict__ src,
+                                                             const float* __restrict__ src2,
+                                                             const float* __restrict__ own, float* __restrict__ dst,
+                                                             int B, int ld, int stream_stores, int n_main,
+                                                             int* __restrict__ zero_flag, int n_comb_blocks,
+                                                             PassArgs cmb) {
+    if ((int)blockIdx.x < n_comb_blocks) {
+        if ((int)blockIdx.x < cmb.n_main) combine_body<COP, VEC, 4>((int)blockIdx.x, cmb);
+    } else {
+        stream_body<OP, VEC>((int)blockIdx.x - n_comb_blocks, (int)gridDim.x - n_comb_blocks, tasks, n_tasks, idx, src,
+                             src2, own, dst, B, ld, stream_stores, nullptr, 0, nullptr, nullptr, n_main, zero_flag);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

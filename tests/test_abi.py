@@ -33,7 +33,7 @@ def test_struct_sizes_match_the_header():
     classes = [t.split("=")[0].strip() for t in enum.split(",") if t.strip()]
     assert classes[-1] == "KLAY_K_COUNT"
     k = len(classes) - 1
-    assert len(binding.KERNEL_CLASSES) == k == 20
+    assert len(binding.KERNEL_CLASSES) == k == 21
     assert [c[len("KLAY_K_"):].lower() for c in classes[:-1]] == list(binding.KERNEL_CLASSES)
     assert ctypes.sizeof(binding.klay_profile_t) == k * 4 + k * 4 + k * 8 + k * 8
 

@@ -253,6 +253,32 @@ def test_split_rows(klay, heavy, seg, B):
     check_both(klay, c, leaf_probs(5, B, 64, ("beta", 0.5, 0.5)), what="split", heavy_fan=heavy, min_segment=seg)
 
 
+@pytest.mark.parametrize("B", [40, 64])
+def test_main_rows_and_combine_rows_in_one_launch(klay, B):
+    """32 < B <= 64 and layers too large for one generic launch: the segments of split rows run first, then
+    one launch takes the main rows and the combine rows together; all three semirings, both sweeps, both
+    layerizations"""
+    c, p, _ = make_config("powerlaw_10m", seed=2, scale=0.08, batch=B)
+    k = build(klay, c)
+    k.set_profiling(True)
+    gpu_eval(k, as_inputs(p, True), LOG, np.ones((B, c.roots.shape[0]), np.float32))
+    prof = k.get_profile()
+    assert prof["main_combine"]["launches"] >= 1 and prof["main_combine"]["ms"] > 0
+    k.close()
+    check_both(klay, c, p, semirings=(LOG,), what="main+combine B=%d" % B)
+    check_both(klay, c, p, semirings=(LOG,), what="main+combine, chains B=%d" % B, unary_chains=True)
+    check_max(klay, c, p, what="main+combine maxlog B=%d" % B)
+    # the real semiring (its values leave the fp32 range on the power-law circuit): a layered circuit whose rows
+    # are split from 8 entries on
+    c, p, _ = make_config("layered_1m", seed=2, scale=1.0, batch=B)
+    k = build(klay, c, heavy_fan=8, min_segment=4)
+    k.set_profiling(True)
+    gpu_eval(k, as_inputs(p, False), REAL, np.ones((B, c.roots.shape[0]), np.float32))
+    assert k.get_profile()["main_combine"]["launches"] >= 8
+    k.close()
+    check_both(klay, c, p, what="main+combine, layered B=%d" % B, heavy_fan=8, min_segment=4)
+
+
 def test_very_high_fan_in_and_gate_with_magnitude_aware_bound(klay):
     """one AND and one OR over 10^4 literals: exercises the split path at the fan-in cap; |log| of the
     AND reaches ~10^4, where fp32 cannot hold 1e-4 absolute, so the bound scales with sum |x_j| / 64"""
