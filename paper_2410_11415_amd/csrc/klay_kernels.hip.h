@@ -1204,12 +1204,10 @@ __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restr
 
 // ---------------------------------------------------------------------------------------------
 // Leaf layer: leaf_weights[B,V] (batch-outer) -> wT[V,ld] (kept for the backward pass) and the
-// literal rows of layer 0; the negated literal gets 1-p (REAL) or log(1-exp(x)) (LOG).
-// Tile = 32 variables x 64 batch columns through LDS.
-// ---------------------------------------------------------------------------------------------
-// Leaf layer: transposes leaf weights [B, V] into rows [*, ld] through an LDS tile.  The negated
+// literal rows of layer 0, through an LDS tile of 32 variables x 64 batch columns.  The negated
 // literal of v gets wneg[b, v] when the caller supplies weights of its own for the negated literals,
 // otherwise 1 - w (real semiring) or log(1 - exp(w)) (log domain).
+// ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void leaf_fwd_kernel(const float* __restrict__ w, const float* __restrict__ wneg,
                                                        int B, int V, int ld,
                                                        const int32_t* __restrict__ pos_row,
