@@ -29,6 +29,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
 // larger 0.66 / 0.80, every layer 0.68 / 0.92; with the layerization of unary chains throughout 60000 and
 // 150000 both gave 0.73 against 0.81 without the rule).
 constexpr int64_t kSmallPassEntries = 100000;
+constexpr size_t kTailLdsMax = 160 * 1024;     // LDS of a gfx950 compute unit: the most a workgroup of the persistent kernels gets
 
 namespace {
 
@@ -137,7 +138,6 @@ struct klay_circuit {
     const int32_t* d_leaf_code = nullptr;      // layer 0: literal / constant code of every row
     size_t tail_lds_bytes = 0;                 // LDS a workgroup of the persistent kernels may use (0: kernels unusable)
     int64_t tail_rows = 0;                     // T: rows of all tail candidate layers (one column of the tail buffer)
-    int64_t stage_rows = 0;                    // widest layer that can sit directly below the persistent forward kernel
     int32_t last_tail_first = 0;               // first layer the last forward ran in the persistent kernel (0: none)
     // real-semiring reverse sweep (built at its first use): per AND layer the plain by-parent index
     // vectors (for prod_parent_kernel); for the layers below alias_top also the by-child pass over the
@@ -178,6 +178,8 @@ int64_t top_layer_rows(const klay::CircuitPlan& p) {
     return n;
 }
 
+int64_t tail_stage_rows(const klay_circuit* c, int B);
+
 Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     const Geometry g = geometry(B);
     const klay::CircuitPlan& p = c->plan;
@@ -190,7 +192,7 @@ Workspace workspace_layout(const klay_circuit* c, int B, bool need_bwd) {
     // values of the tail layers, one run of tail_rows floats per batch column
     w.tb = off; off += align_floats((size_t)c->tail_rows * (size_t)B);
     // the layer below the persistent forward kernel's first one, column-major, for that kernel to read
-    w.stage = off; off += align_floats((size_t)c->stage_rows * (size_t)B);
+    w.stage = off; off += align_floats((size_t)tail_stage_rows(c, B) * (size_t)B);
     if (need_bwd) {
         // adjoints: one row per node of the layers 0 .. alias_top, and two buffers of the widest layer above
         // them that the layer-by-layer part of the sweep alternates between
@@ -509,8 +511,6 @@ klay_status upload(klay_circuit* c) {
         };
         add_streams(false);
         add_streams(true);
-        c->tail_rows = tb_off;
-        for (int l = std::max(1, p.tail_first - 1); l < L; ++l) c->stage_rows = std::max<int64_t>(c->stage_rows, p.layers[(size_t)l].n);
         static_assert(sizeof(klay::SlabLayer) % sizeof(int32_t) == 0, "descriptor must pack into ints");
         o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::SlabLayer) / sizeof(int32_t));
     }
@@ -804,6 +804,17 @@ TailChoice choose_tail(const klay_circuit* c, int B, int buffers, int lowest) {
 
 // the layers the forward sweep runs in the persistent kernel ...
 TailChoice choose_tail_fwd(const klay_circuit* c, int B) { return choose_tail(c, B, 2, c->plan.tail_first); }
+
+// Rows of the layer below the forward kernel's first one if the kernel reads that layer from the column-major
+// stage buffer: it then has to fit an LDS array (the arrays are made as long as it, if the LDS has the room).
+// 0: no stage buffer (the kernel evaluates the leaf layer itself, or gathers from the rows).
+int64_t tail_stage_rows(const klay_circuit* c, const TailChoice& t) {
+    if (t.first < 2) return 0;
+    const int64_t nb = c->plan.layers[(size_t)t.first - 1].n;
+    const int64_t rows = std::max<int64_t>(nb, t.nmax);
+    return (size_t)2 * (size_t)(rows + 1) * t.ct * sizeof(float) <= c->tail_lds_bytes ? nb : 0;
+}
+int64_t tail_stage_rows(const klay_circuit* c, int B) { return tail_stage_rows(c, choose_tail_fwd(c, B)); }
 // ... and the layers the reverse sweep does, given the forward choice (fewer where a layer has a node with more
 // than kTailFanCap parents)
 TailChoice choose_tail_bwd(const klay_circuit* c, int B, int fwd_first) {
@@ -823,6 +834,7 @@ hipError_t tail_attr(int bytes) {
 // LDS bytes a workgroup of the persistent kernels may use: the largest of 160, 128 and 64 KB that the
 // runtime accepts for all of them (gfx950 has 160 KB per compute unit), 0 if none.
 size_t enable_tail_lds() {
+    static_assert(kTailLdsMax == 160 * 1024, "the first size tried is the largest");
     for (int kb : {160, 128, 64}) {
         const int bytes = kb * 1024;
         hipError_t e = tail_attr<8>(bytes);
@@ -835,15 +847,18 @@ size_t enable_tail_lds() {
     return 0;
 }
 
-// `stage`: room for the layer below the kernel's first one in column-major form.  When that layer fits the kernel's
-// LDS array it is transposed there first, so that a workgroup reads its column as one run instead of one float per row.
+// `stage`: room for the layer below the kernel's first one in column-major form.  When that layer fits an LDS
+// array (the arrays are made as long as it, if the LDS has the room) it is transposed there first, so that a
+// workgroup reads its column as one run instead of one float per row.
 void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* act, float* tb, float* stage, int B, int ld,
                      int semiring, const klay::SlabLeaf& leaf, float* out, hipStream_t s) {
     const klay::CircuitPlan& p = c->plan;
     const float* staged = nullptr;
-    if (!leaf.w && t.first >= 2) {
-        const int64_t nb = p.layers[(size_t)t.first - 1].n;
-        if (nb <= t.nmax && nb <= c->stage_rows) {
+    int nmax = t.nmax;
+    if (!leaf.w) {
+        const int64_t nb = tail_stage_rows(c, t);
+        if (nb > 0) {
+            nmax = (int)std::max<int64_t>(nb, t.nmax);
             dim3 tg((unsigned)((nb + 31) / 32), (unsigned)((B + 31) / 32));
             hipLaunchKernelGGL(klay::rows_to_cols_kernel, tg, dim3(256), 0, s,
                                act + (size_t)c->dl[(size_t)t.first - 1].row0 * ld, (int)nb, B, ld, stage);
@@ -853,11 +868,11 @@ void launch_tail_fwd(const klay_circuit* c, const TailChoice& t, const float* ac
     const klay::SlabLayer* descs = c->d_tail + (t.first - p.tail_first);
     const int n_layers = p.num_layers - t.first + 1;
     const int first_is_and = t.first & 1;
-    const size_t lds = (size_t)2 * (t.nmax + 1) * t.ct * sizeof(float);
+    const size_t lds = (size_t)2 * (nmax + 1) * t.ct * sizeof(float);
     dim3 grid((unsigned)((B + t.ct - 1) / t.ct));
 #define KLAY_TAIL_FWD(CT)                                                                              \
     hipLaunchKernelGGL((klay::slab_fwd_kernel<CT>), grid, dim3(klay::kSlabThreads), lds, s, descs,     \
-                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, t.nmax, tb, (int)c->tail_rows, leaf, \
+                       n_layers, first_is_and, c->d_index, act, B, ld, semiring, nmax, tb, (int)c->tail_rows, leaf, \
                        c->d_root_pos, p.num_roots, out, staged)
     switch (t.ct) {
     case 8: KLAY_TAIL_FWD(8); break;
@@ -1304,6 +1319,11 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
     }
     c->device = device;
     c->small_batch_edges = o.small_batch_edges;
+    if (c->plan.tail_first > 0) {
+        // sizes of the persistent kernels' buffers (part of the workspace, so host-only handles know them too)
+        const klay::CircuitPlan& p = c->plan;
+        for (int l = p.tail_first; l <= p.num_layers; ++l) c->tail_rows += p.layers[(size_t)l].n;
+    }
     if (device >= 0) {
         int ndev = 0;
         if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
@@ -1321,6 +1341,9 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
             return st;
         }
         c->tail_lds_bytes = c->plan.tail_first > 0 ? enable_tail_lds() : 0;
+    } else {
+        // a host-only handle sizes workspaces for a device that grants the whole LDS of a compute unit
+        c->tail_lds_bytes = c->plan.tail_first > 0 ? kTailLdsMax : 0;
     }
     *out = c.release();
     return KLAY_OK;
