@@ -220,6 +220,31 @@ def test_configs_full_size_every_column(klay, name, semiring):
     k.close()
 
 
+def test_large_batch_crosses_32_bit_element_indices(klay):
+    """Maximum sizes: B = 6000 on the 1e6-node circuit puts 4.9e9 floats (19 GB) into the activation buffer, so
+    the rows of its upper layers start beyond 2^32 elements, and the column-major buffers of the persistent
+    kernels are longer than that in bytes.  Sampled batch columns (both ends, the middle, random ones) against
+    the oracle, values and gradients; and columns with identical inputs must give bitwise identical outputs
+    wherever they sit in the batch."""
+    B = 6000
+    c, p, _ = make_config("layered_1m", seed=3, batch=B)
+    w32 = as_inputs(p, True)
+    w32[B - 1] = w32[0]
+    w32[B // 2 + 7] = w32[3]
+    dout = np.ones((B, c.roots.shape[0]), dtype=np.float32)
+    k = build(klay, c)
+    assert k.info()["num_nodes"] * B > 2 ** 32
+    got, gd = gpu_eval(k, w32, LOG, dout)
+    k.close()
+    assert np.array_equal(got[B - 1], got[0]) and np.array_equal(gd[B - 1], gd[0])
+    assert np.array_equal(got[B // 2 + 7], got[3]) and np.array_equal(gd[B // 2 + 7], gd[3])
+    cols = np.unique(np.concatenate([[0, 1, B // 2, B - 2, B - 1], np.random.default_rng(3).integers(0, B, 11)]))
+    ref, rd = _oracle_columns(c, w32[cols], LOG, dout[cols])
+    e = assert_log_close(got[cols], ref, "B=6000")
+    ratio = assert_grad_plain(gd[cols], rd, "B=6000 grad, dout = 1")
+    print("layered_1m B=%d, %d sampled columns: max|dlog| %.2e, gradient error %.3g x the plain bound" % (B, len(cols), e, ratio))
+
+
 # ------------------------------------------------------------------ batch shapes (lane mappings, ragged tails)
 @pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 9, 17, 31, 32, 33, 63, 64, 65, 100, 101, 128, 129, 255, 257, 300, 513])
 def test_batch_sizes(klay, B):
