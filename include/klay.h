@@ -270,7 +270,9 @@ klay_status klay_layer_nodes(const klay_circuit* c, int32_t layer, int32_t* orig
  */
 klay_status klay_root_positions(const klay_circuit* c, int32_t* position);
 
-/* Bytes of device workspace a forward (and, if need_backward, backward) call with batch B needs. */
+/* Bytes of device workspace a forward (and, if need_backward, backward) call with batch B needs.  A handle built
+ * with device = -1 answers for a device that grants a workgroup the whole 160 KB LDS of a compute unit (the
+ * persistent kernels' buffers depend on which layers fit). */
 size_t klay_workspace_bytes(const klay_circuit* c, int32_t B, int need_backward);
 
 /* Use caller device memory (256-byte aligned) as workspace instead of library-owned memory;
