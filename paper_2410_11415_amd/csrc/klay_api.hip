@@ -1027,7 +1027,9 @@ void launch_prod_parent(const klay_circuit::RealLayer& r, int n, const float* be
                         const int* zero_flag, const Geometry& g, int B, hipStream_t s) {
     if (n <= 0) return;                               // a layer without chain nodes can be empty
     const int rpw = 64 / g.w;
-    const int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
+    int64_t blocks = ((int64_t)n + 4 * rpw - 1) / (4 * rpw);
+    // with the values of the nodes given the kernel mostly finds nothing to do: a small grid that strides
+    if (own) blocks = std::min<int64_t>(blocks, std::max<int64_t>(256, 2048 / g.tiles));
     dim3 grid((unsigned)blocks, (unsigned)g.tiles);
 #define KLAY_PP(VEC, W) \
     hipLaunchKernelGGL((klay::prod_parent_kernel<VEC, W>), grid, dim3(256), 0, s, r.ptr, r.child, below, gl, n, B, g.ld, own, zero_flag)

@@ -1155,17 +1155,20 @@ __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restr
     const int lane = threadIdx.x & 63;
     const int col = ((int)blockIdx.y * W + (lane % W)) * VEC;
     if (col >= B) return;
-    const int64_t row64 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / W;
-    if (row64 >= n) return;
+    if (own && zero_flag && *zero_flag == 0) return;          // the pass that wrote the rows met no zero value: nothing to repair
+    // the grid is capped (the launch that finds the flag down should cost as little as a launch can): a
+    // workgroup takes every gridDim.x-th group of rows
+    for (int64_t blk = blockIdx.x; blk * (4 * RPW) < n; blk += gridDim.x) {
+    const int64_t row64 = (blk * 4 + (threadIdx.x >> 6)) * RPW + lane / W;
+    if (row64 >= n) continue;
     const int row = (int)row64;
     float nv[VEC];
-    if (own && zero_flag && *zero_flag == 0) return;          // the pass that wrote the rows met no zero value: nothing to repair
     if (own) {
         load_vec<VEC>(nv, own + (size_t)row * ld + col);
         bool zero_here = false;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) zero_here = zero_here || nv[v] == 0.0f;
-        if (!__any(zero_here)) return;
+        if (!__any(zero_here)) continue;
     }
     const int beg = ptr[row], end = ptr[row + 1];
     float q[VEC], z[VEC], gr[VEC];
@@ -1200,6 +1203,7 @@ __global__ __launch_bounds__(256) void prod_parent_kernel(const int32_t* __restr
         if (own && nv[v] != 0.0f) p[v] = gr[v];          // premultiplied already
     }
     store_vec<VEC>(g + (size_t)row * ld + col, p);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
