@@ -74,7 +74,7 @@ def kernel_symbol(cls, B, edges=False):
     while ct < 8 and (B + ct - 1) // ct > 256:
         ct *= 2
     fixed = {"tail_fwd": "klay::slab_fwd_kernel<%d>" % ct, "tail_bwd": "klay::slab_bwd_kernel<%d>" % ct,
-             "leaf": "klay::leaf_fwd_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
+             "leaf": "klay::leaf_fwd_kernel" if B > 32 else "klay::leaf_fwd_small_kernel", "bwd_leaf": "klay::leaf_bwd_kernel", "root": "klay::root_out_kernel",
              "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments of split rows)",
              "combine": "klay::combine_kernel<*>" if B > 32 else "klay::pass_kernel<*> (combine rows of split rows)",
              "main_combine": "klay::stream_combine_kernel<*>",

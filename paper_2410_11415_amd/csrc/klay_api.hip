@@ -1581,7 +1581,10 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     // leaf layer
     if (!fused_leaf) {
         prof.begin(KLAY_K_LEAF, 4.0 * B * V + 4.0 * B * (double)(V + p.layers[0].n));
-        if (V > 0) {
+        if (V > 0 && g.ld == B && B <= 32) {
+            hipLaunchKernelGGL(klay::leaf_fwd_small_kernel, dim3((unsigned)(((int64_t)V * B + 255) / 256)), dim3(256), 0, s,
+                               leaf_weights, neg_weights, (int)B, V, c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);
+        } else if (V > 0) {
             dim3 grid((unsigned)((V + 31) / 32), (unsigned)((g.ld + 63) / 64));
             hipLaunchKernelGGL(klay::leaf_fwd_kernel, grid, dim3(256), 0, s, leaf_weights, neg_weights, (int)B, V, g.ld,
                                c->d_pos_row, c->d_neg_row, wT, act, log_domain ? 1 : 0);

@@ -1251,6 +1251,22 @@ __global__ __launch_bounds__(256) void leaf_fwd_kernel(const float* __restrict__
     }
 }
 
+// The same for small batches (ld = B <= 32), where the tile would be all but empty: a thread per (variable, column).
+__global__ __launch_bounds__(256) void leaf_fwd_small_kernel(const float* __restrict__ w, const float* __restrict__ wneg,
+                                                             int B, int V, const int32_t* __restrict__ pos_row,
+                                                             const int32_t* __restrict__ neg_row,
+                                                             float* __restrict__ wT, float* __restrict__ act0,
+                                                             int log_domain) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)V * B) return;
+    const int v = (int)(i / B), b = (int)(i % B);
+    const float x = w[(size_t)b * V + v];
+    wT[i] = x;
+    const int pr = pos_row[v], nr = neg_row[v];
+    if (pr >= 0) act0[(size_t)pr * B + b] = x;
+    if (nr >= 0) act0[(size_t)nr * B + b] = wneg ? wneg[(size_t)b * V + v] : (log_domain ? log1mexp_f(x) : 1.0f - x);
+}
+
 __global__ void fill_row_kernel(float* row, int ld, float value) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b < ld) row[b] = value;
