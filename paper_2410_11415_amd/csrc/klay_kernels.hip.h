@@ -169,10 +169,13 @@ __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float
     else if (OP == OP_PROD) acc *= x;
     else if (OP == OP_MAX) acc = fmaxf(acc, x);
     else if (OP == OP_LSE) {
-        const float d = x - mx;                                   // +inf on the first finite element
-        const float e = (x == -INFINITY) ? 0.0f : fexp(-fabsf(d));
-        acc = (d > 0.0f) ? fmaf(acc, e, 1.0f) : acc + e;          // d is NaN only for -inf - -inf: e = 0
-        mx = fmaxf(mx, x);
+        // d is +inf on the first finite element (e = 0, acc = 1), -inf for an impossible child under a finite
+        // maximum (e = 0), and NaN only for -inf - -inf, where the maximum of NaN and 0 is 0 and the comparison fails
+        const float d = x - mx;
+        const float e = fmaxf(fexp(-fabsf(d)), 0.0f);
+        const bool up = d > 0.0f;                                 // the same as x > mx
+        acc = up ? fmaf(acc, e, 1.0f) : acc + e;
+        mx = up ? x : mx;
     } else {
         const float wgt = !weighted ? 1.0f : ((y == -INFINITY) ? 0.0f : fexp(nc - y));
         acc = fmaf(x, wgt, acc);
