@@ -167,7 +167,7 @@ __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float
     }
     if (OP == OP_SUM) acc += x;
     else if (OP == OP_PROD) acc *= x;
-    else if (OP == OP_MAX) acc = fmaxf(acc, x);
+    else if (OP == OP_MAX) acc = x > acc ? x : acc;               // no NaN reaches here: two instructions, fmaxf takes three
     else if (OP == OP_LSE) {
         // d is +inf on the first finite element (e = 0, acc = 1), -inf for an impossible child under a finite
         // maximum (e = 0), and NaN only for -inf - -inf, where the maximum of NaN and 0 is 0 and the comparison fails
@@ -775,7 +775,10 @@ __device__ __forceinline__ void slab_fwd_block(const uint32_t (&a)[kSlabD], uint
                 const float v = below[(size_t)(live ? ch : 0) * ld + (live ? k : 0)];
                 x[u][k] = live ? v : dead_value<OP>();
             } else {
-                x[u][k] = prev[ch * CT + k];
+                // byte offset of the source's CT values: the shift drops the end-of-chunk bit, the only flag
+                // of a forward stream (CT = 1, 2, 4, 8: at least the top two bits go)
+                constexpr int kShift = CT == 1 ? 2 : (CT == 2 ? 3 : (CT == 4 ? 4 : 5));
+                x[u][k] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(prev) + (a[u] << kShift) + 4 * k);
             }
         }
     }
