@@ -146,7 +146,7 @@ __device__ __forceinline__ float encode_h(float g, float n) {
 __device__ __forceinline__ float decode_h(float hbits, float nc) {
     const uint32_t b = __float_as_uint(hbits);
     const float v = fexp(__uint_as_float(b & ~1u) + nc);
-    return (b & 1u) ? -v : v;
+    return __uint_as_float(__float_as_uint(v) | (b << 31));      // v >= 0: the stored sign bit goes on with one shift-or
 }
 
 __device__ __forceinline__ float premultiply(float g, float n) {
