@@ -55,7 +55,7 @@ def load_traffic(workload, batch, semiring, backward, chains):
     return table.get("runs", {}).get(key)
 
 
-def kernel_symbol(cls, B, edges=False):
+def kernel_symbol(cls, B, edges=False, maxlog=False):
     """rocprofv3's name for the kernel behind a profiling class (template arguments as it prints them)."""
     vec = 4 if B > 128 else (2 if B > 64 else 1)
     ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4, "bwd_prod": 5,
@@ -78,6 +78,7 @@ def kernel_symbol(cls, B, edges=False):
              "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments of split rows)",
              "combine": "klay::combine_kernel<*>" if B > 32 else "klay::pass_kernel<*> (combine rows of split rows)",
              "main_combine": "klay::stream_combine_kernel<*>",
+             "fwd_or_fused": "klay::stream_kernel<%d, %d>" % (11 if maxlog else 10, vec),
              "prod_edges": "klay::prod_parent_kernel<%d, %d>" % (vec, 64 if B > 32 else w_small)}
     return fixed.get(cls, cls)
 
@@ -126,6 +127,10 @@ def main():
     ap.add_argument("--unary-chains", action="store_true",
                     help="the paper's layerization throughout (one unary chain node per node and layer an edge skips) "
                          "instead of the default, which is padding-free below the narrow top of the circuit")
+    ap.add_argument("--no-fusion", action="store_true",
+                    help="every forward pass writes the value of every AND node (for comparison; by default a forward "
+                         "pass that no backward pass follows leaves out the AND rows that the OR rows above can "
+                         "evaluate themselves)")
     ap.add_argument("--small-batch-edges", action="store_true",
                     help="B <= 32: the lanes = edges kernel instead of a lane group per row (for comparison)")
     ap.add_argument("--f64", action="store_true",
@@ -185,7 +190,7 @@ def main():
 
     t0 = time.perf_counter()
     k = pkg.Circuit(*circ.arrays(), device=0, no_tail=args.no_tail, unary_chains=args.unary_chains,
-                    small_batch_edges=args.small_batch_edges)
+                    small_batch_edges=args.small_batch_edges, no_fusion=args.no_fusion)
     t_build = time.perf_counter() - t0
     info = k.info()
     E, N = info["num_edges"], info["num_nodes"]
@@ -260,7 +265,7 @@ def main():
     for name, c in classes.items():
         if not c["launches"]:
             continue
-        g = by_symbol.setdefault(kernel_symbol(name, B, args.small_batch_edges), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
+        g = by_symbol.setdefault(kernel_symbol(name, B, args.small_batch_edges, semiring == pkg.KLAY_MAXLOG), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
                                                           "classes": []})
         for f in ("ms", "launches", "alg_bytes", "min_bytes"):
             g[f] += c[f]
@@ -271,7 +276,7 @@ def main():
     alg_bytes_step = sum(c["alg_bytes"] for c in classes.values()) / prof_steps
     min_bytes_step = sum(c["min_bytes"] for c in classes.values()) / prof_steps
     measured = None
-    if not args.no_tail and not args.graph and not args.small_batch_edges:
+    if not args.no_tail and not args.graph and not args.small_batch_edges and not args.no_fusion:
         measured = load_traffic(args.workload, B, semiring_name, backward, bool(args.unary_chains))
     per_launch_s = d["ms"] * 1e-3 / max(1, d["launches"])
     traffic = None
@@ -387,6 +392,7 @@ def main():
                                    "padding-free up to layer %d of %d, unary chain nodes above" % (
                                        info["alias_top_layer"], info["num_layers"]),
                    "padding_free_layers": info["alias_top_layer"],
+                   "fused_and_rows": 0 if (args.no_fusion or backward or B <= 64 or semiring == pkg.KLAY_REAL) else info["num_fused_rows"],
                    "layers": info["num_layers"], "layered_nodes": N, "layered_edges": E,
                    "dag_nodes": info["dag_nodes"], "dag_edges": info["dag_edges"],
                    "pad_nodes": info["num_pad_nodes"], "num_vars": info["num_vars"], "num_roots": info["num_roots"],

@@ -72,6 +72,13 @@ typedef struct klay_options {
     int32_t tail_rows_cap;   /* > 0: layers with more nodes than this are no candidates for the persistent
                                 kernels (at most 20000, the default; smaller values move the boundary
                                 between the two parts of the layerization up: for tests)                 */
+    int32_t no_fusion;       /* 1: every AND node's value is written.  Default (0): in the padding-free part an
+                                AND node with at most one child that is not a leaf, few children and parents,
+                                and only short OR rows above it is fused into those rows when the batch has more
+                                than 64 columns and the semiring is a log-domain one: they read its children and
+                                sum them themselves, and the reverse sweep forms its value the same way, so its
+                                row of the value buffer is never written (one launch and one row per node less;
+                                same results up to the order of the sums)                                */
 } klay_options;
 
 typedef struct klay_info_t {
@@ -93,6 +100,7 @@ typedef struct klay_info_t {
                                  (0: none); the layers actually taken depend on the batch size       */
     int64_t num_merged_nodes; /* input gates identified with a structurally identical gate          */
     int64_t alias_top_layer;  /* A: the layers 1 .. A are padding-free (see klay_options.unary_chains)  */
+    int64_t num_fused_rows;   /* AND rows that the fused plans do not evaluate (see klay_options.no_fusion) */
 } klay_info_t;
 
 /* Per-kernel-class timing of the most recent forward / backward call, filled only while
@@ -101,6 +109,7 @@ typedef struct klay_info_t {
  * the streaming kernel for B > 32), SPLIT the segment launches of split rows, COMBINE their
  * combine launches, MAIN_COMBINE (any operation) the launches that take the main rows and the combine
  * rows of a layer together (32 < B <= 64, where the segments run in a launch of their own first),
+ * FWD_OR_FUSED the forward launches of OR layers that read the children of fused AND rows (klay_options.no_fusion),
  * PROD_EDGES the per-parent pass of the real-semiring reverse sweep over a product layer (adjoint
  * times the product of the non-zero children, in place), BWD_PROD the by-child pass that follows
  * it, BWD_SUM_MUL / BWD_PROD_MUL the passes into a product layer, whose rows leave multiplied by
@@ -113,7 +122,7 @@ enum { KLAY_K_LEAF = 0, KLAY_K_FWD_SUM, KLAY_K_FWD_PROD, KLAY_K_FWD_LSE, KLAY_K_
        KLAY_K_SEED, KLAY_K_BWD_SUM, KLAY_K_BWD_SOFTMAX, KLAY_K_BWD_LEAF, KLAY_K_TAIL_FWD,
        KLAY_K_TAIL_BWD, KLAY_K_SPLIT, KLAY_K_PROD_EDGES, KLAY_K_FWD_MAX, KLAY_K_BWD_SUM_ENC,
        KLAY_K_BWD_SOFTMAX_ONE, KLAY_K_BWD_PROD, KLAY_K_BWD_SUM_MUL, KLAY_K_BWD_PROD_MUL,
-       KLAY_K_COMBINE, KLAY_K_MAIN_COMBINE, KLAY_K_COUNT };
+       KLAY_K_COMBINE, KLAY_K_MAIN_COMBINE, KLAY_K_FWD_OR_FUSED, KLAY_K_COUNT };
 typedef struct klay_profile_t {
     float   ms[KLAY_K_COUNT];          /* summed device time of the class's launches       */
     int32_t launches[KLAY_K_COUNT];

@@ -21,7 +21,7 @@ KLAY_LIT, KLAY_AND, KLAY_OR, KLAY_TRUE, KLAY_FALSE = range(5)
 KLAY_STATIC_WORKSPACE_BYTES = 64 << 20
 KERNEL_CLASSES = ("leaf", "fwd_sum", "fwd_prod", "fwd_lse", "root", "seed", "bwd_sum", "bwd_softmax", "bwd_leaf",
                   "tail_fwd", "tail_bwd", "split", "prod_edges", "fwd_max", "bwd_sum_enc", "bwd_softmax_one",
-                  "bwd_prod", "bwd_sum_mul", "bwd_prod_mul", "combine", "main_combine")
+                  "bwd_prod", "bwd_sum_mul", "bwd_prod_mul", "combine", "main_combine", "fwd_or_fused")
 
 EXPORTS = ("klay_build", "klay_build_ex", "klay_forward", "klay_backward", "klay_info", "klay_layer_sizes",
            "klay_layer_csr", "klay_layer_nodes", "klay_workspace_bytes", "klay_set_workspace",
@@ -39,7 +39,7 @@ class KlayError(RuntimeError):
 class klay_options(ctypes.Structure):
     _fields_ = [("no_reorder", ctypes.c_int32), ("heavy_fan", ctypes.c_int32), ("min_segment", ctypes.c_int32),
                 ("no_tail", ctypes.c_int32), ("unary_chains", ctypes.c_int32), ("no_merge", ctypes.c_int32),
-                ("small_batch_edges", ctypes.c_int32), ("tail_rows_cap", ctypes.c_int32)]
+                ("small_batch_edges", ctypes.c_int32), ("tail_rows_cap", ctypes.c_int32), ("no_fusion", ctypes.c_int32)]
 
 
 class klay_info_t(ctypes.Structure):
@@ -49,7 +49,7 @@ class klay_info_t(ctypes.Structure):
                 ("max_layer_nodes", ctypes.c_int64), ("max_fan_in", ctypes.c_int64), ("max_fan_out", ctypes.c_int64),
                 ("num_split_rows", ctypes.c_int64), ("index_bytes", ctypes.c_int64),
                 ("tail_first_layer", ctypes.c_int64), ("num_merged_nodes", ctypes.c_int64),
-                ("alias_top_layer", ctypes.c_int64)]
+                ("alias_top_layer", ctypes.c_int64), ("num_fused_rows", ctypes.c_int64)]
 
 
 class klay_profile_t(ctypes.Structure):
@@ -224,7 +224,7 @@ class Circuit:
 
     def __init__(self, num_vars, node_type, node_lit, child_ptr, child_idx, roots, device=0,
                  no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False,
-                 unary_chains=False, no_merge=False, small_batch_edges=False, tail_rows_cap=0):
+                 unary_chains=False, no_merge=False, small_batch_edges=False, tail_rows_cap=0, no_fusion=False):
         node_type = np.ascontiguousarray(node_type, dtype=np.uint8)
         node_lit = np.ascontiguousarray(node_lit, dtype=np.int32)
         child_ptr = np.ascontiguousarray(child_ptr, dtype=np.int64)
@@ -235,7 +235,7 @@ class Circuit:
         if child_ptr.shape[0] and child_idx.shape[0] != child_ptr[-1]:
             raise ValueError("child_idx must have child_ptr[-1] entries")
         opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail), int(unary_chains),
-                            int(no_merge), int(small_batch_edges), int(tail_rows_cap))
+                            int(no_merge), int(small_batch_edges), int(tail_rows_cap), int(no_fusion))
         self._h = None
         self._h = klay_build(int(num_vars), node_type.shape[0], _np_ptr(node_type), _np_ptr(node_lit),
                              _np_ptr(child_ptr), _np_ptr(child_idx) if child_idx.size else None,
@@ -467,9 +467,9 @@ class Builder:
                                 roots.shape[0], _np_ptr(roots))
 
     def finish(self, device=0, no_reorder=False, heavy_fan=0, min_segment=0, no_tail=False,
-               unary_chains=False, no_merge=False, small_batch_edges=False, tail_rows_cap=0) -> Circuit:
+               unary_chains=False, no_merge=False, small_batch_edges=False, tail_rows_cap=0, no_fusion=False) -> Circuit:
         opts = klay_options(int(no_reorder), int(heavy_fan), int(min_segment), int(no_tail), int(unary_chains),
-                            int(no_merge), int(small_batch_edges), int(tail_rows_cap))
+                            int(no_merge), int(small_batch_edges), int(tail_rows_cap), int(no_fusion))
         return Circuit._from_handle(klay_builder_finish(self._b, int(device), opts), device)
 
     def close(self):

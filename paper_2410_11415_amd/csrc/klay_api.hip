@@ -85,6 +85,11 @@ struct DevLayer {
     int64_t n = 0, e = 0;
     int64_t row0 = 0;        // first row of this layer in the activation buffer
     DevPass fwd, bwd;
+    // the fused plans (LayerPlan::fwd_kept, fwd2), where the layerizer built them
+    DevPass fwd_kept, fwd2;
+    bool has_fwd2 = false;
+    int64_t n_fused = 0;     // AND layers: so many rows are fused (their values are not written when the fused plans run)
+    bool has_fwd_kept = false;
     const uint32_t* multi = nullptr;   // OR layers: bit r = node r has more than one child
     bool has_multi = false;
 };
@@ -150,7 +155,10 @@ struct klay_circuit {
     void* ws_user = nullptr;
     size_t ws_user_bytes = 0;
     // state of the most recent forward
+    bool no_fusion = false;                    // klay_options.no_fusion
     bool have_fwd = false;
+    bool last_fused = false;                   // the forward pass ran the fused plans: the values of fused AND rows do not exist
+    bool bwd_followed = false;                 // klay_backward was called after the most recent forward pass
     int32_t last_B = 0;
     int last_semiring = 0;
     bool last_neg_explicit = false;            // the negated literals had weights of their own
@@ -338,6 +346,8 @@ void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, con
     case klay::OP_SOFTMAX_H: launch_stream_op<klay::OP_SOFTMAX_H>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     case klay::OP_SUM_P: launch_stream_op<klay::OP_SUM_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     case klay::OP_PROD_BWD_P: launch_stream_op<klay::OP_PROD_BWD_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_LSE2: launch_stream_op<klay::OP_LSE2>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_MAX2: launch_stream_op<klay::OP_MAX2>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     }
 }
@@ -515,10 +525,12 @@ klay_status upload(klay_circuit* c) {
         o_tail = pk.add(reinterpret_cast<const int32_t*>(descs.data()), descs.size() * sizeof(klay::SlabLayer) / sizeof(int32_t));
     }
     const size_t o_leaf_code = pk.add(p.leaf_code);
-    std::vector<PassOffsets> fo((size_t)L + 1), bo((size_t)L + 1);
+    std::vector<PassOffsets> fo((size_t)L + 1), bo((size_t)L + 1), fko((size_t)L + 1), f2o((size_t)L + 1);
     for (int l = 1; l <= L; ++l) {
         fo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd);
         bo[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].bwd);
+        if (!p.layers[(size_t)l].fwd_kept.ptr.empty()) fko[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd_kept);
+        if (!p.layers[(size_t)l].fwd2.ptr.empty()) f2o[(size_t)l] = pack_pass(pk, p.layers[(size_t)l].fwd2);
     }
     std::vector<size_t> mo((size_t)L + 1, 0);
     for (int l = 2; l <= L; l += 2) mo[(size_t)l] = pk.add(p.layers[(size_t)l].multi);
@@ -548,6 +560,10 @@ klay_status upload(klay_circuit* c) {
         if (l >= 1) {
             bind_pass(d.fwd, p.layers[(size_t)l].fwd, fo[(size_t)l], base);
             bind_pass(d.bwd, p.layers[(size_t)l].bwd, bo[(size_t)l], base);
+            const klay::LayerPlan& lp = p.layers[(size_t)l];
+            d.n_fused = lp.n_fused;
+            if (!lp.fwd_kept.ptr.empty()) { bind_pass(d.fwd_kept, lp.fwd_kept, fko[(size_t)l], base); d.has_fwd_kept = true; }
+            if (!lp.fwd2.ptr.empty()) { bind_pass(d.fwd2, lp.fwd2, f2o[(size_t)l], base); d.has_fwd2 = true; }
             if ((l & 1) == 0) {
                 d.multi = reinterpret_cast<const uint32_t*>(base + mo[(size_t)l]);
                 for (uint32_t w : p.layers[(size_t)l].multi) d.has_multi = d.has_multi || w != 0;
@@ -575,7 +591,8 @@ klay_status upload(klay_circuit* c) {
 // entries themselves.
 double pass_bytes(int op, double entries, double rows, int B) {
     const double per_entry = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
-    const double per_row = (op == klay::OP_SUM || op == klay::OP_PROD || op == klay::OP_LSE || op == klay::OP_MAX) ? 1.0 : 2.0;
+    const double per_row = (op == klay::OP_SUM || op == klay::OP_PROD || op == klay::OP_LSE || op == klay::OP_MAX ||
+                            op == klay::OP_LSE2 || op == klay::OP_MAX2) ? 1.0 : 2.0;
     return 4.0 * B * (per_entry * entries + per_row * rows) + 4.0 * (entries + rows);
 }
 
@@ -1304,6 +1321,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
         if (opts->tail_rows_cap > 0) o.tail_rows_cap = opts->tail_rows_cap;
         o.no_merge = opts->no_merge != 0;
         o.small_batch_edges = opts->small_batch_edges != 0;
+        o.no_fusion = opts->no_fusion != 0;
     }
     std::unique_ptr<klay_circuit> c;
     try {
@@ -1321,6 +1339,7 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
     }
     c->device = device;
     c->small_batch_edges = o.small_batch_edges;
+    c->no_fusion = o.no_fusion;
     if (c->plan.tail_first > 0) {
         // sizes of the persistent kernels' buffers (part of the workspace, so host-only handles know them too)
         const klay::CircuitPlan& p = c->plan;
@@ -1454,6 +1473,7 @@ klay_status klay_info(const klay_circuit* c, klay_info_t* info) {
     info->tail_first_layer = p.tail_first;
     info->num_merged_nodes = p.num_merged;
     info->alias_top_layer = p.alias_top;
+    info->num_fused_rows = p.num_fused;
     return KLAY_OK;
 }
 
@@ -1599,6 +1619,12 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     }
 
     // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4)
+    // The fused plans run in the log-domain semirings where the streaming kernel takes main rows and segments in one
+    // launch (two or four columns per lane) and the reverse sweep works in the one-gather form.
+    // A handle whose previous forward pass was followed by klay_backward is in a training loop: the reverse sweep
+    // needs every value, so this pass writes them all (klay_backward would otherwise evaluate the fused rows first).
+    const bool fused = log_domain && g.w == 64 && g.vec >= 2 && p.num_fused > 0 && !c->no_fusion &&
+                       (static_ws || !c->bwd_followed);
     const int last_regular = tail.first > 0 ? tail.first - 1 : L;
     for (int l = 1; l <= last_regular; ++l) {
         const DevLayer& d = c->dl[(size_t)l];
@@ -1610,7 +1636,15 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
                         : op == klay::OP_MAX ? KLAY_K_FWD_MAX : KLAY_K_FWD_LSE;
         // up to alias_top child entries are rows of the whole buffer, above it of the layer below
         const float* below = l <= p.alias_top ? act : act + (size_t)c->dl[(size_t)l - 1].row0 * g.ld;
-        run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
+        if (fused && is_and && d.n_fused > 0) {
+            // the fused rows are not evaluated: the OR rows above read their children
+            if (d.has_fwd_kept) run_pass_set(op, op, d.fwd_kept, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
+        } else if (fused && !is_and && d.has_fwd2) {
+            run_pass_set(semiring == KLAY_MAXLOG ? klay::OP_MAX2 : klay::OP_LSE2, op, d.fwd2, below, nullptr, nullptr,
+                         act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, KLAY_K_FWD_OR_FUSED);
+        } else {
+            run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
+        }
     }
 
     if (tail.first > 0) {
@@ -1639,6 +1673,8 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     KLAY_HIP(hipGetLastError());
     if (static_ws) return KLAY_OK;       // the values live in the shared array: nothing to differentiate later
     c->have_fwd = true;
+    c->last_fused = fused;
+    c->bwd_followed = false;
     c->last_B = B;
     c->last_semiring = semiring;
     c->last_neg_explicit = neg_weights != nullptr;
@@ -1683,6 +1719,18 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
     // final by then).  The leaf kernel reads the rows of layer 0 at the start of G.
     auto grow = [&](int l) { return G + (size_t)c->dl[(size_t)l].row0 * g.ld; };
     auto values = [&](int l) { return act + (size_t)c->dl[(size_t)l].row0 * g.ld; };
+
+    c->bwd_followed = true;
+    if (c->last_fused) {
+        // The forward pass ran the fused plans: the values of the fused AND rows, which this sweep needs, were
+        // never written.  Evaluate those layers now (all their rows; the others come out the same again).
+        for (int l = 1; l < B0; l += 2) {
+            const DevLayer& d = c->dl[(size_t)l];
+            if (d.n_fused > 0)
+                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.fwd, act, nullptr, nullptr, values(l), seg_rows, g, B, s, prof, KLAY_K_FWD_SUM);
+        }
+        c->last_fused = false;
+    }
 
     if (real) {
         // Real semiring: a sum layer passes adjoints through (plain by-child sums).  For a product layer

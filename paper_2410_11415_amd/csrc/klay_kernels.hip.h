@@ -16,7 +16,10 @@
 namespace klay {
 
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4, OP_PROD_BWD = 5, OP_SUM_H = 6, OP_SOFTMAX_H = 7,
-                    OP_SUM_P = 8, OP_PROD_BWD_P = 9 };
+                    OP_SUM_P = 8, OP_PROD_BWD_P = 9,
+                    // over the fused plans (see LayerPlan::fwd2): an OR row whose children are groups of entries
+                    // (sum within a group, then logsumexp / max over the groups)
+                    OP_LSE2 = 10, OP_MAX2 = 11 };
 // what the ops have in common: `own` = the walk needs the value of the output row itself, `additive` = partial
 // results add up
 template <int OP> struct OpTraits {
@@ -153,10 +156,32 @@ __device__ __forceinline__ float premultiply(float g, float n) {
     return n != 0.0f ? __uint_as_float(__float_as_uint(g * n) & ~1u) : g;
 }
 
+// one element of a running logsumexp: (mx, acc) = (maximum so far, sum of exp(x - mx)), one exp per element
+__device__ __forceinline__ void lse_step(float& acc, float& mx, float x) {
+    // d is +inf on the first finite element (e = 0, acc = 1), -inf for an impossible child under a finite
+    // maximum (e = 0), and NaN only for -inf - -inf, where the maximum of NaN and 0 is 0 and the comparison fails
+    const float d = x - mx;
+    const float e = fmaxf(fexp(-fabsf(d)), 0.0f);
+    const bool up = d > 0.0f;                                 // the same as x > mx
+    acc = up ? fmaf(acc, e, 1.0f) : acc + e;
+    mx = up ? x : mx;
+}
+
+// nc: the value of the output row itself where the operation needs it; OP_LSE2 / OP_MAX2 keep the sum of the
+// group in hand there (weighted = the entry closes its group).
 template <int OP>
-__device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float nc, bool weighted = true) {
+__device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float& nc, bool weighted = true) {
     if (OP == OP_SUM_H || OP == OP_SUM_P) { acc += x; return; }
     if (OP == OP_SOFTMAX_H) { acc += weighted ? decode_h(x, nc) : x; return; }
+    if (OP == OP_LSE2 || OP == OP_MAX2) {
+        nc += x;
+        if (weighted) {
+            if (OP == OP_LSE2) lse_step(acc, mx, nc);
+            else acc = nc > acc ? nc : acc;
+            nc = 0.0f;
+        }
+        return;
+    }
     if (OpTraits<OP>::shares) {
         const uint32_t bits = __float_as_uint(x);
         const float val = __uint_as_float(bits & ~1u);
@@ -168,15 +193,8 @@ __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float
     if (OP == OP_SUM) acc += x;
     else if (OP == OP_PROD) acc *= x;
     else if (OP == OP_MAX) acc = x > acc ? x : acc;               // no NaN reaches here: two instructions, fmaxf takes three
-    else if (OP == OP_LSE) {
-        // d is +inf on the first finite element (e = 0, acc = 1), -inf for an impossible child under a finite
-        // maximum (e = 0), and NaN only for -inf - -inf, where the maximum of NaN and 0 is 0 and the comparison fails
-        const float d = x - mx;
-        const float e = fmaxf(fexp(-fabsf(d)), 0.0f);
-        const bool up = d > 0.0f;                                 // the same as x > mx
-        acc = up ? fmaf(acc, e, 1.0f) : acc + e;
-        mx = up ? x : mx;
-    } else {
+    else if (OP == OP_LSE) lse_step(acc, mx, x);
+    else {
         const float wgt = !weighted ? 1.0f : ((y == -INFINITY) ? 0.0f : fexp(nc - y));
         acc = fmaf(x, wgt, acc);
     }
@@ -184,12 +202,12 @@ __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float
 
 template <int OP>
 __device__ __forceinline__ float finish(float acc, float mx) {
-    if (OP == OP_LSE) return (mx == -INFINITY) ? -INFINITY : mx + flog(acc);
+    if (OP == OP_LSE || OP == OP_LSE2) return (mx == -INFINITY) ? -INFINITY : mx + flog(acc);
     return acc;
 }
 
 template <int OP>
-__device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : (OP == OP_MAX ? -INFINITY : 0.0f); }
+__device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : ((OP == OP_MAX || OP == OP_MAX2) ? -INFINITY : 0.0f); }
 
 // what an index entry that is not part of the row contributes: nothing
 template <int OP>
@@ -221,6 +239,7 @@ __device__ __forceinline__ void stream_body(int bx, int nbx, const int2* __restr
     // With one column per lane (B <= 64) a row is 256 bytes and twice as many have to be in flight:
     // 8 (4) measured 3% faster on the power-law workload at B = 64, 4% on the headline circuit at B = 64.
     constexpr int CH = (OP == OP_SOFTMAX_BWD) ? (VEC == 1 ? 4 : 2) : (VEC == 1 ? 8 : 4);
+    static_assert(kGroupEnd == kWeighted, "the fused plans reuse this bit");
     // the walk needs the output row's own value
     constexpr bool OWN = OpTraits<OP>::own;
     const int lane = threadIdx.x & 63;
@@ -633,7 +652,7 @@ __device__ __forceinline__ void combine_body(int row, const PassArgs& a) {
         for (int i = 0; i < CH; ++i) {
             const bool live = j + i < end;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) accumulate<OP>(acc[v], mx[v], live ? x[i][v] : dead_value<OP>(), 0.0f, 0.0f, false);
+            for (int v = 0; v < VEC; ++v) { float none = 0.0f; accumulate<OP>(acc[v], mx[v], live ? x[i][v] : dead_value<OP>(), 0.0f, none, false); }
         }
     }
     if (wave > 0) {
@@ -786,7 +805,7 @@ __device__ __forceinline__ void slab_fwd_block(const uint32_t (&a)[kSlabD], uint
 #pragma unroll
     for (int u = 0; u < kSlabD; ++u) {
 #pragma unroll
-        for (int k = 0; k < CT; ++k) accumulate<OP>(acc[k], mx[k], x[u][k], 0.0f, 0.0f);
+        for (int k = 0; k < CT; ++k) { float none = 0.0f; accumulate<OP>(acc[k], mx[k], x[u][k], 0.0f, none); }
         // the end-of-chunk bit is the same in all words of a line
         if (__builtin_amdgcn_readfirstlane((int)a[u]) & (int)kLast) {
             const int r = q * 64 + lane;

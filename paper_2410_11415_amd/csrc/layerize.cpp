@@ -36,8 +36,28 @@ int32_t segment_len(int64_t k, const Options& opt) {
 }
 }  // namespace
 
-void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out,
-                    const uint32_t* flags, const uint32_t* row_bits) {
+void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx_in, const Options& opt, PassPlan& out,
+                    const uint32_t* flags_in, const uint32_t* row_bits, const uint8_t* skip) {
+    // rows to leave out become empty rows of a CSR of their own, then one kSkipRow entry each, like split rows
+    std::vector<int32_t> kept_ptr, kept_idx;
+    std::vector<uint32_t> kept_flags;
+    const int32_t* idx = idx_in;
+    const uint32_t* flags = flags_in;
+    if (skip) {
+        kept_ptr.resize((size_t)n + 1);
+        kept_ptr[0] = 0;
+        for (int64_t r = 0; r < n; ++r) {
+            if (!skip[(size_t)r])
+                for (int32_t j = ptr[r]; j < ptr[r + 1]; ++j) {
+                    kept_idx.push_back(idx_in[j]);
+                    if (flags_in) kept_flags.push_back(flags_in[j]);
+                }
+            kept_ptr[(size_t)r + 1] = (int32_t)kept_idx.size();
+        }
+        ptr = kept_ptr.data();
+        idx = kept_idx.data();
+        if (flags_in) flags = kept_flags.data();
+    }
     auto row_flag = [&](int64_t r) -> uint32_t { return row_bits && ((row_bits[(size_t)r >> 5] >> (r & 31)) & 1u) ? kRowFlag : 0u; };
     const int64_t e = ptr[n];
     out = PassPlan();
@@ -77,7 +97,10 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
     out.n_seg = (int32_t)n_seg;
     out.n_heavy = (int32_t)n_heavy;
     out.ptr.resize((size_t)(n + n_seg + 1));
-    out.idx.assign((size_t)(e - heavy_edges + n_heavy + heavy_edges + kIdxPad), 0u);
+    int64_t n_skip = 0;
+    if (skip)
+        for (int64_t r = 0; r < n; ++r) n_skip += skip[(size_t)r] != 0;
+    out.idx.assign((size_t)(e - heavy_edges + n_heavy + n_skip + heavy_edges + kIdxPad), 0u);
     out.seg_owner.resize((size_t)n_seg);
     out.comb_ptr.resize((size_t)(n_heavy + 1));
     out.comb_row.resize((size_t)n_heavy);
@@ -86,7 +109,9 @@ void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Opt
     for (int64_t r = 0; r < n; ++r) {
         out.ptr[(size_t)r] = w;
         int64_t k = ptr[r + 1] - ptr[r];
-        if (k <= heavy) {
+        if (skip && skip[(size_t)r]) {
+            out.idx[(size_t)w++] = kSkipRow;
+        } else if (k <= heavy) {
             for (int64_t j = ptr[r]; j < ptr[r + 1]; ++j) out.idx[(size_t)w++] = (uint32_t)idx[j] | (flags ? flags[j] : 0u);
             if (k > 0) out.idx[(size_t)w - 1] |= kLastEdge | row_flag(r);
         } else {
@@ -431,6 +456,34 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     // lowest level at which c has a stand-in (none if that is above need[c])
     auto lo = [&](int64_t c) { return std::max(h[(size_t)c] + 1, B0); };
 
+    // Fused AND rows (see LayerPlan): AND nodes of the padding-free part whose value nothing has to read.
+    std::vector<uint8_t> fused((size_t)N, 0);
+    if (B0 > 0 && !opt.no_fusion) {
+        std::vector<uint8_t> cand((size_t)N, 0);
+        for (int64_t c = 0; c < N; ++c) {
+            if (!reach[(size_t)c] || !(h[(size_t)c] & 1) || h[(size_t)c] >= B0 || need[(size_t)c] >= B0) continue;
+            const int64_t fi = child_ptr[c + 1] - child_ptr[c];
+            int64_t gates = 0;
+            for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) gates += h[(size_t)child_idx[j]] > 0;
+            cand[(size_t)c] = fi >= 1 && gates <= 1 && fi <= kFusedRowMax;
+        }
+        // every parent has to be an OR row that stays short when it reads the children of its fused children
+        for (int64_t p = 0; p < N; ++p) {
+            if (!reach[(size_t)p] || h[(size_t)p] == 0) continue;
+            int64_t len = 0;
+            bool any = false;
+            for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) {
+                const int32_t c = child_idx[j];
+                any = any || cand[(size_t)c];
+                len += cand[(size_t)c] ? child_ptr[c + 1] - child_ptr[c] : 1;
+            }
+            if (!any || ((h[(size_t)p] & 1) == 0 && len <= kFusedRowMax)) continue;
+            for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) cand[(size_t)child_idx[j]] |= 2;      // not through this parent
+        }
+        for (int64_t c = 0; c < N; ++c)
+            if (cand[(size_t)c] == 1) { fused[(size_t)c] = 1; ++plan.num_fused; }
+    }
+
     std::vector<int64_t> count((size_t)L + 1, 0);
     std::vector<int64_t> pad_base((size_t)N + 1, 0);
     for (int64_t c = 0; c < N; ++c) {
@@ -626,6 +679,9 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         }
     }
 
+    // the row of node x in the whole activation buffer (the padding-free part)
+    auto own_row = [&](int32_t x) -> int32_t { return (int32_t)(plan.row0[(size_t)h[(size_t)x]] + pos_real[(size_t)x]); };
+
     // ---------------------------------------------------------------- index vectors per layer (Alg. 3), CSR by parent
     Options popt = opt;
     for (int32_t l = 1; l <= L; ++l) {
@@ -654,6 +710,58 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
         for (int64_t p = 0; p < lay.n; ++p)
             if (lay.row_ptr[(size_t)p + 1] - lay.row_ptr[(size_t)p] > 1) lay.multi[(size_t)p >> 5] |= 1u << (p & 31);
         make_pass_plan(lay.n, lay.row_ptr.data(), lay.child.data(), popt, lay.fwd);
+        if ((l & 1) && l < B0 && plan.num_fused > 0) {
+            std::vector<uint8_t> skip((size_t)lay.n, 0);
+            for (int64_t p = 0; p < lay.n; ++p) {
+                skip[(size_t)p] = fused[(size_t)lay.origin[(size_t)p]];
+                lay.n_fused += skip[(size_t)p];
+            }
+            if (lay.n_fused > 0 && lay.n_fused < lay.n)
+                make_pass_plan(lay.n, lay.row_ptr.data(), lay.child.data(), popt, lay.fwd_kept, nullptr, nullptr, skip.data());
+        }
+        if ((l & 1) == 0 && l <= B0 && plan.num_fused > 0) {
+            // fwd2: every child of an OR row as a group of entries; a fused AND child is replaced by its children
+            bool reads_fused = false;
+            std::vector<int32_t> ptr2((size_t)lay.n + 1, 0), idx2;
+            std::vector<uint32_t> flag2;
+            idx2.reserve((size_t)e * 2);
+            flag2.reserve((size_t)e * 2);
+            std::vector<std::pair<int32_t, int32_t>> kids;       // (row, node) of a row's children, by row
+            std::vector<int32_t> grp;
+            for (int64_t p = 0; p < lay.n; ++p) {
+                const int32_t c = lay.origin[(size_t)p];
+                if (lay.is_pad[(size_t)p]) {
+                    idx2.push_back(lay.child[(size_t)lay.row_ptr[(size_t)p]]);
+                    flag2.push_back(kGroupEnd);
+                } else {
+                    kids.clear();
+                    for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) kids.emplace_back(own_row(child_idx[j]), child_idx[j]);
+                    std::sort(kids.begin(), kids.end());
+                    for (const auto& kid : kids) {
+                        if (!fused[(size_t)kid.second]) {
+                            idx2.push_back(kid.first);
+                            flag2.push_back(kGroupEnd);
+                            continue;
+                        }
+                        reads_fused = true;
+                        const int32_t a = kid.second;
+                        grp.clear();
+                        for (int64_t j = child_ptr[a]; j < child_ptr[a + 1]; ++j) grp.push_back(own_row(child_idx[j]));
+                        std::sort(grp.begin(), grp.end());
+                        for (size_t g = 0; g < grp.size(); ++g) {
+                            idx2.push_back(grp[g]);
+                            flag2.push_back(g + 1 == grp.size() ? kGroupEnd : 0u);
+                        }
+                    }
+                }
+                if (idx2.size() >= (size_t)INT32_MAX - 64) { err = "klay_build: a layer has more than 2^31 edges"; return ST_INVAL; }
+                ptr2[(size_t)p + 1] = (int32_t)idx2.size();
+            }
+            if (reads_fused) {
+                make_pass_plan(lay.n, ptr2.data(), idx2.data(), popt, lay.fwd2, flag2.data());
+                plan.max_fwd_seg = std::max<int64_t>(plan.max_fwd_seg, lay.fwd2.n_seg);
+            }
+        }
 
         plan.num_edges += e;
         plan.num_split_rows += lay.fwd.n_heavy;

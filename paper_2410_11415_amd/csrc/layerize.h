@@ -19,6 +19,7 @@ struct Options {
     int32_t tail_rows_cap = 0;  // > 0: layers with more nodes than this are no candidates for the persistent kernels
                                 // (at most kTailRowsCap; for tests of the boundary between the two parts)
     bool small_batch_edges = false;   // evaluator option (not used by the layerizer): lanes = edges kernel for B <= 32
+    bool no_fusion = false;     // build no fused plans (LayerPlan::fwd2): every forward sweep writes every AND node's value
 };
 
 // Layers at the top of the circuit with at most this many nodes are candidates for the persistent
@@ -59,6 +60,11 @@ struct SlabPlan {
 // tasks: runs of consecutive main rows with a bounded edge count, as (first row, first edge)
 // pairs with a closing (n_main, main edge count) pair: the unit of work of one wave.
 constexpr uint32_t kLastEdge = 0x80000000u, kWeightedEdge = 0x40000000u, kRowFlag = 0x20000000u, kSkipRow = 0xFFFFFFFFu;
+// In the fused plans (LayerPlan::fwd2) that bit means something else: kGroupEnd on the last entry of a group.  The
+// entries of a group are combined by the AND operation, the group results are the children of the OR row.
+constexpr uint32_t kGroupEnd = kWeightedEdge;
+// the OR rows that read through fused AND rows stay below this many entries, so they are never split
+constexpr int64_t kFusedRowMax = 24;
 constexpr int64_t kMaxRows = (int64_t)1 << 29;      // row ids fit the 29-bit source field
 constexpr int kIdxPad = 16;
 struct PassPlan {
@@ -94,6 +100,14 @@ struct LayerPlan {
     SlabPlan slab_bwd;               // rows = nodes of layer - 1, sources = parents in this layer (| kWeightedEdge)
     PassPlan fwd;                    // outputs = nodes of this layer, sources = layer - 1
     PassPlan bwd;                    // outputs = nodes of layer - 1, sources = this layer
+    // Fused AND rows (padding-free part only).  An AND node below layer alias_top that has at most one child
+    // which is not a leaf and only OR parents whose rows stay short when they read its children instead of
+    // it, is "fused": the forward plans below never read its value, so a forward sweep that uses them does not
+    // have to write it.
+    int64_t n_fused = 0;             // AND layers: so many of the rows are fused
+    PassPlan fwd_kept;               // AND layers with fused rows: fwd with those rows left out (kSkipRow entries)
+    PassPlan fwd2;                   // OR layers that read fused rows: every child is a group of entries (kGroupEnd),
+                                     // a fused AND child being replaced by its own children
 };
 
 struct CircuitPlan {
@@ -118,6 +132,7 @@ struct CircuitPlan {
     // throughout; num_layers: no chain nodes except the stand-ins of roots in the top layer.
     int32_t alias_top = 0;
     bool alias = false;                  // alias_top > 0
+    int64_t num_fused = 0;               // AND rows whose values the fused plans do not need
     std::vector<int64_t> row0;
 };
 
@@ -130,7 +145,8 @@ int layerize(int32_t num_vars, int64_t num_nodes, const uint8_t* node_type, cons
 // `flags` (optional, one per edge) is OR-ed into the entries.
 // `row_bits` (optional, a bit per output row) puts kRowFlag on the last entry of the flagged rows (for a
 // split row: on the last entry of its combine list).
+// `skip` (optional, a byte per row): rows to leave out; like a split row such a row is one kSkipRow entry.
 void make_pass_plan(int64_t n, const int32_t* ptr, const int32_t* idx, const Options& opt, PassPlan& out,
-                    const uint32_t* flags = nullptr, const uint32_t* row_bits = nullptr);
+                    const uint32_t* flags = nullptr, const uint32_t* row_bits = nullptr, const uint8_t* skip = nullptr);
 
 }  // namespace klay

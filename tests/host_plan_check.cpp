@@ -69,8 +69,9 @@ static void walk_rows(const PassPlan& p, int row_begin, int row_end, int64_t n_s
 }
 
 // runs one plan both ways and compares with `want` (one value per output row)
+// `left_out` (optional, a byte per row): rows the plan must not write (the fused rows of LayerPlan::fwd_kept)
 static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const std::vector<u64>& want, const char* what,
-                       const std::vector<uint32_t>* row_bits = nullptr) {
+                       const std::vector<uint32_t>* row_bits = nullptr, const std::vector<uint8_t>* left_out = nullptr) {
     CHECK(p.n_main == n_out, "%s: n_main", what);
     // the row flag sits on the last entry of exactly the flagged rows (a split row: on the last entry of its
     // combine list) and nowhere else
@@ -120,6 +121,7 @@ static void check_plan(const PassPlan& p, int64_t n_out, int64_t n_src, const st
         }
         for (int s = 0; s < p.n_seg; ++s) CHECK(seg_used[(size_t)s] == 1, "%s: segment %d combined %d times", what, s, seg_used[(size_t)s]);
         for (int64_t i = 0; i < n_out; ++i) {
+            if (left_out && (*left_out)[(size_t)i]) { CHECK(wr[(size_t)i] == 0, "%s: row %lld is written", what, (long long)i); continue; }
             CHECK(wr[(size_t)i] == 1, "%s: row %lld written %d times (variant %d)", what, (long long)i, wr[(size_t)i], variant);
             CHECK(out[(size_t)i] == want[(size_t)i], "%s: row %lld value (variant %d)", what, (long long)i, variant);
         }
@@ -177,7 +179,7 @@ static void check_slab(const klay::SlabPlan& sp, int64_t n_out, int64_t n_src, c
 int main(int argc, char** argv) {
     const int trials = argc > 1 ? std::atoi(argv[1]) : 120;
     std::mt19937_64 rng(12345);
-    long plans = 0, b0_seen[3] = {0, 0, 0};
+    long plans = 0, fused_plans = 0, b0_seen[3] = {0, 0, 0};
     for (int trial = 0; trial < trials; ++trial) {
         const int V = 1 + (int)(rng() % 12), nl = 2 * V;
         const int ng = 1 + (int)(rng() % 400);
@@ -271,6 +273,60 @@ int main(int argc, char** argv) {
                     }
                     check_plan(lay.fwd, lay.n, plan.row0[(size_t)l], fwd, "alias forward plan"); ++plans;
                 }
+                // Fused AND rows: fwd_kept is fwd without them; fwd2 of the OR layers reads, in place of a fused
+                // row, that row's children as one group (the entry that closes a group counts three times here,
+                // like a weighted one, so that a misplaced group end changes the sum).
+                std::vector<uint8_t> is_fused((size_t)NR, 0);
+                int64_t n_fused = 0;
+                for (int l = 1; l < B0; l += 2) {
+                    const klay::LayerPlan& lay = plan.layers[(size_t)l];
+                    if (lay.n_fused == 0) { CHECK(lay.fwd_kept.ptr.empty(), "fwd_kept without fused rows"); continue; }
+                    CHECK(lay.n_fused <= lay.n, "fused row count");
+                    if (lay.n_fused == lay.n) { CHECK(lay.fwd_kept.ptr.empty(), "fwd_kept with nothing to evaluate"); }
+                    std::vector<uint8_t> out((size_t)lay.n, 0);
+                    std::vector<u64> fwd((size_t)lay.n, 0);
+                    int64_t seen = 0;
+                    std::vector<uint8_t> split_kept((size_t)lay.n, 0);
+                    for (int32_t row : lay.fwd_kept.comb_row) split_kept[(size_t)row] = 1;
+                    for (int64_t r = 0; r < lay.n; ++r) {
+                        // a fused row: a skip entry in fwd_kept that no combine list of fwd_kept writes
+                        const bool skipped = lay.n_fused == lay.n ||
+                            (lay.fwd_kept.idx[(size_t)lay.fwd_kept.ptr[(size_t)r]] == klay::kSkipRow && !split_kept[(size_t)r]);
+                        out[(size_t)r] = skipped;
+                        seen += skipped;
+                        is_fused[(size_t)(plan.row0[(size_t)l] + r)] = skipped;
+                        for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) fwd[(size_t)r] += val(lay.child[(size_t)j]);
+                        if (skipped) {
+                            int64_t gates = 0;
+                            for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) gates += lay.child[(size_t)j] >= plan.row0[1];
+                            CHECK(gates <= 1, "a fused row has more than one child that is not a leaf");
+                        }
+                    }
+                    CHECK(seen == lay.n_fused, "fused rows of layer %d: %lld counted, %lld marked", l, (long long)lay.n_fused, (long long)seen);
+                    n_fused += seen;
+                    if (lay.n_fused < lay.n) { check_plan(lay.fwd_kept, lay.n, plan.row0[(size_t)l], fwd, "forward plan without the fused rows", nullptr, &out); ++plans; }
+                }
+                CHECK(n_fused == plan.num_fused, "fused rows in total");
+                for (int l = 2; l <= B0; l += 2) {
+                    const klay::LayerPlan& lay = plan.layers[(size_t)l];
+                    bool reads_fused = false;
+                    std::vector<u64> want((size_t)lay.n, 0);
+                    for (int64_t r = 0; r < lay.n; ++r)
+                        for (int j = lay.row_ptr[(size_t)r]; j < lay.row_ptr[(size_t)r + 1]; ++j) {
+                            const int32_t ch = lay.child[(size_t)j];
+                            if (!is_fused[(size_t)ch]) { want[(size_t)r] += 3u * val(ch); continue; }
+                            reads_fused = true;
+                            // the fused child's own children; the last of them closes the group
+                            int a = 1;
+                            while (plan.row0[(size_t)a + 1] <= ch) ++a;
+                            const klay::LayerPlan& al = plan.layers[(size_t)a];
+                            const int64_t ar = ch - plan.row0[(size_t)a];
+                            for (int jj = al.row_ptr[(size_t)ar]; jj < al.row_ptr[(size_t)ar + 1]; ++jj)      // (child lists are sorted)
+                                want[(size_t)r] += val(al.child[(size_t)jj]) * (jj == al.row_ptr[(size_t)ar + 1] - 1 ? 3u : 1u);
+                        }
+                    CHECK(reads_fused == !lay.fwd2.ptr.empty(), "fwd2 of layer %d", l);
+                    if (reads_fused) { check_plan(lay.fwd2, lay.n, plan.row0[(size_t)l], want, "fused forward plan"); ++plans; fused_plans++; }
+                }
                 for (int l = 0; l < B0; ++l) {
                     const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;
                     std::vector<u64> want(adj.begin() + a, adj.begin() + a + n);
@@ -283,6 +339,7 @@ int main(int argc, char** argv) {
         }
     }
     CHECK(b0_seen[0] > 0 && b0_seen[1] > 0 && b0_seen[2] > 0, "boundary layer cases seen: %ld %ld %ld", b0_seen[0], b0_seen[1], b0_seen[2]);
-    std::printf("ok: %ld plans checked\n", plans);
+    CHECK(fused_plans > 0, "no fused forward plan was built");
+    std::printf("ok: %ld plans checked (%ld fused forward plans)\n", plans, fused_plans);
     return 0;
 }

@@ -24,8 +24,8 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_sizes_match_the_header():
-    assert ctypes.sizeof(binding.klay_options) == 32
-    assert ctypes.sizeof(binding.klay_info_t) == 16 + 13 * 8
+    assert ctypes.sizeof(binding.klay_options) == 36
+    assert ctypes.sizeof(binding.klay_info_t) == 16 + 14 * 8
     # the profile arrays have one slot per kernel class of the header's enum
     with open(os.path.join(ROOT, "include", "klay.h")) as fh:
         header = fh.read()
@@ -33,7 +33,7 @@ def test_struct_sizes_match_the_header():
     classes = [t.split("=")[0].strip() for t in enum.split(",") if t.strip()]
     assert classes[-1] == "KLAY_K_COUNT"
     k = len(classes) - 1
-    assert len(binding.KERNEL_CLASSES) == k == 21
+    assert len(binding.KERNEL_CLASSES) == k == 22
     assert [c[len("KLAY_K_"):].lower() for c in classes[:-1]] == list(binding.KERNEL_CLASSES)
     assert ctypes.sizeof(binding.klay_profile_t) == k * 4 + k * 4 + k * 8 + k * 8
 

@@ -304,6 +304,59 @@ def test_main_rows_and_combine_rows_in_one_launch(klay, B):
     check_both(klay, c, p, what="main+combine, layered B=%d" % B, heavy_fan=8, min_segment=4)
 
 
+@pytest.mark.parametrize("B", [100, 256])
+def test_fused_and_rows_forward_only_and_followed_by_backward(klay, B):
+    """B > 64, log-domain semirings: a forward pass leaves out the AND rows that the OR rows above evaluate from
+    their children (fused plans); klay_backward evaluates them first when it follows such a pass, and a handle
+    that has seen a forward / backward pair writes every value in its next forward pass.  Every output of every
+    call order against the oracle and against a handle built without fusion."""
+    c, p, _ = make_config("layered_1m", seed=4, scale=0.3, batch=B)
+    w32 = as_inputs(p, True)
+    rng = np.random.default_rng(4)
+    dout = rng.normal(size=(B, c.roots.shape[0])).astype(np.float32)
+    k = build(klay, c, tail_rows_cap=1500)
+    plain = build(klay, c, tail_rows_cap=1500, no_fusion=True)
+    info = k.info()
+    assert info["num_fused_rows"] > 1000 and 0 < info["alias_top_layer"] < k.num_layers
+    assert plain.info()["num_fused_rows"] == 0
+    ref, rd = oracle_eval(c, w32, LOG, dout, or_levels=k.num_layers // 2)
+    want, wd = gpu_eval(plain, w32, LOG, dout)
+    k.set_profiling(True)
+
+    def fused_launches():
+        return k.get_profile()["fwd_or_fused"]["launches"]
+
+    a, _ = gpu_eval(k, w32, LOG)                    # forward only: fused
+    assert fused_launches() > 0
+    b, gb = gpu_eval(k, w32, LOG, dout)             # fused again, then the reverse sweep fills in the missing values
+    assert fused_launches() > 0
+    e, ge = gpu_eval(k, w32, LOG, dout)             # a backward pass followed the last forward pass: every value written
+    assert fused_launches() == 0
+    f, _ = gpu_eval(k, w32, LOG)                    # still in the training loop's mode
+    assert fused_launches() == 0
+    h, _ = gpu_eval(k, w32, LOG)                    # no backward pass followed: fused again
+    assert fused_launches() > 0
+    for got in (a, b, e, f, h):
+        assert_log_close(got, ref, "fused forward B=%d" % B)
+        np.testing.assert_allclose(got, want, rtol=0, atol=2e-5)
+    for gd in (gb, ge):
+        assert_grad_close(gd, rd, "gradient after a fused forward pass B=%d" % B)
+        np.testing.assert_allclose(gd, wd, rtol=1e-4, atol=1e-5)
+    m, _ = gpu_eval(k, w32, MAXLOG)
+    assert fused_launches() > 0
+    refm, _ = oracle_eval(c, w32, MAXLOG)
+    assert_log_close(m, refm, "fused forward, (max, +) B=%d" % B)
+    # the real semiring and batches of 64 columns or fewer run the ordinary plans
+    r, _ = gpu_eval(k, as_inputs(p, False), REAL)
+    assert fused_launches() == 0
+    refr, _ = oracle_eval(c, as_inputs(p, False), REAL)
+    assert_real_close(r, refr, "real after fused")
+    s64, _ = gpu_eval(k, w32[:64], LOG)
+    assert fused_launches() == 0
+    assert_log_close(s64, ref[:64], "B=64 after fused")
+    k.close(); plain.close()
+
+
 def test_very_high_fan_in_and_gate_with_magnitude_aware_bound(klay):
     """one AND and one OR over 10^4 literals: exercises the split path at the fan-in cap; |log| of the
     AND reaches ~10^4, where fp32 cannot hold 1e-4 absolute, so the bound scales with sum |x_j| / 64"""
