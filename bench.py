@@ -55,7 +55,7 @@ def load_traffic(workload, batch, semiring, backward, chains):
     return table.get("runs", {}).get(key)
 
 
-def kernel_symbol(cls, B, edges=False, maxlog=False):
+def kernel_symbol(cls, B, edges=False, fused_op=10):
     """rocprofv3's name for the kernel behind a profiling class (template arguments as it prints them)."""
     vec = 4 if B > 128 else (2 if B > 64 else 1)
     ops = {"fwd_sum": 0, "bwd_sum": 0, "fwd_prod": 1, "fwd_lse": 2, "bwd_softmax": 3, "fwd_max": 4, "bwd_prod": 5,
@@ -78,7 +78,7 @@ def kernel_symbol(cls, B, edges=False, maxlog=False):
              "seed": "klay::seed_kernel", "split": "klay::pass_kernel<*> (segments of split rows)",
              "combine": "klay::combine_kernel<*>" if B > 32 else "klay::pass_kernel<*> (combine rows of split rows)",
              "main_combine": "klay::stream_combine_kernel<*>",
-             "fwd_or_fused": "klay::stream_kernel<%d, %d>" % (11 if maxlog else 10, vec),
+             "fwd_or_fused": "klay::stream_kernel<%d, %d>" % (fused_op, vec),
              "prod_edges": "klay::prod_parent_kernel<%d, %d>" % (vec, 64 if B > 32 else w_small)}
     return fixed.get(cls, cls)
 
@@ -265,7 +265,7 @@ def main():
     for name, c in classes.items():
         if not c["launches"]:
             continue
-        g = by_symbol.setdefault(kernel_symbol(name, B, args.small_batch_edges, semiring == pkg.KLAY_MAXLOG), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
+        g = by_symbol.setdefault(kernel_symbol(name, B, args.small_batch_edges, {pkg.KLAY_LOG: 10, pkg.KLAY_MAXLOG: 11, pkg.KLAY_REAL: 12}[semiring]), {"ms": 0.0, "launches": 0, "alg_bytes": 0.0, "min_bytes": 0.0,
                                                           "classes": []})
         for f in ("ms", "launches", "alg_bytes", "min_bytes"):
             g[f] += c[f]
@@ -392,7 +392,7 @@ def main():
                                    "padding-free up to layer %d of %d, unary chain nodes above" % (
                                        info["alias_top_layer"], info["num_layers"]),
                    "padding_free_layers": info["alias_top_layer"],
-                   "fused_and_rows": 0 if (args.no_fusion or backward or B <= 64 or semiring == pkg.KLAY_REAL) else info["num_fused_rows"],
+                   "fused_and_rows": 0 if (args.no_fusion or backward or B <= 64) else info["num_fused_rows"],
                    "layers": info["num_layers"], "layered_nodes": N, "layered_edges": E,
                    "dag_nodes": info["dag_nodes"], "dag_edges": info["dag_edges"],
                    "pad_nodes": info["num_pad_nodes"], "num_vars": info["num_vars"], "num_roots": info["num_roots"],

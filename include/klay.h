@@ -75,10 +75,11 @@ typedef struct klay_options {
     int32_t no_fusion;       /* 1: every AND node's value is written.  Default (0): in the padding-free part an
                                 AND node with at most one child that is not a leaf, few children and parents,
                                 and only short OR rows above it is fused into those rows when the batch has more
-                                than 64 columns and the semiring is a log-domain one: they read its children and
-                                sum them themselves, and the reverse sweep forms its value the same way, so its
-                                row of the value buffer is never written (one launch and one row per node less;
-                                same results up to the order of the sums)                                */
+                                than 64 columns: they read its children and combine them themselves, so a forward
+                                pass does not write its value.  klay_backward, which needs every value, evaluates
+                                the fused rows first when it follows such a pass, and the forward pass of a handle
+                                whose previous forward pass was followed by klay_backward writes every value.
+                                Same results                                                              */
 } klay_options;
 
 typedef struct klay_info_t {

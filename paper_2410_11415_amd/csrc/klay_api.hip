@@ -348,6 +348,7 @@ void launch_stream(int op, const DevPass& dp, bool main_rows, bool segments, con
     case klay::OP_PROD_BWD_P: launch_stream_op<klay::OP_PROD_BWD_P>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     case klay::OP_LSE2: launch_stream_op<klay::OP_LSE2>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     case klay::OP_MAX2: launch_stream_op<klay::OP_MAX2>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
+    case klay::OP_SUMPROD2: launch_stream_op<klay::OP_SUMPROD2>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     default: launch_stream_op<klay::OP_SOFTMAX_BWD>(dp, main_rows, segments, g, src, src2, own, dst, dst_seg, B, s, zf); break;
     }
 }
@@ -592,7 +593,7 @@ klay_status upload(klay_circuit* c) {
 double pass_bytes(int op, double entries, double rows, int B) {
     const double per_entry = op == klay::OP_SOFTMAX_BWD ? 2.0 : 1.0;
     const double per_row = (op == klay::OP_SUM || op == klay::OP_PROD || op == klay::OP_LSE || op == klay::OP_MAX ||
-                            op == klay::OP_LSE2 || op == klay::OP_MAX2) ? 1.0 : 2.0;
+                            op == klay::OP_LSE2 || op == klay::OP_MAX2 || op == klay::OP_SUMPROD2) ? 1.0 : 2.0;
     return 4.0 * B * (per_entry * entries + per_row * rows) + 4.0 * (entries + rows);
 }
 
@@ -1619,11 +1620,11 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
     }
 
     // gate layers: odd = AND, even = OR (Alg. 1 / Alg. 4)
-    // The fused plans run in the log-domain semirings where the streaming kernel takes main rows and segments in one
-    // launch (two or four columns per lane) and the reverse sweep works in the one-gather form.
+    // The fused plans run where the streaming kernel takes main rows and segments in one launch (two or four
+    // columns per lane).
     // A handle whose previous forward pass was followed by klay_backward is in a training loop: the reverse sweep
     // needs every value, so this pass writes them all (klay_backward would otherwise evaluate the fused rows first).
-    const bool fused = log_domain && g.w == 64 && g.vec >= 2 && p.num_fused > 0 && !c->no_fusion &&
+    const bool fused = g.w == 64 && g.vec >= 2 && p.num_fused > 0 && !c->no_fusion &&
                        (static_ws || !c->bwd_followed);
     const int last_regular = tail.first > 0 ? tail.first - 1 : L;
     for (int l = 1; l <= last_regular; ++l) {
@@ -1640,7 +1641,7 @@ static klay_status forward_impl(klay_circuit* c, const float* leaf_weights, cons
             // the fused rows are not evaluated: the OR rows above read their children
             if (d.has_fwd_kept) run_pass_set(op, op, d.fwd_kept, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
         } else if (fused && !is_and && d.has_fwd2) {
-            run_pass_set(semiring == KLAY_MAXLOG ? klay::OP_MAX2 : klay::OP_LSE2, op, d.fwd2, below, nullptr, nullptr,
+            run_pass_set(!log_domain ? klay::OP_SUMPROD2 : semiring == KLAY_MAXLOG ? klay::OP_MAX2 : klay::OP_LSE2, op, d.fwd2, below, nullptr, nullptr,
                          act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, KLAY_K_FWD_OR_FUSED);
         } else {
             run_pass_set(op, op, d.fwd, below, nullptr, nullptr, act + (size_t)d.row0 * g.ld, seg_rows, g, B, s, prof, cls);
@@ -1727,7 +1728,8 @@ static klay_status backward_impl(klay_circuit* c, const float* dout, float* dlea
         for (int l = 1; l < B0; l += 2) {
             const DevLayer& d = c->dl[(size_t)l];
             if (d.n_fused > 0)
-                run_pass_set(klay::OP_SUM, klay::OP_SUM, d.fwd, act, nullptr, nullptr, values(l), seg_rows, g, B, s, prof, KLAY_K_FWD_SUM);
+                run_pass_set(real ? klay::OP_PROD : klay::OP_SUM, real ? klay::OP_PROD : klay::OP_SUM, d.fwd, act, nullptr, nullptr,
+                             values(l), seg_rows, g, B, s, prof, real ? KLAY_K_FWD_PROD : KLAY_K_FWD_SUM);
         }
         c->last_fused = false;
     }

@@ -18,8 +18,9 @@ namespace klay {
 enum PassOp : int { OP_SUM = 0, OP_PROD = 1, OP_LSE = 2, OP_SOFTMAX_BWD = 3, OP_MAX = 4, OP_PROD_BWD = 5, OP_SUM_H = 6, OP_SOFTMAX_H = 7,
                     OP_SUM_P = 8, OP_PROD_BWD_P = 9,
                     // over the fused plans (see LayerPlan::fwd2): an OR row whose children are groups of entries
-                    // (sum within a group, then logsumexp / max over the groups)
-                    OP_LSE2 = 10, OP_MAX2 = 11 };
+                    // (sum within a group, then logsumexp / max over the groups; real semiring: product within a
+                    // group, then the sum of the groups)
+                    OP_LSE2 = 10, OP_MAX2 = 11, OP_SUMPROD2 = 12 };
 // what the ops have in common: `own` = the walk needs the value of the output row itself, `additive` = partial
 // results add up
 template <int OP> struct OpTraits {
@@ -173,6 +174,11 @@ template <int OP>
 __device__ __forceinline__ void accumulate(float& acc, float& mx, float x, float y, float& nc, bool weighted = true) {
     if (OP == OP_SUM_H || OP == OP_SUM_P) { acc += x; return; }
     if (OP == OP_SOFTMAX_H) { acc += weighted ? decode_h(x, nc) : x; return; }
+    if (OP == OP_SUMPROD2) {
+        nc *= x;
+        if (weighted) { acc += nc; nc = 1.0f; }
+        return;
+    }
     if (OP == OP_LSE2 || OP == OP_MAX2) {
         nc += x;
         if (weighted) {
@@ -212,7 +218,7 @@ __device__ __forceinline__ float identity() { return OP == OP_PROD ? 1.0f : ((OP
 // what an index entry that is not part of the row contributes: nothing
 template <int OP>
 __device__ __forceinline__ float dead_value() {
-    return OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
+    return (OP == OP_PROD || OP == OP_SUMPROD2) ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -264,7 +270,7 @@ __device__ __forceinline__ void stream_body(int bx, int nbx, const int2* __restr
 
     float acc[VEC], mx[VEC], nc[VEC];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) { acc[v] = identity<OP>(); mx[v] = -INFINITY; nc[v] = 0.0f; }
+    for (int v = 0; v < VEC; ++v) { acc[v] = identity<OP>(); mx[v] = -INFINITY; nc[v] = OP == OP_SUMPROD2 ? 1.0f : 0.0f; }
     bool fresh = true;                       // the next edge opens a new output row
     uint32_t ids[CH];
 #pragma unroll
@@ -319,8 +325,7 @@ __device__ __forceinline__ void stream_body(int bx, int nbx, const int2* __restr
             }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                const float dead = OP == OP_PROD ? 1.0f : ((OP == OP_LSE || OP == OP_MAX) ? -INFINITY : 0.0f);
-                const float xv = live ? x[i][v] : dead;
+                const float xv = live ? x[i][v] : dead_value<OP>();
                 const float yv = OP == OP_SOFTMAX_BWD ? (live ? y[i][v] : -INFINITY) : 0.0f;
                 accumulate<OP>(acc[v], mx[v], xv, yv, nc[v], live && (ids[i] & kWeighted) != 0);
             }

@@ -459,13 +459,16 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
     // Fused AND rows (see LayerPlan): AND nodes of the padding-free part whose value nothing has to read.
     std::vector<uint8_t> fused((size_t)N, 0);
     if (B0 > 0 && !opt.no_fusion) {
+        // a row is split when it has more entries than heavy_fan, or than half of it (make_pass_plan): the rows that
+        // read through fused rows stay at or below that, so that no group of entries is cut by a segment boundary
+        const int64_t row_max = std::min<int64_t>(kFusedRowMax, std::max(1, opt.heavy_fan / 2));
         std::vector<uint8_t> cand((size_t)N, 0);
         for (int64_t c = 0; c < N; ++c) {
             if (!reach[(size_t)c] || !(h[(size_t)c] & 1) || h[(size_t)c] >= B0 || need[(size_t)c] >= B0) continue;
             const int64_t fi = child_ptr[c + 1] - child_ptr[c];
             int64_t gates = 0;
             for (int64_t j = child_ptr[c]; j < child_ptr[c + 1]; ++j) gates += h[(size_t)child_idx[j]] > 0;
-            cand[(size_t)c] = fi >= 1 && gates <= 1 && fi <= kFusedRowMax;
+            cand[(size_t)c] = fi >= 1 && gates <= 1 && fi <= row_max;
         }
         // every parent has to be an OR row that stays short when it reads the children of its fused children
         for (int64_t p = 0; p < N; ++p) {
@@ -477,7 +480,7 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
                 any = any || cand[(size_t)c];
                 len += cand[(size_t)c] ? child_ptr[c + 1] - child_ptr[c] : 1;
             }
-            if (!any || ((h[(size_t)p] & 1) == 0 && len <= kFusedRowMax)) continue;
+            if (!any || ((h[(size_t)p] & 1) == 0 && len <= row_max)) continue;
             for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) cand[(size_t)child_idx[j]] |= 2;      // not through this parent
         }
         for (int64_t c = 0; c < N; ++c)

@@ -325,7 +325,14 @@ int main(int argc, char** argv) {
                                 want[(size_t)r] += val(al.child[(size_t)jj]) * (jj == al.row_ptr[(size_t)ar + 1] - 1 ? 3u : 1u);
                         }
                     CHECK(reads_fused == !lay.fwd2.ptr.empty(), "fwd2 of layer %d", l);
-                    if (reads_fused) { check_plan(lay.fwd2, lay.n, plan.row0[(size_t)l], want, "fused forward plan"); ++plans; fused_plans++; }
+                    if (reads_fused) {
+                        check_plan(lay.fwd2, lay.n, plan.row0[(size_t)l], want, "fused forward plan"); ++plans; fused_plans++;
+                        // no group is cut by the end of a row or of a segment
+                        for (size_t j = 0; j + klay::kIdxPad < lay.fwd2.idx.size(); ++j) {
+                            const uint32_t id = lay.fwd2.idx[j];
+                            if (id != klay::kSkipRow && (id & klay::kLastEdge)) CHECK((id & klay::kGroupEnd) != 0, "a group of entries runs past the end of its row");
+                        }
+                    }
                 }
                 for (int l = 0; l < B0; ++l) {
                     const int64_t a = plan.row0[(size_t)l], n = plan.layers[(size_t)l].n;

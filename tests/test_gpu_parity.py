@@ -346,11 +346,18 @@ def test_fused_and_rows_forward_only_and_followed_by_backward(klay, B):
     assert fused_launches() > 0
     refm, _ = oracle_eval(c, w32, MAXLOG)
     assert_log_close(m, refm, "fused forward, (max, +) B=%d" % B)
-    # the real semiring and batches of 64 columns or fewer run the ordinary plans
-    r, _ = gpu_eval(k, as_inputs(p, False), REAL)
+    # the real semiring: products within the groups, and the reverse sweep after a fused pass
+    doutr = np.ones((B, c.roots.shape[0]), dtype=np.float32)
+    r, gr = gpu_eval(k, as_inputs(p, False), REAL, doutr)
+    assert fused_launches() > 0
+    refr, rdr = oracle_eval(c, as_inputs(p, False), REAL, doutr, or_levels=k.num_layers // 2)
+    assert_real_close(r, refr, "fused forward, real B=%d" % B)
+    assert_grad_close(gr, rdr, "real gradient after a fused forward pass B=%d" % B, real=True)
+    r2, gr2 = gpu_eval(k, as_inputs(p, False), REAL, doutr)
     assert fused_launches() == 0
-    refr, _ = oracle_eval(c, as_inputs(p, False), REAL)
-    assert_real_close(r, refr, "real after fused")
+    np.testing.assert_allclose(r2, r, rtol=1e-6, atol=0)
+    assert_grad_close(gr2, rdr, "real gradient in the loop's mode B=%d" % B, real=True)
+    # batches of 64 columns or fewer run the ordinary plans
     s64, _ = gpu_eval(k, w32[:64], LOG)
     assert fused_launches() == 0
     assert_log_close(s64, ref[:64], "B=64 after fused")
