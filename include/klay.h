@@ -177,7 +177,8 @@ klay_status klay_build_ex(int32_t num_vars, int64_t num_nodes, const uint8_t* no
  *   B             batch size >= 1
  *   out           device [B, R] row-major fp32; out[b, r] = value of roots[r] on sample b
  *   stream        hipStream_t (as void*), may be NULL for the default stream
- * Keeps every layer's values in the workspace for klay_backward.  Grows the library-owned
+ * Keeps the layers' values in the workspace for klay_backward (all but those of fused AND rows, which
+ * klay_backward then evaluates itself: see klay_options.no_fusion).  Grows the library-owned
  * workspace (hipMalloc, which synchronises) when B exceeds what earlier calls needed, unless a
  * caller workspace was set.  Errors: KLAY_EINVAL, KLAY_ENOMEM, KLAY_EHIP, KLAY_ESTATE.
  */
