@@ -477,8 +477,8 @@ int layerize(int32_t V, int64_t N, const uint8_t* node_type, const int32_t* node
             bool any = false;
             for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) {
                 const int32_t c = child_idx[j];
-                any = any || cand[(size_t)c];
-                len += cand[(size_t)c] ? child_ptr[c + 1] - child_ptr[c] : 1;
+                any = any || (cand[(size_t)c] & 1);
+                len += (cand[(size_t)c] & 1) ? child_ptr[c + 1] - child_ptr[c] : 1;
             }
             if (!any || ((h[(size_t)p] & 1) == 0 && len <= row_max)) continue;
             for (int64_t j = child_ptr[p]; j < child_ptr[p + 1]; ++j) cand[(size_t)child_idx[j]] |= 2;      // not through this parent

@@ -330,7 +330,7 @@ int main(int argc, char** argv) {
                         // no group is cut by the end of a row or of a segment
                         for (size_t j = 0; j + klay::kIdxPad < lay.fwd2.idx.size(); ++j) {
                             const uint32_t id = lay.fwd2.idx[j];
-                            if (id != klay::kSkipRow && (id & klay::kLastEdge)) CHECK((id & klay::kGroupEnd) != 0, "a group of entries runs past the end of its row");
+                            if (id != klay::kSkipRow && (id & klay::kLastEdge)) CHECK((id & klay::kGroupEnd) != 0, "a group of entries runs past the end of its row (layer %d, entry %zu of %zu, %d main rows, %d segments, main entries %d)", l, j, lay.fwd2.idx.size(), lay.fwd2.n_main, lay.fwd2.n_seg, lay.fwd2.ptr[(size_t)lay.fwd2.n_main]);
                         }
                     }
                 }
