@@ -1097,7 +1097,7 @@ def test_random_dags_with_random_options(klay, seed):
     c = _random_dag(rng, V, int(rng.integers(5, 400)), hub_share=0.25, max_fan=int(rng.choice([3, 6, 40])))
     opts = dict(unary_chains=bool(rng.integers(3) == 0), tail_rows_cap=int(rng.choice([0, 0, 3, 6, 12, 30])), no_merge=bool(rng.integers(2)), no_reorder=bool(rng.integers(2)),
                 no_tail=bool(rng.integers(2)), heavy_fan=int(rng.choice([0, 2, 5, 17])), min_segment=int(rng.choice([0, 1, 3])),
-                small_batch_edges=bool(seed % 3 == 0))
+                small_batch_edges=bool(seed % 3 == 0), no_fusion=bool(seed % 5 == 0))
     B = int(rng.choice([1, 2, 7, 33, 64, 100, 257]))
     # probabilities near 1/2 keep the real semiring inside fp32 whatever the random structure multiplies up
     p = rng.uniform(0.35, 0.65, size=(B, V))
