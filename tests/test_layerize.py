@@ -499,3 +499,25 @@ def test_index_vectors_evaluate_to_the_oracle_values(golden, opts):
         np.testing.assert_allclose(eval_layered(c, k, p, 0), oracle.forward(*c.arrays(), p, 0), rtol=1e-11)
         np.testing.assert_allclose(eval_layered(c, k, np.log(p), 1), oracle.forward(*c.arrays(), np.log(p), 1),
                                    rtol=0, atol=1e-10)
+
+
+def test_fused_rows_are_counted_and_can_be_switched_off():
+    """AND nodes with at most one gate child below the narrow top are fused into short OR rows above them
+    (forward plans only: values and gradients are those of the same circuit); none with the paper's layerization
+    throughout, none with no_fusion, and never more than there are AND rows below the boundary layer"""
+    from klay_synth import make_config
+    c, _, _ = make_config("layered_1m", seed=0, scale=0.1, batch=1)
+    k = host(c, unary_chains=False, tail_rows_cap=800)
+    info = k.info()
+    A = info["alias_top_layer"]
+    assert 0 < A < info["num_layers"]
+    nodes, _ = k.layer_sizes()
+    and_rows = int(sum(nodes[l] for l in range(1, A, 2)))
+    assert 0 < info["num_fused_rows"] <= and_rows
+    assert host(c, unary_chains=False, tail_rows_cap=800, no_fusion=True).info()["num_fused_rows"] == 0
+    assert host(c).info()["num_fused_rows"] == 0
+    # the layer-by-layer index vectors do not depend on it
+    plain = host(c, unary_chains=False, tail_rows_cap=800, no_fusion=True)
+    for l in (1, 2, A):
+        a, b = k.layer_csr(l), plain.layer_csr(l)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
